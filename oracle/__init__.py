@@ -1,0 +1,197 @@
+"""ctypes front end of the CPU oracle (oracle/f3m_oracle.c).
+
+TEST INFRASTRUCTURE: only tests/, __graft_entry__.smoke() and the cpu_baseline
+leg of bench.py may import this package.  It never touches the HIP library.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "f3m_oracle.c")
+_LIB = os.path.join(_HERE, "libf3m_oracle.so")
+
+
+def build(force=False):
+    """Compile the oracle with gcc (fp contraction off so that the fp32 cell
+    expression is evaluated as two separately rounded operations)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-D_GNU_SOURCE", "-fopenmp", "-ffp-contract=off", "-fPIC",
+             "-shared", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = ctypes.CDLL(build())
+        c_i64, c_int, c_dbl, c_vp = ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
+        L.oracle_num_threads.restype = c_int
+        L.oracle_rows_k.argtypes = [c_vp, c_i64, c_int, c_dbl, c_int, c_int, c_vp, c_vp, c_i64, c_vp]
+        L.oracle_cheb2_nodes.argtypes = [c_int, c_vp]
+        L.oracle_lagrange_product.argtypes = [c_int, c_vp, c_dbl, c_vp]
+        L.oracle_lagrange_barycentric.argtypes = [c_int, c_vp, c_dbl, c_vp]
+        L.oracle_quant_depth.argtypes = [c_int]
+        L.oracle_quant_depth.restype = c_int
+        L.oracle_tree_build.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int]
+        L.oracle_tree_build.restype = c_vp
+        L.oracle_tree_free.argtypes = [c_vp]
+        for name in ("oracle_tree_depth", "oracle_tree_quant_depth"):
+            getattr(L, name).argtypes = [c_vp]
+            getattr(L, name).restype = c_int
+        L.oracle_tree_edge.argtypes = [c_vp]
+        L.oracle_tree_edge.restype = c_dbl
+        L.oracle_tree_alpha.argtypes = [c_vp, c_vp]
+        L.oracle_tree_nboxes.argtypes = [c_vp, c_int]
+        L.oracle_tree_nboxes.restype = c_i64
+        L.oracle_tree_perm.argtypes = [c_vp, c_vp]
+        L.oracle_tree_point_keys.argtypes = [c_vp, c_vp]
+        L.oracle_tree_boxes.argtypes = [c_vp, c_int, c_vp, c_vp]
+        L.oracle_tree_list_size.argtypes = [c_vp, c_int, c_int]
+        L.oracle_tree_list_size.restype = c_i64
+        L.oracle_tree_list.argtypes = [c_vp, c_int, c_int, c_vp, c_vp]
+        L.oracle_beta.argtypes = [c_vp, c_int, c_vp]
+        L.oracle_p2m_level.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_vp]
+        L.oracle_f3m_apply.argtypes = [c_vp, c_vp, c_dbl, c_int, c_int, c_int, c_vp, c_vp, c_int]
+        L.oracle_f3m_apply.restype = c_int
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())
+
+
+def rows(X, b, gamma, rows=None, kernel_id=0, kparam=0):
+    """Exact y_i = sum_j k(x_i, x_j) b_j (fp64) for the given rows (all rows if None)."""
+    X = _f32(X)
+    b = _f32(b)
+    n, D = X.shape
+    if rows is None:
+        idx, m, rp = None, n, None
+    else:
+        idx = np.ascontiguousarray(rows, dtype=np.int64)
+        m, rp = idx.size, _ptr(idx)
+    y = np.empty(m, dtype=np.float64)
+    lib().oracle_rows_k(_ptr(X), n, D, float(gamma), kernel_id, kparam, _ptr(b), rp, m, _ptr(y))
+    return y
+
+
+def direct(X, b, gamma, kernel_id=0, kparam=0):
+    return rows(X, b, gamma, None, kernel_id, kparam)
+
+
+def cheb2_nodes(p):
+    s = np.empty(p, dtype=np.float64)
+    lib().oracle_cheb2_nodes(p, _ptr(s))
+    return s
+
+
+def lagrange_product(p, t):
+    s = cheb2_nodes(p)
+    out = np.empty(p, dtype=np.float64)
+    lib().oracle_lagrange_product(p, _ptr(s), float(t), _ptr(out))
+    return out
+
+
+def lagrange_barycentric(p, t):
+    s = cheb2_nodes(p)
+    out = np.empty(p, dtype=np.float64)
+    lib().oracle_lagrange_barycentric(p, _ptr(s), float(t), _ptr(out))
+    return out
+
+
+def quant_depth(D):
+    return int(lib().oracle_quant_depth(D))
+
+
+class Tree:
+    """Partition + interaction lists of Algorithm 1 for one point set."""
+
+    def __init__(self, X, theta=2.0, zeta=128, max_depth=0, force_all_near=False):
+        self.X = _f32(X)
+        self.n, self.D = self.X.shape
+        self._h = lib().oracle_tree_build(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
+                                          int(max_depth), int(bool(force_all_near)))
+        if not self._h:
+            raise ValueError("oracle_tree_build rejected its arguments")
+        self.L = int(lib().oracle_tree_depth(self._h))
+        self.Lq = int(lib().oracle_tree_quant_depth(self._h))
+        self.E = float(lib().oracle_tree_edge(self._h))
+        a = np.empty(self.D, dtype=np.float64)
+        lib().oracle_tree_alpha(self._h, _ptr(a))
+        self.alpha = a
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h:
+            lib().oracle_tree_free(h)
+
+    def nboxes(self, level):
+        return int(lib().oracle_tree_nboxes(self._h, level))
+
+    def perm(self):
+        out = np.empty(self.n, dtype=np.int64)
+        lib().oracle_tree_perm(self._h, _ptr(out))
+        return out
+
+    def point_keys(self):
+        out = np.empty(self.n, dtype=np.uint64)
+        lib().oracle_tree_point_keys(self._h, _ptr(out))
+        return out
+
+    def boxes(self, level):
+        nb = self.nboxes(level)
+        keys = np.empty(nb, dtype=np.uint64)
+        starts = np.empty(nb + 1, dtype=np.int64)
+        lib().oracle_tree_boxes(self._h, level, _ptr(keys), _ptr(starts))
+        return keys, starts
+
+    def interactions(self, level, kind):
+        """CSR (row_ptr, cols) by target rank; kind 0 = near, 1 = far."""
+        nb = self.nboxes(level)
+        sz = int(lib().oracle_tree_list_size(self._h, level, kind))
+        ptr = np.empty(nb + 1, dtype=np.int64)
+        cols = np.empty(max(sz, 1), dtype=np.int64)
+        lib().oracle_tree_list(self._h, level, kind, _ptr(ptr), _ptr(cols))
+        return ptr, cols[:sz]
+
+    def beta(self, level):
+        out = np.empty(self.n, dtype=np.uint64)
+        lib().oracle_beta(self._h, level, _ptr(out))
+        return out
+
+    def p2m(self, b, p, level):
+        b = _f32(b)
+        r = p ** self.D
+        W = np.empty((self.nboxes(level), r), dtype=np.float64)
+        lib().oracle_p2m_level(self._h, _ptr(self.X), _ptr(b), p, level, _ptr(W))
+        return W
+
+    def apply(self, b, gamma, p, kernel_id=0, kparam=0, literal=False):
+        b = _f32(b)
+        y = np.empty(self.n, dtype=np.float64)
+        rc = lib().oracle_f3m_apply(self._h, _ptr(self.X), float(gamma), int(p), kernel_id, kparam,
+                                    _ptr(b), _ptr(y), int(bool(literal)))
+        if rc:
+            raise ValueError("oracle_f3m_apply rejected its arguments")
+        return y
+
+
+def f3m(X, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False):
+    """CPU F3M product (fp64), original point order."""
+    return Tree(X, theta, zeta, max_depth, force_all_near).apply(b, gamma, p)

@@ -1,0 +1,692 @@
+/*
+ * CPU oracle for the kernel matrix-vector product y = K(X,X) b and for the
+ * F3M approximation of it (arXiv 2202.01085).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, fp64 statement of
+ * what the GPU library has to compute; nothing in the product path may call
+ * it.  It shares no code, header, table or constant with the HIP sources.
+ *
+ * What follows the paper, and where:
+ *   - exact product v_i = sum_j k(x_i,y_j) b_j ............ Sec. 2 (KeOps paragraph)
+ *   - Gaussian kernel exp(-|x-y|^2/(2 gamma^2)) ........... Sec. 5, first paragraph
+ *   - enclosing cube edge E, anchored at the per-dim min .. Sec. 3 "Enclosing and
+ *                                                            partitioning the data",
+ *                                                            Sec. 4.2 box-index formula
+ *   - box index of a point at a depth ..................... Sec. 4.2 box-index formula
+ *   - empty boxes are dropped ............................. Sec. 4.2 "Removing empty boxes"
+ *   - far iff |centre_x - centre_y| >= 2 l, l = E/2^depth . Sec. 3 "Far and near-field"
+ *   - new pairs = children x children of old near pairs ... Sec. 4.1 "Ensuring
+ *                                                            interactions are sorted"
+ *   - Chebyshev nodes of the 2nd kind, Lagrange basis ..... Sec. 3 "Lagrange interpolation"
+ *   - barycentric form and its weights .................... Appendix C
+ *   - v ~ L_X^T (K (L_Y b)) for a far pair ................ Sec. 3 "Interpolating k(x,y)"
+ *   - driver loop, stop on the MAXIMUM box size ........... Appendix E, Algorithm 1
+ *
+ * Readings where the paper is silent or garbled (each is listed in the
+ * design document of the repository as well):
+ *   R1  interp_nodes p = nodes PER DIMENSION, s_i = cos(i pi/(p-1)), i=0..p-1;
+ *       the grid of a box has r = p^D nodes; flat node index i = sum_d i_d p^d.
+ *   R2  the cell of a point is fixed ONCE, in fp32, at the quantisation depth
+ *       Lq(D):  c_d = min( trunc( fl32( fl32(x_d - alpha_d) * s ) ), 2^Lq - 1 ),
+ *       s = fl32( 2^Lq / E ), E = max_d fl32(max_d - min_d); the cell at depth
+ *       l <= Lq is c_d >> (Lq - l).  This is the floor formula of Sec. 4.2 with
+ *       its rounding spelled out; the clamp covers the points on the max face.
+ *       Everything else in this file is fp64.
+ *   R3  a box is identified by its integer cell vector; boxes are ordered by
+ *       the bit-interleaved key (bit k of c_d -> key bit k*D + d), points inside
+ *       the finest cell by original index.  The row-major index beta of
+ *       Sec. 4.2 is also available (oracle_beta) and must induce the same
+ *       partition.
+ *   R4  far iff sum_d o_d^2 >= theta^2 with o the integer cell offset: this is
+ *       |delta centre| >= theta*l divided by l, free of rounding.  theta = 2 in
+ *       the paper.
+ *   R5  ordered pairs (target p, source q); (p,p) is always near; the j = i
+ *       term is part of the sum.
+ *   R6  depth L = first depth whose largest box has <= zeta points, capped by
+ *       max_depth and Lq; if E == 0 (all points equal) L = 0.
+ *   R7  centre of cell c at depth l: alpha + (c + 1/2) * E/2^l; local
+ *       coordinate t = (x - centre) / (l/2).
+ *
+ * PINS (tests/test_oracle_*.py, none needs a GPU): hand-expanded tiny sums,
+ * closed forms of nodes and barycentric weights, partition of unity and
+ * monomial reproduction, charge conservation of P2M, exactness of the whole
+ * far-field machinery for kernels that are polynomials of degree < p per
+ * coordinate, all-near == brute force, symmetry of the F3M operator, pair
+ * coverage = n^2, interior neighbour counts 27/189 in 3-D, recursive lists ==
+ * brute-force all-pairs classification, error falling with p.
+ * Unpinned by the paper: the value of zeta and the ordering conventions (R3).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_MAX_D 7
+#define ORACLE_MAX_LEVELS 24
+
+/* ------------------------------------------------------------------ */
+/* kernels                                                              */
+/* ------------------------------------------------------------------ */
+/* kernel_id 0: Gaussian exp(-|x-y|^2 / (2 gamma^2))        (the paper's)
+ * kernel_id 1: constant 1                                  (test only)
+ * kernel_id 2: prod_d sum_{k=0..kparam} (x_d y_d)^k        (test only; a
+ *              polynomial of degree kparam in every coordinate)          */
+static double kernel_eval(int kernel_id, int kparam, double gamma, int D,
+                          const double *x, const double *y)
+{
+    if (kernel_id == 0) {
+        double r2 = 0.0;
+        for (int d = 0; d < D; ++d) {
+            double diff = x[d] - y[d];
+            r2 += diff * diff;
+        }
+        return exp(-r2 / (2.0 * gamma * gamma));
+    }
+    if (kernel_id == 1)
+        return 1.0;
+    double prod = 1.0;
+    for (int d = 0; d < D; ++d) {
+        double z = x[d] * y[d], term = 1.0, sum = 1.0;
+        for (int k = 1; k <= kparam; ++k) {
+            term *= z;
+            sum += term;
+        }
+        prod *= sum;
+    }
+    return prod;
+}
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------ */
+/* exact product                                                        */
+/* ------------------------------------------------------------------ */
+/* y_i = sum_{j=0..n-1} k(x_i, x_j) b_j for the rows listed in rows[0..m)
+ * (rows == NULL: all rows, m == n).  X is n x D row-major fp32, widened to
+ * double before any arithmetic. */
+void oracle_rows_k(const float *X, int64_t n, int D, double gamma,
+                   int kernel_id, int kparam, const float *b,
+                   const int64_t *rows, int64_t m, double *y)
+{
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t a = 0; a < m; ++a) {
+        int64_t i = rows ? rows[a] : a;
+        double xi[ORACLE_MAX_D], xj[ORACLE_MAX_D];
+        for (int d = 0; d < D; ++d)
+            xi[d] = (double)X[i * D + d];
+        double acc = 0.0;
+        for (int64_t j = 0; j < n; ++j) {
+            for (int d = 0; d < D; ++d)
+                xj[d] = (double)X[j * D + d];
+            acc += kernel_eval(kernel_id, kparam, gamma, D, xi, xj) * (double)b[j];
+        }
+        y[a] = acc;
+    }
+}
+
+void oracle_direct(const float *X, int64_t n, int D, double gamma,
+                   const float *b, double *y)
+{
+    oracle_rows_k(X, n, D, gamma, 0, 0, b, NULL, n, y);
+}
+
+void oracle_rows(const float *X, int64_t n, int D, double gamma,
+                 const float *b, const int64_t *rows, int64_t m, double *y)
+{
+    oracle_rows_k(X, n, D, gamma, 0, 0, b, rows, m, y);
+}
+
+/* ------------------------------------------------------------------ */
+/* interpolation                                                        */
+/* ------------------------------------------------------------------ */
+/* Chebyshev nodes of the second kind, p of them: s_i = cos(i pi/(p-1)). */
+void oracle_cheb2_nodes(int p, double *s)
+{
+    for (int i = 0; i < p; ++i)
+        s[i] = cos((double)i * M_PI / (double)(p - 1));
+}
+
+/* Product form: L_i(t) = prod_{j != i} (t - s_j)/(s_i - s_j). */
+void oracle_lagrange_product(int p, const double *s, double t, double *L)
+{
+    for (int i = 0; i < p; ++i) {
+        double num = 1.0, den = 1.0;
+        for (int j = 0; j < p; ++j) {
+            if (j == i)
+                continue;
+            num *= t - s[j];
+            den *= s[i] - s[j];
+        }
+        L[i] = num / den;
+    }
+}
+
+/* Barycentric form with the closed-form weights w_i = (-1)^i delta_i,
+ * delta = 1/2 at both ends; L_i(s_j) = delta_ij when t hits a node. */
+void oracle_lagrange_barycentric(int p, const double *s, double t, double *L)
+{
+    for (int j = 0; j < p; ++j) {
+        if (t == s[j]) {
+            for (int i = 0; i < p; ++i)
+                L[i] = (i == j) ? 1.0 : 0.0;
+            return;
+        }
+    }
+    double sum = 0.0;
+    for (int i = 0; i < p; ++i) {
+        double w = ((i % 2) ? -1.0 : 1.0) * ((i == 0 || i == p - 1) ? 0.5 : 1.0);
+        L[i] = w / (t - s[i]);
+        sum += L[i];
+    }
+    for (int i = 0; i < p; ++i)
+        L[i] /= sum;
+}
+
+/* ------------------------------------------------------------------ */
+/* tree                                                                 */
+/* ------------------------------------------------------------------ */
+typedef struct {
+    int64_t nb;        /* occupied boxes at this depth                   */
+    uint64_t *key;     /* [nb] interleaved key of the box, ascending     */
+    int64_t *start;    /* [nb+1] index interval into the permuted points */
+    int64_t *parent;   /* [nb] rank of the parent box one depth up       */
+    int64_t *cstart;   /* [nb+1] rank interval of the children one depth down (filled when divided) */
+    int64_t *near_ptr, *near_col; /* CSR by target rank, columns ascending */
+    int64_t *far_ptr, *far_col;
+} olevel;
+
+typedef struct {
+    int64_t n;
+    int D, Lq, L;
+    double alpha[ORACLE_MAX_D];
+    double E;
+    float s_f;
+    uint32_t *cell;    /* [n*D] cells at depth Lq, ORIGINAL point order */
+    uint64_t *pkey;    /* [n] key at depth Lq, PERMUTED order            */
+    int64_t *perm;     /* [n] perm[k] = original index of the k-th point in box order */
+    olevel lev[ORACLE_MAX_LEVELS + 1];
+} otree;
+
+/* quantisation depth: as deep as a 32-bit key allows, at most 20 */
+int oracle_quant_depth(int D)
+{
+    int q = 32 / D;
+    return q > 20 ? 20 : q;
+}
+
+static uint64_t interleave(const uint32_t *c, int D, int depth)
+{
+    uint64_t key = 0;
+    for (int k = 0; k < depth; ++k)
+        for (int d = 0; d < D; ++d)
+            key |= (uint64_t)((c[d] >> k) & 1u) << (k * D + d);
+    return key;
+}
+
+static void deinterleave(uint64_t key, int D, int depth, int64_t *c)
+{
+    for (int d = 0; d < D; ++d)
+        c[d] = 0;
+    for (int k = 0; k < depth; ++k)
+        for (int d = 0; d < D; ++d)
+            c[d] |= (int64_t)((key >> (k * D + d)) & 1u) << k;
+}
+
+typedef struct {
+    uint64_t key;
+    int64_t idx;
+} keyidx;
+
+static int cmp_keyidx(const void *a, const void *b)
+{
+    const keyidx *p = (const keyidx *)a, *q = (const keyidx *)b;
+    if (p->key != q->key)
+        return p->key < q->key ? -1 : 1;
+    return p->idx < q->idx ? -1 : (p->idx > q->idx);
+}
+
+static void free_level(olevel *lv)
+{
+    free(lv->key); free(lv->start); free(lv->parent); free(lv->cstart);
+    free(lv->near_ptr); free(lv->near_col); free(lv->far_ptr); free(lv->far_col);
+    memset(lv, 0, sizeof(*lv));
+}
+
+void oracle_tree_free(otree *t)
+{
+    if (!t)
+        return;
+    for (int l = 0; l <= ORACLE_MAX_LEVELS; ++l)
+        free_level(&t->lev[l]);
+    free(t->cell); free(t->pkey); free(t->perm);
+    free(t);
+}
+
+/* Divide: the box table of depth l, read off the permuted keys. */
+static void divide(otree *t, int l)
+{
+    olevel *lv = &t->lev[l];
+    int shift = t->D * (t->Lq - l);
+    int64_t n = t->n, nb = 0;
+    for (int64_t k = 0; k < n; ++k)
+        if (k == 0 || (t->pkey[k] >> shift) != (t->pkey[k - 1] >> shift))
+            ++nb;
+    lv->nb = nb;
+    lv->key = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)nb);
+    lv->start = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nb + 1));
+    lv->parent = (int64_t *)malloc(sizeof(int64_t) * (size_t)nb);
+    int64_t r = 0;
+    for (int64_t k = 0; k < n; ++k)
+        if (k == 0 || (t->pkey[k] >> shift) != (t->pkey[k - 1] >> shift)) {
+            lv->key[r] = t->pkey[k] >> shift;
+            lv->start[r] = k;
+            ++r;
+        }
+    lv->start[nb] = n;
+    if (l > 0) {
+        olevel *up = &t->lev[l - 1];
+        up->cstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(up->nb + 1));
+        int64_t P = -1;
+        for (int64_t a = 0; a < nb; ++a) {
+            if (a == 0 || (lv->key[a] >> t->D) != (lv->key[a - 1] >> t->D)) {
+                ++P;
+                up->cstart[P] = a;
+            }
+            lv->parent[a] = P;
+        }
+        up->cstart[up->nb] = nb;
+    } else {
+        lv->parent[0] = -1;
+    }
+}
+
+static int64_t max_box(const olevel *lv)
+{
+    int64_t m = 0;
+    for (int64_t a = 0; a < lv->nb; ++a)
+        if (lv->start[a + 1] - lv->start[a] > m)
+            m = lv->start[a + 1] - lv->start[a];
+    return m;
+}
+
+/* New interactions at depth l from the near pairs of depth l-1, split into
+ * near and far (reading R4).  Rows come out sorted because the parent's row is
+ * sorted and the children of a box have consecutive ranks. */
+static void new_interactions(otree *t, int l, double theta, int force_all_near)
+{
+    olevel *lv = &t->lev[l], *up = &t->lev[l - 1];
+    int D = t->D;
+    int64_t nb = lv->nb;
+    lv->near_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
+    lv->far_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {
+            for (int64_t a = 0; a < nb; ++a) {
+                lv->near_ptr[a + 1] += lv->near_ptr[a];
+                lv->far_ptr[a + 1] += lv->far_ptr[a];
+            }
+            lv->near_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(lv->near_ptr[nb] + 1));
+            lv->far_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(lv->far_ptr[nb] + 1));
+        }
+#pragma omp parallel for schedule(dynamic, 64)
+        for (int64_t a = 0; a < nb; ++a) {
+            int64_t ca[ORACLE_MAX_D], cb[ORACLE_MAX_D];
+            deinterleave(lv->key[a], D, l, ca);
+            int64_t P = lv->parent[a];
+            int64_t nn = 0, nf = 0;
+            int64_t *ncol = pass ? lv->near_col + lv->near_ptr[a] : NULL;
+            int64_t *fcol = pass ? lv->far_col + lv->far_ptr[a] : NULL;
+            for (int64_t e = up->near_ptr[P]; e < up->near_ptr[P + 1]; ++e) {
+                int64_t Q = up->near_col[e];
+                for (int64_t bq = up->cstart[Q]; bq < up->cstart[Q + 1]; ++bq) {
+                    deinterleave(lv->key[bq], D, l, cb);
+                    double d2 = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        d2 += (double)((cb[d] - ca[d]) * (cb[d] - ca[d]));
+                    int is_far = !force_all_near && d2 >= theta * theta;
+                    if (is_far) {
+                        if (pass) fcol[nf] = bq;
+                        ++nf;
+                    } else {
+                        if (pass) ncol[nn] = bq;
+                        ++nn;
+                    }
+                }
+            }
+            if (!pass) {
+                lv->near_ptr[a + 1] = nn;
+                lv->far_ptr[a + 1] = nf;
+            }
+        }
+    }
+}
+
+/* Builds the partition and the interaction lists of Algorithm 1 (everything
+ * that does not depend on b).  Returns NULL on bad arguments. */
+otree *oracle_tree_build(const float *X, int64_t n, int D, double theta,
+                         int64_t zeta, int max_depth, int force_all_near)
+{
+    if (!X || n <= 0 || D < 1 || D > ORACLE_MAX_D || !(theta > 0.0) || zeta < 1)
+        return NULL;
+    otree *t = (otree *)calloc(1, sizeof(otree));
+    t->n = n;
+    t->D = D;
+    t->Lq = oracle_quant_depth(D);
+
+    /* enclosing cube: per-dim minimum, edge = largest extent (fp32, R2) */
+    float Ef = 0.0f;
+    for (int d = 0; d < D; ++d) {
+        float mn = X[d], mx = X[d];
+        for (int64_t i = 1; i < n; ++i) {
+            float v = X[i * D + d];
+            if (v < mn) mn = v;
+            if (v > mx) mx = v;
+        }
+        volatile float ext = mx - mn;
+        if (ext > Ef) Ef = ext;
+        t->alpha[d] = (double)mn;
+    }
+    t->E = (double)Ef;
+    t->s_f = Ef > 0.0f ? (float)(ldexp(1.0, t->Lq) / (double)Ef) : 0.0f;
+
+    /* cells and keys at the quantisation depth (R2, R3) */
+    uint32_t cmax = (uint32_t)((1ull << t->Lq) - 1);
+    t->cell = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n * (size_t)D);
+    keyidx *ki = (keyidx *)malloc(sizeof(keyidx) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) {
+        for (int d = 0; d < D; ++d) {
+            volatile float diff = X[i * D + d] - (float)t->alpha[d];
+            volatile float u = diff * t->s_f;
+            uint32_t c = (uint32_t)u;
+            t->cell[i * D + d] = c > cmax ? cmax : c;
+        }
+        ki[i].key = interleave(&t->cell[i * D], D, t->Lq);
+        ki[i].idx = i;
+    }
+    qsort(ki, (size_t)n, sizeof(keyidx), cmp_keyidx);
+    t->pkey = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)n);
+    t->perm = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+    for (int64_t k = 0; k < n; ++k) {
+        t->pkey[k] = ki[k].key;
+        t->perm[k] = ki[k].idx;
+    }
+    free(ki);
+
+    /* depth 0: one box, one (near) interaction */
+    divide(t, 0);
+    olevel *root = &t->lev[0];
+    root->near_ptr = (int64_t *)calloc(2, sizeof(int64_t));
+    root->near_ptr[1] = 1;
+    root->near_col = (int64_t *)calloc(1, sizeof(int64_t));
+    root->far_ptr = (int64_t *)calloc(2, sizeof(int64_t));
+    root->far_col = (int64_t *)calloc(1, sizeof(int64_t));
+
+    int cap = t->Lq;
+    if (max_depth > 0 && max_depth < cap) cap = max_depth;
+    if (cap > ORACLE_MAX_LEVELS) cap = ORACLE_MAX_LEVELS;
+    if (Ef == 0.0f) cap = 0; /* R6 */
+    int l = 0;
+    /* Algorithm 1: while interactions remain and the largest box is above zeta */
+    while (t->lev[l].near_ptr[t->lev[l].nb] > 0 && max_box(&t->lev[l]) > zeta && l < cap) {
+        ++l;
+        divide(t, l);
+        new_interactions(t, l, theta, force_all_near);
+    }
+    t->L = l;
+    return t;
+}
+
+/* ---- introspection ---- */
+int oracle_tree_depth(const otree *t) { return t->L; }
+int oracle_tree_quant_depth(const otree *t) { return t->Lq; }
+double oracle_tree_edge(const otree *t) { return t->E; }
+void oracle_tree_alpha(const otree *t, double *alpha)
+{
+    for (int d = 0; d < t->D; ++d) alpha[d] = t->alpha[d];
+}
+int64_t oracle_tree_nboxes(const otree *t, int level) { return t->lev[level].nb; }
+void oracle_tree_perm(const otree *t, int64_t *perm)
+{
+    memcpy(perm, t->perm, sizeof(int64_t) * (size_t)t->n);
+}
+/* key of every point at depth Lq, ORIGINAL order */
+void oracle_tree_point_keys(const otree *t, uint64_t *keys)
+{
+    for (int64_t i = 0; i < t->n; ++i)
+        keys[i] = interleave(&t->cell[i * t->D], t->D, t->Lq);
+}
+void oracle_tree_boxes(const otree *t, int level, uint64_t *keys, int64_t *starts)
+{
+    const olevel *lv = &t->lev[level];
+    memcpy(keys, lv->key, sizeof(uint64_t) * (size_t)lv->nb);
+    memcpy(starts, lv->start, sizeof(int64_t) * (size_t)(lv->nb + 1));
+}
+int64_t oracle_tree_list_size(const otree *t, int level, int kind)
+{
+    const olevel *lv = &t->lev[level];
+    return kind ? lv->far_ptr[lv->nb] : lv->near_ptr[lv->nb];
+}
+void oracle_tree_list(const otree *t, int level, int kind, int64_t *row_ptr, int64_t *cols)
+{
+    const olevel *lv = &t->lev[level];
+    const int64_t *ptr = kind ? lv->far_ptr : lv->near_ptr;
+    const int64_t *col = kind ? lv->far_col : lv->near_col;
+    memcpy(row_ptr, ptr, sizeof(int64_t) * (size_t)(lv->nb + 1));
+    memcpy(cols, col, sizeof(int64_t) * (size_t)ptr[lv->nb]);
+}
+/* The row-major box index of Sec. 4.2 at a depth, per point, ORIGINAL order:
+ * beta = sum_d 2^(depth*d) * cell_d  (d counted from 0). */
+void oracle_beta(const otree *t, int level, uint64_t *beta)
+{
+    for (int64_t i = 0; i < t->n; ++i) {
+        uint64_t bidx = 0;
+        for (int d = 0; d < t->D; ++d)
+            bidx += ((uint64_t)1 << (level * d)) * (uint64_t)(t->cell[i * t->D + d] >> (t->Lq - level));
+        beta[i] = bidx;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* far field and near field                                             */
+/* ------------------------------------------------------------------ */
+static int64_t ipow(int p, int D)
+{
+    int64_t r = 1;
+    for (int d = 0; d < D; ++d) r *= p;
+    return r;
+}
+
+/* centre of a box from its key (R7) */
+static void box_centre(const otree *t, int level, uint64_t key, double *c)
+{
+    int64_t cell[ORACLE_MAX_D];
+    deinterleave(key, t->D, level, cell);
+    double l = t->E / ldexp(1.0, level);
+    for (int d = 0; d < t->D; ++d)
+        c[d] = t->alpha[d] + ((double)cell[d] + 0.5) * l;
+}
+
+/* node i of the grid of a box: centre + (l/2) * s_{i_d} in every dimension */
+static void node_coords(const otree *t, int level, const double *centre, int p,
+                        const double *s, int64_t i, double *x)
+{
+    double half = 0.5 * t->E / ldexp(1.0, level);
+    for (int d = 0; d < t->D; ++d) {
+        x[d] = centre[d] + half * s[i % p];
+        i /= p;
+    }
+}
+
+/* all r tensor-product Lagrange weights of one point of box `centre` */
+static void point_weights(const otree *t, int level, const double *centre, int p,
+                          const double *s, const float *x, double *Lw /* [r] */)
+{
+    int D = t->D;
+    double half = 0.5 * t->E / ldexp(1.0, level);
+    double L1[ORACLE_MAX_D][32];
+    for (int d = 0; d < D; ++d) {
+        double tt = ((double)x[d] - centre[d]) / half;
+        oracle_lagrange_product(p, s, tt, L1[d]);
+    }
+    int64_t r = ipow(p, D);
+    for (int64_t i = 0; i < r; ++i) {
+        int64_t rem = i;
+        double w = 1.0;
+        for (int d = 0; d < D; ++d) {
+            w *= L1[d][rem % p];
+            rem /= p;
+        }
+        Lw[i] = w;
+    }
+}
+
+/* v1 = L_Y b for one box: W[i] = sum_{j in box} L_i(t_j) b_j */
+static void p2m_box(const otree *t, const float *X, const float *b, int level,
+                    int64_t q, int p, const double *s, double *W, double *scratch)
+{
+    const olevel *lv = &t->lev[level];
+    int64_t r = ipow(p, t->D);
+    double centre[ORACLE_MAX_D];
+    box_centre(t, level, lv->key[q], centre);
+    for (int64_t i = 0; i < r; ++i) W[i] = 0.0;
+    for (int64_t k = lv->start[q]; k < lv->start[q + 1]; ++k) {
+        int64_t j = t->perm[k];
+        point_weights(t, level, centre, p, s, X + j * t->D, scratch);
+        for (int64_t i = 0; i < r; ++i) W[i] += scratch[i] * (double)b[j];
+    }
+}
+
+/* Node weights W of every box of a depth (for the charge-conservation pin). */
+void oracle_p2m_level(const otree *t, const float *X, const float *b, int p,
+                      int level, double *W /* [nb*r] */)
+{
+    int64_t r = ipow(p, t->D);
+    double s[32];
+    oracle_cheb2_nodes(p, s);
+#pragma omp parallel
+    {
+        double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
+#pragma omp for schedule(dynamic, 8)
+        for (int64_t q = 0; q < t->lev[level].nb; ++q)
+            p2m_box(t, X, b, level, q, p, s, W + q * r, scratch);
+        free(scratch);
+    }
+}
+
+/* y = F3M(X, b) following Algorithm 1.
+ *   literal == 0: per depth, v1 of every source box is formed once, then
+ *                 v2 of a target box is summed over its far row, then applied.
+ *   literal == 1: every far pair is handled on its own, v1 -> v2 -> v, exactly
+ *                 as a single far-field product is described (small inputs).
+ * y is in ORIGINAL point order, fp64. */
+int oracle_f3m_apply(const otree *t, const float *X, double gamma, int p,
+                     int kernel_id, int kparam, const float *b, double *y, int literal)
+{
+    if (!t || !X || !b || !y || p < 2 || p > 32)
+        return 1;
+    int D = t->D;
+    int64_t n = t->n, r = ipow(p, D);
+    double s[32];
+    oracle_cheb2_nodes(p, s);
+    double *ys = (double *)calloc((size_t)n, sizeof(double)); /* permuted order */
+
+    for (int l = 1; l <= t->L; ++l) {
+        const olevel *lv = &t->lev[l];
+        if (lv->far_ptr[lv->nb] == 0)
+            continue;
+        double *W = NULL;
+        if (!literal) {
+            W = (double *)malloc(sizeof(double) * (size_t)lv->nb * (size_t)r);
+            oracle_p2m_level(t, X, b, p, l, W);
+        }
+#pragma omp parallel
+        {
+            double *V = (double *)malloc(sizeof(double) * (size_t)r);
+            double *Wq = (double *)malloc(sizeof(double) * (size_t)r);
+            double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
+            double *xs = (double *)malloc(sizeof(double) * (size_t)r * D);
+            double cp[ORACLE_MAX_D], cq[ORACLE_MAX_D], xq[ORACLE_MAX_D];
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t a = 0; a < lv->nb; ++a) {
+                if (lv->far_ptr[a + 1] == lv->far_ptr[a])
+                    continue;
+                box_centre(t, l, lv->key[a], cp);
+                for (int64_t i = 0; i < r; ++i)
+                    node_coords(t, l, cp, p, s, i, xs + i * D);
+                for (int64_t i = 0; i < r; ++i) V[i] = 0.0;
+                for (int64_t e = lv->far_ptr[a]; e < lv->far_ptr[a + 1]; ++e) {
+                    int64_t q = lv->far_col[e];
+                    const double *wq = W ? W + q * r : Wq;
+                    if (literal) {
+                        p2m_box(t, X, b, l, q, p, s, Wq, scratch);
+                        for (int64_t i = 0; i < r; ++i) V[i] = 0.0;
+                    }
+                    box_centre(t, l, lv->key[q], cq);
+                    /* v2 = K v1 with K_ij = k(s^p_i, s^q_j) */
+                    for (int64_t j = 0; j < r; ++j) {
+                        node_coords(t, l, cq, p, s, j, xq);
+                        for (int64_t i = 0; i < r; ++i)
+                            V[i] += kernel_eval(kernel_id, kparam, gamma, D, xs + i * D, xq) * wq[j];
+                    }
+                    if (literal) {
+                        for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k) {
+                            point_weights(t, l, cp, p, s, X + t->perm[k] * D, scratch);
+                            double acc = 0.0;
+                            for (int64_t i = 0; i < r; ++i) acc += scratch[i] * V[i];
+                            ys[k] += acc;
+                        }
+                    }
+                }
+                if (!literal) {
+                    /* v = L_X^T v2 */
+                    for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k) {
+                        point_weights(t, l, cp, p, s, X + t->perm[k] * D, scratch);
+                        double acc = 0.0;
+                        for (int64_t i = 0; i < r; ++i) acc += scratch[i] * V[i];
+                        ys[k] += acc;
+                    }
+                }
+            }
+            free(V); free(Wq); free(scratch); free(xs);
+        }
+        free(W);
+    }
+
+    /* remaining near-field interactions at the last depth: exact sums */
+    {
+        const olevel *lv = &t->lev[t->L];
+#pragma omp parallel for schedule(dynamic, 4)
+        for (int64_t a = 0; a < lv->nb; ++a) {
+            double xi[ORACLE_MAX_D], xj[ORACLE_MAX_D];
+            for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k) {
+                int64_t i = t->perm[k];
+                for (int d = 0; d < D; ++d) xi[d] = (double)X[i * D + d];
+                double acc = 0.0;
+                for (int64_t e = lv->near_ptr[a]; e < lv->near_ptr[a + 1]; ++e) {
+                    int64_t q = lv->near_col[e];
+                    for (int64_t kk = lv->start[q]; kk < lv->start[q + 1]; ++kk) {
+                        int64_t j = t->perm[kk];
+                        for (int d = 0; d < D; ++d) xj[d] = (double)X[j * D + d];
+                        acc += kernel_eval(kernel_id, kparam, gamma, D, xi, xj) * (double)b[j];
+                    }
+                }
+                ys[k] += acc;
+            }
+        }
+    }
+    /* back to the caller's order */
+    for (int64_t k = 0; k < n; ++k)
+        y[t->perm[k]] = ys[k];
+    free(ys);
+    return 0;
+}

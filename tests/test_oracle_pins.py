@@ -1,0 +1,446 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+None of these tests needs a GPU or touches the HIP library.  Each one is
+chosen so that a plausible slip in oracle/f3m_oracle.c (a dropped term, a
+wrong sign or index, a transposed operand) fails it.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2202_01085_amd import inputs
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------
+# exact product: hand-expanded sums (Sec. 2, v_i = sum_j k(x_i,y_j) b_j with the
+# Gaussian kernel of Sec. 5)
+# ----------------------------------------------------------------------------
+def test_direct_two_points_1d_closed_form():
+    X = np.array([[0.0], [1.0]], dtype=np.float32)
+    b = np.array([1.0, 2.0], dtype=np.float32)
+    y = oracle.direct(X, b, 1.0)
+    e = math.exp(-0.5)
+    assert y == pytest.approx([1.0 + 2.0 * e, e + 2.0], rel=0, abs=1e-15)
+
+
+def test_direct_three_points_2d_hand_expanded():
+    # |x0-x1|^2 = 9+16 = 25, |x0-x2|^2 = 1, |x1-x2|^2 = 9+9 = 18 ; gamma = 2 -> /8
+    X = np.array([[0.0, 0.0], [3.0, 4.0], [0.0, 1.0]], dtype=np.float32)
+    b = np.array([0.5, -1.0, 3.0], dtype=np.float32)
+    k01, k02, k12 = math.exp(-25 / 8), math.exp(-1 / 8), math.exp(-18 / 8)
+    want = [0.5 - k01 + 3 * k02, 0.5 * k01 - 1.0 + 3 * k12, 0.5 * k02 - k12 + 3.0]
+    assert oracle.direct(X, b, 2.0) == pytest.approx(want, rel=0, abs=1e-15)
+
+
+def test_direct_lengthscale_enters_as_two_gamma_squared():
+    X = np.array([[0.0, 0.0, 0.0], [1.0, 2.0, 2.0]], dtype=np.float32)   # |d|^2 = 9
+    b = np.array([0.0, 1.0], dtype=np.float32)
+    for gamma in (0.5, 1.5, 3.0):
+        assert oracle.direct(X, b, gamma)[0] == pytest.approx(math.exp(-9.0 / (2 * gamma * gamma)), abs=1e-16)
+
+
+def test_direct_coincident_points_and_flat_limit():
+    X = np.full((5, 3), 0.25, dtype=np.float32)
+    b = np.arange(1, 6, dtype=np.float32)
+    assert oracle.direct(X, b, 0.7) == pytest.approx([15.0] * 5, abs=1e-13)
+    rng = np.random.default_rng(0)
+    X = rng.random((50, 3)).astype(np.float32)
+    b = rng.standard_normal(50).astype(np.float32)
+    y = oracle.direct(X, b, 1e6)
+    assert y == pytest.approx([float(b.astype(np.float64).sum())] * 50, abs=1e-9)
+
+
+def test_direct_is_symmetric_operator_and_rows_subset():
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((200, 4)).astype(np.float32)
+    b = rng.standard_normal(200).astype(np.float32)
+    u = rng.standard_normal(200).astype(np.float32)
+    Kb, Ku = oracle.direct(X, b, 0.8), oracle.direct(X, u, 0.8)
+    assert float(u.astype(np.float64) @ Kb) == pytest.approx(float(b.astype(np.float64) @ Ku), rel=1e-12)
+    rows = np.array([7, 0, 199, 42])
+    assert oracle.rows(X, b, 0.8, rows) == pytest.approx(Kb[rows], rel=0, abs=0)
+
+
+def test_direct_matches_numpy_dense_matrix():
+    rng = np.random.default_rng(2)
+    X = rng.random((300, 7)).astype(np.float32)
+    b = rng.standard_normal(300).astype(np.float32)
+    Xd = X.astype(np.float64)
+    d2 = ((Xd[:, None, :] - Xd[None, :, :]) ** 2).sum(-1)
+    want = np.exp(-d2 / (2 * 0.9 ** 2)) @ b.astype(np.float64)
+    assert oracle.direct(X, b, 0.9) == pytest.approx(want, rel=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# nodes and weights (Sec. 3 "Lagrange interpolation", Appendix C)
+# ----------------------------------------------------------------------------
+def test_cheb2_nodes_p4_golden():
+    # tests/golden/cheb2_p4.txt: the four second-kind nodes cos(i pi/3) and the
+    # closed-form barycentric weights (-1)^i delta_i of Appendix C
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "cheb2_p4.txt")) if not l.startswith("#")]
+    nodes = [float(r[0]) for r in rows]
+    weights = [float(r[1]) for r in rows]
+    assert oracle.cheb2_nodes(4) == pytest.approx(nodes, abs=1e-15)
+    # barycentric weights are defined up to a common factor: compare ratios
+    s = oracle.cheb2_nodes(4)
+    w = np.array([1.0 / np.prod([s[i] - s[j] for j in range(4) if j != i]) for i in range(4)])
+    assert w / w[0] == pytest.approx(np.array(weights) / weights[0], rel=1e-13)
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 5, 6, 8])
+def test_nodes_endpoints_and_symmetry(p):
+    s = oracle.cheb2_nodes(p)
+    assert s[0] == 1.0 and s[-1] == pytest.approx(-1.0, abs=1e-15)
+    assert np.all(np.diff(s) < 0)
+    assert s + s[::-1] == pytest.approx(np.zeros(p), abs=1e-15)
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 5, 7])
+def test_lagrange_kronecker_delta_at_nodes(p):
+    s = oracle.cheb2_nodes(p)
+    for j in range(p):
+        assert oracle.lagrange_product(p, s[j]) == pytest.approx(np.eye(p)[j], abs=1e-14)
+        assert oracle.lagrange_barycentric(p, s[j]) == pytest.approx(np.eye(p)[j], abs=0)
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 5, 6])
+def test_product_form_equals_barycentric_form(p):
+    for t in np.linspace(-1.07, 1.07, 41):
+        assert oracle.lagrange_product(p, t) == pytest.approx(oracle.lagrange_barycentric(p, t), abs=1e-12)
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 6])
+def test_partition_of_unity_and_monomial_reproduction(p):
+    s = oracle.cheb2_nodes(p)
+    for t in (-0.93, -0.2, 0.0, 0.41, 1.0, 1.2):
+        L = oracle.lagrange_product(p, t)
+        for k in range(p):
+            assert float(L @ s ** k) == pytest.approx(t ** k, abs=1e-12)
+
+
+def test_lagrange_p2_is_linear_hat():
+    # p = 2: nodes {1,-1}, L_0 = (1+t)/2, L_1 = (1-t)/2
+    for t in (-1.0, -0.3, 0.5):
+        assert oracle.lagrange_product(2, t) == pytest.approx([(1 + t) / 2, (1 - t) / 2], abs=1e-15)
+
+
+# ----------------------------------------------------------------------------
+# partition (Sec. 3 enclosing cube, Sec. 4.2 box index formula and empty boxes)
+# ----------------------------------------------------------------------------
+def _cloud(n, D, seed, dist="uniform"):
+    gen = {"uniform": inputs.points_uniform, "normal": inputs.points_normal,
+           "mixture": inputs.points_mixture}[dist]
+    return gen(n, D, seed).numpy()
+
+
+def test_cube_edge_and_anchor():
+    X = np.array([[0.0, 10.0], [4.0, 11.0], [1.0, 10.5]], dtype=np.float32)
+    T = oracle.Tree(X, zeta=1)
+    assert T.E == 4.0
+    assert list(T.alpha) == [0.0, 10.0]
+
+
+def test_cells_follow_the_floor_formula_on_a_lattice():
+    # points on an exactly representable lattice: floor(2^l (x-alpha)/E) can be
+    # written down by hand.  E = 8, alpha = 0, cell at depth 3 = floor(x).
+    pts = np.array([[0.0, 0.0], [8.0, 8.0], [1.5, 6.25], [7.99, 0.5], [4.0, 4.0], [3.999, 4.001], [5.2, 5.2]],
+                   dtype=np.float32)
+    T = oracle.Tree(pts, zeta=1, max_depth=3)
+    assert T.L == 3
+    beta = T.beta(3)                       # sum_d 2^(3 d) cell_d
+    want_cells = [(0, 0), (7, 7), (1, 6), (7, 0), (4, 4), (3, 4), (5, 5)]     # max face clamps to 7
+    assert list(beta) == [cx + 8 * cy for cx, cy in want_cells]
+    beta1 = T.beta(1)
+    assert list(beta1) == [(cx >> 2) + 2 * (cy >> 2) for cx, cy in want_cells]
+
+
+@pytest.mark.parametrize("D,dist", [(1, "uniform"), (2, "normal"), (3, "uniform"), (3, "normal"), (5, "uniform"), (7, "mixture")])
+def test_partition_consistency(D, dist):
+    n = 4000
+    X = _cloud(n, D, 11 + D, dist)
+    T = oracle.Tree(X, zeta=32)
+    perm = T.perm()
+    assert sorted(perm.tolist()) == list(range(n))
+    pk = T.point_keys()
+    # permutation = ascending (key, original index)
+    order = np.lexsort((np.arange(n), pk))
+    assert np.array_equal(order, perm)
+    for l in range(T.L + 1):
+        keys, starts = T.boxes(l)
+        counts = np.diff(starts)
+        assert counts.sum() == n and np.all(counts > 0)          # empty boxes removed
+        assert np.all(np.diff(keys.astype(np.int64)) > 0)
+        # grouping by the paper's row-major beta == grouping by the interleaved key
+        beta = T.beta(l)[perm]
+        k_l = (pk[perm] >> np.uint64(D * (T.Lq - l)))
+        for arr in (beta, k_l):
+            heads = np.flatnonzero(np.r_[True, arr[1:] != arr[:-1]])
+            assert np.array_equal(heads, starts[:-1])
+        assert len(np.unique(beta)) == len(keys)
+        if l > 0:
+            pkeys, _ = T.boxes(l - 1)
+            assert set((keys >> np.uint64(D)).tolist()) == set(pkeys.tolist())   # children inside parents
+    # stop rule: largest box above zeta at every depth before L, not above at L (unless capped)
+    for l in range(T.L):
+        assert np.diff(T.boxes(l)[1]).max() > 32
+    if T.L < T.Lq:
+        assert np.diff(T.boxes(T.L)[1]).max() <= 32
+
+
+def test_points_lie_in_their_geometric_cell():
+    X = _cloud(3000, 3, 5)
+    T = oracle.Tree(X, zeta=16)
+    perm, (keys, starts) = T.perm(), T.boxes(T.L)
+    l = T.E / 2 ** T.L
+    for r in range(0, len(keys), 37):
+        cell = [sum(((int(keys[r]) >> (k * 3 + d)) & 1) << k for k in range(T.L)) for d in range(3)]
+        pts = X[perm[starts[r]:starts[r + 1]]].astype(np.float64)
+        lo = T.alpha + np.array(cell) * l
+        assert np.all(pts >= lo - 1e-6) and np.all(pts <= lo + l + 1e-6)
+
+
+def test_degenerate_single_location_is_one_box():
+    X = np.full((300, 3), 1.5, dtype=np.float32)
+    b = np.linspace(-1, 1, 300).astype(np.float32)
+    T = oracle.Tree(X, zeta=8)
+    assert T.L == 0 and T.E == 0.0
+    assert T.apply(b, 1.0, 4) == pytest.approx([float(b.astype(np.float64).sum())] * 300, abs=1e-12)
+
+
+# ----------------------------------------------------------------------------
+# interaction lists (Sec. 3 far rule, Sec. 4.1 recursive division, Thm 2)
+# ----------------------------------------------------------------------------
+def _cells(keys, D, l):
+    out = np.zeros((len(keys), D), dtype=np.int64)
+    for d in range(D):
+        for k in range(l):
+            out[:, d] |= ((keys.astype(np.int64) >> (k * D + d)) & 1) << k
+    return out
+
+
+def _brute_lists(T, l, theta):
+    """near(l) = all occupied pairs closer than theta cells; far(l) = occupied pairs that are not
+    near and whose parents are near: written from the definition, no recursion."""
+    keys, _ = T.boxes(l)
+    c = _cells(keys, T.D, l)
+    d2 = ((c[:, None, :] - c[None, :, :]) ** 2).sum(-1)
+    near = d2 < theta * theta
+    pc = c >> 1
+    pd2 = ((pc[:, None, :] - pc[None, :, :]) ** 2).sum(-1)
+    far = (~near) & (pd2 < theta * theta)
+    return near, far
+
+
+@pytest.mark.parametrize("D,n,dist,theta", [(1, 600, "uniform", 2.0), (2, 1500, "normal", 2.0), (3, 2500, "uniform", 2.0),
+                                            (3, 2500, "normal", 1.5), (3, 1500, "normal", 3.0), (4, 2000, "uniform", 2.0),
+                                            (7, 3000, "mixture", 2.0)])
+def test_recursive_lists_equal_bruteforce_classification(D, n, dist, theta):
+    X = _cloud(n, D, 100 + D, dist)
+    T = oracle.Tree(X, theta=theta, zeta=12, max_depth=4 if D >= 4 else 0)
+    assert T.L >= 2
+    for l in range(1, T.L + 1):
+        near, far = _brute_lists(T, l, theta)
+        for kind, want in ((0, near), (1, far)):
+            ptr, cols = T.interactions(l, kind)
+            got = np.zeros_like(want)
+            for a in range(len(ptr) - 1):
+                row = cols[ptr[a]:ptr[a + 1]]
+                assert np.all(np.diff(row) > 0)                 # rows stay sorted
+                got[a, row] = True
+            assert np.array_equal(got, want), (l, kind)
+
+
+def test_pair_coverage_every_point_pair_exactly_once():
+    for D, n, dist in ((3, 5000, "normal"), (2, 3000, "uniform"), (5, 3000, "mixture")):
+        X = _cloud(n, D, 200 + D, dist)
+        T = oracle.Tree(X, zeta=20, max_depth=5)
+        total = 0
+        for l in range(1, T.L + 1):
+            cnt = np.diff(T.boxes(l)[1])
+            ptr, cols = T.interactions(l, 1)
+            total += int((np.repeat(cnt, np.diff(ptr)) * cnt[cols]).sum())
+        cnt = np.diff(T.boxes(T.L)[1])
+        ptr, cols = T.interactions(T.L, 0)
+        total += int((np.repeat(cnt, np.diff(ptr)) * cnt[cols]).sum())
+        assert total == n * n
+
+
+def test_interior_neighbour_counts_3d_2d_1d():
+    # a dense lattice: every cell occupied, so interior boxes see the full stencil
+    for D, near_want, far_want in ((1, 3, 3), (2, 9, 27), (3, 27, 189)):
+        m = 16 if D < 3 else 8
+        L = int(math.log2(m))
+        grid = np.array(list(itertools.product(range(m), repeat=D)), dtype=np.float32) + 0.5
+        # two extra corner points fix the cube to [0,m]^D
+        X = np.vstack([grid, np.zeros((1, D), np.float32), np.full((1, D), m, np.float32)])
+        T = oracle.Tree(X, zeta=1, max_depth=L)
+        assert T.L == L and T.nboxes(L) == m ** D
+        keys, _ = T.boxes(L)
+        c = _cells(keys, D, L)
+        interior = np.all((c >= 3) & (c <= m - 4), axis=1)
+        nptr, _ = T.interactions(L, 0)
+        fptr, _ = T.interactions(L, 1)
+        assert set(np.diff(nptr)[interior]) == {near_want}
+        assert set(np.diff(fptr)[interior]) == {far_want}
+
+
+def test_near_count_7d_stencil():
+    # offsets in {-1,0,1}^7 with at most three non-zero entries: 1 + 14 + 84 + 280 = 379
+    offs = [o for o in itertools.product((-1, 0, 1), repeat=7) if sum(v * v for v in o) < 4]
+    assert len(offs) == 379
+    centre = np.full((1, 7), 1.5, np.float32)
+    X = np.vstack([centre + np.array(offs, np.float32), np.zeros((1, 7), np.float32),
+                   np.full((1, 7), 4.0, np.float32)])
+    T = oracle.Tree(X, zeta=1, max_depth=2)
+    keys, _ = T.boxes(2)
+    c = _cells(keys, 7, 2)
+    a = int(np.flatnonzero(np.all(c == 1, axis=1))[0])
+    nptr, _ = T.interactions(2, 0)
+    assert nptr[a + 1] - nptr[a] == 379
+
+
+def test_near_list_growth_bound_and_symmetry():
+    X = _cloud(6000, 3, 77, "normal")
+    T = oracle.Tree(X, zeta=10)
+    prev = 1
+    for l in range(1, T.L + 1):
+        nptr, ncol = T.interactions(l, 0)
+        fptr, fcol = T.interactions(l, 1)
+        assert len(ncol) + len(fcol) <= prev * 4 ** 3          # M_i <= M_{i-1} 2^{2D}
+        prev = len(ncol)
+        for ptr, col in ((nptr, ncol), (fptr, fcol)):
+            rows = np.repeat(np.arange(len(ptr) - 1), np.diff(ptr))
+            pairs = set(zip(rows.tolist(), col.tolist()))
+            assert pairs == {(q, p) for p, q in pairs}          # (p,q) in list <=> (q,p) in list
+        assert all(a in ncol[nptr[a]:nptr[a + 1]] for a in range(0, len(nptr) - 1, 17))   # self pair near
+
+
+def test_no_far_pairs_at_depth_one_up_to_3d_but_some_in_4d():
+    for D in (1, 2, 3):
+        T = oracle.Tree(_cloud(500, D, 9), zeta=4)
+        assert len(T.interactions(1, 1)[1]) == 0
+    T = oracle.Tree(_cloud(2000, 4, 9), zeta=4, max_depth=2)
+    assert len(T.interactions(1, 1)[1]) == 16               # the 16 opposite-corner ordered pairs
+
+
+# ----------------------------------------------------------------------------
+# far-field machinery (Sec. 3 "Interpolating k(x,y)", Fig. 4 steps 1-3)
+# ----------------------------------------------------------------------------
+def test_p2m_conserves_charge_and_first_moments():
+    X = _cloud(3000, 3, 31, "normal")
+    b = inputs.rhs_normal(3000, 32).numpy()
+    T = oracle.Tree(X, zeta=40)
+    p = 4
+    s = oracle.cheb2_nodes(p)
+    for l in (1, T.L):
+        W = T.p2m(b, p, l)
+        keys, starts = T.boxes(l)
+        perm = T.perm()
+        cells = _cells(keys, 3, l)
+        edge = T.E / 2 ** l
+        csum = np.add.reduceat(b.astype(np.float64)[perm], starts[:-1])
+        assert W.sum(1) == pytest.approx(csum, abs=1e-11)       # sum_i L_i = 1
+        # first moment along dim 0: sum_i W_i s_{i_0} = sum_j t_j0 b_j  (monomial reproduction)
+        node_x = np.tile(s, p * p)                              # flat index: dim 0 fastest
+        t0 = (X[perm, 0].astype(np.float64) - (T.alpha[0] + (np.repeat(cells[:, 0], np.diff(starts)) + 0.5) * edge)) / (edge / 2)
+        m1 = np.add.reduceat(t0 * b.astype(np.float64)[perm], starts[:-1])
+        assert W @ node_x == pytest.approx(m1, abs=1e-10)
+        # and along the LAST dim (slowest index): catches a transposed node ordering
+        node_z = np.repeat(s, p * p)
+        t2 = (X[perm, 2].astype(np.float64) - (T.alpha[2] + (np.repeat(cells[:, 2], np.diff(starts)) + 0.5) * edge)) / (edge / 2)
+        m2 = np.add.reduceat(t2 * b.astype(np.float64)[perm], starts[:-1])
+        assert W @ node_z == pytest.approx(m2, abs=1e-10)
+
+
+@pytest.mark.parametrize("D,p,kernel_id,kparam", [(3, 2, 1, 0), (3, 4, 1, 0), (2, 3, 2, 2), (3, 4, 2, 3), (3, 3, 2, 1), (1, 5, 2, 4), (4, 2, 2, 1)])
+def test_far_field_is_exact_for_polynomial_kernels(D, p, kernel_id, kparam):
+    # a kernel that is a polynomial of degree <= p-1 in every coordinate of x and of y is its
+    # own interpolant, so the CPU F3M must equal brute force to rounding whatever the lists are
+    n = 1500
+    X = _cloud(n, D, 300 + D, "normal")
+    b = inputs.rhs_normal(n, 301).numpy()
+    T = oracle.Tree(X, zeta=15, max_depth=4)
+    assert sum(len(T.interactions(l, 1)[1]) for l in range(1, T.L + 1)) > 0
+    exact = oracle.direct(X, b, 1.0, kernel_id, kparam)
+    approx = T.apply(b, 1.0, p, kernel_id, kparam)
+    assert np.linalg.norm(approx - exact) <= 1e-11 * np.linalg.norm(exact)
+
+
+def test_far_field_is_not_exact_when_degree_exceeds_nodes():
+    # the counterpart of the test above: degree 3 kernel, 3 nodes -> a visible error
+    X = _cloud(1500, 3, 303, "normal")
+    b = inputs.rhs_normal(1500, 301).numpy()
+    T = oracle.Tree(X, zeta=15)
+    exact = oracle.direct(X, b, 1.0, 2, 3)
+    approx = T.apply(b, 1.0, 3, 2, 3)
+    assert np.linalg.norm(approx - exact) > 1e-6 * np.linalg.norm(exact)
+
+
+def test_factored_far_field_equals_pair_by_pair_evaluation():
+    X = _cloud(700, 3, 41, "normal")
+    b = inputs.rhs_normal(700, 42).numpy()
+    T = oracle.Tree(X, zeta=10)
+    a = T.apply(b, 0.6, 3)
+    lit = T.apply(b, 0.6, 3, literal=True)
+    assert np.linalg.norm(a - lit) <= 1e-13 * np.linalg.norm(a)
+
+
+# ----------------------------------------------------------------------------
+# whole method
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("D,dist", [(1, "uniform"), (3, "normal"), (7, "mixture")])
+def test_all_near_equals_brute_force(D, dist):
+    n = 2000
+    X = _cloud(n, D, 500 + D, dist)
+    b = inputs.rhs_normal(n, 501).numpy()
+    T = oracle.Tree(X, zeta=16, max_depth=3, force_all_near=True)
+    assert T.L >= 1
+    exact = oracle.direct(X, b, 0.9)
+    assert np.linalg.norm(T.apply(b, 0.9, 4 if D < 7 else 2) - exact) <= 1e-13 * np.linalg.norm(exact)
+
+
+def test_error_falls_with_more_nodes_config1_recipe():
+    X, b, cfg = inputs.make_config(1, n=6000)
+    X, b = X.numpy(), b.numpy()
+    exact = oracle.direct(X, b, 0.35)          # a shorter lengthscale than config 1 makes the error visible
+    T = oracle.Tree(X, zeta=64)
+    errs = [np.linalg.norm(T.apply(b, 0.35, p) - exact) / np.linalg.norm(exact) for p in (2, 3, 4, 5, 6)]
+    assert all(e1 < 0.6 * e0 for e0, e1 in zip(errs, errs[1:])), errs
+    assert errs[2] < 1e-3                      # p = 4: the order of magnitude the paper reports
+
+
+def test_f3m_operator_is_symmetric():
+    X = _cloud(2500, 3, 61, "normal")
+    b = inputs.rhs_normal(2500, 62).numpy()
+    u = inputs.rhs_normal(2500, 63).numpy()
+    T = oracle.Tree(X, zeta=20)
+    Ab, Au = T.apply(b, 0.5, 4), T.apply(u, 0.5, 4)
+    assert float(u.astype(np.float64) @ Ab) == pytest.approx(float(b.astype(np.float64) @ Au), rel=1e-11)
+
+
+def test_f3m_is_linear_in_b():
+    X = _cloud(1200, 2, 71, "uniform")
+    b1 = inputs.rhs_normal(1200, 72).numpy()
+    b2 = inputs.rhs_normal(1200, 73).numpy()
+    T = oracle.Tree(X, zeta=20)
+    # b1 + 2 b2 is formed in fp32 first so that the oracle sees exactly that vector
+    bs = (b1 + 2 * b2).astype(np.float32)
+    y = T.apply(bs, 0.3, 4)
+    resid = bs.astype(np.float64) - (b1.astype(np.float64) + 2 * b2.astype(np.float64))
+    want = T.apply(b1, 0.3, 4) + 2 * T.apply(b2, 0.3, 4)
+    # the fp32 rounding of bs is the only difference: bound it through the operator norm <= n
+    assert np.abs(y - want).max() <= 1200 * np.abs(resid).max() + 1e-10
+
+
+def test_config1_accuracy_gate():
+    X, b, cfg = inputs.make_config(1)
+    X, b = X.numpy(), b.numpy()
+    exact = oracle.direct(X, b, cfg["lengthscale"])
+    y = oracle.f3m(X, b, cfg["lengthscale"], cfg["p"], cfg["theta"])
+    assert np.linalg.norm(y - exact) / np.linalg.norm(exact) <= 1e-3
