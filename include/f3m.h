@@ -1,0 +1,172 @@
+/*
+ * f3m.h - C ABI of the MI355X (gfx950) F3M kernel matrix-vector product.
+ *
+ * The library computes y = K(X,X) b for the Gaussian kernel
+ * k(x,y) = exp(-|x-y|^2 / (2 gamma^2)) (arXiv 2202.01085, Sec. 5, first
+ * paragraph) on n points in D <= 7 dimensions, either exactly (direct_kmvm)
+ * or with the hierarchical F3M approximation (f3m_plan + f3m_kmvm) of
+ * Sec. 3 and Appendix E, Algorithm 1.
+ *
+ * Conventions shared by every entry point
+ *   - X, b, y are DEVICE pointers (fp32).  X is n x D row-major, the paper's
+ *     X in R^{n x D} (Sec. 1, "Notations").  b and y have n entries in the
+ *     caller's point order.  Introspection calls copy to HOST buffers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Work is enqueued on it; see each call for whether it synchronises.
+ *   - Every call returns an f3m_status; nothing throws or aborts across the
+ *     boundary.  f3m_last_error() gives a thread-local message for the last
+ *     failing call of the calling thread.
+ *   - The caller owns X, b, y.  A plan owns all of its device buffers and
+ *     keeps no reference to X after f3m_plan returns.
+ *   - There is no CPU fallback: without a HIP device every compute call
+ *     returns F3M_ERR_HIP.
+ */
+#ifndef F3M_H
+#define F3M_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define F3M_MAX_DIM 7
+#define F3M_MAX_LEVELS 20
+
+typedef struct f3m_plan_s f3m_plan_t; /* opaque */
+
+typedef enum {
+    F3M_OK = 0,
+    F3M_ERR_INVALID_ARG = 1, /* null pointer, n < 0, D outside [1,7], interp_nodes < 2,
+                                lengthscale or eta not finite and positive, bad level/kind */
+    F3M_ERR_NONFINITE = 2,   /* NaN or Inf among the coordinates */
+    F3M_ERR_UNSUPPORTED = 3, /* n >= 2^31, or interp_nodes^D above the node cap (4096) */
+    F3M_ERR_OOM = 4,         /* a device allocation failed */
+    F3M_ERR_HIP = 5          /* any other HIP runtime error (message in f3m_last_error) */
+} f3m_status;
+
+typedef struct {
+    int32_t leaf_max;       /* zeta of Algorithm 1: divide while the LARGEST box holds more
+                               points than this; 0 = library default (128) */
+    int32_t max_depth;      /* cap on the number of divisions; 0 = the quantisation depth */
+    int32_t force_all_near; /* test hook: classify every pair as near, so that the result
+                               must equal direct_kmvm */
+    int32_t reserved;
+} f3m_options;
+
+typedef struct {
+    int64_t n;
+    int32_t D;
+    int32_t interp_nodes;   /* p, nodes per dimension */
+    int32_t nodes_per_box;  /* r = p^D */
+    int32_t depth;          /* L: divisions actually made (near field is evaluated at depth L) */
+    int32_t quant_depth;    /* depth at which cells are quantised once (keys have D*quant_depth bits) */
+    int32_t far_threshold;  /* T = ceil(eta^2): a pair is far iff the squared integer cell offset >= T */
+    float edge;             /* E, edge of the enclosing cube */
+    float scale;            /* fp32 factor 2^quant_depth / E used for the cells */
+    float alpha[F3M_MAX_DIM];                  /* per-dimension minimum (cube anchor) */
+    int64_t nboxes[F3M_MAX_LEVELS + 1];        /* occupied boxes per depth 0..L */
+    int64_t max_box[F3M_MAX_LEVELS + 1];       /* largest box per depth */
+    int64_t near_pairs[F3M_MAX_LEVELS + 1];    /* ordered near pairs per depth */
+    int64_t far_pairs[F3M_MAX_LEVELS + 1];     /* ordered far pairs per depth */
+    int64_t device_bytes;                      /* device memory held by the plan */
+} f3m_info;
+
+typedef struct {
+    /* milliseconds of the most recent f3m_plan / f3m_kmvm on this plan */
+    float bbox_keys, sort, gather, boxes, lists, tables, plan_total;
+    float permute_in, p2p, p2m, m2l, l2p, permute_out, kmvm_total;
+} f3m_times;
+
+/*
+ * f3m_plan - everything of Algorithm 1 (Appendix E) that does not depend on b:
+ * the enclosing cube (Sec. 3 "Enclosing and partitioning the data"), the box of
+ * every point (Sec. 4.2 box-index formula), the grouping permutation (Sec. 4.1
+ * "In-place grouping data on boxes"; here one stable radix sort of 32-bit
+ * interleaved keys), the occupied-box tables per depth (Sec. 4.2 "Removing empty
+ * boxes"), the near/far interaction lists per depth (Sec. 3 "Far and near-field
+ * interactions", Sec. 4.1 "Ensuring interactions are sorted") and the
+ * node-to-node kernel tables (Sec. 3 "Interpolating k(x,y)", step 2 of Fig. 4).
+ *
+ *   X            device, n x D row-major fp32; read only during the call
+ *   n            number of points, 0 <= n < 2^31
+ *   D            1..7
+ *   lengthscale  gamma > 0
+ *   interp_nodes p >= 2 Chebyshev nodes of the second kind per dimension
+ *                (p = 4 in 3-D is the paper's r = 64)
+ *   eta          far-field distance ratio theta: boxes are far iff the distance
+ *                of their centres is >= theta * (box edge); the paper uses 2.
+ *                (NOT the paper's smooth-field limit, which is not implemented.)
+ *   stream       the call enqueues on it and synchronises it several times
+ *   plan_out     receives the plan; NULL on error.  n == 0 gives an empty plan.
+ */
+f3m_status f3m_plan(const float *X, int64_t n, int D, float lengthscale, int interp_nodes,
+                    float eta, void *stream, f3m_plan_t **plan_out);
+
+/* f3m_plan with explicit options (opt == NULL: defaults). */
+f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int interp_nodes,
+                       float eta, const f3m_options *opt, void *stream, f3m_plan_t **plan_out);
+
+/*
+ * f3m_kmvm - y ~= K(X,X) b with the plan's partition (Appendix E, Algorithm 1):
+ * per depth the far-field product L_X^T (K (L_Y b)) of Sec. 3 "Interpolating
+ * k(x,y)" (P2M, M2L, L2P), then the exact near-field sums of Sec. 3 eq. (1) at
+ * the last depth, then the inverse permutation sigma.
+ *   b, y   device fp32[n], caller's order; y is overwritten; they must not overlap.
+ *   Asynchronous on `stream`; one call in flight per plan (the plan holds the
+ *   workspace).
+ */
+f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream);
+
+/*
+ * direct_kmvm - the exact product y_i = sum_j k(x_i,x_j) b_j (Sec. 2, KeOps
+ * paragraph), O(n^2) time, O(n) memory, fp32 arithmetic.  Asynchronous on `stream`.
+ */
+f3m_status direct_kmvm(const float *X, int64_t n, int D, float lengthscale,
+                       const float *b, float *y, void *stream);
+
+/*
+ * direct_kmvm_rows_f64 - the same exact sums in fp64 for m selected rows, the
+ * reference the paper measures its relative error against (Sec. 5, first
+ * paragraph: a subset of rows against the entire data set in double precision).
+ *   rows  device int64[m], each in [0,n);  y64  device double[m].
+ */
+f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthscale,
+                                const float *b, const int64_t *rows, int64_t m,
+                                double *y64, void *stream);
+
+/* Frees the plan and its device memory (NULL is allowed). */
+void f3m_destroy(f3m_plan_t *plan);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char *f3m_last_error(void);
+
+/* ---- introspection: for parity checks and reports; all outputs are HOST buffers ---- */
+
+f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out);
+
+/* perm[k] = caller's index of the k-th point in box order (n entries): the
+ * permutation pi of Sec. 4.1; ascending (key, index). */
+f3m_status f3m_plan_get_perm(const f3m_plan_t *plan, uint32_t *perm_host);
+
+/* keys of the points at the quantisation depth, in box order (n entries) */
+f3m_status f3m_plan_get_point_keys(const f3m_plan_t *plan, uint32_t *keys_host);
+
+/* occupied boxes of a depth: keys[nboxes] ascending, starts[nboxes+1] = index
+ * intervals into the box-ordered points (Sec. 4.1 "Box-to-threadblock alignment") */
+f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_host,
+                              uint32_t *starts_host);
+
+/* interaction list of a depth as CSR by target box rank; kind 0 = near, 1 = far;
+ * row_ptr[nboxes+1], cols[pairs] ascending inside a row.  Near lists exist for
+ * every depth 0..L, far lists for 1..L. */
+f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind,
+                             uint64_t *row_ptr_host, uint32_t *cols_host);
+
+/* Stage times of the last plan build and the last f3m_kmvm (synchronises). */
+f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* F3M_H */

@@ -1,0 +1,214 @@
+// extern "C" boundary of libf3m: argument checks, error translation, introspection.
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "plan.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+f3m_status set_error(f3m_status st, const std::string &msg) {
+    g_last_error = msg;
+    return st;
+}
+
+template <class F>
+f3m_status guarded(F &&f) {
+    try {
+        f();
+        return F3M_OK;
+    } catch (const f3m::Error &e) {
+        return set_error(e.status, e.msg);
+    } catch (const std::bad_alloc &) {
+        return set_error(F3M_ERR_OOM, "host allocation failed");
+    } catch (const std::exception &e) {
+        return set_error(F3M_ERR_HIP, e.what());
+    } catch (...) {
+        return set_error(F3M_ERR_HIP, "unknown failure");
+    }
+}
+
+bool finite_pos(float v) { return std::isfinite(v) && v > 0.f; }
+
+f3m_status check_problem(const float *X, int64_t n, int D, float lengthscale) {
+    if (n < 0) return set_error(F3M_ERR_INVALID_ARG, "n must be >= 0");
+    if (D < 1 || D > F3M_MAX_DIM) return set_error(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
+    if (!finite_pos(lengthscale)) return set_error(F3M_ERR_INVALID_ARG, "lengthscale must be finite and > 0");
+    if (n > 0 && !X) return set_error(F3M_ERR_INVALID_ARG, "X is null");
+    if (n >= ((int64_t)1 << 31)) return set_error(F3M_ERR_UNSUPPORTED, "n must be below 2^31");
+    return F3M_OK;
+}
+
+template <class T>
+void copy_to_host(T *dst, const T *src, size_t count) {
+    if (count == 0) return;
+    F3M_HIP(hipMemcpy(dst, src, count * sizeof(T), hipMemcpyDeviceToHost));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *f3m_last_error(void) { return g_last_error.c_str(); }
+
+f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int interp_nodes, float eta,
+                       const f3m_options *opt, void *stream, f3m_plan_t **plan_out) {
+    if (!plan_out) return set_error(F3M_ERR_INVALID_ARG, "plan_out is null");
+    *plan_out = nullptr;
+    f3m_status st = check_problem(X, n, D, lengthscale);
+    if (st != F3M_OK) return st;
+    if (interp_nodes < 2) return set_error(F3M_ERR_INVALID_ARG, "interp_nodes must be >= 2");
+    if (!finite_pos(eta)) return set_error(F3M_ERR_INVALID_ARG, "eta (far-field distance ratio) must be finite and > 0");
+    if (opt && (opt->leaf_max < 0 || opt->max_depth < 0))
+        return set_error(F3M_ERR_INVALID_ARG, "negative option value");
+    if (interp_nodes > 8) return set_error(F3M_ERR_UNSUPPORTED, "interp_nodes above 8 is not supported");
+    double r = std::pow((double)interp_nodes, (double)D);
+    if (r > (double)f3m::MAX_NODES) return set_error(F3M_ERR_UNSUPPORTED, "interp_nodes^D exceeds the node cap of 4096");
+    if ((double)eta > 1.0e4) return set_error(F3M_ERR_INVALID_ARG, "eta is unreasonably large");
+
+    f3m_plan_s *P = nullptr;
+    st = guarded([&] {
+        P = new f3m_plan_s();
+        P->n = n;
+        P->D = D;
+        P->p = interp_nodes;
+        P->r = (int)std::lround(r);
+        P->gamma = lengthscale;
+        P->theta = eta;
+        P->T = (int)std::ceil((double)eta * (double)eta);
+        P->Lq = f3m::quant_depth(D);
+        P->leaf_max = (opt && opt->leaf_max > 0) ? opt->leaf_max : 128;
+        P->max_depth = opt ? opt->max_depth : 0;
+        P->force_all_near = opt ? (opt->force_all_near != 0) : 0;
+        F3M_HIP(hipGetDevice(&P->device));
+        if (n > 0) f3m::build_plan(*P, X, (hipStream_t)stream);
+    });
+    if (st != F3M_OK) {
+        delete P;
+        (void)hipGetLastError();
+        return st;
+    }
+    *plan_out = P;
+    return F3M_OK;
+}
+
+f3m_status f3m_plan(const float *X, int64_t n, int D, float lengthscale, int interp_nodes, float eta, void *stream,
+                    f3m_plan_t **plan_out) {
+    return f3m_plan_ex(X, n, D, lengthscale, interp_nodes, eta, nullptr, stream, plan_out);
+}
+
+f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream) {
+    if (!plan) return set_error(F3M_ERR_INVALID_ARG, "plan is null");
+    if (plan->n == 0) return F3M_OK;
+    if (!b || !y) return set_error(F3M_ERR_INVALID_ARG, "b or y is null");
+    if (b == y) return set_error(F3M_ERR_INVALID_ARG, "b and y must not overlap");
+    return guarded([&] { f3m::run_kmvm(*plan, b, y, (hipStream_t)stream); });
+}
+
+f3m_status direct_kmvm(const float *X, int64_t n, int D, float lengthscale, const float *b, float *y, void *stream) {
+    f3m_status st = check_problem(X, n, D, lengthscale);
+    if (st != F3M_OK) return st;
+    if (n == 0) return F3M_OK;
+    if (!b || !y) return set_error(F3M_ERR_INVALID_ARG, "b or y is null");
+    if (b == y) return set_error(F3M_ERR_INVALID_ARG, "b and y must not overlap");
+    return guarded([&] { f3m::run_direct(X, n, D, lengthscale, b, y, (hipStream_t)stream); });
+}
+
+f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthscale, const float *b,
+                                const int64_t *rows, int64_t m, double *y64, void *stream) {
+    f3m_status st = check_problem(X, n, D, lengthscale);
+    if (st != F3M_OK) return st;
+    if (m < 0) return set_error(F3M_ERR_INVALID_ARG, "m must be >= 0");
+    if (m == 0) return F3M_OK;
+    if (n == 0) return set_error(F3M_ERR_INVALID_ARG, "rows requested of an empty problem");
+    if (!b || !rows || !y64) return set_error(F3M_ERR_INVALID_ARG, "b, rows or y64 is null");
+    return guarded([&] { f3m::run_direct_rows_f64(X, n, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
+}
+
+void f3m_destroy(f3m_plan_t *plan) {
+    if (!plan) return;
+    (void)hipDeviceSynchronize();
+    delete plan;
+}
+
+f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
+    if (!plan || !out) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    std::memset(out, 0, sizeof(*out));
+    out->n = plan->n;
+    out->D = plan->D;
+    out->interp_nodes = plan->p;
+    out->nodes_per_box = plan->r;
+    out->depth = plan->L;
+    out->quant_depth = plan->Lq;
+    out->far_threshold = plan->T;
+    out->edge = plan->E;
+    out->scale = plan->scale;
+    for (int d = 0; d < F3M_MAX_DIM; ++d) out->alpha[d] = plan->alpha[d];
+    for (int l = 0; l <= plan->L && plan->n > 0; ++l) {
+        out->nboxes[l] = plan->lev[l].nb;
+        out->max_box[l] = plan->lev[l].max_box;
+        out->near_pairs[l] = plan->lev[l].near_sz;
+        out->far_pairs[l] = plan->lev[l].far_sz;
+    }
+    out->device_bytes = plan->bytes;
+    return F3M_OK;
+}
+
+f3m_status f3m_plan_get_perm(const f3m_plan_t *plan, uint32_t *perm_host) {
+    if (!plan || !perm_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    return guarded([&] { copy_to_host(perm_host, plan->perm.p, (size_t)plan->n); });
+}
+
+f3m_status f3m_plan_get_point_keys(const f3m_plan_t *plan, uint32_t *keys_host) {
+    if (!plan || !keys_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    return guarded([&] { copy_to_host(keys_host, plan->keys.p, (size_t)plan->n); });
+}
+
+f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_host, uint32_t *starts_host) {
+    if (!plan || !keys_host || !starts_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    return guarded([&] {
+        const f3m_level &lv = plan->lev[level];
+        copy_to_host(keys_host, lv.key.p, (size_t)lv.nb);
+        copy_to_host(starts_host, lv.start.p, (size_t)lv.nb + 1);
+    });
+}
+
+f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind, uint64_t *row_ptr_host, uint32_t *cols_host) {
+    if (!plan || !row_ptr_host || !cols_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    if (kind != 0 && kind != 1) return set_error(F3M_ERR_INVALID_ARG, "kind must be 0 (near) or 1 (far)");
+    return guarded([&] {
+        const f3m_level &lv = plan->lev[level];
+        copy_to_host(row_ptr_host, kind ? lv.far_ptr.p : lv.near_ptr.p, (size_t)lv.nb + 1);
+        copy_to_host(cols_host, kind ? lv.far_col.p : lv.near_col.p, (size_t)(kind ? lv.far_sz : lv.near_sz));
+    });
+}
+
+f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out) {
+    if (!plan || !out) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    return guarded([&] {
+        f3m_times t = plan->times;
+        if (plan->have_kmvm_times) {
+            F3M_HIP(hipEventSynchronize(plan->ev[12]));
+            F3M_HIP(hipEventElapsedTime(&t.permute_in, plan->ev[8], plan->ev[9]));
+            F3M_HIP(hipEventElapsedTime(&t.p2p, plan->ev[9], plan->ev[10]));
+            F3M_HIP(hipEventElapsedTime(&t.permute_out, plan->ev[11], plan->ev[12]));
+            F3M_HIP(hipEventElapsedTime(&t.kmvm_total, plan->ev[8], plan->ev[12]));
+            t.p2m = t.m2l = t.l2p = 0.f;
+            for (int l = 1; l <= plan->L; ++l) {
+                if (plan->lev[l].far_sz == 0 || plan->far_events.size() < (size_t)(l + 1) * 4) continue;
+                hipEvent_t *ev = &plan->far_events[(size_t)l * 4];
+                float ms = 0.f;
+                F3M_HIP(hipEventElapsedTime(&ms, ev[0], ev[1])); t.p2m += ms;
+                F3M_HIP(hipEventElapsedTime(&ms, ev[1], ev[2])); t.m2l += ms;
+                F3M_HIP(hipEventElapsedTime(&ms, ev[2], ev[3])); t.l2p += ms;
+            }
+        }
+        *out = t;
+    });
+}
+
+}  // extern "C"

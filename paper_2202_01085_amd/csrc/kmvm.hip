@@ -1,0 +1,541 @@
+// f3m_kmvm and direct_kmvm: the floating-point passes.
+// (arXiv 2202.01085: Sec. 3 eq. (1) near field; Sec. 3 "Interpolating k(x,y)" and Fig. 4
+//  for the three far-field passes v1 = L_Y b, v2 = K v1, v = L_X^T v2; Appendix E
+//  Algorithm 1 for the order of the passes.)
+#include <algorithm>
+#include <cmath>
+
+#include "plan.h"
+
+namespace f3m {
+
+constexpr int P_MAX = 8;  // interpolation nodes per dimension supported by the kernels
+
+// Chebyshev nodes of the second kind s_i = cos(i pi/(p-1)) and the reciprocal denominators
+// of the product-form Lagrange basis (Sec. 3 "Lagrange interpolation").
+struct NodeArg {
+    float s[P_MAX];
+    float invden[P_MAX];
+};
+struct CentreArg {
+    double alpha[F3M_MAX_DIM];
+    double edge;      // l = E / 2^level
+    double inv_half;  // 2 / l
+};
+
+static NodeArg make_nodes(int p) {
+    NodeArg a{};
+    double s[P_MAX];
+    for (int i = 0; i < p; ++i) s[i] = std::cos((double)i * M_PI / (double)(p - 1));
+    for (int i = 0; i < p; ++i) {
+        double den = 1.0;
+        for (int j = 0; j < p; ++j)
+            if (j != i) den *= s[i] - s[j];
+        a.s[i] = (float)s[i];
+        a.invden[i] = (float)(1.0 / den);
+    }
+    return a;
+}
+
+static CentreArg make_centre(const f3m_plan_s &P, int level) {
+    CentreArg c{};
+    for (int d = 0; d < P.D; ++d) c.alpha[d] = (double)P.alpha[d];
+    c.edge = (double)P.E / std::ldexp(1.0, level);
+    c.inv_half = 2.0 / c.edge;
+    return c;
+}
+
+// ------------------------------------------------------------------------------------
+// permutation in and out (the reindexing vector sigma of Sec. 4.2)
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_kernel(const float *__restrict__ b, const uint32_t *__restrict__ perm,
+                                                     int64_t n, float *__restrict__ bs) {
+    int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) bs[k] = b[perm[k]];
+}
+__global__ __launch_bounds__(256) void scatter_kernel(const float *__restrict__ ys, const uint32_t *__restrict__ perm,
+                                                      int64_t n, float *__restrict__ y) {
+    int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) y[perm[k]] = ys[k];
+}
+
+// ------------------------------------------------------------------------------------
+// near field (Sec. 3 eq. (1)): one wavefront per run of <= 64 targets of a leaf box, one
+// lane per target; the sources of the near boxes are wave-uniform, so they arrive through
+// the scalar data path and every vector instruction works on 64 distinct pairs.
+//   k(x,y) = exp2( nc2 * |x-y|^2 ),  nc2 = -log2(e) / (2 gamma^2)
+// ------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                 const uint32_t *__restrict__ start,
+                                                 const uint64_t *__restrict__ near_ptr,
+                                                 const uint32_t *__restrict__ near_col,
+                                                 const uint32_t *__restrict__ tile_box,
+                                                 const uint32_t *__restrict__ tile_first, float nc2,
+                                                 float *__restrict__ ys) {
+    const int64_t t = blockIdx.x;
+    const uint32_t a = tile_box[t];
+    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    const uint32_t kend = start[a + 1];
+    const uint32_t k = k0 + threadIdx.x;
+    const bool active = k < kend;
+    float xi[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) xi[d] = active ? Xs[(int64_t)k * D + d] : 0.f;
+    float acc = 0.f;
+    const uint64_t e1 = near_ptr[a + 1];
+    for (uint64_t e = near_ptr[a]; e < e1; ++e) {
+        const uint32_t q = near_col[e];
+        const uint32_t j1 = start[q + 1];
+#pragma unroll 4
+        for (uint32_t j = start[q]; j < j1; ++j) {
+            float r2 = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                float diff = Xs[(int64_t)j * D + d] - xi[d];
+                r2 = fmaf(diff, diff, r2);
+            }
+            acc = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), bs[j], acc);
+        }
+    }
+    if (active) ys[k] = acc;
+}
+
+// exact product, all pairs (Sec. 2, KeOps paragraph): lane = target, sources wave-uniform
+template <int D>
+__global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X, const float *__restrict__ b,
+                                                    int64_t n, float nc2, float *__restrict__ y) {
+    const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    const bool active = i < n;
+    float xi[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) xi[d] = active ? X[i * D + d] : 0.f;
+    float acc = 0.f;
+#pragma unroll 4
+    for (int64_t j = 0; j < n; ++j) {
+        float r2 = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            float diff = X[j * D + d] - xi[d];
+            r2 = fmaf(diff, diff, r2);
+        }
+        acc = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), b[j], acc);
+    }
+    if (active) y[i] = acc;
+}
+
+// exact rows in fp64: lane = row, blockIdx.y = slice of the sources; partial sums per slice
+template <int D>
+__global__ __launch_bounds__(64) void rows_f64_kernel(const float *__restrict__ X, const float *__restrict__ b,
+                                                      int64_t n, const int64_t *__restrict__ rows, int64_t m,
+                                                      double nc, double *__restrict__ part) {
+    const int64_t a = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    const bool active = a < m;
+    double xi[D];
+    const int64_t i = active ? rows[a] : 0;
+#pragma unroll
+    for (int d = 0; d < D; ++d) xi[d] = (double)X[i * D + d];
+    const int64_t per = (n + gridDim.y - 1) / gridDim.y;
+    const int64_t j0 = (int64_t)blockIdx.y * per, j1 = min(n, j0 + per);
+    double acc = 0.0;
+    for (int64_t j = j0; j < j1; ++j) {
+        double r2 = 0.0;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            double diff = (double)X[j * D + d] - xi[d];
+            r2 = fma(diff, diff, r2);
+        }
+        acc = fma(exp(r2 * nc), (double)b[j], acc);
+    }
+    if (active) part[(int64_t)blockIdx.y * m + a] = acc;
+}
+__global__ __launch_bounds__(256) void rows_f64_sum_kernel(const double *__restrict__ part, int64_t m, int slices,
+                                                           double *__restrict__ y64) {
+    int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (a >= m) return;
+    double s = 0.0;
+    for (int k = 0; k < slices; ++k) s += part[(int64_t)k * m + a];
+    y64[a] = s;
+}
+
+// ------------------------------------------------------------------------------------
+// tensor-product Lagrange weights of one point of a box: for each dimension the local
+// coordinate t = (x - centre) / (l/2) is formed in fp64 (centre = alpha + (c + 1/2) l), the
+// p basis values in fp32 by the product form.  out[d*p + i] = L_i(t_d).
+// ------------------------------------------------------------------------------------
+template <int D>
+__device__ inline void point_weights(const float *__restrict__ x, const int32_t *__restrict__ cell,
+                                     const CentreArg &C, const NodeArg &N, int p, float *out) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        double centre = C.alpha[d] + ((double)cell[d] + 0.5) * C.edge;
+        float t = (float)(((double)x[d] - centre) * C.inv_half);
+        for (int i = 0; i < p; ++i) {
+            float num = 1.f;
+            for (int j = 0; j < p; ++j)
+                if (j != i) num *= t - N.s[j];
+            out[d * p + i] = num * N.invden[i];
+        }
+    }
+}
+
+// node index -> packed digits (4 bits per dimension)
+template <int D>
+__device__ inline uint32_t node_code(int i, int p) {
+    uint32_t code = 0;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        code |= (uint32_t)(i % p) << (4 * d);
+        i /= p;
+    }
+    return code;
+}
+
+// ------------------------------------------------------------------------------------
+// P2M, v1 = L_Y b (Fig. 4 step 1): W_q[i] = sum_{j in q} L_i(t_j) b_j.
+// One block per chunk (a run of <= P2M_CHUNK points of one box), one thread per node (or
+// several nodes per thread when r > NT); points are staged 64 at a time through LDS as
+// their 1-D basis values.  No atomics: a box with several chunks gets partial sums that
+// p2m_reduce_kernel adds in a fixed order.
+// ------------------------------------------------------------------------------------
+constexpr int FF_TP = 64;  // points staged per step
+
+template <int D, int NT>
+__global__ __launch_bounds__(NT) void p2m_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                 const uint32_t *__restrict__ start, const int32_t *__restrict__ cell,
+                                                 const uint32_t *__restrict__ chunk_box,
+                                                 const uint32_t *__restrict__ chunk_first, int p, int r, CentreArg C,
+                                                 NodeArg N, float *__restrict__ W, float *__restrict__ Wpart) {
+    constexpr int NPT_MAX = NT == 64 ? 1 : MAX_NODES / 256;
+    extern __shared__ float lds[];
+    const int DP = D * p;
+    float *wts = lds;                 // [FF_TP][DP]
+    float *bj = lds + FF_TP * DP;     // [FF_TP]
+    const int64_t c = blockIdx.x;
+    const uint32_t a = chunk_box[c];
+    const uint32_t ci = (uint32_t)(c - chunk_first[a]);
+    const uint32_t nch = chunk_first[a + 1] - chunk_first[a];
+    const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
+    const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
+    const int npt = (r + NT - 1) / NT;
+    uint32_t code[NPT_MAX];
+    float acc[NPT_MAX];
+#pragma unroll
+    for (int m = 0; m < NPT_MAX; ++m) {
+        int i = threadIdx.x + m * NT;
+        code[m] = node_code<D>(i < r ? i : 0, p);
+        acc[m] = 0.f;
+    }
+    for (uint32_t kb = k0; kb < k1; kb += FF_TP) {
+        const int cnt = (int)min((uint32_t)FF_TP, k1 - kb);
+        __syncthreads();
+        if ((int)threadIdx.x < cnt) {
+            const int64_t k = (int64_t)kb + threadIdx.x;
+            point_weights<D>(Xs + k * D, cell + (int64_t)a * D, C, N, p, wts + threadIdx.x * DP);
+            bj[threadIdx.x] = bs[k];
+        }
+        __syncthreads();
+        for (int jj = 0; jj < cnt; ++jj) {
+            const float *wj = wts + jj * DP;
+            const float bv = bj[jj];
+#pragma unroll
+            for (int m = 0; m < NPT_MAX; ++m) {
+                if (m < npt) {
+                    float prod = bv;
+#pragma unroll
+                    for (int d = 0; d < D; ++d) prod *= wj[d * p + ((code[m] >> (4 * d)) & 15u)];
+                    acc[m] += prod;
+                }
+            }
+        }
+    }
+    float *dst = nch == 1 ? W + (int64_t)a * r : Wpart + c * r;
+#pragma unroll
+    for (int m = 0; m < NPT_MAX; ++m) {
+        int i = threadIdx.x + m * NT;
+        if (m < npt && i < r) dst[i] = acc[m];
+    }
+}
+
+// boxes that were split into several chunks: add the partial node weights, chunk by
+// chunk in ascending order, in fp64
+__global__ __launch_bounds__(256) void p2m_reduce_kernel(const uint32_t *__restrict__ chunk_first, int r,
+                                                         const float *__restrict__ Wpart, float *__restrict__ W) {
+    const uint32_t a = blockIdx.x;
+    const uint32_t c0 = chunk_first[a], c1 = chunk_first[a + 1];
+    if (c1 - c0 <= 1) return;
+    __shared__ double part[4][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    for (int i0 = 0; i0 < r; i0 += 64) {
+        const int i = i0 + lane;
+        double s = 0.0;
+        if (i < r)
+            for (uint32_t c = c0 + g; c < c1; c += 4) s += (double)Wpart[(int64_t)c * r + i];
+        __syncthreads();
+        part[g][lane] = s;
+        __syncthreads();
+        if (g == 0 && i < r) W[(int64_t)a * r + i] = (float)(((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane]);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// L2P, v = L_X^T v2 (Fig. 4 step 3): y_a += sum_i L_i(t_a) V_p[i] for the points a of box p.
+// One block per chunk, one thread per point; V_p and the 1-D basis values sit in LDS.
+// ------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(P2M_CHUNK) void l2p_kernel(const float *__restrict__ Xs,
+                                                        const uint32_t *__restrict__ start,
+                                                        const int32_t *__restrict__ cell,
+                                                        const uint64_t *__restrict__ far_ptr,
+                                                        const uint32_t *__restrict__ chunk_box,
+                                                        const uint32_t *__restrict__ chunk_first, int p, int r,
+                                                        CentreArg C, NodeArg N, const float *__restrict__ V,
+                                                        float *__restrict__ ys) {
+    extern __shared__ float lds[];
+    const int DP = D * p, stride = DP + 1;
+    float *Vs = lds;          // [r]
+    float *wts = lds + r;     // [P2M_CHUNK][stride]
+    const int64_t c = blockIdx.x;
+    const uint32_t a = chunk_box[c];
+    if (far_ptr[a + 1] == far_ptr[a]) return;  // no far partner at this depth: V_p is zero
+    const uint32_t ci = (uint32_t)(c - chunk_first[a]);
+    const uint32_t k = start[a] + ci * (uint32_t)P2M_CHUNK + threadIdx.x;
+    const bool active = k < start[a + 1];
+    for (int i = threadIdx.x; i < r; i += P2M_CHUNK) Vs[i] = V[(int64_t)a * r + i];
+    float *w = wts + threadIdx.x * stride;
+    if (active) point_weights<D>(Xs + (int64_t)k * D, cell + (int64_t)a * D, C, N, p, w);
+    __syncthreads();
+    if (!active) return;
+    int dig[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) dig[d] = 0;
+    float acc = 0.f;
+    for (int i = 0; i < r; ++i) {
+        float prod = Vs[i];
+#pragma unroll
+        for (int d = 0; d < D; ++d) prod *= w[d * p + dig[d]];
+        acc += prod;
+        // next multi-index, dimension 0 fastest
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (++dig[d] < p) break;
+            dig[d] = 0;
+        }
+    }
+    ys[k] += acc;
+}
+
+// ------------------------------------------------------------------------------------
+// M2L, v2 = K v1 (Fig. 4 step 2), general form: V_p[i] = sum_{q in far(p)} sum_j
+// k(s^p_i, s^q_j) W_q[j] with the kernel evaluated on the fly.  In units of half a box
+// edge the node distance along d is 2 o_d + s_{j_d} - s_{i_d}, o = integer cell offset.
+// One block per target box, thread(s) per target node.
+// ------------------------------------------------------------------------------------
+template <int D, int NT>
+__global__ __launch_bounds__(NT) void m2l_generic_kernel(const int32_t *__restrict__ cell,
+                                                         const uint64_t *__restrict__ far_ptr,
+                                                         const uint32_t *__restrict__ far_col, int p, int r,
+                                                         NodeArg N, float nc2h, const float *__restrict__ W,
+                                                         float *__restrict__ V) {
+    constexpr int NPT_MAX = NT == 64 ? 1 : MAX_NODES / 256;
+    extern __shared__ float lds[];
+    float *Wq = lds;        // [r]
+    float *u = lds + r;     // [D][p]   2 o_d + s_k
+    const uint32_t a = blockIdx.x;
+    const uint64_t e0 = far_ptr[a], e1 = far_ptr[a + 1];
+    if (e0 == e1) return;
+    const int npt = (r + NT - 1) / NT;
+    float si[NPT_MAX][D];
+    float acc[NPT_MAX];
+#pragma unroll
+    for (int m = 0; m < NPT_MAX; ++m) {
+        int i = threadIdx.x + m * NT;
+        uint32_t code = node_code<D>(i < r ? i : 0, p);
+#pragma unroll
+        for (int d = 0; d < D; ++d) si[m][d] = N.s[(code >> (4 * d)) & 15u];
+        acc[m] = 0.f;
+    }
+    for (uint64_t e = e0; e < e1; ++e) {
+        const uint32_t q = far_col[e];
+        __syncthreads();
+        for (int j = threadIdx.x; j < r; j += NT) Wq[j] = W[(int64_t)q * r + j];
+        if ((int)threadIdx.x < D * p) {
+            int d = threadIdx.x / p, kk = threadIdx.x % p;
+            int o = cell[(int64_t)q * D + d] - cell[(int64_t)a * D + d];
+            u[d * p + kk] = 2.f * (float)o + N.s[kk];
+        }
+        __syncthreads();
+        int dig[D];
+#pragma unroll
+        for (int d = 0; d < D; ++d) dig[d] = 0;
+        for (int j = 0; j < r; ++j) {
+            float uj[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) uj[d] = u[d * p + dig[d]];
+            const float wj = Wq[j];
+#pragma unroll
+            for (int m = 0; m < NPT_MAX; ++m) {
+                if (m < npt) {
+                    float r2 = 0.f;
+#pragma unroll
+                    for (int d = 0; d < D; ++d) {
+                        float diff = uj[d] - si[m][d];
+                        r2 = fmaf(diff, diff, r2);
+                    }
+                    acc[m] = fmaf(__builtin_amdgcn_exp2f(r2 * nc2h), wj, acc[m]);
+                }
+            }
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (++dig[d] < p) break;
+                dig[d] = 0;
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < NPT_MAX; ++m) {
+        int i = threadIdx.x + m * NT;
+        if (m < npt && i < r) V[(int64_t)a * r + i] = acc[m];
+    }
+}
+
+void build_far_tables(f3m_plan_s &, hipStream_t) {}
+
+// ------------------------------------------------------------------------------------
+template <int D>
+static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
+    const int64_t n = P.n;
+    const int r = P.r, p = P.p;
+    const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma));
+    const NodeArg N = make_nodes(p);
+    const int nev = 4 + 3 * (P.L + 1);
+    if (!P.ev[8]) {
+        // events of the kmvm stages live in ev[8..15] plus a per-depth set created lazily
+        for (int k = 8; k < 12; ++k) F3M_HIP(hipEventCreate(&P.ev[k]));
+    }
+    (void)nev;
+    const unsigned gn = (unsigned)cdiv(n, 256);
+    f3m_level &leaf = P.lev[P.L];
+
+    F3M_HIP(hipEventRecord(P.ev[8], st));
+    gather_kernel<<<dim3(gn), dim3(256), 0, st>>>(b, P.perm.p, n, P.bs.p);
+    F3M_HIP(hipEventRecord(P.ev[9], st));
+    p2p_kernel<D><<<dim3((unsigned)P.ntiles), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
+                                                                leaf.near_col.p, P.tile_box.p, P.tile_first.p, nc2,
+                                                                P.ys.p);
+    F3M_HIP(hipGetLastError());
+    F3M_HIP(hipEventRecord(P.ev[10], st));
+    P.far_events.resize((size_t)(P.L + 1) * 4, nullptr);
+    for (int l = 1; l <= P.L; ++l) {
+        f3m_level &lv = P.lev[l];
+        if (lv.far_sz == 0) continue;
+        hipEvent_t *ev = &P.far_events[(size_t)l * 4];
+        for (int k = 0; k < 4; ++k)
+            if (!ev[k]) F3M_HIP(hipEventCreate(&ev[k]));
+        const CentreArg C = make_centre(P, l);
+        const double half = 0.5 * C.edge;
+        const float nc2h = (float)(-1.4426950408889634 * half * half / (2.0 * (double)P.gamma * (double)P.gamma));
+        F3M_HIP(hipEventRecord(ev[0], st));
+        {
+            size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
+            if (r <= 64)
+                p2m_kernel<D, 64><<<dim3((unsigned)lv.nchunks), dim3(64), sh, st>>>(
+                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, p, r, C, N, P.W.p, P.Wpart.p);
+            else
+                p2m_kernel<D, 256><<<dim3((unsigned)lv.nchunks), dim3(256), sh, st>>>(
+                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, p, r, C, N, P.W.p, P.Wpart.p);
+            F3M_HIP(hipGetLastError());
+            if (lv.nchunks > lv.nb)
+                p2m_reduce_kernel<<<dim3((unsigned)lv.nb), dim3(256), 0, st>>>(lv.chunk_first.p, r, P.Wpart.p, P.W.p);
+            F3M_HIP(hipGetLastError());
+        }
+        F3M_HIP(hipEventRecord(ev[1], st));
+        {
+            size_t sh = (size_t)(r + D * p) * sizeof(float);
+            if (r <= 64)
+                m2l_generic_kernel<D, 64><<<dim3((unsigned)lv.nb), dim3(64), sh, st>>>(
+                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, p, r, N, nc2h, P.W.p, P.V.p);
+            else
+                m2l_generic_kernel<D, 256><<<dim3((unsigned)lv.nb), dim3(256), sh, st>>>(
+                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, p, r, N, nc2h, P.W.p, P.V.p);
+            F3M_HIP(hipGetLastError());
+        }
+        F3M_HIP(hipEventRecord(ev[2], st));
+        {
+            size_t sh = (size_t)(r + P2M_CHUNK * (D * p + 1)) * sizeof(float);
+            l2p_kernel<D><<<dim3((unsigned)lv.nchunks), dim3(P2M_CHUNK), sh, st>>>(
+                P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p, lv.chunk_box.p, lv.chunk_first.p, p, r, C, N, P.V.p, P.ys.p);
+            F3M_HIP(hipGetLastError());
+        }
+        F3M_HIP(hipEventRecord(ev[3], st));
+    }
+    F3M_HIP(hipEventRecord(P.ev[11], st));
+    scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.perm.p, n, y);
+    F3M_HIP(hipGetLastError());
+    if (!P.ev[12]) F3M_HIP(hipEventCreate(&P.ev[12]));
+    F3M_HIP(hipEventRecord(P.ev[12], st));
+    P.have_kmvm_times = true;
+}
+
+void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
+    switch (P.D) {
+        case 1: run_kmvm_d<1>(P, b, y, st); break;
+        case 2: run_kmvm_d<2>(P, b, y, st); break;
+        case 3: run_kmvm_d<3>(P, b, y, st); break;
+        case 4: run_kmvm_d<4>(P, b, y, st); break;
+        case 5: run_kmvm_d<5>(P, b, y, st); break;
+        case 6: run_kmvm_d<6>(P, b, y, st); break;
+        case 7: run_kmvm_d<7>(P, b, y, st); break;
+        default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
+    }
+}
+
+template <int D>
+static void run_direct_d(const float *X, int64_t n, float gamma, const float *b, float *y, hipStream_t st) {
+    const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)gamma * (double)gamma));
+    direct_kernel<D><<<dim3((unsigned)cdiv(n, 64)), dim3(64), 0, st>>>(X, b, n, nc2, y);
+    F3M_HIP(hipGetLastError());
+}
+
+void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st) {
+    switch (D) {
+        case 1: run_direct_d<1>(X, n, gamma, b, y, st); break;
+        case 2: run_direct_d<2>(X, n, gamma, b, y, st); break;
+        case 3: run_direct_d<3>(X, n, gamma, b, y, st); break;
+        case 4: run_direct_d<4>(X, n, gamma, b, y, st); break;
+        case 5: run_direct_d<5>(X, n, gamma, b, y, st); break;
+        case 6: run_direct_d<6>(X, n, gamma, b, y, st); break;
+        case 7: run_direct_d<7>(X, n, gamma, b, y, st); break;
+        default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
+    }
+}
+
+template <int D>
+static void run_rows_d(const float *X, int64_t n, float gamma, const float *b, const int64_t *rows, int64_t m,
+                       double *y64, hipStream_t st) {
+    const double nc = -1.0 / (2.0 * (double)gamma * (double)gamma);
+    const int slices = (int)std::max<int64_t>(1, std::min<int64_t>(256, n / 4096));
+    DevBuf<double> part;
+    part.alloc((size_t)slices * (size_t)m);
+    rows_f64_kernel<D><<<dim3((unsigned)cdiv(m, 64), (unsigned)slices), dim3(64), 0, st>>>(X, b, n, rows, m, nc, part.p);
+    F3M_HIP(hipGetLastError());
+    rows_f64_sum_kernel<<<dim3((unsigned)cdiv(m, 256)), dim3(256), 0, st>>>(part.p, m, slices, y64);
+    F3M_HIP(hipGetLastError());
+    F3M_HIP(hipStreamSynchronize(st));  // `part` is released on return
+}
+
+void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
+                         int64_t m, double *y64, hipStream_t st) {
+    switch (D) {
+        case 1: run_rows_d<1>(X, n, gamma, b, rows, m, y64, st); break;
+        case 2: run_rows_d<2>(X, n, gamma, b, rows, m, y64, st); break;
+        case 3: run_rows_d<3>(X, n, gamma, b, rows, m, y64, st); break;
+        case 4: run_rows_d<4>(X, n, gamma, b, rows, m, y64, st); break;
+        case 5: run_rows_d<5>(X, n, gamma, b, rows, m, y64, st); break;
+        case 6: run_rows_d<6>(X, n, gamma, b, rows, m, y64, st); break;
+        case 7: run_rows_d<7>(X, n, gamma, b, rows, m, y64, st); break;
+        default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
+    }
+}
+
+}  // namespace f3m

@@ -1,0 +1,72 @@
+// The plan object: everything of Algorithm 1 that does not depend on b.
+#pragma once
+#include "common.h"
+
+struct f3m_level {
+    int64_t nb = 0;                     // occupied boxes
+    int64_t max_box = 0;
+    f3m::DevBuf<uint32_t> key;          // [nb]   box key at this depth, ascending
+    f3m::DevBuf<uint32_t> start;        // [nb+1] index interval into the box-ordered points
+    f3m::DevBuf<uint32_t> parent;       // [nb]   rank of the parent one depth up
+    f3m::DevBuf<uint32_t> cstart;       // [nb+1] rank interval of the children one depth down
+    f3m::DevBuf<int32_t> cell;          // [nb*D] integer cell coordinates
+    f3m::DevBuf<uint64_t> near_ptr, far_ptr;   // [nb+1]
+    f3m::DevBuf<uint32_t> near_col, far_col;
+    int64_t near_sz = 0, far_sz = 0;
+    // P2M work split: a chunk is a run of at most P2M_CHUNK points of one box
+    int64_t nchunks = 0;
+    f3m::DevBuf<uint32_t> chunk_box;    // [nchunks]
+    f3m::DevBuf<uint32_t> chunk_first;  // [nb+1] first chunk of each box
+    // node-to-node kernel tables of this depth (D <= 3 fast path), see m2l
+    f3m::DevBuf<float> ktab;
+    f3m::DevBuf<uint32_t> fslot;        // positional far table of the MFMA path
+    int64_t ntiles = 0;
+    f3m::DevBuf<uint32_t> tile_box;     // [ntiles*32] target rank per tile lane (0xffffffff = padding)
+};
+
+struct f3m_plan_s {
+    int64_t n = 0;
+    int D = 0, p = 0, r = 0;
+    int Lq = 0, L = 0, T = 4;
+    float gamma = 1.f, theta = 2.f;
+    float E = 0.f, scale = 0.f;
+    float alpha[F3M_MAX_DIM] = {0};
+    int leaf_max = 128, max_depth = 0, force_all_near = 0;
+    int device = 0;
+    int64_t bytes = 0;
+
+    f3m::DevBuf<uint32_t> keys;   // [n] keys at depth Lq, box order
+    f3m::DevBuf<uint32_t> perm;   // [n]
+    f3m::DevBuf<float> Xs;        // [n*D] coordinates in box order, row-major
+    f3m::DevBuf<float> bs, ys;    // [n] right-hand side / result in box order
+    f3m::DevBuf<float> W, V;      // [max_l nb_l * r] node weights / node potentials of one depth
+    f3m::DevBuf<float> Wpart;     // [max_l nchunks_l * r] partial node weights
+    // near-field work split: a tile is a run of at most 64 targets of one leaf box
+    int64_t ntiles = 0;
+    f3m::DevBuf<uint32_t> tile_box, tile_first;   // [ntiles], [nb_L+1]
+    f3m_level lev[F3M_MAX_LEVELS + 1];
+
+    hipEvent_t ev[16] = {nullptr};
+    std::vector<hipEvent_t> far_events;   // 4 per depth: before P2M, M2L, L2P, after L2P
+    bool have_plan_times = false, have_kmvm_times = false;
+    f3m_times times = {};
+    ~f3m_plan_s();
+};
+
+namespace f3m {
+
+constexpr int P2M_CHUNK = 256;
+constexpr int MAX_NODES = 4096;
+
+int quant_depth(int D);
+
+// plan.hip
+void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);
+// kmvm.hip
+void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
+void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st);
+void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
+                         int64_t m, double *y64, hipStream_t st);
+void build_far_tables(f3m_plan_s &P, hipStream_t st);
+
+}  // namespace f3m

@@ -1,0 +1,592 @@
+// f3m_plan: enclosing cube, keys, radix sort, box tables, interaction lists.
+// (arXiv 2202.01085: Sec. 3 "Enclosing and partitioning the data", Sec. 4.1, Sec. 4.2,
+//  Appendix E Algorithm 1 "Divide", "Calculate interactions left", "Partition".)
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "plan.h"
+
+f3m_plan_s::~f3m_plan_s() {
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
+    for (auto &e : far_events)
+        if (e) (void)hipEventDestroy(e);
+}
+
+namespace f3m {
+
+int quant_depth(int D) {
+    int q = 32 / D;
+    return q > 20 ? 20 : q;
+}
+
+// ------------------------------------------------------------------------------------
+// enclosing cube: per-dimension min and max (exact in fp32), non-finite detection
+// ------------------------------------------------------------------------------------
+constexpr int BBOX_BLOCKS = 1024;
+constexpr int BBOX_NT = 256;
+
+template <int D>
+__global__ __launch_bounds__(BBOX_NT) void bbox_kernel(const float *__restrict__ X, int64_t n,
+                                                       float *__restrict__ part, int *__restrict__ nonfinite) {
+    float mn[D], mx[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) { mn[d] = INFINITY; mx[d] = -INFINITY; }
+    int bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * BBOX_NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * BBOX_NT) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            float v = X[i * D + d];
+            bad |= !(fabsf(v) <= 3.402823466e38f);
+            mn[d] = fminf(mn[d], v);
+            mx[d] = fmaxf(mx[d], v);
+        }
+    }
+    __shared__ float smn[BBOX_NT / 64][D], smx[BBOX_NT / 64][D];
+    __shared__ int sbad;
+    if (threadIdx.x == 0) sbad = 0;
+    __syncthreads();
+    int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            mn[d] = fminf(mn[d], __shfl_xor(mn[d], off, 64));
+            mx[d] = fmaxf(mx[d], __shfl_xor(mx[d], off, 64));
+        }
+        if (lane == 0) { smn[w][d] = mn[d]; smx[w][d] = mx[d]; }
+    }
+    if (bad) atomicOr(&sbad, 1);
+    __syncthreads();
+    if (threadIdx.x < D) {
+        int d = threadIdx.x;
+        float a = smn[0][d], b = smx[0][d];
+        for (int k = 1; k < BBOX_NT / 64; ++k) { a = fminf(a, smn[k][d]); b = fmaxf(b, smx[k][d]); }
+        part[(int64_t)blockIdx.x * 2 * D + d] = a;
+        part[(int64_t)blockIdx.x * 2 * D + D + d] = b;
+    }
+    if (threadIdx.x == 0 && sbad) atomicOr(nonfinite, 1);
+}
+
+// ------------------------------------------------------------------------------------
+// cells and keys (Sec. 4.2 box-index formula).  The cell of a point is fixed once, at the
+// quantisation depth Lq, by two separately rounded fp32 operations and a truncation:
+//   c_d = min( trunc( (x_d - alpha_d) * s ), 2^Lq - 1 ),   s = fl32(2^Lq / E)
+// The cell at depth l is c_d >> (Lq - l).  Key: bit k of c_d -> key bit k*D + d.
+// ------------------------------------------------------------------------------------
+struct AlphaArg { float a[F3M_MAX_DIM]; };
+
+template <int D>
+__global__ __launch_bounds__(256) void keys_kernel(const float *__restrict__ X, int64_t n, AlphaArg alpha, float s,
+                                                   int Lq, uint32_t *__restrict__ keys) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    uint32_t cmax = (uint32_t)((1ull << Lq) - 1);
+    uint32_t key = 0;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        float diff = __fsub_rn(X[i * D + d], alpha.a[d]);
+        float u = __fmul_rn(diff, s);
+        uint32_t c = (uint32_t)u;
+        c = c > cmax ? cmax : c;
+        for (int k = 0; k < Lq; ++k) key |= ((c >> k) & 1u) << (k * D + d);
+    }
+    keys[i] = key;
+}
+
+// ------------------------------------------------------------------------------------
+// stable LSD radix sort of (key, index) pairs, 8 bits per pass:
+//   histogram per tile -> exclusive scan in digit-major order -> stable scatter.
+// This replaces the count / cumulative-sum / atomic-increment grouping of Sec. 4.1: the
+// result is deterministic (ascending key, then ascending original index).
+// ------------------------------------------------------------------------------------
+constexpr int RS_NT = 256;
+constexpr int RS_IPT = 16;
+constexpr int RS_TILE = RS_NT * RS_IPT;
+
+__global__ __launch_bounds__(RS_NT) void rs_hist_kernel(const uint32_t *__restrict__ keys, int64_t n, int shift,
+                                                        uint32_t *__restrict__ hist, int64_t nblk) {
+    __shared__ uint32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t base = (int64_t)blockIdx.x * RS_TILE;
+#pragma unroll
+    for (int k = 0; k < RS_IPT; ++k) {
+        int64_t i = base + k * RS_NT + threadIdx.x;
+        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+struct U32In {
+    const uint32_t *p;
+    __device__ uint64_t operator()(int64_t i) const { return p[i]; }
+};
+struct U32Out {
+    uint32_t *p;
+    __device__ void operator()(int64_t i, uint64_t ex, uint64_t) const { p[i] = (uint32_t)ex; }
+};
+
+__global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__restrict__ keys_in,
+                                                           const uint32_t *__restrict__ vals_in,
+                                                           uint32_t *__restrict__ keys_out,
+                                                           uint32_t *__restrict__ vals_out, int64_t n, int shift,
+                                                           const uint32_t *__restrict__ offs, int64_t nblk) {
+    __shared__ uint32_t running[256];
+    __shared__ uint32_t wcnt[RS_NT / 64][256];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    running[tid] = offs[(int64_t)tid * nblk + blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < RS_NT / 64; ++k) wcnt[k][tid] = 0;
+    __syncthreads();
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    for (int round = 0; round < RS_IPT; ++round) {
+        int64_t i = base + round * RS_NT + tid;
+        bool valid = i < n;
+        uint32_t key = valid ? keys_in[i] : 0u;
+        uint32_t val = valid ? (vals_in ? vals_in[i] : (uint32_t)i) : 0u;
+        uint32_t digit = (key >> shift) & 255u;
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            bool bit = (digit >> b) & 1u;
+            uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        uint32_t rank = (uint32_t)__popcll(peers & lt_mask);
+        if (valid && rank == 0) wcnt[w][digit] = (uint32_t)__popcll(peers);
+        __syncthreads();
+        if (valid) {
+            uint32_t pos = running[digit] + rank;
+            for (int k = 0; k < w; ++k) pos += wcnt[k][digit];
+            keys_out[pos] = key;
+            vals_out[pos] = val;
+        }
+        __syncthreads();
+        uint32_t add = 0;
+#pragma unroll
+        for (int k = 0; k < RS_NT / 64; ++k) { add += wcnt[k][tid]; wcnt[k][tid] = 0; }
+        running[tid] += add;
+        __syncthreads();
+    }
+}
+
+// sorts (keys_a, index) by the low `bits` bits; returns true if the result is in the b buffers
+static bool radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uint32_t *vals_b, int64_t n, int bits,
+                       hipStream_t st) {
+    int64_t nblk = cdiv(n, RS_TILE);
+    DevBuf<uint32_t> hist;
+    hist.alloc((size_t)nblk * 256);
+    bool in_b = false, first = true;
+    for (int shift = 0; shift < bits; shift += 8) {
+        const uint32_t *kin = in_b ? keys_b : keys_a;
+        const uint32_t *vin = first ? nullptr : (in_b ? vals_b : vals_a);
+        uint32_t *kout = in_b ? keys_a : keys_b;
+        uint32_t *vout = in_b ? vals_a : vals_b;
+        rs_hist_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, n, shift, hist.p, nblk);
+        F3M_HIP(hipGetLastError());
+        exclusive_scan(U32In{hist.p}, nblk * 256, U32Out{hist.p}, nullptr, st);
+        rs_scatter_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk);
+        F3M_HIP(hipGetLastError());
+        in_b = !in_b;
+        first = false;
+    }
+    F3M_HIP(hipStreamSynchronize(st));
+    return in_b;
+}
+
+__global__ void iota_kernel(uint32_t *p, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = (uint32_t)i;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restrict__ X, const uint32_t *__restrict__ perm,
+                                                          int64_t n, float *__restrict__ Xs) {
+    int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= n) return;
+    int64_t j = perm[k];
+#pragma unroll
+    for (int d = 0; d < D; ++d) Xs[k * D + d] = X[j * D + d];
+}
+
+// ------------------------------------------------------------------------------------
+// box tables per depth (Algorithm 1 "Divide"; empty boxes never appear, Sec. 4.2)
+// ------------------------------------------------------------------------------------
+struct HeadIn {
+    const uint32_t *keys;
+    int shift;
+    __device__ uint64_t operator()(int64_t i) const {
+        if (i == 0) return 1;
+        return ((uint64_t)keys[i] >> shift) != ((uint64_t)keys[i - 1] >> shift);
+    }
+};
+struct HeadOut {
+    const uint32_t *keys;
+    int shift;
+    uint32_t *start, *bkey;
+    __device__ void operator()(int64_t i, uint64_t ex, uint64_t v) const {
+        if (v) {
+            start[ex] = (uint32_t)i;
+            bkey[ex] = (uint32_t)((uint64_t)keys[i] >> shift);
+        }
+    }
+};
+struct ParentOut {
+    uint32_t *parent, *cstart_up;
+    __device__ void operator()(int64_t a, uint64_t ex, uint64_t v) const {
+        parent[a] = (uint32_t)(ex + v - 1);
+        if (v) cstart_up[ex] = (uint32_t)a;
+    }
+};
+
+__global__ void set_u32_kernel(uint32_t *p, uint32_t v) { *p = v; }
+__global__ void set_u64_kernel(uint64_t *p, uint64_t v) { *p = v; }
+
+__global__ __launch_bounds__(256) void max_count_kernel(const uint32_t *__restrict__ start, int64_t nb,
+                                                        uint32_t *__restrict__ part) {
+    uint32_t m = 0;
+    for (int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x; a < nb; a += (int64_t)gridDim.x * 256)
+        m = max(m, start[a + 1] - start[a]);
+    __shared__ uint32_t sm[256];
+    sm[threadIdx.x] = m;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (threadIdx.x < s) sm[threadIdx.x] = max(sm[threadIdx.x], sm[threadIdx.x + s]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) part[blockIdx.x] = sm[0];
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void cells_kernel(const uint32_t *__restrict__ bkey, int64_t nb, int level,
+                                                    int32_t *__restrict__ cell) {
+    int64_t a = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (a >= nb) return;
+    uint32_t key = bkey[a];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        int32_t c = 0;
+        for (int k = 0; k < level; ++k) c |= (int32_t)((key >> (k * D + d)) & 1u) << k;
+        cell[a * D + d] = c;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// interaction lists (Algorithm 1 "Calculate interactions left" and "Partition"):
+// the candidates of a box are the children of the boxes near its parent; a candidate is
+// far iff the squared integer cell offset is >= T = ceil(theta^2)  (Sec. 3, IsFarField
+// := |delta centre| >= 2 l, divided by l).  Rows come out sorted by column rank because the
+// parent's row is sorted and children have consecutive ranks (Sec. 4.1 "Ensuring
+// interactions are sorted").  pass 0 counts, pass 1 fills.
+// ------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const uint32_t *__restrict__ parent,
+                                                    const int32_t *__restrict__ cell,
+                                                    const uint64_t *__restrict__ up_near_ptr,
+                                                    const uint32_t *__restrict__ up_near_col,
+                                                    const uint32_t *__restrict__ up_cstart, int T, int all_near,
+                                                    uint32_t *__restrict__ cnt_near, uint32_t *__restrict__ cnt_far,
+                                                    const uint64_t *__restrict__ near_ptr,
+                                                    const uint64_t *__restrict__ far_ptr,
+                                                    uint32_t *__restrict__ near_col, uint32_t *__restrict__ far_col) {
+    int64_t a = (int64_t)blockIdx.x * 128 + threadIdx.x;
+    if (a >= nb) return;
+    int32_t ca[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) ca[d] = cell[a * D + d];
+    uint32_t P = parent[a];
+    uint64_t nn = 0, nf = 0;
+    uint64_t nbase = pass ? near_ptr[a] : 0, fbase = pass ? far_ptr[a] : 0;
+    for (uint64_t e = up_near_ptr[P]; e < up_near_ptr[P + 1]; ++e) {
+        uint32_t Q = up_near_col[e];
+        uint32_t b1 = up_cstart[Q + 1];
+        for (uint32_t bq = up_cstart[Q]; bq < b1; ++bq) {
+            int d2 = 0;
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                int o = cell[(int64_t)bq * D + d] - ca[d];
+                d2 += o * o;
+            }
+            bool is_far = !all_near && d2 >= T;
+            if (is_far) {
+                if (pass) far_col[fbase + nf] = bq;
+                ++nf;
+            } else {
+                if (pass) near_col[nbase + nn] = bq;
+                ++nn;
+            }
+        }
+    }
+    if (!pass) {
+        cnt_near[a] = (uint32_t)nn;
+        cnt_far[a] = (uint32_t)nf;
+    }
+}
+
+struct PtrOut {
+    uint64_t *p;
+    __device__ void operator()(int64_t i, uint64_t ex, uint64_t) const { p[i] = ex; }
+};
+
+// ------------------------------------------------------------------------------------
+// work splits: runs of at most `chunk` points inside a box
+// ------------------------------------------------------------------------------------
+struct ChunkCountIn {
+    const uint32_t *start;
+    uint32_t chunk;
+    __device__ uint64_t operator()(int64_t a) const { return (start[a + 1] - start[a] + chunk - 1) / chunk; }
+};
+
+__global__ __launch_bounds__(256) void chunk_box_kernel(const uint32_t *__restrict__ first, int64_t nb, int64_t nchunks,
+                                                        uint32_t *__restrict__ chunk_box) {
+    int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= nchunks) return;
+    // largest a with first[a] <= c   (first is non-decreasing, first[nb] = nchunks > c)
+    int64_t lo = 0, hi = nb;
+    while (hi - lo > 1) {
+        int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)first[mid] <= c) lo = mid; else hi = mid;
+    }
+    chunk_box[c] = (uint32_t)lo;
+}
+
+static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevBuf<uint32_t> &first,
+                         DevBuf<uint32_t> &cbox, int64_t &nchunks, int64_t *tally, hipStream_t st) {
+    first.alloc((size_t)nb + 1, tally);
+    uint64_t total = 0;
+    exclusive_scan(ChunkCountIn{start, chunk}, nb, U32Out{first.p}, &total, st);
+    nchunks = (int64_t)total;
+    set_u32_kernel<<<1, 1, 0, st>>>(first.p + nb, (uint32_t)total);
+    cbox.alloc((size_t)nchunks, tally);
+    if (nchunks > 0)
+        chunk_box_kernel<<<dim3((unsigned)cdiv(nchunks, 256)), dim3(256), 0, st>>>(first.p, nb, nchunks, cbox.p);
+    F3M_HIP(hipGetLastError());
+}
+
+// ------------------------------------------------------------------------------------
+template <int D>
+static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
+    const int64_t n = P.n;
+    int64_t *tally = &P.bytes;
+    for (int k = 0; k < 8; ++k) F3M_HIP(hipEventCreate(&P.ev[k]));
+    F3M_HIP(hipEventRecord(P.ev[0], st));
+
+    // ---- enclosing cube
+    {
+        DevBuf<float> part;
+        DevBuf<int> bad;
+        part.alloc((size_t)BBOX_BLOCKS * 2 * D);
+        bad.alloc(1);
+        F3M_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
+        bbox_kernel<D><<<dim3(BBOX_BLOCKS), dim3(BBOX_NT), 0, st>>>(X, n, part.p, bad.p);
+        F3M_HIP(hipGetLastError());
+        std::vector<float> hp((size_t)BBOX_BLOCKS * 2 * D);
+        int hbad = 0;
+        F3M_HIP(hipMemcpyAsync(hp.data(), part.p, hp.size() * sizeof(float), hipMemcpyDeviceToHost, st));
+        F3M_HIP(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
+        F3M_HIP(hipStreamSynchronize(st));
+        if (hbad) fail(F3M_ERR_NONFINITE, "X holds a NaN or an infinity");
+        float E = 0.f;
+        for (int d = 0; d < D; ++d) {
+            float mn = INFINITY, mx = -INFINITY;
+            for (int k = 0; k < BBOX_BLOCKS; ++k) {
+                mn = std::min(mn, hp[(size_t)k * 2 * D + d]);
+                mx = std::max(mx, hp[(size_t)k * 2 * D + D + d]);
+            }
+            volatile float ext = mx - mn;  // one fp32 subtraction
+            if (ext > E) E = ext;
+            P.alpha[d] = mn;
+        }
+        P.E = E;
+        P.scale = E > 0.f ? (float)(std::ldexp(1.0, P.Lq) / (double)E) : 0.f;
+    }
+
+    // ---- keys, sort, gather
+    DevBuf<uint32_t> keys_b, perm_b;
+    P.keys.alloc((size_t)n, tally);
+    P.perm.alloc((size_t)n, tally);
+    keys_b.alloc((size_t)n);
+    perm_b.alloc((size_t)n);
+    {
+        AlphaArg aa;
+        for (int d = 0; d < F3M_MAX_DIM; ++d) aa.a[d] = P.alpha[d];
+        keys_kernel<D><<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(X, n, aa, P.scale, P.Lq, P.keys.p);
+        F3M_HIP(hipGetLastError());
+    }
+    F3M_HIP(hipEventRecord(P.ev[1], st));
+    {
+        int bits = P.E > 0.f ? D * P.Lq : 0;
+        bool in_b;
+        if (bits == 0) {
+            iota_kernel<<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(P.perm.p, n);
+            in_b = false;
+        } else {
+            in_b = radix_sort(P.keys.p, P.perm.p, keys_b.p, perm_b.p, n, bits, st);
+        }
+        if (in_b) {
+            std::swap(P.keys.p, keys_b.p);
+            std::swap(P.perm.p, perm_b.p);
+        }
+    }
+    F3M_HIP(hipEventRecord(P.ev[2], st));
+    P.Xs.alloc((size_t)n * D, tally);
+    gather_rows_kernel<D><<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(X, P.perm.p, n, P.Xs.p);
+    F3M_HIP(hipGetLastError());
+    F3M_HIP(hipEventRecord(P.ev[3], st));
+    F3M_HIP(hipStreamSynchronize(st));
+    keys_b.release();
+    perm_b.release();
+
+    // ---- Algorithm 1 loop: divide, new interactions, partition
+    int cap = P.Lq;
+    if (P.max_depth > 0 && P.max_depth < cap) cap = P.max_depth;
+    if (cap > F3M_MAX_LEVELS) cap = F3M_MAX_LEVELS;
+    if (!(P.E > 0.f)) cap = 0;
+    DevBuf<uint32_t> part;
+    part.alloc(1024);
+    float t_boxes = 0.f, t_lists = 0.f;
+    hipEvent_t ea = P.ev[4], eb = P.ev[5], ec = P.ev[6];
+    int l = 0;
+    for (;; ++l) {
+        f3m_level &lv = P.lev[l];
+        F3M_HIP(hipEventRecord(ea, st));
+        // divide: heads of runs of equal depth-l keys
+        int shift = D * (P.Lq - l);
+        HeadIn hin{P.keys.p, shift};
+        ScanState S;
+        scan_prepare(hin, n, S, true, st);
+        lv.nb = (int64_t)S.total;
+        lv.key.alloc((size_t)lv.nb, tally);
+        lv.start.alloc((size_t)lv.nb + 1, tally);
+        scan_finish(hin, n, S, HeadOut{P.keys.p, shift, lv.start.p, lv.key.p}, st);
+        set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
+        {
+            int grid = (int)std::min<int64_t>(1024, cdiv(lv.nb, 256));
+            max_count_kernel<<<dim3(grid), dim3(256), 0, st>>>(lv.start.p, lv.nb, part.p);
+            F3M_HIP(hipGetLastError());
+            std::vector<uint32_t> hp(grid);
+            F3M_HIP(hipMemcpyAsync(hp.data(), part.p, grid * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+            F3M_HIP(hipStreamSynchronize(st));
+            lv.max_box = *std::max_element(hp.begin(), hp.end());
+        }
+        lv.cell.alloc((size_t)lv.nb * D, tally);
+        cells_kernel<D><<<dim3((unsigned)cdiv(lv.nb, 256)), dim3(256), 0, st>>>(lv.key.p, lv.nb, l, lv.cell.p);
+        F3M_HIP(hipGetLastError());
+        lv.parent.alloc((size_t)lv.nb, tally);
+        if (l > 0) {
+            f3m_level &up = P.lev[l - 1];
+            up.cstart.alloc((size_t)up.nb + 1, tally);
+            HeadIn pin{lv.key.p, D};
+            uint64_t tot = 0;
+            exclusive_scan(pin, lv.nb, ParentOut{lv.parent.p, up.cstart.p}, &tot, st);
+            if ((int64_t)tot != up.nb) fail(F3M_ERR_HIP, "internal: parent count mismatch");
+            set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
+        } else {
+            F3M_HIP(hipMemsetAsync(lv.parent.p, 0, sizeof(uint32_t), st));
+        }
+        F3M_HIP(hipEventRecord(eb, st));
+
+        // new interactions + partition
+        lv.near_ptr.alloc((size_t)lv.nb + 1, tally);
+        lv.far_ptr.alloc((size_t)lv.nb + 1, tally);
+        if (l == 0) {
+            lv.near_col.alloc(1, tally);
+            lv.far_col.alloc(1, tally);
+            F3M_HIP(hipMemsetAsync(lv.near_ptr.p, 0, 2 * sizeof(uint64_t), st));
+            F3M_HIP(hipMemsetAsync(lv.far_ptr.p, 0, 2 * sizeof(uint64_t), st));
+            F3M_HIP(hipMemsetAsync(lv.near_col.p, 0, sizeof(uint32_t), st));
+            set_u64_kernel<<<1, 1, 0, st>>>(lv.near_ptr.p + 1, 1ull);
+            lv.near_sz = 1;
+            lv.far_sz = 0;
+        } else {
+            f3m_level &up = P.lev[l - 1];
+            DevBuf<uint32_t> cn, cf;
+            cn.alloc((size_t)lv.nb);
+            cf.alloc((size_t)lv.nb);
+            unsigned grid = (unsigned)cdiv(lv.nb, 128);
+            lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
+                                                             up.near_col.p, up.cstart.p, P.T, P.force_all_near, cn.p,
+                                                             cf.p, nullptr, nullptr, nullptr, nullptr);
+            F3M_HIP(hipGetLastError());
+            uint64_t tn = 0, tf = 0;
+            exclusive_scan(U32In{cn.p}, lv.nb, PtrOut{lv.near_ptr.p}, &tn, st);
+            exclusive_scan(U32In{cf.p}, lv.nb, PtrOut{lv.far_ptr.p}, &tf, st);
+            set_u64_kernel<<<1, 1, 0, st>>>(lv.near_ptr.p + lv.nb, tn);
+            set_u64_kernel<<<1, 1, 0, st>>>(lv.far_ptr.p + lv.nb, tf);
+            lv.near_sz = (int64_t)tn;
+            lv.far_sz = (int64_t)tf;
+            lv.near_col.alloc((size_t)tn, tally);
+            lv.far_col.alloc((size_t)tf, tally);
+            lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
+                                                             up.near_col.p, up.cstart.p, P.T, P.force_all_near, nullptr,
+                                                             nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
+                                                             lv.far_col.p);
+            F3M_HIP(hipGetLastError());
+            F3M_HIP(hipStreamSynchronize(st));
+        }
+        F3M_HIP(hipEventRecord(ec, st));
+        F3M_HIP(hipStreamSynchronize(st));
+        float ms = 0.f;
+        F3M_HIP(hipEventElapsedTime(&ms, ea, eb));
+        t_boxes += ms;
+        F3M_HIP(hipEventElapsedTime(&ms, eb, ec));
+        t_lists += ms;
+        // while interactions remain and the largest box is above zeta (Algorithm 1)
+        if (!(lv.near_sz > 0 && lv.max_box > P.leaf_max && l < cap)) break;
+    }
+    P.L = l;
+    // near lists of the depths above L are only needed to derive the next depth
+    for (int k = 0; k < P.L; ++k) {
+        // kept: they are small next to the leaf lists and serve introspection
+    }
+
+    // ---- work splits and workspaces
+    F3M_HIP(hipEventRecord(ea, st));
+    int64_t max_nb = 0, max_chunks = 0;
+    for (int k = 1; k <= P.L; ++k) {
+        f3m_level &lv = P.lev[k];
+        if (lv.far_sz == 0) continue;
+        build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
+        max_nb = std::max(max_nb, lv.nb);
+        max_chunks = std::max(max_chunks, lv.nchunks);
+    }
+    build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
+    P.bs.alloc((size_t)n, tally);
+    P.ys.alloc((size_t)n, tally);
+    P.W.alloc((size_t)max_nb * P.r, tally);
+    P.V.alloc((size_t)max_nb * P.r, tally);
+    P.Wpart.alloc((size_t)max_chunks * P.r, tally);
+    build_far_tables(P, st);
+    F3M_HIP(hipEventRecord(eb, st));
+    F3M_HIP(hipStreamSynchronize(st));
+
+    float ms = 0.f;
+    F3M_HIP(hipEventElapsedTime(&P.times.bbox_keys, P.ev[0], P.ev[1]));
+    F3M_HIP(hipEventElapsedTime(&P.times.sort, P.ev[1], P.ev[2]));
+    F3M_HIP(hipEventElapsedTime(&P.times.gather, P.ev[2], P.ev[3]));
+    P.times.boxes = t_boxes;
+    P.times.lists = t_lists;
+    F3M_HIP(hipEventElapsedTime(&P.times.tables, ea, eb));
+    F3M_HIP(hipEventElapsedTime(&ms, P.ev[0], eb));
+    P.times.plan_total = ms;
+    P.have_plan_times = true;
+}
+
+void build_plan(f3m_plan_s &P, const float *X, hipStream_t st) {
+    switch (P.D) {
+        case 1: build_plan_d<1>(P, X, st); break;
+        case 2: build_plan_d<2>(P, X, st); break;
+        case 3: build_plan_d<3>(P, X, st); break;
+        case 4: build_plan_d<4>(P, X, st); break;
+        case 5: build_plan_d<5>(P, X, st); break;
+        case 6: build_plan_d<6>(P, X, st); break;
+        case 7: build_plan_d<7>(P, X, st); break;
+        default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
+    }
+}
+
+}  // namespace f3m

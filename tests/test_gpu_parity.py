@@ -1,0 +1,299 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle.
+
+Bars: keys, permutation, box tables and interaction lists bit-exact; y against the CPU
+F3M to relative L2 <= 1e-5; y against the exact product to <= 1e-3 where the method
+itself (the oracle) reaches that, otherwise the oracle's own error is the bar.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2202_01085_amd import f3m, inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL_F3M = 1e-5      # GPU F3M vs CPU F3M, relative L2
+TOL_EXACT = 1e-3    # F3M vs exact, relative L2
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+def cloud(dist, n, D, seed):
+    gen = {"uniform": inputs.points_uniform, "normal": inputs.points_normal, "mixture": inputs.points_mixture}[dist]
+    return gen(n, D, seed)
+
+
+def g32(gamma):
+    """the lengthscale as the C ABI sees it (a float), for the oracle"""
+    return float(np.float32(gamma))
+
+
+def to_dev(*arrs):
+    return [a.to(DEV).contiguous() for a in arrs]
+
+
+def check_plan_bit_exact(plan, T):
+    inf = plan.info()
+    assert inf.depth == T.L and inf.quant_depth == T.Lq
+    assert float(inf.edge) == np.float32(T.E)
+    assert [float(inf.alpha[d]) for d in range(T.D)] == [float(np.float32(a)) for a in T.alpha]
+    perm = plan.perm().astype(np.int64)
+    assert np.array_equal(perm, T.perm())
+    assert np.array_equal(plan.point_keys().astype(np.uint64), T.point_keys()[T.perm()])
+    for l in range(T.L + 1):
+        keys, starts = plan.boxes(l)
+        okeys, ostarts = T.boxes(l)
+        assert np.array_equal(keys.astype(np.uint64), okeys), l
+        assert np.array_equal(starts.astype(np.int64), ostarts), l
+        for kind in (0, 1):
+            ptr, cols = plan.interactions(l, kind)
+            optr, ocols = T.interactions(l, kind)
+            assert np.array_equal(ptr.astype(np.int64), optr), (l, kind)
+            assert np.array_equal(cols.astype(np.int64), ocols), (l, kind)
+
+
+# --------------------------------------------------------------------------------------
+def test_direct_config1_matches_oracle():
+    X, b, cfg = inputs.make_config(1)
+    say("direct_kmvm config 1 n=%d" % cfg["n"])
+    Xd, bd = to_dev(X, b)
+    y = f3m.direct_kmvm(Xd, bd, cfg["lengthscale"])
+    torch.cuda.synchronize()
+    exact = oracle.direct(X.numpy(), b.numpy(), g32(cfg["lengthscale"]))
+    e = rel(y.cpu().numpy(), exact)
+    say("  rel err vs oracle_direct %.3e" % e)
+    assert e <= TOL_F3M
+
+
+@pytest.mark.parametrize("n,D,dist,gamma", [(1, 3, "uniform", 1.0), (63, 1, "uniform", 0.3), (64, 2, "normal", 0.7),
+                                            (65, 3, "normal", 1.0), (1000, 5, "uniform", 1.5),
+                                            (3001, 7, "mixture", 2.0)])
+def test_direct_ragged_sizes_and_dims(n, D, dist, gamma):
+    say("direct_kmvm n=%d D=%d %s" % (n, D, dist))
+    X = cloud(dist, n, D, 40 + D)
+    b = inputs.rhs_normal(n, 41)
+    Xd, bd = to_dev(X, b)
+    y = f3m.direct_kmvm(Xd, bd, gamma)
+    torch.cuda.synchronize()
+    assert rel(y.cpu().numpy(), oracle.direct(X.numpy(), b.numpy(), g32(gamma))) <= TOL_F3M
+
+
+def test_rows_f64_matches_oracle_rows():
+    X, b, cfg = inputs.make_config(2, n=50_000)
+    rows = inputs.sample_rows(50_000, 300, 3002)
+    say("direct_kmvm_rows_f64 n=50000 rows=300")
+    Xd, bd = to_dev(X, b)
+    y64 = f3m.direct_kmvm_rows_f64(Xd, bd, cfg["lengthscale"], rows)
+    torch.cuda.synchronize()
+    want = oracle.rows(X.numpy(), b.numpy(), g32(cfg["lengthscale"]), rows.numpy())
+    assert rel(y64.cpu().numpy(), want) <= 1e-12
+
+
+# --------------------------------------------------------------------------------------
+PLAN_CASES = [
+    # n, D, dist, p, gamma, theta, zeta, max_depth
+    (20_000, 3, "uniform", 4, 1.0, 2.0, 128, 0),      # configuration 1
+    (30_000, 3, "normal", 4, 0.5, 2.0, 64, 0),
+    (5_000, 1, "uniform", 5, 0.05, 2.0, 16, 0),
+    (8_000, 2, "normal", 6, 0.4, 2.0, 32, 0),
+    (9_000, 3, "normal", 3, 0.8, 1.5, 40, 0),
+    (9_000, 3, "uniform", 2, 0.8, 3.0, 40, 0),
+    (6_000, 4, "uniform", 3, 1.0, 2.0, 50, 2),
+    (4_000, 5, "uniform", 2, 1.0, 2.0, 60, 2),
+    (6_000, 7, "mixture", 2, 1.5, 2.0, 100, 1),
+]
+
+
+@pytest.mark.parametrize("n,D,dist,p,gamma,theta,zeta,max_depth", PLAN_CASES)
+def test_plan_bit_exact_and_kmvm_parity(n, D, dist, p, gamma, theta, zeta, max_depth):
+    say("f3m n=%d D=%d %s p=%d gamma=%g theta=%g zeta=%d max_depth=%d" % (n, D, dist, p, gamma, theta, zeta, max_depth))
+    X = cloud(dist, n, D, 1000 + D)
+    b = inputs.rhs_normal(n, 2000 + D)
+    T = oracle.Tree(X.numpy(), theta=theta, zeta=zeta, max_depth=max_depth)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, gamma, p, theta, leaf_max=zeta, max_depth=max_depth)
+    check_plan_bit_exact(plan, T)
+    say("  plan bit-exact, L=%d boxes=%s" % (T.L, [T.nboxes(l) for l in range(T.L + 1)]))
+    y = plan.kmvm(bd)
+    torch.cuda.synchronize()
+    yo = T.apply(b.numpy(), g32(gamma), p)
+    e = rel(y.cpu().numpy(), yo)
+    say("  rel err vs CPU F3M %.3e" % e)
+    assert e <= TOL_F3M
+    # a second product on the same plan gives the same bits (no atomics on the float path)
+    y2 = plan.kmvm(bd)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    plan.close()
+
+
+def test_config1_error_vs_exact():
+    X, b, cfg = inputs.make_config(1)
+    say("f3m config 1 vs exact")
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, cfg["lengthscale"], cfg["p"], cfg["theta"])
+    y = plan.kmvm(bd).cpu().numpy()
+    exact = oracle.direct(X.numpy(), b.numpy(), g32(cfg["lengthscale"]))
+    e = rel(y, exact)
+    say("  rel err vs exact %.3e, stage times %s" % (e, plan.stage_times()))
+    assert e <= TOL_EXACT
+
+
+def test_tiny_7d_three_nodes():
+    # D = 7 with 3 nodes per dimension (r = 2187), kept tiny because the oracle evaluates
+    # r^2 kernel values per far pair
+    n = 160
+    X = cloud("mixture", n, 7, 77)
+    b = inputs.rhs_normal(n, 78)
+    say("f3m D=7 p=3 n=%d" % n)
+    T = oracle.Tree(X.numpy(), zeta=8, max_depth=1)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, 3.0, 3, 2.0, leaf_max=8, max_depth=1)
+    check_plan_bit_exact(plan, T)
+    y = plan.kmvm(bd).cpu().numpy()
+    assert sum(len(T.interactions(l, 1)[1]) for l in range(1, T.L + 1)) > 0
+    assert rel(y, T.apply(b.numpy(), 3.0, 3)) <= TOL_F3M
+
+
+def test_force_all_near_equals_direct():
+    X = cloud("normal", 12_000, 3, 9)
+    b = inputs.rhs_normal(12_000, 10)
+    say("f3m force_all_near n=12000")
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, 0.6, 4, 2.0, leaf_max=64, force_all_near=True)
+    inf = plan.info()
+    assert inf.depth >= 2 and all(inf.far_pairs[l] == 0 for l in range(inf.depth + 1))
+    y = plan.kmvm(bd).cpu().numpy()
+    yd = f3m.direct_kmvm(Xd, bd, 0.6).cpu().numpy()
+    say("  all-near vs direct_kmvm (both fp32) %.3e" % rel(y, yd))
+    assert rel(y, yd) <= TOL_F3M
+    assert rel(y, oracle.direct(X.numpy(), b.numpy(), g32(0.6))) <= TOL_F3M
+
+
+# --------------------------------------------------------------------------------------
+# edge cases
+# --------------------------------------------------------------------------------------
+def test_empty_problem():
+    X = torch.empty((0, 3), dtype=torch.float32, device=DEV)
+    b = torch.empty(0, dtype=torch.float32, device=DEV)
+    plan = f3m.Plan(X, 1.0, 4)
+    assert plan.kmvm(b).numel() == 0
+    assert f3m.direct_kmvm(X, b, 1.0).numel() == 0
+
+
+@pytest.mark.parametrize("n", [1, 2, 64, 129])
+def test_all_points_equal_is_one_box(n):
+    say("degenerate n=%d" % n)
+    X = torch.full((n, 3), 0.75, dtype=torch.float32)
+    b = inputs.rhs_normal(n, 5)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, 1.0, 4, leaf_max=16)
+    inf = plan.info()
+    assert inf.depth == 0 and inf.edge == 0.0
+    y = plan.kmvm(bd).cpu().numpy()
+    assert y == pytest.approx(np.full(n, b.double().sum().item()), rel=1e-5, abs=1e-5)
+
+
+def test_small_n_below_leaf_size_is_direct():
+    X = cloud("uniform", 100, 3, 3)
+    b = inputs.rhs_normal(100, 4)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, 0.5, 4)
+    assert plan.info().depth == 0
+    assert rel(plan.kmvm(bd).cpu().numpy(), oracle.direct(X.numpy(), b.numpy(), g32(0.5))) <= TOL_F3M
+
+
+def test_points_on_the_max_face_and_duplicates():
+    # the cube's max face must clamp into the last cell; duplicate points share a box
+    rng = np.random.default_rng(0)
+    base = rng.integers(0, 9, size=(3000, 3)).astype(np.float32) / 8.0     # lattice incl. 0 and 1
+    X = torch.from_numpy(base)
+    b = inputs.rhs_normal(3000, 6)
+    T = oracle.Tree(X.numpy(), zeta=40)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, 0.4, 4, leaf_max=40)
+    check_plan_bit_exact(plan, T)
+    assert rel(plan.kmvm(bd).cpu().numpy(), T.apply(b.numpy(), g32(0.4), 4)) <= TOL_F3M
+
+
+def test_error_paths():
+    X = cloud("uniform", 500, 3, 1).to(DEV)
+    b = inputs.rhs_normal(500, 2).to(DEV)
+    bad = X.clone()
+    bad[17, 1] = float("nan")
+    with pytest.raises(f3m.F3MError) as ei:
+        f3m.Plan(bad, 1.0, 4)
+    assert ei.value.status == 2
+    bad[17, 1] = float("inf")
+    with pytest.raises(f3m.F3MError) as ei:
+        f3m.Plan(bad, 1.0, 4)
+    assert ei.value.status == 2
+    for kwargs in (dict(lengthscale=0.0), dict(lengthscale=float("nan")), dict(interp_nodes=1), dict(eta=-1.0)):
+        args = dict(lengthscale=1.0, interp_nodes=4, eta=2.0)
+        args.update(kwargs)
+        with pytest.raises(f3m.F3MError) as ei:
+            f3m.Plan(X, args["lengthscale"], args["interp_nodes"], args["eta"])
+        assert ei.value.status == 1
+    with pytest.raises(f3m.F3MError) as ei:
+        f3m.Plan(X, 1.0, 9)                       # above the supported nodes per dimension
+    assert ei.value.status == 3
+    X7 = cloud("uniform", 100, 7, 1).to(DEV)
+    with pytest.raises(f3m.F3MError) as ei:
+        f3m.Plan(X7, 1.0, 4)                      # 4^7 nodes is above the cap
+    assert ei.value.status == 3
+    plan = f3m.Plan(X, 1.0, 4)
+    with pytest.raises(f3m.F3MError):
+        plan.kmvm(b, b)                           # aliasing
+    # the plan still works after the failed calls
+    assert torch.isfinite(plan.kmvm(b)).all()
+
+
+# --------------------------------------------------------------------------------------
+# configuration 2 at full size: sampled rows against the fp64 exact rows
+# --------------------------------------------------------------------------------------
+def test_config2_full_size_sampled_rows():
+    X, b, cfg = inputs.make_config(2, device=DEV)
+    n = cfg["n"]
+    say("f3m config 2 n=%d (normal, lengthscale 0.1)" % n)
+    plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"])
+    y = plan.kmvm(b)
+    torch.cuda.synchronize()
+    inf = plan.info()
+    say("  L=%d boxes=%s far=%s near_L=%d times=%s" % (inf.depth, list(inf.nboxes)[:inf.depth + 1],
+                                                     list(inf.far_pairs)[:inf.depth + 1], inf.near_pairs[inf.depth],
+                                                     plan.stage_times()))
+    rows = inputs.sample_rows(n, 10_000, 3002)
+    y64 = f3m.direct_kmvm_rows_f64(X, b, cfg["lengthscale"], rows).cpu().numpy()
+    # the fp64 row kernel is itself pinned to the CPU oracle on 200 of the same rows
+    Xh, bh = X.cpu().numpy(), b.cpu().numpy()
+    sub = rows[:200].numpy()
+    assert rel(y64[:200], oracle.rows(Xh, bh, g32(cfg["lengthscale"]), sub)) <= 1e-12
+    e = rel(y[rows.to(DEV)].cpu().numpy(), y64)
+    say("  rel err vs exact on 10000 rows %.3e" % e)
+    # The method itself is less accurate on this workload than on the uniform ones: the CPU
+    # oracle of the same recipe at n = 60000 is 1.5e-3 away from the exact product (far
+    # boxes of the middle depths are wide against the lengthscale).  Bar: the same order.
+    assert e <= 3e-3
+    # structure check at full size: every ordered point pair is covered exactly once
+    total = 0
+    for l in range(1, inf.depth + 1):
+        cnt = np.diff(plan.boxes(l)[1].astype(np.int64))
+        ptr, cols = plan.interactions(l, 1)
+        total += int((np.repeat(cnt, np.diff(ptr.astype(np.int64))) * cnt[cols]).sum())
+    cnt = np.diff(plan.boxes(inf.depth)[1].astype(np.int64))
+    ptr, cols = plan.interactions(inf.depth, 0)
+    total += int((np.repeat(cnt, np.diff(ptr.astype(np.int64))) * cnt[cols]).sum())
+    assert total == n * n
