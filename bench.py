@@ -1,0 +1,159 @@
+"""Benchmark of the whole F3M hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is
+already resident in HBM: f3m_plan (enclosing cube, keys, sort, box tables,
+interaction lists, kernel tables) followed by f3m_kmvm (P2M, M2L, L2P per depth,
+near-field P2P, permutations).  Prints ONE JSON line on stdout.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--n N] [--rows R] [--no-cpu]
+
+The default workload is configuration 5 of the benchmark list: n = 1e9 points,
+D = 3, iid Uniform[0,1]^3, Gaussian lengthscale 1.0, b ~ N(0,1), 4 nodes per
+dimension, far ratio 2.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3     # MI355X dense fp32 matrix peak
+PEAK_VALU_F32_TFLOPS = 78.6      # 256 CU x 64 lanes x 2.4 GHz x 2 flop, packed fp32 not used
+PEAK_HBM_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, n_sample):
+    """The CPU oracle (fp64 F3M, as it stands) on a bounded sample of the same workload."""
+    import oracle
+    from paper_2202_01085_amd import inputs
+    gen = {"uniform": inputs.points_uniform, "normal": inputs.points_normal, "mixture": inputs.points_mixture}[cfg["dist"]]
+    X = gen(n_sample, cfg["D"], 1000 + cfg["k"]).numpy()
+    b = inputs.rhs_normal(n_sample, 2000 + cfg["k"]).numpy()
+    t0 = time.time()
+    T = oracle.Tree(X, theta=cfg["theta"], zeta=128)
+    T.apply(b, cfg["lengthscale"], cfg["p"])
+    dt = time.time() - t0
+    return {"value": n_sample / dt, "unit": "points/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "oracle F3M (tree + product, fp64) on n=%d points of the same distribution, depth %d, %.1f s"
+                      % (n_sample, T.L, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--n", type=float, default=1e9, help="points (default: configuration 5, 1e9)")
+    ap.add_argument("--rows", type=int, default=10000, help="sampled rows for the error against the exact product")
+    ap.add_argument("--cpu-sample", type=int, default=400000, help="points of the CPU oracle sample")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (the path is one GPU's share; see DESIGN.md, "
+              "'How the path would shard'); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2202_01085_amd import f3m, inputs
+
+    n = int(args.n)
+    k = 5 if n >= 500_000_000 else 3
+    cfg = dict(inputs.CONFIGS[k], k=k)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    log("generating n=%d %s points on the device ..." % (n, cfg["dist"]))
+    X, b, _ = inputs.make_config(k, n=n, device=dev)
+    y = torch.empty_like(b)
+    torch.cuda.synchronize()
+
+    def step():
+        plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"])
+        plan.kmvm(b, y)
+        return plan
+
+    plan = None
+    for _ in range(args.warmup):
+        if plan is not None:
+            plan.close()
+        plan = step()
+    torch.cuda.synchronize()
+    if plan is not None:
+        plan.close()
+        plan = None
+
+    stage_sum, level_ms = {}, None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        if plan is not None:
+            plan.close()            # frees the previous step's plan (its memory is needed at n = 1e9)
+        plan = step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # per-kernel durations from the HIP events the library records on the launch stream
+    st = plan.stage_times()
+    inf = plan.info()
+    L = inf.depth
+    level_ms = {l: plan.level_times(l) for l in range(1, L + 1)}
+    far_L = int(inf.far_pairs[L])
+    r = inf.nodes_per_box
+    m2l_ms = level_ms[L][1] if L >= 1 else 0.0
+    near_pairs_pts = None
+    roof = None
+    if far_L > 0 and m2l_ms > 0:
+        flops = 2.0 * r * r * far_L          # algorithmic: 2 r^2 flop per far pair
+        ach = flops / (m2l_ms * 1e-3) / 1e12
+        roof = {"kernel": "m2l (leaf depth %d, %d far pairs)" % (L, far_L), "bound": "mfma", "achieved": ach,
+                "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_MFMA_F32_TFLOPS, "traffic": None,
+                "launch_ms": m2l_ms}
+
+    # error against the exact product on sampled rows (fp64 row kernel, pinned to the oracle in the tests)
+    rows = inputs.sample_rows(n, args.rows, 3000 + k)
+    t1 = time.perf_counter()
+    y64 = f3m.direct_kmvm_rows_f64(X, b, cfg["lengthscale"], rows)
+    torch.cuda.synchronize()
+    t_rows = time.perf_counter() - t1
+    yr = y[rows.to(dev)].double()
+    rel_err = (torch.linalg.norm(yr - y64) / torch.linalg.norm(y64)).item()
+    log("exact rows: %d rows in %.1f s, rel err %.3e" % (rows.numel(), t_rows, rel_err))
+
+    out = {
+        "metric": "full KMVM throughput (plan + product), F3M",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "points/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config %d: n=%d D=%d %s, Gaussian lengthscale %g, b~N(0,1), %d nodes/dim, far ratio %g"
+                               % (k, n, cfg["D"], cfg["dist"], cfg["lengthscale"], cfg["p"], cfg["theta"]),
+                   "depth": L, "leaf_max": 128, "boxes_leaf": int(inf.nboxes[L]), "near_pairs_leaf": int(inf.near_pairs[L]),
+                   "far_pairs_leaf": far_L, "device_bytes": int(inf.device_bytes)},
+        "wall_s_per_kmvm_with_plan": ms_per_step * 1e-3,
+        "rel_err_vs_exact": rel_err, "rel_err_rows": int(rows.numel()),
+        "stage_ms": st,
+        "level_ms": {str(l): {"p2m": v[0], "m2l": v[1], "l2p": v[2]} for l, v in level_ms.items()},
+        "roofline": roof,
+        "paper_context": "paper: 125.9 s (r=64) and 174.0+-76.6 s (mean over data sets) for n=1e9, D=3 on one V100-32GB",
+    }
+    plan.close()
+    del X, y
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -166,6 +166,11 @@ f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind,
 /* Stage times of the last plan build and the last f3m_kmvm (synchronises). */
 f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out);
 
+/* Far-field kernel times of one depth in the last f3m_kmvm, measured with HIP events on
+ * the stream the kernels were launched on: ms_host[0..2] = P2M, M2L, L2P of that depth
+ * (zeros if the depth has no far pairs).  Synchronises. */
+f3m_status f3m_level_times(f3m_plan_t *plan, int level, float *ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -211,4 +211,18 @@ f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out) {
     });
 }
 
+f3m_status f3m_level_times(f3m_plan_t *plan, int level, float *ms_host) {
+    if (!plan || !ms_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    return guarded([&] {
+        ms_host[0] = ms_host[1] = ms_host[2] = 0.f;
+        if (!plan->have_kmvm_times || plan->lev[level].far_sz == 0 || plan->far_events.size() < (size_t)(level + 1) * 4)
+            return;
+        hipEvent_t *ev = &plan->far_events[(size_t)level * 4];
+        if (!ev[3]) return;
+        F3M_HIP(hipEventSynchronize(ev[3]));
+        for (int k = 0; k < 3; ++k) F3M_HIP(hipEventElapsedTime(&ms_host[k], ev[k], ev[k + 1]));
+    });
+}
+
 }  // extern "C"

@@ -23,6 +23,15 @@ struct CentreArg {
     double inv_half;  // 2 / l
 };
 
+// 2-D launch shape for `count` blocks: the runtime limits grid.x * block.x to 32 bits, so
+// large block counts are folded over y; kernels recover the index with block_index().
+static dim3 grid_for(int64_t count) {
+    const int64_t gx = 1 << 16;
+    if (count <= gx) return dim3((unsigned)(count > 0 ? count : 1), 1, 1);
+    return dim3((unsigned)gx, (unsigned)cdiv(count, gx), 1);
+}
+__device__ inline int64_t block_index() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+
 static NodeArg make_nodes(int p) {
     NodeArg a{};
     double s[P_MAX];
@@ -71,9 +80,10 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, c
                                                  const uint64_t *__restrict__ near_ptr,
                                                  const uint32_t *__restrict__ near_col,
                                                  const uint32_t *__restrict__ tile_box,
-                                                 const uint32_t *__restrict__ tile_first, float nc2,
-                                                 float *__restrict__ ys) {
-    const int64_t t = blockIdx.x;
+                                                 const uint32_t *__restrict__ tile_first, int64_t ntiles,
+                                                 float nc2, float *__restrict__ ys) {
+    const int64_t t = block_index();
+    if (t >= ntiles) return;
     const uint32_t a = tile_box[t];
     const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
     const uint32_t kend = start[a + 1];
@@ -204,14 +214,16 @@ template <int D, int NT>
 __global__ __launch_bounds__(NT) void p2m_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
                                                  const uint32_t *__restrict__ start, const int32_t *__restrict__ cell,
                                                  const uint32_t *__restrict__ chunk_box,
-                                                 const uint32_t *__restrict__ chunk_first, int p, int r, CentreArg C,
-                                                 NodeArg N, float *__restrict__ W, float *__restrict__ Wpart) {
+                                                 const uint32_t *__restrict__ chunk_first, int64_t nchunks, int p,
+                                                 int r, CentreArg C, NodeArg N, float *__restrict__ W,
+                                                 float *__restrict__ Wpart) {
     constexpr int NPT_MAX = NT == 64 ? 1 : MAX_NODES / 256;
     extern __shared__ float lds[];
     const int DP = D * p;
     float *wts = lds;                 // [FF_TP][DP]
     float *bj = lds + FF_TP * DP;     // [FF_TP]
-    const int64_t c = blockIdx.x;
+    const int64_t c = block_index();
+    if (c >= nchunks) return;
     const uint32_t a = chunk_box[c];
     const uint32_t ci = (uint32_t)(c - chunk_first[a]);
     const uint32_t nch = chunk_first[a + 1] - chunk_first[a];
@@ -259,9 +271,10 @@ __global__ __launch_bounds__(NT) void p2m_kernel(const float *__restrict__ Xs, c
 
 // boxes that were split into several chunks: add the partial node weights, chunk by
 // chunk in ascending order, in fp64
-__global__ __launch_bounds__(256) void p2m_reduce_kernel(const uint32_t *__restrict__ chunk_first, int r,
+__global__ __launch_bounds__(256) void p2m_reduce_kernel(const uint32_t *__restrict__ chunk_first, int64_t nb, int r,
                                                          const float *__restrict__ Wpart, float *__restrict__ W) {
-    const uint32_t a = blockIdx.x;
+    const int64_t a = block_index();
+    if (a >= nb) return;
     const uint32_t c0 = chunk_first[a], c1 = chunk_first[a + 1];
     if (c1 - c0 <= 1) return;
     __shared__ double part[4][64];
@@ -288,14 +301,15 @@ __global__ __launch_bounds__(P2M_CHUNK) void l2p_kernel(const float *__restrict_
                                                         const int32_t *__restrict__ cell,
                                                         const uint64_t *__restrict__ far_ptr,
                                                         const uint32_t *__restrict__ chunk_box,
-                                                        const uint32_t *__restrict__ chunk_first, int p, int r,
-                                                        CentreArg C, NodeArg N, const float *__restrict__ V,
-                                                        float *__restrict__ ys) {
+                                                        const uint32_t *__restrict__ chunk_first, int64_t nchunks,
+                                                        int p, int r, CentreArg C, NodeArg N,
+                                                        const float *__restrict__ V, float *__restrict__ ys) {
     extern __shared__ float lds[];
     const int DP = D * p, stride = DP + 1;
     float *Vs = lds;          // [r]
     float *wts = lds + r;     // [P2M_CHUNK][stride]
-    const int64_t c = blockIdx.x;
+    const int64_t c = block_index();
+    if (c >= nchunks) return;
     const uint32_t a = chunk_box[c];
     if (far_ptr[a + 1] == far_ptr[a]) return;  // no far partner at this depth: V_p is zero
     const uint32_t ci = (uint32_t)(c - chunk_first[a]);
@@ -334,14 +348,15 @@ __global__ __launch_bounds__(P2M_CHUNK) void l2p_kernel(const float *__restrict_
 template <int D, int NT>
 __global__ __launch_bounds__(NT) void m2l_generic_kernel(const int32_t *__restrict__ cell,
                                                          const uint64_t *__restrict__ far_ptr,
-                                                         const uint32_t *__restrict__ far_col, int p, int r,
-                                                         NodeArg N, float nc2h, const float *__restrict__ W,
+                                                         const uint32_t *__restrict__ far_col, int64_t nb, int p,
+                                                         int r, NodeArg N, float nc2h, const float *__restrict__ W,
                                                          float *__restrict__ V) {
     constexpr int NPT_MAX = NT == 64 ? 1 : MAX_NODES / 256;
     extern __shared__ float lds[];
     float *Wq = lds;        // [r]
     float *u = lds + r;     // [D][p]   2 o_d + s_k
-    const uint32_t a = blockIdx.x;
+    const int64_t a = block_index();
+    if (a >= nb) return;
     const uint64_t e0 = far_ptr[a], e1 = far_ptr[a + 1];
     if (e0 == e1) return;
     const int npt = (r + NT - 1) / NT;
@@ -399,8 +414,6 @@ __global__ __launch_bounds__(NT) void m2l_generic_kernel(const int32_t *__restri
     }
 }
 
-void build_far_tables(f3m_plan_s &, hipStream_t) {}
-
 // ------------------------------------------------------------------------------------
 template <int D>
 static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
@@ -420,9 +433,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     F3M_HIP(hipEventRecord(P.ev[8], st));
     gather_kernel<<<dim3(gn), dim3(256), 0, st>>>(b, P.perm.p, n, P.bs.p);
     F3M_HIP(hipEventRecord(P.ev[9], st));
-    p2p_kernel<D><<<dim3((unsigned)P.ntiles), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
-                                                                leaf.near_col.p, P.tile_box.p, P.tile_first.p, nc2,
-                                                                P.ys.p);
+    p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
+                                                          leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, nc2,
+                                                          P.ys.p);
     F3M_HIP(hipGetLastError());
     F3M_HIP(hipEventRecord(P.ev[10], st));
     P.far_events.resize((size_t)(P.L + 1) * 4, nullptr);
@@ -439,32 +452,35 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         {
             size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
             if (r <= 64)
-                p2m_kernel<D, 64><<<dim3((unsigned)lv.nchunks), dim3(64), sh, st>>>(
-                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, p, r, C, N, P.W.p, P.Wpart.p);
+                p2m_kernel<D, 64><<<grid_for(lv.nchunks), dim3(64), sh, st>>>(
+                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
+                    P.W.p, P.Wpart.p);
             else
-                p2m_kernel<D, 256><<<dim3((unsigned)lv.nchunks), dim3(256), sh, st>>>(
-                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, p, r, C, N, P.W.p, P.Wpart.p);
+                p2m_kernel<D, 256><<<grid_for(lv.nchunks), dim3(256), sh, st>>>(
+                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
+                    P.W.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
             if (lv.nchunks > lv.nb)
-                p2m_reduce_kernel<<<dim3((unsigned)lv.nb), dim3(256), 0, st>>>(lv.chunk_first.p, r, P.Wpart.p, P.W.p);
+                p2m_reduce_kernel<<<grid_for(lv.nb), dim3(256), 0, st>>>(lv.chunk_first.p, lv.nb, r, P.Wpart.p, P.W.p);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[1], st));
-        {
+        if (!run_m2l_tables(P, l, st)) {
             size_t sh = (size_t)(r + D * p) * sizeof(float);
             if (r <= 64)
-                m2l_generic_kernel<D, 64><<<dim3((unsigned)lv.nb), dim3(64), sh, st>>>(
-                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, p, r, N, nc2h, P.W.p, P.V.p);
+                m2l_generic_kernel<D, 64><<<grid_for(lv.nb), dim3(64), sh, st>>>(
+                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, p, r, N, nc2h, P.W.p, P.V.p);
             else
-                m2l_generic_kernel<D, 256><<<dim3((unsigned)lv.nb), dim3(256), sh, st>>>(
-                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, p, r, N, nc2h, P.W.p, P.V.p);
+                m2l_generic_kernel<D, 256><<<grid_for(lv.nb), dim3(256), sh, st>>>(
+                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, p, r, N, nc2h, P.W.p, P.V.p);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[2], st));
         {
             size_t sh = (size_t)(r + P2M_CHUNK * (D * p + 1)) * sizeof(float);
-            l2p_kernel<D><<<dim3((unsigned)lv.nchunks), dim3(P2M_CHUNK), sh, st>>>(
-                P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p, lv.chunk_box.p, lv.chunk_first.p, p, r, C, N, P.V.p, P.ys.p);
+            l2p_kernel<D><<<grid_for(lv.nchunks), dim3(P2M_CHUNK), sh, st>>>(
+                P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
+                P.V.p, P.ys.p);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[3], st));

@@ -1,0 +1,272 @@
+// Table-driven M2L, v2 = K v1 (arXiv 2202.01085, Sec. 3 "Interpolating k(x,y)", Fig. 4
+// step 2), for D = 3 with 4 nodes per dimension (r = 64 nodes per box) and the paper's far
+// rule (ratio 2).
+//
+// All boxes of a depth are congruent and the kernel depends on x - y only, so the r x r
+// matrix K_pq = k(s^p_i, s^q_j) of a far pair depends on the integer cell offset o = c_q - c_p
+// alone: o in [-3,3]^3, 343 matrices of 64 x 64 per depth.  For a target whose cell has
+// parity c (c_d = cell_d & 1) the far partners sit at o_d in [-2-c_d, 3-c_d] minus the 27
+// near offsets: 189 "slots" per parity class.  Targets of one parity class are grouped into
+// tiles of 32, and for a tile and a slot the products of 32 far pairs become ONE dense
+// contraction  V[64 x 32] += K_o[64 x 64] * W_gathered[64 x 32]  on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32), 64 MFMA instructions per slot, no atomics: a tile owns its
+// targets.  Everything else (other D, p, far ratios) takes the general kernel in kmvm.hip.
+#include <algorithm>
+#include <cmath>
+
+#include "plan.h"
+
+namespace f3m {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int M2L_R = 64;
+constexpr int M2L_NOFF = 343;
+constexpr int M2L_NSLOT = 189;
+constexpr int M2L_TILE = 32;
+constexpr int M2L_WAVES = 4;
+
+struct TileBase { uint32_t b[9]; };
+
+static dim3 grid2(int64_t count) {
+    const int64_t gx = 1 << 16;
+    if (count <= gx) return dim3((unsigned)(count > 0 ? count : 1), 1, 1);
+    return dim3((unsigned)gx, (unsigned)cdiv(count, gx), 1);
+}
+__device__ inline int64_t block_index2() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+
+// offset index of o in [-3,3]^3
+__host__ __device__ inline int off_index(int ox, int oy, int oz) { return (ox + 3) + 7 * (oy + 3) + 49 * (oz + 3); }
+
+static void make_slot_tables(std::vector<int32_t> &slot_of, std::vector<int32_t> &slot_oi) {
+    slot_of.assign(8 * M2L_NOFF, -1);
+    slot_oi.assign(8 * M2L_NSLOT, 0);
+    for (int c = 0; c < 8; ++c) {
+        int s = 0;
+        int lo[3], hi[3];
+        for (int d = 0; d < 3; ++d) {
+            int cd = (c >> d) & 1;
+            lo[d] = -2 - cd;
+            hi[d] = 3 - cd;
+        }
+        for (int oz = lo[2]; oz <= hi[2]; ++oz)
+            for (int oy = lo[1]; oy <= hi[1]; ++oy)
+                for (int ox = lo[0]; ox <= hi[0]; ++ox) {
+                    if (ox * ox + oy * oy + oz * oz < 4) continue;  // near
+                    int oi = off_index(ox, oy, oz);
+                    slot_of[c * M2L_NOFF + oi] = s;
+                    slot_oi[c * M2L_NSLOT + s] = oi;
+                    ++s;
+                }
+        if (s != M2L_NSLOT) fail(F3M_ERR_HIP, "internal: far slot count");
+    }
+}
+
+// K_o[i][j] = exp(-|delta|^2 / (2 gamma^2)), delta_d = (l/2) (2 o_d + s_{j_d} - s_{i_d}), evaluated in
+// fp64 and stored in the order the MFMA A operand is consumed:
+//   ktab[oi][g][lane][e] = K_o[ mb*32 + (lane&31) ][ (lane>>5)*32 + ks ],  g*4+e = mb*32 + ks
+struct NodeD { double s[4]; };
+__global__ __launch_bounds__(256) void ktab_kernel(float *__restrict__ ktab, NodeD nd, double c /* (l/2)^2/(2 gamma^2) */) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)M2L_NOFF * M2L_R * M2L_R) return;
+    const int oi = (int)(idx / (M2L_R * M2L_R));
+    const int rem = (int)(idx % (M2L_R * M2L_R));
+    const int g = rem / 256, lane = (rem % 256) / 4, e = rem % 4;
+    const int q = g * 4 + e, mb = q / 32, ks = q % 32;
+    const int i = mb * 32 + (lane & 31);
+    const int j = (lane >> 5) * 32 + ks;
+    const int o[3] = {oi % 7 - 3, (oi / 7) % 7 - 3, oi / 49 - 3};
+    double r2 = 0.0;
+    int ii = i, jj = j;
+    for (int d = 0; d < 3; ++d) {
+        double diff = 2.0 * (double)o[d] + nd.s[jj % 4] - nd.s[ii % 4];
+        r2 += diff * diff;
+        ii /= 4;
+        jj /= 4;
+    }
+    ktab[idx] = (float)exp(-r2 * c);
+}
+
+struct ParityIn {
+    const uint32_t *key;
+    uint32_t c;
+    __device__ uint64_t operator()(int64_t a) const { return (key[a] & 7u) == c; }
+};
+struct ParityOut {
+    uint32_t *tile_box;
+    uint32_t *gpos;
+    uint64_t base;
+    __device__ void operator()(int64_t a, uint64_t ex, uint64_t v) const {
+        if (v) {
+            tile_box[base + ex] = (uint32_t)a;
+            gpos[a] = (uint32_t)(base + ex);
+        }
+    }
+};
+
+// positional far table: thread = (tile, lane); its target's far row is spread over the slots
+__global__ __launch_bounds__(256) void fpos_kernel(const uint32_t *__restrict__ tile_box, int64_t nlanes,
+                                                   const uint32_t *__restrict__ key, const int32_t *__restrict__ cell,
+                                                   const uint64_t *__restrict__ far_ptr,
+                                                   const uint32_t *__restrict__ far_col,
+                                                   const int32_t *__restrict__ slot_of, uint32_t *__restrict__ fpos) {
+    const int64_t g = block_index2() * 256 + threadIdx.x;
+    if (g >= nlanes) return;
+    const uint32_t a = tile_box[g];
+    if (a == 0xFFFFFFFFu) return;
+    const int32_t *so = slot_of + (key[a] & 7u) * M2L_NOFF;
+    const int cx = cell[(int64_t)a * 3], cy = cell[(int64_t)a * 3 + 1], cz = cell[(int64_t)a * 3 + 2];
+    uint32_t *dst = fpos + (g >> 5) * (int64_t)(M2L_NSLOT * M2L_TILE) + (g & 31);
+    for (uint64_t e = far_ptr[a]; e < far_ptr[a + 1]; ++e) {
+        const uint32_t b = far_col[e];
+        const int ox = cell[(int64_t)b * 3] - cx, oy = cell[(int64_t)b * 3 + 1] - cy, oz = cell[(int64_t)b * 3 + 2] - cz;
+        if (ox < -3 || ox > 3 || oy < -3 || oy > 3 || oz < -3 || oz > 3) continue;  // cannot happen for ratio 2
+        const int slot = so[off_index(ox, oy, oz)];
+        if (slot >= 0) dst[(int64_t)slot * M2L_TILE] = b;
+    }
+}
+
+// One wavefront per tile of 32 same-parity targets.  Lane l: target column n = l & 31,
+// half h = l >> 5 of the contraction index.  Per slot: A = K_o (64 values per lane, operand
+// order), B = the lane's half row of W of its far partner, 64 MFMAs into two 32 x 32
+// accumulators (output nodes 0..31 and 32..63).
+__global__ __launch_bounds__(64 * M2L_WAVES) void m2l_mfma_kernel(const float *__restrict__ W, float *__restrict__ V,
+                                                                  const float *__restrict__ ktab,
+                                                                  const uint32_t *__restrict__ tile_box,
+                                                                  const uint32_t *__restrict__ fpos,
+                                                                  const int32_t *__restrict__ slot_oi, TileBase tb,
+                                                                  int64_t ntiles, int64_t nblocks8) {
+    // blocks are handed to the 8 XCDs round-robin: give each XCD a contiguous range of tiles so
+    // that neighbouring tiles (which share far partners) meet in the same L2
+    const int64_t bi = block_index2();
+    if ((bi >> 3) >= nblocks8) return;
+    const int64_t blk = (bi & 7) * nblocks8 + (bi >> 3);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t tile = blk * M2L_WAVES + wave;
+    if (tile >= ntiles) return;
+    const int n = lane & 31, h = lane >> 5;
+    int par = 0;
+#pragma unroll
+    for (int c = 1; c < 8; ++c)
+        if (tile >= (int64_t)tb.b[c]) par = c;
+    const int32_t *soi = slot_oi + par * M2L_NSLOT;
+    const uint32_t tgt = tile_box[tile * M2L_TILE + n];
+    const uint32_t *fp = fpos + tile * (int64_t)(M2L_NSLOT * M2L_TILE) + n;
+    f16v acc0 = {0.f}, acc1 = {0.f};
+#pragma unroll 1
+    for (int s = 0; s < M2L_NSLOT; ++s) {
+        const uint32_t src = fp[s * M2L_TILE];
+        const bool has = src != 0xFFFFFFFFu;
+        if (__ballot(has) == 0ull) continue;
+        const int oi = __builtin_amdgcn_readfirstlane(soi[s]);
+        const float4 *Ap = reinterpret_cast<const float4 *>(ktab + (int64_t)oi * (M2L_R * M2L_R)) + lane;
+        const float4 *Bp = reinterpret_cast<const float4 *>(W + (int64_t)(has ? src : 0u) * M2L_R + h * 32);
+        float4 A[16], B[8];
+#pragma unroll
+        for (int g = 0; g < 16; ++g) A[g] = Ap[g * 64];
+#pragma unroll
+        for (int g = 0; g < 8; ++g) B[g] = Bp[g];
+        if (!has) {
+#pragma unroll
+            for (int g = 0; g < 8; ++g) B[g] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 32; ++ks) {
+            const float4 b4 = B[ks >> 2], a0 = A[ks >> 2], a1 = A[8 + (ks >> 2)];
+            const int e = ks & 3;
+            const float bv = e == 0 ? b4.x : e == 1 ? b4.y : e == 2 ? b4.z : b4.w;
+            const float av0 = e == 0 ? a0.x : e == 1 ? a0.y : e == 2 ? a0.z : a0.w;
+            const float av1 = e == 0 ? a1.x : e == 1 ? a1.y : e == 2 ? a1.z : a1.w;
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av0, bv, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av1, bv, acc1, 0, 0, 0);
+        }
+    }
+    if (tgt != 0xFFFFFFFFu) {
+        float *dst = V + (int64_t)tgt * M2L_R;
+        // accumulator register v of lane (n,h) holds output node 8*(v/4) + 4*h + (v%4) of column n
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int row = 8 * v4 + 4 * h;
+            *reinterpret_cast<float4 *>(dst + row) = make_float4(acc0[4 * v4], acc0[4 * v4 + 1], acc0[4 * v4 + 2], acc0[4 * v4 + 3]);
+            *reinterpret_cast<float4 *>(dst + 32 + row) = make_float4(acc1[4 * v4], acc1[4 * v4 + 1], acc1[4 * v4 + 2], acc1[4 * v4 + 3]);
+        }
+    }
+}
+
+static bool tables_apply(const f3m_plan_s &P) { return P.D == 3 && P.p == 4 && P.T == 4 && !P.force_all_near; }
+
+void build_far_tables(f3m_plan_s &P, hipStream_t st) {
+    if (!tables_apply(P)) return;
+    bool any = false;
+    for (int l = 1; l <= P.L; ++l) any |= P.lev[l].far_sz > 0;
+    if (!any) return;
+    int64_t *tally = &P.bytes;
+    std::vector<int32_t> so, soi;
+    make_slot_tables(so, soi);
+    P.slot_of.alloc(so.size(), tally);
+    P.slot_oi.alloc(soi.size(), tally);
+    F3M_HIP(hipMemcpyAsync(P.slot_of.p, so.data(), so.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    F3M_HIP(hipMemcpyAsync(P.slot_oi.p, soi.data(), soi.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    F3M_HIP(hipStreamSynchronize(st));
+    NodeD nd;
+    for (int i = 0; i < 4; ++i) nd.s[i] = std::cos((double)i * M_PI / 3.0);
+    for (int l = 1; l <= P.L; ++l) {
+        f3m_level &lv = P.lev[l];
+        if (lv.far_sz == 0) continue;
+        // kernel matrices of this depth
+        const double half = 0.5 * (double)P.E / std::ldexp(1.0, l);
+        const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
+        const int64_t nk = (int64_t)M2L_NOFF * M2L_R * M2L_R;
+        lv.ktab.alloc((size_t)nk, tally);
+        ktab_kernel<<<dim3((unsigned)cdiv(nk, 256)), dim3(256), 0, st>>>(lv.ktab.p, nd, c);
+        F3M_HIP(hipGetLastError());
+        // tiles: the boxes of each parity class, in rank order, 32 per tile
+        DevBuf<uint32_t> gpos;
+        gpos.alloc((size_t)lv.nb);
+        int64_t cnt[8];
+        {
+            // sizes first (one counting scan per class), then placement
+            int64_t tiles = 0;
+            std::vector<ScanState> S(8);
+            for (uint32_t cidx = 0; cidx < 8; ++cidx) {
+                scan_prepare(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx], true, st);
+                cnt[cidx] = (int64_t)S[cidx].total;
+                lv.tile_base[cidx] = (uint32_t)tiles;
+                tiles += cdiv(cnt[cidx], M2L_TILE);
+            }
+            lv.tile_base[8] = (uint32_t)tiles;
+            lv.ntiles = tiles;
+            lv.tile_box.alloc((size_t)tiles * M2L_TILE, tally);
+            F3M_HIP(hipMemsetAsync(lv.tile_box.p, 0xFF, (size_t)tiles * M2L_TILE * sizeof(uint32_t), st));
+            for (uint32_t cidx = 0; cidx < 8; ++cidx)
+                scan_finish(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx],
+                            ParityOut{lv.tile_box.p, gpos.p, (uint64_t)lv.tile_base[cidx] * M2L_TILE}, st);
+            F3M_HIP(hipStreamSynchronize(st));
+        }
+        // far partners by (tile, slot, lane)
+        const size_t nf = (size_t)lv.ntiles * M2L_NSLOT * M2L_TILE;
+        lv.fpos.alloc(nf, tally);
+        F3M_HIP(hipMemsetAsync(lv.fpos.p, 0xFF, nf * sizeof(uint32_t), st));
+        const int64_t nlanes = lv.ntiles * M2L_TILE;
+        fpos_kernel<<<grid2(cdiv(nlanes, 256)), dim3(256), 0, st>>>(lv.tile_box.p, nlanes, lv.key.p, lv.cell.p,
+                                                                    lv.far_ptr.p, lv.far_col.p, P.slot_of.p, lv.fpos.p);
+        F3M_HIP(hipGetLastError());
+        F3M_HIP(hipStreamSynchronize(st));
+        lv.m2l_tables = true;
+    }
+}
+
+bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st) {
+    f3m_level &lv = P.lev[level];
+    if (!lv.m2l_tables) return false;
+    TileBase tb;
+    for (int c = 0; c < 9; ++c) tb.b[c] = lv.tile_base[c];
+    const int64_t nblocks = cdiv(lv.ntiles, M2L_WAVES);
+    const int64_t nblocks8 = cdiv(nblocks, 8);
+    m2l_mfma_kernel<<<grid2(nblocks8 * 8), dim3(64 * M2L_WAVES), 0, st>>>(P.W.p, P.V.p, lv.ktab.p, lv.tile_box.p,
+                                                                          lv.fpos.p, P.slot_oi.p, tb, lv.ntiles, nblocks8);
+    F3M_HIP(hipGetLastError());
+    return true;
+}
+
+}  // namespace f3m

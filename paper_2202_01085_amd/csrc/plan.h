@@ -17,11 +17,14 @@ struct f3m_level {
     int64_t nchunks = 0;
     f3m::DevBuf<uint32_t> chunk_box;    // [nchunks]
     f3m::DevBuf<uint32_t> chunk_first;  // [nb+1] first chunk of each box
-    // node-to-node kernel tables of this depth (D <= 3 fast path), see m2l
-    f3m::DevBuf<float> ktab;
-    f3m::DevBuf<uint32_t> fslot;        // positional far table of the MFMA path
+    // table-driven M2L (m2l.hip): node-to-node kernel matrices per cell offset, targets
+    // grouped by parity into tiles of 32, far sources by (tile, offset slot, lane)
+    bool m2l_tables = false;
+    f3m::DevBuf<float> ktab;            // [343][16][64][4] matrices in MFMA operand order
     int64_t ntiles = 0;
+    uint32_t tile_base[9] = {0};        // first tile of each parity class (tile_base[8] = ntiles)
     f3m::DevBuf<uint32_t> tile_box;     // [ntiles*32] target rank per tile lane (0xffffffff = padding)
+    f3m::DevBuf<uint32_t> fpos;         // [ntiles][189][32] source rank or 0xffffffff
 };
 
 struct f3m_plan_s {
@@ -45,6 +48,8 @@ struct f3m_plan_s {
     int64_t ntiles = 0;
     f3m::DevBuf<uint32_t> tile_box, tile_first;   // [ntiles], [nb_L+1]
     f3m_level lev[F3M_MAX_LEVELS + 1];
+    f3m::DevBuf<int32_t> slot_of;       // [8][343] offset index -> slot of a parity class (-1: not far)
+    f3m::DevBuf<int32_t> slot_oi;       // [8][189] slot -> offset index
 
     hipEvent_t ev[16] = {nullptr};
     std::vector<hipEvent_t> far_events;   // 4 per depth: before P2M, M2L, L2P, after L2P
@@ -67,6 +72,8 @@ void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
 void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st);
 void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
                          int64_t m, double *y64, hipStream_t st);
+// m2l.hip
 void build_far_tables(f3m_plan_s &P, hipStream_t st);
+bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st);   // false: no tables for this plan
 
 }  // namespace f3m

@@ -76,9 +76,10 @@ def lib():
         L.f3m_plan_get_boxes.argtypes = [vp, ci, vp, vp]
         L.f3m_plan_get_list.argtypes = [vp, ci, ci, vp, vp]
         L.f3m_stage_times.argtypes = [vp, ctypes.POINTER(Times)]
+        L.f3m_level_times.argtypes = [vp, ci, vp]
         for name in ("f3m_plan", "f3m_plan_ex", "f3m_kmvm", "direct_kmvm", "direct_kmvm_rows_f64", "f3m_plan_info",
                      "f3m_plan_get_perm", "f3m_plan_get_point_keys", "f3m_plan_get_boxes", "f3m_plan_get_list",
-                     "f3m_stage_times"):
+                     "f3m_stage_times", "f3m_level_times"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -120,8 +121,8 @@ class Plan:
 
     def close(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
-            lib().f3m_destroy(h)
+        if h and _lib is not None:      # _lib is already gone when the interpreter shuts down
+            _lib.f3m_destroy(h)
 
     __del__ = close
 
@@ -166,6 +167,12 @@ class Plan:
         cols = np.empty(max(sz, 1), dtype=np.uint32)
         _check(lib().f3m_plan_get_list(self._h, int(level), int(kind), _np_ptr(ptr), _np_ptr(cols)))
         return ptr, cols[:sz]
+
+    def level_times(self, level):
+        """(P2M, M2L, L2P) milliseconds of one depth in the last kmvm"""
+        out = (ctypes.c_float * 3)()
+        _check(lib().f3m_level_times(self._h, int(level), out))
+        return tuple(float(v) for v in out)
 
     def stage_times(self):
         out = Times()

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"f3m_plan", "f3m_plan_ex", "f3m_kmvm", "direct_kmvm", "direct_kmvm_rows_f64", "f3m_destroy",
             "f3m_last_error", "f3m_plan_info", "f3m_plan_get_perm", "f3m_plan_get_point_keys",
-            "f3m_plan_get_boxes", "f3m_plan_get_list", "f3m_stage_times"} <= set(names)
+            "f3m_plan_get_boxes", "f3m_plan_get_list", "f3m_stage_times", "f3m_level_times"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
