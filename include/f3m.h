@@ -69,6 +69,8 @@ typedef struct {
     int64_t max_box[F3M_MAX_LEVELS + 1];       /* largest box per depth */
     int64_t near_pairs[F3M_MAX_LEVELS + 1];    /* ordered near pairs per depth */
     int64_t far_pairs[F3M_MAX_LEVELS + 1];     /* ordered far pairs per depth */
+    int64_t near_point_pairs;                  /* point pairs evaluated exactly: sum of |p||q| over the
+                                                  near pairs of depth L */
     int64_t device_bytes;                      /* device memory held by the plan */
 } f3m_info;
 

@@ -152,6 +152,7 @@ f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
         out->near_pairs[l] = plan->lev[l].near_sz;
         out->far_pairs[l] = plan->lev[l].far_sz;
     }
+    out->near_point_pairs = plan->near_point_pairs;
     out->device_bytes = plan->bytes;
     return F3M_OK;
 }

@@ -37,6 +37,7 @@ struct f3m_plan_s {
     int leaf_max = 128, max_depth = 0, force_all_near = 0;
     int device = 0;
     int64_t bytes = 0;
+    int64_t near_point_pairs = 0;
 
     f3m::DevBuf<uint32_t> keys;   // [n] keys at depth Lq, box order
     f3m::DevBuf<uint32_t> perm;   // [n]

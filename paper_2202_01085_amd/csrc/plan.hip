@@ -354,6 +354,21 @@ __global__ __launch_bounds__(256) void chunk_box_kernel(const uint32_t *__restri
     chunk_box[c] = (uint32_t)lo;
 }
 
+// point pairs of the near field: |p| * sum of |q| over the near row of p
+struct NearPairsIn {
+    const uint32_t *start;
+    const uint64_t *near_ptr;
+    const uint32_t *near_col;
+    __device__ uint64_t operator()(int64_t a) const {
+        uint64_t s = 0;
+        for (uint64_t e = near_ptr[a]; e < near_ptr[a + 1]; ++e) {
+            uint32_t q = near_col[e];
+            s += start[q + 1] - start[q];
+        }
+        return s * (uint64_t)(start[a + 1] - start[a]);
+    }
+};
+
 static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevBuf<uint32_t> &first,
                          DevBuf<uint32_t> &cbox, int64_t &nchunks, int64_t *tally, hipStream_t st) {
     first.alloc((size_t)nb + 1, tally);
@@ -560,6 +575,12 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     P.W.alloc((size_t)max_nb * P.r, tally);
     P.V.alloc((size_t)max_nb * P.r, tally);
     P.Wpart.alloc((size_t)max_chunks * P.r, tally);
+    {
+        ScanState S;
+        const f3m_level &lf = P.lev[P.L];
+        scan_prepare(NearPairsIn{lf.start.p, lf.near_ptr.p, lf.near_col.p}, lf.nb, S, true, st);
+        P.near_point_pairs = (int64_t)S.total;
+    }
     build_far_tables(P, st);
     F3M_HIP(hipEventRecord(eb, st));
     F3M_HIP(hipStreamSynchronize(st));

@@ -38,7 +38,7 @@ class Info(ctypes.Structure):
                 ("alpha", ctypes.c_float * MAX_DIM),
                 ("nboxes", ctypes.c_int64 * (MAX_LEVELS + 1)), ("max_box", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("near_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)), ("far_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
-                ("device_bytes", ctypes.c_int64)]
+                ("near_point_pairs", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
 
 
 class Times(ctypes.Structure):
