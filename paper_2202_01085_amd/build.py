@@ -11,7 +11,9 @@ LIB = os.path.join(HERE, "libf3m.so")
 SOURCES = ["api.hip", "plan.hip", "kmvm.hip", "m2l.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are not to be generated on the test machines
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results go to ordinary VGPRs (gfx950 has a unified file): no v_accvgpr_read per value
+         "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def _hipcc():

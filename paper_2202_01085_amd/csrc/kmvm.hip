@@ -111,6 +111,115 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, c
     if (active) ys[k] = acc;
 }
 
+// ------------------------------------------------------------------------------------
+// near field with the Gram matrix on the matrix cores.  With coordinates taken relative to
+// the centre of the target box (x' = x - centre, y' = y - centre) and c = log2(e)/(2 gamma^2)
+//   k(x,y) = exp2(-c|x'|^2) * exp2( 2c x'.y' - c|y'|^2 ).
+// The second exponent for 32 sources x 32 targets is a dense contraction with inner
+// dimension D+1 (coordinates plus the norm term): (D+2)/2 v_mfma_f32_32x32x2_f32 per block,
+// leaving exp2 and one FMA per pair on the vector ALU; the factor exp2(-c|x'|^2) is applied
+// once per target at the end.  A wavefront handles a run of <= 64 targets of one leaf box as
+// two column blocks of 32.  After the MFMA lane (n,h) holds the 16 sources 8(v/4)+4h+(v%4) of
+// target column n; the two halves are added with one shuffle at the end.
+// Used only while c l^2 is small (the caller checks it): the expanded square loses
+// |x'|^2+|y'|^2 times fp32 epsilon in the exponent, which box-local coordinates keep small.
+// ------------------------------------------------------------------------------------
+typedef float f16v __attribute__((ext_vector_type(16)));
+struct __attribute__((packed, aligned(4))) float4u { float v[4]; };
+
+template <int D>
+__global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                       const uint32_t *__restrict__ start,
+                                                       const int32_t *__restrict__ cell,
+                                                       const uint64_t *__restrict__ near_ptr,
+                                                       const uint32_t *__restrict__ near_col,
+                                                       const uint32_t *__restrict__ tile_box,
+                                                       const uint32_t *__restrict__ tile_first, int64_t ntiles,
+                                                       float c, CentreArg C, float *__restrict__ ys) {
+    constexpr int KS = (D + 2) / 2;
+    const int lane = threadIdx.x & 63;
+    const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
+    if (t >= ntiles) return;
+    const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
+    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    const uint32_t kend = start[a + 1];
+    const bool two = __builtin_amdgcn_readfirstlane((int)(kend - k0)) > 32;
+    const int nn = lane & 31, kk = lane >> 5;
+    float ctr[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) ctr[d] = (float)(C.alpha[d] + ((double)cell[(int64_t)a * D + d] + 0.5) * C.edge);
+
+    // B operands: the targets of the two column blocks
+    float Bop[2][KS], ni[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const uint32_t kt = k0 + cb * 32 + nn;
+        const bool valid = kt < kend;
+        float xp[2 * KS];
+        float s = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            xp[d] = valid ? Xs[(int64_t)kt * D + d] - ctr[d] : 0.f;
+            s = fmaf(xp[d], xp[d], s);
+        }
+        xp[D] = 1.f;
+        if (D + 1 < 2 * KS) xp[D + 1] = 0.f;
+        ni[cb] = -c * s;
+#pragma unroll
+        for (int st = 0; st < KS; ++st) Bop[cb][st] = kk ? xp[2 * st + 1] : xp[2 * st];
+    }
+    float acc0 = 0.f, acc1 = 0.f;
+    const float c2 = 2.f * c;
+    const uint64_t e1 = near_ptr[a + 1];
+    for (uint64_t e = near_ptr[a]; e < e1; ++e) {
+        const uint32_t q = near_col[e];
+        const uint32_t je = start[q + 1];
+        for (uint32_t jb = start[q]; jb < je; jb += 32) {
+            // A operand: source jb + nn, scaled.  Rows beyond the box read the points that
+            // follow (or the zero padding behind the last point) and get a norm term of -1e30,
+            // so that their kernel value is exp2(-huge) = 0 whatever their right-hand side is.
+            const uint32_t j = jb + nn;
+            float yp[2 * KS];
+            float s = 0.f;
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                float v = Xs[(int64_t)j * D + d] - ctr[d];
+                s = fmaf(v, v, s);
+                yp[d] = c2 * v;
+            }
+            yp[D] = j < je ? -c * s : -1.0e30f;
+            if (D + 1 < 2 * KS) yp[D + 1] = 0.f;
+            // right-hand sides of the 16 sources this lane sees after the MFMA
+            float bv[16];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const float4u tt = *reinterpret_cast<const float4u *>(bs + jb + 8 * q4 + 4 * kk);
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) bv[4 * q4 + e4] = tt.v[e4];
+            }
+            f16v c0 = {0.f};
+#pragma unroll
+            for (int st = 0; st < KS; ++st)
+                c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(kk ? yp[2 * st + 1] : yp[2 * st], Bop[0][st], c0, 0, 0, 0);
+            if (two) {
+                f16v c1 = {0.f};
+#pragma unroll
+                for (int st = 0; st < KS; ++st)
+                    c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(kk ? yp[2 * st + 1] : yp[2 * st], Bop[1][st], c1, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bv[v], acc1);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bv[v], acc0);
+        }
+    }
+    acc0 += __shfl_xor(acc0, 32, 64);
+    acc1 += __shfl_xor(acc1, 32, 64);
+    const float res = kk ? __builtin_amdgcn_exp2f(ni[1]) * acc1 : __builtin_amdgcn_exp2f(ni[0]) * acc0;
+    const uint32_t kt = k0 + kk * 32 + nn;
+    if (kt < kend) ys[kt] = res;
+}
+
 // exact product, all pairs (Sec. 2, KeOps paragraph): lane = target, sources wave-uniform
 template <int D>
 __global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X, const float *__restrict__ b,
@@ -433,9 +542,21 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     F3M_HIP(hipEventRecord(P.ev[8], st));
     gather_kernel<<<dim3(gn), dim3(256), 0, st>>>(b, P.perm.p, n, P.bs.p);
     F3M_HIP(hipEventRecord(P.ev[9], st));
-    p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
-                                                          leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, nc2,
-                                                          P.ys.p);
+    {
+        // c l^2 bounds the magnitude of the expanded exponent terms in box-local coordinates
+        // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
+        const CentreArg CL = make_centre(P, P.L);
+        const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
+        const bool gram = c * CL.edge * CL.edge * (double)D <= 6.0;
+        if (gram)
+            p2p_mfma_kernel<D><<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, st>>>(
+                P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
+                P.tile_first.p, P.ntiles, (float)c, CL, P.ys.p);
+        else
+            p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
+                                                                  leaf.near_col.p, P.tile_box.p, P.tile_first.p,
+                                                                  P.ntiles, nc2, P.ys.p);
+    }
     F3M_HIP(hipGetLastError());
     F3M_HIP(hipEventRecord(P.ev[10], st));
     P.far_events.resize((size_t)(P.L + 1) * 4, nullptr);

@@ -62,6 +62,7 @@ struct f3m_plan_s {
 namespace f3m {
 
 constexpr int P2M_CHUNK = 256;
+constexpr int PAD_POINTS = 64;   // zero padding behind Xs and bs
 constexpr int MAX_NODES = 4096;
 
 int quant_depth(int D);

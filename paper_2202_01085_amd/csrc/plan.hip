@@ -448,7 +448,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         }
     }
     F3M_HIP(hipEventRecord(P.ev[2], st));
-    P.Xs.alloc((size_t)n * D, tally);
+    // 64 zero points of padding after the last point: kernels may read whole 32-point blocks
+    P.Xs.alloc(((size_t)n + PAD_POINTS) * D, tally);
+    F3M_HIP(hipMemsetAsync(P.Xs.p + (size_t)n * D, 0, (size_t)PAD_POINTS * D * sizeof(float), st));
     gather_rows_kernel<D><<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(X, P.perm.p, n, P.Xs.p);
     F3M_HIP(hipGetLastError());
     F3M_HIP(hipEventRecord(P.ev[3], st));
@@ -570,7 +572,8 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         max_chunks = std::max(max_chunks, lv.nchunks);
     }
     build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
-    P.bs.alloc((size_t)n, tally);
+    P.bs.alloc((size_t)n + PAD_POINTS, tally);
+    F3M_HIP(hipMemsetAsync(P.bs.p + n, 0, (size_t)PAD_POINTS * sizeof(float), st));
     P.ys.alloc((size_t)n, tally);
     P.W.alloc((size_t)max_nb * P.r, tally);
     P.V.alloc((size_t)max_nb * P.r, tally);
