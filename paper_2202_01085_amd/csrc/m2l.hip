@@ -24,7 +24,7 @@ constexpr int M2L_R = 64;
 constexpr int M2L_NOFF = 343;
 constexpr int M2L_NSLOT = 189;
 constexpr int M2L_TILE = 32;
-constexpr int M2L_WAVES = 4;
+constexpr int M2L_GROUP = 4;   // tiles handled by one wavefront
 
 struct TileBase { uint32_t b[9]; };
 
@@ -126,71 +126,93 @@ __global__ __launch_bounds__(256) void fpos_kernel(const uint32_t *__restrict__ 
     }
 }
 
-// One wavefront per tile of 32 same-parity targets.  Lane l: target column n = l & 31,
-// half h = l >> 5 of the contraction index.  Per slot: A = K_o (64 values per lane, operand
-// order), B = the lane's half row of W of its far partner, 64 MFMAs into two 32 x 32
-// accumulators (output nodes 0..31 and 32..63).
-__global__ __launch_bounds__(64 * M2L_WAVES) void m2l_mfma_kernel(const float *__restrict__ W, float *__restrict__ V,
-                                                                  const float *__restrict__ ktab,
-                                                                  const uint32_t *__restrict__ tile_box,
-                                                                  const uint32_t *__restrict__ fpos,
-                                                                  const int32_t *__restrict__ slot_oi, TileBase tb,
-                                                                  int64_t ntiles, int64_t nblocks8) {
-    // blocks are handed to the 8 XCDs round-robin: give each XCD a contiguous range of tiles so
-    // that neighbouring tiles (which share far partners) meet in the same L2
-    const int64_t bi = block_index2();
-    if ((bi >> 3) >= nblocks8) return;
-    const int64_t blk = (bi & 7) * nblocks8 + (bi >> 3);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t tile = blk * M2L_WAVES + wave;
-    if (tile >= ntiles) return;
-    const int n = lane & 31, h = lane >> 5;
-    int par = 0;
+// One wavefront per group of M2L_GROUP = 4 tiles (128 same-parity targets); no LDS, no
+// barrier, so wavefronts drift apart and the matrix pipe of a SIMD always finds one of its
+// two resident waves with operands ready.  Lane l: target column n = l & 31, half h = l >> 5
+// of the contraction index.  Per slot the wave loads K_o once (64 values per lane, already in
+// operand order: 16 contiguous 1 KB loads) and keeps it in registers for the four tiles;
+// per tile B = the lane's half row of W of its far partner and 64 MFMAs go into that tile's
+// two 32 x 32 accumulators (output nodes 0..31 and 32..63).
+__device__ inline void m2l_tile(const float *__restrict__ W, uint32_t src, int h, const float4 (&A)[16], f16v &acc0,
+                                f16v &acc1) {
+    const bool has = src != 0xFFFFFFFFu;
+    if (__ballot(has) == 0ull) return;
+    const float4 *Bp = reinterpret_cast<const float4 *>(W + (int64_t)(has ? src : 0u) * M2L_R + h * 32);
+    float4 B[8];
 #pragma unroll
-    for (int c = 1; c < 8; ++c)
-        if (tile >= (int64_t)tb.b[c]) par = c;
+    for (int g = 0; g < 8; ++g) B[g] = has ? Bp[g] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int ks = 0; ks < 32; ++ks) {
+        const float4 b4 = B[ks >> 2], a0 = A[ks >> 2], a1 = A[8 + (ks >> 2)];
+        const int e = ks & 3;
+        const float bv = e == 0 ? b4.x : e == 1 ? b4.y : e == 2 ? b4.z : b4.w;
+        const float av0 = e == 0 ? a0.x : e == 1 ? a0.y : e == 2 ? a0.z : a0.w;
+        const float av1 = e == 0 ? a1.x : e == 1 ? a1.y : e == 2 ? a1.z : a1.w;
+        acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av0, bv, acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av1, bv, acc1, 0, 0, 0);
+    }
+}
+
+__device__ inline void m2l_store(float *__restrict__ V, uint32_t tgt, int h, const f16v &acc0, const f16v &acc1) {
+    if (tgt == 0xFFFFFFFFu) return;
+    float *dst = V + (int64_t)tgt * M2L_R;
+    // accumulator register v of lane (n,h) holds output node 8*(v/4) + 4*h + (v%4) of column n
+#pragma unroll
+    for (int v4 = 0; v4 < 4; ++v4) {
+        const int row = 8 * v4 + 4 * h;
+        *reinterpret_cast<float4 *>(dst + row) = make_float4(acc0[4 * v4], acc0[4 * v4 + 1], acc0[4 * v4 + 2], acc0[4 * v4 + 3]);
+        *reinterpret_cast<float4 *>(dst + 32 + row) = make_float4(acc1[4 * v4], acc1[4 * v4 + 1], acc1[4 * v4 + 2], acc1[4 * v4 + 3]);
+    }
+}
+
+__global__ __launch_bounds__(64) void m2l_mfma_kernel(const float *__restrict__ W, float *__restrict__ V,
+                                                      const float *__restrict__ ktab,
+                                                      const uint32_t *__restrict__ tile_box,
+                                                      const uint32_t *__restrict__ fpos,
+                                                      const int32_t *__restrict__ slot_oi, TileBase tb, int64_t ngroups) {
+    // Virtual block v = 8 * group + class: the eight parity classes of one group of 4 x 256
+    // consecutive boxes run back to back, so that the waves in flight share their far
+    // partners in L2; hardware blocks go to the 8 XCDs round-robin, so XCD x takes the
+    // contiguous range v in [x * ngroups, (x+1) * ngroups).
+    const int64_t bi = block_index2();
+    if ((bi >> 3) >= ngroups) return;
+    const int64_t v = (bi & 7) * ngroups + (bi >> 3);
+    const int par = (int)(v & 7);
+    const int64_t tile0 = (int64_t)tb.b[par] + (v >> 3) * M2L_GROUP;   // classes hold whole groups of tiles
+    if (tile0 >= (int64_t)tb.b[par + 1]) return;
+    const int lane = threadIdx.x;
+    const int n = lane & 31, h = lane >> 5;
     const int32_t *soi = slot_oi + par * M2L_NSLOT;
-    const uint32_t tgt = tile_box[tile * M2L_TILE + n];
-    const uint32_t *fp = fpos + tile * (int64_t)(M2L_NSLOT * M2L_TILE) + n;
-    f16v acc0 = {0.f}, acc1 = {0.f};
+    const float4 *ktab4 = reinterpret_cast<const float4 *>(ktab);
+    const uint32_t *fp = fpos + tile0 * (int64_t)(M2L_NSLOT * M2L_TILE) + n;
+    f16v a00 = {0.f}, a01 = {0.f}, a10 = {0.f}, a11 = {0.f}, a20 = {0.f}, a21 = {0.f}, a30 = {0.f}, a31 = {0.f};
+    // far partners of slot 0; those of slot s+1 are fetched while slot s is multiplied
+    uint32_t src[M2L_GROUP];
+#pragma unroll
+    for (int t = 0; t < M2L_GROUP; ++t) src[t] = fp[(int64_t)t * (M2L_NSLOT * M2L_TILE)];
 #pragma unroll 1
     for (int s = 0; s < M2L_NSLOT; ++s) {
-        const uint32_t src = fp[s * M2L_TILE];
-        const bool has = src != 0xFFFFFFFFu;
-        if (__ballot(has) == 0ull) continue;
         const int oi = __builtin_amdgcn_readfirstlane(soi[s]);
-        const float4 *Ap = reinterpret_cast<const float4 *>(ktab + (int64_t)oi * (M2L_R * M2L_R)) + lane;
-        const float4 *Bp = reinterpret_cast<const float4 *>(W + (int64_t)(has ? src : 0u) * M2L_R + h * 32);
-        float4 A[16], B[8];
+        uint32_t nxt[M2L_GROUP];
+        const int sn = s + 1 < M2L_NSLOT ? s + 1 : s;
+#pragma unroll
+        for (int t = 0; t < M2L_GROUP; ++t) nxt[t] = fp[(int64_t)t * (M2L_NSLOT * M2L_TILE) + sn * M2L_TILE];
+        const float4 *Ap = ktab4 + (int64_t)oi * (M2L_R * M2L_R / 4) + lane;
+        float4 A[16];
 #pragma unroll
         for (int g = 0; g < 16; ++g) A[g] = Ap[g * 64];
+        m2l_tile(W, src[0], h, A, a00, a01);
+        m2l_tile(W, src[1], h, A, a10, a11);
+        m2l_tile(W, src[2], h, A, a20, a21);
+        m2l_tile(W, src[3], h, A, a30, a31);
 #pragma unroll
-        for (int g = 0; g < 8; ++g) B[g] = Bp[g];
-        if (!has) {
-#pragma unroll
-            for (int g = 0; g < 8; ++g) B[g] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 32; ++ks) {
-            const float4 b4 = B[ks >> 2], a0 = A[ks >> 2], a1 = A[8 + (ks >> 2)];
-            const int e = ks & 3;
-            const float bv = e == 0 ? b4.x : e == 1 ? b4.y : e == 2 ? b4.z : b4.w;
-            const float av0 = e == 0 ? a0.x : e == 1 ? a0.y : e == 2 ? a0.z : a0.w;
-            const float av1 = e == 0 ? a1.x : e == 1 ? a1.y : e == 2 ? a1.z : a1.w;
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(av0, bv, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(av1, bv, acc1, 0, 0, 0);
-        }
+        for (int t = 0; t < M2L_GROUP; ++t) src[t] = nxt[t];
     }
-    if (tgt != 0xFFFFFFFFu) {
-        float *dst = V + (int64_t)tgt * M2L_R;
-        // accumulator register v of lane (n,h) holds output node 8*(v/4) + 4*h + (v%4) of column n
-#pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            const int row = 8 * v4 + 4 * h;
-            *reinterpret_cast<float4 *>(dst + row) = make_float4(acc0[4 * v4], acc0[4 * v4 + 1], acc0[4 * v4 + 2], acc0[4 * v4 + 3]);
-            *reinterpret_cast<float4 *>(dst + 32 + row) = make_float4(acc1[4 * v4], acc1[4 * v4 + 1], acc1[4 * v4 + 2], acc1[4 * v4 + 3]);
-        }
-    }
+    const uint32_t *tb4 = tile_box + tile0 * M2L_TILE + n;
+    m2l_store(V, tb4[0 * M2L_TILE], h, a00, a01);
+    m2l_store(V, tb4[1 * M2L_TILE], h, a10, a11);
+    m2l_store(V, tb4[2 * M2L_TILE], h, a20, a21);
+    m2l_store(V, tb4[3 * M2L_TILE], h, a30, a31);
 }
 
 static bool tables_apply(const f3m_plan_s &P) { return P.D == 3 && P.p == 4 && P.T == 4 && !P.force_all_near; }
@@ -232,7 +254,7 @@ void build_far_tables(f3m_plan_s &P, hipStream_t st) {
                 scan_prepare(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx], true, st);
                 cnt[cidx] = (int64_t)S[cidx].total;
                 lv.tile_base[cidx] = (uint32_t)tiles;
-                tiles += cdiv(cnt[cidx], M2L_TILE);
+                tiles += cdiv(cdiv(cnt[cidx], M2L_TILE), M2L_GROUP) * M2L_GROUP;   // whole groups per class
             }
             lv.tile_base[8] = (uint32_t)tiles;
             lv.ntiles = tiles;
@@ -261,10 +283,10 @@ bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st) {
     if (!lv.m2l_tables) return false;
     TileBase tb;
     for (int c = 0; c < 9; ++c) tb.b[c] = lv.tile_base[c];
-    const int64_t nblocks = cdiv(lv.ntiles, M2L_WAVES);
-    const int64_t nblocks8 = cdiv(nblocks, 8);
-    m2l_mfma_kernel<<<grid2(nblocks8 * 8), dim3(64 * M2L_WAVES), 0, st>>>(P.W.p, P.V.p, lv.ktab.p, lv.tile_box.p,
-                                                                          lv.fpos.p, P.slot_oi.p, tb, lv.ntiles, nblocks8);
+    int64_t ngroups = 0;   // blocks of the largest class
+    for (int c = 0; c < 8; ++c) ngroups = std::max<int64_t>(ngroups, (lv.tile_base[c + 1] - lv.tile_base[c]) / M2L_GROUP);
+    m2l_mfma_kernel<<<grid2(ngroups * 8), dim3(64), 0, st>>>(P.W.p, P.V.p, lv.ktab.p, lv.tile_box.p,
+                                                                         lv.fpos.p, P.slot_oi.p, tb, ngroups);
     F3M_HIP(hipGetLastError());
     return true;
 }
