@@ -449,6 +449,130 @@ __global__ __launch_bounds__(P2M_CHUNK) void l2p_kernel(const float *__restrict_
 }
 
 // ------------------------------------------------------------------------------------
+// P2M and L2P for D = 3 with 4 nodes per dimension (r = 64 = one wavefront): one wave per
+// chunk, one lane per POINT.  The nodes are {1, 1/2, -1/2, -1}; the product-form basis of one
+// coordinate costs 4 subtractions and 10 multiplications.
+//   P2M: every lane keeps all 64 node sums of its own points in registers (64 FMAs per point
+//        after 20 multiplications for the partial products), and the 64 x 64 lane-by-node
+//        array is summed over lanes once per chunk through LDS (lane i ends up with node i).
+//   L2P: V of the box is wave-uniform (scalar operands); the tensor contraction is nested:
+//        64 + 16 + 4 FMAs per point.
+// ------------------------------------------------------------------------------------
+__device__ inline void lagrange4(float t, float (&L)[4]) {
+    const float d0 = t - 1.f, d1 = t - 0.5f, d2 = t + 0.5f, d3 = t + 1.f;
+    const float p01 = d0 * d1, p23 = d2 * d3;
+    L[0] = d1 * p23 * (1.f / 1.5f);
+    L[1] = d0 * p23 * (-1.f / 0.75f);
+    L[2] = p01 * d3 * (1.f / 0.75f);
+    L[3] = p01 * d2 * (-1.f / 1.5f);
+}
+
+__device__ inline void weights34(const float *__restrict__ x, const double (&ctr)[3], double inv_half, float (&Lx)[4],
+                                 float (&Ly)[4], float (&Lz)[4]) {
+    lagrange4((float)(((double)x[0] - ctr[0]) * inv_half), Lx);
+    lagrange4((float)(((double)x[1] - ctr[1]) * inv_half), Ly);
+    lagrange4((float)(((double)x[2] - ctr[2]) * inv_half), Lz);
+}
+
+constexpr int TR_STRIDE = 68;  // floats per lane row in the LDS transpose (16-byte aligned, bank-shifted)
+
+__global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                   const uint32_t *__restrict__ start, const int32_t *__restrict__ cell,
+                                                   const uint32_t *__restrict__ chunk_box,
+                                                   const uint32_t *__restrict__ chunk_first, int64_t nchunks, CentreArg C,
+                                                   float *__restrict__ W, float *__restrict__ Wpart) {
+    __shared__ float tr[64 * TR_STRIDE];
+    const int64_t c = block_index();
+    if (c >= nchunks) return;
+    const int lane = threadIdx.x;
+    const uint32_t a = __builtin_amdgcn_readfirstlane(chunk_box[c]);
+    const uint32_t ci = (uint32_t)(c - chunk_first[a]);
+    const uint32_t nch = chunk_first[a + 1] - chunk_first[a];
+    const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
+    const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
+    double ctr[3];
+#pragma unroll
+    for (int d = 0; d < 3; ++d) ctr[d] = C.alpha[d] + ((double)cell[(int64_t)a * 3 + d] + 0.5) * C.edge;
+    float acc[64];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = 0.f;
+    for (uint32_t kb = k0; kb < k1; kb += 64) {
+        const uint32_t k = kb + lane;
+        if (k < k1) {
+            float Lx[4], Ly[4], Lz[4];
+            weights34(Xs + (int64_t)k * 3, ctr, C.inv_half, Lx, Ly, Lz);
+            const float bb = bs[k];
+#pragma unroll
+            for (int i3 = 0; i3 < 4; ++i3) {
+                const float zb = Lz[i3] * bb;
+#pragma unroll
+                for (int i2 = 0; i2 < 4; ++i2) {
+                    const float yz = Ly[i2] * zb;
+#pragma unroll
+                    for (int i1 = 0; i1 < 4; ++i1) acc[i1 + 4 * i2 + 16 * i3] = fmaf(Lx[i1], yz, acc[i1 + 4 * i2 + 16 * i3]);
+                }
+            }
+        }
+    }
+    // sum over lanes: lane l writes its row, lane i adds column i
+#pragma unroll
+    for (int g = 0; g < 16; ++g)
+        *reinterpret_cast<float4 *>(&tr[lane * TR_STRIDE + 4 * g]) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
+    __syncthreads();
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+    for (int row = 0; row < 64; row += 4) {
+        s0 += tr[(row + 0) * TR_STRIDE + lane];
+        s1 += tr[(row + 1) * TR_STRIDE + lane];
+        s2 += tr[(row + 2) * TR_STRIDE + lane];
+        s3 += tr[(row + 3) * TR_STRIDE + lane];
+    }
+    float *dst = nch == 1 ? W + (int64_t)a * 64 : Wpart + c * 64;
+    dst[lane] = (s0 + s1) + (s2 + s3);
+}
+
+__global__ __launch_bounds__(64) void l2p34_kernel(const float *__restrict__ Xs, const uint32_t *__restrict__ start,
+                                                   const int32_t *__restrict__ cell,
+                                                   const uint64_t *__restrict__ far_ptr,
+                                                   const uint32_t *__restrict__ chunk_box,
+                                                   const uint32_t *__restrict__ chunk_first, int64_t nchunks, CentreArg C,
+                                                   const float *__restrict__ V, float *__restrict__ ys) {
+    const int64_t c = block_index();
+    if (c >= nchunks) return;
+    const int lane = threadIdx.x;
+    const uint32_t a = __builtin_amdgcn_readfirstlane(chunk_box[c]);
+    if (far_ptr[a + 1] == far_ptr[a]) return;  // no far partner at this depth: V_p is zero
+    const uint32_t ci = (uint32_t)(c - chunk_first[a]);
+    const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
+    const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
+    double ctr[3];
+#pragma unroll
+    for (int d = 0; d < 3; ++d) ctr[d] = C.alpha[d] + ((double)cell[(int64_t)a * 3 + d] + 0.5) * C.edge;
+    const float *Vp = V + (int64_t)a * 64;  // wave-uniform
+    for (uint32_t kb = k0; kb < k1; kb += 64) {
+        const uint32_t k = kb + lane;
+        if (k < k1) {
+            float Lx[4], Ly[4], Lz[4];
+            weights34(Xs + (int64_t)k * 3, ctr, C.inv_half, Lx, Ly, Lz);
+            float y = 0.f;
+#pragma unroll
+            for (int i3 = 0; i3 < 4; ++i3) {
+                float sy = 0.f;
+#pragma unroll
+                for (int i2 = 0; i2 < 4; ++i2) {
+                    float sx = 0.f;
+#pragma unroll
+                    for (int i1 = 0; i1 < 4; ++i1) sx = fmaf(Lx[i1], Vp[i1 + 4 * i2 + 16 * i3], sx);
+                    sy = fmaf(Ly[i2], sx, sy);
+                }
+                y = fmaf(Lz[i3], sy, y);
+            }
+            ys[k] += y;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // M2L, v2 = K v1 (Fig. 4 step 2), general form: V_p[i] = sum_{q in far(p)} sum_j
 // k(s^p_i, s^q_j) W_q[j] with the kernel evaluated on the fly.  In units of half a box
 // edge the node distance along d is 2 o_d + s_{j_d} - s_{i_d}, o = integer cell offset.
@@ -572,7 +696,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         F3M_HIP(hipEventRecord(ev[0], st));
         {
             size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
-            if (r <= 64)
+            if (D == 3 && p == 4)
+                p2m34_kernel<<<grid_for(lv.nchunks), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, lv.start.p, lv.cell.p,
+                                                                      lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, C,
+                                                                      P.W.p, P.Wpart.p);
+            else if (r <= 64)
                 p2m_kernel<D, 64><<<grid_for(lv.nchunks), dim3(64), sh, st>>>(
                     P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
                     P.W.p, P.Wpart.p);
@@ -599,9 +727,14 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         F3M_HIP(hipEventRecord(ev[2], st));
         {
             size_t sh = (size_t)(r + P2M_CHUNK * (D * p + 1)) * sizeof(float);
-            l2p_kernel<D><<<grid_for(lv.nchunks), dim3(P2M_CHUNK), sh, st>>>(
-                P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
-                P.V.p, P.ys.p);
+            if (D == 3 && p == 4)
+                l2p34_kernel<<<grid_for(lv.nchunks), dim3(64), 0, st>>>(P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p,
+                                                                      lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, C,
+                                                                      P.V.p, P.ys.p);
+            else
+                l2p_kernel<D><<<grid_for(lv.nchunks), dim3(P2M_CHUNK), sh, st>>>(
+                    P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
+                    P.V.p, P.ys.p);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[3], st));
