@@ -21,9 +21,6 @@ namespace f3m {
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int M2L_R = 64;
-constexpr int M2L_NOFF = 343;
-constexpr int M2L_NSLOT = 189;
-constexpr int M2L_TILE = 32;
 constexpr int M2L_GROUP = 4;   // tiles handled by one wavefront
 
 struct TileBase { uint32_t b[9]; };
@@ -34,9 +31,6 @@ static dim3 grid2(int64_t count) {
     return dim3((unsigned)gx, (unsigned)cdiv(count, gx), 1);
 }
 __device__ inline int64_t block_index2() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
-
-// offset index of o in [-3,3]^3
-__host__ __device__ inline int off_index(int ox, int oy, int oz) { return (ox + 3) + 7 * (oy + 3) + 49 * (oz + 3); }
 
 static void make_slot_tables(std::vector<int32_t> &slot_of, std::vector<int32_t> &slot_oi) {
     slot_of.assign(8 * M2L_NOFF, -1);
@@ -104,26 +98,33 @@ struct ParityOut {
     }
 };
 
-// positional far table: thread = (tile, lane); its target's far row is spread over the slots
-__global__ __launch_bounds__(256) void fpos_kernel(const uint32_t *__restrict__ tile_box, int64_t nlanes,
-                                                   const uint32_t *__restrict__ key, const int32_t *__restrict__ cell,
-                                                   const uint64_t *__restrict__ far_ptr,
-                                                   const uint32_t *__restrict__ far_col,
-                                                   const int32_t *__restrict__ slot_of, uint32_t *__restrict__ fpos) {
+// far row of a box on a table depth, back in CSR form (ascending ranks): introspection only
+__global__ __launch_bounds__(64) void far_rows_kernel(const uint32_t *__restrict__ gpos, int64_t nb,
+                                                      const uint64_t *__restrict__ far_ptr,
+                                                      const uint32_t *__restrict__ fpos, uint32_t *__restrict__ cols) {
+    const int64_t a = block_index2() * 64 + threadIdx.x;
+    if (a >= nb) return;
+    const uint32_t g = gpos[a];
+    const uint32_t *row = fpos + (int64_t)(g >> 5) * (M2L_NSLOT * M2L_TILE) + (g & 31);
+    uint32_t *out = cols + far_ptr[a];
+    const int cnt = (int)(far_ptr[a + 1] - far_ptr[a]);
+    // insertion sort of the present partners into the output row
+    int m = 0;
+    for (int s = 0; s < M2L_NSLOT; ++s) {
+        const uint32_t b = row[(int64_t)s * M2L_TILE];
+        if (b == 0xFFFFFFFFu || m >= cnt) continue;
+        int k = m++;
+        while (k > 0 && out[k - 1] > b) { out[k] = out[k - 1]; --k; }
+        out[k] = b;
+    }
+}
+
+__global__ __launch_bounds__(256) void gpos_kernel(const uint32_t *__restrict__ tile_box, int64_t nlanes,
+                                                   uint32_t *__restrict__ gpos) {
     const int64_t g = block_index2() * 256 + threadIdx.x;
     if (g >= nlanes) return;
     const uint32_t a = tile_box[g];
-    if (a == 0xFFFFFFFFu) return;
-    const int32_t *so = slot_of + (key[a] & 7u) * M2L_NOFF;
-    const int cx = cell[(int64_t)a * 3], cy = cell[(int64_t)a * 3 + 1], cz = cell[(int64_t)a * 3 + 2];
-    uint32_t *dst = fpos + (g >> 5) * (int64_t)(M2L_NSLOT * M2L_TILE) + (g & 31);
-    for (uint64_t e = far_ptr[a]; e < far_ptr[a + 1]; ++e) {
-        const uint32_t b = far_col[e];
-        const int ox = cell[(int64_t)b * 3] - cx, oy = cell[(int64_t)b * 3 + 1] - cy, oz = cell[(int64_t)b * 3 + 2] - cz;
-        if (ox < -3 || ox > 3 || oy < -3 || oy > 3 || oz < -3 || oz > 3) continue;  // cannot happen for ratio 2
-        const int slot = so[off_index(ox, oy, oz)];
-        if (slot >= 0) dst[(int64_t)slot * M2L_TILE] = b;
-    }
+    if (a != 0xFFFFFFFFu) gpos[a] = (uint32_t)g;
 }
 
 // One wavefront per group of M2L_GROUP = 4 tiles (128 same-parity targets); no LDS, no
@@ -215,67 +216,64 @@ __global__ __launch_bounds__(64) void m2l_mfma_kernel(const float *__restrict__ 
     m2l_store(V, tb4[3 * M2L_TILE], h, a30, a31);
 }
 
-static bool tables_apply(const f3m_plan_s &P) { return P.D == 3 && P.p == 4 && P.T == 4 && !P.force_all_near; }
+bool m2l_tables_apply(const f3m_plan_s &P) { return P.D == 3 && P.p == 4 && P.T == 4 && !P.force_all_near; }
 
-void build_far_tables(f3m_plan_s &P, hipStream_t st) {
-    if (!tables_apply(P)) return;
-    bool any = false;
-    for (int l = 1; l <= P.L; ++l) any |= P.lev[l].far_sz > 0;
-    if (!any) return;
-    int64_t *tally = &P.bytes;
+void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st) {
     std::vector<int32_t> so, soi;
     make_slot_tables(so, soi);
-    P.slot_of.alloc(so.size(), tally);
-    P.slot_oi.alloc(soi.size(), tally);
+    P.slot_of.alloc(so.size(), &P.bytes);
+    P.slot_oi.alloc(soi.size(), &P.bytes);
     F3M_HIP(hipMemcpyAsync(P.slot_of.p, so.data(), so.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
     F3M_HIP(hipMemcpyAsync(P.slot_oi.p, soi.data(), soi.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
     F3M_HIP(hipStreamSynchronize(st));
+}
+
+// Everything the table-driven M2L of one depth needs except the far partners themselves,
+// which the list kernel writes into fpos afterwards.
+void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st) {
+    f3m_level &lv = P.lev[level];
+    int64_t *tally = &P.bytes;
     NodeD nd;
     for (int i = 0; i < 4; ++i) nd.s[i] = std::cos((double)i * M_PI / 3.0);
-    for (int l = 1; l <= P.L; ++l) {
-        f3m_level &lv = P.lev[l];
-        if (lv.far_sz == 0) continue;
-        // kernel matrices of this depth
-        const double half = 0.5 * (double)P.E / std::ldexp(1.0, l);
-        const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
-        const int64_t nk = (int64_t)M2L_NOFF * M2L_R * M2L_R;
-        lv.ktab.alloc((size_t)nk, tally);
-        ktab_kernel<<<dim3((unsigned)cdiv(nk, 256)), dim3(256), 0, st>>>(lv.ktab.p, nd, c);
-        F3M_HIP(hipGetLastError());
-        // tiles: the boxes of each parity class, in rank order, 32 per tile
-        DevBuf<uint32_t> gpos;
-        gpos.alloc((size_t)lv.nb);
-        int64_t cnt[8];
-        {
-            // sizes first (one counting scan per class), then placement
-            int64_t tiles = 0;
-            std::vector<ScanState> S(8);
-            for (uint32_t cidx = 0; cidx < 8; ++cidx) {
-                scan_prepare(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx], true, st);
-                cnt[cidx] = (int64_t)S[cidx].total;
-                lv.tile_base[cidx] = (uint32_t)tiles;
-                tiles += cdiv(cdiv(cnt[cidx], M2L_TILE), M2L_GROUP) * M2L_GROUP;   // whole groups per class
-            }
-            lv.tile_base[8] = (uint32_t)tiles;
-            lv.ntiles = tiles;
-            lv.tile_box.alloc((size_t)tiles * M2L_TILE, tally);
-            F3M_HIP(hipMemsetAsync(lv.tile_box.p, 0xFF, (size_t)tiles * M2L_TILE * sizeof(uint32_t), st));
-            for (uint32_t cidx = 0; cidx < 8; ++cidx)
-                scan_finish(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx],
-                            ParityOut{lv.tile_box.p, gpos.p, (uint64_t)lv.tile_base[cidx] * M2L_TILE}, st);
-            F3M_HIP(hipStreamSynchronize(st));
-        }
-        // far partners by (tile, slot, lane)
-        const size_t nf = (size_t)lv.ntiles * M2L_NSLOT * M2L_TILE;
-        lv.fpos.alloc(nf, tally);
-        F3M_HIP(hipMemsetAsync(lv.fpos.p, 0xFF, nf * sizeof(uint32_t), st));
-        const int64_t nlanes = lv.ntiles * M2L_TILE;
-        fpos_kernel<<<grid2(cdiv(nlanes, 256)), dim3(256), 0, st>>>(lv.tile_box.p, nlanes, lv.key.p, lv.cell.p,
-                                                                    lv.far_ptr.p, lv.far_col.p, P.slot_of.p, lv.fpos.p);
-        F3M_HIP(hipGetLastError());
-        F3M_HIP(hipStreamSynchronize(st));
-        lv.m2l_tables = true;
+    // kernel matrices of this depth
+    const double half = 0.5 * (double)P.E / std::ldexp(1.0, level);
+    const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
+    const int64_t nk = (int64_t)M2L_NOFF * M2L_R * M2L_R;
+    lv.ktab.alloc((size_t)nk, tally);
+    ktab_kernel<<<dim3((unsigned)cdiv(nk, 256)), dim3(256), 0, st>>>(lv.ktab.p, nd, c);
+    F3M_HIP(hipGetLastError());
+    // tiles: the boxes of each parity class, in rank order, 32 per tile, whole groups per class
+    lv.gpos.alloc((size_t)lv.nb);
+    int64_t tiles = 0;
+    std::vector<ScanState> S(8);
+    for (uint32_t cidx = 0; cidx < 8; ++cidx) {
+        scan_prepare(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx], true, st);
+        lv.tile_base[cidx] = (uint32_t)tiles;
+        tiles += cdiv(cdiv((int64_t)S[cidx].total, M2L_TILE), M2L_GROUP) * M2L_GROUP;
     }
+    lv.tile_base[8] = (uint32_t)tiles;
+    lv.ntiles = tiles;
+    lv.tile_box.alloc((size_t)tiles * M2L_TILE, tally);
+    F3M_HIP(hipMemsetAsync(lv.tile_box.p, 0xFF, (size_t)tiles * M2L_TILE * sizeof(uint32_t), st));
+    for (uint32_t cidx = 0; cidx < 8; ++cidx)
+        scan_finish(ParityIn{lv.key.p, cidx}, lv.nb, S[cidx],
+                    ParityOut{lv.tile_box.p, lv.gpos.p, (uint64_t)lv.tile_base[cidx] * M2L_TILE}, st);
+    const size_t nf = (size_t)lv.ntiles * M2L_NSLOT * M2L_TILE;
+    lv.fpos.alloc(nf, tally);
+    F3M_HIP(hipMemsetAsync(lv.fpos.p, 0xFF, nf * sizeof(uint32_t), st));
+    F3M_HIP(hipStreamSynchronize(st));   // the scan states are released on return
+    lv.m2l_tables = true;
+}
+
+void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st) {
+    const f3m_level &lv = P.lev[level];
+    DevBuf<uint32_t> gpos;
+    gpos.alloc((size_t)lv.nb);
+    const int64_t nlanes = lv.ntiles * M2L_TILE;
+    gpos_kernel<<<grid2(cdiv(nlanes, 256)), dim3(256), 0, st>>>(lv.tile_box.p, nlanes, gpos.p);
+    far_rows_kernel<<<grid2(cdiv(lv.nb, 64)), dim3(64), 0, st>>>(gpos.p, lv.nb, lv.far_ptr.p, lv.fpos.p, cols_dev);
+    F3M_HIP(hipGetLastError());
+    F3M_HIP(hipStreamSynchronize(st));
 }
 
 bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st) {

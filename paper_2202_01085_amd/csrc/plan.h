@@ -24,7 +24,9 @@ struct f3m_level {
     int64_t ntiles = 0;
     uint32_t tile_base[9] = {0};        // first tile of each parity class (tile_base[8] = ntiles)
     f3m::DevBuf<uint32_t> tile_box;     // [ntiles*32] target rank per tile lane (0xffffffff = padding)
-    f3m::DevBuf<uint32_t> fpos;         // [ntiles][189][32] source rank or 0xffffffff
+    f3m::DevBuf<uint32_t> fpos;         // [ntiles][189][32] source rank or 0xffffffff; on such a
+                                        // depth this table IS the far list (far_col stays empty)
+    f3m::DevBuf<uint32_t> gpos;         // [nb] tile position (tile*32 + lane) of every box
 };
 
 struct f3m_plan_s {
@@ -75,7 +77,15 @@ void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, f
 void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
                          int64_t m, double *y64, hipStream_t st);
 // m2l.hip
-void build_far_tables(f3m_plan_s &P, hipStream_t st);
-bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st);   // false: no tables for this plan
+constexpr int M2L_NOFF = 343;    // cell offsets in [-3,3]^3
+constexpr int M2L_NSLOT = 189;   // far offsets of one parity class
+constexpr int M2L_TILE = 32;     // targets per tile
+__host__ __device__ inline int off_index(int ox, int oy, int oz) { return (ox + 3) + 7 * (oy + 3) + 49 * (oz + 3); }
+bool m2l_tables_apply(const f3m_plan_s &P);                      // D = 3, 4 nodes/dim, far ratio 2
+void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st);            // slot tables
+void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st);  // kernel matrices, tiles, empty fpos
+bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st);   // false: no tables for this depth
+// far list of a table depth as CSR columns (ascending inside a row), device buffer of far_sz entries
+void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);
 
 }  // namespace f3m

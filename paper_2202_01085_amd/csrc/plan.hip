@@ -129,48 +129,90 @@ struct U32Out {
     __device__ void operator()(int64_t i, uint64_t ex, uint64_t) const { p[i] = (uint32_t)ex; }
 };
 
+// Stable scatter of one tile of RS_TILE keys.  Tile order = (wave, round, lane): every wave
+// ranks its own 16 rounds of 64 keys with ballots and a private LDS counter array, with no
+// block barrier inside the loop; then the tile is put in digit order in LDS and written out
+// so that consecutive threads write consecutive addresses of a digit run.
 __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__restrict__ keys_in,
                                                            const uint32_t *__restrict__ vals_in,
                                                            uint32_t *__restrict__ keys_out,
                                                            uint32_t *__restrict__ vals_out, int64_t n, int shift,
                                                            const uint32_t *__restrict__ offs, int64_t nblk) {
-    __shared__ uint32_t running[256];
-    __shared__ uint32_t wcnt[RS_NT / 64][256];
+    constexpr int NW = RS_NT / 64;
+    __shared__ uint32_t wcnt[NW][256];      // per wave: keys of each digit seen so far
+    __shared__ uint32_t dstart[256];        // first tile-local position of each digit
+    __shared__ uint32_t gbase[256];         // global position of the tile's first key of each digit
+    __shared__ uint32_t skey[RS_TILE], sval[RS_TILE];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    running[tid] = offs[(int64_t)tid * nblk + blockIdx.x];
 #pragma unroll
-    for (int k = 0; k < RS_NT / 64; ++k) wcnt[k][tid] = 0;
+    for (int k = 0; k < NW; ++k) wcnt[k][tid] = 0;
+    gbase[tid] = offs[(int64_t)tid * nblk + blockIdx.x];
     __syncthreads();
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    int64_t base = (int64_t)blockIdx.x * RS_TILE;
-    for (int round = 0; round < RS_IPT; ++round) {
-        int64_t i = base + round * RS_NT + tid;
-        bool valid = i < n;
-        uint32_t key = valid ? keys_in[i] : 0u;
-        uint32_t val = valid ? (vals_in ? vals_in[i] : (uint32_t)i) : 0u;
-        uint32_t digit = (key >> shift) & 255u;
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE + (int64_t)w * (RS_IPT * 64);
+    uint32_t key[RS_IPT], val[RS_IPT], rk[RS_IPT];   // rk = rank within (wave, digit), or ~0 if out of range
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        const int64_t i = base + r * 64 + lane;
+        const bool valid = i < n;
+        key[r] = valid ? keys_in[i] : 0u;
+        val[r] = valid ? (vals_in ? vals_in[i] : (uint32_t)i) : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        const int64_t i = base + r * 64 + lane;
+        const bool valid = i < n;
+        const uint32_t digit = (key[r] >> shift) & 255u;
         uint64_t peers = __ballot(valid);
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
-            bool bit = (digit >> b) & 1u;
-            uint64_t m = __ballot(bit);
+            const bool bit = (digit >> b) & 1u;
+            const uint64_t m = __ballot(bit);
             peers &= bit ? m : ~m;
         }
-        uint32_t rank = (uint32_t)__popcll(peers & lt_mask);
-        if (valid && rank == 0) wcnt[w][digit] = (uint32_t)__popcll(peers);
-        __syncthreads();
-        if (valid) {
-            uint32_t pos = running[digit] + rank;
-            for (int k = 0; k < w; ++k) pos += wcnt[k][digit];
-            keys_out[pos] = key;
-            vals_out[pos] = val;
-        }
-        __syncthreads();
-        uint32_t add = 0;
+        const uint32_t before = (uint32_t)__popcll(peers & lt_mask);
+        uint32_t cnt = 0;
+        if (valid) cnt = wcnt[w][digit];
+        rk[r] = valid ? cnt + before : 0xFFFFFFFFu;
+        // the wave runs in lockstep and LDS operations of a wave complete in order: all lanes
+        // have read the counter before the leader of each digit group updates it
+        if (valid && before == 0) wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
+        __builtin_amdgcn_wave_barrier();   // keep the rounds' LDS accesses in program order
+    }
+    __syncthreads();
+    // digit totals of the tile, exclusive scan over the 256 digits (one digit per thread)
+    {
+        uint32_t tot = 0;
 #pragma unroll
-        for (int k = 0; k < RS_NT / 64; ++k) { add += wcnt[k][tid]; wcnt[k][tid] = 0; }
-        running[tid] += add;
-        __syncthreads();
+        for (int k = 0; k < NW; ++k) tot += wcnt[k][tid];
+        uint64_t blocktot;
+        const uint32_t ex = (uint32_t)block_excl_scan_u64(tot, &blocktot);
+        dstart[tid] = ex;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        if (rk[r] != 0xFFFFFFFFu) {
+            const uint32_t digit = (key[r] >> shift) & 255u;
+            uint32_t pos = dstart[digit] + rk[r];
+            for (int k = 0; k < w; ++k) pos += wcnt[k][digit];
+            skey[pos] = key[r];
+            sval[pos] = val[r];
+        }
+    }
+    __syncthreads();
+    const int64_t left = n - (int64_t)blockIdx.x * RS_TILE;
+    const int cntile = (int)(left < RS_TILE ? left : RS_TILE);
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        const int pos = r * RS_NT + tid;
+        if (pos < cntile) {
+            const uint32_t k = skey[pos];
+            const uint32_t digit = (k >> shift) & 255u;
+            const uint32_t g = gbase[digit] + ((uint32_t)pos - dstart[digit]);
+            keys_out[g] = k;
+            vals_out[g] = sval[pos];
+        }
     }
 }
 
@@ -281,8 +323,18 @@ __global__ __launch_bounds__(256) void cells_kernel(const uint32_t *__restrict__
 // far iff the squared integer cell offset is >= T = ceil(theta^2)  (Sec. 3, IsFarField
 // := |delta centre| >= 2 l, divided by l).  Rows come out sorted by column rank because the
 // parent's row is sorted and children have consecutive ranks (Sec. 4.1 "Ensuring
-// interactions are sorted").  pass 0 counts, pass 1 fills.
+// interactions are sorted").  pass 0 counts, pass 1 fills.  On depths that use the
+// table-driven M2L the far partners are written straight into the positional table
+// fpos[tile][slot][lane] (slot = index of the cell offset within the box's parity class)
+// instead of far_col.
 // ------------------------------------------------------------------------------------
+struct FposArg {
+    uint32_t *fpos;          // nullptr: write far_col
+    const uint32_t *gpos;    // tile position of every box
+    const int32_t *slot_of;  // [8][343]
+    const uint32_t *key;     // box keys (parity = key & 7)
+};
+
 template <int D>
 __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const uint32_t *__restrict__ parent,
                                                     const int32_t *__restrict__ cell,
@@ -292,12 +344,21 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
                                                     uint32_t *__restrict__ cnt_near, uint32_t *__restrict__ cnt_far,
                                                     const uint64_t *__restrict__ near_ptr,
                                                     const uint64_t *__restrict__ far_ptr,
-                                                    uint32_t *__restrict__ near_col, uint32_t *__restrict__ far_col) {
+                                                    uint32_t *__restrict__ near_col, uint32_t *__restrict__ far_col,
+                                                    FposArg fa) {
     int64_t a = (int64_t)blockIdx.x * 128 + threadIdx.x;
     if (a >= nb) return;
     int32_t ca[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) ca[d] = cell[a * D + d];
+    const bool to_table = D == 3 && pass && fa.fpos != nullptr;
+    uint32_t *frow = nullptr;
+    const int32_t *so = nullptr;
+    if (to_table) {
+        const uint32_t g = fa.gpos[a];
+        frow = fa.fpos + (int64_t)(g >> 5) * (M2L_NSLOT * M2L_TILE) + (g & 31);
+        so = fa.slot_of + (fa.key[a] & 7u) * M2L_NOFF;
+    }
     uint32_t P = parent[a];
     uint64_t nn = 0, nf = 0;
     uint64_t nbase = pass ? near_ptr[a] : 0, fbase = pass ? far_ptr[a] : 0;
@@ -306,14 +367,22 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
         uint32_t b1 = up_cstart[Q + 1];
         for (uint32_t bq = up_cstart[Q]; bq < b1; ++bq) {
             int d2 = 0;
+            int o[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                int o = cell[(int64_t)bq * D + d] - ca[d];
-                d2 += o * o;
+                o[d] = cell[(int64_t)bq * D + d] - ca[d];
+                d2 += o[d] * o[d];
             }
             bool is_far = !all_near && d2 >= T;
             if (is_far) {
-                if (pass) far_col[fbase + nf] = bq;
+                if (to_table) {
+                    if (D == 3) {
+                        const int slot = so[off_index(o[0], o[D > 1 ? 1 : 0], o[D > 2 ? 2 : 0])];
+                        frow[(int64_t)slot * M2L_TILE] = bq;
+                    }
+                } else if (pass) {
+                    far_col[fbase + nf] = bq;
+                }
                 ++nf;
             } else {
                 if (pass) near_col[nbase + nn] = bq;
@@ -458,6 +527,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     keys_b.release();
     perm_b.release();
 
+    if (m2l_tables_apply(P)) m2l_prepare_plan(P, st);
     // ---- Algorithm 1 loop: divide, new interactions, partition
     int cap = P.Lq;
     if (P.max_depth > 0 && P.max_depth < cap) cap = P.max_depth;
@@ -527,7 +597,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             unsigned grid = (unsigned)cdiv(lv.nb, 128);
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
                                                              up.near_col.p, up.cstart.p, P.T, P.force_all_near, cn.p,
-                                                             cf.p, nullptr, nullptr, nullptr, nullptr);
+                                                             cf.p, nullptr, nullptr, nullptr, nullptr, FposArg{});
             F3M_HIP(hipGetLastError());
             uint64_t tn = 0, tf = 0;
             exclusive_scan(U32In{cn.p}, lv.nb, PtrOut{lv.near_ptr.p}, &tn, st);
@@ -537,11 +607,20 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lv.near_sz = (int64_t)tn;
             lv.far_sz = (int64_t)tf;
             lv.near_col.alloc((size_t)tn, tally);
-            lv.far_col.alloc((size_t)tf, tally);
+            FposArg fa{};
+            if (tf > 0 && m2l_tables_apply(P)) {
+                // the far pairs of this depth live in the positional table of the MFMA M2L
+                m2l_prepare_level(P, l, st);
+                fa = FposArg{lv.fpos.p, lv.gpos.p, P.slot_of.p, lv.key.p};
+                lv.far_col.alloc(0, tally);
+            } else {
+                lv.far_col.alloc((size_t)tf, tally);
+            }
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
                                                              up.near_col.p, up.cstart.p, P.T, P.force_all_near, nullptr,
                                                              nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
-                                                             lv.far_col.p);
+                                                             lv.far_col.p, fa);
+            lv.gpos.release();
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
@@ -584,7 +663,6 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         scan_prepare(NearPairsIn{lf.start.p, lf.near_ptr.p, lf.near_col.p}, lf.nb, S, true, st);
         P.near_point_pairs = (int64_t)S.total;
     }
-    build_far_tables(P, st);
     F3M_HIP(hipEventRecord(eb, st));
     F3M_HIP(hipStreamSynchronize(st));
 
