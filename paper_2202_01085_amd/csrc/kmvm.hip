@@ -171,11 +171,16 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
     float acc0 = 0.f, acc1 = 0.f;
     const float c2 = 2.f * c;
     const uint64_t e1 = near_ptr[a + 1];
-    for (uint64_t e = near_ptr[a]; e < e1; ++e) {
-        const uint32_t q = near_col[e];
+    for (uint64_t e = near_ptr[a]; e < e1;) {
+        // near boxes with consecutive ranks are one contiguous run of points: blocks of 32
+        // sources are cut from runs, not from single boxes, which wastes fewer rows
+        uint32_t q = near_col[e];
+        const uint32_t jb0 = start[q];
+        ++e;
+        while (e < e1 && near_col[e] == q + 1) { ++q; ++e; }
         const uint32_t je = start[q + 1];
-        for (uint32_t jb = start[q]; jb < je; jb += 32) {
-            // A operand: source jb + nn, scaled.  Rows beyond the box read the points that
+        for (uint32_t jb = jb0; jb < je; jb += 32) {
+            // A operand: source jb + nn, scaled.  Rows beyond the run read the points that
             // follow (or the zero padding behind the last point) and get a norm term of -1e30,
             // so that their kernel value is exp2(-huge) = 0 whatever their right-hand side is.
             const uint32_t j = jb + nn;
