@@ -82,6 +82,7 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
         P->leaf_max = (opt && opt->leaf_max > 0) ? opt->leaf_max : 128;
         P->max_depth = opt ? opt->max_depth : 0;
         P->force_all_near = opt ? (opt->force_all_near != 0) : 0;
+        P->no_overlap = opt ? (opt->overlap == 0) : 1;
         F3M_HIP(hipGetDevice(&P->device));
         if (n > 0) f3m::build_plan(*P, X, (hipStream_t)stream);
     });
@@ -152,6 +153,7 @@ f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
         out->near_pairs[l] = plan->lev[l].near_sz;
         out->far_pairs[l] = plan->lev[l].far_sz;
     }
+    for (int l = 0; l <= plan->L && plan->n > 0; ++l) out->far_point_pairs[l] = plan->lev[l].far_point_pairs;
     out->near_point_pairs = plan->near_point_pairs;
     out->device_bytes = plan->bytes;
     return F3M_OK;
@@ -203,7 +205,8 @@ f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out) {
         if (plan->have_kmvm_times) {
             F3M_HIP(hipEventSynchronize(plan->ev[12]));
             F3M_HIP(hipEventElapsedTime(&t.permute_in, plan->ev[8], plan->ev[9]));
-            F3M_HIP(hipEventElapsedTime(&t.p2p, plan->ev[9], plan->ev[10]));
+            F3M_HIP(hipEventSynchronize(plan->ev_p2p1));
+            F3M_HIP(hipEventElapsedTime(&t.p2p, plan->ev_p2p0, plan->ev_p2p1));
             F3M_HIP(hipEventElapsedTime(&t.permute_out, plan->ev[11], plan->ev[12]));
             F3M_HIP(hipEventElapsedTime(&t.kmvm_total, plan->ev[8], plan->ev[12]));
             t.p2m = t.m2l = t.l2p = 0.f;

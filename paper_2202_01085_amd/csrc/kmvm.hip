@@ -62,10 +62,16 @@ __global__ __launch_bounds__(256) void gather_kernel(const float *__restrict__ b
     int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k < n) bs[k] = b[perm[k]];
 }
-__global__ __launch_bounds__(256) void scatter_kernel(const float *__restrict__ ys, const uint32_t *__restrict__ perm,
-                                                      int64_t n, float *__restrict__ y) {
+// y = far-field part + near-field part, back in the caller's order
+__global__ __launch_bounds__(256) void scatter_kernel(const float *__restrict__ ys, const float *__restrict__ yn,
+                                                      const uint32_t *__restrict__ perm, int64_t n,
+                                                      float *__restrict__ y) {
     int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (k < n) y[perm[k]] = ys[k];
+    if (k < n) y[perm[k]] = ys[k] + yn[k];
+}
+__global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ p, int64_t n) {
+    int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) p[k] = 0.f;
 }
 
 // ------------------------------------------------------------------------------------
@@ -671,6 +677,14 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     F3M_HIP(hipEventRecord(P.ev[8], st));
     gather_kernel<<<dim3(gn), dim3(256), 0, st>>>(b, P.perm.p, n, P.bs.p);
     F3M_HIP(hipEventRecord(P.ev[9], st));
+    // The near field goes to the plan's second stream (vector ALU work) and overlaps the
+    // far field (matrix-core work) on the caller's stream; with no_overlap it runs in line.
+    hipStream_t sn = P.side ? P.side : st;
+    if (P.side) {
+        F3M_HIP(hipEventRecord(P.ev_fork, st));
+        F3M_HIP(hipStreamWaitEvent(P.side, P.ev_fork, 0));
+    }
+    F3M_HIP(hipEventRecord(P.ev_p2p0, sn));
     {
         // c l^2 bounds the magnitude of the expanded exponent terms in box-local coordinates
         // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
@@ -678,15 +692,18 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
         const bool gram = c * CL.edge * CL.edge * (double)D <= 6.0;
         if (gram)
-            p2p_mfma_kernel<D><<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, st>>>(
+            p2p_mfma_kernel<D><<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
-                P.tile_first.p, P.ntiles, (float)c, CL, P.ys.p);
+                P.tile_first.p, P.ntiles, (float)c, CL, P.yn.p);
         else
-            p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
+            p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, sn>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
                                                                   leaf.near_col.p, P.tile_box.p, P.tile_first.p,
-                                                                  P.ntiles, nc2, P.ys.p);
+                                                                  P.ntiles, nc2, P.yn.p);
     }
     F3M_HIP(hipGetLastError());
+    F3M_HIP(hipEventRecord(P.ev_p2p1, sn));
+    if (P.side) F3M_HIP(hipEventRecord(P.ev_join, P.side));
+    zero_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, n);
     F3M_HIP(hipEventRecord(P.ev[10], st));
     P.far_events.resize((size_t)(P.L + 1) * 4, nullptr);
     for (int l = 1; l <= P.L; ++l) {
@@ -744,8 +761,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         }
         F3M_HIP(hipEventRecord(ev[3], st));
     }
+    if (P.side) F3M_HIP(hipStreamWaitEvent(st, P.ev_join, 0));
     F3M_HIP(hipEventRecord(P.ev[11], st));
-    scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.perm.p, n, y);
+    scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, P.perm.p, n, y);
     F3M_HIP(hipGetLastError());
     if (!P.ev[12]) F3M_HIP(hipEventCreate(&P.ev[12]));
     F3M_HIP(hipEventRecord(P.ev[12], st));

@@ -265,6 +265,28 @@ void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st) {
     lv.m2l_tables = true;
 }
 
+struct FposPairsIn {
+    const uint32_t *tile_box, *fpos, *start;
+    __device__ uint64_t operator()(int64_t g) const {
+        const uint32_t a = tile_box[g];
+        if (a == 0xFFFFFFFFu) return 0;
+        const uint32_t *row = fpos + (g >> 5) * (int64_t)(M2L_NSLOT * M2L_TILE) + (g & 31);
+        uint64_t s = 0;
+        for (int k = 0; k < M2L_NSLOT; ++k) {
+            const uint32_t q = row[(int64_t)k * M2L_TILE];
+            if (q != 0xFFFFFFFFu) s += start[q + 1] - start[q];
+        }
+        return s * (uint64_t)(start[a + 1] - start[a]);
+    }
+};
+
+int64_t m2l_far_point_pairs(const f3m_plan_s &P, int level, hipStream_t st) {
+    const f3m_level &lv = P.lev[level];
+    ScanState S;
+    scan_prepare(FposPairsIn{lv.tile_box.p, lv.fpos.p, lv.start.p}, lv.ntiles * M2L_TILE, S, true, st);
+    return (int64_t)S.total;
+}
+
 void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st) {
     const f3m_level &lv = P.lev[level];
     DevBuf<uint32_t> gpos;

@@ -13,6 +13,7 @@ struct f3m_level {
     f3m::DevBuf<uint64_t> near_ptr, far_ptr;   // [nb+1]
     f3m::DevBuf<uint32_t> near_col, far_col;
     int64_t near_sz = 0, far_sz = 0;
+    int64_t far_point_pairs = 0;        // sum of |p||q| over the far pairs of this depth
     // P2M work split: a chunk is a run of at most P2M_CHUNK points of one box
     int64_t nchunks = 0;
     f3m::DevBuf<uint32_t> chunk_box;    // [nchunks]
@@ -36,7 +37,9 @@ struct f3m_plan_s {
     float gamma = 1.f, theta = 2.f;
     float E = 0.f, scale = 0.f;
     float alpha[F3M_MAX_DIM] = {0};
-    int leaf_max = 128, max_depth = 0, force_all_near = 0;
+    int leaf_max = 128, max_depth = 0, force_all_near = 0, no_overlap = 0;
+    hipStream_t side = nullptr;                 // second stream for the near field
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_p2p0 = nullptr, ev_p2p1 = nullptr;
     int device = 0;
     int64_t bytes = 0;
     int64_t near_point_pairs = 0;
@@ -44,7 +47,8 @@ struct f3m_plan_s {
     f3m::DevBuf<uint32_t> keys;   // [n] keys at depth Lq, box order
     f3m::DevBuf<uint32_t> perm;   // [n]
     f3m::DevBuf<float> Xs;        // [n*D] coordinates in box order, row-major
-    f3m::DevBuf<float> bs, ys;    // [n] right-hand side / result in box order
+    f3m::DevBuf<float> bs, ys;    // [n] right-hand side / far-field result in box order
+    f3m::DevBuf<float> yn;        // [n] near-field result in box order
     f3m::DevBuf<float> W, V;      // [max_l nb_l * r] node weights / node potentials of one depth
     f3m::DevBuf<float> Wpart;     // [max_l nchunks_l * r] partial node weights
     // near-field work split: a tile is a run of at most 64 targets of one leaf box
@@ -86,6 +90,7 @@ void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st);            // slot tables
 void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st);  // kernel matrices, tiles, empty fpos
 bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st);   // false: no tables for this depth
 // far list of a table depth as CSR columns (ascending inside a row), device buffer of far_sz entries
+int64_t m2l_far_point_pairs(const f3m_plan_s &P, int level, hipStream_t st);
 void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);
 
 }  // namespace f3m

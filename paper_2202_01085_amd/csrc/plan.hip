@@ -12,6 +12,9 @@ f3m_plan_s::~f3m_plan_s() {
         if (e) (void)hipEventDestroy(e);
     for (auto &e : far_events)
         if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {ev_fork, ev_join, ev_p2p0, ev_p2p1})
+        if (e) (void)hipEventDestroy(e);
+    if (side) (void)hipStreamDestroy(side);
 }
 
 namespace f3m {
@@ -396,6 +399,21 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
     }
 }
 
+// point pairs of a CSR interaction list: |p| * sum of |q| over the row of p
+struct NearPairsIn {
+    const uint32_t *start;
+    const uint64_t *near_ptr;
+    const uint32_t *near_col;
+    __device__ uint64_t operator()(int64_t a) const {
+        uint64_t s = 0;
+        for (uint64_t e = near_ptr[a]; e < near_ptr[a + 1]; ++e) {
+            uint32_t q = near_col[e];
+            s += start[q + 1] - start[q];
+        }
+        return s * (uint64_t)(start[a + 1] - start[a]);
+    }
+};
+
 struct PtrOut {
     uint64_t *p;
     __device__ void operator()(int64_t i, uint64_t ex, uint64_t) const { p[i] = ex; }
@@ -422,21 +440,6 @@ __global__ __launch_bounds__(256) void chunk_box_kernel(const uint32_t *__restri
     }
     chunk_box[c] = (uint32_t)lo;
 }
-
-// point pairs of the near field: |p| * sum of |q| over the near row of p
-struct NearPairsIn {
-    const uint32_t *start;
-    const uint64_t *near_ptr;
-    const uint32_t *near_col;
-    __device__ uint64_t operator()(int64_t a) const {
-        uint64_t s = 0;
-        for (uint64_t e = near_ptr[a]; e < near_ptr[a + 1]; ++e) {
-            uint32_t q = near_col[e];
-            s += start[q + 1] - start[q];
-        }
-        return s * (uint64_t)(start[a + 1] - start[a]);
-    }
-};
 
 static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevBuf<uint32_t> &first,
                          DevBuf<uint32_t> &cbox, int64_t &nchunks, int64_t *tally, hipStream_t st) {
@@ -621,6 +624,15 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
                                                              nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
                                                              lv.far_col.p, fa);
             lv.gpos.release();
+            if (tf > 0) {
+                if (lv.m2l_tables) {
+                    lv.far_point_pairs = m2l_far_point_pairs(P, l, st);
+                } else {
+                    ScanState S;
+                    scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, lv.far_col.p}, lv.nb, S, true, st);
+                    lv.far_point_pairs = (int64_t)S.total;
+                }
+            }
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
@@ -654,6 +666,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     P.bs.alloc((size_t)n + PAD_POINTS, tally);
     F3M_HIP(hipMemsetAsync(P.bs.p + n, 0, (size_t)PAD_POINTS * sizeof(float), st));
     P.ys.alloc((size_t)n, tally);
+    P.yn.alloc((size_t)n, tally);
+    if (!P.no_overlap) F3M_HIP(hipStreamCreateWithFlags(&P.side, hipStreamNonBlocking));
+    for (hipEvent_t *e : {&P.ev_fork, &P.ev_join, &P.ev_p2p0, &P.ev_p2p1}) F3M_HIP(hipEventCreate(e));
     P.W.alloc((size_t)max_nb * P.r, tally);
     P.V.alloc((size_t)max_nb * P.r, tally);
     P.Wpart.alloc((size_t)max_chunks * P.r, tally);

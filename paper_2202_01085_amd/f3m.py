@@ -28,7 +28,7 @@ class F3MError(RuntimeError):
 
 class Options(ctypes.Structure):
     _fields_ = [("leaf_max", ctypes.c_int32), ("max_depth", ctypes.c_int32),
-                ("force_all_near", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("force_all_near", ctypes.c_int32), ("overlap", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -38,6 +38,7 @@ class Info(ctypes.Structure):
                 ("alpha", ctypes.c_float * MAX_DIM),
                 ("nboxes", ctypes.c_int64 * (MAX_LEVELS + 1)), ("max_box", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("near_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)), ("far_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
+                ("far_point_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("near_point_pairs", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
 
 
@@ -110,11 +111,11 @@ class Plan:
     """f3m_plan / f3m_plan_ex: the partition and interaction lists of one point set."""
 
     def __init__(self, X, lengthscale, interp_nodes, eta=2.0, leaf_max=0, max_depth=0, force_all_near=False,
-                 stream=None):
+                 overlap=False, stream=None):
         n, D = X.shape
         self.n, self.D = int(n), int(D)
         self._h = ctypes.c_void_p()
-        opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), 0)
+        opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), int(bool(overlap)))
         xp = _dev_f32(X, "X") if n > 0 else ctypes.c_void_p()
         _check(lib().f3m_plan_ex(xp, self.n, self.D, float(lengthscale), int(interp_nodes), float(eta),
                                  ctypes.byref(opt), _stream(stream), ctypes.byref(self._h)))

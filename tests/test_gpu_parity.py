@@ -168,6 +168,19 @@ def test_tiny_7d_three_nodes():
     assert rel(y, T.apply(b.numpy(), 3.0, 3)) <= TOL_F3M
 
 
+def test_overlap_option_gives_the_same_bits():
+    # near field on the plan's second stream, far field on the caller's: same sums, same order
+    X, b, cfg = inputs.make_config(1, n=50_000)
+    Xd, bd = to_dev(X, b)
+    say("f3m overlap option n=50000")
+    y_serial = f3m.Plan(Xd, 0.3, 4, 2.0).kmvm(bd)
+    plan = f3m.Plan(Xd, 0.3, 4, 2.0, overlap=True)
+    y_a = plan.kmvm(bd)
+    y_b = plan.kmvm(bd)          # back to back on the same plan: the second call must wait for the first
+    torch.cuda.synchronize()
+    assert torch.equal(y_serial, y_a) and torch.equal(y_a, y_b)
+
+
 def test_force_all_near_equals_direct():
     X = cloud("normal", 12_000, 3, 9)
     b = inputs.rhs_normal(12_000, 10)
@@ -297,3 +310,43 @@ def test_config2_full_size_sampled_rows():
     ptr, cols = plan.interactions(inf.depth, 0)
     total += int((np.repeat(cnt, np.diff(ptr.astype(np.int64))) * cnt[cols]).sum())
     assert total == n * n
+
+
+# --------------------------------------------------------------------------------------
+# configurations 3 and 5 at full size, in the launch configuration bench.py times
+# --------------------------------------------------------------------------------------
+def _full_size_uniform(k, oracle_rows):
+    X, b, cfg = inputs.make_config(k, device=DEV)
+    n = cfg["n"]
+    say("f3m config %d n=%d (uniform, lengthscale 1)" % (k, n))
+    plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"])
+    y = plan.kmvm(b)
+    torch.cuda.synchronize()
+    inf = plan.info()
+    L = inf.depth
+    say("  L=%d boxes=%s max_box=%d" % (L, list(inf.nboxes)[:L + 1], inf.max_box[L]))
+    # properties that hold at any size
+    assert inf.max_box[L] <= 128 < inf.max_box[L - 1]
+    assert inf.nboxes[L] == 8 ** L                                   # uniform data: every cell occupied
+    assert inf.near_point_pairs + sum(inf.far_point_pairs[l] for l in range(L + 1)) == n * n
+    assert inf.near_pairs[L] == (3 * 2 ** L - 2) ** 3                # 27-stencil clipped at the cube faces
+    # candidates = children of the parent's neighbours: 6 cells per dimension, 4 next to a face
+    assert all(inf.far_pairs[l] == (6 * 2 ** l - 8) ** 3 - (3 * 2 ** l - 2) ** 3 for l in range(2, L + 1))
+    # sampled rows against the fp64 exact rows, themselves pinned to the CPU oracle on a few rows
+    rows = inputs.sample_rows(n, 10_000 if n <= 10 ** 8 else 4_000, 3000 + k)
+    y64 = f3m.direct_kmvm_rows_f64(X, b, cfg["lengthscale"], rows).cpu().numpy()
+    e = rel(y[rows.to(DEV)].cpu().numpy(), y64)
+    say("  rel err vs exact on %d rows %.3e" % (rows.numel(), e))
+    assert e <= TOL_EXACT
+    Xh, bh = X.cpu().numpy(), b.cpu().numpy()
+    sub = rows[:oracle_rows].numpy()
+    assert rel(y64[:oracle_rows], oracle.rows(Xh, bh, g32(cfg["lengthscale"]), sub)) <= 1e-12
+    plan.close()
+
+
+def test_config3_full_size_sampled_rows():
+    _full_size_uniform(3, 128)
+
+
+def test_config5_full_size_sampled_rows():
+    _full_size_uniform(5, 24)
