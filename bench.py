@@ -55,6 +55,12 @@ def main():
     ap.add_argument("--rows", type=int, default=10000, help="sampled rows for the error against the exact product")
     ap.add_argument("--cpu-sample", type=int, default=400000, help="points of the CPU oracle sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first copy 1 GiB device-to-device with a plain kernel: the reference that the "
+                         "FETCH_SIZE / WRITE_SIZE counter readings of a rocprofv3 --pmc run are scaled by")
+    ap.add_argument("--traffic", type=str, default=None,
+                    help="JSON file with measured HBM bytes per launch, {\"p2p\": bytes, \"m2l\": bytes}, from "
+                         "the rocprofv3 --pmc runs summarised under profiles/")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU by design (the path is one GPU's share; see DESIGN.md, "
@@ -73,6 +79,12 @@ def main():
     X, b, _ = inputs.make_config(k, n=n, device=dev)
     y = torch.empty_like(b)
     torch.cuda.synchronize()
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"])
@@ -126,6 +138,11 @@ def main():
                             "pairs_per_s": pairs / (st["p2p"] * 1e-3),
                             "peak_note": "256 CU x 64 lanes x 2.4 GHz x 2 flop (FMA) = 78.6 TFLOP/s; the published "
                                          "157.3 needs packed FP32, which this build does not generate"}
+    if args.traffic:
+        with open(args.traffic) as f:
+            for name, nbytes in json.load(f).items():
+                if name in rooflines:
+                    rooflines[name]["traffic"] = nbytes
     # the dominant kernel of the step is the one reported as `roofline`
     roof = None
     if rooflines:

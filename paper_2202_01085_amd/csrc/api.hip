@@ -136,6 +136,11 @@ void f3m_destroy(f3m_plan_t *plan) {
 
 f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
     if (!plan || !out) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    if (plan->n > 0 && !plan->have_far_point_pairs) {
+        // cached on first use; the plan is logically unchanged
+        f3m_status st = guarded([&] { f3m::compute_far_point_pairs(*const_cast<f3m_plan_t *>(plan)); });
+        if (st != F3M_OK) return st;
+    }
     std::memset(out, 0, sizeof(*out));
     out->n = plan->n;
     out->D = plan->D;
@@ -211,12 +216,13 @@ f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out) {
             F3M_HIP(hipEventElapsedTime(&t.kmvm_total, plan->ev[8], plan->ev[12]));
             t.p2m = t.m2l = t.l2p = 0.f;
             for (int l = 1; l <= plan->L; ++l) {
-                if (plan->lev[l].far_sz == 0 || plan->far_events.size() < (size_t)(l + 1) * 4) continue;
-                hipEvent_t *ev = &plan->far_events[(size_t)l * 4];
+                if (plan->lev[l].far_sz == 0 || plan->far_events.size() < (size_t)(l + 1) * 6) continue;
+                hipEvent_t *ev = &plan->far_events[(size_t)l * 6];
+                if (!ev[5]) continue;
                 float ms = 0.f;
                 F3M_HIP(hipEventElapsedTime(&ms, ev[0], ev[1])); t.p2m += ms;
-                F3M_HIP(hipEventElapsedTime(&ms, ev[1], ev[2])); t.m2l += ms;
-                F3M_HIP(hipEventElapsedTime(&ms, ev[2], ev[3])); t.l2p += ms;
+                F3M_HIP(hipEventElapsedTime(&ms, ev[2], ev[3])); t.m2l += ms;
+                F3M_HIP(hipEventElapsedTime(&ms, ev[4], ev[5])); t.l2p += ms;
             }
         }
         *out = t;
@@ -228,12 +234,12 @@ f3m_status f3m_level_times(f3m_plan_t *plan, int level, float *ms_host) {
     if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
     return guarded([&] {
         ms_host[0] = ms_host[1] = ms_host[2] = 0.f;
-        if (!plan->have_kmvm_times || plan->lev[level].far_sz == 0 || plan->far_events.size() < (size_t)(level + 1) * 4)
+        if (!plan->have_kmvm_times || plan->lev[level].far_sz == 0 || plan->far_events.size() < (size_t)(level + 1) * 6)
             return;
-        hipEvent_t *ev = &plan->far_events[(size_t)level * 4];
-        if (!ev[3]) return;
-        F3M_HIP(hipEventSynchronize(ev[3]));
-        for (int k = 0; k < 3; ++k) F3M_HIP(hipEventElapsedTime(&ms_host[k], ev[k], ev[k + 1]));
+        hipEvent_t *ev = &plan->far_events[(size_t)level * 6];
+        if (!ev[5]) return;
+        F3M_HIP(hipEventSynchronize(plan->ev[12]));
+        for (int k = 0; k < 3; ++k) F3M_HIP(hipEventElapsedTime(&ms_host[k], ev[2 * k], ev[2 * k + 1]));
     });
 }
 

@@ -552,7 +552,9 @@ __global__ __launch_bounds__(64) void l2p34_kernel(const float *__restrict__ Xs,
     if (c >= nchunks) return;
     const int lane = threadIdx.x;
     const uint32_t a = __builtin_amdgcn_readfirstlane(chunk_box[c]);
-    if (far_ptr[a + 1] == far_ptr[a]) return;  // no far partner at this depth: V_p is zero
+    // far_ptr given: skip boxes without far partner at this depth (V_p is zero); nullptr: V holds the
+    // potentials accumulated over all depths and every box is evaluated
+    if (far_ptr && far_ptr[a + 1] == far_ptr[a]) return;
     const uint32_t ci = (uint32_t)(c - chunk_first[a]);
     const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
     const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
@@ -581,6 +583,110 @@ __global__ __launch_bounds__(64) void l2p34_kernel(const float *__restrict__ Xs,
             ys[k] += y;
         }
     }
+}
+
+// ------------------------------------------------------------------------------------
+// Node weights and node potentials between depths (D = 3, 4 nodes per dimension).
+// The basis functions of a parent box are polynomials of degree 3 per coordinate, and the
+// 4-node interpolant of a child box reproduces such polynomials exactly.  Hence
+//   W_parent[i] = sum_children sum_k L^parent_i(s^child_k) W_child[k]           (upward)
+// equals the P2M sum over the parent's points, and evaluating a parent's potential at a
+// child's nodes,  V_child[k] += sum_i L^parent_i(s^child_k) V_parent[i]          (downward),
+// followed by ONE L2P at the last depth equals the per-depth L2P sums -- both up to
+// rounding.  This replaces the streaming passes over all points at every depth (Fig. 4
+// steps 1 and 3 per depth) by one pass each at the last depth.
+// In parent coordinates the child's node k sits at (s_k -+ 1)/2 (lower / upper half), so the
+// 64 x 64 transfer matrix is a tensor product of three 4 x 4 matrices T1[half][i][k].
+// ------------------------------------------------------------------------------------
+struct TransferArg { float t[2][4][4]; };   // t[half][i][k] = L_i((s_k + (half ? 1 : -1)) / 2)
+
+static TransferArg make_transfer() {
+    TransferArg T{};
+    double s[4];
+    for (int i = 0; i < 4; ++i) s[i] = std::cos((double)i * M_PI / 3.0);
+    for (int h = 0; h < 2; ++h)
+        for (int k = 0; k < 4; ++k) {
+            const double tp = 0.5 * (s[k] + (h ? 1.0 : -1.0));
+            for (int i = 0; i < 4; ++i) {
+                double num = 1.0, den = 1.0;
+                for (int j = 0; j < 4; ++j)
+                    if (j != i) { num *= tp - s[j]; den *= s[i] - s[j]; }
+                T.t[h][i][k] = (float)(num / den);
+            }
+        }
+    return T;
+}
+
+void upload_transfer(f3m_plan_s &P, hipStream_t st) {
+    const TransferArg T = make_transfer();
+    P.transfer.alloc(32, &P.bytes);
+    F3M_HIP(hipMemcpyAsync(P.transfer.p, &T.t[0][0][0], 32 * sizeof(float), hipMemcpyHostToDevice, st));
+    F3M_HIP(hipStreamSynchronize(st));
+}
+
+// one block (wavefront) per parent, lane = parent node i
+__global__ __launch_bounds__(64) void m2m34_kernel(const uint32_t *__restrict__ cstart,
+                                                   const uint32_t *__restrict__ child_key, int64_t nparents,
+                                                   const float *__restrict__ T, const float *__restrict__ Wchild,
+                                                   float *__restrict__ Wparent) {
+    const int64_t P = block_index();
+    if (P >= nparents) return;
+    const int i = threadIdx.x, ix = i & 3, iy = (i >> 2) & 3, iz = i >> 4;
+    float acc = 0.f;
+    const uint32_t c1 = cstart[P + 1];
+    for (uint32_t c = cstart[P]; c < c1; ++c) {
+        const uint32_t par = child_key[c] & 7u;   // bit d = upper half along dimension d
+        const float *Wc = Wchild + (int64_t)c * 64;   // wave-uniform
+        const float4 tx = *reinterpret_cast<const float4 *>(T + (par & 1) * 16 + ix * 4);
+        const float4 ty = *reinterpret_cast<const float4 *>(T + ((par >> 1) & 1) * 16 + iy * 4);
+        const float4 tz = *reinterpret_cast<const float4 *>(T + ((par >> 2) & 1) * 16 + iz * 4);
+        const float ax[4] = {tx.x, tx.y, tx.z, tx.w}, ay[4] = {ty.x, ty.y, ty.z, ty.w}, az[4] = {tz.x, tz.y, tz.z, tz.w};
+        float sz = 0.f;
+#pragma unroll
+        for (int kz = 0; kz < 4; ++kz) {
+            float sy = 0.f;
+#pragma unroll
+            for (int ky = 0; ky < 4; ++ky) {
+                float sx = 0.f;
+#pragma unroll
+                for (int kx = 0; kx < 4; ++kx) sx = fmaf(ax[kx], Wc[kx + 4 * ky + 16 * kz], sx);
+                sy = fmaf(ay[ky], sx, sy);
+            }
+            sz = fmaf(az[kz], sy, sz);
+        }
+        acc += sz;
+    }
+    Wparent[P * 64 + i] = acc;
+}
+
+// one block (wavefront) per child, lane = child node k
+__global__ __launch_bounds__(64) void l2l34_kernel(const uint32_t *__restrict__ parent,
+                                                   const uint32_t *__restrict__ child_key, int64_t nchildren,
+                                                   const float *__restrict__ T, const float *__restrict__ Vparent,
+                                                   float *__restrict__ Vchild) {
+    const int64_t c = block_index();
+    if (c >= nchildren) return;
+    const int k = threadIdx.x, kx = k & 3, ky = (k >> 2) & 3, kz = k >> 4;
+    const uint32_t par = child_key[c] & 7u;
+    const float *Tx = T + (par & 1) * 16 + kx, *Ty = T + ((par >> 1) & 1) * 16 + ky, *Tz = T + ((par >> 2) & 1) * 16 + kz;
+    float ax[4], ay[4], az[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { ax[i] = Tx[4 * i]; ay[i] = Ty[4 * i]; az[i] = Tz[4 * i]; }
+    const float *Vp = Vparent + (int64_t)parent[c] * 64;   // wave-uniform
+    float sz = 0.f;
+#pragma unroll
+    for (int iz = 0; iz < 4; ++iz) {
+        float sy = 0.f;
+#pragma unroll
+        for (int iy = 0; iy < 4; ++iy) {
+            float sx = 0.f;
+#pragma unroll
+            for (int ix = 0; ix < 4; ++ix) sx = fmaf(ax[ix], Vp[ix + 4 * iy + 16 * iz], sx);
+            sy = fmaf(ay[iy], sx, sy);
+        }
+        sz = fmaf(az[iz], sy, sz);
+    }
+    Vchild[c * 64 + k] += sz;
 }
 
 // ------------------------------------------------------------------------------------
@@ -705,13 +811,21 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     if (P.side) F3M_HIP(hipEventRecord(P.ev_join, P.side));
     zero_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, n);
     F3M_HIP(hipEventRecord(P.ev[10], st));
-    P.far_events.resize((size_t)(P.L + 1) * 4, nullptr);
+    // six events per depth: [0,1] bracket the upward pass (P2M or M2M), [2,3] the M2L, [4,5] the
+    // downward pass (L2L and/or L2P) of that depth
+    P.far_events.resize((size_t)(P.L + 1) * 6, nullptr);
+    auto level_events = [&](int l) {
+        hipEvent_t *ev = &P.far_events[(size_t)l * 6];
+        for (int k = 0; k < 6; ++k)
+            if (!ev[k]) F3M_HIP(hipEventCreate(&ev[k]));
+        return ev;
+    };
+    const bool tree = P.tree_lmin > 0;   // D = 3, 4 nodes per dimension, tables on depths tree_lmin..L
+    // ---- depths that are handled on their own, straight from the points (Fig. 4 steps 1-3)
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
-        if (lv.far_sz == 0) continue;
-        hipEvent_t *ev = &P.far_events[(size_t)l * 4];
-        for (int k = 0; k < 4; ++k)
-            if (!ev[k]) F3M_HIP(hipEventCreate(&ev[k]));
+        if (lv.far_sz == 0 || (tree && l >= P.tree_lmin)) continue;
+        hipEvent_t *ev = level_events(l);
         const CentreArg C = make_centre(P, l);
         const double half = 0.5 * C.edge;
         const float nc2h = (float)(-1.4426950408889634 * half * half / (2.0 * (double)P.gamma * (double)P.gamma));
@@ -736,7 +850,8 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[1], st));
-        if (!run_m2l_tables(P, l, st)) {
+        F3M_HIP(hipEventRecord(ev[2], st));
+        if (!run_m2l_tables(P, l, P.W.p, P.V.p, st)) {
             size_t sh = (size_t)(r + D * p) * sizeof(float);
             if (r <= 64)
                 m2l_generic_kernel<D, 64><<<grid_for(lv.nb), dim3(64), sh, st>>>(
@@ -746,7 +861,8 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                     lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, p, r, N, nc2h, P.W.p, P.V.p);
             F3M_HIP(hipGetLastError());
         }
-        F3M_HIP(hipEventRecord(ev[2], st));
+        F3M_HIP(hipEventRecord(ev[3], st));
+        F3M_HIP(hipEventRecord(ev[4], st));
         {
             size_t sh = (size_t)(r + P2M_CHUNK * (D * p + 1)) * sizeof(float);
             if (D == 3 && p == 4)
@@ -759,7 +875,64 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                     P.V.p, P.ys.p);
             F3M_HIP(hipGetLastError());
         }
-        F3M_HIP(hipEventRecord(ev[3], st));
+        F3M_HIP(hipEventRecord(ev[5], st));
+    }
+    // ---- depths tree_lmin..L: P2M at the last depth, weights passed upward, M2L per depth,
+    //      potentials passed downward, one L2P at the last depth
+    if (tree) {
+        const int L = P.L;
+        f3m_level &lf = P.lev[L];
+        {
+            hipEvent_t *ev = level_events(L);
+            F3M_HIP(hipEventRecord(ev[0], st));
+            p2m34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, lf.start.p, lf.cell.p, lf.chunk_box.p,
+                                                                  lf.chunk_first.p, lf.nchunks, make_centre(P, L),
+                                                                  lf.Wl.p, P.Wpart.p);
+            F3M_HIP(hipGetLastError());
+            if (lf.nchunks > lf.nb)
+                p2m_reduce_kernel<<<grid_for(lf.nb), dim3(256), 0, st>>>(lf.chunk_first.p, lf.nb, r, P.Wpart.p, lf.Wl.p);
+            F3M_HIP(hipGetLastError());
+            F3M_HIP(hipEventRecord(ev[1], st));
+        }
+        for (int l = L - 1; l >= P.tree_lmin; --l) {
+            f3m_level &lv = P.lev[l], &dn = P.lev[l + 1];
+            hipEvent_t *ev = level_events(l);
+            F3M_HIP(hipEventRecord(ev[0], st));
+            m2m34_kernel<<<grid_for(lv.nb), dim3(64), 0, st>>>(lv.cstart.p, dn.key.p, lv.nb, P.transfer.p, dn.Wl.p, lv.Wl.p);
+            F3M_HIP(hipGetLastError());
+            F3M_HIP(hipEventRecord(ev[1], st));
+        }
+        for (int l = P.tree_lmin; l <= L; ++l) {
+            hipEvent_t *ev = level_events(l);
+            F3M_HIP(hipEventRecord(ev[2], st));
+            if (!run_m2l_tables(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st)) fail(F3M_ERR_HIP, "internal: depth without M2L tables");
+            F3M_HIP(hipEventRecord(ev[3], st));
+        }
+        for (int l = P.tree_lmin + 1; l <= L; ++l) {
+            f3m_level &lv = P.lev[l], &up = P.lev[l - 1];
+            hipEvent_t *ev = level_events(l);
+            F3M_HIP(hipEventRecord(ev[4], st));
+            l2l34_kernel<<<grid_for(lv.nb), dim3(64), 0, st>>>(lv.parent.p, lv.key.p, lv.nb, P.transfer.p, up.Vl.p, lv.Vl.p);
+            F3M_HIP(hipGetLastError());
+            if (l < L) F3M_HIP(hipEventRecord(ev[5], st));
+        }
+        {
+            hipEvent_t *ev = level_events(L);
+            if (P.tree_lmin == L) F3M_HIP(hipEventRecord(ev[4], st));
+            l2p34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, lf.start.p, lf.cell.p, nullptr, lf.chunk_box.p,
+                                                                  lf.chunk_first.p, lf.nchunks, make_centre(P, L),
+                                                                  lf.Vl.p, P.ys.p);
+            F3M_HIP(hipGetLastError());
+            F3M_HIP(hipEventRecord(ev[5], st));
+        }
+        // the lowest tree depth has no downward pass of its own
+        {
+            hipEvent_t *ev = level_events(P.tree_lmin);
+            if (P.tree_lmin < L) {
+                F3M_HIP(hipEventRecord(ev[4], st));
+                F3M_HIP(hipEventRecord(ev[5], st));
+            }
+        }
     }
     if (P.side) F3M_HIP(hipStreamWaitEvent(st, P.ev_join, 0));
     F3M_HIP(hipEventRecord(P.ev[11], st));

@@ -298,14 +298,14 @@ void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hip
     F3M_HIP(hipStreamSynchronize(st));
 }
 
-bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st) {
+bool run_m2l_tables(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st) {
     f3m_level &lv = P.lev[level];
     if (!lv.m2l_tables) return false;
     TileBase tb;
     for (int c = 0; c < 9; ++c) tb.b[c] = lv.tile_base[c];
     int64_t ngroups = 0;   // blocks of the largest class
     for (int c = 0; c < 8; ++c) ngroups = std::max<int64_t>(ngroups, (lv.tile_base[c + 1] - lv.tile_base[c]) / M2L_GROUP);
-    m2l_mfma_kernel<<<grid2(ngroups * 8), dim3(64), 0, st>>>(P.W.p, P.V.p, lv.ktab.p, lv.tile_box.p,
+    m2l_mfma_kernel<<<grid2(ngroups * 8), dim3(64), 0, st>>>(W, V, lv.ktab.p, lv.tile_box.p,
                                                                          lv.fpos.p, P.slot_oi.p, tb, ngroups);
     F3M_HIP(hipGetLastError());
     return true;

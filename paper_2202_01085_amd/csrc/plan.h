@@ -28,6 +28,8 @@ struct f3m_level {
     f3m::DevBuf<uint32_t> fpos;         // [ntiles][189][32] source rank or 0xffffffff; on such a
                                         // depth this table IS the far list (far_col stays empty)
     f3m::DevBuf<uint32_t> gpos;         // [nb] tile position (tile*32 + lane) of every box
+    // node weights / node potentials kept per depth when they are passed between depths
+    f3m::DevBuf<float> Wl, Vl;          // [nb*64]
 };
 
 struct f3m_plan_s {
@@ -57,10 +59,13 @@ struct f3m_plan_s {
     f3m_level lev[F3M_MAX_LEVELS + 1];
     f3m::DevBuf<int32_t> slot_of;       // [8][343] offset index -> slot of a parity class (-1: not far)
     f3m::DevBuf<int32_t> slot_oi;       // [8][189] slot -> offset index
+    int tree_lmin = 0;                  // > 0: node weights/potentials are passed between depths
+                                        // tree_lmin..L (D = 3, 4 nodes/dim); 0: every depth from the points
+    f3m::DevBuf<float> transfer;        // [2][4][4] parent basis at the child's nodes
 
     hipEvent_t ev[16] = {nullptr};
     std::vector<hipEvent_t> far_events;   // 4 per depth: before P2M, M2L, L2P, after L2P
-    bool have_plan_times = false, have_kmvm_times = false;
+    bool have_plan_times = false, have_kmvm_times = false, have_far_point_pairs = false;
     f3m_times times = {};
     ~f3m_plan_s();
 };
@@ -75,6 +80,7 @@ int quant_depth(int D);
 
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);
+void compute_far_point_pairs(f3m_plan_s &P);   // fills lev[].far_point_pairs once (synchronises)
 // kmvm.hip
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
 void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st);
@@ -88,7 +94,8 @@ __host__ __device__ inline int off_index(int ox, int oy, int oz) { return (ox + 
 bool m2l_tables_apply(const f3m_plan_s &P);                      // D = 3, 4 nodes/dim, far ratio 2
 void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st);            // slot tables
 void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st);  // kernel matrices, tiles, empty fpos
-bool run_m2l_tables(f3m_plan_s &P, int level, hipStream_t st);   // false: no tables for this depth
+bool run_m2l_tables(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);   // false: no tables
+void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
 // far list of a table depth as CSR columns (ascending inside a row), device buffer of far_sz entries
 int64_t m2l_far_point_pairs(const f3m_plan_s &P, int level, hipStream_t st);
 void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);

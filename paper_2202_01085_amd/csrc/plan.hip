@@ -624,15 +624,6 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
                                                              nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
                                                              lv.far_col.p, fa);
             lv.gpos.release();
-            if (tf > 0) {
-                if (lv.m2l_tables) {
-                    lv.far_point_pairs = m2l_far_point_pairs(P, l, st);
-                } else {
-                    ScanState S;
-                    scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, lv.far_col.p}, lv.nb, S, true, st);
-                    lv.far_point_pairs = (int64_t)S.total;
-                }
-            }
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
@@ -654,12 +645,24 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
 
     // ---- work splits and workspaces
     F3M_HIP(hipEventRecord(ea, st));
+    // With the table-driven M2L on the last depth (D = 3, 4 nodes/dim) node weights and node
+    // potentials are passed between depths, so only the last depth streams the points.
+    if (P.L >= 2 && P.lev[P.L].m2l_tables) {
+        P.tree_lmin = P.L;
+        while (P.tree_lmin > 2 && P.lev[P.tree_lmin - 1].far_sz > 0) --P.tree_lmin;
+        upload_transfer(P, st);
+    }
     int64_t max_nb = 0, max_chunks = 0;
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
         if (lv.far_sz == 0) continue;
+        if (P.tree_lmin > 0 && k >= P.tree_lmin) {
+            lv.Wl.alloc((size_t)lv.nb * P.r, tally);
+            lv.Vl.alloc((size_t)lv.nb * P.r, tally);
+            if (k < P.L) continue;   // only the last depth needs chunks
+        }
         build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
-        max_nb = std::max(max_nb, lv.nb);
+        if (!(P.tree_lmin > 0 && k >= P.tree_lmin)) max_nb = std::max(max_nb, lv.nb);
         max_chunks = std::max(max_chunks, lv.nchunks);
     }
     build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
@@ -691,6 +694,25 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     F3M_HIP(hipEventElapsedTime(&ms, P.ev[0], eb));
     P.times.plan_total = ms;
     P.have_plan_times = true;
+}
+
+// Point pairs behind the far lists (for reports and the coverage identity near + far = n^2);
+// computed on first request because it re-reads every far list.
+void compute_far_point_pairs(f3m_plan_s &P) {
+    if (P.have_far_point_pairs) return;
+    for (int l = 1; l <= P.L; ++l) {
+        f3m_level &lv = P.lev[l];
+        lv.far_point_pairs = 0;
+        if (lv.far_sz == 0) continue;
+        if (lv.m2l_tables) {
+            lv.far_point_pairs = m2l_far_point_pairs(P, l, nullptr);
+        } else {
+            ScanState S;
+            scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, lv.far_col.p}, lv.nb, S, true, nullptr);
+            lv.far_point_pairs = (int64_t)S.total;
+        }
+    }
+    P.have_far_point_pairs = true;
 }
 
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st) {
