@@ -118,20 +118,81 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, c
 }
 
 // ------------------------------------------------------------------------------------
-// near field with the Gram matrix on the matrix cores.  With coordinates taken relative to
-// the centre of the target box (x' = x - centre, y' = y - centre) and c = log2(e)/(2 gamma^2)
-//   k(x,y) = exp2(-c|x'|^2) * exp2( 2c x'.y' - c|y'|^2 ).
+// near field with the Gram matrix on the matrix cores.  In box units, relative to the centre
+// of the target box (u = (x - centre)/l for a target, w = (y - centre)/l for a source) and with
+// g = log2(e) l^2 / (2 gamma^2):
+//   k(x,y) = exp2(-g|u|^2) * exp2( 2g u.w - g|w|^2 ).
 // The second exponent for 32 sources x 32 targets is a dense contraction with inner
-// dimension D+1 (coordinates plus the norm term): (D+2)/2 v_mfma_f32_32x32x2_f32 per block,
-// leaving exp2 and one FMA per pair on the vector ALU; the factor exp2(-c|x'|^2) is applied
-// once per target at the end.  A wavefront handles a run of <= 64 targets of one leaf box as
-// two column blocks of 32.  After the MFMA lane (n,h) holds the 16 sources 8(v/4)+4h+(v%4) of
-// target column n; the two halves are added with one shuffle at the end.
-// Used only while c l^2 is small (the caller checks it): the expanded square loses
-// |x'|^2+|y'|^2 times fp32 epsilon in the exponent, which box-local coordinates keep small.
+// dimension D+1: source vector (2g w_1..2g w_D, -g|w|^2), target vector (u_1..u_D, 1).  Each
+// component is split into two fp16 numbers (hi = fp16(v), lo = fp16(v - hi): 22 significant
+// bits) and the products hi*hi + hi*lo + lo*hi are laid side by side along the inner
+// dimension, so one v_mfma_f32_32x32x16_f16 (fp32 accumulation, 8 passes) does the work of
+// (D+2)/2 fp32 MFMAs of 16 passes each: 3(D+1) <= 16 terms for D <= 4, two instructions above.
+// The dropped lo*lo term and the split are a perturbation of the coordinates by 2^-22 of a box
+// edge.  exp2 and one FMA per pair stay on the vector ALU; exp2(-g|u|^2) is applied once per
+// target.  A wavefront handles a run of <= 64 targets of one leaf box as two column blocks of
+// 32; after the MFMA lane (n,h) holds the 16 sources 8(v/4)+4h+(v%4) of target column n, and
+// the two halves are added with one shuffle at the end.
+// Sources are cut from runs of rank-consecutive near boxes (contiguous points); rows beyond a
+// run get zero coordinates and a norm term of -60000, so that their kernel value is
+// exp2(-huge) = 0 whatever right-hand side is read for them.
+// Used only while g is small (the caller checks it): the expanded square loses
+// (|u|^2+|w|^2) g times the rounding unit in the exponent.
 // ------------------------------------------------------------------------------------
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef _Float16 h8v __attribute__((ext_vector_type(8)));
 struct __attribute__((packed, aligned(4))) float4u { float v[4]; };
+
+// hi/lo fp16 split of NC components and the MFMA operand of one instruction:
+//   term t of the inner dimension (t = 16 q + 8 h + e): kind = t / NC, component = t % NC
+//   source side: (hi, hi, lo)[kind],  target side: (hi, lo, hi)[kind],  zero beyond 3 NC terms
+template <int NC, bool SOURCE>
+__device__ inline h8v split_operand(const float (&v)[NC], int q, int h) {
+    _Float16 hi[NC], lo[NC];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        hi[i] = (_Float16)v[i];
+        lo[i] = (_Float16)(v[i] - (float)hi[i]);
+    }
+    h8v r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        _Float16 val[2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int t = 16 * q + 8 * hh + e;
+            const int kind = t / NC, comp = t % NC;
+            const bool use_lo = SOURCE ? kind == 2 : kind == 1;
+            val[hh] = kind >= 3 ? (_Float16)0.f : (use_lo ? lo[comp] : hi[comp]);
+        }
+        r[e] = h ? val[1] : val[0];
+    }
+    return r;
+}
+
+typedef float f2v __attribute__((ext_vector_type(2)));
+typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+
+__device__ inline uint32_t pack_f16(float a, float b) {
+    const h2v h = __builtin_convertvector((f2v){a, b}, h2v);
+    return __builtin_bit_cast(uint32_t, h);
+}
+__device__ inline f2v unpack_f16(uint32_t v) { return __builtin_convertvector(__builtin_bit_cast(h2v, v), f2v); }
+
+// source operand for four components (D = 3): the same layout as split_operand<4, true>,
+// built from packed pairs.  Lane half 0 holds (hi, hi), lane half 1 (lo, 0).
+__device__ inline h8v split_source4(const float (&w)[4], int h) {
+    const uint32_t hi01 = pack_f16(w[0], w[1]), hi23 = pack_f16(w[2], w[3]);
+    const f2v b01 = unpack_f16(hi01), b23 = unpack_f16(hi23);
+    const uint32_t lo01 = pack_f16(w[0] - b01.x, w[1] - b01.y), lo23 = pack_f16(w[2] - b23.x, w[3] - b23.y);
+    u4v r;
+    r.x = h ? lo01 : hi01;
+    r.y = h ? lo23 : hi23;
+    r.z = h ? 0u : hi01;
+    r.w = h ? 0u : hi23;
+    return __builtin_bit_cast(h8v, r);
+}
 
 template <int D>
 __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
@@ -141,8 +202,9 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
                                                        const uint32_t *__restrict__ near_col,
                                                        const uint32_t *__restrict__ tile_box,
                                                        const uint32_t *__restrict__ tile_first, int64_t ntiles,
-                                                       float c, CentreArg C, float *__restrict__ ys) {
-    constexpr int KS = (D + 2) / 2;
+                                                       float g, float inv_l, CentreArg C, float *__restrict__ ys) {
+    constexpr int NC = D + 1;
+    constexpr int NQ = (3 * NC + 15) / 16;   // MFMA instructions per 32 x 32 block
     const int lane = threadIdx.x & 63;
     const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
     if (t >= ntiles) return;
@@ -156,73 +218,112 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
     for (int d = 0; d < D; ++d) ctr[d] = (float)(C.alpha[d] + ((double)cell[(int64_t)a * D + d] + 0.5) * C.edge);
 
     // B operands: the targets of the two column blocks
-    float Bop[2][KS], ni[2];
+    h8v Bop[2][NQ];
+    float ni[2];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         const uint32_t kt = k0 + cb * 32 + nn;
-        const bool valid = kt < kend;
-        float xp[2 * KS];
+        // unconditional loads (in bounds: Xs is padded by 64 points), masked by a factor so
+        // that they are issued together and not one by one under a branch
+        const float valid = kt < kend ? 1.f : 0.f;
+        float u[NC];
         float s = 0.f;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            xp[d] = valid ? Xs[(int64_t)kt * D + d] - ctr[d] : 0.f;
-            s = fmaf(xp[d], xp[d], s);
+            u[d] = (Xs[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
+            s = fmaf(u[d], u[d], s);
         }
-        xp[D] = 1.f;
-        if (D + 1 < 2 * KS) xp[D + 1] = 0.f;
-        ni[cb] = -c * s;
+        u[D] = 1.f;
+        ni[cb] = -g * s;
 #pragma unroll
-        for (int st = 0; st < KS; ++st) Bop[cb][st] = kk ? xp[2 * st + 1] : xp[2 * st];
+        for (int q = 0; q < NQ; ++q) Bop[cb][q] = split_operand<NC, false>(u, q, kk);
     }
     float acc0 = 0.f, acc1 = 0.f;
-    const float c2 = 2.f * c;
+    const float g2l = 2.f * g * inv_l;
+    const float nrm = -0.25f / g;
+
+    // the blocks of 32 sources: near boxes with consecutive ranks are one contiguous run of
+    // points, and blocks are cut from runs, not from single boxes, which wastes fewer rows.
+    // (jb, je) is a block start and the end of its run; e walks the near list.
+    uint64_t e = near_ptr[a];
     const uint64_t e1 = near_ptr[a + 1];
-    for (uint64_t e = near_ptr[a]; e < e1;) {
-        // near boxes with consecutive ranks are one contiguous run of points: blocks of 32
-        // sources are cut from runs, not from single boxes, which wastes fewer rows
+    auto next_run = [&](uint32_t &jb, uint32_t &je) {
         uint32_t q = near_col[e];
-        const uint32_t jb0 = start[q];
+        jb = start[q];
         ++e;
         while (e < e1 && near_col[e] == q + 1) { ++q; ++e; }
-        const uint32_t je = start[q + 1];
-        for (uint32_t jb = jb0; jb < je; jb += 32) {
-            // A operand: source jb + nn, scaled.  Rows beyond the run read the points that
-            // follow (or the zero padding behind the last point) and get a norm term of -1e30,
-            // so that their kernel value is exp2(-huge) = 0 whatever their right-hand side is.
-            const uint32_t j = jb + nn;
-            float yp[2 * KS];
-            float s = 0.f;
+        je = start[q + 1];
+    };
+    // the loads of a block: one source row per lane (both halves the same) and the right-hand
+    // sides of the 16 sources this lane sees after the MFMA.  Always in bounds (64 points of
+    // padding behind Xs and bs); rows at or beyond je are masked in block().
+    auto load = [&](uint32_t jb, float (&x)[D], float4u (&bq)[4]) {
+        const uint32_t j = jb + nn;
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                float v = Xs[(int64_t)j * D + d] - ctr[d];
-                s = fmaf(v, v, s);
-                yp[d] = c2 * v;
-            }
-            yp[D] = j < je ? -c * s : -1.0e30f;
-            if (D + 1 < 2 * KS) yp[D + 1] = 0.f;
-            // right-hand sides of the 16 sources this lane sees after the MFMA
-            float bv[16];
+        for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)j * D + d];
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const float4u tt = *reinterpret_cast<const float4u *>(bs + jb + 8 * q4 + 4 * kk);
+        for (int q4 = 0; q4 < 4; ++q4) bq[q4] = *reinterpret_cast<const float4u *>(bs + jb + 8 * q4 + 4 * kk);
+    };
+    auto block = [&](uint32_t jb, uint32_t je, const float (&x)[D], const float4u (&bq)[4]) {
+        const bool live = jb + nn < je;
+        float w[NC];
+        float s = 0.f;
 #pragma unroll
-                for (int e4 = 0; e4 < 4; ++e4) bv[4 * q4 + e4] = tt.v[e4];
-            }
-            f16v c0 = {0.f};
-#pragma unroll
-            for (int st = 0; st < KS; ++st)
-                c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(kk ? yp[2 * st + 1] : yp[2 * st], Bop[0][st], c0, 0, 0, 0);
-            if (two) {
-                f16v c1 = {0.f};
-#pragma unroll
-                for (int st = 0; st < KS; ++st)
-                    c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(kk ? yp[2 * st + 1] : yp[2 * st], Bop[1][st], c1, 0, 0, 0);
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bv[v], acc1);
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bv[v], acc0);
+        for (int d = 0; d < D; ++d) {
+            w[d] = (x[d] - ctr[d]) * (live ? g2l : 0.f);     // 2 g w_d
+            s = fmaf(w[d], w[d], s);
         }
+        w[D] = live ? s * nrm : -60000.f;              // -g |w|^2
+        h8v Aop[NQ];
+        if constexpr (NC == 4) {
+            Aop[0] = split_source4(w, kk);
+        } else {
+#pragma unroll
+            for (int qq = 0; qq < NQ; ++qq) Aop[qq] = split_operand<NC, true>(w, qq, kk);
+        }
+        f16v c0 = {0.f};
+#pragma unroll
+        for (int qq = 0; qq < NQ; ++qq) c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Aop[qq], Bop[0][qq], c0, 0, 0, 0);
+        if (two) {
+            f16v c1 = {0.f};
+#pragma unroll
+            for (int qq = 0; qq < NQ; ++qq) c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(Aop[qq], Bop[1][qq], c1, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bq[v >> 2].v[v & 3], acc1);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
+        }
+    };
+    // two register sets in turn: the loads of the next block are in flight while the current
+    // one is worked on.  The near list is never empty (a box is near to itself).
+    float xa[D], xb[D];
+    float4u ba[4], bb[4];
+    uint32_t jba, jea, jbb, jeb;
+    next_run(jba, jea);
+    load(jba, xa, ba);
+    for (;;) {
+        jbb = jba + 32;
+        jeb = jea;
+        bool more = true;
+        if (jbb >= jea) {
+            if (e < e1) next_run(jbb, jeb);
+            else more = false;
+        }
+        load(more ? jbb : jba, xb, bb);     // unconditional: a fixed number of loads in flight
+        block(jba, jea, xa, ba);
+        if (!more) break;
+        jba = jbb + 32;
+        jea = jeb;
+        if (jba >= jeb) {
+            if (e < e1) next_run(jba, jea);
+            else more = false;
+        }
+        load(more ? jba : jbb, xa, ba);
+        block(jbb, jeb, xb, bb);
+        if (!more) break;
     }
     acc0 += __shfl_xor(acc0, 32, 64);
     acc1 += __shfl_xor(acc1, 32, 64);
@@ -796,11 +897,12 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
         const CentreArg CL = make_centre(P, P.L);
         const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
-        const bool gram = c * CL.edge * CL.edge * (double)D <= 6.0;
+        const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
+        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024;
         if (gram)
             p2p_mfma_kernel<D><<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
-                P.tile_first.p, P.ntiles, (float)c, CL, P.yn.p);
+                P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, P.yn.p);
         else
             p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, sn>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
                                                                   leaf.near_col.p, P.tile_box.p, P.tile_first.p,
