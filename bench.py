@@ -130,19 +130,33 @@ def main():
                             "achieved": ach, "peak": PEAK_MFMA_F32_TFLOPS, "unit": "TFLOP/s",
                             "frac": ach / PEAK_MFMA_F32_TFLOPS, "traffic": None, "launch_ms": m2l_ms}
     if pairs > 0 and st["p2p"] > 0:
-        flops = (3.0 * D + 2.0) * pairs      # algorithmic: D sub, D mul/fma, exp2, fma = 3D+2 flop per point pair
-        ach = flops / (st["p2p"] * 1e-3) / 1e12
-        rooflines["p2p"] = {"kernel": "p2p_kernel, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
+        # algorithmic: D sub, D mul/fma, exp2, fma = 3D+2 flop per point pair.  The kernel computes the
+        # D-term part as a Gram matrix on the matrix cores, so per pair the vector ALU is left with one
+        # v_exp_f32 (2 issue slots per lane: measured half rate) and one FMA: 3 slots per pair is the floor
+        # of this instruction mix, reported as valu_slot_frac.
+        t = st["p2p"] * 1e-3
+        flops = (3.0 * D + 2.0) * pairs
+        ach = flops / t / 1e12
+        lane_slots_per_s = 256 * 64 * 2.4e9
+        rooflines["p2p"] = {"kernel": "p2p_mfma_kernel, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
                             "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS,
                             "traffic": None, "launch_ms": st["p2p"],
-                            "pairs_per_s": pairs / (st["p2p"] * 1e-3),
+                            "pairs_per_s": pairs / t,
+                            "valu_slot_frac": 3.0 * pairs / t / lane_slots_per_s,
+                            "frac_of_packed_fp32_peak": ach / 157.3,
                             "peak_note": "256 CU x 64 lanes x 2.4 GHz x 2 flop (FMA) = 78.6 TFLOP/s; the published "
                                          "157.3 needs packed FP32, which this build does not generate"}
-    if args.traffic:
-        with open(args.traffic) as f:
-            for name, nbytes in json.load(f).items():
-                if name in rooflines:
-                    rooflines[name]["traffic"] = nbytes
+    traffic_file = args.traffic
+    if traffic_file is None and n == 1_000_000_000:
+        # HBM bytes per launch measured with rocprofv3 --pmc on this workload (profiles/hbm_traffic_config5_n1e9.md)
+        cand = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_config5_n1e9.json")
+        traffic_file = cand if os.path.exists(cand) else None
+    if traffic_file:
+        with open(traffic_file) as f:
+            tj = json.load(f)
+        for name, nbytes in tj.get("bytes_per_launch", tj).items():
+            if name in rooflines:
+                rooflines[name]["traffic"] = nbytes
     # the dominant kernel of the step is the one reported as `roofline`
     roof = None
     if rooflines:

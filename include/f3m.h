@@ -149,6 +149,9 @@ const char *f3m_last_error(void);
 
 /* ---- introspection: for parity checks and reports; all outputs are HOST buffers ---- */
 
+/* Fills *out.  The point-pair counts (near_point_pairs, far_point_pairs) are not needed by the
+ * product, so the first call on a plan computes them on the device, re-reading every
+ * interaction list, and waits for that; later calls only copy.  Not thread-safe on one plan. */
 f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out);
 
 /* perm[k] = caller's index of the k-th point in box order (n entries): the

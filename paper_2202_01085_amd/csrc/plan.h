@@ -64,7 +64,7 @@ struct f3m_plan_s {
     f3m::DevBuf<float> transfer;        // [2][4][4] parent basis at the child's nodes
 
     hipEvent_t ev[16] = {nullptr};
-    std::vector<hipEvent_t> far_events;   // 4 per depth: before P2M, M2L, L2P, after L2P
+    std::vector<hipEvent_t> far_events;   // 6 per depth, around the far-field kernels of that depth
     bool have_plan_times = false, have_kmvm_times = false, have_far_point_pairs = false;
     f3m_times times = {};
     ~f3m_plan_s();
@@ -80,7 +80,7 @@ int quant_depth(int D);
 
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);
-void compute_far_point_pairs(f3m_plan_s &P);   // fills lev[].far_point_pairs once (synchronises)
+void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far_point_pairs, once (synchronises)
 // kmvm.hip
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
 void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st);

@@ -675,12 +675,6 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     P.W.alloc((size_t)max_nb * P.r, tally);
     P.V.alloc((size_t)max_nb * P.r, tally);
     P.Wpart.alloc((size_t)max_chunks * P.r, tally);
-    {
-        ScanState S;
-        const f3m_level &lf = P.lev[P.L];
-        scan_prepare(NearPairsIn{lf.start.p, lf.near_ptr.p, lf.near_col.p}, lf.nb, S, true, st);
-        P.near_point_pairs = (int64_t)S.total;
-    }
     F3M_HIP(hipEventRecord(eb, st));
     F3M_HIP(hipStreamSynchronize(st));
 
@@ -696,10 +690,17 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     P.have_plan_times = true;
 }
 
-// Point pairs behind the far lists (for reports and the coverage identity near + far = n^2);
-// computed on first request because it re-reads every far list.
+// Point pairs behind the near list of the last depth and the far lists of every depth (for
+// reports and the coverage identity near + far = n^2); computed on first request because it
+// re-reads every list.
 void compute_far_point_pairs(f3m_plan_s &P) {
     if (P.have_far_point_pairs) return;
+    {
+        ScanState S;
+        const f3m_level &lf = P.lev[P.L];
+        scan_prepare(NearPairsIn{lf.start.p, lf.near_ptr.p, lf.near_col.p}, lf.nb, S, true, nullptr);
+        P.near_point_pairs = (int64_t)S.total;
+    }
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
         lv.far_point_pairs = 0;
