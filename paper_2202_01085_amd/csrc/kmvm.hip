@@ -791,79 +791,171 @@ __global__ __launch_bounds__(64) void l2l34_kernel(const uint32_t *__restrict__ 
 }
 
 // ------------------------------------------------------------------------------------
-// M2L, v2 = K v1 (Fig. 4 step 2), general form: V_p[i] = sum_{q in far(p)} sum_j
-// k(s^p_i, s^q_j) W_q[j] with the kernel evaluated on the fly.  In units of half a box
-// edge the node distance along d is 2 o_d + s_{j_d} - s_{i_d}, o = integer cell offset.
-// One block per target box, thread(s) per target node.
+// M2L for any D and node count (Fig. 4 step 2), V_t += K(s^t, s^q) W_q over the far row of t.
+// The Gaussian is a product over dimensions, and so is the tensor grid of nodes, hence the
+// node-to-node matrix of a far pair with cell offset o is a Kronecker product,
+//   K = G_{o_D} x ... x G_{o_1},   G_o[i][j] = exp(-(l/2)^2 (2 o + s_j - s_i)^2 / (2 gamma^2)),
+// of p x p matrices that depend on the offset in one dimension only.  It is applied one
+// dimension at a time (D passes of r p multiply-adds instead of r^2 kernel values): the same
+// sums as the dense product, in another order.  The table G[o + omax][i][j] is built in fp64
+// per depth at plan time.
+// One wavefront per target box.  Pass 0 reads W_q from global memory and writes to LDS with
+// dimension 0 slowest (index = rest + i_0 r/p: conflict-free writes); the middle passes work
+// in place in LDS (a fibre is read and written by the same lane); the last pass adds into
+// register accumulators that are stored once per target.  A fibre = the p entries along the
+// pass's dimension; lane = fibre.
 // ------------------------------------------------------------------------------------
-template <int D, int NT>
-__global__ __launch_bounds__(NT) void m2l_generic_kernel(const int32_t *__restrict__ cell,
-                                                         const uint64_t *__restrict__ far_ptr,
-                                                         const uint32_t *__restrict__ far_col, int64_t nb, int p,
-                                                         int r, NodeArg N, float nc2h, const float *__restrict__ W,
-                                                         float *__restrict__ V) {
-    constexpr int NPT_MAX = NT == 64 ? 1 : MAX_NODES / 256;
-    extern __shared__ float lds[];
-    float *Wq = lds;        // [r]
-    float *u = lds + r;     // [D][p]   2 o_d + s_k
+// largest number of fibres (r/p) that p nodes per dimension allow with D <= 7 and r <= 4096
+constexpr int kron_max_fibres(int p) {
+    int r = 1;
+    for (int d = 0; d < F3M_MAX_DIM && r * p <= MAX_NODES; ++d) r *= p;
+    return r / p;
+}
+
+template <int PN>
+__global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict__ cell,
+                                                      const uint64_t *__restrict__ far_ptr,
+                                                      const uint32_t *__restrict__ far_col, int64_t nb, int D, int r,
+                                                      const float *__restrict__ G, int omax,
+                                                      const float *__restrict__ W, float *__restrict__ V) {
+    constexpr int NF = (kron_max_fibres(PN) + 63) / 64;   // fibres per lane, at most
+    extern __shared__ float lds[];                        // [r]
     const int64_t a = block_index();
     if (a >= nb) return;
     const uint64_t e0 = far_ptr[a], e1 = far_ptr[a + 1];
     if (e0 == e1) return;
-    const int npt = (r + NT - 1) / NT;
-    float si[NPT_MAX][D];
-    float acc[NPT_MAX];
+    const int lane = threadIdx.x;
+    const int nfib = r / PN;
+    float acc[NF][PN];
 #pragma unroll
-    for (int m = 0; m < NPT_MAX; ++m) {
-        int i = threadIdx.x + m * NT;
-        uint32_t code = node_code<D>(i < r ? i : 0, p);
+    for (int k = 0; k < NF; ++k)
 #pragma unroll
-        for (int d = 0; d < D; ++d) si[m][d] = N.s[(code >> (4 * d)) & 15u];
-        acc[m] = 0.f;
-    }
-    for (uint64_t e = e0; e < e1; ++e) {
-        const uint32_t q = far_col[e];
-        __syncthreads();
-        for (int j = threadIdx.x; j < r; j += NT) Wq[j] = W[(int64_t)q * r + j];
-        if ((int)threadIdx.x < D * p) {
-            int d = threadIdx.x / p, kk = threadIdx.x % p;
-            int o = cell[(int64_t)q * D + d] - cell[(int64_t)a * D + d];
-            u[d * p + kk] = 2.f * (float)o + N.s[kk];
+        for (int i = 0; i < PN; ++i) acc[k][i] = 0.f;
+    int ca[F3M_MAX_DIM];
+    for (int d = 0; d < D; ++d) ca[d] = cell[a * D + d];
+
+    // out[i] = sum_j g[i][j] in[j] with g wave-uniform
+    auto apply = [&](const float *__restrict__ g, const float (&in)[PN], float (&out)[PN]) {
+#pragma unroll
+        for (int i = 0; i < PN; ++i) {
+            float t = 0.f;
+#pragma unroll
+            for (int j = 0; j < PN; ++j) t = fmaf(g[i * PN + j], in[j], t);
+            out[i] = t;
         }
-        __syncthreads();
-        int dig[D];
+    };
+    for (uint64_t e = e0; e < e1; ++e) {
+        const uint32_t q = __builtin_amdgcn_readfirstlane(far_col[e]);
+        const float *Wq = W + (int64_t)q * r;
+        float *cur = lds;
+        __syncthreads();   // the last pass of the previous pair has read the buffer
+        {
+            const int o = cell[(int64_t)q * D] - ca[0];
+            const float *g = G + (int64_t)(o + omax) * (PN * PN);
 #pragma unroll
-        for (int d = 0; d < D; ++d) dig[d] = 0;
-        for (int j = 0; j < r; ++j) {
-            float uj[D];
+            for (int k = 0; k < NF; ++k) {
+                if (64 * k >= nfib) break;
+                const int f = lane + 64 * k;
+                if (f < nfib) {
+                    float in[PN], out[PN];
 #pragma unroll
-            for (int d = 0; d < D; ++d) uj[d] = u[d * p + dig[d]];
-            const float wj = Wq[j];
+                    for (int j = 0; j < PN; ++j) in[j] = Wq[f * PN + j];
+                    apply(g, in, out);
+                    if (D == 1) {
 #pragma unroll
-            for (int m = 0; m < NPT_MAX; ++m) {
-                if (m < npt) {
-                    float r2 = 0.f;
+                        for (int i = 0; i < PN; ++i) acc[k][i] += out[i];
+                    } else {
 #pragma unroll
-                    for (int d = 0; d < D; ++d) {
-                        float diff = uj[d] - si[m][d];
-                        r2 = fmaf(diff, diff, r2);
+                        for (int i = 0; i < PN; ++i) cur[f + i * nfib] = out[i];
                     }
-                    acc[m] = fmaf(__builtin_amdgcn_exp2f(r2 * nc2h), wj, acc[m]);
                 }
             }
+        }
+        int stride = 1;   // of dimension d in the LDS layout (dimensions 1..D-1 fastest first, then 0)
+        for (int d = 1; d < D; ++d) {
+            __syncthreads();
+            const int o = cell[(int64_t)q * D + d] - ca[d];
+            const float *g = G + (int64_t)(o + omax) * (PN * PN);
+            const float inv = 1.f / (float)stride;
+            const bool last = d == D - 1;
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                if (++dig[d] < p) break;
-                dig[d] = 0;
+            for (int k = 0; k < NF; ++k) {
+                if (64 * k >= nfib) break;
+                const int f = lane + 64 * k;
+                if (f < nfib) {
+                    const int hi = (int)(((float)f + 0.5f) * inv);   // f / stride, exact for these sizes
+                    const int base = hi * stride * PN + (f - hi * stride);
+                    float in[PN], out[PN];
+#pragma unroll
+                    for (int j = 0; j < PN; ++j) in[j] = cur[base + j * stride];
+                    apply(g, in, out);
+                    if (last) {
+#pragma unroll
+                        for (int i = 0; i < PN; ++i) acc[k][i] += out[i];
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < PN; ++i) cur[base + i * stride] = out[i];
+                    }
+                }
+            }
+            stride *= PN;
+        }
+    }
+    // accumulators of the last pass (dimension D-1, stride r/p^2 in the LDS layout) back to the
+    // flat node index i = sum_d i_d p^d
+    float *Va = V + a * r;
+    int stride = 1;
+    for (int d = 2; d < D; ++d) stride *= PN;
+    const float inv = 1.f / (float)stride;
+#pragma unroll
+    for (int k = 0; k < NF; ++k) {
+        if (64 * k >= nfib) break;
+        const int f = lane + 64 * k;
+        if (f < nfib) {
+#pragma unroll
+            for (int i = 0; i < PN; ++i) {
+                int flat;
+                if (D == 1) {
+                    flat = f * PN + i;
+                } else {
+                    const int hi = (int)(((float)f + 0.5f) * inv);
+                    const int idx = hi * stride * PN + (f - hi * stride) + i * stride;   // LDS layout index
+                    const int i0 = idx / nfib;
+                    flat = i0 + PN * (idx - i0 * nfib);
+                }
+                Va[flat] = acc[k][i];
             }
         }
     }
-#pragma unroll
-    for (int m = 0; m < NPT_MAX; ++m) {
-        int i = threadIdx.x + m * NT;
-        if (m < npt && i < r) V[(int64_t)a * r + i] = acc[m];
+}
+
+// per depth without M2L tables: the 1-D factor matrices of m2l_kron_kernel, built in fp64
+void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
+    const int p = P.p;
+    int m = 0;   // largest near offset in one dimension: m^2 < T
+    while ((m + 1) * (m + 1) < P.T) ++m;
+    const int omax = 2 * m + 1;   // children of near parents
+    std::vector<double> s(p);
+    for (int k = 0; k < p; ++k) s[k] = p > 1 ? std::cos(M_PI * (double)k / (double)(p - 1)) : 0.0;
+    for (int l = 1; l <= P.L; ++l) {
+        f3m_level &lv = P.lev[l];
+        if (lv.far_sz == 0 || lv.m2l_tables) continue;
+        const double half = 0.5 * (double)P.E / (double)(1ull << l);
+        const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
+        std::vector<float> g((size_t)(2 * omax + 1) * p * p);
+        for (int o = -omax; o <= omax; ++o)
+            for (int i = 0; i < p; ++i)
+                for (int j = 0; j < p; ++j) {
+                    const double t = 2.0 * (double)o + s[j] - s[i];
+                    g[((size_t)(o + omax) * p + i) * p + j] = (float)std::exp(-c * t * t);
+                }
+        lv.gtab.alloc(g.size(), &P.bytes);
+        lv.gtab_omax = omax;
+        F3M_HIP(hipMemcpyAsync(lv.gtab.p, g.data(), g.size() * sizeof(float), hipMemcpyHostToDevice, st));
+        F3M_HIP(hipStreamSynchronize(st));
     }
 }
+
 
 // ------------------------------------------------------------------------------------
 template <int D>
@@ -954,13 +1046,21 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         F3M_HIP(hipEventRecord(ev[1], st));
         F3M_HIP(hipEventRecord(ev[2], st));
         if (!run_m2l_tables(P, l, P.W.p, P.V.p, st)) {
-            size_t sh = (size_t)(r + D * p) * sizeof(float);
-            if (r <= 64)
-                m2l_generic_kernel<D, 64><<<grid_for(lv.nb), dim3(64), sh, st>>>(
-                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, p, r, N, nc2h, P.W.p, P.V.p);
-            else
-                m2l_generic_kernel<D, 256><<<grid_for(lv.nb), dim3(256), sh, st>>>(
-                    lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, p, r, N, nc2h, P.W.p, P.V.p);
+            const size_t sh = (size_t)r * sizeof(float);
+            auto launch = [&](auto kern) {
+                kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
+                                                            lv.gtab.p, lv.gtab_omax, P.W.p, P.V.p);
+            };
+            switch (p) {
+                case 2: launch(m2l_kron_kernel<2>); break;
+                case 3: launch(m2l_kron_kernel<3>); break;
+                case 4: launch(m2l_kron_kernel<4>); break;
+                case 5: launch(m2l_kron_kernel<5>); break;
+                case 6: launch(m2l_kron_kernel<6>); break;
+                case 7: launch(m2l_kron_kernel<7>); break;
+                case 8: launch(m2l_kron_kernel<8>); break;
+                default: fail(F3M_ERR_UNSUPPORTED, "interp_nodes must be in [2,8]");
+            }
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[3], st));

@@ -28,6 +28,9 @@ struct f3m_level {
     f3m::DevBuf<uint32_t> fpos;         // [ntiles][189][32] source rank or 0xffffffff; on such a
                                         // depth this table IS the far list (far_col stays empty)
     f3m::DevBuf<uint32_t> gpos;         // [nb] tile position (tile*32 + lane) of every box
+    // depths without tables: 1-D factors of the node-to-node kernel matrix, [2*omax+1][p][p]
+    f3m::DevBuf<float> gtab;
+    int gtab_omax = 0;
     // node weights / node potentials kept per depth when they are passed between depths
     f3m::DevBuf<float> Wl, Vl;          // [nb*64]
 };
@@ -96,6 +99,7 @@ void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st);            // slot tables
 void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st);  // kernel matrices, tiles, empty fpos
 bool run_m2l_tables(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);   // false: no tables
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
+void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of the other depths
 // far list of a table depth as CSR columns (ascending inside a row), device buffer of far_sz entries
 int64_t m2l_far_point_pairs(const f3m_plan_s &P, int level, hipStream_t st);
 void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);

@@ -652,6 +652,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         while (P.tree_lmin > 2 && P.lev[P.tree_lmin - 1].far_sz > 0) --P.tree_lmin;
         upload_transfer(P, st);
     }
+    upload_kron_tables(P, st);
     int64_t max_nb = 0, max_chunks = 0;
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
