@@ -939,7 +939,7 @@ void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
     for (int k = 0; k < p; ++k) s[k] = p > 1 ? std::cos(M_PI * (double)k / (double)(p - 1)) : 0.0;
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
-        if (lv.far_sz == 0 || lv.m2l_tables) continue;
+        if (lv.far_sz == 0) continue;
         const double half = 0.5 * (double)P.E / (double)(1ull << l);
         const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
         std::vector<float> g((size_t)(2 * omax + 1) * p * p);
@@ -1107,7 +1107,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         for (int l = P.tree_lmin; l <= L; ++l) {
             hipEvent_t *ev = level_events(l);
             F3M_HIP(hipEventRecord(ev[2], st));
-            if (!run_m2l_tables(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st)) fail(F3M_ERR_HIP, "internal: depth without M2L tables");
+            if (!run_m2l_stencil(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st) &&
+                !run_m2l_tables(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st))
+                fail(F3M_ERR_HIP, "internal: depth without M2L tables");
             F3M_HIP(hipEventRecord(ev[3], st));
         }
         for (int l = P.tree_lmin + 1; l <= L; ++l) {

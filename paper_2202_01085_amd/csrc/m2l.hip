@@ -311,4 +311,175 @@ bool run_m2l_tables(f3m_plan_s &P, int level, const float *W, float *V, hipStrea
     return true;
 }
 
+// ------------------------------------------------------------------------------------
+// M2L by sum factorisation over the candidate grid (D = 3, 4 nodes per dimension, far ratio 2).
+//
+// The Gaussian is a product over dimensions and the nodes are a tensor grid, so the node-to-node
+// matrix of a far pair with cell offset o is G_{o_z} x G_{o_y} x G_{o_x} (Kronecker product of
+// 4 x 4 factors, G_o[i][j] = exp(-(l/2)^2 (2 o + s_j - s_i)^2 / (2 gamma^2))).  The candidates
+// of a target are the children of the boxes near its parent: a 6 x 6 x 6 grid of cells around
+// the parent, of which the 3 x 3 x 3 block around the target is near and the rest far.  Hence
+//   V_t = sum_cz G_{o_z} [ sum_cy G_{o_y} [ sum_{cx far} G_{o_x} W_(cx,cy,cz) ] ]
+// with the x factor applied once per far candidate (189), the y factor once per line of the
+// grid (36) and the z factor once per plane (6): the same sums as 189 dense 64 x 64 products,
+// reordered, in 231 x 256 instead of 189 x 4096 multiply-adds.
+//
+// One workgroup per parent box: its 8 wavefronts first copy the node weights of all
+// candidates (<= 216 rows of 64 floats, read once per parent instead of once per target)
+// into LDS at their grid position, then wavefront w handles the child with parity w: lane =
+// node (ix + 4 iy + 16 iz).  The x factor needs the other three entries of the lane's quad:
+// DPP quad permutations; the y and z factors use ds_bpermute.  The factor entries a lane
+// needs (6 candidate coordinates x 4 rotations x 3 dimensions) sit in registers.
+// ------------------------------------------------------------------------------------
+constexpr int ST_CAND = 216;
+
+template <int CTRL>
+__device__ inline float dpp_quad(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+__global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__restrict__ up_near_ptr,
+                                                          const uint32_t *__restrict__ up_near_col,
+                                                          const uint32_t *__restrict__ up_cstart,
+                                                          const int32_t *__restrict__ up_cell,
+                                                          const int32_t *__restrict__ cell,
+                                                          const uint32_t *__restrict__ key, int64_t nparents,
+                                                          int64_t per_xcd, const float *__restrict__ G,
+                                                          const float *__restrict__ W, float *__restrict__ V) {
+    __shared__ float rows[ST_CAND * 64];
+    __shared__ int present[ST_CAND];
+    __shared__ uint32_t cand[ST_CAND];      // candidate k of near parent j at [8 j + k]: rank or ~0
+    __shared__ int cpos[ST_CAND];           // its position in the 6 x 6 x 6 grid
+    __shared__ uint32_t qfirst[27], qcount[27];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // consecutive parents (neighbours in space) on the same XCD, so that its L2 serves the overlap
+    const int64_t bi = block_index2();
+    const int64_t pb = (bi & 7) * per_xcd + (bi >> 3);
+    if ((bi >> 3) >= per_xcd || pb >= nparents) return;
+    // the boxes near the parent (at most 27 with far ratio 2) and their child ranges
+    if (tid < 27) {
+        const uint64_t e = up_near_ptr[pb] + tid;
+        uint32_t first = 0, count = 0;
+        if (e < up_near_ptr[pb + 1]) {
+            const uint32_t q = up_near_col[e];
+            first = up_cstart[q];
+            count = up_cstart[q + 1] - first;
+        }
+        qfirst[tid] = first;
+        qcount[tid] = count;
+    }
+    if (tid < ST_CAND) present[tid] = 0;
+    __syncthreads();
+    if (tid < ST_CAND) {
+        const int j = tid >> 3, k = tid & 7;
+        uint32_t c = 0xFFFFFFFFu;
+        if ((uint32_t)k < qcount[j]) {
+            c = qfirst[j] + k;
+            const int px = cell[(int64_t)c * 3] - 2 * up_cell[pb * 3] + 2,
+                      py = cell[(int64_t)c * 3 + 1] - 2 * up_cell[pb * 3 + 1] + 2,
+                      pz = cell[(int64_t)c * 3 + 2] - 2 * up_cell[pb * 3 + 2] + 2;
+            const int pos = px + 6 * py + 36 * pz;     // in [0, 216): the near box is within one cell of the parent
+            cpos[tid] = pos;
+            present[pos] = 1;
+        }
+        cand[tid] = c;
+    }
+    __syncthreads();
+    // node weights of the candidates into LDS: 27 rows per wavefront, all loads in flight together
+    {
+        float tmp[27];
+#pragma unroll
+        for (int i = 0; i < 27; ++i) {
+            const uint32_t c = cand[w + 8 * i];
+            tmp[i] = W[(int64_t)(c == 0xFFFFFFFFu ? 0u : c) * 64 + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < 27; ++i)
+            if (cand[w + 8 * i] != 0xFFFFFFFFu) rows[cpos[w + 8 * i] * 64 + lane] = tmp[i];
+    }
+    __syncthreads();
+    // the child with parity w, if it exists (no barrier below this point)
+    uint32_t t = 0xFFFFFFFFu;
+    for (uint32_t c = up_cstart[pb]; c < up_cstart[pb + 1]; ++c)
+        if ((key[c] & 7u) == (uint32_t)w) t = c;
+    if (t == 0xFFFFFFFFu) return;
+    const int tx = w & 1, ty = (w >> 1) & 1, tz = w >> 2;
+    // far and present candidates, one bit each
+    uint64_t mask[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int m = lane + 64 * k;
+        bool ok = false;
+        if (m < ST_CAND) {
+            const int ox = m % 6 - 2 - tx, oy = (m / 6) % 6 - 2 - ty, oz = m / 36 - 2 - tz;
+            ok = present[m] != 0 && ox * ox + oy * oy + oz * oz >= 4;
+        }
+        mask[k] = __ballot(ok);
+    }
+    const int ix = lane & 3, iy = (lane >> 2) & 3, iz = lane >> 4;
+    // factor entries: candidate coordinate c (offset c - 2 - t_d), rotation k -> G_o[i][(i + k) % 4]
+    float fx[6][4], fy[6][4], fz[6][4];
+#pragma unroll
+    for (int c = 0; c < 6; ++c)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            fx[c][k] = G[(c + 1 - tx) * 16 + ix * 4 + ((ix + k) & 3)];
+            fy[c][k] = G[(c + 1 - ty) * 16 + iy * 4 + ((iy + k) & 3)];
+            fz[c][k] = G[(c + 1 - tz) * 16 + iz * 4 + ((iz + k) & 3)];
+        }
+    int ylane[4], zlane[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        ylane[k] = ix + 4 * ((iy + k) & 3) + 16 * iz;
+        zlane[k] = ix + 4 * iy + 16 * ((iz + k) & 3);
+    }
+    float acc = 0.f;
+#pragma unroll
+    for (int cz = 0; cz < 6; ++cz) {
+        float plane = 0.f;
+#pragma unroll
+        for (int cy = 0; cy < 6; ++cy) {
+            float line = 0.f;
+            // the six rows of the line are read unconditionally (rows of absent candidates hold
+            // stale data and are skipped below), so one wait covers them
+            float v[6];
+#pragma unroll
+            for (int cx = 0; cx < 6; ++cx) v[cx] = rows[(cx + 6 * cy + 36 * cz) * 64 + lane];
+#pragma unroll
+            for (int cx = 0; cx < 6; ++cx) {
+                const int m = cx + 6 * cy + 36 * cz;
+                if ((mask[m >> 6] >> (m & 63)) & 1ull) {
+                    // line += sum_k fx[cx][k] * (entry k places further in the lane's quad); the
+                    // row value comes straight from the LDS read, so no vector-ALU write
+                    // precedes the DPP reads of it
+                    asm("v_fmac_f32 %0, %2, %1\n\t"
+                        "v_fmac_f32_dpp %0, %1, %3 quad_perm:[1,2,3,0] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                        "v_fmac_f32_dpp %0, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                        "v_fmac_f32_dpp %0, %1, %5 quad_perm:[3,0,1,2] row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                        : "+v"(line)
+                        : "v"(v[cx]), "v"(fx[cx][0]), "v"(fx[cx][1]), "v"(fx[cx][2]), "v"(fx[cx][3]));
+                }
+            }
+            plane = fmaf(fy[cy][0], line, plane);
+#pragma unroll
+            for (int k = 1; k < 4; ++k) plane = fmaf(fy[cy][k], __shfl(line, ylane[k], 64), plane);
+        }
+        acc = fmaf(fz[cz][0], plane, acc);
+#pragma unroll
+        for (int k = 1; k < 4; ++k) acc = fmaf(fz[cz][k], __shfl(plane, zlane[k], 64), acc);
+    }
+    V[(int64_t)t * 64 + lane] = acc;
+}
+
+bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st) {
+    if (!m2l_tables_apply(P) || level < 1) return false;
+    f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
+    if (lv.gtab.p == nullptr || lv.gtab_omax != 3) return false;
+    const int64_t per_xcd = cdiv(up.nb, 8);
+    m2l_stencil_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p, up.cell.p,
+                                                                lv.cell.p, lv.key.p, up.nb, per_xcd, lv.gtab.p, W, V);
+    F3M_HIP(hipGetLastError());
+    return true;
+}
+
 }  // namespace f3m

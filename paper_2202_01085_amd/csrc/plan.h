@@ -98,6 +98,7 @@ bool m2l_tables_apply(const f3m_plan_s &P);                      // D = 3, 4 nod
 void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st);            // slot tables
 void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st);  // kernel matrices, tiles, empty fpos
 bool run_m2l_tables(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);   // false: no tables
+bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);  // false: does not apply
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of the other depths
 // far list of a table depth as CSR columns (ascending inside a row), device buffer of far_sz entries
