@@ -191,11 +191,11 @@ f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind, uint64
     return guarded([&] {
         const f3m_level &lv = plan->lev[level];
         copy_to_host(row_ptr_host, kind ? lv.far_ptr.p : lv.near_ptr.p, (size_t)lv.nb + 1);
-        if (kind && lv.m2l_tables) {
-            // this depth keeps its far pairs in the positional table of the MFMA M2L
+        if (kind && lv.far_implicit) {
+            // this depth keeps only the lengths of its far rows
             f3m::DevBuf<uint32_t> cols;
             cols.alloc((size_t)lv.far_sz);
-            f3m::m2l_materialize_far(*plan, level, cols.p, nullptr);
+            f3m::materialize_far(*plan, level, cols.p, nullptr);
             copy_to_host(cols_host, cols.p, (size_t)lv.far_sz);
         } else {
             copy_to_host(cols_host, kind ? lv.far_col.p : lv.near_col.p, (size_t)(kind ? lv.far_sz : lv.near_sz));

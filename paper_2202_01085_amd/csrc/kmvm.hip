@@ -929,7 +929,7 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
     }
 }
 
-// per depth without M2L tables: the 1-D factor matrices of m2l_kron_kernel, built in fp64
+// per depth with far pairs: the 1-D factor matrices of the node-to-node kernel matrix, built in fp64
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
     const int p = P.p;
     int m = 0;   // largest near offset in one dimension: m^2 < T
@@ -1045,7 +1045,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         }
         F3M_HIP(hipEventRecord(ev[1], st));
         F3M_HIP(hipEventRecord(ev[2], st));
-        if (!run_m2l_tables(P, l, P.W.p, P.V.p, st)) {
+        if (!(lv.far_implicit && run_m2l_stencil(P, l, P.W.p, P.V.p, st))) {
             const size_t sh = (size_t)r * sizeof(float);
             auto launch = [&](auto kern) {
                 kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
@@ -1107,9 +1107,8 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         for (int l = P.tree_lmin; l <= L; ++l) {
             hipEvent_t *ev = level_events(l);
             F3M_HIP(hipEventRecord(ev[2], st));
-            if (!run_m2l_stencil(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st) &&
-                !run_m2l_tables(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st))
-                fail(F3M_ERR_HIP, "internal: depth without M2L tables");
+            if (!run_m2l_stencil(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st))
+                fail(F3M_ERR_HIP, "internal: depth outside the candidate-grid M2L");
             F3M_HIP(hipEventRecord(ev[3], st));
         }
         for (int l = P.tree_lmin + 1; l <= L; ++l) {

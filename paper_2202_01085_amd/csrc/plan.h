@@ -18,17 +18,10 @@ struct f3m_level {
     int64_t nchunks = 0;
     f3m::DevBuf<uint32_t> chunk_box;    // [nchunks]
     f3m::DevBuf<uint32_t> chunk_first;  // [nb+1] first chunk of each box
-    // table-driven M2L (m2l.hip): node-to-node kernel matrices per cell offset, targets
-    // grouped by parity into tiles of 32, far sources by (tile, offset slot, lane)
-    bool m2l_tables = false;
-    f3m::DevBuf<float> ktab;            // [343][16][64][4] matrices in MFMA operand order
-    int64_t ntiles = 0;
-    uint32_t tile_base[9] = {0};        // first tile of each parity class (tile_base[8] = ntiles)
-    f3m::DevBuf<uint32_t> tile_box;     // [ntiles*32] target rank per tile lane (0xffffffff = padding)
-    f3m::DevBuf<uint32_t> fpos;         // [ntiles][189][32] source rank or 0xffffffff; on such a
-                                        // depth this table IS the far list (far_col stays empty)
-    f3m::DevBuf<uint32_t> gpos;         // [nb] tile position (tile*32 + lane) of every box
-    // depths without tables: 1-D factors of the node-to-node kernel matrix, [2*omax+1][p][p]
+    // D = 3, 4 nodes/dim, far ratio 2: the M2L enumerates the far partners on the candidate grid
+    // around the parent (m2l.hip); far_ptr keeps the row lengths, far_col stays empty
+    bool far_implicit = false;
+    // 1-D factors of the node-to-node kernel matrix, [2*omax+1][p][p]
     f3m::DevBuf<float> gtab;
     int gtab_omax = 0;
     // node weights / node potentials kept per depth when they are passed between depths
@@ -60,8 +53,6 @@ struct f3m_plan_s {
     int64_t ntiles = 0;
     f3m::DevBuf<uint32_t> tile_box, tile_first;   // [ntiles], [nb_L+1]
     f3m_level lev[F3M_MAX_LEVELS + 1];
-    f3m::DevBuf<int32_t> slot_of;       // [8][343] offset index -> slot of a parity class (-1: not far)
-    f3m::DevBuf<int32_t> slot_oi;       // [8][189] slot -> offset index
     int tree_lmin = 0;                  // > 0: node weights/potentials are passed between depths
                                         // tree_lmin..L (D = 3, 4 nodes/dim); 0: every depth from the points
     f3m::DevBuf<float> transfer;        // [2][4][4] parent basis at the child's nodes
@@ -84,25 +75,16 @@ int quant_depth(int D);
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);
 void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far_point_pairs, once (synchronises)
+void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);   // far rows of an implicit depth
 // kmvm.hip
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
 void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st);
 void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
                          int64_t m, double *y64, hipStream_t st);
-// m2l.hip
-constexpr int M2L_NOFF = 343;    // cell offsets in [-3,3]^3
-constexpr int M2L_NSLOT = 189;   // far offsets of one parity class
-constexpr int M2L_TILE = 32;     // targets per tile
-__host__ __device__ inline int off_index(int ox, int oy, int oz) { return (ox + 3) + 7 * (oy + 3) + 49 * (oz + 3); }
-bool m2l_tables_apply(const f3m_plan_s &P);                      // D = 3, 4 nodes/dim, far ratio 2
-void m2l_prepare_plan(f3m_plan_s &P, hipStream_t st);            // slot tables
-void m2l_prepare_level(f3m_plan_s &P, int level, hipStream_t st);  // kernel matrices, tiles, empty fpos
-bool run_m2l_tables(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);   // false: no tables
-bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);  // false: does not apply
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
-void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of the other depths
-// far list of a table depth as CSR columns (ascending inside a row), device buffer of far_sz entries
-int64_t m2l_far_point_pairs(const f3m_plan_s &P, int level, hipStream_t st);
-void m2l_materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);
+void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of every far depth
+// m2l.hip
+bool m2l_stencil_applies(const f3m_plan_s &P);                   // D = 3, 4 nodes/dim, far ratio 2
+bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);  // false: does not apply
 
 }  // namespace f3m

@@ -326,18 +326,10 @@ __global__ __launch_bounds__(256) void cells_kernel(const uint32_t *__restrict__
 // far iff the squared integer cell offset is >= T = ceil(theta^2)  (Sec. 3, IsFarField
 // := |delta centre| >= 2 l, divided by l).  Rows come out sorted by column rank because the
 // parent's row is sorted and children have consecutive ranks (Sec. 4.1 "Ensuring
-// interactions are sorted").  pass 0 counts, pass 1 fills.  On depths that use the
-// table-driven M2L the far partners are written straight into the positional table
-// fpos[tile][slot][lane] (slot = index of the cell offset within the box's parity class)
-// instead of far_col.
+// interactions are sorted").  pass 0 counts, pass 1 fills.  A null near_col or far_col skips
+// that side: depths whose M2L works on the candidate grid keep only the far counts, and their
+// far rows are produced on request.
 // ------------------------------------------------------------------------------------
-struct FposArg {
-    uint32_t *fpos;          // nullptr: write far_col
-    const uint32_t *gpos;    // tile position of every box
-    const int32_t *slot_of;  // [8][343]
-    const uint32_t *key;     // box keys (parity = key & 7)
-};
-
 template <int D>
 __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const uint32_t *__restrict__ parent,
                                                     const int32_t *__restrict__ cell,
@@ -347,21 +339,12 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
                                                     uint32_t *__restrict__ cnt_near, uint32_t *__restrict__ cnt_far,
                                                     const uint64_t *__restrict__ near_ptr,
                                                     const uint64_t *__restrict__ far_ptr,
-                                                    uint32_t *__restrict__ near_col, uint32_t *__restrict__ far_col,
-                                                    FposArg fa) {
+                                                    uint32_t *__restrict__ near_col, uint32_t *__restrict__ far_col) {
     int64_t a = (int64_t)blockIdx.x * 128 + threadIdx.x;
     if (a >= nb) return;
     int32_t ca[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) ca[d] = cell[a * D + d];
-    const bool to_table = D == 3 && pass && fa.fpos != nullptr;
-    uint32_t *frow = nullptr;
-    const int32_t *so = nullptr;
-    if (to_table) {
-        const uint32_t g = fa.gpos[a];
-        frow = fa.fpos + (int64_t)(g >> 5) * (M2L_NSLOT * M2L_TILE) + (g & 31);
-        so = fa.slot_of + (fa.key[a] & 7u) * M2L_NOFF;
-    }
     uint32_t P = parent[a];
     uint64_t nn = 0, nf = 0;
     uint64_t nbase = pass ? near_ptr[a] : 0, fbase = pass ? far_ptr[a] : 0;
@@ -378,17 +361,10 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
             }
             bool is_far = !all_near && d2 >= T;
             if (is_far) {
-                if (to_table) {
-                    if (D == 3) {
-                        const int slot = so[off_index(o[0], o[D > 1 ? 1 : 0], o[D > 2 ? 2 : 0])];
-                        frow[(int64_t)slot * M2L_TILE] = bq;
-                    }
-                } else if (pass) {
-                    far_col[fbase + nf] = bq;
-                }
+                if (pass && far_col) far_col[fbase + nf] = bq;
                 ++nf;
             } else {
-                if (pass) near_col[nbase + nn] = bq;
+                if (pass && near_col) near_col[nbase + nn] = bq;
                 ++nn;
             }
         }
@@ -530,7 +506,6 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     keys_b.release();
     perm_b.release();
 
-    if (m2l_tables_apply(P)) m2l_prepare_plan(P, st);
     // ---- Algorithm 1 loop: divide, new interactions, partition
     int cap = P.Lq;
     if (P.max_depth > 0 && P.max_depth < cap) cap = P.max_depth;
@@ -600,7 +575,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             unsigned grid = (unsigned)cdiv(lv.nb, 128);
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
                                                              up.near_col.p, up.cstart.p, P.T, P.force_all_near, cn.p,
-                                                             cf.p, nullptr, nullptr, nullptr, nullptr, FposArg{});
+                                                             cf.p, nullptr, nullptr, nullptr, nullptr);
             F3M_HIP(hipGetLastError());
             uint64_t tn = 0, tf = 0;
             exclusive_scan(U32In{cn.p}, lv.nb, PtrOut{lv.near_ptr.p}, &tn, st);
@@ -610,11 +585,10 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lv.near_sz = (int64_t)tn;
             lv.far_sz = (int64_t)tf;
             lv.near_col.alloc((size_t)tn, tally);
-            FposArg fa{};
-            if (tf > 0 && m2l_tables_apply(P)) {
-                // the far pairs of this depth live in the positional table of the MFMA M2L
-                m2l_prepare_level(P, l, st);
-                fa = FposArg{lv.fpos.p, lv.gpos.p, P.slot_of.p, lv.key.p};
+            if (tf > 0 && m2l_stencil_applies(P)) {
+                // the M2L of this depth enumerates the far partners itself (candidate grid around the
+                // parent): only the row lengths are kept
+                lv.far_implicit = true;
                 lv.far_col.alloc(0, tally);
             } else {
                 lv.far_col.alloc((size_t)tf, tally);
@@ -622,8 +596,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
                                                              up.near_col.p, up.cstart.p, P.T, P.force_all_near, nullptr,
                                                              nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
-                                                             lv.far_col.p, fa);
-            lv.gpos.release();
+                                                             lv.far_implicit ? nullptr : lv.far_col.p);
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
@@ -645,9 +618,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
 
     // ---- work splits and workspaces
     F3M_HIP(hipEventRecord(ea, st));
-    // With the table-driven M2L on the last depth (D = 3, 4 nodes/dim) node weights and node
-    // potentials are passed between depths, so only the last depth streams the points.
-    if (P.L >= 2 && P.lev[P.L].m2l_tables) {
+    // With D = 3 and 4 nodes per dimension node weights and node potentials are passed between
+    // depths, so only the last depth streams the points.
+    if (P.L >= 2 && P.lev[P.L].far_implicit) {
         P.tree_lmin = P.L;
         while (P.tree_lmin > 2 && P.lev[P.tree_lmin - 1].far_sz > 0) --P.tree_lmin;
         upload_transfer(P, st);
@@ -691,6 +664,29 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     P.have_plan_times = true;
 }
 
+// Far rows (CSR columns, ascending) of a depth that keeps only their lengths: the fill pass of
+// the list kernel with the near side switched off.  cols_dev holds far_sz entries.
+void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st) {
+    const f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
+    const unsigned grid = (unsigned)cdiv(lv.nb, 128);
+    auto launch = [&](auto kern) {
+        kern<<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p, up.near_col.p,
+                                               up.cstart.p, P.T, P.force_all_near, nullptr, nullptr, lv.near_ptr.p,
+                                               lv.far_ptr.p, nullptr, cols_dev);
+    };
+    switch (P.D) {
+        case 1: launch(lists_kernel<1>); break;
+        case 2: launch(lists_kernel<2>); break;
+        case 3: launch(lists_kernel<3>); break;
+        case 4: launch(lists_kernel<4>); break;
+        case 5: launch(lists_kernel<5>); break;
+        case 6: launch(lists_kernel<6>); break;
+        default: launch(lists_kernel<7>); break;
+    }
+    F3M_HIP(hipGetLastError());
+    F3M_HIP(hipStreamSynchronize(st));
+}
+
 // Point pairs behind the near list of the last depth and the far lists of every depth (for
 // reports and the coverage identity near + far = n^2); computed on first request because it
 // re-reads every list.
@@ -706,8 +702,13 @@ void compute_far_point_pairs(f3m_plan_s &P) {
         f3m_level &lv = P.lev[l];
         lv.far_point_pairs = 0;
         if (lv.far_sz == 0) continue;
-        if (lv.m2l_tables) {
-            lv.far_point_pairs = m2l_far_point_pairs(P, l, nullptr);
+        if (lv.far_implicit) {
+            DevBuf<uint32_t> cols;
+            cols.alloc((size_t)lv.far_sz);
+            materialize_far(P, l, cols.p, nullptr);
+            ScanState S;
+            scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, cols.p}, lv.nb, S, true, nullptr);
+            lv.far_point_pairs = (int64_t)S.total;
         } else {
             ScanState S;
             scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, lv.far_col.p}, lv.nb, S, true, nullptr);
