@@ -332,6 +332,150 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
     if (kt < kend) ys[kt] = res;
 }
 
+// The same near-field kernel for D = 3, with the source operands prepared for 64 sources at a
+// time: lane l loads source jb + l, splits its four components (2g w_x, 2g w_y, 2g w_z,
+// -g|w|^2) into packed fp16 pairs hi01, hi23, lo01, lo23, and one v_permlane32_swap per pair
+// turns (hi, lo) into the operand registers of two blocks of 32 sources at once:
+//   swap(hi, lo): hi' = [hi of sources 0-31 | lo of sources 0-31]   -> block A, both lane halves
+//                 lo' = [hi of sources 32-63 | lo of sources 32-63] -> block B
+// Inner dimension of the MFMA (k = 8 half + e): source side half 0 = (hi, hi), half 1 = (lo, lo);
+// target side half 0 = (hi, lo), half 1 = (hi, 0): hi*hi + hi*lo + lo*hi, the fourth product
+// meets a zero.  The right-hand sides are loaded per block of 32 as in the general kernel.
+__global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                        const uint32_t *__restrict__ start,
+                                                        const int32_t *__restrict__ cell,
+                                                        const uint64_t *__restrict__ near_ptr,
+                                                        const uint32_t *__restrict__ near_col,
+                                                        const uint32_t *__restrict__ tile_box,
+                                                        const uint32_t *__restrict__ tile_first, int64_t ntiles,
+                                                        float g, float inv_l, CentreArg C, float *__restrict__ ys) {
+    constexpr int D = 3, NC = 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
+    if (t >= ntiles) return;
+    const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
+    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    const uint32_t kend = start[a + 1];
+    const bool two = __builtin_amdgcn_readfirstlane((int)(kend - k0)) > 32;
+    const int nn = lane & 31, kk = lane >> 5;
+    float ctr[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) ctr[d] = (float)(C.alpha[d] + ((double)cell[(int64_t)a * D + d] + 0.5) * C.edge);
+
+    // B operands: the targets of the two column blocks
+    h8v Bop[2];
+    float ni[2];
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const uint32_t kt = k0 + cb * 32 + nn;
+        const float valid = kt < kend ? 1.f : 0.f;   // loads are in bounds (padding), masked by a factor
+        float u[NC];
+        float s = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            u[d] = (Xs[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
+            s = fmaf(u[d], u[d], s);
+        }
+        u[D] = 1.f;
+        ni[cb] = -g * s;
+        Bop[cb] = split_operand<NC, false>(u, 0, kk);
+    }
+    float acc0 = 0.f, acc1 = 0.f;
+    const float g2l = 2.f * g * inv_l;
+    const float nrm = -0.25f / g;
+
+    uint64_t e = near_ptr[a];
+    const uint64_t e1 = near_ptr[a + 1];
+    auto next_run = [&](uint32_t &jb, uint32_t &je) {
+        uint32_t q = near_col[e];
+        jb = start[q];
+        ++e;
+        while (e < e1 && near_col[e] == q + 1) { ++q; ++e; }
+        je = start[q + 1];
+    };
+    auto load_x = [&](uint32_t jb, float (&x)[D]) {
+        const uint32_t j = jb + lane;
+#pragma unroll
+        for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)j * D + d];
+    };
+    auto load_b = [&](uint32_t jb, float4u (&bq)[4]) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) bq[q4] = *reinterpret_cast<const float4u *>(bs + jb + 8 * q4 + 4 * kk);
+    };
+    // operands of the two blocks of 32 sources that start at jb (run end je)
+    auto prepare = [&](uint32_t jb, uint32_t je, const float (&x)[D], h8v &opA, h8v &opB) {
+        const bool live = jb + lane < je;
+        float w[NC];
+        float s = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            w[d] = (x[d] - ctr[d]) * (live ? g2l : 0.f);     // 2 g w_d
+            s = fmaf(w[d], w[d], s);
+        }
+        w[D] = live ? s * nrm : -60000.f;                    // -g |w|^2
+        const uint32_t hi01 = pack_f16(w[0], w[1]), hi23 = pack_f16(w[2], w[3]);
+        const f2v b01 = unpack_f16(hi01), b23 = unpack_f16(hi23);
+        const uint32_t lo01 = pack_f16(w[0] - b01.x, w[1] - b01.y), lo23 = pack_f16(w[2] - b23.x, w[3] - b23.y);
+        const auto s01 = __builtin_amdgcn_permlane32_swap(hi01, lo01, false, false);
+        const auto s23 = __builtin_amdgcn_permlane32_swap(hi23, lo23, false, false);
+        u4v ra, rb;
+        ra.x = s01[0]; ra.y = s23[0]; ra.z = s01[0]; ra.w = s23[0];
+        rb.x = s01[1]; rb.y = s23[1]; rb.z = s01[1]; rb.w = s23[1];
+        opA = __builtin_bit_cast(h8v, ra);
+        opB = __builtin_bit_cast(h8v, rb);
+    };
+    auto block = [&](const h8v &op, const float4u (&bq)[4]) {
+        f16v c0 = {0.f};
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[0], c0, 0, 0, 0);
+        if (two) {
+            f16v c1 = {0.f};
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], c1, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bq[v >> 2].v[v & 3], acc1);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
+        }
+    };
+    // steps of 64 sources; the coordinates of the next step and the right-hand sides of the
+    // next block are in flight while the current block is worked on.  All loads are
+    // unconditional and in bounds (64 points of padding), so their number in flight is fixed.
+    float xc[D], xn[D];
+    float4u ba[4], bb[4];
+    uint32_t jb, je;
+    next_run(jb, je);
+    load_x(jb, xc);
+    load_b(jb, ba);
+    for (;;) {
+        uint32_t njb = jb + 64, nje = je;
+        bool more = true;
+        if (njb >= je) {
+            if (e < e1) next_run(njb, nje);
+            else more = false;
+        }
+        const uint32_t pjb = more ? njb : jb;   // a harmless address when there is no next step
+        load_x(pjb, xn);
+        load_b(jb + 32, bb);
+        h8v opA, opB;
+        prepare(jb, je, xc, opA, opB);
+        block(opA, ba);
+        load_b(pjb, ba);
+        if (jb + 32 < je) block(opB, bb);
+        if (!more) break;
+#pragma unroll
+        for (int d = 0; d < D; ++d) xc[d] = xn[d];
+        jb = njb;
+        je = nje;
+    }
+    acc0 += __shfl_xor(acc0, 32, 64);
+    acc1 += __shfl_xor(acc1, 32, 64);
+    const float res = kk ? __builtin_amdgcn_exp2f(ni[1]) * acc1 : __builtin_amdgcn_exp2f(ni[0]) * acc0;
+    const uint32_t kt = k0 + kk * 32 + nn;
+    if (kt < kend) ys[kt] = res;
+}
+
 // exact product, all pairs (Sec. 2, KeOps paragraph): lane = target, sources wave-uniform
 template <int D>
 __global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X, const float *__restrict__ b,
@@ -991,7 +1135,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
         const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
         const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024;
-        if (gram)
+        if (gram && D == 3)
+            p2p_gram3_kernel<<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
+                P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, P.yn.p);
+        else if (gram)
             p2p_mfma_kernel<D><<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
                 P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, P.yn.p);
