@@ -288,6 +288,48 @@ struct ParentOut {
     }
 };
 
+// Divide from the depth above (used while boxes are much fewer than points): the children of a
+// box are sub-intervals of its sorted interval, found by binary search on the key prefix.
+// lb[P * 2^D + c] = first point of parent P whose depth-l key is >= (key_P << D | c).
+template <int D>
+__global__ __launch_bounds__(256) void child_bounds_kernel(const uint32_t *__restrict__ keys, int shift,
+                                                           const uint32_t *__restrict__ up_start, int64_t nslots,
+                                                           const uint32_t *__restrict__ up_key, uint32_t *__restrict__ lb) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nslots) return;
+    const int64_t P = idx >> D;
+    const uint32_t c = (uint32_t)(idx & ((1 << D) - 1));
+    uint32_t lo = up_start[P], hi = up_start[P + 1];
+    if (c != 0) {
+        const uint64_t want = ((uint64_t)up_key[P] << D) | c;
+        while (lo < hi) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            if (((uint64_t)keys[mid] >> shift) < want) lo = mid + 1;
+            else hi = mid;
+        }
+    }
+    lb[idx] = lo;
+}
+struct ChildIn {
+    const uint32_t *lb;   // [nslots + 1]
+    __device__ uint64_t operator()(int64_t i) const { return lb[i + 1] != lb[i]; }
+};
+template <int D>
+struct ChildOut {
+    const uint32_t *lb, *up_key;
+    uint32_t *start, *bkey, *parent, *cstart_up;
+    __device__ void operator()(int64_t i, uint64_t ex, uint64_t v) const {
+        const int64_t P = i >> D;
+        const uint32_t c = (uint32_t)(i & ((1 << D) - 1));
+        if (c == 0) cstart_up[P] = (uint32_t)ex;
+        if (v) {
+            start[ex] = lb[i];
+            bkey[ex] = (uint32_t)(((uint64_t)up_key[P] << D) | c);
+            parent[ex] = (uint32_t)P;
+        }
+    }
+};
+
 __global__ void set_u32_kernel(uint32_t *p, uint32_t v) { *p = v; }
 __global__ void set_u64_kernel(uint64_t *p, uint64_t v) { *p = v; }
 
@@ -519,16 +561,41 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     for (;; ++l) {
         f3m_level &lv = P.lev[l];
         F3M_HIP(hipEventRecord(ea, st));
-        // divide: heads of runs of equal depth-l keys
+        // divide: heads of runs of equal depth-l keys, from the points or, once the boxes of the
+        // depth above are few against the points, from their intervals
         int shift = D * (P.Lq - l);
-        HeadIn hin{P.keys.p, shift};
-        ScanState S;
-        scan_prepare(hin, n, S, true, st);
-        lv.nb = (int64_t)S.total;
-        lv.key.alloc((size_t)lv.nb, tally);
-        lv.start.alloc((size_t)lv.nb + 1, tally);
-        scan_finish(hin, n, S, HeadOut{P.keys.p, shift, lv.start.p, lv.key.p}, st);
-        set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
+        const bool from_parents = l > 0 && (P.lev[l - 1].nb << D) <= n / 4;
+        if (from_parents) {
+            f3m_level &up = P.lev[l - 1];
+            const int64_t nslots = up.nb << D;
+            DevBuf<uint32_t> lb;
+            lb.alloc((size_t)nslots + 1);
+            child_bounds_kernel<D><<<dim3((unsigned)cdiv(nslots, 256)), dim3(256), 0, st>>>(P.keys.p, shift, up.start.p,
+                                                                                          nslots, up.key.p, lb.p);
+            F3M_HIP(hipGetLastError());
+            set_u32_kernel<<<1, 1, 0, st>>>(lb.p + nslots, (uint32_t)n);
+            ChildIn cin{lb.p};
+            ScanState S;
+            scan_prepare(cin, nslots, S, true, st);
+            lv.nb = (int64_t)S.total;
+            lv.key.alloc((size_t)lv.nb, tally);
+            lv.start.alloc((size_t)lv.nb + 1, tally);
+            lv.parent.alloc((size_t)lv.nb, tally);
+            up.cstart.alloc((size_t)up.nb + 1, tally);
+            scan_finish(cin, nslots, S, ChildOut<D>{lb.p, up.key.p, lv.start.p, lv.key.p, lv.parent.p, up.cstart.p}, st);
+            set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
+            set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
+            F3M_HIP(hipStreamSynchronize(st));   // lb is released on leaving the scope
+        } else {
+            HeadIn hin{P.keys.p, shift};
+            ScanState S;
+            scan_prepare(hin, n, S, true, st);
+            lv.nb = (int64_t)S.total;
+            lv.key.alloc((size_t)lv.nb, tally);
+            lv.start.alloc((size_t)lv.nb + 1, tally);
+            scan_finish(hin, n, S, HeadOut{P.keys.p, shift, lv.start.p, lv.key.p}, st);
+            set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
+        }
         {
             int grid = (int)std::min<int64_t>(1024, cdiv(lv.nb, 256));
             max_count_kernel<<<dim3(grid), dim3(256), 0, st>>>(lv.start.p, lv.nb, part.p);
@@ -541,8 +608,10 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         lv.cell.alloc((size_t)lv.nb * D, tally);
         cells_kernel<D><<<dim3((unsigned)cdiv(lv.nb, 256)), dim3(256), 0, st>>>(lv.key.p, lv.nb, l, lv.cell.p);
         F3M_HIP(hipGetLastError());
-        lv.parent.alloc((size_t)lv.nb, tally);
-        if (l > 0) {
+        if (from_parents) {
+            // parent ranks and child intervals came with the division
+        } else if (l > 0) {
+            lv.parent.alloc((size_t)lv.nb, tally);
             f3m_level &up = P.lev[l - 1];
             up.cstart.alloc((size_t)up.nb + 1, tally);
             HeadIn pin{lv.key.p, D};
@@ -551,6 +620,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             if ((int64_t)tot != up.nb) fail(F3M_ERR_HIP, "internal: parent count mismatch");
             set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
         } else {
+            lv.parent.alloc((size_t)lv.nb, tally);
             F3M_HIP(hipMemsetAsync(lv.parent.p, 0, sizeof(uint32_t), st));
         }
         F3M_HIP(hipEventRecord(eb, st));
