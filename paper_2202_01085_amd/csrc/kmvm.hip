@@ -1287,8 +1287,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     }
     if (P.side) F3M_HIP(hipStreamWaitEvent(st, P.ev_join, 0));
     F3M_HIP(hipEventRecord(P.ev[11], st));
-    scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, P.perm.p, n, y);
-    F3M_HIP(hipGetLastError());
+    if (!permute_out_bucketed(P, y, st)) {
+        scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, P.perm.p, n, y);
+        F3M_HIP(hipGetLastError());
+    }
     if (!P.ev[12]) F3M_HIP(hipEventCreate(&P.ev[12]));
     F3M_HIP(hipEventRecord(P.ev[12], st));
     P.have_kmvm_times = true;

@@ -56,6 +56,11 @@ struct f3m_plan_s {
     int tree_lmin = 0;                  // > 0: node weights/potentials are passed between depths
                                         // tree_lmin..L (D = 3, 4 nodes/dim); 0: every depth from the points
     f3m::DevBuf<float> transfer;        // [2][4][4] parent basis at the child's nodes
+    // un-permutation through buckets of destinations (large n): tile offsets of the radix scatter on the
+    // top 8 bits of perm, and the bucketed (destination, value) pairs
+    f3m::DevBuf<uint32_t> po_offs, po_key, po_val;
+    int po_shift = 0;
+    int64_t po_nblk = 0;
 
     hipEvent_t ev[16] = {nullptr};
     std::vector<hipEvent_t> far_events;   // 6 per depth, around the far-field kernels of that depth
@@ -75,6 +80,7 @@ int quant_depth(int D);
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);
 void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far_point_pairs, once (synchronises)
+bool permute_out_bucketed(f3m_plan_s &P, float *y, hipStream_t st);   // false: n too small, use the plain scatter
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);   // far rows of an implicit depth
 // kmvm.hip
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);

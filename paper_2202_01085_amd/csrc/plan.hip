@@ -140,7 +140,9 @@ __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__res
                                                            const uint32_t *__restrict__ vals_in,
                                                            uint32_t *__restrict__ keys_out,
                                                            uint32_t *__restrict__ vals_out, int64_t n, int shift,
-                                                           const uint32_t *__restrict__ offs, int64_t nblk) {
+                                                           const uint32_t *__restrict__ offs, int64_t nblk,
+                                                           const float *__restrict__ fa,
+                                                           const float *__restrict__ fb) {
     constexpr int NW = RS_NT / 64;
     __shared__ uint32_t wcnt[NW][256];      // per wave: keys of each digit seen so far
     __shared__ uint32_t dstart[256];        // first tile-local position of each digit
@@ -159,7 +161,8 @@ __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__res
         const int64_t i = base + r * 64 + lane;
         const bool valid = i < n;
         key[r] = valid ? keys_in[i] : 0u;
-        val[r] = valid ? (vals_in ? vals_in[i] : (uint32_t)i) : 0u;
+        // value: the bits of fa[i] + fb[i], or vals_in[i], or the position itself
+        val[r] = !valid ? 0u : fa ? __float_as_uint(fa[i] + fb[i]) : vals_in ? vals_in[i] : (uint32_t)i;
     }
 #pragma unroll
     for (int r = 0; r < RS_IPT; ++r) {
@@ -234,13 +237,58 @@ static bool radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uin
         rs_hist_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, n, shift, hist.p, nblk);
         F3M_HIP(hipGetLastError());
         exclusive_scan(U32In{hist.p}, nblk * 256, U32Out{hist.p}, nullptr, st);
-        rs_scatter_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk);
+        rs_scatter_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk,
+                                                                        nullptr, nullptr);
         F3M_HIP(hipGetLastError());
         in_b = !in_b;
         first = false;
     }
     F3M_HIP(hipStreamSynchronize(st));
     return in_b;
+}
+
+// ------------------------------------------------------------------------------------
+// result back to the caller's order, y[perm[k]] = ys[k] + yn[k] (Sec. 3, after eq. (1)).
+// A plain scatter writes 4 bytes into 1e9 random cache lines (8x write amplification).  For
+// large n the pairs (perm[k], value) are first bucketed by the top 8 bits of the destination
+// with the stable radix scatter above (streaming reads and writes), so that the final
+// scatter works through one window of n/256 destinations at a time, which the caches hold.
+// The tile offsets depend on perm only and are computed once per plan.
+// ------------------------------------------------------------------------------------
+void permute_out_prepare(f3m_plan_s &P, hipStream_t st) {
+    const int64_t n = P.n;
+    if (n < (1ll << 24)) return;
+    int bits = 0;
+    while (((int64_t)1 << bits) < n) ++bits;
+    P.po_shift = bits > 8 ? bits - 8 : 0;
+    P.po_nblk = cdiv(n, RS_TILE);
+    P.po_offs.alloc((size_t)P.po_nblk * 256, &P.bytes);
+    P.po_key.alloc((size_t)n, &P.bytes);
+    P.po_val.alloc((size_t)n, &P.bytes);
+    rs_hist_kernel<<<dim3((unsigned)P.po_nblk), dim3(RS_NT), 0, st>>>(P.perm.p, n, P.po_shift, P.po_offs.p, P.po_nblk);
+    F3M_HIP(hipGetLastError());
+    exclusive_scan(U32In{P.po_offs.p}, P.po_nblk * 256, U32Out{P.po_offs.p}, nullptr, st);
+}
+
+__global__ __launch_bounds__(256) void scatter_pairs_kernel(const uint32_t *__restrict__ dest,
+                                                            const uint32_t *__restrict__ val, int64_t n,
+                                                            float *__restrict__ y) {
+    const int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    if (i < n) y[dest[i]] = __uint_as_float(val[i]);
+}
+
+bool permute_out_bucketed(f3m_plan_s &P, float *y, hipStream_t st) {
+    if (!P.po_offs.p) return false;
+    const int64_t n = P.n;
+    rs_scatter_kernel<<<dim3((unsigned)P.po_nblk), dim3(RS_NT), 0, st>>>(P.perm.p, nullptr, P.po_key.p, P.po_val.p, n,
+                                                                        P.po_shift, P.po_offs.p, P.po_nblk, P.ys.p,
+                                                                        P.yn.p);
+    F3M_HIP(hipGetLastError());
+    const int64_t blocks = cdiv(n, 256);
+    const dim3 grid = blocks <= 65536 ? dim3((unsigned)blocks) : dim3(65536u, (unsigned)cdiv(blocks, 65536));
+    scatter_pairs_kernel<<<grid, dim3(256), 0, st>>>(P.po_key.p, P.po_val.p, n, y);
+    F3M_HIP(hipGetLastError());
+    return true;
 }
 
 __global__ void iota_kernel(uint32_t *p, int64_t n) {
@@ -696,6 +744,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         upload_transfer(P, st);
     }
     upload_kron_tables(P, st);
+    permute_out_prepare(P, st);
     int64_t max_nb = 0, max_chunks = 0;
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
