@@ -730,7 +730,7 @@ __device__ inline void weights34(const float *__restrict__ x, const double (&ctr
     lagrange4((float)(((double)x[2] - ctr[2]) * inv_half), Lz);
 }
 
-constexpr int TR_STRIDE = 68;  // floats per lane row in the LDS transpose (16-byte aligned, bank-shifted)
+constexpr int TR_STRIDE = 36;  // floats per lane row in the LDS transpose of 32 accumulators (16-byte aligned, bank-shifted)
 
 __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
                                                    const uint32_t *__restrict__ start, const int32_t *__restrict__ cell,
@@ -770,21 +770,31 @@ __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs,
             }
         }
     }
-    // sum over lanes: lane l writes its row, lane i adds column i
-#pragma unroll
-    for (int g = 0; g < 16; ++g)
-        *reinterpret_cast<float4 *>(&tr[lane * TR_STRIDE + 4 * g]) = make_float4(acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]);
-    __syncthreads();
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-    for (int row = 0; row < 64; row += 4) {
-        s0 += tr[(row + 0) * TR_STRIDE + lane];
-        s1 += tr[(row + 1) * TR_STRIDE + lane];
-        s2 += tr[(row + 2) * TR_STRIDE + lane];
-        s3 += tr[(row + 3) * TR_STRIDE + lane];
-    }
+    // sum over lanes, 32 nodes at a time (half the LDS, twice the resident wavefronts): lane l
+    // writes its row; lane (i, part) adds rows 32 part .. 32 part + 31 of column i, and the two
+    // parts meet through one shuffle
     float *dst = nch == 1 ? W + (int64_t)a * 64 : Wpart + c * 64;
-    dst[lane] = (s0 + s1) + (s2 + s3);
+    const int i = lane & 31, part = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        if (q) __syncthreads();
+#pragma unroll
+        for (int g = 0; g < 8; ++g)
+            *reinterpret_cast<float4 *>(&tr[lane * TR_STRIDE + 4 * g]) =
+                make_float4(acc[32 * q + 4 * g], acc[32 * q + 4 * g + 1], acc[32 * q + 4 * g + 2], acc[32 * q + 4 * g + 3]);
+        __syncthreads();
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+        for (int row = 0; row < 32; row += 4) {
+            s0 += tr[(32 * part + row + 0) * TR_STRIDE + i];
+            s1 += tr[(32 * part + row + 1) * TR_STRIDE + i];
+            s2 += tr[(32 * part + row + 2) * TR_STRIDE + i];
+            s3 += tr[(32 * part + row + 3) * TR_STRIDE + i];
+        }
+        float t = (s0 + s1) + (s2 + s3);
+        t += __shfl_xor(t, 32, 64);
+        if (part == 0) dst[32 * q + i] = t;
+    }
 }
 
 __global__ __launch_bounds__(64) void l2p34_kernel(const float *__restrict__ Xs, const uint32_t *__restrict__ start,
