@@ -332,15 +332,20 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
     if (kt < kend) ys[kt] = res;
 }
 
-// The same near-field kernel for D = 3, with the source operands prepared for 64 sources at a
-// time: lane l loads source jb + l, splits its four components (2g w_x, 2g w_y, 2g w_z,
-// -g|w|^2) into packed fp16 pairs hi01, hi23, lo01, lo23, and one v_permlane32_swap per pair
-// turns (hi, lo) into the operand registers of two blocks of 32 sources at once:
+// The near-field kernel for D = 3.  The sources of a target tile are the points of its near
+// boxes, taken as ONE dense sequence: lane r of the wavefront holds (first point, length,
+// running offsets) of near box r, and the source at sequence position p is found from that
+// table with wave-uniform lane reads, so steps of 64 sources are full except the last one.
+// Source operands are prepared for 64 sources at a time: lane l loads the source at position
+// w0 + l, splits its four components (2g w_x, 2g w_y, 2g w_z, -g|w|^2) into packed fp16 pairs
+// hi01, hi23, lo01, lo23, and one v_permlane32_swap per pair turns (hi, lo) into the operand
+// registers of two blocks of 32 sources at once:
 //   swap(hi, lo): hi' = [hi of sources 0-31 | lo of sources 0-31]   -> block A, both lane halves
 //                 lo' = [hi of sources 32-63 | lo of sources 32-63] -> block B
 // Inner dimension of the MFMA (k = 8 half + e): source side half 0 = (hi, hi), half 1 = (lo, lo);
 // target side half 0 = (hi, lo), half 1 = (hi, 0): hi*hi + hi*lo + lo*hi, the fourth product
-// meets a zero.  The right-hand sides are loaded per block of 32 as in the general kernel.
+// meets a zero.  The right-hand sides of a step pass through 64 floats of LDS per wavefront
+// (written by the lane that owns the source, read as the 16 values a lane needs per block).
 __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
                                                         const uint32_t *__restrict__ start,
                                                         const int32_t *__restrict__ cell,
@@ -350,8 +355,9 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
                                                         float g, float inv_l, CentreArg C, float *__restrict__ ys) {
     constexpr int D = 3, NC = 4;
-    const int lane = threadIdx.x & 63;
-    const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
+    __shared__ __attribute__((aligned(16))) float bbuf[4][64];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t t = block_index() * 4 + wv;
     if (t >= ntiles) return;
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
     const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
@@ -383,28 +389,10 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     float acc0 = 0.f, acc1 = 0.f;
     const float g2l = 2.f * g * inv_l;
     const float nrm = -0.25f / g;
+    float *bw = bbuf[wv];
 
-    uint64_t e = near_ptr[a];
-    const uint64_t e1 = near_ptr[a + 1];
-    auto next_run = [&](uint32_t &jb, uint32_t &je) {
-        uint32_t q = near_col[e];
-        jb = start[q];
-        ++e;
-        while (e < e1 && near_col[e] == q + 1) { ++q; ++e; }
-        je = start[q + 1];
-    };
-    auto load_x = [&](uint32_t jb, float (&x)[D]) {
-        const uint32_t j = jb + lane;
-#pragma unroll
-        for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)j * D + d];
-    };
-    auto load_b = [&](uint32_t jb, float4u (&bq)[4]) {
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) bq[q4] = *reinterpret_cast<const float4u *>(bs + jb + 8 * q4 + 4 * kk);
-    };
-    // operands of the two blocks of 32 sources that start at jb (run end je)
-    auto prepare = [&](uint32_t jb, uint32_t je, const float (&x)[D], h8v &opA, h8v &opB) {
-        const bool live = jb + lane < je;
+    // operands of the two blocks of 32 sources of a step; live = the lane's position is a source
+    auto prepare = [&](bool live, const float (&x)[D], h8v &opA, h8v &opB) {
         float w[NC];
         float s = 0.f;
 #pragma unroll
@@ -412,7 +400,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             w[d] = (x[d] - ctr[d]) * (live ? g2l : 0.f);     // 2 g w_d
             s = fmaf(w[d], w[d], s);
         }
-        w[D] = live ? s * nrm : -60000.f;                    // -g |w|^2
+        w[D] = live ? s * nrm : -60000.f;                    // -g |w|^2; a dead row gives exp2(-huge) = 0
         const uint32_t hi01 = pack_f16(w[0], w[1]), hi23 = pack_f16(w[2], w[3]);
         const f2v b01 = unpack_f16(hi01), b23 = unpack_f16(hi23);
         const uint32_t lo01 = pack_f16(w[0] - b01.x, w[1] - b01.y), lo23 = pack_f16(w[2] - b23.x, w[3] - b23.y);
@@ -424,50 +412,86 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         opA = __builtin_bit_cast(h8v, ra);
         opB = __builtin_bit_cast(h8v, rb);
     };
-    auto block = [&](const h8v &op, const float4u (&bq)[4]) {
+    // one block of 32 sources against the tile; bq = right-hand sides at bw[first .. first + 31]
+    auto block = [&](const h8v &op, int first) {
+        float4 bq[4];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) bq[q4] = *reinterpret_cast<const float4 *>(bw + first + 8 * q4 + 4 * kk);
+        const float *bf = reinterpret_cast<const float *>(bq);
         f16v c0 = {0.f};
         c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[0], c0, 0, 0, 0);
         if (two) {
             f16v c1 = {0.f};
             c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], c1, 0, 0, 0);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bq[v >> 2].v[v & 3], acc1);
+            for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bf[v], acc1);
         } else {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
         }
     };
-    // steps of 64 sources; the coordinates of the next step and the right-hand sides of the
-    // next block are in flight while the current block is worked on.  All loads are
-    // unconditional and in bounds (64 points of padding), so their number in flight is fixed.
-    float xc[D], xn[D];
-    float4u ba[4], bb[4];
-    uint32_t jb, je;
-    next_run(jb, je);
-    load_x(jb, xc);
-    load_b(jb, ba);
-    for (;;) {
-        uint32_t njb = jb + 64, nje = je;
-        bool more = true;
-        if (njb >= je) {
-            if (e < e1) next_run(njb, nje);
-            else more = false;
+
+    const uint64_t e0 = near_ptr[a], e1 = near_ptr[a + 1];
+    for (uint64_t er = e0; er < e1; er += 64) {   // rounds of up to 64 near boxes (one round with far ratio 2)
+        const int m = (int)(e1 - er < 64 ? e1 - er : 64);
+        uint32_t sfirst = 0, slen = 0;
+        if (lane < m) {
+            const uint32_t q = near_col[er + lane];
+            sfirst = start[q];
+            slen = start[q + 1] - sfirst;
         }
-        const uint32_t pjb = more ? njb : jb;   // a harmless address when there is no next step
-        load_x(pjb, xn);
-        load_b(jb + 32, bb);
-        h8v opA, opB;
-        prepare(jb, je, xc, opA, opB);
-        block(opA, ba);
-        load_b(pjb, ba);
-        if (jb + 32 < je) block(opB, bb);
-        if (!more) break;
+        uint32_t cend = slen;   // inclusive running sum of the lengths over the lanes
 #pragma unroll
-        for (int d = 0; d < D; ++d) xc[d] = xn[d];
-        jb = njb;
-        je = nje;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t up = __shfl_up(cend, d, 64);
+            if (lane >= d) cend += up;
+        }
+        const uint32_t cbeg = cend - slen;
+        const uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // sources of this round
+        if (S == 0) continue;
+        int r = 0;   // first near box that reaches into the current window (wave-uniform)
+        // source index of position w0 + lane (any in-bounds index beyond the end of the sequence)
+        auto locate = [&](uint32_t w0) {
+            const uint32_t p = w0 + lane;
+            while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;   // ends: w0 < S = cend of lane 63
+            uint32_t src = 0;
+            for (int rr = r; rr < m; ++rr) {
+                const uint32_t c0 = __builtin_amdgcn_readlane(cbeg, rr);
+                if (c0 >= w0 + 64) break;
+                const uint32_t c1 = __builtin_amdgcn_readlane(cend, rr), s0 = __builtin_amdgcn_readlane(sfirst, rr);
+                if (p >= c0 && p < c1) src = s0 + (p - c0);
+            }
+            return src;
+        };
+        float xn[D], bn;
+        {
+            const uint32_t src = locate(0);
+#pragma unroll
+            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
+            bn = bs[src];
+        }
+        for (uint32_t w0 = 0; w0 < S; w0 += 64) {
+            float xc[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) xc[d] = xn[d];
+            const float bc = bn;
+            // the loads of the next step are in flight during this one (the last step reloads a
+            // harmless address, so the number of loads in flight is fixed)
+            const uint32_t src = w0 + 64 < S ? locate(w0 + 64) : 0u;
+#pragma unroll
+            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
+            bn = bs[src];
+            const bool live = w0 + lane < S;
+            __builtin_amdgcn_wave_barrier();
+            bw[lane] = live ? bc : 0.f;
+            __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
+            h8v opA, opB;
+            prepare(live, xc, opA, opB);
+            block(opA, 0);
+            if (w0 + 32 < S) block(opB, 32);
+        }
     }
     acc0 += __shfl_xor(acc0, 32, 64);
     acc1 += __shfl_xor(acc1, 32, 64);
