@@ -150,7 +150,7 @@ def main():
         flops = (3.0 * D + 2.0) * pairs
         ach = flops / t / 1e12
         lane_slots_per_s = 256 * 64 * 2.4e9
-        rooflines["p2p"] = {"kernel": "p2p_mfma_kernel, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
+        rooflines["p2p"] = {"kernel": "p2p_gram3_kernel, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
                             "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS,
                             "traffic": None, "launch_ms": st["p2p"],
                             "pairs_per_s": pairs / t,
