@@ -57,6 +57,7 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
     __shared__ uint32_t cand[ST_CAND];      // candidate k of near parent j at [8 j + k]: rank or ~0
     __shared__ int cpos[ST_CAND];           // its position in the 6 x 6 x 6 grid
     __shared__ uint32_t qfirst[27], qcount[27];
+    __shared__ float gs[7 * 16];            // the factor table
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     // consecutive parents (neighbours in space) on the same XCD, so that its L2 serves the overlap
     const int64_t bi = block_index2();
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
         qcount[tid] = count;
     }
     if (tid < ST_CAND) present[tid] = 0;
+    if (tid >= 256 && tid < 256 + 7 * 16) gs[tid - 256] = G[tid - 256];
     __syncthreads();
     if (tid < ST_CAND) {
         const int j = tid >> 3, k = tid & 7;
@@ -110,15 +112,17 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
         if ((key[c] & 7u) == (uint32_t)w) t = c;
     if (t == 0xFFFFFFFFu) return;
     const int tx = w & 1, ty = (w >> 1) & 1, tz = w >> 2;
-    // far and present candidates, one bit each
-    uint64_t mask[4];
+    // far and present candidates, one bit each: bit cx + 8 (cy + 6 cz), so that the six bits of a
+    // line of the grid sit in one byte
+    uint64_t mask[5];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int m = lane + 64 * k;
+    for (int k = 0; k < 5; ++k) {
+        const int mm = lane + 64 * k, cx = mm & 7, ln = mm >> 3;
         bool ok = false;
-        if (m < ST_CAND) {
-            const int ox = m % 6 - 2 - tx, oy = (m / 6) % 6 - 2 - ty, oz = m / 36 - 2 - tz;
-            ok = present[m] != 0 && ox * ox + oy * oy + oz * oz >= 4;
+        if (cx < 6 && ln < 36) {
+            const int cy = ln % 6, cz = ln / 6;
+            const int ox = cx - 2 - tx, oy = cy - 2 - ty, oz = cz - 2 - tz;
+            ok = present[cx + 6 * ln] != 0 && ox * ox + oy * oy + oz * oz >= 4;
         }
         mask[k] = __ballot(ok);
     }
@@ -129,9 +133,9 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
     for (int c = 0; c < 6; ++c)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            fx[c][k] = G[(c + 1 - tx) * 16 + ix * 4 + ((ix + k) & 3)];
-            fy[c][k] = G[(c + 1 - ty) * 16 + iy * 4 + ((iy + k) & 3)];
-            fz[c][k] = G[(c + 1 - tz) * 16 + iz * 4 + ((iz + k) & 3)];
+            fx[c][k] = gs[(c + 1 - tx) * 16 + ix * 4 + ((ix + k) & 3)];
+            fy[c][k] = gs[(c + 1 - ty) * 16 + iy * 4 + ((iy + k) & 3)];
+            fz[c][k] = gs[(c + 1 - tz) * 16 + iz * 4 + ((iz + k) & 3)];
         }
     int ylane[4], zlane[4];
 #pragma unroll
@@ -151,20 +155,25 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
             float v[6];
 #pragma unroll
             for (int cx = 0; cx < 6; ++cx) v[cx] = rows[(cx + 6 * cy + 36 * cz) * 64 + lane];
+            // line += sum_k fx[cx][k] * (entry k places further in the lane's quad); the row value
+            // comes straight from the LDS read, so no vector-ALU write precedes the DPP reads of it
+            auto xfactor = [&](int cx) {
+                asm("v_fmac_f32 %0, %2, %1\n\t"
+                    "v_fmac_f32_dpp %0, %1, %3 quad_perm:[1,2,3,0] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                    "v_fmac_f32_dpp %0, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                    "v_fmac_f32_dpp %0, %1, %5 quad_perm:[3,0,1,2] row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                    : "+v"(line)
+                    : "v"(v[cx]), "v"(fx[cx][0]), "v"(fx[cx][1]), "v"(fx[cx][2]), "v"(fx[cx][3]));
+            };
+            const int ln = cy + 6 * cz;
+            const uint32_t bits = (uint32_t)(mask[ln >> 3] >> (8 * (ln & 7))) & 0x3Fu;
+            if (bits == 0x3Fu) {   // the whole line is far and present: no tests
 #pragma unroll
-            for (int cx = 0; cx < 6; ++cx) {
-                const int m = cx + 6 * cy + 36 * cz;
-                if ((mask[m >> 6] >> (m & 63)) & 1ull) {
-                    // line += sum_k fx[cx][k] * (entry k places further in the lane's quad); the
-                    // row value comes straight from the LDS read, so no vector-ALU write
-                    // precedes the DPP reads of it
-                    asm("v_fmac_f32 %0, %2, %1\n\t"
-                        "v_fmac_f32_dpp %0, %1, %3 quad_perm:[1,2,3,0] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-                        "v_fmac_f32_dpp %0, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
-                        "v_fmac_f32_dpp %0, %1, %5 quad_perm:[3,0,1,2] row_mask:0xf bank_mask:0xf bound_ctrl:1"
-                        : "+v"(line)
-                        : "v"(v[cx]), "v"(fx[cx][0]), "v"(fx[cx][1]), "v"(fx[cx][2]), "v"(fx[cx][3]));
-                }
+                for (int cx = 0; cx < 6; ++cx) xfactor(cx);
+            } else {
+#pragma unroll
+                for (int cx = 0; cx < 6; ++cx)
+                    if ((bits >> cx) & 1u) xfactor(cx);
             }
             plane = fmaf(fy[cy][0], line, plane);
 #pragma unroll
