@@ -175,9 +175,12 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
                 for (int cx = 0; cx < 6; ++cx)
                     if ((bits >> cx) & 1u) xfactor(cx);
             }
+            // y factor: the lane needs the entries 4, 8, 12 lanes further on in its row of 16
+            // lanes (cyclically): row rotations by 12, 8, 4 to the right
             plane = fmaf(fy[cy][0], line, plane);
-#pragma unroll
-            for (int k = 1; k < 4; ++k) plane = fmaf(fy[cy][k], __shfl(line, ylane[k], 64), plane);
+            plane = fmaf(fy[cy][1], dpp_quad<0x12C>(line), plane);
+            plane = fmaf(fy[cy][2], dpp_quad<0x128>(line), plane);
+            plane = fmaf(fy[cy][3], dpp_quad<0x124>(line), plane);
         }
         acc = fmaf(fz[cz][0], plane, acc);
 #pragma unroll
