@@ -177,10 +177,15 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
             }
             // y factor: the lane needs the entries 4, 8, 12 lanes further on in its row of 16
             // lanes (cyclically): row rotations by 12, 8, 4 to the right
-            plane = fmaf(fy[cy][0], line, plane);
-            plane = fmaf(fy[cy][1], dpp_quad<0x12C>(line), plane);
-            plane = fmaf(fy[cy][2], dpp_quad<0x128>(line), plane);
-            plane = fmaf(fy[cy][3], dpp_quad<0x124>(line), plane);
+            // (`line` was last written by a vector-ALU instruction: the plain multiply-add and
+            // the s_nop give the two wait states that a DPP read of it needs)
+            asm("v_fmac_f32 %0, %2, %1\n\t"
+                "s_nop 0\n\t"
+                "v_fmac_f32_dpp %0, %1, %3 row_ror:12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                "v_fmac_f32_dpp %0, %1, %4 row_ror:8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+                "v_fmac_f32_dpp %0, %1, %5 row_ror:4 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                : "+v"(plane)
+                : "v"(line), "v"(fy[cy][0]), "v"(fy[cy][1]), "v"(fy[cy][2]), "v"(fy[cy][3]));
         }
         acc = fmaf(fz[cz][0], plane, acc);
 #pragma unroll
