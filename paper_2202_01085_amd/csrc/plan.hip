@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void keys_kernel(const float *__restrict__ X, 
 // result is deterministic (ascending key, then ascending original index).
 // ------------------------------------------------------------------------------------
 constexpr int RS_NT = 256;
-constexpr int RS_IPT = 16;
+constexpr int RS_IPT = 32;
 constexpr int RS_TILE = RS_NT * RS_IPT;
 
 __global__ __launch_bounds__(RS_NT) void rs_hist_kernel(const uint32_t *__restrict__ keys, int64_t n, int shift,
