@@ -444,3 +444,101 @@ def test_config1_accuracy_gate():
     exact = oracle.direct(X, b, cfg["lengthscale"])
     y = oracle.f3m(X, b, cfg["lengthscale"], cfg["p"], cfg["theta"])
     assert np.linalg.norm(y - exact) / np.linalg.norm(exact) <= 1e-3
+
+
+# ----------------------------------------------------------------------------
+# identities that the GPU's far-field kernels rely on, checked against the oracle's own
+# kernel values and Lagrange routine (the formulas are retyped here, not shared)
+# ----------------------------------------------------------------------------
+def _node_matrix_by_oracle(D, p, o, edge, gamma):
+    """K[i][j] = k(target node i, source node j) for two boxes of the given edge whose cells
+    differ by o (source minus target), evaluated by the oracle's exact-sum routine."""
+    s = oracle.cheb2_nodes(p)
+    r = p ** D
+    grid = np.array(list(itertools.product(range(p), repeat=D)))[:, ::-1]   # flat i = sum_d i_d p^d
+    tgt = 0.5 * edge * s[grid]
+    src = edge * np.asarray(o, dtype=np.float64)[None, :] + 0.5 * edge * s[grid]
+    X = np.concatenate([tgt, src]).astype(np.float32)
+    K = np.empty((r, r))
+    for j in range(r):
+        b = np.zeros(2 * r, dtype=np.float32)
+        b[r + j] = 1.0
+        K[:, j] = oracle.rows(X, b, gamma, np.arange(r))
+    return K, X
+
+
+@pytest.mark.parametrize("D,p,o", [(3, 4, (2, -1, 0)), (3, 4, (-3, 3, 1)), (2, 3, (0, 2)), (4, 2, (1, -2, 3, 0))])
+def test_node_kernel_matrix_is_a_kronecker_product_of_1d_factors(D, p, o):
+    # Gaussian = product over dimensions, nodes = tensor grid (Sec. 3): the r x r node-to-node
+    # matrix of a far pair is G_{o_D} x ... x G_{o_1}, G_o[i][j] = exp(-(l/2)^2 (2o + s_j - s_i)^2 / (2 gamma^2)).
+    edge, gamma = 0.5, 0.8          # exactly representable coordinates: edge/2 * s is rounded to fp32 below
+    K, X = _node_matrix_by_oracle(D, p, o, edge, gamma)
+    s32 = X[: p ** D].astype(np.float64)     # the fp32-rounded node coordinates the oracle saw
+    # 1-D node coordinates as the oracle saw them: dimension d of target node with only i_d varying
+    def coords(block, d):
+        idx = [k * p ** d for k in range(p)]
+        return X[block * p ** D + np.array(idx), d].astype(np.float64)
+    kron = np.ones((1, 1))
+    for d in range(D):
+        t, q = coords(0, d), coords(1, d)
+        G = np.exp(-((q[None, :] - t[:, None]) ** 2) / (2.0 * gamma * gamma))
+        kron = np.kron(G, kron)      # dimension 0 fastest in the flat node index
+    assert np.allclose(K, kron, rtol=1e-12, atol=1e-300)
+    # and the closed form of the factor in node units (checked where fp32 rounding of the nodes is exact)
+    s = oracle.cheb2_nodes(p)
+    if p == 2 or p == 3:             # nodes +-1 (and 0): edge/2 * s exact in fp32
+        c = (0.5 * edge) ** 2 / (2.0 * gamma * gamma)
+        for d in range(D):
+            t, q = coords(0, d), coords(1, d)
+            G = np.exp(-((q[None, :] - t[:, None]) ** 2) / (2.0 * gamma * gamma))
+            Gc = np.exp(-c * (2.0 * o[d] + s[None, :] - s[:, None]) ** 2)
+            assert np.allclose(G, Gc, rtol=1e-13)
+    assert s32.shape[0] == p ** D
+
+
+def test_far_sum_factorises_over_the_candidate_grid():
+    # D = 3, far ratio 2: the candidates of a target are the 6 x 6 x 6 cells around its parent, the
+    # 3 x 3 x 3 block around the target is near (sum of squared offsets < 4 <=> all |o_d| <= 1), and
+    # sum_far (Gz x Gy x Gx) W = sum_cz Gz [ sum_cy Gy [ sum_{cx far} Gx W ] ]  for every parity.
+    rng = np.random.default_rng(5)
+    p, c = 4, 0.37
+    s = oracle.cheb2_nodes(p)
+    G = {o: np.exp(-c * (2.0 * o + s[None, :] - s[:, None]) ** 2) for o in range(-3, 4)}
+    W = rng.standard_normal((6, 6, 6, p, p, p))             # [cz][cy][cx][jz][jy][jx]
+    for tz, ty, tx in itertools.product((0, 1), repeat=3):
+        dense = np.zeros((p, p, p))
+        nfar = 0
+        fact = np.zeros((p, p, p))
+        for cz in range(6):
+            plane = np.zeros((p, p, p))
+            for cy in range(6):
+                line = np.zeros((p, p, p))
+                for cx in range(6):
+                    o = (cx - 2 - tx, cy - 2 - ty, cz - 2 - tz)
+                    far = o[0] ** 2 + o[1] ** 2 + o[2] ** 2 >= 4
+                    assert far == (max(abs(v) for v in o) > 1)
+                    if not far:
+                        continue
+                    nfar += 1
+                    dense += np.einsum("zc,yb,xa,cba->zyx", G[o[2]], G[o[1]], G[o[0]], W[cz, cy, cx])
+                    line += np.einsum("xa,cba->cbx", G[o[0]], W[cz, cy, cx])
+                plane += np.einsum("yb,cbx->cyx", G[cy - 2 - ty], line)
+            fact += np.einsum("zc,cyx->zyx", G[cz - 2 - tz], plane)
+        assert nfar == 189
+        assert np.allclose(dense, fact, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 5])
+def test_parent_basis_is_reproduced_by_the_child_bases(p):
+    # Passing node weights up (and node potentials down) between depths is exact: the parent's
+    # basis function restricted to a child box is a polynomial of degree p-1, which the child's own
+    # p-node interpolant reproduces: L^parent_i(t_par) = sum_j L^parent_i(child node j) L^child_j(t_child).
+    s = oracle.cheb2_nodes(p)
+    rng = np.random.default_rng(p)
+    for half in (-1.0, 1.0):                       # lower / upper child in this dimension
+        T = np.array([oracle.lagrange_product(p, 0.5 * (sj + half)) for sj in s])    # T[j][i]
+        for tc in rng.uniform(-1, 1, size=7):
+            tp = 0.5 * (tc + half)
+            lhs = oracle.lagrange_product(p, tp)
+            rhs = T.T @ oracle.lagrange_product(p, tc)
+            assert np.allclose(lhs, rhs, rtol=0, atol=1e-13)
