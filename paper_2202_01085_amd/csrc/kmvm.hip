@@ -1203,8 +1203,6 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         if (lv.far_sz == 0 || (tree && l >= P.tree_lmin)) continue;
         hipEvent_t *ev = level_events(l);
         const CentreArg C = make_centre(P, l);
-        const double half = 0.5 * C.edge;
-        const float nc2h = (float)(-1.4426950408889634 * half * half / (2.0 * (double)P.gamma * (double)P.gamma));
         F3M_HIP(hipEventRecord(ev[0], st));
         {
             size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
