@@ -41,8 +41,14 @@ def lib():
         L.oracle_quant_depth.restype = c_int
         L.oracle_tree_build.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int]
         L.oracle_tree_build.restype = c_vp
+        L.oracle_tree_build_ex.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int, c_dbl, c_dbl]
+        L.oracle_tree_build_ex.restype = c_vp
+        L.oracle_is_smooth_depth.argtypes = [c_dbl, c_int, c_int, c_dbl, c_dbl]
+        L.oracle_is_smooth_depth.restype = c_int
+        L.oracle_adaptive_nodes.argtypes = [c_dbl, c_int, c_dbl, c_int]
+        L.oracle_adaptive_nodes.restype = c_int
         L.oracle_tree_free.argtypes = [c_vp]
-        for name in ("oracle_tree_depth", "oracle_tree_quant_depth"):
+        for name in ("oracle_tree_depth", "oracle_tree_quant_depth", "oracle_tree_smooth_depth"):
             getattr(L, name).argtypes = [c_vp]
             getattr(L, name).restype = c_int
         L.oracle_tree_edge.argtypes = [c_vp]
@@ -60,6 +66,8 @@ def lib():
         L.oracle_p2m_level.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_vp]
         L.oracle_f3m_apply.argtypes = [c_vp, c_vp, c_dbl, c_int, c_int, c_int, c_vp, c_vp, c_int]
         L.oracle_f3m_apply.restype = c_int
+        L.oracle_f3m_apply_ex.argtypes = [c_vp, c_vp, c_dbl, c_int, c_int, c_int, c_vp, c_vp, c_int, c_int]
+        L.oracle_f3m_apply_ex.restype = c_int
         _lib = L
     return _lib
 
@@ -122,14 +130,17 @@ def quant_depth(D):
 class Tree:
     """Partition + interaction lists of Algorithm 1 for one point set."""
 
-    def __init__(self, X, theta=2.0, zeta=128, max_depth=0, force_all_near=False):
+    def __init__(self, X, theta=2.0, zeta=128, max_depth=0, force_all_near=False, gamma=0.0, eta_smooth=0.0):
+        """eta_smooth > 0 switches the smooth field of Sec. 4.3 on (needs the lengthscale gamma)."""
         self.X = _f32(X)
         self.n, self.D = self.X.shape
-        self._h = lib().oracle_tree_build(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
-                                          int(max_depth), int(bool(force_all_near)))
+        self._h = lib().oracle_tree_build_ex(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
+                                             int(max_depth), int(bool(force_all_near)), float(gamma),
+                                             float(eta_smooth))
         if not self._h:
             raise ValueError("oracle_tree_build rejected its arguments")
         self.L = int(lib().oracle_tree_depth(self._h))
+        self.smooth_depth = int(lib().oracle_tree_smooth_depth(self._h))
         self.Lq = int(lib().oracle_tree_quant_depth(self._h))
         self.E = float(lib().oracle_tree_edge(self._h))
         a = np.empty(self.D, dtype=np.float64)
@@ -182,16 +193,21 @@ class Tree:
         lib().oracle_p2m_level(self._h, _ptr(self.X), _ptr(b), p, level, _ptr(W))
         return W
 
-    def apply(self, b, gamma, p, kernel_id=0, kparam=0, literal=False):
+    def apply(self, b, gamma, p, kernel_id=0, kparam=0, literal=False, adaptive=False):
         b = _f32(b)
         y = np.empty(self.n, dtype=np.float64)
-        rc = lib().oracle_f3m_apply(self._h, _ptr(self.X), float(gamma), int(p), kernel_id, kparam,
-                                    _ptr(b), _ptr(y), int(bool(literal)))
+        rc = lib().oracle_f3m_apply_ex(self._h, _ptr(self.X), float(gamma), int(p), kernel_id, kparam,
+                                       _ptr(b), _ptr(y), int(bool(literal)), int(bool(adaptive)))
         if rc:
             raise ValueError("oracle_f3m_apply rejected its arguments")
         return y
 
 
-def f3m(X, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False):
+def adaptive_nodes(E, depth, gamma, p):
+    """Nodes per dimension of a depth under the adaptive far-field rule of Sec. 4.3 (0 = dropped)."""
+    return int(lib().oracle_adaptive_nodes(float(E), int(depth), float(gamma), int(p)))
+
+
+def f3m(X, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False, eta_smooth=0.0, adaptive=False):
     """CPU F3M product (fp64), original point order."""
-    return Tree(X, theta, zeta, max_depth, force_all_near).apply(b, gamma, p)
+    return Tree(X, theta, zeta, max_depth, force_all_near, gamma, eta_smooth).apply(b, gamma, p, adaptive=adaptive)

@@ -215,6 +215,9 @@ typedef struct {
     uint64_t *pkey;    /* [n] key at depth Lq, PERMUTED order            */
     int64_t *perm;     /* [n] perm[k] = original index of the k-th point in box order */
     olevel lev[ORACLE_MAX_LEVELS + 1];
+    /* smooth field (Sec. 4.3): depth at which every adjacent pair is interpolated, or -1 */
+    int smooth_depth;
+    double gamma;      /* lengthscale the smooth rule was evaluated with (0: rule off) */
 } otree;
 
 /* quantisation depth: as deep as a 32-bit key allows, at most 20 */
@@ -322,7 +325,7 @@ static int64_t max_box(const olevel *lv)
 /* New interactions at depth l from the near pairs of depth l-1, split into
  * near and far (reading R4).  Rows come out sorted because the parent's row is
  * sorted and the children of a box have consecutive ranks. */
-static void new_interactions(otree *t, int l, double theta, int force_all_near)
+static void new_interactions(otree *t, int l, double theta, int force_all_near, int all_interpolated)
 {
     olevel *lv = &t->lev[l], *up = &t->lev[l - 1];
     int D = t->D;
@@ -353,7 +356,8 @@ static void new_interactions(otree *t, int l, double theta, int force_all_near)
                     double d2 = 0.0;
                     for (int d = 0; d < D; ++d)
                         d2 += (double)((cb[d] - ca[d]) * (cb[d] - ca[d]));
-                    int is_far = !force_all_near && d2 >= theta * theta;
+                    /* smooth depth: adjacent pairs are interpolated too (Sec. 4.3) */
+                    int is_far = all_interpolated || (!force_all_near && d2 >= theta * theta);
                     if (is_far) {
                         if (pass) fcol[nf] = bq;
                         ++nf;
@@ -371,10 +375,47 @@ static void new_interactions(otree *t, int l, double theta, int force_all_near)
     }
 }
 
+/* Smoothness criterion with the O(1) bound of Sec. 4.3: the effective variance of a box of
+ * edge l is at most D l^2 / (8 gamma^2) (variance <= l^2/4 per dimension), two boxes give
+ * D l^2 / (4 gamma^2); adjacent pairs of a depth are interpolated when that is <= eta. */
+int oracle_is_smooth_depth(double E, int depth, int D, double gamma, double eta_smooth)
+{
+    if (!(eta_smooth > 0.0) || !(gamma > 0.0))
+        return 0;
+    double l = E / ldexp(1.0, depth);
+    return (double)D * l * l / (4.0 * gamma * gamma) <= eta_smooth;
+}
+
+/* Adaptive far-field rule of Sec. 4.3 on q = l^2 / (2 gamma^2), l the box edge of the depth:
+ * nodes per dimension min(p, 3) if q <= 0.01 (the paper's min(r, 3^D) on a tensor grid),
+ * p if 0.01 < q <= 5, and 0 (the far pairs of the depth are dropped) if q > 5. */
+int oracle_adaptive_nodes(double E, int depth, double gamma, int p)
+{
+    double l = E / ldexp(1.0, depth);
+    double q = l * l / (2.0 * gamma * gamma);
+    if (q <= 0.01)
+        return p < 3 ? p : 3;
+    if (q <= 5.0)
+        return p;
+    return 0;
+}
+
+otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                            int force_all_near, double gamma, double eta_smooth);
+
 /* Builds the partition and the interaction lists of Algorithm 1 (everything
  * that does not depend on b).  Returns NULL on bad arguments. */
 otree *oracle_tree_build(const float *X, int64_t n, int D, double theta,
                          int64_t zeta, int max_depth, int force_all_near)
+{
+    return oracle_tree_build_ex(X, n, D, theta, zeta, max_depth, force_all_near, 0.0, 0.0);
+}
+
+/* The same with the smooth field of Sec. 4.3 (eta_smooth > 0): at the first depth whose boxes
+ * pass the smoothness criterion every pair left is put on the far (interpolated) list, the
+ * near list of that depth is empty and the loop of Algorithm 1 ends there. */
+otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                            int force_all_near, double gamma, double eta_smooth)
 {
     if (!X || n <= 0 || D < 1 || D > ORACLE_MAX_D || !(theta > 0.0) || zeta < 1)
         return NULL;
@@ -382,6 +423,8 @@ otree *oracle_tree_build(const float *X, int64_t n, int D, double theta,
     t->n = n;
     t->D = D;
     t->Lq = oracle_quant_depth(D);
+    t->smooth_depth = -1;
+    t->gamma = eta_smooth > 0.0 ? gamma : 0.0;
 
     /* enclosing cube: per-dim minimum, edge = largest extent (fp32, R2) */
     float Ef = 0.0f;
@@ -440,7 +483,10 @@ otree *oracle_tree_build(const float *X, int64_t n, int D, double theta,
     while (t->lev[l].near_ptr[t->lev[l].nb] > 0 && max_box(&t->lev[l]) > zeta && l < cap) {
         ++l;
         divide(t, l);
-        new_interactions(t, l, theta, force_all_near);
+        int smooth = !force_all_near && oracle_is_smooth_depth(t->E, l, D, gamma, eta_smooth);
+        new_interactions(t, l, theta, force_all_near, smooth);
+        if (smooth)
+            t->smooth_depth = l;
     }
     t->L = l;
     return t;
@@ -448,6 +494,7 @@ otree *oracle_tree_build(const float *X, int64_t n, int D, double theta,
 
 /* ---- introspection ---- */
 int oracle_tree_depth(const otree *t) { return t->L; }
+int oracle_tree_smooth_depth(const otree *t) { return t->smooth_depth; }
 int oracle_tree_quant_depth(const otree *t) { return t->Lq; }
 double oracle_tree_edge(const otree *t) { return t->E; }
 void oracle_tree_alpha(const otree *t, double *alpha)
@@ -589,21 +636,38 @@ void oracle_p2m_level(const otree *t, const float *X, const float *b, int p,
  *   literal == 1: every far pair is handled on its own, v1 -> v2 -> v, exactly
  *                 as a single far-field product is described (small inputs).
  * y is in ORIGINAL point order, fp64. */
+int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
+                        const float *b, double *y, int literal, int adaptive);
+
 int oracle_f3m_apply(const otree *t, const float *X, double gamma, int p,
                      int kernel_id, int kparam, const float *b, double *y, int literal)
 {
-    if (!t || !X || !b || !y || p < 2 || p > 32)
+    return oracle_f3m_apply_ex(t, X, gamma, p, kernel_id, kparam, b, y, literal, 0);
+}
+
+/* adaptive != 0: the node count of every depth follows oracle_adaptive_nodes (Sec. 4.3,
+ * adaptive far-field approximation; a depth with 0 nodes contributes nothing). */
+int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
+                        const float *b, double *y, int literal, int adaptive)
+{
+    if (!t || !X || !b || !y || p_all < 2 || p_all > 32)
         return 1;
+    if (t->gamma != 0.0 && t->gamma != gamma)
+        return 2; /* the smooth rule of the tree was evaluated with another lengthscale */
     int D = t->D;
-    int64_t n = t->n, r = ipow(p, D);
-    double s[32];
-    oracle_cheb2_nodes(p, s);
+    int64_t n = t->n;
     double *ys = (double *)calloc((size_t)n, sizeof(double)); /* permuted order */
 
     for (int l = 1; l <= t->L; ++l) {
         const olevel *lv = &t->lev[l];
         if (lv->far_ptr[lv->nb] == 0)
             continue;
+        int p = adaptive ? oracle_adaptive_nodes(t->E, l, gamma, p_all) : p_all;
+        if (p == 0)
+            continue; /* interactions too far from each other are thrown away (Algorithm 1) */
+        int64_t r = ipow(p, D);
+        double s[32];
+        oracle_cheb2_nodes(p, s);
         double *W = NULL;
         if (!literal) {
             W = (double *)malloc(sizeof(double) * (size_t)lv->nb * (size_t)r);

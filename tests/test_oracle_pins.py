@@ -542,3 +542,155 @@ def test_parent_basis_is_reproduced_by_the_child_bases(p):
             lhs = oracle.lagrange_product(p, tp)
             rhs = T.T @ oracle.lagrange_product(p, tc)
             assert np.allclose(lhs, rhs, rtol=0, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# smooth field and adaptive far-field rule (Sec. 4.3)
+# ----------------------------------------------------------------------------
+def test_smooth_rule_closed_form_depths():
+    # D l^2 / (4 gamma^2) <= eta with l = E / 2^depth.  E = 1, D = 3, gamma = 1, eta = 0.5:
+    # depth 0 gives 0.75 (not smooth), depth 1 gives 0.1875 (smooth).
+    L = oracle.lib()
+    assert L.oracle_is_smooth_depth(1.0, 0, 3, 1.0, 0.5) == 0
+    assert L.oracle_is_smooth_depth(1.0, 1, 3, 1.0, 0.5) == 1
+    # equality counts as smooth: D = 1, l = 1, gamma = 0.5 -> 1 / (4 * 0.25) = 1.0
+    assert L.oracle_is_smooth_depth(1.0, 0, 1, 0.5, 1.0) == 1
+    assert L.oracle_is_smooth_depth(1.0, 0, 1, 0.5, 0.999) == 0
+    # rule off
+    assert L.oracle_is_smooth_depth(1.0, 5, 3, 1.0, 0.0) == 0
+
+
+def test_smooth_depth_interpolates_every_pair_and_ends_the_loop():
+    X = inputs.points_uniform(3000, 3, 11).numpy()
+    X[0] = 0.0
+    X[1] = 1.0                      # E = 1 exactly
+    T = oracle.Tree(X, theta=2.0, zeta=16, gamma=1.0, eta_smooth=0.5)
+    assert T.L == 1 and T.smooth_depth == 1
+    assert len(T.interactions(1, 0)[1]) == 0                  # no near pair left
+    ptr, cols = T.interactions(1, 1)
+    assert np.array_equal(np.diff(ptr), np.full(8, 8))        # all 8 x 8 ordered pairs, self pairs included
+    assert np.array_equal(cols.reshape(8, 8), np.tile(np.arange(8), (8, 1)))
+    # a tighter limit moves the smooth depth down: 3 l^2 / 4 <= 0.02 -> l <= 0.163 -> depth 3
+    T2 = oracle.Tree(X, theta=2.0, zeta=1, gamma=1.0, eta_smooth=0.02)
+    assert T2.smooth_depth == 3 and T2.L == 3
+    # coverage: every ordered point pair is handled exactly once, all of them by interpolation
+    total = 0
+    for l in range(1, T2.L + 1):
+        cnt = np.diff(T2.boxes(l)[1])
+        ptr, cols = T2.interactions(l, 1)
+        total += int((np.repeat(cnt, np.diff(ptr)) * cnt[cols]).sum())
+    assert total == 3000 * 3000 and len(T2.interactions(T2.L, 0)[1]) == 0
+    # the loop also ends on the box-size rule before the smooth depth is reached
+    T3 = oracle.Tree(X, theta=2.0, zeta=4000, gamma=1.0, eta_smooth=0.5)
+    assert T3.L == 0 and T3.smooth_depth == -1
+
+
+def test_smooth_field_equals_dense_interpolated_matrix():
+    # With every pair interpolated at depth 1 the product is  y = A b,
+    #   A[i][j] = sum_{a,c} L_a(t_i) k(s_a^{box(i)}, s_c^{box(j)}) L_c(t_j),
+    # written out here as a dense n x n matrix in numpy (2-D, 3 nodes per dimension).
+    n, D, p, gamma = 240, 2, 3, 1.3
+    X = inputs.points_uniform(n, D, 12).numpy()
+    X[0] = 0.0
+    X[1] = 1.0
+    b = inputs.rhs_normal(n, 13).numpy()
+    T = oracle.Tree(X, theta=2.0, zeta=8, gamma=gamma, eta_smooth=0.5)   # 2 l^2 / (4 * 1.69) <= 0.5 at depth 0?  l = 1: 0.296
+    # depth 0 is never interpolated (the rule is applied to the pairs created by a division): depth 1
+    assert T.smooth_depth == 1
+    y = T.apply(b, gamma, p)
+    s = oracle.cheb2_nodes(p)
+    half = 0.25
+    Xd = X.astype(np.float64)
+    cell = np.minimum((Xd * 2).astype(int), 1)
+    centre = (cell + 0.5) * 0.5
+    tt = (Xd - centre) / half
+    Lw = np.empty((n, p * p))
+    nodes = np.empty((n, p * p, D))
+    for i in range(n):
+        l0, l1 = oracle.lagrange_product(p, tt[i, 0]), oracle.lagrange_product(p, tt[i, 1])
+        Lw[i] = np.outer(l1, l0).ravel()                       # flat index = i0 + p i1
+        g0, g1 = centre[i, 0] + half * s, centre[i, 1] + half * s
+        nodes[i, :, 0] = np.tile(g0, p)
+        nodes[i, :, 1] = np.repeat(g1, p)
+    A = np.zeros((n, n))
+    for i in range(n):
+        d2 = ((nodes[i][None, :, None, :] - nodes[:, None, :, :]) ** 2).sum(-1)    # [j][a][c]
+        K = np.exp(-d2 / (2 * gamma * gamma))
+        A[i] = np.einsum("a,jac,jc->j", Lw[i], K, Lw)
+    assert np.allclose(y, A @ b.astype(np.float64), rtol=1e-11, atol=1e-11)
+
+
+def test_smooth_field_exact_for_low_degree_kernels():
+    # all pairs interpolated, self pairs included: still exact for kernels of degree < p per coordinate
+    X = inputs.points_normal(1500, 3, 14).numpy()
+    b = inputs.rhs_normal(1500, 15).numpy()
+    want = oracle.direct(X, b, 1.0, kernel_id=2, kparam=3)
+    E = float(np.max(X.max(0) - X.min(0)))
+    T = oracle.Tree(X, theta=2.0, zeta=32, gamma=E, eta_smooth=0.1)      # smooth at depth 2: 3 (E/4)^2 / (4 E^2) = 0.047
+    assert T.smooth_depth == 2 and len(T.interactions(T.L, 0)[1]) == 0
+    got = T.apply(b, E, 4, kernel_id=2, kparam=3)
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-10 * np.abs(want).max())
+
+
+def test_smooth_field_error_shrinks_with_the_limit_and_with_the_nodes():
+    X, b, _ = inputs.make_config(1, n=6000)
+    X, b = X.numpy(), b.numpy()
+    ye = oracle.direct(X, b, 1.0)
+    rel = lambda y: np.linalg.norm(y - ye) / np.linalg.norm(ye)
+    errs = [rel(oracle.f3m(X, b, 1.0, 4, eta_smooth=eta)) for eta in (0.5, 0.1)]
+    assert errs[0] < 2e-3 and errs[1] < errs[0] / 3
+    by_p = [rel(oracle.f3m(X, b, 1.0, p, eta_smooth=0.5)) for p in (2, 3, 4, 5)]
+    assert all(by_p[k + 1] < by_p[k] / 2 for k in range(3))
+
+
+def test_adaptive_rule_thresholds_closed_form():
+    # q = l^2 / (2 gamma^2): <= 0.01 -> min(p, 3); <= 5 -> p; above -> 0
+    g = 1.0 / math.sqrt(2.0)          # q = l^2
+    assert oracle.adaptive_nodes(1.0, 0, g, 6) == 6            # q = 1
+    assert oracle.adaptive_nodes(4.0, 1, g, 6) == 6            # l = 2, q = 4
+    assert oracle.adaptive_nodes(4.0, 0, g, 6) == 0            # l = 4, q = 16
+    assert oracle.adaptive_nodes(1.0, 4, g, 6) == 3            # l = 1/16, q = 0.0039
+    assert oracle.adaptive_nodes(1.0, 4, g, 2) == 2            # never more than p
+    assert oracle.adaptive_nodes(1.0, 3, g, 6) == 6            # l = 1/8, q = 0.0156
+    assert oracle.adaptive_nodes(2.0, 0, 1.0, 5) == 5          # q = 2
+    assert oracle.adaptive_nodes(4.0, 0, 1.0, 5) == 0          # q = 8
+
+
+def test_adaptive_far_field_bands():
+    X = inputs.points_uniform(4000, 3, 16).numpy()
+    X[0] = 0.0
+    X[1] = 1.0
+    b = inputs.rhs_normal(4000, 17).numpy()
+    T = oracle.Tree(X, theta=2.0, zeta=24)                     # depths 1..3, far pairs at 2 and 3
+    assert T.L == 3
+    # middle band at every far depth (q = l^2 / (2 gamma^2) in (0.01, 5]): nothing changes
+    g = 0.3                                                     # depth 2: q = 0.35, depth 3: q = 0.087
+    assert np.array_equal(T.apply(b, g, 5, adaptive=True), T.apply(b, g, 5))
+    # smooth kernel (q <= 0.01 at depths 2 and 3): 3 nodes per dimension whatever p is
+    g = 2.0                                                     # depth 2: q = 0.0078
+    assert np.array_equal(T.apply(b, g, 5, adaptive=True), T.apply(b, g, 3))
+    # sharp kernel (q > 5 at depths 2 and 3): the far field is thrown away, the near field stays
+    g = 0.03                                                    # depth 3: q = 8.7
+    y = T.apply(b, g, 4, adaptive=True)
+    perm = T.perm()
+    keys, starts = T.boxes(T.L)
+    ptr, cols = T.interactions(T.L, 0)
+    Xd, bd = X.astype(np.float64), b.astype(np.float64)
+    want = np.zeros(4000)
+    for a in range(len(keys)):
+        src = np.concatenate([perm[starts[q]:starts[q + 1]] for q in cols[ptr[a]:ptr[a + 1]]])
+        tgt = perm[starts[a]:starts[a + 1]]
+        d2 = ((Xd[tgt][:, None, :] - Xd[src][None, :, :]) ** 2).sum(-1)
+        want[tgt] = np.exp(-d2 / (2 * g * g)) @ bd[src]
+    assert np.allclose(y, want, rtol=1e-12, atol=1e-14)
+    # mixed: depth 2 in the middle band, depth 3 with 3 nodes -> sum of the two depth contributions
+    g = 0.9                                                     # depth 2: q = 0.0386, depth 3: q = 0.0096
+    assert oracle.adaptive_nodes(T.E, 2, g, 5) == 5 and oracle.adaptive_nodes(T.E, 3, g, 5) == 3
+    y = T.apply(b, g, 5, adaptive=True)
+    T2 = oracle.Tree(X, theta=2.0, zeta=24, max_depth=2)       # the same tree cut at depth 2
+    far2_plus_near2 = T2.apply(b, g, 5)
+    y3 = T.apply(b, g, 3)                                       # depth 2 and 3 with 3 nodes
+    y3_cut = T2.apply(b, g, 3)                                  # depth 2 with 3 nodes + exact near(2)
+    # y = far2(p=5) + far3(p=3) + near3 ;  y3 = far2(p=3) + far3(p=3) + near3
+    # far2(p=5) - far2(p=3) = far2_plus_near2 - y3_cut  (the exact near(2) part cancels)
+    assert np.allclose(y - y3, far2_plus_near2 - y3_cut, rtol=0, atol=1e-11 * np.abs(y).max())
