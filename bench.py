@@ -54,6 +54,9 @@ def main():
     ap.add_argument("--rows", type=int, default=10000, help="sampled rows for the error against the exact product")
     ap.add_argument("--cpu-sample", type=int, default=400000, help="points of the CPU oracle sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--eta-smooth", type=float, default=0.0,
+                    help="smooth-field limit of Sec. 4.3 (0 = off, the headline configuration; the paper uses 0.5)")
+    ap.add_argument("--adaptive-far", action="store_true", help="adaptive far-field node rule of Sec. 4.3")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first copy 1 GiB device-to-device with a plain kernel: the reference that the "
                          "FETCH_SIZE / WRITE_SIZE counter readings of a rocprofv3 --pmc run are scaled by")
@@ -86,7 +89,8 @@ def main():
         del src, dst
 
     def step():
-        plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"])
+        plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"], eta_smooth=args.eta_smooth,
+                        adaptive_far=args.adaptive_far)
         plan.kmvm(b, y)
         return plan
 
@@ -195,7 +199,9 @@ def main():
         "config": {"workload": "config %d: n=%d D=%d %s, Gaussian lengthscale %g, b~N(0,1), %d nodes/dim, far ratio %g"
                                % (k, n, cfg["D"], cfg["dist"], cfg["lengthscale"], cfg["p"], cfg["theta"]),
                    "depth": L, "leaf_max": 128, "boxes_leaf": int(inf.nboxes[L]), "near_pairs_leaf": int(inf.near_pairs[L]),
-                   "far_pairs_leaf": far_L, "device_bytes": int(inf.device_bytes)},
+                   "far_pairs_leaf": far_L, "device_bytes": int(inf.device_bytes),
+                   "eta_smooth": args.eta_smooth, "adaptive_far": bool(args.adaptive_far),
+                   "smooth_depth": int(inf.smooth_depth)},
         "wall_s_per_kmvm_with_plan": ms_per_step * 1e-3,
         "rel_err_vs_exact": rel_err, "rel_err_rows": int(rows.numel()),
         "stage_ms": st,

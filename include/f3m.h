@@ -54,6 +54,16 @@ typedef struct {
     int32_t overlap;        /* 1: the near field runs on a second stream of the plan, concurrently with
                                the far field (measured gain about 4 %); 0 (default): everything in order
                                on the caller's stream (per-kernel timings are then undisturbed) */
+    float eta_smooth;       /* smooth field of Sec. 4.3 ("Smoothness criteria"): once the boxes of a depth
+                               satisfy D l^2 / (4 lengthscale^2) <= eta_smooth (l = box edge, the O(1) bound
+                               on the effective variance of two boxes) every pair left at that depth,
+                               adjacent and self pairs included, is interpolated like a far pair and the
+                               division stops: no near field remains.  0 (default) = off; the paper uses
+                               0.1 .. 0.5.  Must be finite and >= 0. */
+    int32_t adaptive_far;   /* adaptive far-field approximation of Sec. 4.3: with q = l^2 / (2 lengthscale^2)
+                               a depth uses min(interp_nodes, 3) nodes per dimension if q <= 0.01,
+                               interp_nodes if q <= 5, and its far pairs are dropped if q > 5.
+                               0 (default) = every depth uses interp_nodes. */
 } f3m_options;
 
 typedef struct {
@@ -76,6 +86,10 @@ typedef struct {
     int64_t near_point_pairs;                  /* point pairs evaluated exactly: sum of |p||q| over the
                                                   near pairs of depth L */
     int64_t device_bytes;                      /* device memory held by the plan */
+    int32_t smooth_depth;                      /* depth whose adjacent pairs are interpolated (smooth
+                                                  field), -1 if none */
+    int32_t level_nodes[F3M_MAX_LEVELS + 1];   /* nodes per dimension used at each depth 1..L (0: the far
+                                                  pairs of the depth are dropped by the adaptive rule) */
 } f3m_info;
 
 typedef struct {
@@ -102,7 +116,7 @@ typedef struct {
  *                (p = 4 in 3-D is the paper's r = 64)
  *   eta          far-field distance ratio theta: boxes are far iff the distance
  *                of their centres is >= theta * (box edge); the paper uses 2.
- *                (NOT the paper's smooth-field limit, which is not implemented.)
+ *                (NOT the paper's smooth-field limit: that is f3m_options.eta_smooth.)
  *   stream       the call enqueues on it and synchronises it several times
  *   plan_out     receives the plan; NULL on error.  n == 0 gives an empty plan.
  */

@@ -63,6 +63,8 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
     if (!finite_pos(eta)) return set_error(F3M_ERR_INVALID_ARG, "eta (far-field distance ratio) must be finite and > 0");
     if (opt && (opt->leaf_max < 0 || opt->max_depth < 0))
         return set_error(F3M_ERR_INVALID_ARG, "negative option value");
+    if (opt && !(std::isfinite(opt->eta_smooth) && opt->eta_smooth >= 0.f))
+        return set_error(F3M_ERR_INVALID_ARG, "eta_smooth must be finite and >= 0");
     if (interp_nodes > 8) return set_error(F3M_ERR_UNSUPPORTED, "interp_nodes above 8 is not supported");
     double r = std::pow((double)interp_nodes, (double)D);
     if (r > (double)f3m::MAX_NODES) return set_error(F3M_ERR_UNSUPPORTED, "interp_nodes^D exceeds the node cap of 4096");
@@ -83,6 +85,8 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
         P->max_depth = opt ? opt->max_depth : 0;
         P->force_all_near = opt ? (opt->force_all_near != 0) : 0;
         P->no_overlap = opt ? (opt->overlap == 0) : 1;
+        P->eta_smooth = opt ? opt->eta_smooth : 0.f;
+        P->adaptive_far = opt ? (opt->adaptive_far != 0) : 0;
         F3M_HIP(hipGetDevice(&P->device));
         if (n > 0) f3m::build_plan(*P, X, (hipStream_t)stream);
     });
@@ -160,6 +164,8 @@ f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
     }
     for (int l = 0; l <= plan->L && plan->n > 0; ++l) out->far_point_pairs[l] = plan->lev[l].far_point_pairs;
     out->near_point_pairs = plan->near_point_pairs;
+    out->smooth_depth = plan->smooth_depth;
+    for (int l = 0; l <= F3M_MAX_LEVELS; ++l) out->level_nodes[l] = (l >= 1 && l <= plan->L) ? plan->lev[l].p : 0;
     out->device_bytes = plan->bytes;
     return F3M_OK;
 }

@@ -680,6 +680,45 @@ __global__ __launch_bounds__(256) void p2m_reduce_kernel(const uint32_t *__restr
     }
 }
 
+// Two-stage form for boxes with very many chunks: a block adds the partial node weights of one
+// slice (at most P2M_SLICE chunks of one box) in fp64, then a block per box adds its slices,
+// both in a fixed order.
+__global__ __launch_bounds__(256) void p2m_slice_kernel(const uint32_t *__restrict__ slice_box,
+                                                        const uint32_t *__restrict__ slice_first,
+                                                        const uint32_t *__restrict__ chunk_first, int64_t nslices, int r,
+                                                        const float *__restrict__ Wpart, double *__restrict__ Wslice) {
+    const int64_t sidx = block_index();
+    if (sidx >= nslices) return;
+    const uint32_t a = slice_box[sidx];
+    const uint32_t c0 = chunk_first[a] + (uint32_t)(sidx - slice_first[a]) * (uint32_t)P2M_SLICE;
+    const uint32_t c1 = min(c0 + (uint32_t)P2M_SLICE, chunk_first[a + 1]);
+    __shared__ double part[4][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    for (int i0 = 0; i0 < r; i0 += 64) {
+        const int i = i0 + lane;
+        double s = 0.0;
+        if (i < r)
+            for (uint32_t c = c0 + g; c < c1; c += 4) s += (double)Wpart[(int64_t)c * r + i];
+        __syncthreads();
+        part[g][lane] = s;
+        __syncthreads();
+        if (g == 0 && i < r) Wslice[sidx * r + i] = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+    }
+}
+__global__ __launch_bounds__(256) void p2m_slice_sum_kernel(const uint32_t *__restrict__ slice_first,
+                                                            const uint32_t *__restrict__ chunk_first, int64_t nb, int r,
+                                                            const double *__restrict__ Wslice, float *__restrict__ W) {
+    const int64_t a = block_index();
+    if (a >= nb) return;
+    if (chunk_first[a + 1] - chunk_first[a] <= 1) return;   // the P2M kernel wrote W itself
+    const uint32_t s0 = slice_first[a], s1 = slice_first[a + 1];
+    for (int i = threadIdx.x; i < r; i += 256) {
+        double s = 0.0;
+        for (uint32_t k = s0; k < s1; ++k) s += Wslice[(int64_t)k * r + i];
+        W[(int64_t)a * r + i] = (float)s;
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // L2P, v = L_X^T v2 (Fig. 4 step 3): y_a += sum_i L_i(t_a) V_p[i] for the points a of box p.
 // One block per chunk, one thread per point; V_p and the 1-D basis values sit in LDS.
@@ -1109,15 +1148,15 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
 
 // per depth with far pairs: the 1-D factor matrices of the node-to-node kernel matrix, built in fp64
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
-    const int p = P.p;
     int m = 0;   // largest near offset in one dimension: m^2 < T
     while ((m + 1) * (m + 1) < P.T) ++m;
     const int omax = 2 * m + 1;   // children of near parents
-    std::vector<double> s(p);
-    for (int k = 0; k < p; ++k) s[k] = p > 1 ? std::cos(M_PI * (double)k / (double)(p - 1)) : 0.0;
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
-        if (lv.far_sz == 0) continue;
+        if (lv.far_sz == 0 || lv.p == 0) continue;
+        const int p = lv.p;
+        std::vector<double> s(p);
+        for (int k = 0; k < p; ++k) s[k] = p > 1 ? std::cos(M_PI * (double)k / (double)(p - 1)) : 0.0;
         const double half = 0.5 * (double)P.E / (double)(1ull << l);
         const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
         std::vector<float> g((size_t)(2 * omax + 1) * p * p);
@@ -1136,12 +1175,22 @@ void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
 
 
 // ------------------------------------------------------------------------------------
+// partial node weights of the chunks of a box -> W, in one or two stages
+static void reduce_partials(f3m_plan_s &P, f3m_level &lv, int r, float *W, hipStream_t st) {
+    if (lv.nslices > 0) {
+        p2m_slice_kernel<<<grid_for(lv.nslices), dim3(256), 0, st>>>(lv.slice_box.p, lv.slice_first.p, lv.chunk_first.p,
+                                                                    lv.nslices, r, P.Wpart.p, P.Wslice.p);
+        p2m_slice_sum_kernel<<<grid_for(lv.nb), dim3(256), 0, st>>>(lv.slice_first.p, lv.chunk_first.p, lv.nb, r,
+                                                                   P.Wslice.p, W);
+    } else {
+        p2m_reduce_kernel<<<grid_for(lv.nb), dim3(256), 0, st>>>(lv.chunk_first.p, lv.nb, r, P.Wpart.p, W);
+    }
+}
+
 template <int D>
 static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
     const int64_t n = P.n;
-    const int r = P.r, p = P.p;
     const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma));
-    const NodeArg N = make_nodes(p);
     const int nev = 4 + 3 * (P.L + 1);
     if (!P.ev[8]) {
         // events of the kmvm stages live in ev[8..15] plus a per-depth set created lazily
@@ -1162,7 +1211,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         F3M_HIP(hipStreamWaitEvent(P.side, P.ev_fork, 0));
     }
     F3M_HIP(hipEventRecord(P.ev_p2p0, sn));
-    {
+    if (leaf.near_sz == 0) {
+        // smooth field (Sec. 4.3): every pair was interpolated, no near field is left
+        zero_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.yn.p, n);
+    } else {
         // c l^2 bounds the magnitude of the expanded exponent terms in box-local coordinates
         // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
         const CentreArg CL = make_centre(P, P.L);
@@ -1196,11 +1248,14 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
             if (!ev[k]) F3M_HIP(hipEventCreate(&ev[k]));
         return ev;
     };
-    const bool tree = P.tree_lmin > 0;   // D = 3, 4 nodes per dimension, tables on depths tree_lmin..L
+    const bool tree = P.tree_lmin > 0;   // D = 3, 4 nodes per dimension on depths tree_lmin..tree_lmax
     // ---- depths that are handled on their own, straight from the points (Fig. 4 steps 1-3)
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
-        if (lv.far_sz == 0 || (tree && l >= P.tree_lmin)) continue;
+        // no far pairs, dropped by the adaptive rule (Sec. 4.3), or part of the band below
+        if (lv.far_sz == 0 || lv.p == 0 || (tree && l >= P.tree_lmin && l <= P.tree_lmax)) continue;
+        const int p = lv.p, r = lv.r;
+        const NodeArg N = make_nodes(p);
         hipEvent_t *ev = level_events(l);
         const CentreArg C = make_centre(P, l);
         F3M_HIP(hipEventRecord(ev[0], st));
@@ -1220,7 +1275,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                     P.W.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
             if (lv.nchunks > lv.nb)
-                p2m_reduce_kernel<<<grid_for(lv.nb), dim3(256), 0, st>>>(lv.chunk_first.p, lv.nb, r, P.Wpart.p, P.W.p);
+                reduce_partials(P, lv, r, P.W.p, st);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[1], st));
@@ -1259,10 +1314,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         }
         F3M_HIP(hipEventRecord(ev[5], st));
     }
-    // ---- depths tree_lmin..L: P2M at the last depth, weights passed upward, M2L per depth,
-    //      potentials passed downward, one L2P at the last depth
+    // ---- depths tree_lmin..tree_lmax: P2M at the last depth of the band, weights passed upward,
+    //      M2L per depth, potentials passed downward, one L2P at the last depth of the band
     if (tree) {
-        const int L = P.L;
+        const int L = P.tree_lmax;
+        const int r = 64;
         f3m_level &lf = P.lev[L];
         {
             hipEvent_t *ev = level_events(L);
@@ -1272,7 +1328,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                                                                   lf.Wl.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
             if (lf.nchunks > lf.nb)
-                p2m_reduce_kernel<<<grid_for(lf.nb), dim3(256), 0, st>>>(lf.chunk_first.p, lf.nb, r, P.Wpart.p, lf.Wl.p);
+                reduce_partials(P, lf, r, lf.Wl.p, st);
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipEventRecord(ev[1], st));
         }

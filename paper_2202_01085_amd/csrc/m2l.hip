@@ -50,7 +50,7 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
                                                           const int32_t *__restrict__ up_cell,
                                                           const int32_t *__restrict__ cell,
                                                           const uint32_t *__restrict__ key, int64_t nparents,
-                                                          int64_t per_xcd, const float *__restrict__ G,
+                                                          int64_t per_xcd, const float *__restrict__ G, int all_far,
                                                           const float *__restrict__ W, float *__restrict__ V) {
     __shared__ float rows[ST_CAND * 64];
     __shared__ int present[ST_CAND];
@@ -122,7 +122,8 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
         if (cx < 6 && ln < 36) {
             const int cy = ln % 6, cz = ln / 6;
             const int ox = cx - 2 - tx, oy = cy - 2 - ty, oz = cz - 2 - tz;
-            ok = present[cx + 6 * ln] != 0 && ox * ox + oy * oy + oz * oz >= 4;
+            // all_far: the smooth depth of Sec. 4.3, where adjacent pairs are interpolated too
+            ok = present[cx + 6 * ln] != 0 && (all_far || ox * ox + oy * oy + oz * oz >= 4);
         }
         mask[k] = __ballot(ok);
     }
@@ -200,7 +201,8 @@ bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStre
     if (lv.gtab.p == nullptr || lv.gtab_omax != 3) return false;
     const int64_t per_xcd = cdiv(up.nb, 8);
     m2l_stencil_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p, up.cell.p,
-                                                                lv.cell.p, lv.key.p, up.nb, per_xcd, lv.gtab.p, W, V);
+                                                                lv.cell.p, lv.key.p, up.nb, per_xcd, lv.gtab.p,
+                                                                lv.smooth ? 1 : 0, W, V);
     F3M_HIP(hipGetLastError());
     return true;
 }

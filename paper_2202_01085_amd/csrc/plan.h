@@ -18,9 +18,17 @@ struct f3m_level {
     int64_t nchunks = 0;
     f3m::DevBuf<uint32_t> chunk_box;    // [nchunks]
     f3m::DevBuf<uint32_t> chunk_first;  // [nb+1] first chunk of each box
+    // boxes with very many chunks (few, huge boxes): a slice is a run of at most P2M_SLICE chunks of one
+    // box, and the partial node weights are added slice by slice first
+    int64_t nslices = 0;
+    f3m::DevBuf<uint32_t> slice_box, slice_first;
     // D = 3, 4 nodes/dim, far ratio 2: the M2L enumerates the far partners on the candidate grid
     // around the parent (m2l.hip); far_ptr keeps the row lengths, far_col stays empty
     bool far_implicit = false;
+    // Sec. 4.3: nodes per dimension used at this depth (interp_nodes, 3 under the adaptive rule, or 0 =
+    // the far pairs of the depth are dropped), r = p^D, and whether every pair of the depth is interpolated
+    int p = 0, r = 0;
+    bool smooth = false;
     // 1-D factors of the node-to-node kernel matrix, [2*omax+1][p][p]
     f3m::DevBuf<float> gtab;
     int gtab_omax = 0;
@@ -36,6 +44,9 @@ struct f3m_plan_s {
     float E = 0.f, scale = 0.f;
     float alpha[F3M_MAX_DIM] = {0};
     int leaf_max = 128, max_depth = 0, force_all_near = 0, no_overlap = 0;
+    float eta_smooth = 0.f;                     // smooth-field limit of Sec. 4.3 (0 = off)
+    int adaptive_far = 0;                       // adaptive far-field node rule of Sec. 4.3
+    int smooth_depth = -1;                      // depth whose adjacent pairs are interpolated, or -1
     hipStream_t side = nullptr;                 // second stream for the near field
     hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_p2p0 = nullptr, ev_p2p1 = nullptr;
     int device = 0;
@@ -49,12 +60,14 @@ struct f3m_plan_s {
     f3m::DevBuf<float> yn;        // [n] near-field result in box order
     f3m::DevBuf<float> W, V;      // [max_l nb_l * r] node weights / node potentials of one depth
     f3m::DevBuf<float> Wpart;     // [max_l nchunks_l * r] partial node weights
+    f3m::DevBuf<double> Wslice;   // [max_l nslices_l * r] sums of the partial node weights of a slice
     // near-field work split: a tile is a run of at most 64 targets of one leaf box
     int64_t ntiles = 0;
     f3m::DevBuf<uint32_t> tile_box, tile_first;   // [ntiles], [nb_L+1]
     f3m_level lev[F3M_MAX_LEVELS + 1];
-    int tree_lmin = 0;                  // > 0: node weights/potentials are passed between depths
-                                        // tree_lmin..L (D = 3, 4 nodes/dim); 0: every depth from the points
+    int tree_lmin = 0, tree_lmax = 0;   // tree_lmin > 0: node weights/potentials are passed between depths
+                                        // tree_lmin..tree_lmax (D = 3, 4 nodes/dim); other depths work
+                                        // straight from the points
     f3m::DevBuf<float> transfer;        // [2][4][4] parent basis at the child's nodes
     // un-permutation through buckets of destinations (large n): tile offsets of the radix scatter on the
     // top 8 bits of perm, and the bucketed (destination, value) pairs
@@ -72,10 +85,13 @@ struct f3m_plan_s {
 namespace f3m {
 
 constexpr int P2M_CHUNK = 256;
+constexpr int P2M_SLICE = 512;   // chunks per slice of the two-stage sum of partial node weights
 constexpr int PAD_POINTS = 64;   // zero padding behind Xs and bs
 constexpr int MAX_NODES = 4096;
 
 int quant_depth(int D);
+bool smooth_rule(double E, int depth, int D, double gamma, double eta_smooth);   // Sec. 4.3 smoothness criterion
+int adaptive_nodes(double E, int depth, double gamma, int p);                   // Sec. 4.3 node rule (0: dropped)
 
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);

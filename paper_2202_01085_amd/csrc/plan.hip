@@ -425,7 +425,7 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
                                                     const int32_t *__restrict__ cell,
                                                     const uint64_t *__restrict__ up_near_ptr,
                                                     const uint32_t *__restrict__ up_near_col,
-                                                    const uint32_t *__restrict__ up_cstart, int T, int all_near,
+                                                    const uint32_t *__restrict__ up_cstart, int T, int mode /* 0: far rule, 1: all near, 2: all far */,
                                                     uint32_t *__restrict__ cnt_near, uint32_t *__restrict__ cnt_far,
                                                     const uint64_t *__restrict__ near_ptr,
                                                     const uint64_t *__restrict__ far_ptr,
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
                 o[d] = cell[(int64_t)bq * D + d] - ca[d];
                 d2 += o[d] * o[d];
             }
-            bool is_far = !all_near && d2 >= T;
+            bool is_far = mode == 2 || (mode == 0 && d2 >= T);
             if (is_far) {
                 if (pass && far_col) far_col[fbase + nf] = bq;
                 ++nf;
@@ -691,8 +691,12 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             cn.alloc((size_t)lv.nb);
             cf.alloc((size_t)lv.nb);
             unsigned grid = (unsigned)cdiv(lv.nb, 128);
+            // Sec. 4.3: once the boxes pass the smoothness criterion every pair left is interpolated
+            lv.smooth = !P.force_all_near && smooth_rule((double)P.E, l, D, (double)P.gamma, (double)P.eta_smooth);
+            if (lv.smooth) P.smooth_depth = l;
+            const int mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, up.cstart.p, P.T, P.force_all_near, cn.p,
+                                                             up.near_col.p, up.cstart.p, P.T, mode, cn.p,
                                                              cf.p, nullptr, nullptr, nullptr, nullptr);
             F3M_HIP(hipGetLastError());
             uint64_t tn = 0, tf = 0;
@@ -703,7 +707,10 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lv.near_sz = (int64_t)tn;
             lv.far_sz = (int64_t)tf;
             lv.near_col.alloc((size_t)tn, tally);
-            if (tf > 0 && m2l_stencil_applies(P)) {
+            lv.p = P.adaptive_far ? adaptive_nodes((double)P.E, l, (double)P.gamma, P.p) : P.p;
+            lv.r = 1;
+            for (int d = 0; d < D; ++d) lv.r *= lv.p;
+            if (tf > 0 && m2l_stencil_applies(P) && (lv.p == 4 || lv.p == 0)) {
                 // the M2L of this depth enumerates the far partners itself (candidate grid around the
                 // parent): only the row lengths are kept
                 lv.far_implicit = true;
@@ -712,7 +719,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
                 lv.far_col.alloc((size_t)tf, tally);
             }
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, up.cstart.p, P.T, P.force_all_near, nullptr,
+                                                             up.near_col.p, up.cstart.p, P.T, mode, nullptr,
                                                              nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
                                                              lv.far_implicit ? nullptr : lv.far_col.p);
             F3M_HIP(hipGetLastError());
@@ -738,25 +745,36 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     F3M_HIP(hipEventRecord(ea, st));
     // With D = 3 and 4 nodes per dimension node weights and node potentials are passed between
     // depths, so only the last depth streams the points.
-    if (P.L >= 2 && P.lev[P.L].far_implicit) {
-        P.tree_lmin = P.L;
-        while (P.tree_lmin > 2 && P.lev[P.tree_lmin - 1].far_sz > 0) --P.tree_lmin;
+    // the band of depths with implicit far rows and 4 nodes per dimension (under the adaptive rule
+    // the deepest depths may use 3 nodes and the coarsest may be dropped)
+    auto in_band = [&](int k) { return k >= 2 && P.lev[k].far_sz > 0 && P.lev[k].far_implicit && P.lev[k].p == 4; };
+    for (int k = P.L; k >= 2 && P.tree_lmax == 0; --k)
+        if (in_band(k)) P.tree_lmax = k;
+    if (P.tree_lmax > 0) {
+        P.tree_lmin = P.tree_lmax;
+        while (in_band(P.tree_lmin - 1)) --P.tree_lmin;
         upload_transfer(P, st);
     }
     upload_kron_tables(P, st);
     permute_out_prepare(P, st);
-    int64_t max_nb = 0, max_chunks = 0;
+    int64_t max_w = 0, max_part = 0, max_slice = 0;
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
-        if (lv.far_sz == 0) continue;
-        if (P.tree_lmin > 0 && k >= P.tree_lmin) {
-            lv.Wl.alloc((size_t)lv.nb * P.r, tally);
-            lv.Vl.alloc((size_t)lv.nb * P.r, tally);
-            if (k < P.L) continue;   // only the last depth needs chunks
+        if (lv.far_sz == 0 || lv.p == 0) continue;   // nothing to interpolate, or dropped
+        const bool tree = P.tree_lmin > 0 && k >= P.tree_lmin && k <= P.tree_lmax;
+        if (tree) {
+            lv.Wl.alloc((size_t)lv.nb * lv.r, tally);
+            lv.Vl.alloc((size_t)lv.nb * lv.r, tally);
+            if (k < P.tree_lmax) continue;   // only the last depth of the band needs chunks
         }
         build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
-        if (!(P.tree_lmin > 0 && k >= P.tree_lmin)) max_nb = std::max(max_nb, lv.nb);
-        max_chunks = std::max(max_chunks, lv.nchunks);
+        if (lv.max_box > (int64_t)P2M_CHUNK * P2M_SLICE * 2) {
+            // a box with more than a thousand chunks: its partial node weights are summed in two stages
+            build_chunks(lv.chunk_first.p, lv.nb, P2M_SLICE, lv.slice_first, lv.slice_box, lv.nslices, tally, st);
+            max_slice = std::max(max_slice, lv.nslices * (int64_t)lv.r);
+        }
+        if (!tree) max_w = std::max(max_w, lv.nb * (int64_t)lv.r);
+        max_part = std::max(max_part, lv.nchunks * (int64_t)lv.r);
     }
     build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
     P.bs.alloc((size_t)n + PAD_POINTS, tally);
@@ -765,9 +783,10 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     P.yn.alloc((size_t)n, tally);
     if (!P.no_overlap) F3M_HIP(hipStreamCreateWithFlags(&P.side, hipStreamNonBlocking));
     for (hipEvent_t *e : {&P.ev_fork, &P.ev_join, &P.ev_p2p0, &P.ev_p2p1}) F3M_HIP(hipEventCreate(e));
-    P.W.alloc((size_t)max_nb * P.r, tally);
-    P.V.alloc((size_t)max_nb * P.r, tally);
-    P.Wpart.alloc((size_t)max_chunks * P.r, tally);
+    P.W.alloc((size_t)max_w, tally);
+    P.V.alloc((size_t)max_w, tally);
+    P.Wpart.alloc((size_t)max_part, tally);
+    P.Wslice.alloc((size_t)max_slice, tally);
     F3M_HIP(hipEventRecord(eb, st));
     F3M_HIP(hipStreamSynchronize(st));
 
@@ -790,7 +809,8 @@ void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStre
     const unsigned grid = (unsigned)cdiv(lv.nb, 128);
     auto launch = [&](auto kern) {
         kern<<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p, up.near_col.p,
-                                               up.cstart.p, P.T, P.force_all_near, nullptr, nullptr, lv.near_ptr.p,
+                                               up.cstart.p, P.T, P.force_all_near ? 1 : lv.smooth ? 2 : 0, nullptr, nullptr,
+                                               lv.near_ptr.p,
                                                lv.far_ptr.p, nullptr, cols_dev);
     };
     switch (P.D) {
@@ -835,6 +855,25 @@ void compute_far_point_pairs(f3m_plan_s &P) {
         }
     }
     P.have_far_point_pairs = true;
+}
+
+// Smoothness criterion with the O(1) bound of Sec. 4.3: a box of edge l has an effective variance
+// of at most D l^2 / (8 gamma^2), two boxes D l^2 / (4 gamma^2); adjacent pairs are interpolated
+// when that is <= eta_smooth.
+bool smooth_rule(double E, int depth, int D, double gamma, double eta_smooth) {
+    if (!(eta_smooth > 0.0)) return false;
+    const double l = E / std::ldexp(1.0, depth);
+    return (double)D * l * l / (4.0 * gamma * gamma) <= eta_smooth;
+}
+
+// Adaptive far-field rule of Sec. 4.3 on q = l^2 / (2 gamma^2): min(p, 3) nodes per dimension if
+// q <= 0.01 (the paper's min(r, 3^D) on a tensor grid), p if q <= 5, 0 (dropped) above.
+int adaptive_nodes(double E, int depth, double gamma, int p) {
+    const double l = E / std::ldexp(1.0, depth);
+    const double q = l * l / (2.0 * gamma * gamma);
+    if (q <= 0.01) return p < 3 ? p : 3;
+    if (q <= 5.0) return p;
+    return 0;
 }
 
 void build_plan(f3m_plan_s &P, const float *X, hipStream_t st) {

@@ -28,7 +28,8 @@ class F3MError(RuntimeError):
 
 class Options(ctypes.Structure):
     _fields_ = [("leaf_max", ctypes.c_int32), ("max_depth", ctypes.c_int32),
-                ("force_all_near", ctypes.c_int32), ("overlap", ctypes.c_int32)]
+                ("force_all_near", ctypes.c_int32), ("overlap", ctypes.c_int32),
+                ("eta_smooth", ctypes.c_float), ("adaptive_far", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -39,7 +40,8 @@ class Info(ctypes.Structure):
                 ("nboxes", ctypes.c_int64 * (MAX_LEVELS + 1)), ("max_box", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("near_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)), ("far_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("far_point_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
-                ("near_point_pairs", ctypes.c_int64), ("device_bytes", ctypes.c_int64)]
+                ("near_point_pairs", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
+                ("smooth_depth", ctypes.c_int32), ("level_nodes", ctypes.c_int32 * (MAX_LEVELS + 1))]
 
 
 class Times(ctypes.Structure):
@@ -111,11 +113,12 @@ class Plan:
     """f3m_plan / f3m_plan_ex: the partition and interaction lists of one point set."""
 
     def __init__(self, X, lengthscale, interp_nodes, eta=2.0, leaf_max=0, max_depth=0, force_all_near=False,
-                 overlap=False, stream=None):
+                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False):
         n, D = X.shape
         self.n, self.D = int(n), int(D)
         self._h = ctypes.c_void_p()
-        opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), int(bool(overlap)))
+        opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), int(bool(overlap)),
+                      float(eta_smooth), int(bool(adaptive_far)))
         xp = _dev_f32(X, "X") if n > 0 else ctypes.c_void_p()
         _check(lib().f3m_plan_ex(xp, self.n, self.D, float(lengthscale), int(interp_nodes), float(eta),
                                  ctypes.byref(opt), _stream(stream), ctypes.byref(self._h)))

@@ -275,6 +275,63 @@ def test_error_paths():
 
 
 # --------------------------------------------------------------------------------------
+# smooth field and adaptive far-field rule (Sec. 4.3) against the oracle
+# --------------------------------------------------------------------------------------
+SMOOTH_CASES = [
+    # n, D, dist, p, gamma, zeta, eta_smooth, adaptive
+    (20_000, 3, "uniform", 4, 1.0, 128, 0.5, False),     # configuration 1 recipe: everything interpolated at depth 1
+    (20_000, 3, "uniform", 4, 0.3, 16, 0.05, False),     # smooth depth 3: candidate-grid M2L with all pairs far
+    (30_000, 3, "normal", 4, 1.5, 32, 0.1, False),       # non-uniform: absent candidates
+    (8_000, 2, "normal", 5, 0.8, 16, 0.2, False),        # general path (Kronecker M2L) with self pairs
+    (6_000, 4, "uniform", 3, 1.0, 8, 0.3, False),
+    (20_000, 3, "uniform", 4, 3.0, 8, 0.0, True),        # adaptive only: deepest depths use 3 nodes, the others 4
+    (20_000, 3, "uniform", 5, 0.02, 8, 0.0, True),       # adaptive only: coarse depths dropped
+    (20_000, 3, "normal", 4, 2.0, 8, 0.01, True),        # both
+    (3_000_000, 3, "uniform", 4, 1.0, 128, 0.5, False),  # 8 boxes of 375 000 points: two-stage sum of the partial node weights
+]
+
+
+@pytest.mark.parametrize("n,D,dist,p,gamma,zeta,eta_smooth,adaptive", SMOOTH_CASES)
+def test_smooth_and_adaptive_parity(n, D, dist, p, gamma, zeta, eta_smooth, adaptive):
+    say("f3m smooth/adaptive n=%d D=%d %s p=%d gamma=%g zeta=%d eta_smooth=%g adaptive=%s"
+        % (n, D, dist, p, gamma, zeta, eta_smooth, adaptive))
+    X = cloud(dist, n, D, 1100 + D)
+    b = inputs.rhs_normal(n, 2100 + D)
+    T = oracle.Tree(X.numpy(), theta=2.0, zeta=zeta, gamma=g32(gamma), eta_smooth=g32(eta_smooth))
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, gamma, p, 2.0, leaf_max=zeta, eta_smooth=eta_smooth, adaptive_far=adaptive)
+    check_plan_bit_exact(plan, T)
+    inf = plan.info()
+    assert inf.smooth_depth == T.smooth_depth
+    nodes = [oracle.adaptive_nodes(T.E, l, g32(gamma), p) if adaptive else p for l in range(1, T.L + 1)]
+    assert [inf.level_nodes[l] for l in range(1, T.L + 1)] == nodes
+    say("  L=%d smooth_depth=%d nodes per depth %s near_L=%d" % (T.L, T.smooth_depth, nodes, inf.near_pairs[T.L]))
+    if eta_smooth > 0 and T.smooth_depth > 0:
+        assert inf.near_pairs[T.L] == 0
+        assert sum(inf.far_point_pairs[l] for l in range(T.L + 1)) == n * n
+    y = plan.kmvm(bd)
+    torch.cuda.synchronize()
+    yo = T.apply(b.numpy(), g32(gamma), p, adaptive=adaptive)
+    e = rel(y.cpu().numpy(), yo)
+    say("  rel err vs CPU F3M %.3e" % e)
+    assert e <= TOL_F3M
+    assert torch.equal(y, plan.kmvm(bd))
+
+
+def test_smooth_field_config1_error_vs_exact():
+    # the paper's operating point (smooth limit 0.5): no near field at all, error of the order 1e-4..1e-3
+    X, b, cfg = inputs.make_config(1)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, cfg["lengthscale"], cfg["p"], cfg["theta"], eta_smooth=0.5, adaptive_far=True)
+    y = plan.kmvm(bd).cpu().numpy()
+    exact = oracle.direct(X.numpy(), b.numpy(), g32(cfg["lengthscale"]))
+    e = rel(y, exact)
+    say("f3m config 1 with smooth limit 0.5: depth %d, rel err vs exact %.3e" % (plan.info().depth, e))
+    assert plan.info().near_pairs[plan.info().depth] == 0
+    assert e <= 2e-3
+
+
+# --------------------------------------------------------------------------------------
 # configuration 2 at full size: sampled rows against the fp64 exact rows
 # --------------------------------------------------------------------------------------
 def test_config2_full_size_sampled_rows():
