@@ -65,8 +65,8 @@ def main():
                          "the rocprofv3 --pmc runs summarised under profiles/")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU by design (the path is one GPU's share; see DESIGN.md, "
-              "'How the path would shard'); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the kernels are one GPU's share of the path; nothing "
+              "here uses a second device); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
