@@ -43,6 +43,8 @@ def lib():
         L.oracle_tree_build.restype = c_vp
         L.oracle_tree_build_ex.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int, c_dbl, c_dbl]
         L.oracle_tree_build_ex.restype = c_vp
+        L.oracle_tree_build_ex2.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int, c_dbl, c_dbl, c_i64]
+        L.oracle_tree_build_ex2.restype = c_vp
         L.oracle_is_smooth_depth.argtypes = [c_dbl, c_int, c_int, c_dbl, c_dbl]
         L.oracle_is_smooth_depth.restype = c_int
         L.oracle_adaptive_nodes.argtypes = [c_dbl, c_int, c_dbl, c_int]
@@ -130,13 +132,15 @@ def quant_depth(D):
 class Tree:
     """Partition + interaction lists of Algorithm 1 for one point set."""
 
-    def __init__(self, X, theta=2.0, zeta=128, max_depth=0, force_all_near=False, gamma=0.0, eta_smooth=0.0):
-        """eta_smooth > 0 switches the smooth field of Sec. 4.3 on (needs the lengthscale gamma)."""
+    def __init__(self, X, theta=2.0, zeta=128, max_depth=0, force_all_near=False, gamma=0.0, eta_smooth=0.0,
+                 small_field=0):
+        """eta_smooth > 0 switches the smooth field of Sec. 4.3 on (needs the lengthscale gamma);
+        small_field = rho > 0 the small field of Sec. 4.2."""
         self.X = _f32(X)
         self.n, self.D = self.X.shape
-        self._h = lib().oracle_tree_build_ex(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
-                                             int(max_depth), int(bool(force_all_near)), float(gamma),
-                                             float(eta_smooth))
+        self._h = lib().oracle_tree_build_ex2(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
+                                              int(max_depth), int(bool(force_all_near)), float(gamma),
+                                              float(eta_smooth), int(small_field))
         if not self._h:
             raise ValueError("oracle_tree_build rejected its arguments")
         self.L = int(lib().oracle_tree_depth(self._h))
@@ -173,7 +177,7 @@ class Tree:
         return keys, starts
 
     def interactions(self, level, kind):
-        """CSR (row_ptr, cols) by target rank; kind 0 = near, 1 = far."""
+        """CSR (row_ptr, cols) by target rank; kind 0 = near, 1 = far, 2 = small field."""
         nb = self.nboxes(level)
         sz = int(lib().oracle_tree_list_size(self._h, level, kind))
         ptr = np.empty(nb + 1, dtype=np.int64)
@@ -208,6 +212,8 @@ def adaptive_nodes(E, depth, gamma, p):
     return int(lib().oracle_adaptive_nodes(float(E), int(depth), float(gamma), int(p)))
 
 
-def f3m(X, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False, eta_smooth=0.0, adaptive=False):
+def f3m(X, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False, eta_smooth=0.0, adaptive=False,
+        small_field=0):
     """CPU F3M product (fp64), original point order."""
-    return Tree(X, theta, zeta, max_depth, force_all_near, gamma, eta_smooth).apply(b, gamma, p, adaptive=adaptive)
+    return Tree(X, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, small_field).apply(b, gamma, p,
+                                                                                               adaptive=adaptive)

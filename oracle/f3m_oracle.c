@@ -203,6 +203,7 @@ typedef struct {
     int64_t *cstart;   /* [nb+1] rank interval of the children one depth down (filled when divided) */
     int64_t *near_ptr, *near_col; /* CSR by target rank, columns ascending */
     int64_t *far_ptr, *far_col;
+    int64_t *small_ptr, *small_col; /* small-field pairs (Sec. 4.2): computed directly at this depth */
 } olevel;
 
 typedef struct {
@@ -262,6 +263,7 @@ static void free_level(olevel *lv)
 {
     free(lv->key); free(lv->start); free(lv->parent); free(lv->cstart);
     free(lv->near_ptr); free(lv->near_col); free(lv->far_ptr); free(lv->far_col);
+    free(lv->small_ptr); free(lv->small_col);
     memset(lv, 0, sizeof(*lv));
 }
 
@@ -325,30 +327,36 @@ static int64_t max_box(const olevel *lv)
 /* New interactions at depth l from the near pairs of depth l-1, split into
  * near and far (reading R4).  Rows come out sorted because the parent's row is
  * sorted and the children of a box have consecutive ranks. */
-static void new_interactions(otree *t, int l, double theta, int force_all_near, int all_interpolated)
+static void new_interactions(otree *t, int l, double theta, int force_all_near, int all_interpolated,
+                             int64_t rho)
 {
     olevel *lv = &t->lev[l], *up = &t->lev[l - 1];
     int D = t->D;
     int64_t nb = lv->nb;
     lv->near_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
     lv->far_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
+    lv->small_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
     for (int pass = 0; pass < 2; ++pass) {
         if (pass == 1) {
             for (int64_t a = 0; a < nb; ++a) {
                 lv->near_ptr[a + 1] += lv->near_ptr[a];
                 lv->far_ptr[a + 1] += lv->far_ptr[a];
+                lv->small_ptr[a + 1] += lv->small_ptr[a];
             }
             lv->near_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(lv->near_ptr[nb] + 1));
             lv->far_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(lv->far_ptr[nb] + 1));
+            lv->small_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(lv->small_ptr[nb] + 1));
         }
 #pragma omp parallel for schedule(dynamic, 64)
         for (int64_t a = 0; a < nb; ++a) {
             int64_t ca[ORACLE_MAX_D], cb[ORACLE_MAX_D];
             deinterleave(lv->key[a], D, l, ca);
             int64_t P = lv->parent[a];
-            int64_t nn = 0, nf = 0;
+            int64_t nn = 0, nf = 0, ns = 0;
             int64_t *ncol = pass ? lv->near_col + lv->near_ptr[a] : NULL;
             int64_t *fcol = pass ? lv->far_col + lv->far_ptr[a] : NULL;
+            int64_t *scol = pass ? lv->small_col + lv->small_ptr[a] : NULL;
+            int64_t cnt_a = lv->start[a + 1] - lv->start[a];
             for (int64_t e = up->near_ptr[P]; e < up->near_ptr[P + 1]; ++e) {
                 int64_t Q = up->near_col[e];
                 for (int64_t bq = up->cstart[Q]; bq < up->cstart[Q + 1]; ++bq) {
@@ -358,7 +366,14 @@ static void new_interactions(otree *t, int l, double theta, int force_all_near, 
                         d2 += (double)((cb[d] - ca[d]) * (cb[d] - ca[d]));
                     /* smooth depth: adjacent pairs are interpolated too (Sec. 4.3) */
                     int is_far = all_interpolated || (!force_all_near && d2 >= theta * theta);
-                    if (is_far) {
+                    /* small field (Sec. 4.2): two boxes with few points are summed directly at
+                     * this depth, whatever their distance, and the pair is not divided further */
+                    int is_small = !force_all_near && rho > 0 &&
+                                   cnt_a + (lv->start[bq + 1] - lv->start[bq]) <= rho;
+                    if (is_small) {
+                        if (pass) scol[ns] = bq;
+                        ++ns;
+                    } else if (is_far) {
                         if (pass) fcol[nf] = bq;
                         ++nf;
                     } else {
@@ -370,6 +385,7 @@ static void new_interactions(otree *t, int l, double theta, int force_all_near, 
             if (!pass) {
                 lv->near_ptr[a + 1] = nn;
                 lv->far_ptr[a + 1] = nf;
+                lv->small_ptr[a + 1] = ns;
             }
         }
     }
@@ -402,6 +418,8 @@ int oracle_adaptive_nodes(double E, int depth, double gamma, int p)
 
 otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
                             int force_all_near, double gamma, double eta_smooth);
+otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                             int force_all_near, double gamma, double eta_smooth, int64_t rho);
 
 /* Builds the partition and the interaction lists of Algorithm 1 (everything
  * that does not depend on b).  Returns NULL on bad arguments. */
@@ -416,6 +434,14 @@ otree *oracle_tree_build(const float *X, int64_t n, int D, double theta,
  * near list of that depth is empty and the loop of Algorithm 1 ends there. */
 otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
                             int force_all_near, double gamma, double eta_smooth)
+{
+    return oracle_tree_build_ex2(X, n, D, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, 0);
+}
+
+/* The same with the small field of Sec. 4.2 (rho > 0): a pair of boxes created by a division whose
+ * point counts add up to at most rho goes on the direct list of that depth. */
+otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                             int force_all_near, double gamma, double eta_smooth, int64_t rho)
 {
     if (!X || n <= 0 || D < 1 || D > ORACLE_MAX_D || !(theta > 0.0) || zeta < 1)
         return NULL;
@@ -473,6 +499,8 @@ otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int6
     root->near_col = (int64_t *)calloc(1, sizeof(int64_t));
     root->far_ptr = (int64_t *)calloc(2, sizeof(int64_t));
     root->far_col = (int64_t *)calloc(1, sizeof(int64_t));
+    root->small_ptr = (int64_t *)calloc(2, sizeof(int64_t));
+    root->small_col = (int64_t *)calloc(1, sizeof(int64_t));
 
     int cap = t->Lq;
     if (max_depth > 0 && max_depth < cap) cap = max_depth;
@@ -484,7 +512,7 @@ otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int6
         ++l;
         divide(t, l);
         int smooth = !force_all_near && oracle_is_smooth_depth(t->E, l, D, gamma, eta_smooth);
-        new_interactions(t, l, theta, force_all_near, smooth);
+        new_interactions(t, l, theta, force_all_near, smooth, rho);
         if (smooth)
             t->smooth_depth = l;
     }
@@ -521,13 +549,13 @@ void oracle_tree_boxes(const otree *t, int level, uint64_t *keys, int64_t *start
 int64_t oracle_tree_list_size(const otree *t, int level, int kind)
 {
     const olevel *lv = &t->lev[level];
-    return kind ? lv->far_ptr[lv->nb] : lv->near_ptr[lv->nb];
+    return kind == 2 ? lv->small_ptr[lv->nb] : kind ? lv->far_ptr[lv->nb] : lv->near_ptr[lv->nb];
 }
 void oracle_tree_list(const otree *t, int level, int kind, int64_t *row_ptr, int64_t *cols)
 {
     const olevel *lv = &t->lev[level];
-    const int64_t *ptr = kind ? lv->far_ptr : lv->near_ptr;
-    const int64_t *col = kind ? lv->far_col : lv->near_col;
+    const int64_t *ptr = kind == 2 ? lv->small_ptr : kind ? lv->far_ptr : lv->near_ptr;
+    const int64_t *col = kind == 2 ? lv->small_col : kind ? lv->far_col : lv->near_col;
     memcpy(row_ptr, ptr, sizeof(int64_t) * (size_t)(lv->nb + 1));
     memcpy(cols, col, sizeof(int64_t) * (size_t)ptr[lv->nb]);
 }
@@ -726,9 +754,15 @@ int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all,
         free(W);
     }
 
-    /* remaining near-field interactions at the last depth: exact sums */
-    {
-        const olevel *lv = &t->lev[t->L];
+    /* exact sums: the small-field pairs of every depth (Sec. 4.2) and the near-field
+     * interactions that remain at the last depth */
+    for (int l = 1; l <= t->L + 1; ++l) {
+        const int last = l == t->L + 1;
+        const olevel *lv = &t->lev[last ? t->L : l];
+        const int64_t *ptr = last ? lv->near_ptr : lv->small_ptr;
+        const int64_t *col = last ? lv->near_col : lv->small_col;
+        if (!ptr || ptr[lv->nb] == 0)
+            continue;
 #pragma omp parallel for schedule(dynamic, 4)
         for (int64_t a = 0; a < lv->nb; ++a) {
             double xi[ORACLE_MAX_D], xj[ORACLE_MAX_D];
@@ -736,8 +770,8 @@ int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all,
                 int64_t i = t->perm[k];
                 for (int d = 0; d < D; ++d) xi[d] = (double)X[i * D + d];
                 double acc = 0.0;
-                for (int64_t e = lv->near_ptr[a]; e < lv->near_ptr[a + 1]; ++e) {
-                    int64_t q = lv->near_col[e];
+                for (int64_t e = ptr[a]; e < ptr[a + 1]; ++e) {
+                    int64_t q = col[e];
                     for (int64_t kk = lv->start[q]; kk < lv->start[q + 1]; ++kk) {
                         int64_t j = t->perm[kk];
                         for (int d = 0; d < D; ++d) xj[d] = (double)X[j * D + d];

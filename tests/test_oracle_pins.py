@@ -694,3 +694,90 @@ def test_adaptive_far_field_bands():
     # y = far2(p=5) + far3(p=3) + near3 ;  y3 = far2(p=3) + far3(p=3) + near3
     # far2(p=5) - far2(p=3) = far2_plus_near2 - y3_cut  (the exact near(2) part cancels)
     assert np.allclose(y - y3, far2_plus_near2 - y3_cut, rtol=0, atol=1e-11 * np.abs(y).max())
+
+
+# ----------------------------------------------------------------------------
+# small field (Sec. 4.2): pairs of boxes with few points are summed directly at their depth
+# ----------------------------------------------------------------------------
+def _pair_lists_by_recursion(T, theta, rho):
+    """near / far / small pair sets per depth from the definition, in plain Python:
+    candidates(l) = children x children of near(l-1); small iff |p|+|q| <= rho, else far iff
+    the squared cell offset is >= theta^2, else near."""
+    D = T.D
+    out = {}
+    near_prev = {(0, 0)}
+    for l in range(1, T.L + 1):
+        keys, starts = T.boxes(l)
+        cnt = np.diff(starts)
+        cells = np.zeros((len(keys), D), dtype=np.int64)
+        for d in range(D):
+            for k in range(l):
+                cells[:, d] |= ((keys >> np.uint64(k * D + d)) & np.uint64(1)).astype(np.int64) << k
+        parent_of = {}
+        pk = {int(k): i for i, k in enumerate(T.boxes(l - 1)[0])}
+        children = {}
+        for a, k in enumerate(keys):
+            P = pk[int(k) >> D]
+            parent_of[a] = P
+            children.setdefault(P, []).append(a)
+        near, far, small = set(), set(), set()
+        for (P, Q) in near_prev:
+            for a in children.get(P, []):
+                for c in children.get(Q, []):
+                    if rho > 0 and cnt[a] + cnt[c] <= rho:
+                        small.add((a, c))
+                    elif int(((cells[c] - cells[a]) ** 2).sum()) >= theta * theta:
+                        far.add((a, c))
+                    else:
+                        near.add((a, c))
+        out[l] = (near, far, small)
+        near_prev = near
+    return out
+
+
+@pytest.mark.parametrize("D,n,rho,zeta", [(2, 700, 12, 6), (3, 1500, 20, 8), (1, 300, 6, 3)])
+def test_small_field_lists_follow_the_definition(D, n, rho, zeta):
+    X = inputs.points_normal(n, D, 20 + D).numpy()
+    T = oracle.Tree(X, theta=2.0, zeta=zeta, small_field=rho)
+    want = _pair_lists_by_recursion(T, 2.0, rho)
+    assert sum(len(want[l][2]) for l in want) > 0
+    for l in range(1, T.L + 1):
+        for kind in (0, 1, 2):
+            ptr, cols = T.interactions(l, kind)
+            got = {(a, int(c)) for a in range(len(ptr) - 1) for c in cols[ptr[a]:ptr[a + 1]]}
+            assert got == want[l][kind], (l, kind)
+            for a in range(len(ptr) - 1):
+                row = cols[ptr[a]:ptr[a + 1]]
+                assert np.all(np.diff(row) > 0)                 # rows stay sorted
+    # every ordered point pair is covered exactly once: far + small of every depth + near of the last
+    total = 0
+    for l in range(1, T.L + 1):
+        cnt = np.diff(T.boxes(l)[1])
+        for kind in (1, 2):
+            ptr, cols = T.interactions(l, kind)
+            total += int((np.repeat(cnt, np.diff(ptr)) * cnt[cols]).sum())
+    cnt = np.diff(T.boxes(T.L)[1])
+    ptr, cols = T.interactions(T.L, 0)
+    total += int((np.repeat(cnt, np.diff(ptr)) * cnt[cols]).sum())
+    assert total == n * n
+
+
+def test_small_field_everything_small_is_the_exact_product():
+    X = inputs.points_uniform(900, 3, 31).numpy()
+    b = inputs.rhs_normal(900, 32).numpy()
+    T = oracle.Tree(X, theta=2.0, zeta=4, small_field=2 * 900)
+    assert T.L == 1 and len(T.interactions(1, 0)[1]) == 0 and len(T.interactions(1, 1)[1]) == 0
+    assert np.allclose(T.apply(b, 0.4, 3), oracle.direct(X, b, 0.4), rtol=1e-13, atol=1e-13)
+
+
+def test_small_field_keeps_low_degree_exactness_and_does_not_hurt_accuracy():
+    X = inputs.points_normal(4000, 3, 33).numpy()
+    b = inputs.rhs_normal(4000, 34).numpy()
+    want = oracle.direct(X, b, 1.0, kernel_id=2, kparam=3)
+    got = oracle.Tree(X, zeta=8, small_field=24).apply(b, 1.0, 4, kernel_id=2, kparam=3)
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-10 * np.abs(want).max())
+    ye = oracle.direct(X, b, 0.4)
+    rel = lambda y: np.linalg.norm(y - ye) / np.linalg.norm(ye)
+    e0 = rel(oracle.f3m(X, b, 0.4, 4, zeta=16))
+    e1 = rel(oracle.f3m(X, b, 0.4, 4, zeta=16, small_field=128))
+    assert e1 <= 1.05 * e0
