@@ -64,6 +64,11 @@ typedef struct {
                                a depth uses min(interp_nodes, 3) nodes per dimension if q <= 0.01,
                                interp_nodes if q <= 5, and its far pairs are dropped if q > 5.
                                0 (default) = every depth uses interp_nodes. */
+    int32_t small_field;    /* small field of Sec. 4.2 ("Handling boxes with few points"): rho >= 0.  A pair of
+                               boxes created by a division whose point counts add up to at most rho is
+                               summed directly (exactly) at that depth, whatever its distance, and is not
+                               divided further.  0 (default) = off; the paper suggests rho = 2 * nodes per
+                               box. */
 } f3m_options;
 
 typedef struct {
@@ -90,6 +95,8 @@ typedef struct {
                                                   field), -1 if none */
     int32_t level_nodes[F3M_MAX_LEVELS + 1];   /* nodes per dimension used at each depth 1..L (0: the far
                                                   pairs of the depth are dropped by the adaptive rule) */
+    int64_t small_pairs[F3M_MAX_LEVELS + 1];   /* ordered small-field pairs per depth */
+    int64_t small_point_pairs[F3M_MAX_LEVELS + 1]; /* their point pairs; far + small + near = n*n */
 } f3m_info;
 
 typedef struct {
@@ -180,9 +187,11 @@ f3m_status f3m_plan_get_point_keys(const f3m_plan_t *plan, uint32_t *keys_host);
 f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_host,
                               uint32_t *starts_host);
 
-/* interaction list of a depth as CSR by target box rank; kind 0 = near, 1 = far;
+/* interaction list of a depth as CSR by target box rank; kind 0 = near, 1 = far,
+ * 2 = small field (pairs summed directly at that depth, f3m_options.small_field);
  * row_ptr[nboxes+1], cols[pairs] ascending inside a row.  Near lists exist for
- * every depth 0..L, far lists for 1..L. */
+ * every depth 0..L, far and small-field lists for 1..L (empty rows at depth 0 and
+ * when the rule is off). */
 f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind,
                              uint64_t *row_ptr_host, uint32_t *cols_host);
 

@@ -63,6 +63,7 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
     if (!finite_pos(eta)) return set_error(F3M_ERR_INVALID_ARG, "eta (far-field distance ratio) must be finite and > 0");
     if (opt && (opt->leaf_max < 0 || opt->max_depth < 0))
         return set_error(F3M_ERR_INVALID_ARG, "negative option value");
+    if (opt && opt->small_field < 0) return set_error(F3M_ERR_INVALID_ARG, "small_field must be >= 0");
     if (opt && !(std::isfinite(opt->eta_smooth) && opt->eta_smooth >= 0.f))
         return set_error(F3M_ERR_INVALID_ARG, "eta_smooth must be finite and >= 0");
     if (interp_nodes > 8) return set_error(F3M_ERR_UNSUPPORTED, "interp_nodes above 8 is not supported");
@@ -87,6 +88,7 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
         P->no_overlap = opt ? (opt->overlap == 0) : 1;
         P->eta_smooth = opt ? opt->eta_smooth : 0.f;
         P->adaptive_far = opt ? (opt->adaptive_far != 0) : 0;
+        P->rho = opt ? opt->small_field : 0;
         F3M_HIP(hipGetDevice(&P->device));
         if (n > 0) f3m::build_plan(*P, X, (hipStream_t)stream);
     });
@@ -165,6 +167,10 @@ f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
     for (int l = 0; l <= plan->L && plan->n > 0; ++l) out->far_point_pairs[l] = plan->lev[l].far_point_pairs;
     out->near_point_pairs = plan->near_point_pairs;
     out->smooth_depth = plan->smooth_depth;
+    for (int l = 0; l <= plan->L && plan->n > 0; ++l) {
+        out->small_pairs[l] = plan->lev[l].small_sz;
+        out->small_point_pairs[l] = plan->lev[l].small_point_pairs;
+    }
     for (int l = 0; l <= F3M_MAX_LEVELS; ++l) out->level_nodes[l] = (l >= 1 && l <= plan->L) ? plan->lev[l].p : 0;
     out->device_bytes = plan->bytes;
     return F3M_OK;
@@ -193,9 +199,18 @@ f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_
 f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind, uint64_t *row_ptr_host, uint32_t *cols_host) {
     if (!plan || !row_ptr_host || !cols_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
     if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
-    if (kind != 0 && kind != 1) return set_error(F3M_ERR_INVALID_ARG, "kind must be 0 (near) or 1 (far)");
+    if (kind < 0 || kind > 2) return set_error(F3M_ERR_INVALID_ARG, "kind must be 0 (near), 1 (far) or 2 (small field)");
     return guarded([&] {
         const f3m_level &lv = plan->lev[level];
+        if (kind == 2) {
+            if (lv.small_ptr.p) {
+                copy_to_host(row_ptr_host, lv.small_ptr.p, (size_t)lv.nb + 1);
+                copy_to_host(cols_host, lv.small_col.p, (size_t)lv.small_sz);
+            } else {
+                std::memset(row_ptr_host, 0, sizeof(uint64_t) * ((size_t)lv.nb + 1));
+            }
+            return;
+        }
         copy_to_host(row_ptr_host, kind ? lv.far_ptr.p : lv.near_ptr.p, (size_t)lv.nb + 1);
         if (kind && lv.far_implicit) {
             // this depth keeps only the lengths of its far rows

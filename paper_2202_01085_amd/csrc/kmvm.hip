@@ -87,7 +87,7 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, c
                                                  const uint32_t *__restrict__ near_col,
                                                  const uint32_t *__restrict__ tile_box,
                                                  const uint32_t *__restrict__ tile_first, int64_t ntiles,
-                                                 float nc2, float *__restrict__ ys) {
+                                                 float nc2, float *__restrict__ ys, int accumulate) {
     const int64_t t = block_index();
     if (t >= ntiles) return;
     const uint32_t a = tile_box[t];
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, c
             acc = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), bs[j], acc);
         }
     }
-    if (active) ys[k] = acc;
+    if (active) ys[k] = accumulate ? ys[k] + acc : acc;
 }
 
 // ------------------------------------------------------------------------------------
@@ -202,7 +202,8 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
                                                        const uint32_t *__restrict__ near_col,
                                                        const uint32_t *__restrict__ tile_box,
                                                        const uint32_t *__restrict__ tile_first, int64_t ntiles,
-                                                       float g, float inv_l, CentreArg C, float *__restrict__ ys) {
+                                                       float g, float inv_l, CentreArg C, float *__restrict__ ys,
+                                                       int accumulate) {
     constexpr int NC = D + 1;
     constexpr int NQ = (3 * NC + 15) / 16;   // MFMA instructions per 32 x 32 block
     const int lane = threadIdx.x & 63;
@@ -329,7 +330,7 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
     acc1 += __shfl_xor(acc1, 32, 64);
     const float res = kk ? __builtin_amdgcn_exp2f(ni[1]) * acc1 : __builtin_amdgcn_exp2f(ni[0]) * acc0;
     const uint32_t kt = k0 + kk * 32 + nn;
-    if (kt < kend) ys[kt] = res;
+    if (kt < kend) ys[kt] = accumulate ? ys[kt] + res : res;
 }
 
 // The near-field kernel for D = 3.  The sources of a target tile are the points of its near
@@ -353,7 +354,8 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ near_col,
                                                         const uint32_t *__restrict__ tile_box,
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
-                                                        float g, float inv_l, CentreArg C, float *__restrict__ ys) {
+                                                        float g, float inv_l, CentreArg C, float *__restrict__ ys,
+                                                       int accumulate) {
     constexpr int D = 3, NC = 4;
     __shared__ __attribute__((aligned(16))) float bbuf[4][64];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -497,7 +499,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     acc1 += __shfl_xor(acc1, 32, 64);
     const float res = kk ? __builtin_amdgcn_exp2f(ni[1]) * acc1 : __builtin_amdgcn_exp2f(ni[0]) * acc0;
     const uint32_t kt = k0 + kk * 32 + nn;
-    if (kt < kend) ys[kt] = res;
+    if (kt < kend) ys[kt] = accumulate ? ys[kt] + res : res;
 }
 
 // exact product, all pairs (Sec. 2, KeOps paragraph): lane = target, sources wave-uniform
@@ -1211,28 +1213,42 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         F3M_HIP(hipStreamWaitEvent(P.side, P.ev_fork, 0));
     }
     F3M_HIP(hipEventRecord(P.ev_p2p0, sn));
-    if (leaf.near_sz == 0) {
-        // smooth field (Sec. 4.3): every pair was interpolated, no near field is left
-        zero_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.yn.p, n);
-    } else {
+    // exact sums over a CSR list of box pairs of one depth (target tiles given), into yn
+    auto direct_pairs = [&](int l, const uint64_t *row_ptr, const uint32_t *cols, const uint32_t *tile_box,
+                            const uint32_t *tile_first, int64_t ntiles, int accumulate) {
+        f3m_level &lv = P.lev[l];
         // c l^2 bounds the magnitude of the expanded exponent terms in box-local coordinates
         // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
-        const CentreArg CL = make_centre(P, P.L);
+        const CentreArg CL = make_centre(P, l);
         const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
         const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
-        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024;
+        // the Gram form assumes sources within a few boxes of the target (near pairs); small-field
+        // pairs may be far pairs, several boxes away, so they take it only when adjacent boxes are all there is
+        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 && !accumulate;
         if (gram && D == 3)
-            p2p_gram3_kernel<<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
-                P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, P.yn.p);
+            p2p_gram3_kernel<<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate);
         else if (gram)
-            p2p_mfma_kernel<D><<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, P.bs.p, leaf.start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p,
-                P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, P.yn.p);
+            p2p_mfma_kernel<D><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate);
         else
-            p2p_kernel<D><<<grid_for(P.ntiles), dim3(64), 0, sn>>>(P.Xs.p, P.bs.p, leaf.start.p, leaf.near_ptr.p,
-                                                                  leaf.near_col.p, P.tile_box.p, P.tile_first.p,
-                                                                  P.ntiles, nc2, P.yn.p);
+            p2p_kernel<D><<<grid_for(ntiles), dim3(64), 0, sn>>>(P.Xs.p, P.bs.p, lv.start.p, row_ptr, cols, tile_box,
+                                                                tile_first, ntiles, nc2, P.yn.p, accumulate);
+        F3M_HIP(hipGetLastError());
+    };
+    if (leaf.near_sz == 0) {
+        // every pair was interpolated (smooth field, Sec. 4.3) or summed at its own depth (small field)
+        zero_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.yn.p, n);
+    } else {
+        direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, 0);
+    }
+    // small-field pairs of every depth (Sec. 4.2), added on top
+    for (int l = 1; l <= P.L; ++l) {
+        f3m_level &lv = P.lev[l];
+        if (lv.small_sz > 0)
+            direct_pairs(l, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p, lv.sm_tile_first.p, lv.sm_ntiles, 1);
     }
     F3M_HIP(hipGetLastError());
     F3M_HIP(hipEventRecord(P.ev_p2p1, sn));

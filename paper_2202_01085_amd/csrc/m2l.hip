@@ -51,11 +51,13 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
                                                           const int32_t *__restrict__ cell,
                                                           const uint32_t *__restrict__ key, int64_t nparents,
                                                           int64_t per_xcd, const float *__restrict__ G, int all_far,
+                                                          const uint32_t *__restrict__ start, uint32_t rho,
                                                           const float *__restrict__ W, float *__restrict__ V) {
     __shared__ float rows[ST_CAND * 64];
     __shared__ int present[ST_CAND];
     __shared__ uint32_t cand[ST_CAND];      // candidate k of near parent j at [8 j + k]: rank or ~0
     __shared__ int cpos[ST_CAND];           // its position in the 6 x 6 x 6 grid
+    __shared__ uint32_t ccnt[ST_CAND];      // points of the candidate at a grid position (small-field rule)
     __shared__ uint32_t qfirst[27], qcount[27];
     __shared__ float gs[7 * 16];            // the factor table
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -89,6 +91,7 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
             const int pos = px + 6 * py + 36 * pz;     // in [0, 216): the near box is within one cell of the parent
             cpos[tid] = pos;
             present[pos] = 1;
+            if (rho) ccnt[pos] = start[c + 1] - start[c];
         }
         cand[tid] = c;
     }
@@ -112,6 +115,7 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
         if ((key[c] & 7u) == (uint32_t)w) t = c;
     if (t == 0xFFFFFFFFu) return;
     const int tx = w & 1, ty = (w >> 1) & 1, tz = w >> 2;
+    const uint32_t tcnt = rho ? start[t + 1] - start[t] : 0u;
     // far and present candidates, one bit each: bit cx + 8 (cy + 6 cz), so that the six bits of a
     // line of the grid sit in one byte
     uint64_t mask[5];
@@ -124,6 +128,8 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
             const int ox = cx - 2 - tx, oy = cy - 2 - ty, oz = cz - 2 - tz;
             // all_far: the smooth depth of Sec. 4.3, where adjacent pairs are interpolated too
             ok = present[cx + 6 * ln] != 0 && (all_far || ox * ox + oy * oy + oz * oz >= 4);
+            // small field (Sec. 4.2): a pair with at most rho points is summed directly elsewhere
+            if (ok && rho && tcnt + ccnt[cx + 6 * ln] <= rho) ok = false;
         }
         mask[k] = __ballot(ok);
     }
@@ -202,7 +208,7 @@ bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStre
     const int64_t per_xcd = cdiv(up.nb, 8);
     m2l_stencil_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p, up.cell.p,
                                                                 lv.cell.p, lv.key.p, up.nb, per_xcd, lv.gtab.p,
-                                                                lv.smooth ? 1 : 0, W, V);
+                                                                lv.smooth ? 1 : 0, lv.start.p, (uint32_t)P.rho, W, V);
     F3M_HIP(hipGetLastError());
     return true;
 }

@@ -14,6 +14,12 @@ struct f3m_level {
     f3m::DevBuf<uint32_t> near_col, far_col;
     int64_t near_sz = 0, far_sz = 0;
     int64_t far_point_pairs = 0;        // sum of |p||q| over the far pairs of this depth
+    // small field (Sec. 4.2): pairs summed directly at this depth, and the target tiles of their rows
+    f3m::DevBuf<uint64_t> small_ptr;    // [nb+1]
+    f3m::DevBuf<uint32_t> small_col;
+    int64_t small_sz = 0, small_point_pairs = 0;
+    int64_t sm_ntiles = 0;
+    f3m::DevBuf<uint32_t> sm_tile_box, sm_tile_first;
     // P2M work split: a chunk is a run of at most P2M_CHUNK points of one box
     int64_t nchunks = 0;
     f3m::DevBuf<uint32_t> chunk_box;    // [nchunks]
@@ -46,6 +52,7 @@ struct f3m_plan_s {
     int leaf_max = 128, max_depth = 0, force_all_near = 0, no_overlap = 0;
     float eta_smooth = 0.f;                     // smooth-field limit of Sec. 4.3 (0 = off)
     int adaptive_far = 0;                       // adaptive far-field node rule of Sec. 4.3
+    int64_t rho = 0;                            // small-field limit of Sec. 4.2 (0 = off)
     int smooth_depth = -1;                      // depth whose adjacent pairs are interpolated, or -1
     hipStream_t side = nullptr;                 // second stream for the near field
     hipEvent_t ev_fork = nullptr, ev_join = nullptr, ev_p2p0 = nullptr, ev_p2p1 = nullptr;

@@ -420,24 +420,32 @@ __global__ __launch_bounds__(256) void cells_kernel(const uint32_t *__restrict__
 // that side: depths whose M2L works on the candidate grid keep only the far counts, and their
 // far rows are produced on request.
 // ------------------------------------------------------------------------------------
+struct ListArg {
+    int T;                 // a pair is far iff the squared integer cell offset is >= T
+    int mode;              // 0: far rule, 1: all near, 2: all far (smooth depth, Sec. 4.3)
+    uint32_t rho;          // small field (Sec. 4.2): |p| + |q| <= rho goes on the direct list; 0 = off
+    const uint32_t *start; // point intervals of this depth (box sizes for the small-field rule)
+    uint32_t *cnt_near, *cnt_far, *cnt_small;         // pass 0: row lengths
+    const uint64_t *near_ptr, *far_ptr, *small_ptr;   // pass 1: row offsets
+    uint32_t *near_col, *far_col, *small_col;         // pass 1: columns (null: that list is not written)
+};
+
 template <int D>
 __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const uint32_t *__restrict__ parent,
                                                     const int32_t *__restrict__ cell,
                                                     const uint64_t *__restrict__ up_near_ptr,
                                                     const uint32_t *__restrict__ up_near_col,
-                                                    const uint32_t *__restrict__ up_cstart, int T, int mode /* 0: far rule, 1: all near, 2: all far */,
-                                                    uint32_t *__restrict__ cnt_near, uint32_t *__restrict__ cnt_far,
-                                                    const uint64_t *__restrict__ near_ptr,
-                                                    const uint64_t *__restrict__ far_ptr,
-                                                    uint32_t *__restrict__ near_col, uint32_t *__restrict__ far_col) {
+                                                    const uint32_t *__restrict__ up_cstart, ListArg A) {
     int64_t a = (int64_t)blockIdx.x * 128 + threadIdx.x;
     if (a >= nb) return;
     int32_t ca[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) ca[d] = cell[a * D + d];
     uint32_t P = parent[a];
-    uint64_t nn = 0, nf = 0;
-    uint64_t nbase = pass ? near_ptr[a] : 0, fbase = pass ? far_ptr[a] : 0;
+    uint64_t nn = 0, nf = 0, ns = 0;
+    const uint64_t nbase = pass && A.near_ptr ? A.near_ptr[a] : 0, fbase = pass && A.far_ptr ? A.far_ptr[a] : 0,
+                   sbase = pass && A.small_ptr ? A.small_ptr[a] : 0;
+    const uint32_t cnt_a = A.rho ? A.start[a + 1] - A.start[a] : 0u;
     for (uint64_t e = up_near_ptr[P]; e < up_near_ptr[P + 1]; ++e) {
         uint32_t Q = up_near_col[e];
         uint32_t b1 = up_cstart[Q + 1];
@@ -449,19 +457,24 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
                 o[d] = cell[(int64_t)bq * D + d] - ca[d];
                 d2 += o[d] * o[d];
             }
-            bool is_far = mode == 2 || (mode == 0 && d2 >= T);
-            if (is_far) {
-                if (pass && far_col) far_col[fbase + nf] = bq;
+            const bool is_small = A.rho && A.mode != 1 && cnt_a + (A.start[bq + 1] - A.start[bq]) <= A.rho;
+            const bool is_far = A.mode == 2 || (A.mode == 0 && d2 >= A.T);
+            if (is_small) {
+                if (pass && A.small_col) A.small_col[sbase + ns] = bq;
+                ++ns;
+            } else if (is_far) {
+                if (pass && A.far_col) A.far_col[fbase + nf] = bq;
                 ++nf;
             } else {
-                if (pass && near_col) near_col[nbase + nn] = bq;
+                if (pass && A.near_col) A.near_col[nbase + nn] = bq;
                 ++nn;
             }
         }
     }
     if (!pass) {
-        cnt_near[a] = (uint32_t)nn;
-        cnt_far[a] = (uint32_t)nf;
+        A.cnt_near[a] = (uint32_t)nn;
+        A.cnt_far[a] = (uint32_t)nf;
+        if (A.cnt_small) A.cnt_small[a] = (uint32_t)ns;
     }
 }
 
@@ -507,11 +520,25 @@ __global__ __launch_bounds__(256) void chunk_box_kernel(const uint32_t *__restri
     chunk_box[c] = (uint32_t)lo;
 }
 
+// runs of at most `chunk` points inside the boxes whose row of a CSR list is not empty
+struct ChunkCountIfIn {
+    const uint32_t *start;
+    const uint64_t *row_ptr;
+    uint32_t chunk;
+    __device__ uint64_t operator()(int64_t a) const {
+        return row_ptr[a + 1] > row_ptr[a] ? (start[a + 1] - start[a] + chunk - 1) / chunk : 0;
+    }
+};
+
 static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevBuf<uint32_t> &first,
-                         DevBuf<uint32_t> &cbox, int64_t &nchunks, int64_t *tally, hipStream_t st) {
+                         DevBuf<uint32_t> &cbox, int64_t &nchunks, int64_t *tally, hipStream_t st,
+                         const uint64_t *only_rows = nullptr) {
     first.alloc((size_t)nb + 1, tally);
     uint64_t total = 0;
-    exclusive_scan(ChunkCountIn{start, chunk}, nb, U32Out{first.p}, &total, st);
+    if (only_rows)
+        exclusive_scan(ChunkCountIfIn{start, only_rows, chunk}, nb, U32Out{first.p}, &total, st);
+    else
+        exclusive_scan(ChunkCountIn{start, chunk}, nb, U32Out{first.p}, &total, st);
     nchunks = (int64_t)total;
     set_u32_kernel<<<1, 1, 0, st>>>(first.p + nb, (uint32_t)total);
     cbox.alloc((size_t)nchunks, tally);
@@ -687,25 +714,39 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lv.far_sz = 0;
         } else {
             f3m_level &up = P.lev[l - 1];
-            DevBuf<uint32_t> cn, cf;
+            DevBuf<uint32_t> cn, cf, cs;
             cn.alloc((size_t)lv.nb);
             cf.alloc((size_t)lv.nb);
+            if (P.rho > 0) cs.alloc((size_t)lv.nb);
             unsigned grid = (unsigned)cdiv(lv.nb, 128);
             // Sec. 4.3: once the boxes pass the smoothness criterion every pair left is interpolated
             lv.smooth = !P.force_all_near && smooth_rule((double)P.E, l, D, (double)P.gamma, (double)P.eta_smooth);
             if (lv.smooth) P.smooth_depth = l;
-            const int mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
+            ListArg A{};
+            A.T = P.T;
+            A.mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
+            A.rho = (uint32_t)P.rho;
+            A.start = lv.start.p;
+            A.cnt_near = cn.p;
+            A.cnt_far = cf.p;
+            A.cnt_small = cs.p;
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, up.cstart.p, P.T, mode, cn.p,
-                                                             cf.p, nullptr, nullptr, nullptr, nullptr);
+                                                             up.near_col.p, up.cstart.p, A);
             F3M_HIP(hipGetLastError());
-            uint64_t tn = 0, tf = 0;
+            uint64_t tn = 0, tf = 0, ts = 0;
             exclusive_scan(U32In{cn.p}, lv.nb, PtrOut{lv.near_ptr.p}, &tn, st);
             exclusive_scan(U32In{cf.p}, lv.nb, PtrOut{lv.far_ptr.p}, &tf, st);
             set_u64_kernel<<<1, 1, 0, st>>>(lv.near_ptr.p + lv.nb, tn);
             set_u64_kernel<<<1, 1, 0, st>>>(lv.far_ptr.p + lv.nb, tf);
+            if (P.rho > 0) {
+                lv.small_ptr.alloc((size_t)lv.nb + 1, tally);
+                exclusive_scan(U32In{cs.p}, lv.nb, PtrOut{lv.small_ptr.p}, &ts, st);
+                set_u64_kernel<<<1, 1, 0, st>>>(lv.small_ptr.p + lv.nb, ts);
+                lv.small_col.alloc((size_t)ts, tally);
+            }
             lv.near_sz = (int64_t)tn;
             lv.far_sz = (int64_t)tf;
+            lv.small_sz = (int64_t)ts;
             lv.near_col.alloc((size_t)tn, tally);
             lv.p = P.adaptive_far ? adaptive_nodes((double)P.E, l, (double)P.gamma, P.p) : P.p;
             lv.r = 1;
@@ -718,10 +759,14 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             } else {
                 lv.far_col.alloc((size_t)tf, tally);
             }
+            A.near_ptr = lv.near_ptr.p;
+            A.far_ptr = lv.far_ptr.p;
+            A.small_ptr = lv.small_ptr.p;
+            A.near_col = lv.near_col.p;
+            A.far_col = lv.far_implicit ? nullptr : lv.far_col.p;
+            A.small_col = lv.small_col.p;
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, up.cstart.p, P.T, mode, nullptr,
-                                                             nullptr, lv.near_ptr.p, lv.far_ptr.p, lv.near_col.p,
-                                                             lv.far_implicit ? nullptr : lv.far_col.p);
+                                                             up.near_col.p, up.cstart.p, A);
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
@@ -777,6 +822,13 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         max_part = std::max(max_part, lv.nchunks * (int64_t)lv.r);
     }
     build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
+    // target tiles of the small-field rows of every depth (Sec. 4.2)
+    for (int k = 1; k <= P.L; ++k) {
+        f3m_level &lv = P.lev[k];
+        if (lv.small_sz > 0)
+            build_chunks(lv.start.p, lv.nb, 64, lv.sm_tile_first, lv.sm_tile_box, lv.sm_ntiles, tally, st,
+                         lv.small_ptr.p);
+    }
     P.bs.alloc((size_t)n + PAD_POINTS, tally);
     F3M_HIP(hipMemsetAsync(P.bs.p + n, 0, (size_t)PAD_POINTS * sizeof(float), st));
     P.ys.alloc((size_t)n, tally);
@@ -807,11 +859,16 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st) {
     const f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
     const unsigned grid = (unsigned)cdiv(lv.nb, 128);
+    ListArg A{};
+    A.T = P.T;
+    A.mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
+    A.rho = (uint32_t)P.rho;
+    A.start = lv.start.p;
+    A.far_ptr = lv.far_ptr.p;
+    A.far_col = cols_dev;
     auto launch = [&](auto kern) {
         kern<<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p, up.near_col.p,
-                                               up.cstart.p, P.T, P.force_all_near ? 1 : lv.smooth ? 2 : 0, nullptr, nullptr,
-                                               lv.near_ptr.p,
-                                               lv.far_ptr.p, nullptr, cols_dev);
+                                               up.cstart.p, A);
     };
     switch (P.D) {
         case 1: launch(lists_kernel<1>); break;
@@ -839,6 +896,12 @@ void compute_far_point_pairs(f3m_plan_s &P) {
     }
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
+        lv.small_point_pairs = 0;
+        if (lv.small_sz > 0) {
+            ScanState S;
+            scan_prepare(NearPairsIn{lv.start.p, lv.small_ptr.p, lv.small_col.p}, lv.nb, S, true, nullptr);
+            lv.small_point_pairs = (int64_t)S.total;
+        }
         lv.far_point_pairs = 0;
         if (lv.far_sz == 0) continue;
         if (lv.far_implicit) {

@@ -29,7 +29,7 @@ class F3MError(RuntimeError):
 class Options(ctypes.Structure):
     _fields_ = [("leaf_max", ctypes.c_int32), ("max_depth", ctypes.c_int32),
                 ("force_all_near", ctypes.c_int32), ("overlap", ctypes.c_int32),
-                ("eta_smooth", ctypes.c_float), ("adaptive_far", ctypes.c_int32)]
+                ("eta_smooth", ctypes.c_float), ("adaptive_far", ctypes.c_int32), ("small_field", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -41,7 +41,9 @@ class Info(ctypes.Structure):
                 ("near_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)), ("far_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("far_point_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
                 ("near_point_pairs", ctypes.c_int64), ("device_bytes", ctypes.c_int64),
-                ("smooth_depth", ctypes.c_int32), ("level_nodes", ctypes.c_int32 * (MAX_LEVELS + 1))]
+                ("smooth_depth", ctypes.c_int32), ("level_nodes", ctypes.c_int32 * (MAX_LEVELS + 1)),
+                ("small_pairs", ctypes.c_int64 * (MAX_LEVELS + 1)),
+                ("small_point_pairs", ctypes.c_int64 * (MAX_LEVELS + 1))]
 
 
 class Times(ctypes.Structure):
@@ -113,12 +115,12 @@ class Plan:
     """f3m_plan / f3m_plan_ex: the partition and interaction lists of one point set."""
 
     def __init__(self, X, lengthscale, interp_nodes, eta=2.0, leaf_max=0, max_depth=0, force_all_near=False,
-                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False):
+                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False, small_field=0):
         n, D = X.shape
         self.n, self.D = int(n), int(D)
         self._h = ctypes.c_void_p()
         opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), int(bool(overlap)),
-                      float(eta_smooth), int(bool(adaptive_far)))
+                      float(eta_smooth), int(bool(adaptive_far)), int(small_field))
         xp = _dev_f32(X, "X") if n > 0 else ctypes.c_void_p()
         _check(lib().f3m_plan_ex(xp, self.n, self.D, float(lengthscale), int(interp_nodes), float(eta),
                                  ctypes.byref(opt), _stream(stream), ctypes.byref(self._h)))
@@ -166,7 +168,7 @@ class Plan:
     def interactions(self, level, kind):
         inf = self.info()
         nb = int(inf.nboxes[level])
-        sz = int((inf.far_pairs if kind else inf.near_pairs)[level])
+        sz = int((inf.near_pairs, inf.far_pairs, inf.small_pairs)[kind][level])
         ptr = np.empty(nb + 1, dtype=np.uint64)
         cols = np.empty(max(sz, 1), dtype=np.uint32)
         _check(lib().f3m_plan_get_list(self._h, int(level), int(kind), _np_ptr(ptr), _np_ptr(cols)))

@@ -58,7 +58,7 @@ def check_plan_bit_exact(plan, T):
         okeys, ostarts = T.boxes(l)
         assert np.array_equal(keys.astype(np.uint64), okeys), l
         assert np.array_equal(starts.astype(np.int64), ostarts), l
-        for kind in (0, 1):
+        for kind in (0, 1, 2):
             ptr, cols = plan.interactions(l, kind)
             optr, ocols = T.interactions(l, kind)
             assert np.array_equal(ptr.astype(np.int64), optr), (l, kind)
@@ -309,6 +309,42 @@ def test_smooth_and_adaptive_parity(n, D, dist, p, gamma, zeta, eta_smooth, adap
     if eta_smooth > 0 and T.smooth_depth > 0:
         assert inf.near_pairs[T.L] == 0
         assert sum(inf.far_point_pairs[l] for l in range(T.L + 1)) == n * n
+    y = plan.kmvm(bd)
+    torch.cuda.synchronize()
+    yo = T.apply(b.numpy(), g32(gamma), p, adaptive=adaptive)
+    e = rel(y.cpu().numpy(), yo)
+    say("  rel err vs CPU F3M %.3e" % e)
+    assert e <= TOL_F3M
+    assert torch.equal(y, plan.kmvm(bd))
+
+
+SMALL_CASES = [
+    # n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive
+    (30_000, 3, "normal", 4, 0.3, 32, 128, 0.0, False),    # the paper's rho = 2 r: tree stops early in the tails
+    (30_000, 3, "normal", 4, 0.3, 32, 16, 0.0, False),     # candidate-grid M2L with small pairs masked out
+    (20_000, 3, "uniform", 4, 1.0, 16, 40, 0.0, False),
+    (8_000, 2, "normal", 5, 0.4, 8, 12, 0.0, False),       # general path
+    (5_000, 5, "normal", 2, 1.0, 8, 10, 0.0, False),
+    (30_000, 3, "normal", 4, 1.5, 16, 24, 0.05, True),     # with the smooth field and the adaptive rule
+]
+
+
+@pytest.mark.parametrize("n,D,dist,p,gamma,zeta,rho,eta_smooth,adaptive", SMALL_CASES)
+def test_small_field_parity(n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive):
+    say("f3m small field n=%d D=%d %s p=%d gamma=%g zeta=%d rho=%d eta_smooth=%g adaptive=%s"
+        % (n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive))
+    X = cloud(dist, n, D, 1200 + D)
+    b = inputs.rhs_normal(n, 2200 + D)
+    T = oracle.Tree(X.numpy(), theta=2.0, zeta=zeta, gamma=g32(gamma), eta_smooth=g32(eta_smooth), small_field=rho)
+    Xd, bd = to_dev(X, b)
+    plan = f3m.Plan(Xd, gamma, p, 2.0, leaf_max=zeta, eta_smooth=eta_smooth, adaptive_far=adaptive, small_field=rho)
+    check_plan_bit_exact(plan, T)
+    inf = plan.info()
+    L = T.L
+    say("  L=%d small pairs per depth %s far %s near_L=%d" % (L, list(inf.small_pairs)[1:L + 1], list(inf.far_pairs)[1:L + 1],
+                                                             inf.near_pairs[L]))
+    assert sum(inf.small_pairs[l] for l in range(L + 1)) > 0
+    assert (inf.near_point_pairs + sum(inf.far_point_pairs[l] + inf.small_point_pairs[l] for l in range(L + 1))) == n * n
     y = plan.kmvm(bd)
     torch.cuda.synchronize()
     yo = T.apply(b.numpy(), g32(gamma), p, adaptive=adaptive)
