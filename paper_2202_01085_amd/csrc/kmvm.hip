@@ -502,6 +502,104 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     if (kt < kend) ys[kt] = accumulate ? ys[kt] + res : res;
 }
 
+// Direct sums for the small-field pairs of a depth (Sec. 4.2): both boxes of a pair hold few
+// points, so neither a lane per target nor blocks of 32 x 32 would be filled.  Here lane =
+// source: the sources of a target box's row are taken as one dense sequence over its boxes
+// (the lane-held segment table of p2p_gram3_kernel), 64 per step, and a wavefront handles a run
+// of at most SMALL_TT targets of one box, whose coordinates are wave-uniform.  Every lane keeps
+// one partial sum per target; they are added across the lanes once, at the end.  Differences
+// are formed directly (the pairs may be several boxes apart).  The result is ADDED to ys.
+template <int D>
+constexpr int small_tt() { return D <= 4 ? 16 : 8; }
+
+template <int D>
+__global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                        const uint32_t *__restrict__ start,
+                                                        const uint64_t *__restrict__ row_ptr,
+                                                        const uint32_t *__restrict__ cols,
+                                                        const uint32_t *__restrict__ tile_box,
+                                                        const uint32_t *__restrict__ tile_first, int64_t ntiles,
+                                                        float nc2, float *__restrict__ ys) {
+    constexpr int TT = small_tt<D>();
+    const int lane = threadIdx.x & 63;
+    const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
+    if (t >= ntiles) return;
+    const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
+    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * (uint32_t)TT;
+    const uint32_t kend = start[a + 1];
+    const int nt = (int)(kend - k0 < (uint32_t)TT ? kend - k0 : (uint32_t)TT);   // wave-uniform
+    float xt[TT][D];   // target coordinates, wave-uniform (rows beyond nt repeat an in-bounds point)
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const uint32_t kt = k0 + (uint32_t)(tt < nt ? tt : 0);
+#pragma unroll
+        for (int d = 0; d < D; ++d) xt[tt][d] = Xs[(int64_t)kt * D + d];
+    }
+    float acc[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) acc[tt] = 0.f;
+
+    const uint64_t e0 = row_ptr[a], e1 = row_ptr[a + 1];
+    for (uint64_t er = e0; er < e1; er += 64) {   // rounds of up to 64 boxes of the row
+        const int m = (int)(e1 - er < 64 ? e1 - er : 64);
+        uint32_t sfirst = 0, slen = 0;
+        if (lane < m) {
+            const uint32_t q = cols[er + lane];
+            sfirst = start[q];
+            slen = start[q + 1] - sfirst;
+        }
+        uint32_t cend = slen;   // inclusive running sum of the lengths over the lanes
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t up = __shfl_up(cend, d, 64);
+            if (lane >= d) cend += up;
+        }
+        const uint32_t cbeg = cend - slen;
+        const uint32_t S = __builtin_amdgcn_readlane(cend, 63);
+        if (S == 0) continue;
+        int r = 0;
+        for (uint32_t w0 = 0; w0 < S; w0 += 64) {
+            const uint32_t p = w0 + lane;
+            while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;   // ends: w0 < S = cend of lane 63
+            uint32_t src = 0;
+            for (int rr = r; rr < m; ++rr) {
+                const uint32_t c0 = __builtin_amdgcn_readlane(cbeg, rr);
+                if (c0 >= w0 + 64) break;
+                const uint32_t c1 = __builtin_amdgcn_readlane(cend, rr), s0 = __builtin_amdgcn_readlane(sfirst, rr);
+                if (p >= c0 && p < c1) src = s0 + (p - c0);
+            }
+            float x[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)src * D + d];
+            const float bv = p < S ? bs[src] : 0.f;   // positions beyond the sequence contribute nothing
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                if (tt < nt) {
+                    float r2 = 0.f;
+#pragma unroll
+                    for (int d = 0; d < D; ++d) {
+                        const float df = x[d] - xt[tt][d];
+                        r2 = fmaf(df, df, r2);
+                    }
+                    acc[tt] = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), bv, acc[tt]);
+                }
+            }
+        }
+    }
+    // sums over the lanes; lane tt keeps the total of target tt
+    float res = 0.f;
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        if (tt < nt) {
+            float v = acc[tt];
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+            if (lane == tt) res = v;
+        }
+    }
+    if (lane < nt) ys[k0 + lane] += res;
+}
+
 // exact product, all pairs (Sec. 2, KeOps paragraph): lane = target, sources wave-uniform
 template <int D>
 __global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X, const float *__restrict__ b,
@@ -1222,9 +1320,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         const CentreArg CL = make_centre(P, l);
         const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
         const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
-        // the Gram form assumes sources within a few boxes of the target (near pairs); small-field
-        // pairs may be far pairs, several boxes away, so they take it only when adjacent boxes are all there is
-        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 && !accumulate;
+        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024;
         if (gram && D == 3)
             p2p_gram3_kernel<<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
@@ -1247,8 +1343,12 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     // small-field pairs of every depth (Sec. 4.2), added on top
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
-        if (lv.small_sz > 0)
-            direct_pairs(l, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p, lv.sm_tile_first.p, lv.sm_ntiles, 1);
+        if (lv.small_sz > 0) {
+            p2p_small_kernel<D><<<grid_for(cdiv(lv.sm_ntiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, P.bs.p, lv.start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p, lv.sm_tile_first.p,
+                lv.sm_ntiles, nc2, P.yn.p);
+            F3M_HIP(hipGetLastError());
+        }
     }
     F3M_HIP(hipGetLastError());
     F3M_HIP(hipEventRecord(P.ev_p2p1, sn));

@@ -826,8 +826,8 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
         if (lv.small_sz > 0)
-            build_chunks(lv.start.p, lv.nb, 64, lv.sm_tile_first, lv.sm_tile_box, lv.sm_ntiles, tally, st,
-                         lv.small_ptr.p);
+            build_chunks(lv.start.p, lv.nb, D <= 4 ? 16 : 8, lv.sm_tile_first, lv.sm_tile_box, lv.sm_ntiles, tally, st,
+                         lv.small_ptr.p);   // runs of targets as p2p_small_kernel takes them
     }
     P.bs.alloc((size_t)n + PAD_POINTS, tally);
     F3M_HIP(hipMemsetAsync(P.bs.p + n, 0, (size_t)PAD_POINTS * sizeof(float), st));
