@@ -414,7 +414,10 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         opA = __builtin_bit_cast(h8v, ra);
         opB = __builtin_bit_cast(h8v, rb);
     };
-    // one block of 32 sources against the tile; bq = right-hand sides at bw[first .. first + 31]
+    // one block of 32 sources against the tile; bq = right-hand sides at bw[first .. first + 31].
+    // (The two column blocks are summed in differently shaped code on purpose: identical
+    // sequences get merged by the compiler into one that addresses the accumulators through
+    // scratch memory.)
     auto block = [&](const h8v &op, int first) {
         float4 bq[4];
 #pragma unroll
@@ -427,8 +430,13 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], c1, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
+            float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bf[v], acc1);
+            for (int v = 0; v < 16; v += 2) {
+                s1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bf[v], s1);
+                s2 = fmaf(__builtin_amdgcn_exp2f(c1[v + 1]), bf[v + 1], s2);
+            }
+            acc1 += s1 + s2;
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
