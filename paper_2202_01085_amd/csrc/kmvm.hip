@@ -298,8 +298,15 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
             for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bq[v >> 2].v[v & 3], acc0);
         }
     };
+    // A row can be empty (with the small field or the smooth field the box's own pair may be
+    // handled elsewhere): nothing to add, and next_run must not read past the row.
+    if (e == e1) {
+        const uint32_t kt = k0 + kk * 32 + nn;
+        if (kt < kend) ys[kt] = accumulate ? ys[kt] : 0.f;
+        return;
+    }
     // two register sets in turn: the loads of the next block are in flight while the current
-    // one is worked on.  The near list is never empty (a box is near to itself).
+    // one is worked on.
     float xa[D], xb[D];
     float4u ba[4], bb[4];
     uint32_t jba, jea, jbb, jeb;

@@ -319,25 +319,31 @@ def test_smooth_and_adaptive_parity(n, D, dist, p, gamma, zeta, eta_smooth, adap
 
 
 SMALL_CASES = [
-    # n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive
-    (30_000, 3, "normal", 4, 0.3, 32, 128, 0.0, False),    # the paper's rho = 2 r: tree stops early in the tails
-    (30_000, 3, "normal", 4, 0.3, 32, 16, 0.0, False),     # candidate-grid M2L with small pairs masked out
-    (20_000, 3, "uniform", 4, 1.0, 16, 40, 0.0, False),
-    (8_000, 2, "normal", 5, 0.4, 8, 12, 0.0, False),       # general path
-    (5_000, 5, "normal", 2, 1.0, 8, 10, 0.0, False),
-    (30_000, 3, "normal", 4, 1.5, 16, 24, 0.05, True),     # with the smooth field and the adaptive rule
+    # n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive, max_depth, theta
+    (30_000, 3, "normal", 4, 0.3, 32, 128, 0.0, False, 0, 2.0),    # the paper's rho = 2 r: tree stops early in the tails
+    (30_000, 3, "normal", 4, 0.3, 32, 16, 0.0, False, 0, 2.0),     # candidate-grid M2L with small pairs masked out
+    (20_000, 3, "uniform", 4, 1.0, 16, 40, 0.0, False, 0, 2.0),
+    (8_000, 2, "normal", 5, 0.4, 8, 12, 0.0, False, 0, 2.0),       # general path
+    (5_000, 5, "normal", 2, 1.0, 8, 10, 0.0, False, 0, 2.0),
+    (30_000, 3, "normal", 4, 1.5, 16, 24, 0.05, True, 0, 2.0),     # with the smooth field and the adaptive rule
+    # leaf boxes whose near row is empty (every partner small) under the Gram near kernel for D != 3;
+    # in the second case the last leaf box is one of them
+    (2_324, 7, "mixture", 2, 3.8849, 16, 32, 0.0, False, 2, 2.0),
+    (838, 5, "normal", 3, 3.7301, 4, 8, 0.0, False, 3, 1.5),
 ]
 
 
-@pytest.mark.parametrize("n,D,dist,p,gamma,zeta,rho,eta_smooth,adaptive", SMALL_CASES)
-def test_small_field_parity(n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive):
-    say("f3m small field n=%d D=%d %s p=%d gamma=%g zeta=%d rho=%d eta_smooth=%g adaptive=%s"
-        % (n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive))
+@pytest.mark.parametrize("n,D,dist,p,gamma,zeta,rho,eta_smooth,adaptive,max_depth,theta", SMALL_CASES)
+def test_small_field_parity(n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive, max_depth, theta):
+    say("f3m small field n=%d D=%d %s p=%d gamma=%g zeta=%d rho=%d eta_smooth=%g adaptive=%s max_depth=%d theta=%g"
+        % (n, D, dist, p, gamma, zeta, rho, eta_smooth, adaptive, max_depth, theta))
     X = cloud(dist, n, D, 1200 + D)
     b = inputs.rhs_normal(n, 2200 + D)
-    T = oracle.Tree(X.numpy(), theta=2.0, zeta=zeta, gamma=g32(gamma), eta_smooth=g32(eta_smooth), small_field=rho)
+    T = oracle.Tree(X.numpy(), theta=theta, zeta=zeta, max_depth=max_depth, gamma=g32(gamma), eta_smooth=g32(eta_smooth),
+                    small_field=rho)
     Xd, bd = to_dev(X, b)
-    plan = f3m.Plan(Xd, gamma, p, 2.0, leaf_max=zeta, eta_smooth=eta_smooth, adaptive_far=adaptive, small_field=rho)
+    plan = f3m.Plan(Xd, gamma, p, theta, leaf_max=zeta, max_depth=max_depth, eta_smooth=eta_smooth, adaptive_far=adaptive,
+                    small_field=rho)
     check_plan_bit_exact(plan, T)
     inf = plan.info()
     L = T.L
