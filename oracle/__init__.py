@@ -153,7 +153,7 @@ class Tree:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:   # module globals may be gone at interpreter shutdown
             lib().oracle_tree_free(h)
 
     def nboxes(self, level):
