@@ -70,6 +70,23 @@ def lib():
         L.oracle_f3m_apply.restype = c_int
         L.oracle_f3m_apply_ex.argtypes = [c_vp, c_vp, c_dbl, c_int, c_int, c_int, c_vp, c_vp, c_int, c_int]
         L.oracle_f3m_apply_ex.restype = c_int
+        L.oracle_rows_xy.argtypes = [c_vp, c_i64, c_vp, c_i64, c_int, c_dbl, c_int, c_int, c_vp, c_vp, c_i64, c_vp]
+        L.oracle_tree2_build.argtypes = [c_vp, c_i64, c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int, c_dbl, c_dbl,
+                                         c_i64]
+        L.oracle_tree2_build.restype = c_vp
+        L.oracle_tree2_free.argtypes = [c_vp]
+        for name in ("oracle_tree2_depth", "oracle_tree2_smooth_depth"):
+            getattr(L, name).argtypes = [c_vp]
+            getattr(L, name).restype = c_int
+        L.oracle_tree2_edge.argtypes = [c_vp]
+        L.oracle_tree2_edge.restype = c_dbl
+        L.oracle_tree2_side.argtypes = [c_vp, c_int]
+        L.oracle_tree2_side.restype = c_vp
+        L.oracle_tree2_list_size.argtypes = [c_vp, c_int, c_int]
+        L.oracle_tree2_list_size.restype = c_i64
+        L.oracle_tree2_list.argtypes = [c_vp, c_int, c_int, c_vp, c_vp]
+        L.oracle_f3m2_apply.argtypes = [c_vp, c_vp, c_vp, c_dbl, c_int, c_int, c_int, c_vp, c_vp, c_int]
+        L.oracle_f3m2_apply.restype = c_int
         _lib = L
     return _lib
 
@@ -217,3 +234,89 @@ def f3m(X, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False, 
     """CPU F3M product (fp64), original point order."""
     return Tree(X, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, small_field).apply(b, gamma, p,
                                                                                                adaptive=adaptive)
+
+
+def rows_xy(X, Y, b, gamma, rows=None, kernel_id=0, kparam=0):
+    """Exact v_i = sum_j k(x_i, y_j) b_j (fp64) for the given rows of X (all rows if None)."""
+    X, Y, b = _f32(X), _f32(Y), _f32(b)
+    nx, D = X.shape
+    ny = Y.shape[0]
+    assert Y.shape[1] == D and b.shape == (ny,)
+    if rows is None:
+        idx, m, rp = None, nx, None
+    else:
+        idx = np.ascontiguousarray(rows, dtype=np.int64)
+        m, rp = idx.size, _ptr(idx)
+    y = np.empty(m, dtype=np.float64)
+    lib().oracle_rows_xy(_ptr(X), nx, _ptr(Y), ny, D, float(gamma), kernel_id, kparam, _ptr(b), rp, m, _ptr(y))
+    return y
+
+
+class _Side:
+    """One set's partition inside a Tree2 (borrowed handle): perm, point keys, boxes, beta."""
+
+    def __init__(self, owner, side, n, D):
+        self._owner, self.n, self.D = owner, n, D   # the owner keeps the handle alive
+        self._h = lib().oracle_tree2_side(owner._h, side)
+        a = np.empty(D, dtype=np.float64)
+        lib().oracle_tree_alpha(self._h, _ptr(a))
+        self.alpha = a
+        self.Lq = int(lib().oracle_tree_quant_depth(self._h))
+
+    nboxes = Tree.nboxes
+    perm = Tree.perm
+    point_keys = Tree.point_keys
+    boxes = Tree.boxes
+    beta = Tree.beta
+
+
+class Tree2:
+    """Partitions of X (targets) and Y (sources) and the interaction lists of Algorithm 1 for K(X, Y)."""
+
+    def __init__(self, X, Y, theta=2.0, zeta=128, max_depth=0, force_all_near=False, gamma=0.0, eta_smooth=0.0,
+                 small_field=0):
+        self.X, self.Y = _f32(X), _f32(Y)
+        self.nx, self.D = self.X.shape
+        self.ny = self.Y.shape[0]
+        assert self.Y.shape[1] == self.D
+        self._h = lib().oracle_tree2_build(_ptr(self.X), self.nx, _ptr(self.Y), self.ny, self.D, float(theta),
+                                           int(zeta), int(max_depth), int(bool(force_all_near)), float(gamma),
+                                           float(eta_smooth), int(small_field))
+        if not self._h:
+            raise ValueError("oracle_tree2_build rejected its arguments")
+        self.L = int(lib().oracle_tree2_depth(self._h))
+        self.smooth_depth = int(lib().oracle_tree2_smooth_depth(self._h))
+        self.E = float(lib().oracle_tree2_edge(self._h))
+        self.tx = _Side(self, 0, self.nx, self.D)
+        self.ty = _Side(self, 1, self.ny, self.D)
+
+    def __del__(self):
+        h, self._h = getattr(self, "_h", None), None
+        if h and lib is not None:
+            lib().oracle_tree2_free(h)
+
+    def interactions(self, level, kind):
+        """CSR (row_ptr, cols): rows are boxes of X, columns ranks of boxes of Y; kind 0 near, 1 far, 2 small."""
+        nb = self.tx.nboxes(level)
+        sz = int(lib().oracle_tree2_list_size(self._h, level, kind))
+        ptr = np.empty(nb + 1, dtype=np.int64)
+        cols = np.empty(max(sz, 1), dtype=np.int64)
+        lib().oracle_tree2_list(self._h, level, kind, _ptr(ptr), _ptr(cols))
+        return ptr, cols[:sz]
+
+    def apply(self, b, gamma, p, kernel_id=0, kparam=0, adaptive=False):
+        b = _f32(b)
+        assert b.shape == (self.ny,)
+        y = np.empty(self.nx, dtype=np.float64)
+        rc = lib().oracle_f3m2_apply(self._h, _ptr(self.X), _ptr(self.Y), float(gamma), int(p), kernel_id, kparam,
+                                     _ptr(b), _ptr(y), int(bool(adaptive)))
+        if rc:
+            raise ValueError("oracle_f3m2_apply rejected its arguments")
+        return y
+
+
+def f3m_xy(X, Y, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=False, eta_smooth=0.0, adaptive=False,
+           small_field=0):
+    """CPU F3M product K(X, Y) b (fp64), original order of X."""
+    return Tree2(X, Y, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, small_field).apply(
+        b, gamma, p, adaptive=adaptive)

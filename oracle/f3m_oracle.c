@@ -1,6 +1,7 @@
 /*
  * CPU oracle for the kernel matrix-vector product y = K(X,X) b and for the
- * F3M approximation of it (arXiv 2202.01085).
+ * F3M approximation of it (arXiv 2202.01085); the last section does the same for
+ * two point sets, v = K(X,Y) b (readings R8-R11 there).
  *
  * THIS FILE IS TEST INFRASTRUCTURE.  It is a plain, slow, fp64 statement of
  * what the GPU library has to compute; nothing in the product path may call
@@ -416,6 +417,63 @@ int oracle_adaptive_nodes(double E, int depth, double gamma, int p)
     return 0;
 }
 
+/* Per-dimension minimum of a point set and its largest extent, both in fp32 (R2). */
+static float point_bounds(const float *X, int64_t n, int D, float *mn_out)
+{
+    float Ef = 0.0f;
+    for (int d = 0; d < D; ++d) {
+        float mn = X[d], mx = X[d];
+        for (int64_t i = 1; i < n; ++i) {
+            float v = X[i * D + d];
+            if (v < mn) mn = v;
+            if (v > mx) mx = v;
+        }
+        volatile float ext = mx - mn;
+        if (ext > Ef) Ef = ext;
+        mn_out[d] = mn;
+    }
+    return Ef;
+}
+
+/* The points of one set in the cube anchored at alpha with edge Ef: cells and keys at the
+ * quantisation depth (R2, R3), box order, and the box table of depth 0. */
+static otree *partition_points(const float *X, int64_t n, int D, const float *alpha, float Ef)
+{
+    otree *t = (otree *)calloc(1, sizeof(otree));
+    t->n = n;
+    t->D = D;
+    t->Lq = oracle_quant_depth(D);
+    t->smooth_depth = -1;
+    for (int d = 0; d < D; ++d)
+        t->alpha[d] = (double)alpha[d];
+    t->E = (double)Ef;
+    t->s_f = Ef > 0.0f ? (float)(ldexp(1.0, t->Lq) / (double)Ef) : 0.0f;
+
+    uint32_t cmax = (uint32_t)((1ull << t->Lq) - 1);
+    t->cell = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n * (size_t)D);
+    keyidx *ki = (keyidx *)malloc(sizeof(keyidx) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) {
+        for (int d = 0; d < D; ++d) {
+            volatile float diff = X[i * D + d] - (float)t->alpha[d];
+            volatile float u = diff * t->s_f;
+            uint32_t c = (uint32_t)u;
+            t->cell[i * D + d] = c > cmax ? cmax : c;
+        }
+        ki[i].key = interleave(&t->cell[i * D], D, t->Lq);
+        ki[i].idx = i;
+    }
+    qsort(ki, (size_t)n, sizeof(keyidx), cmp_keyidx);
+    t->pkey = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)n);
+    t->perm = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
+    for (int64_t k = 0; k < n; ++k) {
+        t->pkey[k] = ki[k].key;
+        t->perm[k] = ki[k].idx;
+    }
+    free(ki);
+    divide(t, 0);
+    return t;
+}
+
 otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
                             int force_all_near, double gamma, double eta_smooth);
 otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
@@ -445,54 +503,13 @@ otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int
 {
     if (!X || n <= 0 || D < 1 || D > ORACLE_MAX_D || !(theta > 0.0) || zeta < 1)
         return NULL;
-    otree *t = (otree *)calloc(1, sizeof(otree));
-    t->n = n;
-    t->D = D;
-    t->Lq = oracle_quant_depth(D);
-    t->smooth_depth = -1;
+    /* enclosing cube: per-dim minimum, edge = largest extent (fp32, R2) */
+    float mn[ORACLE_MAX_D];
+    float Ef = point_bounds(X, n, D, mn);
+    otree *t = partition_points(X, n, D, mn, Ef);
     t->gamma = eta_smooth > 0.0 ? gamma : 0.0;
 
-    /* enclosing cube: per-dim minimum, edge = largest extent (fp32, R2) */
-    float Ef = 0.0f;
-    for (int d = 0; d < D; ++d) {
-        float mn = X[d], mx = X[d];
-        for (int64_t i = 1; i < n; ++i) {
-            float v = X[i * D + d];
-            if (v < mn) mn = v;
-            if (v > mx) mx = v;
-        }
-        volatile float ext = mx - mn;
-        if (ext > Ef) Ef = ext;
-        t->alpha[d] = (double)mn;
-    }
-    t->E = (double)Ef;
-    t->s_f = Ef > 0.0f ? (float)(ldexp(1.0, t->Lq) / (double)Ef) : 0.0f;
-
-    /* cells and keys at the quantisation depth (R2, R3) */
-    uint32_t cmax = (uint32_t)((1ull << t->Lq) - 1);
-    t->cell = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n * (size_t)D);
-    keyidx *ki = (keyidx *)malloc(sizeof(keyidx) * (size_t)n);
-    for (int64_t i = 0; i < n; ++i) {
-        for (int d = 0; d < D; ++d) {
-            volatile float diff = X[i * D + d] - (float)t->alpha[d];
-            volatile float u = diff * t->s_f;
-            uint32_t c = (uint32_t)u;
-            t->cell[i * D + d] = c > cmax ? cmax : c;
-        }
-        ki[i].key = interleave(&t->cell[i * D], D, t->Lq);
-        ki[i].idx = i;
-    }
-    qsort(ki, (size_t)n, sizeof(keyidx), cmp_keyidx);
-    t->pkey = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)n);
-    t->perm = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
-    for (int64_t k = 0; k < n; ++k) {
-        t->pkey[k] = ki[k].key;
-        t->perm[k] = ki[k].idx;
-    }
-    free(ki);
-
     /* depth 0: one box, one (near) interaction */
-    divide(t, 0);
     olevel *root = &t->lev[0];
     root->near_ptr = (int64_t *)calloc(2, sizeof(int64_t));
     root->near_ptr[1] = 1;
@@ -785,6 +802,334 @@ int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all,
     /* back to the caller's order */
     for (int64_t k = 0; k < n; ++k)
         y[t->perm[k]] = ys[k];
+    free(ys);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* two point sets: v = K(X, Y) b                                        */
+/* ------------------------------------------------------------------ */
+/* Sec. 3 states the method for a kernel evaluated on two data matrices X (targets, n_x rows)
+ * and Y (sources, n_y rows, b holds one weight per row of Y); Algorithm 1 keeps one treecode per
+ * set.  Readings for X != Y:
+ *   R8   both sets get a cube of the SAME edge E = max(largest extent of X, largest extent of Y)
+ *        (Sec. 3, enclosing formula), each anchored at its own per-dimension minimum (the alpha
+ *        of the box-index formula of Sec. 4.2 is the minimum of the set that is divided).  The
+ *        two grids have equal box edges at every depth and are shifted against each other by
+ *        alpha^Y - alpha^X.
+ *   R9   far iff |centre_y - centre_x| >= theta * l.  In units of l the centre difference of
+ *        source cell c' and target cell c is (c'_d - c_d) + u_d with u_d = (alpha^Y_d -
+ *        alpha^X_d) / l, so far iff  sum_d ((c'_d - c_d) + u_d)^2 >= theta^2.  This decision is
+ *        taken in fp64 with u_d = ((alpha^Y_d - alpha^X_d) / E) * 2^depth, the sum taken in the
+ *        order d = 0..D-1, every operation rounded on its own.  With X == Y it is R4.
+ *   R10  Algorithm 1 divides while interactions remain, the largest box of tau_x is above zeta
+ *        AND the largest box of tau_y is above zeta; depth caps as in R6.
+ *   R11  small field: |B_p^X| + |B_q^Y| <= rho.  Smooth field and adaptive rule: functions of
+ *        the common box edge, unchanged.
+ * Lists are stored by target box (a box of tau_x); the columns are ranks of boxes of tau_y. */
+typedef struct {
+    int64_t *near_ptr, *near_col, *far_ptr, *far_col, *small_ptr, *small_col;
+} olists;
+
+typedef struct {
+    otree *tx, *ty; /* the two partitions; their own list fields stay unused */
+    int D, L, smooth_depth;
+    double E, gamma, theta;
+    olists lev[ORACLE_MAX_LEVELS + 1];
+} otree2;
+
+/* y_i = sum_j k(x_i, y_j) b_j for the rows of X listed in rows[0..m) (NULL: all rows, m = n_x) */
+void oracle_rows_xy(const float *X, int64_t nx, const float *Y, int64_t ny, int D, double gamma,
+                    int kernel_id, int kparam, const float *b, const int64_t *rows, int64_t m, double *y)
+{
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t a = 0; a < m; ++a) {
+        int64_t i = rows ? rows[a] : a;
+        double xi[ORACLE_MAX_D], yj[ORACLE_MAX_D];
+        for (int d = 0; d < D; ++d)
+            xi[d] = (double)X[i * D + d];
+        double acc = 0.0;
+        for (int64_t j = 0; j < ny; ++j) {
+            for (int d = 0; d < D; ++d)
+                yj[d] = (double)Y[j * D + d];
+            acc += kernel_eval(kernel_id, kparam, gamma, D, xi, yj) * (double)b[j];
+        }
+        y[a] = acc;
+    }
+    (void)nx;
+}
+
+void oracle_tree2_free(otree2 *t)
+{
+    if (!t)
+        return;
+    for (int l = 0; l <= ORACLE_MAX_LEVELS; ++l) {
+        olists *ls = &t->lev[l];
+        free(ls->near_ptr); free(ls->near_col); free(ls->far_ptr); free(ls->far_col);
+        free(ls->small_ptr); free(ls->small_col);
+    }
+    oracle_tree_free(t->tx);
+    oracle_tree_free(t->ty);
+    free(t);
+}
+
+/* squared centre distance of source cell cb and target cell ca in units of the box edge (R9) */
+static double centre_dist2(int D, const int64_t *ca, const int64_t *cb, const double *u)
+{
+    double d2 = 0.0;
+    for (int d = 0; d < D; ++d) {
+        volatile double o = (double)(cb[d] - ca[d]) + u[d];
+        volatile double sq = o * o;
+        d2 = d2 + sq;
+    }
+    return d2;
+}
+
+/* grid shift of a depth in units of its box edge (R9) */
+static void grid_shift(const otree2 *t, int l, double *u)
+{
+    for (int d = 0; d < t->D; ++d) {
+        volatile double diff = t->ty->alpha[d] - t->tx->alpha[d];
+        volatile double q = t->E > 0.0 ? diff / t->E : 0.0;
+        u[d] = q * ldexp(1.0, l);
+    }
+}
+
+/* New interactions at depth l: children of a target box's parent's near partners, split three
+ * ways (small first, then far, else near), as for one point set. */
+static void new_interactions2(otree2 *t, int l, int force_all_near, int all_interpolated, int64_t rho)
+{
+    const olevel *xv = &t->tx->lev[l], *xu = &t->tx->lev[l - 1];
+    const olevel *yv = &t->ty->lev[l], *yu = &t->ty->lev[l - 1];
+    olists *ls = &t->lev[l], *up = &t->lev[l - 1];
+    int D = t->D;
+    int64_t nb = xv->nb;
+    double u[ORACLE_MAX_D];
+    grid_shift(t, l, u);
+    const double theta2 = t->theta * t->theta;
+    ls->near_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
+    ls->far_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
+    ls->small_ptr = (int64_t *)calloc((size_t)(nb + 1), sizeof(int64_t));
+    (void)xu;
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass == 1) {
+            for (int64_t a = 0; a < nb; ++a) {
+                ls->near_ptr[a + 1] += ls->near_ptr[a];
+                ls->far_ptr[a + 1] += ls->far_ptr[a];
+                ls->small_ptr[a + 1] += ls->small_ptr[a];
+            }
+            ls->near_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(ls->near_ptr[nb] + 1));
+            ls->far_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(ls->far_ptr[nb] + 1));
+            ls->small_col = (int64_t *)malloc(sizeof(int64_t) * (size_t)(ls->small_ptr[nb] + 1));
+        }
+#pragma omp parallel for schedule(dynamic, 64)
+        for (int64_t a = 0; a < nb; ++a) {
+            int64_t ca[ORACLE_MAX_D], cb[ORACLE_MAX_D];
+            deinterleave(xv->key[a], D, l, ca);
+            int64_t P = xv->parent[a];
+            int64_t nn = 0, nf = 0, ns = 0;
+            int64_t *ncol = pass ? ls->near_col + ls->near_ptr[a] : NULL;
+            int64_t *fcol = pass ? ls->far_col + ls->far_ptr[a] : NULL;
+            int64_t *scol = pass ? ls->small_col + ls->small_ptr[a] : NULL;
+            int64_t cnt_a = xv->start[a + 1] - xv->start[a];
+            for (int64_t e = up->near_ptr[P]; e < up->near_ptr[P + 1]; ++e) {
+                int64_t Q = up->near_col[e];
+                for (int64_t bq = yu->cstart[Q]; bq < yu->cstart[Q + 1]; ++bq) {
+                    deinterleave(yv->key[bq], D, l, cb);
+                    int is_far = all_interpolated ||
+                                 (!force_all_near && centre_dist2(D, ca, cb, u) >= theta2);
+                    int is_small = !force_all_near && rho > 0 &&
+                                   cnt_a + (yv->start[bq + 1] - yv->start[bq]) <= rho;
+                    if (is_small) {
+                        if (pass) scol[ns] = bq;
+                        ++ns;
+                    } else if (is_far) {
+                        if (pass) fcol[nf] = bq;
+                        ++nf;
+                    } else {
+                        if (pass) ncol[nn] = bq;
+                        ++nn;
+                    }
+                }
+            }
+            if (!pass) {
+                ls->near_ptr[a + 1] = nn;
+                ls->far_ptr[a + 1] = nf;
+                ls->small_ptr[a + 1] = ns;
+            }
+        }
+    }
+}
+
+/* Partitions of both sets and the interaction lists of Algorithm 1 for K(X, Y).  Arguments as
+ * oracle_tree_build_ex2.  Returns NULL on bad arguments. */
+otree2 *oracle_tree2_build(const float *X, int64_t nx, const float *Y, int64_t ny, int D, double theta,
+                           int64_t zeta, int max_depth, int force_all_near, double gamma, double eta_smooth,
+                           int64_t rho)
+{
+    if (!X || !Y || nx <= 0 || ny <= 0 || D < 1 || D > ORACLE_MAX_D || !(theta > 0.0) || zeta < 1)
+        return NULL;
+    otree2 *t = (otree2 *)calloc(1, sizeof(otree2));
+    t->D = D;
+    t->theta = theta;
+    t->smooth_depth = -1;
+    t->gamma = eta_smooth > 0.0 ? gamma : 0.0;
+    /* cubes of a common edge, each anchored at its own minimum (R8) */
+    float ax[ORACLE_MAX_D], ay[ORACLE_MAX_D];
+    float Ex = point_bounds(X, nx, D, ax), Ey = point_bounds(Y, ny, D, ay);
+    float Ef = Ex > Ey ? Ex : Ey;
+    t->tx = partition_points(X, nx, D, ax, Ef);
+    t->ty = partition_points(Y, ny, D, ay, Ef);
+    t->E = (double)Ef;
+
+    /* depth 0: one box per set, one (near) interaction */
+    olists *root = &t->lev[0];
+    root->near_ptr = (int64_t *)calloc(2, sizeof(int64_t));
+    root->near_ptr[1] = 1;
+    root->near_col = (int64_t *)calloc(1, sizeof(int64_t));
+    root->far_ptr = (int64_t *)calloc(2, sizeof(int64_t));
+    root->far_col = (int64_t *)calloc(1, sizeof(int64_t));
+    root->small_ptr = (int64_t *)calloc(2, sizeof(int64_t));
+    root->small_col = (int64_t *)calloc(1, sizeof(int64_t));
+
+    int cap = t->tx->Lq;
+    if (max_depth > 0 && max_depth < cap) cap = max_depth;
+    if (cap > ORACLE_MAX_LEVELS) cap = ORACLE_MAX_LEVELS;
+    if (Ef == 0.0f) cap = 0;
+    int l = 0;
+    /* Algorithm 1: while interactions remain and the largest box of either tree is above zeta (R10) */
+    while (t->lev[l].near_ptr[t->tx->lev[l].nb] > 0 && max_box(&t->tx->lev[l]) > zeta &&
+           max_box(&t->ty->lev[l]) > zeta && l < cap) {
+        ++l;
+        divide(t->tx, l);
+        divide(t->ty, l);
+        int smooth = !force_all_near && oracle_is_smooth_depth(t->E, l, D, gamma, eta_smooth);
+        new_interactions2(t, l, force_all_near, smooth, rho);
+        if (smooth)
+            t->smooth_depth = l;
+    }
+    t->L = l;
+    t->tx->L = t->ty->L = l;
+    return t;
+}
+
+int oracle_tree2_depth(const otree2 *t) { return t->L; }
+int oracle_tree2_smooth_depth(const otree2 *t) { return t->smooth_depth; }
+double oracle_tree2_edge(const otree2 *t) { return t->E; }
+/* the partition of one set (side 0: X, 1: Y) for the single-set introspection calls
+ * (perm, point keys, boxes, alpha, beta); owned by the two-set tree */
+const otree *oracle_tree2_side(const otree2 *t, int side) { return side ? t->ty : t->tx; }
+int64_t oracle_tree2_list_size(const otree2 *t, int level, int kind)
+{
+    const olists *ls = &t->lev[level];
+    int64_t nb = t->tx->lev[level].nb;
+    return kind == 2 ? ls->small_ptr[nb] : kind ? ls->far_ptr[nb] : ls->near_ptr[nb];
+}
+void oracle_tree2_list(const otree2 *t, int level, int kind, int64_t *row_ptr, int64_t *cols)
+{
+    const olists *ls = &t->lev[level];
+    int64_t nb = t->tx->lev[level].nb;
+    const int64_t *ptr = kind == 2 ? ls->small_ptr : kind ? ls->far_ptr : ls->near_ptr;
+    const int64_t *col = kind == 2 ? ls->small_col : kind ? ls->far_col : ls->near_col;
+    memcpy(row_ptr, ptr, sizeof(int64_t) * (size_t)(nb + 1));
+    memcpy(cols, col, sizeof(int64_t) * (size_t)ptr[nb]);
+}
+
+/* v = F3M(X, Y, b) following Algorithm 1: per depth v1 = L_Y b of every source box (tau_y),
+ * v2 = sum over the far row of K v1 at the nodes of the target box (tau_x), v += L_X^T v2; then
+ * the direct sums over the small-field pairs of every depth and the near pairs of the last one.
+ * y has n_x entries in the ORIGINAL order of X, fp64. */
+int oracle_f3m2_apply(const otree2 *t, const float *X, const float *Y, double gamma, int p_all, int kernel_id,
+                      int kparam, const float *b, double *y, int adaptive)
+{
+    if (!t || !X || !Y || !b || !y || p_all < 2 || p_all > 32)
+        return 1;
+    if (t->gamma != 0.0 && t->gamma != gamma)
+        return 2;
+    const otree *tx = t->tx, *ty = t->ty;
+    int D = t->D;
+    int64_t nx = tx->n;
+    double *ys = (double *)calloc((size_t)nx, sizeof(double)); /* box order of X */
+
+    for (int l = 1; l <= t->L; ++l) {
+        const olists *ls = &t->lev[l];
+        const olevel *xv = &tx->lev[l], *yv = &ty->lev[l];
+        if (ls->far_ptr[xv->nb] == 0)
+            continue;
+        int p = adaptive ? oracle_adaptive_nodes(t->E, l, gamma, p_all) : p_all;
+        if (p == 0)
+            continue;
+        int64_t r = ipow(p, D);
+        double s[32];
+        oracle_cheb2_nodes(p, s);
+        double *W = (double *)malloc(sizeof(double) * (size_t)yv->nb * (size_t)r);
+        oracle_p2m_level(ty, Y, b, p, l, W);
+#pragma omp parallel
+        {
+            double *V = (double *)malloc(sizeof(double) * (size_t)r);
+            double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
+            double *xs = (double *)malloc(sizeof(double) * (size_t)r * D);
+            double cp[ORACLE_MAX_D], cq[ORACLE_MAX_D], xq[ORACLE_MAX_D];
+#pragma omp for schedule(dynamic, 4)
+            for (int64_t a = 0; a < xv->nb; ++a) {
+                if (ls->far_ptr[a + 1] == ls->far_ptr[a])
+                    continue;
+                box_centre(tx, l, xv->key[a], cp);
+                for (int64_t i = 0; i < r; ++i)
+                    node_coords(tx, l, cp, p, s, i, xs + i * D);
+                for (int64_t i = 0; i < r; ++i) V[i] = 0.0;
+                for (int64_t e = ls->far_ptr[a]; e < ls->far_ptr[a + 1]; ++e) {
+                    int64_t q = ls->far_col[e];
+                    const double *wq = W + q * r;
+                    box_centre(ty, l, yv->key[q], cq);
+                    for (int64_t j = 0; j < r; ++j) {
+                        node_coords(ty, l, cq, p, s, j, xq);
+                        for (int64_t i = 0; i < r; ++i)
+                            V[i] += kernel_eval(kernel_id, kparam, gamma, D, xs + i * D, xq) * wq[j];
+                    }
+                }
+                for (int64_t k = xv->start[a]; k < xv->start[a + 1]; ++k) {
+                    point_weights(tx, l, cp, p, s, X + tx->perm[k] * D, scratch);
+                    double acc = 0.0;
+                    for (int64_t i = 0; i < r; ++i) acc += scratch[i] * V[i];
+                    ys[k] += acc;
+                }
+            }
+            free(V); free(scratch); free(xs);
+        }
+        free(W);
+    }
+
+    for (int l = 1; l <= t->L + 1; ++l) {
+        const int last = l == t->L + 1;
+        const int lev = last ? t->L : l;
+        const olists *ls = &t->lev[lev];
+        const olevel *xv = &tx->lev[lev], *yv = &ty->lev[lev];
+        const int64_t *ptr = last ? ls->near_ptr : ls->small_ptr;
+        const int64_t *col = last ? ls->near_col : ls->small_col;
+        if (!ptr || ptr[xv->nb] == 0)
+            continue;
+#pragma omp parallel for schedule(dynamic, 4)
+        for (int64_t a = 0; a < xv->nb; ++a) {
+            double xi[ORACLE_MAX_D], yj[ORACLE_MAX_D];
+            for (int64_t k = xv->start[a]; k < xv->start[a + 1]; ++k) {
+                int64_t i = tx->perm[k];
+                for (int d = 0; d < D; ++d) xi[d] = (double)X[i * D + d];
+                double acc = 0.0;
+                for (int64_t e = ptr[a]; e < ptr[a + 1]; ++e) {
+                    int64_t q = col[e];
+                    for (int64_t kk = yv->start[q]; kk < yv->start[q + 1]; ++kk) {
+                        int64_t j = ty->perm[kk];
+                        for (int d = 0; d < D; ++d) yj[d] = (double)Y[j * D + d];
+                        acc += kernel_eval(kernel_id, kparam, gamma, D, xi, yj) * (double)b[j];
+                    }
+                }
+                ys[k] += acc;
+            }
+        }
+    }
+    for (int64_t k = 0; k < nx; ++k)
+        y[tx->perm[k]] = ys[k];
     free(ys);
     return 0;
 }
