@@ -5,7 +5,8 @@
  * k(x,y) = exp(-|x-y|^2 / (2 gamma^2)) (arXiv 2202.01085, Sec. 5, first
  * paragraph) on n points in D <= 7 dimensions, either exactly (direct_kmvm)
  * or with the hierarchical F3M approximation (f3m_plan + f3m_kmvm) of
- * Sec. 3 and Appendix E, Algorithm 1.
+ * Sec. 3 and Appendix E, Algorithm 1.  The *_xy entry points do the same for
+ * two point sets, v = K(X,Y) b, the general form of Sec. 3.
  *
  * Conventions shared by every entry point
  *   - X, b, y are DEVICE pointers (fp32).  X is n x D row-major, the paper's
@@ -146,6 +147,33 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
 f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream);
 
 /*
+ * f3m_plan_xy - the plan for v = K(X, Y) b with two point sets: X (nx targets, rows of v) and
+ * Y (ny sources, one weight b_j per row), the general form the method is stated in (Sec. 3;
+ * Algorithm 1 keeps one treecode per set).
+ *   - Both sets get a cube of the same edge E = the largest extent of either set (enclosing
+ *     formula of Sec. 3), each anchored at its own per-dimension minimum (the alpha of the
+ *     box-index formula of Sec. 4.2), and each is divided on its own grid; the grids have equal
+ *     box edges at every depth and are shifted against each other by alpha^Y - alpha^X.
+ *   - A pair (box of X, box of Y) is far iff the distance of the box centres is >= eta * (box
+ *     edge): sum_d ((c'_d - c_d) + u_d)^2 >= eta^2 with c, c' the integer cells of the target and
+ *     the source box and u_d = ((alpha^Y_d - alpha^X_d) / E) * 2^depth, evaluated in fp64 with every
+ *     operation rounded on its own, d ascending.
+ *   - Algorithm 1 divides while interactions remain and the largest box of X AND the largest box
+ *     of Y hold more than leaf_max points.
+ *   - small field: |box of X| + |box of Y| <= small_field; smooth field and adaptive rule as for
+ *     one set (they depend on the common box edge only).
+ * Arguments as f3m_plan_ex; Y is device, ny x D row-major fp32, 0 <= ny < 2^31.  f3m_kmvm on such a
+ * plan reads b[ny] and writes y[nx]; with ny == 0 it writes zeros.  The interaction lists of
+ * f3m_plan_get_list have one row per box of X and hold ranks of boxes of Y; f3m_plan_get_perm,
+ * _get_point_keys, _get_boxes and f3m_info describe the partition of X, the *_source_* calls
+ * below that of Y.  (The near-field and M2L kernels specialised for one shared grid in 3-D are
+ * not used by such a plan.)
+ */
+f3m_status f3m_plan_xy(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float lengthscale,
+                       int interp_nodes, float eta, const f3m_options *opt, void *stream,
+                       f3m_plan_t **plan_out);
+
+/*
  * direct_kmvm - the exact product y_i = sum_j k(x_i,x_j) b_j (Sec. 2, KeOps
  * paragraph), O(n^2) time, O(n) memory, fp32 arithmetic.  Asynchronous on `stream`.
  */
@@ -161,6 +189,17 @@ f3m_status direct_kmvm(const float *X, int64_t n, int D, float lengthscale,
 f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthscale,
                                 const float *b, const int64_t *rows, int64_t m,
                                 double *y64, void *stream);
+
+/*
+ * direct_kmvm_xy / direct_kmvm_xy_rows_f64 - the same exact sums for two point sets,
+ * y_i = sum_j k(x_i, y_j) b_j (Sec. 2): X device nx x D, Y device ny x D, b device fp32[ny],
+ * y device fp32[nx]; rows device int64[m], each in [0,nx); y64 device double[m].
+ */
+f3m_status direct_kmvm_xy(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float lengthscale,
+                          const float *b, float *y, void *stream);
+f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, int64_t ny, int D,
+                                   float lengthscale, const float *b, const int64_t *rows, int64_t m,
+                                   double *y64, void *stream);
 
 /* Frees the plan and its device memory (NULL is allowed). */
 void f3m_destroy(f3m_plan_t *plan);
@@ -194,6 +233,21 @@ f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_
  * when the rule is off). */
 f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind,
                              uint64_t *row_ptr_host, uint32_t *cols_host);
+
+/* The source side of a plan (the partition of Y for f3m_plan_xy; for a one-set plan the same
+ * partition as the targets'): counts, anchor, and the analogues of f3m_plan_get_perm (ny entries)
+ * and f3m_plan_get_boxes. */
+typedef struct {
+    int64_t n;                                 /* sources */
+    int32_t two_sets;                          /* 1 for a plan made by f3m_plan_xy */
+    float alpha[F3M_MAX_DIM];                  /* per-dimension minimum of the sources (their cube anchor) */
+    int64_t nboxes[F3M_MAX_LEVELS + 1];        /* occupied source boxes per depth 0..L */
+    int64_t max_box[F3M_MAX_LEVELS + 1];       /* largest source box per depth */
+} f3m_source_info;
+f3m_status f3m_plan_source_info(const f3m_plan_t *plan, f3m_source_info *out);
+f3m_status f3m_plan_get_source_perm(const f3m_plan_t *plan, uint32_t *perm_host);
+f3m_status f3m_plan_get_source_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_host,
+                                     uint32_t *starts_host);
 
 /* Stage times of the last plan build and the last f3m_kmvm (synchronises). */
 f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out);

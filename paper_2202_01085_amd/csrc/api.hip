@@ -41,6 +41,9 @@ f3m_status check_problem(const float *X, int64_t n, int D, float lengthscale) {
     return F3M_OK;
 }
 
+// false for a plan with no targets or no sources: it holds no tables
+bool built(const f3m_plan_t *plan) { return plan->n > 0 && plan->ns() > 0; }
+
 template <class T>
 void copy_to_host(T *dst, const T *src, size_t count) {
     if (count == 0) return;
@@ -49,16 +52,21 @@ void copy_to_host(T *dst, const T *src, size_t count) {
 
 }  // namespace
 
-extern "C" {
+extern "C" const char *f3m_last_error(void) { return g_last_error.c_str(); }
 
-const char *f3m_last_error(void) { return g_last_error.c_str(); }
-
-f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int interp_nodes, float eta,
-                       const f3m_options *opt, void *stream, f3m_plan_t **plan_out) {
+// plan for one point set (Y == nullptr) or for targets X and sources Y
+static f3m_status make_plan(const float *X, int64_t n, const float *Y, int64_t ny, bool two_sets, int D,
+                            float lengthscale, int interp_nodes, float eta, const f3m_options *opt, void *stream,
+                            f3m_plan_t **plan_out) {
     if (!plan_out) return set_error(F3M_ERR_INVALID_ARG, "plan_out is null");
     *plan_out = nullptr;
     f3m_status st = check_problem(X, n, D, lengthscale);
     if (st != F3M_OK) return st;
+    if (two_sets) {
+        if (ny < 0) return set_error(F3M_ERR_INVALID_ARG, "ny must be >= 0");
+        if (ny > 0 && !Y) return set_error(F3M_ERR_INVALID_ARG, "Y is null");
+        if (ny >= ((int64_t)1 << 31)) return set_error(F3M_ERR_UNSUPPORTED, "ny must be below 2^31");
+    }
     if (interp_nodes < 2) return set_error(F3M_ERR_INVALID_ARG, "interp_nodes must be >= 2");
     if (!finite_pos(eta)) return set_error(F3M_ERR_INVALID_ARG, "eta (far-field distance ratio) must be finite and > 0");
     if (opt && (opt->leaf_max < 0 || opt->max_depth < 0))
@@ -90,7 +98,12 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
         P->adaptive_far = opt ? (opt->adaptive_far != 0) : 0;
         P->rho = opt ? opt->small_field : 0;
         F3M_HIP(hipGetDevice(&P->device));
-        if (n > 0) f3m::build_plan(*P, X, (hipStream_t)stream);
+        if (two_sets) {
+            P->src.reset(new f3m_source());
+            P->src->n = ny;
+        }
+        // with no targets there is nothing to compute, with no sources the product is zero
+        if (n > 0 && (!two_sets || ny > 0)) f3m::build_plan(*P, X, two_sets ? Y : nullptr, (hipStream_t)stream);
     });
     if (st != F3M_OK) {
         delete P;
@@ -101,6 +114,18 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
     return F3M_OK;
 }
 
+extern "C" {
+
+f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int interp_nodes, float eta,
+                       const f3m_options *opt, void *stream, f3m_plan_t **plan_out) {
+    return make_plan(X, n, nullptr, 0, false, D, lengthscale, interp_nodes, eta, opt, stream, plan_out);
+}
+
+f3m_status f3m_plan_xy(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float lengthscale,
+                       int interp_nodes, float eta, const f3m_options *opt, void *stream, f3m_plan_t **plan_out) {
+    return make_plan(X, nx, Y, ny, true, D, lengthscale, interp_nodes, eta, opt, stream, plan_out);
+}
+
 f3m_status f3m_plan(const float *X, int64_t n, int D, float lengthscale, int interp_nodes, float eta, void *stream,
                     f3m_plan_t **plan_out) {
     return f3m_plan_ex(X, n, D, lengthscale, interp_nodes, eta, nullptr, stream, plan_out);
@@ -109,7 +134,9 @@ f3m_status f3m_plan(const float *X, int64_t n, int D, float lengthscale, int int
 f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream) {
     if (!plan) return set_error(F3M_ERR_INVALID_ARG, "plan is null");
     if (plan->n == 0) return F3M_OK;
-    if (!b || !y) return set_error(F3M_ERR_INVALID_ARG, "b or y is null");
+    if (!y) return set_error(F3M_ERR_INVALID_ARG, "y is null");
+    if (plan->ns() == 0) return guarded([&] { f3m::run_zero(y, plan->n, (hipStream_t)stream); });   // no sources
+    if (!b) return set_error(F3M_ERR_INVALID_ARG, "b is null");
     if (b == y) return set_error(F3M_ERR_INVALID_ARG, "b and y must not overlap");
     return guarded([&] { f3m::run_kmvm(*plan, b, y, (hipStream_t)stream); });
 }
@@ -120,7 +147,21 @@ f3m_status direct_kmvm(const float *X, int64_t n, int D, float lengthscale, cons
     if (n == 0) return F3M_OK;
     if (!b || !y) return set_error(F3M_ERR_INVALID_ARG, "b or y is null");
     if (b == y) return set_error(F3M_ERR_INVALID_ARG, "b and y must not overlap");
-    return guarded([&] { f3m::run_direct(X, n, D, lengthscale, b, y, (hipStream_t)stream); });
+    return guarded([&] { f3m::run_direct(X, n, X, n, D, lengthscale, b, y, (hipStream_t)stream); });
+}
+
+f3m_status direct_kmvm_xy(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float lengthscale,
+                          const float *b, float *y, void *stream) {
+    f3m_status st = check_problem(X, nx, D, lengthscale);
+    if (st != F3M_OK) return st;
+    st = check_problem(Y, ny, D, lengthscale);
+    if (st != F3M_OK) return st;
+    if (nx == 0) return F3M_OK;
+    if (!y) return set_error(F3M_ERR_INVALID_ARG, "y is null");
+    if (ny == 0) return guarded([&] { f3m::run_zero(y, nx, (hipStream_t)stream); });
+    if (!b) return set_error(F3M_ERR_INVALID_ARG, "b is null");
+    if (b == y) return set_error(F3M_ERR_INVALID_ARG, "b and y must not overlap");
+    return guarded([&] { f3m::run_direct(X, nx, Y, ny, D, lengthscale, b, y, (hipStream_t)stream); });
 }
 
 f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthscale, const float *b,
@@ -131,7 +172,22 @@ f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthsc
     if (m == 0) return F3M_OK;
     if (n == 0) return set_error(F3M_ERR_INVALID_ARG, "rows requested of an empty problem");
     if (!b || !rows || !y64) return set_error(F3M_ERR_INVALID_ARG, "b, rows or y64 is null");
-    return guarded([&] { f3m::run_direct_rows_f64(X, n, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
+    return guarded([&] { f3m::run_direct_rows_f64(X, X, n, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
+}
+
+f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float lengthscale,
+                                   const float *b, const int64_t *rows, int64_t m, double *y64, void *stream) {
+    f3m_status st = check_problem(X, nx, D, lengthscale);
+    if (st != F3M_OK) return st;
+    st = check_problem(Y, ny, D, lengthscale);
+    if (st != F3M_OK) return st;
+    if (m < 0) return set_error(F3M_ERR_INVALID_ARG, "m must be >= 0");
+    if (m == 0) return F3M_OK;
+    if (nx == 0) return set_error(F3M_ERR_INVALID_ARG, "rows requested of an empty set of targets");
+    if (!rows || !y64) return set_error(F3M_ERR_INVALID_ARG, "rows or y64 is null");
+    if (ny == 0) return guarded([&] { F3M_HIP(hipMemsetAsync(y64, 0, sizeof(double) * (size_t)m, (hipStream_t)stream)); });
+    if (!b) return set_error(F3M_ERR_INVALID_ARG, "b is null");
+    return guarded([&] { f3m::run_direct_rows_f64(X, Y, ny, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
 }
 
 void f3m_destroy(f3m_plan_t *plan) {
@@ -142,7 +198,7 @@ void f3m_destroy(f3m_plan_t *plan) {
 
 f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
     if (!plan || !out) return set_error(F3M_ERR_INVALID_ARG, "null argument");
-    if (plan->n > 0 && !plan->have_far_point_pairs) {
+    if (plan->n > 0 && plan->ns() > 0 && !plan->have_far_point_pairs) {
         // cached on first use; the plan is logically unchanged
         f3m_status st = guarded([&] { f3m::compute_far_point_pairs(*const_cast<f3m_plan_t *>(plan)); });
         if (st != F3M_OK) return st;
@@ -158,16 +214,16 @@ f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
     out->edge = plan->E;
     out->scale = plan->scale;
     for (int d = 0; d < F3M_MAX_DIM; ++d) out->alpha[d] = plan->alpha[d];
-    for (int l = 0; l <= plan->L && plan->n > 0; ++l) {
+    for (int l = 0; l <= plan->L && built(plan); ++l) {
         out->nboxes[l] = plan->lev[l].nb;
         out->max_box[l] = plan->lev[l].max_box;
         out->near_pairs[l] = plan->lev[l].near_sz;
         out->far_pairs[l] = plan->lev[l].far_sz;
     }
-    for (int l = 0; l <= plan->L && plan->n > 0; ++l) out->far_point_pairs[l] = plan->lev[l].far_point_pairs;
+    for (int l = 0; l <= plan->L && built(plan); ++l) out->far_point_pairs[l] = plan->lev[l].far_point_pairs;
     out->near_point_pairs = plan->near_point_pairs;
     out->smooth_depth = plan->smooth_depth;
-    for (int l = 0; l <= plan->L && plan->n > 0; ++l) {
+    for (int l = 0; l <= plan->L && built(plan); ++l) {
         out->small_pairs[l] = plan->lev[l].small_sz;
         out->small_point_pairs[l] = plan->lev[l].small_point_pairs;
     }
@@ -178,17 +234,17 @@ f3m_status f3m_plan_info(const f3m_plan_t *plan, f3m_info *out) {
 
 f3m_status f3m_plan_get_perm(const f3m_plan_t *plan, uint32_t *perm_host) {
     if (!plan || !perm_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
-    return guarded([&] { copy_to_host(perm_host, plan->perm.p, (size_t)plan->n); });
+    return guarded([&] { copy_to_host(perm_host, plan->perm.p, built(plan) ? (size_t)plan->n : 0); });
 }
 
 f3m_status f3m_plan_get_point_keys(const f3m_plan_t *plan, uint32_t *keys_host) {
     if (!plan || !keys_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
-    return guarded([&] { copy_to_host(keys_host, plan->keys.p, (size_t)plan->n); });
+    return guarded([&] { copy_to_host(keys_host, plan->keys.p, built(plan) ? (size_t)plan->n : 0); });
 }
 
 f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_host, uint32_t *starts_host) {
     if (!plan || !keys_host || !starts_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
-    if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    if (!built(plan) || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
     return guarded([&] {
         const f3m_level &lv = plan->lev[level];
         copy_to_host(keys_host, lv.key.p, (size_t)lv.nb);
@@ -196,9 +252,37 @@ f3m_status f3m_plan_get_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_
     });
 }
 
+f3m_status f3m_plan_source_info(const f3m_plan_t *plan, f3m_source_info *out) {
+    if (!plan || !out) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    std::memset(out, 0, sizeof(*out));
+    out->n = plan->ns();
+    out->two_sets = plan->src ? 1 : 0;
+    for (int d = 0; d < F3M_MAX_DIM; ++d) out->alpha[d] = plan->salpha()[d];
+    for (int l = 0; l <= plan->L && built(plan); ++l) {
+        out->nboxes[l] = plan->slev(l).nb;
+        out->max_box[l] = plan->slev(l).max_box;
+    }
+    return F3M_OK;
+}
+
+f3m_status f3m_plan_get_source_perm(const f3m_plan_t *plan, uint32_t *perm_host) {
+    if (!plan || !perm_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    return guarded([&] { copy_to_host(perm_host, plan->sperm(), built(plan) ? (size_t)plan->ns() : 0); });
+}
+
+f3m_status f3m_plan_get_source_boxes(const f3m_plan_t *plan, int level, uint32_t *keys_host, uint32_t *starts_host) {
+    if (!plan || !keys_host || !starts_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
+    if (!built(plan) || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    return guarded([&] {
+        const f3m_level &lv = plan->slev(level);
+        copy_to_host(keys_host, lv.key.p, (size_t)lv.nb);
+        copy_to_host(starts_host, lv.start.p, (size_t)lv.nb + 1);
+    });
+}
+
 f3m_status f3m_plan_get_list(const f3m_plan_t *plan, int level, int kind, uint64_t *row_ptr_host, uint32_t *cols_host) {
     if (!plan || !row_ptr_host || !cols_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
-    if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    if (!built(plan) || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
     if (kind < 0 || kind > 2) return set_error(F3M_ERR_INVALID_ARG, "kind must be 0 (near), 1 (far) or 2 (small field)");
     return guarded([&] {
         const f3m_level &lv = plan->lev[level];
@@ -252,7 +336,7 @@ f3m_status f3m_stage_times(f3m_plan_t *plan, f3m_times *out) {
 
 f3m_status f3m_level_times(f3m_plan_t *plan, int level, float *ms_host) {
     if (!plan || !ms_host) return set_error(F3M_ERR_INVALID_ARG, "null argument");
-    if (plan->n == 0 || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
+    if (!built(plan) || level < 0 || level > plan->L) return set_error(F3M_ERR_INVALID_ARG, "level out of range");
     return guarded([&] {
         ms_host[0] = ms_host[1] = ms_host[2] = 0.f;
         if (!plan->have_kmvm_times || plan->lev[level].far_sz == 0 || plan->far_events.size() < (size_t)(level + 1) * 6)

@@ -46,9 +46,10 @@ static NodeArg make_nodes(int p) {
     return a;
 }
 
-static CentreArg make_centre(const f3m_plan_s &P, int level) {
+// box centres of a depth: of the target grid, or of the source grid (its own anchor in a two-set plan)
+static CentreArg make_centre(const f3m_plan_s &P, int level, bool source = false) {
     CentreArg c{};
-    for (int d = 0; d < P.D; ++d) c.alpha[d] = (double)P.alpha[d];
+    for (int d = 0; d < P.D; ++d) c.alpha[d] = (double)(source ? P.salpha()[d] : P.alpha[d]);
     c.edge = (double)P.E / std::ldexp(1.0, level);
     c.inv_half = 2.0 / c.edge;
     return c;
@@ -79,9 +80,13 @@ __global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ p, int64_
 // lane per target; the sources of the near boxes are wave-uniform, so they arrive through
 // the scalar data path and every vector instruction works on 64 distinct pairs.
 //   k(x,y) = exp2( nc2 * |x-y|^2 ),  nc2 = -log2(e) / (2 gamma^2)
+// All near-field kernels take the targets as (Xt, startT) and the sources as (Xs, bs, start): the
+// box-ordered points and point intervals of the target boxes and of the source boxes.  For one
+// point set both are the same arrays; for K(X, Y) the columns of a list are ranks of boxes of Y.
 // ------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+__global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xt, const uint32_t *__restrict__ startT,
+                                                 const float *__restrict__ Xs, const float *__restrict__ bs,
                                                  const uint32_t *__restrict__ start,
                                                  const uint64_t *__restrict__ near_ptr,
                                                  const uint32_t *__restrict__ near_col,
@@ -91,13 +96,13 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xs, c
     const int64_t t = block_index();
     if (t >= ntiles) return;
     const uint32_t a = tile_box[t];
-    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
-    const uint32_t kend = start[a + 1];
+    const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    const uint32_t kend = startT[a + 1];
     const uint32_t k = k0 + threadIdx.x;
     const bool active = k < kend;
     float xi[D];
 #pragma unroll
-    for (int d = 0; d < D; ++d) xi[d] = active ? Xs[(int64_t)k * D + d] : 0.f;
+    for (int d = 0; d < D; ++d) xi[d] = active ? Xt[(int64_t)k * D + d] : 0.f;
     float acc = 0.f;
     const uint64_t e1 = near_ptr[a + 1];
     for (uint64_t e = near_ptr[a]; e < e1; ++e) {
@@ -195,7 +200,9 @@ __device__ inline h8v split_source4(const float (&w)[4], int h) {
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+__global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__ Xt,
+                                                       const uint32_t *__restrict__ startT,
+                                                       const float *__restrict__ Xs, const float *__restrict__ bs,
                                                        const uint32_t *__restrict__ start,
                                                        const int32_t *__restrict__ cell,
                                                        const uint64_t *__restrict__ near_ptr,
@@ -210,8 +217,8 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
     const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
     if (t >= ntiles) return;
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
-    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
-    const uint32_t kend = start[a + 1];
+    const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    const uint32_t kend = startT[a + 1];
     const bool two = __builtin_amdgcn_readfirstlane((int)(kend - k0)) > 32;
     const int nn = lane & 31, kk = lane >> 5;
     float ctr[D];
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
         float s = 0.f;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            u[d] = (Xs[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
+            u[d] = (Xt[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
             s = fmaf(u[d], u[d], s);
         }
         u[D] = 1.f;
@@ -354,7 +361,9 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
 // target side half 0 = (hi, lo), half 1 = (hi, 0): hi*hi + hi*lo + lo*hi, the fourth product
 // meets a zero.  The right-hand sides of a step pass through 64 floats of LDS per wavefront
 // (written by the lane that owns the source, read as the 16 values a lane needs per block).
-__global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+__global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict__ Xt,
+                                                        const uint32_t *__restrict__ startT,
+                                                        const float *__restrict__ Xs, const float *__restrict__ bs,
                                                         const uint32_t *__restrict__ start,
                                                         const int32_t *__restrict__ cell,
                                                         const uint64_t *__restrict__ near_ptr,
@@ -369,8 +378,8 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     const int64_t t = block_index() * 4 + wv;
     if (t >= ntiles) return;
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
-    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * 64u;
-    const uint32_t kend = start[a + 1];
+    const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    const uint32_t kend = startT[a + 1];
     const bool two = __builtin_amdgcn_readfirstlane((int)(kend - k0)) > 32;
     const int nn = lane & 31, kk = lane >> 5;
     float ctr[D];
@@ -388,7 +397,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         float s = 0.f;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            u[d] = (Xs[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
+            u[d] = (Xt[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
             s = fmaf(u[d], u[d], s);
         }
         u[D] = 1.f;
@@ -528,7 +537,9 @@ template <int D>
 constexpr int small_tt() { return D <= 4 ? 16 : 8; }
 
 template <int D>
-__global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+__global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict__ Xt,
+                                                        const uint32_t *__restrict__ startT,
+                                                        const float *__restrict__ Xs, const float *__restrict__ bs,
                                                         const uint32_t *__restrict__ start,
                                                         const uint64_t *__restrict__ row_ptr,
                                                         const uint32_t *__restrict__ cols,
@@ -540,15 +551,15 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
     const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
     if (t >= ntiles) return;
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
-    const uint32_t k0 = start[a] + (uint32_t)(t - tile_first[a]) * (uint32_t)TT;
-    const uint32_t kend = start[a + 1];
+    const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * (uint32_t)TT;
+    const uint32_t kend = startT[a + 1];
     const int nt = (int)(kend - k0 < (uint32_t)TT ? kend - k0 : (uint32_t)TT);   // wave-uniform
     float xt[TT][D];   // target coordinates, wave-uniform (rows beyond nt repeat an in-bounds point)
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         const uint32_t kt = k0 + (uint32_t)(tt < nt ? tt : 0);
 #pragma unroll
-        for (int d = 0; d < D; ++d) xt[tt][d] = Xs[(int64_t)kt * D + d];
+        for (int d = 0; d < D; ++d) xt[tt][d] = Xt[(int64_t)kt * D + d];
     }
     float acc[TT];
 #pragma unroll
@@ -615,12 +626,14 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
     if (lane < nt) ys[k0 + lane] += res;
 }
 
-// exact product, all pairs (Sec. 2, KeOps paragraph): lane = target, sources wave-uniform
+// exact product, all pairs (Sec. 2, KeOps paragraph): lane = target (rows of X, nx of them), the
+// sources (rows of Y, ny of them, weights b) wave-uniform; X == Y for one point set
 template <int D>
-__global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X, const float *__restrict__ b,
+__global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X, int64_t nx,
+                                                    const float *__restrict__ Y, const float *__restrict__ b,
                                                     int64_t n, float nc2, float *__restrict__ y) {
     const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    const bool active = i < n;
+    const bool active = i < nx;
     float xi[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) xi[d] = active ? X[i * D + d] : 0.f;
@@ -630,7 +643,7 @@ __global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X,
         float r2 = 0.f;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            float diff = X[j * D + d] - xi[d];
+            float diff = Y[j * D + d] - xi[d];
             r2 = fmaf(diff, diff, r2);
         }
         acc = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), b[j], acc);
@@ -640,8 +653,9 @@ __global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X,
 
 // exact rows in fp64: lane = row, blockIdx.y = slice of the sources; partial sums per slice
 template <int D>
-__global__ __launch_bounds__(64) void rows_f64_kernel(const float *__restrict__ X, const float *__restrict__ b,
-                                                      int64_t n, const int64_t *__restrict__ rows, int64_t m,
+__global__ __launch_bounds__(64) void rows_f64_kernel(const float *__restrict__ X, const float *__restrict__ Y,
+                                                      const float *__restrict__ b, int64_t n,
+                                                      const int64_t *__restrict__ rows, int64_t m,
                                                       double nc, double *__restrict__ part) {
     const int64_t a = (int64_t)blockIdx.x * 64 + threadIdx.x;
     const bool active = a < m;
@@ -656,7 +670,7 @@ __global__ __launch_bounds__(64) void rows_f64_kernel(const float *__restrict__ 
         double r2 = 0.0;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            double diff = (double)X[j * D + d] - xi[d];
+            double diff = (double)Y[j * D + d] - xi[d];
             r2 = fma(diff, diff, r2);
         }
         acc = fma(exp(r2 * nc), (double)b[j], acc);
@@ -1136,7 +1150,16 @@ __global__ __launch_bounds__(64) void l2l34_kernel(const uint32_t *__restrict__ 
 // in place in LDS (a fibre is read and written by the same lane); the last pass adds into
 // register accumulators that are stored once per target.  A fibre = the p entries along the
 // pass's dimension; lane = fibre.
+// For two point sets the grids are shifted by u_d box edges in dimension d, so the factor of
+// dimension d depends on o + u_d: the table is kept per dimension, G[d][o - omin_d][i][j] with
+// G = exp(-(l/2)^2 (2 (o + u_d) + s_j - s_i)^2 / (2 gamma^2)), `no` offsets per dimension
+// (cellT: cells of the target boxes, cellS: of the source boxes; u = 0 and equal tables for one set).
 // ------------------------------------------------------------------------------------
+struct KronShape {
+    int omin[F3M_MAX_DIM];   // smallest tabulated offset (source cell - target cell) per dimension
+    int no;                  // tabulated offsets per dimension
+};
+
 // largest number of fibres (r/p) that p nodes per dimension allow with D <= 7 and r <= 4096
 constexpr int kron_max_fibres(int p) {
     int r = 1;
@@ -1145,10 +1168,11 @@ constexpr int kron_max_fibres(int p) {
 }
 
 template <int PN>
-__global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict__ cell,
+__global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict__ cellT,
+                                                      const int32_t *__restrict__ cellS,
                                                       const uint64_t *__restrict__ far_ptr,
                                                       const uint32_t *__restrict__ far_col, int64_t nb, int D, int r,
-                                                      const float *__restrict__ G, int omax,
+                                                      const float *__restrict__ G, KronShape S,
                                                       const float *__restrict__ W, float *__restrict__ V) {
     constexpr int NF = (kron_max_fibres(PN) + 63) / 64;   // fibres per lane, at most
     extern __shared__ float lds[];                        // [r]
@@ -1164,7 +1188,14 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
 #pragma unroll
         for (int i = 0; i < PN; ++i) acc[k][i] = 0.f;
     int ca[F3M_MAX_DIM];
-    for (int d = 0; d < D; ++d) ca[d] = cell[a * D + d];
+    for (int d = 0; d < D; ++d) ca[d] = cellT[a * D + d];
+    // factor matrix of dimension d for a source cell coordinate (the index is clamped to the table:
+    // every far pair lies inside it by construction)
+    auto factor = [&](int d, int cs) {
+        int k = cs - ca[d] - S.omin[d];
+        k = k < 0 ? 0 : (k >= S.no ? S.no - 1 : k);
+        return G + ((int64_t)d * S.no + k) * (PN * PN);
+    };
 
     // out[i] = sum_j g[i][j] in[j] with g wave-uniform
     auto apply = [&](const float *__restrict__ g, const float (&in)[PN], float (&out)[PN]) {
@@ -1182,8 +1213,7 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
         float *cur = lds;
         __syncthreads();   // the last pass of the previous pair has read the buffer
         {
-            const int o = cell[(int64_t)q * D] - ca[0];
-            const float *g = G + (int64_t)(o + omax) * (PN * PN);
+            const float *g = factor(0, cellS[(int64_t)q * D]);
 #pragma unroll
             for (int k = 0; k < NF; ++k) {
                 if (64 * k >= nfib) break;
@@ -1206,8 +1236,7 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
         int stride = 1;   // of dimension d in the LDS layout (dimensions 1..D-1 fastest first, then 0)
         for (int d = 1; d < D; ++d) {
             __syncthreads();
-            const int o = cell[(int64_t)q * D + d] - ca[d];
-            const float *g = G + (int64_t)(o + omax) * (PN * PN);
+            const float *g = factor(d, cellS[(int64_t)q * D + d]);
             const float inv = 1.f / (float)stride;
             const bool last = d == D - 1;
 #pragma unroll
@@ -1261,11 +1290,29 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
     }
 }
 
+// Offsets (source cell - target cell) a far pair of a depth can have in dimension d.  The parents
+// of a far pair are near, |O + U| < theta in every dimension (U the shift at the parents' depth),
+// and a child centre lies half a child edge from its parent's: |o + u| < 2 theta + 1.  Depth 1
+// has the root pair as parents, which is near whatever its distance: o in {-1, 0, 1}.  One more
+// offset on either side is tabulated, and everything is cut to the cells a depth has.
+static KronShape kron_shape(const f3m_plan_s &P, int level) {
+    KronShape S{};
+    double u[F3M_MAX_DIM];
+    P.grid_shift(level, u);
+    const double reach = 2.0 * (double)P.theta + 2.0, cmax = (double)((1ll << level) - 1);
+    S.no = 1;
+    for (int d = 0; d < P.D; ++d) {
+        double lo = level == 1 ? -1.0 : std::max(-cmax, std::floor(-reach - u[d]));
+        double hi = level == 1 ? 1.0 : std::min(cmax, std::ceil(reach - u[d]));
+        if (hi < lo) hi = lo = std::min(std::max(lo, -cmax), cmax);   // no far pair can exist here
+        S.omin[d] = (int)lo;
+        S.no = std::max(S.no, (int)(hi - lo) + 1);
+    }
+    return S;
+}
+
 // per depth with far pairs: the 1-D factor matrices of the node-to-node kernel matrix, built in fp64
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
-    int m = 0;   // largest near offset in one dimension: m^2 < T
-    while ((m + 1) * (m + 1) < P.T) ++m;
-    const int omax = 2 * m + 1;   // children of near parents
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
         if (lv.far_sz == 0 || lv.p == 0) continue;
@@ -1274,15 +1321,26 @@ void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
         for (int k = 0; k < p; ++k) s[k] = p > 1 ? std::cos(M_PI * (double)k / (double)(p - 1)) : 0.0;
         const double half = 0.5 * (double)P.E / (double)(1ull << l);
         const double c = half * half / (2.0 * (double)P.gamma * (double)P.gamma);
-        std::vector<float> g((size_t)(2 * omax + 1) * p * p);
-        for (int o = -omax; o <= omax; ++o)
-            for (int i = 0; i < p; ++i)
-                for (int j = 0; j < p; ++j) {
-                    const double t = 2.0 * (double)o + s[j] - s[i];
-                    g[((size_t)(o + omax) * p + i) * p + j] = (float)std::exp(-c * t * t);
-                }
+        KronShape S = kron_shape(P, l);
+        if (lv.far_implicit) {
+            // the candidate-grid M2L (one point set, far ratio 2) reads one table G[o + 3][i][j], o = -3..3
+            S.no = 7;
+            S.omin[0] = -3;
+            lv.gtab_omax = 3;
+        }
+        const int ndim = lv.far_implicit ? 1 : P.D;
+        double u[F3M_MAX_DIM];
+        P.grid_shift(l, u);
+        std::vector<float> g((size_t)ndim * S.no * p * p);
+        for (int d = 0; d < ndim; ++d)
+            for (int k = 0; k < S.no; ++k)
+                for (int i = 0; i < p; ++i)
+                    for (int j = 0; j < p; ++j) {
+                        // source node minus target node in half box edges: 2 (o + u) + s_j - s_i
+                        const double t = 2.0 * ((double)(S.omin[d] + k) + u[d]) + s[j] - s[i];
+                        g[(((size_t)d * S.no + k) * p + i) * p + j] = (float)std::exp(-c * t * t);
+                    }
         lv.gtab.alloc(g.size(), &P.bytes);
-        lv.gtab_omax = omax;
         F3M_HIP(hipMemcpyAsync(lv.gtab.p, g.data(), g.size() * sizeof(float), hipMemcpyHostToDevice, st));
         F3M_HIP(hipStreamSynchronize(st));
     }
@@ -1314,9 +1372,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     (void)nev;
     const unsigned gn = (unsigned)cdiv(n, 256);
     f3m_level &leaf = P.lev[P.L];
+    const float *Ys = P.Ys();   // sources in box order (the targets themselves for one point set)
 
     F3M_HIP(hipEventRecord(P.ev[8], st));
-    gather_kernel<<<dim3(gn), dim3(256), 0, st>>>(b, P.perm.p, n, P.bs.p);
+    gather_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.sperm(), P.ns(), P.bs.p);
     F3M_HIP(hipEventRecord(P.ev[9], st));
     // The near field goes to the plan's second stream (vector ALU work) and overlaps the
     // far field (matrix-core work) on the caller's stream; with no_overlap it runs in line.
@@ -1330,23 +1389,25 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     auto direct_pairs = [&](int l, const uint64_t *row_ptr, const uint32_t *cols, const uint32_t *tile_box,
                             const uint32_t *tile_first, int64_t ntiles, int accumulate) {
         f3m_level &lv = P.lev[l];
+        const uint32_t *sstart = P.slev(l).start.p;
         // c l^2 bounds the magnitude of the expanded exponent terms in box-local coordinates
         // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
         const CentreArg CL = make_centre(P, l);
         const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
         const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
-        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024;
+        // (the root pair of two point sets is near whatever its distance: no bound on the coordinates)
+        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 && !(P.src && l == 0);
         if (gram && D == 3)
             p2p_gram3_kernel<<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
                 (float)(1.0 / CL.edge), CL, P.yn.p, accumulate);
         else if (gram)
             p2p_mfma_kernel<D><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
                 (float)(1.0 / CL.edge), CL, P.yn.p, accumulate);
         else
-            p2p_kernel<D><<<grid_for(ntiles), dim3(64), 0, sn>>>(P.Xs.p, P.bs.p, lv.start.p, row_ptr, cols, tile_box,
-                                                                tile_first, ntiles, nc2, P.yn.p, accumulate);
+            p2p_kernel<D><<<grid_for(ntiles), dim3(64), 0, sn>>>(P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, row_ptr, cols,
+                                                                tile_box, tile_first, ntiles, nc2, P.yn.p, accumulate);
         F3M_HIP(hipGetLastError());
     };
     if (leaf.near_sz == 0) {
@@ -1360,8 +1421,8 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         f3m_level &lv = P.lev[l];
         if (lv.small_sz > 0) {
             p2p_small_kernel<D><<<grid_for(cdiv(lv.sm_ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, P.bs.p, lv.start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p, lv.sm_tile_first.p,
-                lv.sm_ntiles, nc2, P.yn.p);
+                P.Xs.p, lv.start.p, Ys, P.bs.p, P.slev(l).start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p,
+                lv.sm_tile_first.p, lv.sm_ntiles, nc2, P.yn.p);
             F3M_HIP(hipGetLastError());
         }
     }
@@ -1388,25 +1449,27 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         const int p = lv.p, r = lv.r;
         const NodeArg N = make_nodes(p);
         hipEvent_t *ev = level_events(l);
-        const CentreArg C = make_centre(P, l);
+        const CentreArg C = make_centre(P, l);          // target grid
+        const CentreArg CS = make_centre(P, l, true);   // source grid
+        f3m_level &sv = P.slev(l);                      // source boxes (lv itself for one point set)
         F3M_HIP(hipEventRecord(ev[0], st));
         {
             size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
             if (D == 3 && p == 4)
-                p2m34_kernel<<<grid_for(lv.nchunks), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, lv.start.p, lv.cell.p,
-                                                                      lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, C,
+                p2m34_kernel<<<grid_for(sv.nchunks), dim3(64), 0, st>>>(Ys, P.bs.p, sv.start.p, sv.cell.p,
+                                                                      sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
                                                                       P.W.p, P.Wpart.p);
             else if (r <= 64)
-                p2m_kernel<D, 64><<<grid_for(lv.nchunks), dim3(64), sh, st>>>(
-                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
+                p2m_kernel<D, 64><<<grid_for(sv.nchunks), dim3(64), sh, st>>>(
+                    Ys, P.bs.p, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
                     P.W.p, P.Wpart.p);
             else
-                p2m_kernel<D, 256><<<grid_for(lv.nchunks), dim3(256), sh, st>>>(
-                    P.Xs.p, P.bs.p, lv.start.p, lv.cell.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
+                p2m_kernel<D, 256><<<grid_for(sv.nchunks), dim3(256), sh, st>>>(
+                    Ys, P.bs.p, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
                     P.W.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
-            if (lv.nchunks > lv.nb)
-                reduce_partials(P, lv, r, P.W.p, st);
+            if (sv.nchunks > sv.nb)
+                reduce_partials(P, sv, r, P.W.p, st);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[1], st));
@@ -1414,8 +1477,8 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
         if (!(lv.far_implicit && run_m2l_stencil(P, l, P.W.p, P.V.p, st))) {
             const size_t sh = (size_t)r * sizeof(float);
             auto launch = [&](auto kern) {
-                kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
-                                                            lv.gtab.p, lv.gtab_omax, P.W.p, P.V.p);
+                kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
+                                                            lv.gtab.p, kron_shape(P, l), P.W.p, P.V.p);
             };
             switch (p) {
                 case 2: launch(m2l_kron_kernel<2>); break;
@@ -1515,6 +1578,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     P.have_kmvm_times = true;
 }
 
+void run_zero(float *y, int64_t n, hipStream_t st) {
+    zero_kernel<<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(y, n);
+    F3M_HIP(hipGetLastError());
+}
+
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
     switch (P.D) {
         case 1: run_kmvm_d<1>(P, b, y, st); break;
@@ -1529,49 +1597,51 @@ void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
 }
 
 template <int D>
-static void run_direct_d(const float *X, int64_t n, float gamma, const float *b, float *y, hipStream_t st) {
+static void run_direct_d(const float *X, int64_t nx, const float *Y, int64_t ny, float gamma, const float *b, float *y,
+                         hipStream_t st) {
     const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)gamma * (double)gamma));
-    direct_kernel<D><<<dim3((unsigned)cdiv(n, 64)), dim3(64), 0, st>>>(X, b, n, nc2, y);
+    direct_kernel<D><<<dim3((unsigned)cdiv(nx, 64)), dim3(64), 0, st>>>(X, nx, Y, b, ny, nc2, y);
     F3M_HIP(hipGetLastError());
 }
 
-void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st) {
+void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float gamma, const float *b, float *y,
+                hipStream_t st) {
     switch (D) {
-        case 1: run_direct_d<1>(X, n, gamma, b, y, st); break;
-        case 2: run_direct_d<2>(X, n, gamma, b, y, st); break;
-        case 3: run_direct_d<3>(X, n, gamma, b, y, st); break;
-        case 4: run_direct_d<4>(X, n, gamma, b, y, st); break;
-        case 5: run_direct_d<5>(X, n, gamma, b, y, st); break;
-        case 6: run_direct_d<6>(X, n, gamma, b, y, st); break;
-        case 7: run_direct_d<7>(X, n, gamma, b, y, st); break;
+        case 1: run_direct_d<1>(X, nx, Y, ny, gamma, b, y, st); break;
+        case 2: run_direct_d<2>(X, nx, Y, ny, gamma, b, y, st); break;
+        case 3: run_direct_d<3>(X, nx, Y, ny, gamma, b, y, st); break;
+        case 4: run_direct_d<4>(X, nx, Y, ny, gamma, b, y, st); break;
+        case 5: run_direct_d<5>(X, nx, Y, ny, gamma, b, y, st); break;
+        case 6: run_direct_d<6>(X, nx, Y, ny, gamma, b, y, st); break;
+        case 7: run_direct_d<7>(X, nx, Y, ny, gamma, b, y, st); break;
         default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
     }
 }
 
 template <int D>
-static void run_rows_d(const float *X, int64_t n, float gamma, const float *b, const int64_t *rows, int64_t m,
-                       double *y64, hipStream_t st) {
+static void run_rows_d(const float *X, const float *Y, int64_t n, float gamma, const float *b, const int64_t *rows,
+                       int64_t m, double *y64, hipStream_t st) {
     const double nc = -1.0 / (2.0 * (double)gamma * (double)gamma);
     const int slices = (int)std::max<int64_t>(1, std::min<int64_t>(256, n / 4096));
     DevBuf<double> part;
     part.alloc((size_t)slices * (size_t)m);
-    rows_f64_kernel<D><<<dim3((unsigned)cdiv(m, 64), (unsigned)slices), dim3(64), 0, st>>>(X, b, n, rows, m, nc, part.p);
+    rows_f64_kernel<D><<<dim3((unsigned)cdiv(m, 64), (unsigned)slices), dim3(64), 0, st>>>(X, Y, b, n, rows, m, nc, part.p);
     F3M_HIP(hipGetLastError());
     rows_f64_sum_kernel<<<dim3((unsigned)cdiv(m, 256)), dim3(256), 0, st>>>(part.p, m, slices, y64);
     F3M_HIP(hipGetLastError());
     F3M_HIP(hipStreamSynchronize(st));  // `part` is released on return
 }
 
-void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
-                         int64_t m, double *y64, hipStream_t st) {
+void run_direct_rows_f64(const float *X, const float *Y, int64_t ny, int D, float gamma, const float *b,
+                         const int64_t *rows, int64_t m, double *y64, hipStream_t st) {
     switch (D) {
-        case 1: run_rows_d<1>(X, n, gamma, b, rows, m, y64, st); break;
-        case 2: run_rows_d<2>(X, n, gamma, b, rows, m, y64, st); break;
-        case 3: run_rows_d<3>(X, n, gamma, b, rows, m, y64, st); break;
-        case 4: run_rows_d<4>(X, n, gamma, b, rows, m, y64, st); break;
-        case 5: run_rows_d<5>(X, n, gamma, b, rows, m, y64, st); break;
-        case 6: run_rows_d<6>(X, n, gamma, b, rows, m, y64, st); break;
-        case 7: run_rows_d<7>(X, n, gamma, b, rows, m, y64, st); break;
+        case 1: run_rows_d<1>(X, Y, ny, gamma, b, rows, m, y64, st); break;
+        case 2: run_rows_d<2>(X, Y, ny, gamma, b, rows, m, y64, st); break;
+        case 3: run_rows_d<3>(X, Y, ny, gamma, b, rows, m, y64, st); break;
+        case 4: run_rows_d<4>(X, Y, ny, gamma, b, rows, m, y64, st); break;
+        case 5: run_rows_d<5>(X, Y, ny, gamma, b, rows, m, y64, st); break;
+        case 6: run_rows_d<6>(X, Y, ny, gamma, b, rows, m, y64, st); break;
+        case 7: run_rows_d<7>(X, Y, ny, gamma, b, rows, m, y64, st); break;
         default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
     }
 }

@@ -15,7 +15,10 @@ static dim3 grid2(int64_t count) {
 }
 __device__ inline int64_t block_index2() { return (int64_t)blockIdx.y * gridDim.x + blockIdx.x; }
 
-bool m2l_stencil_applies(const f3m_plan_s &P) { return P.D == 3 && P.p == 4 && P.T == 4 && !P.force_all_near; }
+// (one point set only: the candidate grid assumes that targets and sources share a grid)
+bool m2l_stencil_applies(const f3m_plan_s &P) {
+    return P.D == 3 && P.p == 4 && P.T == 4 && !P.force_all_near && !P.src;
+}
 
 // ------------------------------------------------------------------------------------
 // M2L by sum factorisation over the candidate grid (D = 3, 4 nodes per dimension, far ratio 2).

@@ -1,5 +1,7 @@
 // The plan object: everything of Algorithm 1 that does not depend on b.
 #pragma once
+#include <memory>
+
 #include "common.h"
 
 struct f3m_level {
@@ -42,8 +44,20 @@ struct f3m_level {
     f3m::DevBuf<float> Wl, Vl;          // [nb*64]
 };
 
-struct f3m_plan_s {
+// The partition of the source set Y of a two-set plan, v = K(X, Y) b (Sec. 3 states the method for
+// two data matrices; Algorithm 1 keeps one treecode per set).  Both sets are divided by cubes of
+// the same edge, each anchored at its own per-dimension minimum, so the two grids have equal box
+// edges at every depth and are shifted against each other.  A one-set plan has no such object.
+struct f3m_source {
     int64_t n = 0;
+    float alpha[F3M_MAX_DIM] = {0};
+    f3m::DevBuf<uint32_t> keys, perm;   // [n]
+    f3m::DevBuf<float> Xs;              // [n*D] coordinates in box order, padded
+    f3m_level lev[F3M_MAX_LEVELS + 1];  // box tables and P2M work splits only (no lists)
+};
+
+struct f3m_plan_s {
+    int64_t n = 0;                              // targets (rows of X); also the sources of a one-set plan
     int D = 0, p = 0, r = 0;
     int Lq = 0, L = 0, T = 4;
     float gamma = 1.f, theta = 2.f;
@@ -71,7 +85,24 @@ struct f3m_plan_s {
     // near-field work split: a tile is a run of at most 64 targets of one leaf box
     int64_t ntiles = 0;
     f3m::DevBuf<uint32_t> tile_box, tile_first;   // [ntiles], [nb_L+1]
-    f3m_level lev[F3M_MAX_LEVELS + 1];
+    f3m_level lev[F3M_MAX_LEVELS + 1];          // boxes of X (targets); lists by target box
+    std::unique_ptr<f3m_source> src;            // two-set plan: the partition of Y (sources)
+    // the source side of either kind of plan
+    const f3m_level &slev(int l) const { return src ? src->lev[l] : lev[l]; }
+    f3m_level &slev(int l) { return src ? src->lev[l] : lev[l]; }
+    int64_t ns() const { return src ? src->n : n; }
+    const float *Ys() const { return src ? src->Xs.p : Xs.p; }
+    const uint32_t *sperm() const { return src ? src->perm.p : perm.p; }
+    const float *salpha() const { return src ? src->alpha : alpha; }
+    // grid shift of a depth in units of its box edge, u_d = ((alpha^Y_d - alpha^X_d) / E) 2^depth: the
+    // centre of source cell c' minus the centre of target cell c is ((c' - c) + u) box edges
+    void grid_shift(int level, double *u) const {
+        for (int d = 0; d < D; ++d) {
+            const double diff = (double)salpha()[d] - (double)alpha[d];
+            const double q = (src && E > 0.f) ? diff / (double)E : 0.0;
+            u[d] = q * (double)(1ull << level);
+        }
+    }
     int tree_lmin = 0, tree_lmax = 0;   // tree_lmin > 0: node weights/potentials are passed between depths
                                         // tree_lmin..tree_lmax (D = 3, 4 nodes/dim); other depths work
                                         // straight from the points
@@ -101,15 +132,18 @@ bool smooth_rule(double E, int depth, int D, double gamma, double eta_smooth);  
 int adaptive_nodes(double E, int depth, double gamma, int p);                   // Sec. 4.3 node rule (0: dropped)
 
 // plan.hip
-void build_plan(f3m_plan_s &P, const float *X, hipStream_t st);
+void build_plan(f3m_plan_s &P, const float *X, const float *Y, hipStream_t st);   // Y == nullptr: one set (P.src set otherwise)
 void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far_point_pairs, once (synchronises)
 bool permute_out_bucketed(f3m_plan_s &P, float *y, hipStream_t st);   // false: n too small, use the plain scatter
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);   // far rows of an implicit depth
 // kmvm.hip
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
-void run_direct(const float *X, int64_t n, int D, float gamma, const float *b, float *y, hipStream_t st);
-void run_direct_rows_f64(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
-                         int64_t m, double *y64, hipStream_t st);
+void run_zero(float *y, int64_t n, hipStream_t st);   // y = 0 with a fill kernel
+// exact sums of targets X (nx rows) against sources Y (ny rows, weights b); X == Y for one set
+void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float gamma, const float *b, float *y,
+                hipStream_t st);
+void run_direct_rows_f64(const float *X, const float *Y, int64_t ny, int D, float gamma, const float *b,
+                         const int64_t *rows, int64_t m, double *y64, hipStream_t st);
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of every far depth
 // m2l.hip

@@ -424,12 +424,21 @@ struct ListArg {
     int T;                 // a pair is far iff the squared integer cell offset is >= T
     int mode;              // 0: far rule, 1: all near, 2: all far (smooth depth, Sec. 4.3)
     uint32_t rho;          // small field (Sec. 4.2): |p| + |q| <= rho goes on the direct list; 0 = off
-    const uint32_t *start; // point intervals of this depth (box sizes for the small-field rule)
+    const uint32_t *start; // point intervals of the target boxes of this depth (sizes for the small-field rule)
+    // source side of the depth: the same tables as the targets' for one point set, those of Y for two
+    const int32_t *cell_src;
+    const uint32_t *start_src;
+    // two sets: the grids are shifted by u box edges, and a pair is far iff
+    // sum_d ((c'_d - c_d) + u_d)^2 >= theta2, every fp64 operation rounded on its own, d ascending
+    int shifted;
+    double u[F3M_MAX_DIM];
+    double theta2;
     uint32_t *cnt_near, *cnt_far, *cnt_small;         // pass 0: row lengths
     const uint64_t *near_ptr, *far_ptr, *small_ptr;   // pass 1: row offsets
     uint32_t *near_col, *far_col, *small_col;         // pass 1: columns (null: that list is not written)
 };
 
+// up_cstart: children intervals of the SOURCE-side boxes one depth up
 template <int D>
 __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const uint32_t *__restrict__ parent,
                                                     const int32_t *__restrict__ cell,
@@ -454,11 +463,21 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
             int o[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                o[d] = cell[(int64_t)bq * D + d] - ca[d];
+                o[d] = A.cell_src[(int64_t)bq * D + d] - ca[d];
                 d2 += o[d] * o[d];
             }
-            const bool is_small = A.rho && A.mode != 1 && cnt_a + (A.start[bq + 1] - A.start[bq]) <= A.rho;
-            const bool is_far = A.mode == 2 || (A.mode == 0 && d2 >= A.T);
+            bool far_rule = d2 >= A.T;
+            if (A.shifted) {
+                double s = 0.0;
+#pragma unroll
+                for (int d = 0; d < D; ++d) {
+                    const double t = __dadd_rn((double)o[d], A.u[d]);
+                    s = __dadd_rn(s, __dmul_rn(t, t));
+                }
+                far_rule = s >= A.theta2;
+            }
+            const bool is_small = A.rho && A.mode != 1 && cnt_a + (A.start_src[bq + 1] - A.start_src[bq]) <= A.rho;
+            const bool is_far = A.mode == 2 || (A.mode == 0 && far_rule);
             if (is_small) {
                 if (pass && A.small_col) A.small_col[sbase + ns] = bq;
                 ++ns;
@@ -478,16 +497,32 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
     }
 }
 
+// the rule part of a list kernel argument for one depth of a plan
+static ListArg list_rules(const f3m_plan_s &P, int level) {
+    const f3m_level &lv = P.lev[level], &sv = P.slev(level);
+    ListArg A{};
+    A.T = P.T;
+    A.mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
+    A.rho = (uint32_t)P.rho;
+    A.start = lv.start.p;
+    A.cell_src = sv.cell.p;
+    A.start_src = sv.start.p;
+    A.shifted = P.src ? 1 : 0;
+    P.grid_shift(level, A.u);
+    A.theta2 = (double)P.theta * (double)P.theta;
+    return A;
+}
+
 // point pairs of a CSR interaction list: |p| * sum of |q| over the row of p
 struct NearPairsIn {
-    const uint32_t *start;
+    const uint32_t *start, *start_src;   // point intervals of the target boxes / of the source boxes
     const uint64_t *near_ptr;
     const uint32_t *near_col;
     __device__ uint64_t operator()(int64_t a) const {
         uint64_t s = 0;
         for (uint64_t e = near_ptr[a]; e < near_ptr[a + 1]; ++e) {
             uint32_t q = near_col[e];
-            s += start[q + 1] - start[q];
+            s += start_src[q + 1] - start_src[q];
         }
         return s * (uint64_t)(start[a + 1] - start[a]);
     }
@@ -548,80 +583,175 @@ static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevB
 }
 
 // ------------------------------------------------------------------------------------
+// a point set while it is partitioned: the targets X of the plan, or the sources Y of a two-set plan
+struct SetRef {
+    const float *X;
+    int64_t n;
+    float *alpha;
+    DevBuf<uint32_t> *keys, *perm;
+    DevBuf<float> *Xs;
+    f3m_level *lev;
+};
+
+// per-dimension minimum and the largest extent (one fp32 subtraction per dimension) of a set
 template <int D>
-static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
+static float set_bounds(const SetRef &S, const char *name, hipStream_t st) {
+    DevBuf<float> part;
+    DevBuf<int> bad;
+    part.alloc((size_t)BBOX_BLOCKS * 2 * D);
+    bad.alloc(1);
+    F3M_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
+    bbox_kernel<D><<<dim3(BBOX_BLOCKS), dim3(BBOX_NT), 0, st>>>(S.X, S.n, part.p, bad.p);
+    F3M_HIP(hipGetLastError());
+    std::vector<float> hp((size_t)BBOX_BLOCKS * 2 * D);
+    int hbad = 0;
+    F3M_HIP(hipMemcpyAsync(hp.data(), part.p, hp.size() * sizeof(float), hipMemcpyDeviceToHost, st));
+    F3M_HIP(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
+    F3M_HIP(hipStreamSynchronize(st));
+    if (hbad) fail(F3M_ERR_NONFINITE, std::string(name) + " holds a NaN or an infinity");
+    float E = 0.f;
+    for (int d = 0; d < D; ++d) {
+        float mn = INFINITY, mx = -INFINITY;
+        for (int k = 0; k < BBOX_BLOCKS; ++k) {
+            mn = std::min(mn, hp[(size_t)k * 2 * D + d]);
+            mx = std::max(mx, hp[(size_t)k * 2 * D + D + d]);
+        }
+        volatile float ext = mx - mn;  // one fp32 subtraction
+        if (ext > E) E = ext;
+        S.alpha[d] = mn;
+    }
+    return E;
+}
+
+// Divide (Algorithm 1): the box table of depth l of one set -- heads of runs of equal depth-l keys,
+// from the points or, once the boxes of the depth above are few against the points, from their
+// intervals -- with parent ranks, child intervals of the depth above, cells and the largest box.
+template <int D>
+static void divide_set(f3m_plan_s &P, const SetRef &S, int l, DevBuf<uint32_t> &part, hipStream_t st) {
+    int64_t *tally = &P.bytes;
+    const int64_t n = S.n;
+    f3m_level &lv = S.lev[l];
+    const uint32_t *keys = S.keys->p;
+    int shift = D * (P.Lq - l);
+    const bool from_parents = l > 0 && (S.lev[l - 1].nb << D) <= n / 4;
+    if (from_parents) {
+        f3m_level &up = S.lev[l - 1];
+        const int64_t nslots = up.nb << D;
+        DevBuf<uint32_t> lb;
+        lb.alloc((size_t)nslots + 1);
+        child_bounds_kernel<D><<<dim3((unsigned)cdiv(nslots, 256)), dim3(256), 0, st>>>(keys, shift, up.start.p, nslots,
+                                                                                      up.key.p, lb.p);
+        F3M_HIP(hipGetLastError());
+        set_u32_kernel<<<1, 1, 0, st>>>(lb.p + nslots, (uint32_t)n);
+        ChildIn cin{lb.p};
+        ScanState SS;
+        scan_prepare(cin, nslots, SS, true, st);
+        lv.nb = (int64_t)SS.total;
+        lv.key.alloc((size_t)lv.nb, tally);
+        lv.start.alloc((size_t)lv.nb + 1, tally);
+        lv.parent.alloc((size_t)lv.nb, tally);
+        up.cstart.alloc((size_t)up.nb + 1, tally);
+        scan_finish(cin, nslots, SS, ChildOut<D>{lb.p, up.key.p, lv.start.p, lv.key.p, lv.parent.p, up.cstart.p}, st);
+        set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
+        set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
+        F3M_HIP(hipStreamSynchronize(st));   // lb is released on leaving the scope
+    } else {
+        HeadIn hin{keys, shift};
+        ScanState SS;
+        scan_prepare(hin, n, SS, true, st);
+        lv.nb = (int64_t)SS.total;
+        lv.key.alloc((size_t)lv.nb, tally);
+        lv.start.alloc((size_t)lv.nb + 1, tally);
+        scan_finish(hin, n, SS, HeadOut{keys, shift, lv.start.p, lv.key.p}, st);
+        set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
+    }
+    {
+        int grid = (int)std::min<int64_t>(1024, cdiv(lv.nb, 256));
+        max_count_kernel<<<dim3(grid), dim3(256), 0, st>>>(lv.start.p, lv.nb, part.p);
+        F3M_HIP(hipGetLastError());
+        std::vector<uint32_t> hp(grid);
+        F3M_HIP(hipMemcpyAsync(hp.data(), part.p, grid * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        F3M_HIP(hipStreamSynchronize(st));
+        lv.max_box = *std::max_element(hp.begin(), hp.end());
+    }
+    lv.cell.alloc((size_t)lv.nb * D, tally);
+    cells_kernel<D><<<dim3((unsigned)cdiv(lv.nb, 256)), dim3(256), 0, st>>>(lv.key.p, lv.nb, l, lv.cell.p);
+    F3M_HIP(hipGetLastError());
+    if (from_parents) {
+        // parent ranks and child intervals came with the division
+    } else if (l > 0) {
+        lv.parent.alloc((size_t)lv.nb, tally);
+        f3m_level &up = S.lev[l - 1];
+        up.cstart.alloc((size_t)up.nb + 1, tally);
+        HeadIn pin{lv.key.p, D};
+        uint64_t tot = 0;
+        exclusive_scan(pin, lv.nb, ParentOut{lv.parent.p, up.cstart.p}, &tot, st);
+        if ((int64_t)tot != up.nb) fail(F3M_ERR_HIP, "internal: parent count mismatch");
+        set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
+    } else {
+        lv.parent.alloc((size_t)lv.nb, tally);
+        F3M_HIP(hipMemsetAsync(lv.parent.p, 0, sizeof(uint32_t), st));
+    }
+}
+
+template <int D>
+static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStream_t st) {
     const int64_t n = P.n;
     int64_t *tally = &P.bytes;
     for (int k = 0; k < 8; ++k) F3M_HIP(hipEventCreate(&P.ev[k]));
     F3M_HIP(hipEventRecord(P.ev[0], st));
+    // the set(s) to partition: the targets, and the sources when they are another set
+    std::vector<SetRef> sets;
+    sets.push_back(SetRef{X, n, P.alpha, &P.keys, &P.perm, &P.Xs, P.lev});
+    if (P.src) sets.push_back(SetRef{Y, P.src->n, P.src->alpha, &P.src->keys, &P.src->perm, &P.src->Xs, P.src->lev});
 
-    // ---- enclosing cube
+    // ---- enclosing cubes: a common edge, the largest extent of either set (Sec. 3), each set
+    //      anchored at its own per-dimension minimum (the alpha of the box-index formula, Sec. 4.2)
     {
-        DevBuf<float> part;
-        DevBuf<int> bad;
-        part.alloc((size_t)BBOX_BLOCKS * 2 * D);
-        bad.alloc(1);
-        F3M_HIP(hipMemsetAsync(bad.p, 0, sizeof(int), st));
-        bbox_kernel<D><<<dim3(BBOX_BLOCKS), dim3(BBOX_NT), 0, st>>>(X, n, part.p, bad.p);
-        F3M_HIP(hipGetLastError());
-        std::vector<float> hp((size_t)BBOX_BLOCKS * 2 * D);
-        int hbad = 0;
-        F3M_HIP(hipMemcpyAsync(hp.data(), part.p, hp.size() * sizeof(float), hipMemcpyDeviceToHost, st));
-        F3M_HIP(hipMemcpyAsync(&hbad, bad.p, sizeof(int), hipMemcpyDeviceToHost, st));
-        F3M_HIP(hipStreamSynchronize(st));
-        if (hbad) fail(F3M_ERR_NONFINITE, "X holds a NaN or an infinity");
         float E = 0.f;
-        for (int d = 0; d < D; ++d) {
-            float mn = INFINITY, mx = -INFINITY;
-            for (int k = 0; k < BBOX_BLOCKS; ++k) {
-                mn = std::min(mn, hp[(size_t)k * 2 * D + d]);
-                mx = std::max(mx, hp[(size_t)k * 2 * D + D + d]);
-            }
-            volatile float ext = mx - mn;  // one fp32 subtraction
-            if (ext > E) E = ext;
-            P.alpha[d] = mn;
-        }
+        for (size_t k = 0; k < sets.size(); ++k) E = std::max(E, set_bounds<D>(sets[k], k ? "Y" : "X", st));
         P.E = E;
         P.scale = E > 0.f ? (float)(std::ldexp(1.0, P.Lq) / (double)E) : 0.f;
     }
 
     // ---- keys, sort, gather
-    DevBuf<uint32_t> keys_b, perm_b;
-    P.keys.alloc((size_t)n, tally);
-    P.perm.alloc((size_t)n, tally);
-    keys_b.alloc((size_t)n);
-    perm_b.alloc((size_t)n);
-    {
+    for (const SetRef &S : sets) {
+        S.keys->alloc((size_t)S.n, tally);
+        S.perm->alloc((size_t)S.n, tally);
         AlphaArg aa;
-        for (int d = 0; d < F3M_MAX_DIM; ++d) aa.a[d] = P.alpha[d];
-        keys_kernel<D><<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(X, n, aa, P.scale, P.Lq, P.keys.p);
+        for (int d = 0; d < F3M_MAX_DIM; ++d) aa.a[d] = S.alpha[d];
+        keys_kernel<D><<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.X, S.n, aa, P.scale, P.Lq, S.keys->p);
         F3M_HIP(hipGetLastError());
     }
     F3M_HIP(hipEventRecord(P.ev[1], st));
-    {
+    for (const SetRef &S : sets) {
+        DevBuf<uint32_t> keys_b, perm_b;
+        keys_b.alloc((size_t)S.n);
+        perm_b.alloc((size_t)S.n);
         int bits = P.E > 0.f ? D * P.Lq : 0;
         bool in_b;
         if (bits == 0) {
-            iota_kernel<<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(P.perm.p, n);
+            iota_kernel<<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.perm->p, S.n);
             in_b = false;
         } else {
-            in_b = radix_sort(P.keys.p, P.perm.p, keys_b.p, perm_b.p, n, bits, st);
+            in_b = radix_sort(S.keys->p, S.perm->p, keys_b.p, perm_b.p, S.n, bits, st);
         }
         if (in_b) {
-            std::swap(P.keys.p, keys_b.p);
-            std::swap(P.perm.p, perm_b.p);
+            std::swap(S.keys->p, keys_b.p);
+            std::swap(S.perm->p, perm_b.p);
         }
+        F3M_HIP(hipStreamSynchronize(st));   // the second buffers are released on leaving the scope
     }
     F3M_HIP(hipEventRecord(P.ev[2], st));
-    // 64 zero points of padding after the last point: kernels may read whole 32-point blocks
-    P.Xs.alloc(((size_t)n + PAD_POINTS) * D, tally);
-    F3M_HIP(hipMemsetAsync(P.Xs.p + (size_t)n * D, 0, (size_t)PAD_POINTS * D * sizeof(float), st));
-    gather_rows_kernel<D><<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(X, P.perm.p, n, P.Xs.p);
-    F3M_HIP(hipGetLastError());
+    for (const SetRef &S : sets) {
+        // 64 zero points of padding after the last point: kernels may read whole 32-point blocks
+        S.Xs->alloc(((size_t)S.n + PAD_POINTS) * D, tally);
+        F3M_HIP(hipMemsetAsync(S.Xs->p + (size_t)S.n * D, 0, (size_t)PAD_POINTS * D * sizeof(float), st));
+        gather_rows_kernel<D><<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.X, S.perm->p, S.n, S.Xs->p);
+        F3M_HIP(hipGetLastError());
+    }
     F3M_HIP(hipEventRecord(P.ev[3], st));
     F3M_HIP(hipStreamSynchronize(st));
-    keys_b.release();
-    perm_b.release();
 
     // ---- Algorithm 1 loop: divide, new interactions, partition
     int cap = P.Lq;
@@ -636,68 +766,8 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     for (;; ++l) {
         f3m_level &lv = P.lev[l];
         F3M_HIP(hipEventRecord(ea, st));
-        // divide: heads of runs of equal depth-l keys, from the points or, once the boxes of the
-        // depth above are few against the points, from their intervals
-        int shift = D * (P.Lq - l);
-        const bool from_parents = l > 0 && (P.lev[l - 1].nb << D) <= n / 4;
-        if (from_parents) {
-            f3m_level &up = P.lev[l - 1];
-            const int64_t nslots = up.nb << D;
-            DevBuf<uint32_t> lb;
-            lb.alloc((size_t)nslots + 1);
-            child_bounds_kernel<D><<<dim3((unsigned)cdiv(nslots, 256)), dim3(256), 0, st>>>(P.keys.p, shift, up.start.p,
-                                                                                          nslots, up.key.p, lb.p);
-            F3M_HIP(hipGetLastError());
-            set_u32_kernel<<<1, 1, 0, st>>>(lb.p + nslots, (uint32_t)n);
-            ChildIn cin{lb.p};
-            ScanState S;
-            scan_prepare(cin, nslots, S, true, st);
-            lv.nb = (int64_t)S.total;
-            lv.key.alloc((size_t)lv.nb, tally);
-            lv.start.alloc((size_t)lv.nb + 1, tally);
-            lv.parent.alloc((size_t)lv.nb, tally);
-            up.cstart.alloc((size_t)up.nb + 1, tally);
-            scan_finish(cin, nslots, S, ChildOut<D>{lb.p, up.key.p, lv.start.p, lv.key.p, lv.parent.p, up.cstart.p}, st);
-            set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
-            set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
-            F3M_HIP(hipStreamSynchronize(st));   // lb is released on leaving the scope
-        } else {
-            HeadIn hin{P.keys.p, shift};
-            ScanState S;
-            scan_prepare(hin, n, S, true, st);
-            lv.nb = (int64_t)S.total;
-            lv.key.alloc((size_t)lv.nb, tally);
-            lv.start.alloc((size_t)lv.nb + 1, tally);
-            scan_finish(hin, n, S, HeadOut{P.keys.p, shift, lv.start.p, lv.key.p}, st);
-            set_u32_kernel<<<1, 1, 0, st>>>(lv.start.p + lv.nb, (uint32_t)n);
-        }
-        {
-            int grid = (int)std::min<int64_t>(1024, cdiv(lv.nb, 256));
-            max_count_kernel<<<dim3(grid), dim3(256), 0, st>>>(lv.start.p, lv.nb, part.p);
-            F3M_HIP(hipGetLastError());
-            std::vector<uint32_t> hp(grid);
-            F3M_HIP(hipMemcpyAsync(hp.data(), part.p, grid * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
-            F3M_HIP(hipStreamSynchronize(st));
-            lv.max_box = *std::max_element(hp.begin(), hp.end());
-        }
-        lv.cell.alloc((size_t)lv.nb * D, tally);
-        cells_kernel<D><<<dim3((unsigned)cdiv(lv.nb, 256)), dim3(256), 0, st>>>(lv.key.p, lv.nb, l, lv.cell.p);
-        F3M_HIP(hipGetLastError());
-        if (from_parents) {
-            // parent ranks and child intervals came with the division
-        } else if (l > 0) {
-            lv.parent.alloc((size_t)lv.nb, tally);
-            f3m_level &up = P.lev[l - 1];
-            up.cstart.alloc((size_t)up.nb + 1, tally);
-            HeadIn pin{lv.key.p, D};
-            uint64_t tot = 0;
-            exclusive_scan(pin, lv.nb, ParentOut{lv.parent.p, up.cstart.p}, &tot, st);
-            if ((int64_t)tot != up.nb) fail(F3M_ERR_HIP, "internal: parent count mismatch");
-            set_u32_kernel<<<1, 1, 0, st>>>(up.cstart.p + up.nb, (uint32_t)lv.nb);
-        } else {
-            lv.parent.alloc((size_t)lv.nb, tally);
-            F3M_HIP(hipMemsetAsync(lv.parent.p, 0, sizeof(uint32_t), st));
-        }
+        for (const SetRef &S : sets) divide_set<D>(P, S, l, part, st);
+        const f3m_level &sv = P.slev(l);
         F3M_HIP(hipEventRecord(eb, st));
 
         // new interactions + partition
@@ -714,6 +784,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lv.far_sz = 0;
         } else {
             f3m_level &up = P.lev[l - 1];
+            const f3m_level &sup = P.slev(l - 1);
             DevBuf<uint32_t> cn, cf, cs;
             cn.alloc((size_t)lv.nb);
             cf.alloc((size_t)lv.nb);
@@ -722,16 +793,12 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             // Sec. 4.3: once the boxes pass the smoothness criterion every pair left is interpolated
             lv.smooth = !P.force_all_near && smooth_rule((double)P.E, l, D, (double)P.gamma, (double)P.eta_smooth);
             if (lv.smooth) P.smooth_depth = l;
-            ListArg A{};
-            A.T = P.T;
-            A.mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
-            A.rho = (uint32_t)P.rho;
-            A.start = lv.start.p;
+            ListArg A = list_rules(P, l);
             A.cnt_near = cn.p;
             A.cnt_far = cf.p;
             A.cnt_small = cs.p;
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, up.cstart.p, A);
+                                                             up.near_col.p, sup.cstart.p, A);
             F3M_HIP(hipGetLastError());
             uint64_t tn = 0, tf = 0, ts = 0;
             exclusive_scan(U32In{cn.p}, lv.nb, PtrOut{lv.near_ptr.p}, &tn, st);
@@ -766,7 +833,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             A.far_col = lv.far_implicit ? nullptr : lv.far_col.p;
             A.small_col = lv.small_col.p;
             lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, up.cstart.p, A);
+                                                             up.near_col.p, sup.cstart.p, A);
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
@@ -777,14 +844,10 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
         t_boxes += ms;
         F3M_HIP(hipEventElapsedTime(&ms, eb, ec));
         t_lists += ms;
-        // while interactions remain and the largest box is above zeta (Algorithm 1)
-        if (!(lv.near_sz > 0 && lv.max_box > P.leaf_max && l < cap)) break;
+        // while interactions remain and the largest box of either tree is above zeta (Algorithm 1)
+        if (!(lv.near_sz > 0 && lv.max_box > P.leaf_max && sv.max_box > P.leaf_max && l < cap)) break;
     }
     P.L = l;
-    // near lists of the depths above L are only needed to derive the next depth
-    for (int k = 0; k < P.L; ++k) {
-        // kept: they are small next to the leaf lists and serve introspection
-    }
 
     // ---- work splits and workspaces
     F3M_HIP(hipEventRecord(ea, st));
@@ -802,7 +865,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
     }
     upload_kron_tables(P, st);
     permute_out_prepare(P, st);
-    int64_t max_w = 0, max_part = 0, max_slice = 0;
+    int64_t max_w = 0, max_v = 0, max_part = 0, max_slice = 0;
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
         if (lv.far_sz == 0 || lv.p == 0) continue;   // nothing to interpolate, or dropped
@@ -812,14 +875,20 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             lv.Vl.alloc((size_t)lv.nb * lv.r, tally);
             if (k < P.tree_lmax) continue;   // only the last depth of the band needs chunks
         }
+        // runs of points for the L2P (targets) and the P2M (sources: the same runs for one point set)
         build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
-        if (lv.max_box > (int64_t)P2M_CHUNK * P2M_SLICE * 2) {
+        f3m_level &sv = P.slev(k);
+        if (P.src) build_chunks(sv.start.p, sv.nb, P2M_CHUNK, sv.chunk_first, sv.chunk_box, sv.nchunks, tally, st);
+        if (sv.max_box > (int64_t)P2M_CHUNK * P2M_SLICE * 2) {
             // a box with more than a thousand chunks: its partial node weights are summed in two stages
-            build_chunks(lv.chunk_first.p, lv.nb, P2M_SLICE, lv.slice_first, lv.slice_box, lv.nslices, tally, st);
-            max_slice = std::max(max_slice, lv.nslices * (int64_t)lv.r);
+            build_chunks(sv.chunk_first.p, sv.nb, P2M_SLICE, sv.slice_first, sv.slice_box, sv.nslices, tally, st);
+            max_slice = std::max(max_slice, sv.nslices * (int64_t)lv.r);
         }
-        if (!tree) max_w = std::max(max_w, lv.nb * (int64_t)lv.r);
-        max_part = std::max(max_part, lv.nchunks * (int64_t)lv.r);
+        if (!tree) {
+            max_w = std::max(max_w, sv.nb * (int64_t)lv.r);
+            max_v = std::max(max_v, lv.nb * (int64_t)lv.r);
+        }
+        max_part = std::max(max_part, sv.nchunks * (int64_t)lv.r);
     }
     build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
     // target tiles of the small-field rows of every depth (Sec. 4.2)
@@ -829,14 +898,14 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
             build_chunks(lv.start.p, lv.nb, D <= 4 ? 16 : 8, lv.sm_tile_first, lv.sm_tile_box, lv.sm_ntiles, tally, st,
                          lv.small_ptr.p);   // runs of targets as p2p_small_kernel takes them
     }
-    P.bs.alloc((size_t)n + PAD_POINTS, tally);
-    F3M_HIP(hipMemsetAsync(P.bs.p + n, 0, (size_t)PAD_POINTS * sizeof(float), st));
+    P.bs.alloc((size_t)P.ns() + PAD_POINTS, tally);
+    F3M_HIP(hipMemsetAsync(P.bs.p + P.ns(), 0, (size_t)PAD_POINTS * sizeof(float), st));
     P.ys.alloc((size_t)n, tally);
     P.yn.alloc((size_t)n, tally);
     if (!P.no_overlap) F3M_HIP(hipStreamCreateWithFlags(&P.side, hipStreamNonBlocking));
     for (hipEvent_t *e : {&P.ev_fork, &P.ev_join, &P.ev_p2p0, &P.ev_p2p1}) F3M_HIP(hipEventCreate(e));
     P.W.alloc((size_t)max_w, tally);
-    P.V.alloc((size_t)max_w, tally);
+    P.V.alloc((size_t)max_v, tally);
     P.Wpart.alloc((size_t)max_part, tally);
     P.Wslice.alloc((size_t)max_slice, tally);
     F3M_HIP(hipEventRecord(eb, st));
@@ -859,16 +928,12 @@ static void build_plan_d(f3m_plan_s &P, const float *X, hipStream_t st) {
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st) {
     const f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
     const unsigned grid = (unsigned)cdiv(lv.nb, 128);
-    ListArg A{};
-    A.T = P.T;
-    A.mode = P.force_all_near ? 1 : lv.smooth ? 2 : 0;
-    A.rho = (uint32_t)P.rho;
-    A.start = lv.start.p;
+    ListArg A = list_rules(P, level);
     A.far_ptr = lv.far_ptr.p;
     A.far_col = cols_dev;
     auto launch = [&](auto kern) {
         kern<<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p, up.near_col.p,
-                                               up.cstart.p, A);
+                                               P.slev(level - 1).cstart.p, A);
     };
     switch (P.D) {
         case 1: launch(lists_kernel<1>); break;
@@ -891,7 +956,7 @@ void compute_far_point_pairs(f3m_plan_s &P) {
     {
         ScanState S;
         const f3m_level &lf = P.lev[P.L];
-        scan_prepare(NearPairsIn{lf.start.p, lf.near_ptr.p, lf.near_col.p}, lf.nb, S, true, nullptr);
+        scan_prepare(NearPairsIn{lf.start.p, P.slev(P.L).start.p, lf.near_ptr.p, lf.near_col.p}, lf.nb, S, true, nullptr);
         P.near_point_pairs = (int64_t)S.total;
     }
     for (int l = 1; l <= P.L; ++l) {
@@ -899,7 +964,7 @@ void compute_far_point_pairs(f3m_plan_s &P) {
         lv.small_point_pairs = 0;
         if (lv.small_sz > 0) {
             ScanState S;
-            scan_prepare(NearPairsIn{lv.start.p, lv.small_ptr.p, lv.small_col.p}, lv.nb, S, true, nullptr);
+            scan_prepare(NearPairsIn{lv.start.p, P.slev(l).start.p, lv.small_ptr.p, lv.small_col.p}, lv.nb, S, true, nullptr);
             lv.small_point_pairs = (int64_t)S.total;
         }
         lv.far_point_pairs = 0;
@@ -909,11 +974,11 @@ void compute_far_point_pairs(f3m_plan_s &P) {
             cols.alloc((size_t)lv.far_sz);
             materialize_far(P, l, cols.p, nullptr);
             ScanState S;
-            scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, cols.p}, lv.nb, S, true, nullptr);
+            scan_prepare(NearPairsIn{lv.start.p, P.slev(l).start.p, lv.far_ptr.p, cols.p}, lv.nb, S, true, nullptr);
             lv.far_point_pairs = (int64_t)S.total;
         } else {
             ScanState S;
-            scan_prepare(NearPairsIn{lv.start.p, lv.far_ptr.p, lv.far_col.p}, lv.nb, S, true, nullptr);
+            scan_prepare(NearPairsIn{lv.start.p, P.slev(l).start.p, lv.far_ptr.p, lv.far_col.p}, lv.nb, S, true, nullptr);
             lv.far_point_pairs = (int64_t)S.total;
         }
     }
@@ -939,15 +1004,15 @@ int adaptive_nodes(double E, int depth, double gamma, int p) {
     return 0;
 }
 
-void build_plan(f3m_plan_s &P, const float *X, hipStream_t st) {
+void build_plan(f3m_plan_s &P, const float *X, const float *Y, hipStream_t st) {
     switch (P.D) {
-        case 1: build_plan_d<1>(P, X, st); break;
-        case 2: build_plan_d<2>(P, X, st); break;
-        case 3: build_plan_d<3>(P, X, st); break;
-        case 4: build_plan_d<4>(P, X, st); break;
-        case 5: build_plan_d<5>(P, X, st); break;
-        case 6: build_plan_d<6>(P, X, st); break;
-        case 7: build_plan_d<7>(P, X, st); break;
+        case 1: build_plan_d<1>(P, X, Y, st); break;
+        case 2: build_plan_d<2>(P, X, Y, st); break;
+        case 3: build_plan_d<3>(P, X, Y, st); break;
+        case 4: build_plan_d<4>(P, X, Y, st); break;
+        case 5: build_plan_d<5>(P, X, Y, st); break;
+        case 6: build_plan_d<6>(P, X, Y, st); break;
+        case 7: build_plan_d<7>(P, X, Y, st); break;
         default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
     }
 }

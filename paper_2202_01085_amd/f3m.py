@@ -46,6 +46,11 @@ class Info(ctypes.Structure):
                 ("small_point_pairs", ctypes.c_int64 * (MAX_LEVELS + 1))]
 
 
+class SourceInfo(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("two_sets", ctypes.c_int32), ("alpha", ctypes.c_float * MAX_DIM),
+                ("nboxes", ctypes.c_int64 * (MAX_LEVELS + 1)), ("max_box", ctypes.c_int64 * (MAX_LEVELS + 1))]
+
+
 class Times(ctypes.Structure):
     _fields_ = [(k, ctypes.c_float) for k in
                 ("bbox_keys", "sort", "gather", "boxes", "lists", "tables", "plan_total",
@@ -69,7 +74,13 @@ def lib():
         vp, i64, ci, cf = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
         L.f3m_plan.argtypes = [vp, i64, ci, cf, ci, cf, vp, ctypes.POINTER(vp)]
         L.f3m_plan_ex.argtypes = [vp, i64, ci, cf, ci, cf, ctypes.POINTER(Options), vp, ctypes.POINTER(vp)]
+        L.f3m_plan_xy.argtypes = [vp, i64, vp, i64, ci, cf, ci, cf, ctypes.POINTER(Options), vp, ctypes.POINTER(vp)]
         L.f3m_kmvm.argtypes = [vp, vp, vp, vp]
+        L.direct_kmvm_xy.argtypes = [vp, i64, vp, i64, ci, cf, vp, vp, vp]
+        L.direct_kmvm_xy_rows_f64.argtypes = [vp, i64, vp, i64, ci, cf, vp, vp, i64, vp, vp]
+        L.f3m_plan_source_info.argtypes = [vp, ctypes.POINTER(SourceInfo)]
+        L.f3m_plan_get_source_perm.argtypes = [vp, vp]
+        L.f3m_plan_get_source_boxes.argtypes = [vp, ci, vp, vp]
         L.direct_kmvm.argtypes = [vp, i64, ci, cf, vp, vp, vp]
         L.direct_kmvm_rows_f64.argtypes = [vp, i64, ci, cf, vp, vp, i64, vp, vp]
         L.f3m_destroy.argtypes = [vp]
@@ -84,7 +95,8 @@ def lib():
         L.f3m_level_times.argtypes = [vp, ci, vp]
         for name in ("f3m_plan", "f3m_plan_ex", "f3m_kmvm", "direct_kmvm", "direct_kmvm_rows_f64", "f3m_plan_info",
                      "f3m_plan_get_perm", "f3m_plan_get_point_keys", "f3m_plan_get_boxes", "f3m_plan_get_list",
-                     "f3m_stage_times", "f3m_level_times"):
+                     "f3m_stage_times", "f3m_level_times", "f3m_plan_xy", "direct_kmvm_xy", "direct_kmvm_xy_rows_f64",
+                     "f3m_plan_source_info", "f3m_plan_get_source_perm", "f3m_plan_get_source_boxes"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -112,18 +124,28 @@ def _np_ptr(a):
 
 
 class Plan:
-    """f3m_plan / f3m_plan_ex: the partition and interaction lists of one point set."""
+    """f3m_plan / f3m_plan_ex: the partition and interaction lists of one point set;
+    with Y given, f3m_plan_xy: targets X and sources Y, for v = K(X, Y) b."""
 
     def __init__(self, X, lengthscale, interp_nodes, eta=2.0, leaf_max=0, max_depth=0, force_all_near=False,
-                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False, small_field=0):
+                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False, small_field=0, Y=None):
         n, D = X.shape
         self.n, self.D = int(n), int(D)
+        self.ns = self.n
         self._h = ctypes.c_void_p()
         opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), int(bool(overlap)),
                       float(eta_smooth), int(bool(adaptive_far)), int(small_field))
         xp = _dev_f32(X, "X") if n > 0 else ctypes.c_void_p()
-        _check(lib().f3m_plan_ex(xp, self.n, self.D, float(lengthscale), int(interp_nodes), float(eta),
-                                 ctypes.byref(opt), _stream(stream), ctypes.byref(self._h)))
+        if Y is None:
+            _check(lib().f3m_plan_ex(xp, self.n, self.D, float(lengthscale), int(interp_nodes), float(eta),
+                                     ctypes.byref(opt), _stream(stream), ctypes.byref(self._h)))
+        else:
+            if Y.shape[1] != D:
+                raise ValueError("X and Y must have the same number of columns")
+            self.ns = int(Y.shape[0])
+            yp = _dev_f32(Y, "Y") if self.ns > 0 else ctypes.c_void_p()
+            _check(lib().f3m_plan_xy(xp, self.n, yp, self.ns, self.D, float(lengthscale), int(interp_nodes),
+                                     float(eta), ctypes.byref(opt), _stream(stream), ctypes.byref(self._h)))
 
     def close(self):
         h, self._h = getattr(self, "_h", None), None
@@ -133,15 +155,32 @@ class Plan:
     __del__ = close
 
     def kmvm(self, b, y=None, stream=None):
-        """f3m_kmvm: y ~= K(X,X) b (asynchronous on the stream)."""
+        """f3m_kmvm: y ~= K(X,X) b, or K(X,Y) b for a two-set plan (asynchronous on the stream)."""
         if y is None:
-            y = torch.empty_like(b)
+            y = torch.empty(self.n, dtype=torch.float32, device=b.device)
         if self.n == 0:
             return y
-        if b.numel() != self.n or y.numel() != self.n:
-            raise ValueError("b and y must have n entries")
-        _check(lib().f3m_kmvm(self._h, _dev_f32(b, "b"), _dev_f32(y, "y"), _stream(stream)))
+        if b.numel() != self.ns or y.numel() != self.n:
+            raise ValueError("b must have one entry per source and y one per target")
+        _check(lib().f3m_kmvm(self._h, _dev_f32(b, "b") if self.ns else None, _dev_f32(y, "y"), _stream(stream)))
         return y
+
+    def source_info(self):
+        out = SourceInfo()
+        _check(lib().f3m_plan_source_info(self._h, ctypes.byref(out)))
+        return out
+
+    def source_perm(self):
+        out = np.empty(self.ns, dtype=np.uint32)
+        _check(lib().f3m_plan_get_source_perm(self._h, _np_ptr(out)))
+        return out
+
+    def source_boxes(self, level):
+        nb = int(self.source_info().nboxes[level])
+        keys = np.empty(nb, dtype=np.uint32)
+        starts = np.empty(nb + 1, dtype=np.uint32)
+        _check(lib().f3m_plan_get_source_boxes(self._h, int(level), _np_ptr(keys), _np_ptr(starts)))
+        return keys, starts
 
     def info(self):
         out = Info()
@@ -212,4 +251,29 @@ def direct_kmvm_rows_f64(X, b, lengthscale, rows, stream=None):
     _check(lib().direct_kmvm_rows_f64(_dev_f32(X, "X"), int(n), int(D), float(lengthscale), _dev_f32(b, "b"),
                                       ctypes.c_void_p(rows.data_ptr()), int(rows.numel()),
                                       ctypes.c_void_p(y64.data_ptr()), _stream(stream)))
+    return y64
+
+
+def direct_kmvm_xy(X, Y, b, lengthscale, y=None, stream=None):
+    """direct_kmvm_xy: exact y = K(X,Y) b in fp32."""
+    nx, D = X.shape
+    ny = Y.shape[0]
+    if y is None:
+        y = torch.empty(nx, dtype=torch.float32, device=X.device)
+    _check(lib().direct_kmvm_xy(_dev_f32(X, "X") if nx else None, int(nx), _dev_f32(Y, "Y") if ny else None, int(ny),
+                                int(D), float(lengthscale), _dev_f32(b, "b") if ny else None,
+                                _dev_f32(y, "y") if nx else None, _stream(stream)))
+    return y
+
+
+def direct_kmvm_xy_rows_f64(X, Y, b, lengthscale, rows, stream=None):
+    """direct_kmvm_xy_rows_f64: exact fp64 sums of K(X,Y) b for the selected rows of X."""
+    nx, D = X.shape
+    ny = Y.shape[0]
+    rows = rows.to(device=X.device, dtype=torch.int64).contiguous()
+    y64 = torch.empty(rows.numel(), dtype=torch.float64, device=X.device)
+    _check(lib().direct_kmvm_xy_rows_f64(_dev_f32(X, "X"), int(nx), _dev_f32(Y, "Y") if ny else None, int(ny), int(D),
+                                         float(lengthscale), _dev_f32(b, "b") if ny else None,
+                                         ctypes.c_void_p(rows.data_ptr()), int(rows.numel()),
+                                         ctypes.c_void_p(y64.data_ptr()), _stream(stream)))
     return y64

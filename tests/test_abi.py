@@ -28,7 +28,9 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"f3m_plan", "f3m_plan_ex", "f3m_kmvm", "direct_kmvm", "direct_kmvm_rows_f64", "f3m_destroy",
             "f3m_last_error", "f3m_plan_info", "f3m_plan_get_perm", "f3m_plan_get_point_keys",
-            "f3m_plan_get_boxes", "f3m_plan_get_list", "f3m_stage_times", "f3m_level_times"} <= set(names)
+            "f3m_plan_get_boxes", "f3m_plan_get_list", "f3m_stage_times", "f3m_level_times", "f3m_plan_xy",
+            "direct_kmvm_xy", "direct_kmvm_xy_rows_f64", "f3m_plan_source_info", "f3m_plan_get_source_perm",
+            "f3m_plan_get_source_boxes"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
@@ -37,6 +39,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(f3m.Options) == 4 * 4 + 4 + 4 + 4
     assert ctypes.sizeof(f3m.Info) == 8 + 6 * 4 + 2 * 4 + 7 * 4 + 4 + 5 * 21 * 8 + 8 + 8 + 4 + 21 * 4 + 2 * 21 * 8
     assert ctypes.sizeof(f3m.Times) == 14 * 4
+    assert ctypes.sizeof(f3m.SourceInfo) == 8 + 4 + 7 * 4 + 2 * 21 * 8
 
 
 def test_argument_checks_need_no_device(lib):
@@ -63,4 +66,15 @@ def test_argument_checks_need_no_device(lib):
     assert lib.direct_kmvm(fake, 10, 3, 1.0, None, fake, None) == 1
     assert lib.direct_kmvm(fake, 10, 3, 1.0, fake, fake, None) == 1                # b aliases y
     assert lib.direct_kmvm(None, 0, 3, 1.0, None, None, None) == 0                 # empty problem
+    # two point sets
+    opt = None
+    assert lib.f3m_plan_xy(fake, 10, None, 5, 3, 1.0, 4, 2.0, opt, None, ctypes.byref(h)) == 1   # null Y
+    assert lib.f3m_plan_xy(fake, 10, fake, -1, 3, 1.0, 4, 2.0, opt, None, ctypes.byref(h)) == 1  # ny < 0
+    assert lib.f3m_plan_xy(fake, 10, fake, 2 ** 31, 3, 1.0, 4, 2.0, opt, None, ctypes.byref(h)) == 3
+    assert lib.f3m_plan_xy(None, 10, fake, 5, 3, 1.0, 4, 2.0, opt, None, ctypes.byref(h)) == 1   # null X
+    assert not h.value
+    assert lib.direct_kmvm_xy(fake, 10, None, 5, 3, 1.0, fake, fake, None) == 1                  # null Y
+    assert lib.direct_kmvm_xy(fake, 10, fake, 5, 3, 1.0, fake, fake, None) == 1                  # b aliases y
+    assert lib.direct_kmvm_xy(None, 0, fake, 5, 3, 1.0, fake, None, None) == 0                   # no targets
+    assert lib.direct_kmvm_xy_rows_f64(fake, 10, fake, 5, 3, 1.0, fake, None, 4, fake, None) == 1  # null rows
     lib.f3m_destroy(None)                                                           # allowed

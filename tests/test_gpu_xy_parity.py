@@ -1,0 +1,202 @@
+"""GPU parity for two point sets, v = K(X, Y) b: the HIP library (through its C ABI, f3m_plan_xy,
+f3m_kmvm, direct_kmvm_xy) against the two-set CPU oracle.
+
+Bars as for one set: permutations, box tables of both sets and interaction lists bit-exact (the far
+decision is taken in fp64 by the same expression on both sides); v against the CPU F3M to relative
+L2 <= 1e-5.  The workload stands in for the paper's two-set experiment (Sec. 5 "KMVM experiments":
+uniformly distributed X, normally distributed Y).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2202_01085_amd import f3m, inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL_F3M = 1e-5
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rel(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+def g32(v):
+    return float(np.float32(v))
+
+
+def cloud(dist, n, D, seed):
+    gen = {"uniform": inputs.points_uniform, "normal": inputs.points_normal, "mixture": inputs.points_mixture}[dist]
+    return gen(n, D, seed)
+
+
+def two_sets(nx, ny, D, xdist, ydist, yscale, yshift, seed):
+    X = cloud(xdist, nx, D, seed)
+    Y = (cloud(ydist, ny, D, seed + 1) * yscale + yshift).to(torch.float32).contiguous()
+    b = inputs.rhs_normal(ny, seed + 2)
+    return X, Y, b
+
+
+def check_plan_bit_exact(plan, T):
+    inf, sinf = plan.info(), plan.source_info()
+    assert inf.depth == T.L and sinf.two_sets == 1
+    assert float(inf.edge) == np.float32(T.E)
+    assert [float(inf.alpha[d]) for d in range(T.D)] == [float(np.float32(a)) for a in T.tx.alpha]
+    assert [float(sinf.alpha[d]) for d in range(T.D)] == [float(np.float32(a)) for a in T.ty.alpha]
+    assert np.array_equal(plan.perm().astype(np.int64), T.tx.perm())
+    assert np.array_equal(plan.source_perm().astype(np.int64), T.ty.perm())
+    assert np.array_equal(plan.point_keys().astype(np.uint64), T.tx.point_keys()[T.tx.perm()])
+    for l in range(T.L + 1):
+        for got, want in ((plan.boxes(l), T.tx.boxes(l)), (plan.source_boxes(l), T.ty.boxes(l))):
+            assert np.array_equal(got[0].astype(np.uint64), want[0]), l
+            assert np.array_equal(got[1].astype(np.int64), want[1]), l
+        for kind in (0, 1, 2):
+            ptr, cols = plan.interactions(l, kind)
+            optr, ocols = T.interactions(l, kind)
+            assert np.array_equal(ptr.astype(np.int64), optr), (l, kind)
+            assert np.array_equal(cols.astype(np.int64), ocols), (l, kind)
+
+
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("nx,ny,D,gamma", [(1, 1, 3, 1.0), (65, 63, 1, 0.3), (1000, 3001, 5, 1.5), (3001, 700, 7, 2.0),
+                                           (5000, 4000, 3, 0.2)])
+def test_direct_xy_matches_oracle(nx, ny, D, gamma):
+    say("direct_kmvm_xy nx=%d ny=%d D=%d" % (nx, ny, D))
+    X, Y, b = two_sets(nx, ny, D, "uniform", "normal", 0.5, 0.5, 300 + D)
+    Xd, Yd, bd = [a.to(DEV) for a in (X, Y, b)]
+    y = f3m.direct_kmvm_xy(Xd, Yd, bd, gamma)
+    torch.cuda.synchronize()
+    want = oracle.rows_xy(X.numpy(), Y.numpy(), b.numpy(), g32(gamma))
+    assert rel(y.cpu().numpy(), want) <= TOL_F3M
+    rows = inputs.sample_rows(nx, 50, 9)
+    y64 = f3m.direct_kmvm_xy_rows_f64(Xd, Yd, bd, gamma, rows)
+    torch.cuda.synchronize()
+    assert rel(y64.cpu().numpy(), want[rows.numpy()]) <= 1e-12
+
+
+XY_CASES = [
+    # nx, ny, D, xdist, ydist, yscale, yshift, p, gamma, theta, zeta, max_depth, rho, eta_smooth, adaptive
+    (20_000, 20_000, 3, "uniform", "normal", 1.0, 0.0, 4, 1.0, 2.0, 64, 0, 0, 0.0, False),   # the paper's U & N sets
+    (30_000, 12_000, 3, "uniform", "normal", 0.3, 0.5, 4, 0.3, 2.0, 32, 0, 0, 0.0, False),   # Y inside the cube of X
+    (7_000, 25_000, 3, "normal", "uniform", 4.0, -2.0, 4, 0.5, 2.0, 48, 0, 0, 0.0, False),   # more sources than targets
+    (9_000, 9_000, 3, "uniform", "uniform", 1.0, 0.37, 5, 0.4, 2.0, 40, 0, 0, 0.0, False),   # the same cube, shifted
+    (6_000, 5_000, 1, "uniform", "normal", 0.2, 0.6, 6, 0.02, 2.0, 16, 0, 0, 0.0, False),
+    (8_000, 8_000, 2, "normal", "normal", 1.5, 0.2, 6, 0.3, 2.0, 32, 0, 0, 0.0, False),
+    (9_000, 7_000, 3, "normal", "uniform", 3.0, -1.5, 3, 0.8, 1.5, 40, 0, 0, 0.0, False),    # far ratio 1.5
+    (6_000, 6_000, 3, "uniform", "normal", 0.4, 0.5, 2, 0.8, 3.0, 40, 0, 0, 0.0, False),     # far ratio 3
+    (6_000, 5_000, 4, "uniform", "normal", 0.4, 0.5, 3, 1.0, 2.0, 50, 2, 0, 0.0, False),
+    (4_000, 4_500, 5, "uniform", "normal", 0.4, 0.5, 2, 1.0, 2.0, 60, 2, 0, 0.0, False),
+    (3_000, 3_500, 7, "mixture", "mixture", 1.0, 0.5, 2, 2.5, 2.0, 100, 1, 0, 0.0, False),
+    (20_000, 15_000, 3, "uniform", "normal", 0.3, 0.5, 4, 0.3, 2.0, 16, 0, 24, 0.0, False),  # small field
+    (5_000, 6_000, 5, "normal", "normal", 1.0, 0.3, 2, 1.0, 2.0, 8, 0, 10, 0.0, False),      # small field, D = 5
+    (20_000, 20_000, 3, "uniform", "normal", 0.5, 0.5, 4, 1.5, 2.0, 16, 0, 0, 0.05, True),   # smooth field + adaptive rule
+    (10_000, 10_000, 2, "normal", "normal", 1.0, 0.1, 5, 2.0, 2.0, 8, 0, 12, 0.02, True),
+    (3_000, 2_000, 3, "uniform", "normal", 0.05, 30.0, 4, 20.0, 2.0, 16, 0, 0, 0.0, False),  # distant sets: all far at depth 1
+]
+
+
+@pytest.mark.parametrize("nx,ny,D,xdist,ydist,yscale,yshift,p,gamma,theta,zeta,max_depth,rho,eta_smooth,adaptive",
+                         XY_CASES)
+def test_xy_parity(nx, ny, D, xdist, ydist, yscale, yshift, p, gamma, theta, zeta, max_depth, rho, eta_smooth, adaptive):
+    say("f3m xy nx=%d ny=%d D=%d %s/%s*%g%+g p=%d gamma=%g theta=%g zeta=%d max_depth=%d rho=%d eta_smooth=%g adaptive=%s"
+        % (nx, ny, D, xdist, ydist, yscale, yshift, p, gamma, theta, zeta, max_depth, rho, eta_smooth, adaptive))
+    X, Y, b = two_sets(nx, ny, D, xdist, ydist, yscale, yshift, 400 + D)
+    T = oracle.Tree2(X.numpy(), Y.numpy(), theta=theta, zeta=zeta, max_depth=max_depth, gamma=g32(gamma),
+                     eta_smooth=g32(eta_smooth), small_field=rho)
+    Xd, Yd, bd = [a.to(DEV) for a in (X, Y, b)]
+    plan = f3m.Plan(Xd, gamma, p, theta, Y=Yd, leaf_max=zeta, max_depth=max_depth, eta_smooth=eta_smooth,
+                    adaptive_far=adaptive, small_field=rho)
+    check_plan_bit_exact(plan, T)
+    inf = plan.info()
+    L = T.L
+    say("  L=%d boxes X %s Y %s near_L=%d far %s small %s" % (L, list(inf.nboxes)[:L + 1],
+                                                            list(plan.source_info().nboxes)[:L + 1], inf.near_pairs[L],
+                                                            list(inf.far_pairs)[1:L + 1], list(inf.small_pairs)[1:L + 1]))
+    assert (inf.near_point_pairs + sum(inf.far_point_pairs[l] + inf.small_point_pairs[l] for l in range(L + 1))) == nx * ny
+    y = plan.kmvm(bd)
+    torch.cuda.synchronize()
+    yo = T.apply(b.numpy(), g32(gamma), p, adaptive=adaptive)
+    e = rel(y.cpu().numpy(), yo)
+    say("  rel err vs CPU F3M %.3e" % e)
+    assert e <= TOL_F3M
+    assert torch.equal(y, plan.kmvm(bd))          # a second product on the same plan gives the same bits
+
+
+@pytest.mark.parametrize("D,gamma", [(2, 0.4), (3, 1.0), (6, 2.0)])
+def test_xy_all_near_equals_direct(D, gamma):
+    say("f3m xy force_all_near D=%d" % D)
+    X, Y, b = two_sets(5_000, 4_000, D, "uniform", "normal", 0.5, 0.4, 500 + D)
+    Xd, Yd, bd = [a.to(DEV) for a in (X, Y, b)]
+    plan = f3m.Plan(Xd, gamma, 3, 2.0, Y=Yd, leaf_max=32, max_depth=3, force_all_near=True)
+    y = plan.kmvm(bd)
+    yd = f3m.direct_kmvm_xy(Xd, Yd, bd, gamma)
+    torch.cuda.synchronize()
+    want = oracle.rows_xy(X.numpy(), Y.numpy(), b.numpy(), g32(gamma))
+    assert rel(y.cpu().numpy(), want) <= TOL_F3M and rel(yd.cpu().numpy(), want) <= TOL_F3M
+
+
+def test_xy_with_the_same_set_twice_equals_the_one_set_plan():
+    X, b, cfg = inputs.make_config(1)
+    say("f3m xy with Y = X, configuration 1")
+    Xd, bd = X.to(DEV), b.to(DEV)
+    one = f3m.Plan(Xd, cfg["lengthscale"], cfg["p"], cfg["theta"])
+    two = f3m.Plan(Xd, cfg["lengthscale"], cfg["p"], cfg["theta"], Y=Xd.clone())
+    i1, i2 = one.info(), two.info()
+    assert i1.depth == i2.depth
+    assert np.array_equal(one.perm(), two.perm()) and np.array_equal(one.perm(), two.source_perm())
+    for l in range(i1.depth + 1):
+        for kind in (0, 1):
+            a, c = one.interactions(l, kind), two.interactions(l, kind)
+            assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
+    y1, y2 = one.kmvm(bd), two.kmvm(bd)
+    torch.cuda.synchronize()
+    assert rel(y2.cpu().numpy(), y1.cpu().numpy()) <= 2e-6     # other kernels, the same sums
+
+
+def test_xy_edge_cases():
+    say("f3m xy edge cases")
+    X, Y, b = two_sets(300, 200, 3, "uniform", "normal", 0.5, 0.5, 600)
+    Xd, Yd, bd = [a.to(DEV) for a in (X, Y, b)]
+    # no sources: the product is zero
+    plan = f3m.Plan(Xd, 1.0, 4, 2.0, Y=Yd[:0])
+    y = plan.kmvm(bd[:0], y=torch.full((300,), 7.0, device=DEV))
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(y).item() == 0
+    assert f3m.direct_kmvm_xy(Xd, Yd[:0], bd[:0], 1.0, y=torch.full((300,), 7.0, device=DEV)).abs().max().item() == 0
+    # no targets: nothing to write
+    plan = f3m.Plan(Xd[:0], 1.0, 4, 2.0, Y=Yd)
+    assert plan.kmvm(bd).numel() == 0
+    # one target, one source
+    plan = f3m.Plan(Xd[:1], 1.0, 4, 2.0, Y=Yd[:1])
+    y = plan.kmvm(bd[:1])
+    torch.cuda.synchronize()
+    want = oracle.rows_xy(X[:1].numpy(), Y[:1].numpy(), b[:1].numpy(), 1.0)
+    assert abs(y.item() - want[0]) <= 1e-6 * max(1.0, abs(want[0]))
+    # all sources at one point, all targets at one point (both cubes have edge 0): depth 0, exact
+    Xc, Yc = Xd[:1].repeat(100, 1).contiguous(), Yd[:1].repeat(70, 1).contiguous()
+    plan = f3m.Plan(Xc, 1.0, 4, 2.0, Y=Yc, leaf_max=8)
+    assert plan.info().depth == 0
+    y = plan.kmvm(bd[:70].contiguous())
+    torch.cuda.synchronize()
+    want = oracle.rows_xy(Xc.cpu().numpy(), Yc.cpu().numpy(), b[:70].numpy(), 1.0)
+    assert rel(y.cpu().numpy(), want) <= TOL_F3M
+    # a NaN among the sources is refused
+    Ybad = Yd.clone()
+    Ybad[17, 1] = float("nan")
+    with pytest.raises(f3m.F3MError) as ei:
+        f3m.Plan(Xd, 1.0, 4, 2.0, Y=Ybad)
+    assert ei.value.status == 2
+    # column counts must agree
+    with pytest.raises(ValueError):
+        f3m.Plan(Xd, 1.0, 4, 2.0, Y=Yd[:, :2].contiguous())
