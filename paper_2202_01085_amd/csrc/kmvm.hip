@@ -1290,6 +1290,120 @@ __global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict_
     }
 }
 
+// The same for boxes with few fibres (r/p <= 32, e.g. D = 3 with 4 nodes per dimension: 16): one
+// fibre per lane would leave most of the wavefront idle, so the lanes form 64 / (r/p) groups and
+// every group takes its own far pair of the row (pairs e0 + g, e0 + g + groups, ...), with its
+// own LDS buffer and its own accumulators.  The factor matrices then differ between the groups,
+// so the table of the depth is staged in LDS once per target.  At the end the accumulators of the
+// groups are added in a fixed order.
+template <int PN>
+__global__ __launch_bounds__(64) void m2l_kron_small_kernel(const int32_t *__restrict__ cellT,
+                                                            const int32_t *__restrict__ cellS,
+                                                            const uint64_t *__restrict__ far_ptr,
+                                                            const uint32_t *__restrict__ far_col, int64_t nb, int D,
+                                                            int r, const float *__restrict__ G, KronShape S,
+                                                            const float *__restrict__ W, float *__restrict__ V) {
+    extern __shared__ float lds[];   // [groups][r] buffers, then the table [D][no][PN][PN]
+    const int64_t a = block_index();
+    if (a >= nb) return;
+    const uint64_t e0 = far_ptr[a], e1 = far_ptr[a + 1];
+    if (e0 == e1) return;
+    const int lane = threadIdx.x;
+    const int nfib = r / PN;
+    const int ngrp = 64 / nfib;
+    const int g = lane / nfib, f = lane - g * nfib;
+    const bool act = g < ngrp;
+    float *buf = lds + (act ? g : 0) * r;
+    float *tab = lds + ngrp * r;
+    const int tab_n = D * S.no * PN * PN;
+    for (int i = lane; i < tab_n; i += 64) tab[i] = G[i];
+    float acc[PN];
+#pragma unroll
+    for (int i = 0; i < PN; ++i) acc[i] = 0.f;
+    int ca[F3M_MAX_DIM];
+    for (int d = 0; d < D; ++d) ca[d] = cellT[a * D + d];
+    auto factor = [&](int d, int cs) {
+        int k = cs - ca[d] - S.omin[d];
+        k = k < 0 ? 0 : (k >= S.no ? S.no - 1 : k);
+        return tab + (d * S.no + k) * (PN * PN);
+    };
+    auto apply = [&](const float *gm, const float (&in)[PN], float (&out)[PN]) {
+#pragma unroll
+        for (int i = 0; i < PN; ++i) {
+            float t = 0.f;
+#pragma unroll
+            for (int j = 0; j < PN; ++j) t = fmaf(gm[i * PN + j], in[j], t);
+            out[i] = t;
+        }
+    };
+    for (uint64_t e = e0; e < e1; e += (uint64_t)ngrp) {   // wave-uniform trip count
+        const bool live = act && e + (uint64_t)g < e1;
+        const uint32_t q = far_col[live ? e + (uint64_t)g : e];
+        const float *Wq = W + (int64_t)q * r;
+        __syncthreads();   // the table is in place; the last pass of the previous round has read the buffers
+        if (live) {
+            float in[PN], out[PN];
+#pragma unroll
+            for (int j = 0; j < PN; ++j) in[j] = Wq[f * PN + j];
+            apply(factor(0, cellS[(int64_t)q * D]), in, out);
+            if (D == 1) {
+#pragma unroll
+                for (int i = 0; i < PN; ++i) acc[i] += out[i];
+            } else {
+#pragma unroll
+                for (int i = 0; i < PN; ++i) buf[f + i * nfib] = out[i];
+            }
+        }
+        int stride = 1;   // of dimension d in the LDS layout (dimensions 1..D-1 fastest first, then 0)
+        for (int d = 1; d < D; ++d) {
+            __syncthreads();
+            if (live) {
+                const int hi = (int)(((float)f + 0.5f) * (1.f / (float)stride));   // f / stride
+                const int base = hi * stride * PN + (f - hi * stride);
+                float in[PN], out[PN];
+#pragma unroll
+                for (int j = 0; j < PN; ++j) in[j] = buf[base + j * stride];
+                apply(factor(d, cellS[(int64_t)q * D + d]), in, out);
+                if (d == D - 1) {
+#pragma unroll
+                    for (int i = 0; i < PN; ++i) acc[i] += out[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < PN; ++i) buf[base + i * stride] = out[i];
+                }
+            }
+            stride *= PN;
+        }
+    }
+    // accumulators of every group to its buffer at the flat node index i = sum_d i_d p^d, then the
+    // groups are added in ascending order
+    __syncthreads();
+    if (act) {
+        int stride = 1;
+        for (int d = 2; d < D; ++d) stride *= PN;
+        const int hi = (int)(((float)f + 0.5f) * (1.f / (float)stride));
+#pragma unroll
+        for (int i = 0; i < PN; ++i) {
+            int flat;
+            if (D == 1) {
+                flat = i;
+            } else {
+                const int idx = hi * stride * PN + (f - hi * stride) + i * stride;   // LDS layout index
+                const int i0 = idx / nfib;
+                flat = i0 + PN * (idx - i0 * nfib);
+            }
+            buf[flat] = acc[i];
+        }
+    }
+    __syncthreads();
+    float *Va = V + a * r;
+    for (int i = lane; i < r; i += 64) {
+        float sum = 0.f;
+        for (int gg = 0; gg < ngrp; ++gg) sum += lds[gg * r + i];
+        Va[i] = sum;
+    }
+}
+
 // Offsets (source cell - target cell) a far pair of a depth can have in dimension d.  The parents
 // of a far pair are near, |O + U| < theta in every dimension (U the shift at the parents' depth),
 // and a child centre lies half a child edge from its parent's: |o + u| < 2 theta + 1.  Depth 1
@@ -1468,19 +1582,22 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                     Ys, P.bs.p, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
                     P.W.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
-            if (sv.nchunks > sv.nb)
+            if (sv.max_box > P2M_CHUNK)   // some box has several chunks
                 reduce_partials(P, sv, r, P.W.p, st);
             F3M_HIP(hipGetLastError());
         }
         F3M_HIP(hipEventRecord(ev[1], st));
         F3M_HIP(hipEventRecord(ev[2], st));
         if (!(lv.far_implicit && run_m2l_stencil(P, l, P.W.p, P.V.p, st))) {
-            const size_t sh = (size_t)r * sizeof(float);
+            const KronShape KS = kron_shape(P, l);
+            const int nfib = r / p;
+            const bool small = nfib <= 32;   // several far pairs per wavefront
+            const size_t sh = small ? (size_t)((64 / nfib) * r + D * KS.no * p * p) * sizeof(float) : (size_t)r * sizeof(float);
             auto launch = [&](auto kern) {
                 kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
-                                                            lv.gtab.p, kron_shape(P, l), P.W.p, P.V.p);
+                                                            lv.gtab.p, KS, P.W.p, P.V.p);
             };
-            switch (p) {
+            switch (small ? -p : p) {
                 case 2: launch(m2l_kron_kernel<2>); break;
                 case 3: launch(m2l_kron_kernel<3>); break;
                 case 4: launch(m2l_kron_kernel<4>); break;
@@ -1488,6 +1605,13 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                 case 6: launch(m2l_kron_kernel<6>); break;
                 case 7: launch(m2l_kron_kernel<7>); break;
                 case 8: launch(m2l_kron_kernel<8>); break;
+                case -2: launch(m2l_kron_small_kernel<2>); break;
+                case -3: launch(m2l_kron_small_kernel<3>); break;
+                case -4: launch(m2l_kron_small_kernel<4>); break;
+                case -5: launch(m2l_kron_small_kernel<5>); break;
+                case -6: launch(m2l_kron_small_kernel<6>); break;
+                case -7: launch(m2l_kron_small_kernel<7>); break;
+                case -8: launch(m2l_kron_small_kernel<8>); break;
                 default: fail(F3M_ERR_UNSUPPORTED, "interp_nodes must be in [2,8]");
             }
             F3M_HIP(hipGetLastError());
@@ -1521,7 +1645,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
                                                                   lf.chunk_first.p, lf.nchunks, make_centre(P, L),
                                                                   lf.Wl.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
-            if (lf.nchunks > lf.nb)
+            if (lf.max_box > P2M_CHUNK)   // some box has several chunks
                 reduce_partials(P, lf, r, lf.Wl.p, st);
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipEventRecord(ev[1], st));

@@ -565,12 +565,29 @@ struct ChunkCountIfIn {
     }
 };
 
+// runs of at most `chunk` points inside the boxes that carry a flag
+struct ChunkCountFlagIn {
+    const uint32_t *start;
+    const uint32_t *flag;
+    uint32_t chunk;
+    __device__ uint64_t operator()(int64_t a) const { return flag[a] ? (start[a + 1] - start[a] + chunk - 1) / chunk : 0; }
+};
+
+// flag[c] = 1 for every column c of a list (equal values from several threads: plain vector stores)
+__global__ __launch_bounds__(256) void mark_cols_kernel(const uint32_t *__restrict__ cols, int64_t count,
+                                                        uint32_t *__restrict__ flag) {
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256)
+        flag[cols[e]] = 1u;
+}
+
 static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevBuf<uint32_t> &first,
                          DevBuf<uint32_t> &cbox, int64_t &nchunks, int64_t *tally, hipStream_t st,
-                         const uint64_t *only_rows = nullptr) {
+                         const uint64_t *only_rows = nullptr, const uint32_t *only_flagged = nullptr) {
     first.alloc((size_t)nb + 1, tally);
     uint64_t total = 0;
-    if (only_rows)
+    if (only_flagged)
+        exclusive_scan(ChunkCountFlagIn{start, only_flagged, chunk}, nb, U32Out{first.p}, &total, st);
+    else if (only_rows)
         exclusive_scan(ChunkCountIfIn{start, only_rows, chunk}, nb, U32Out{first.p}, &total, st);
     else
         exclusive_scan(ChunkCountIn{start, chunk}, nb, U32Out{first.p}, &total, st);
@@ -878,7 +895,19 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         // runs of points for the L2P (targets) and the P2M (sources: the same runs for one point set)
         build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
         f3m_level &sv = P.slev(k);
-        if (P.src) build_chunks(sv.start.p, sv.nb, P2M_CHUNK, sv.chunk_first, sv.chunk_box, sv.nchunks, tally, st);
+        if (P.src) {
+            // Only the source boxes that occur in a far row of this depth need node weights (the two sets
+            // may overlap in a small part of the sources' cube only).
+            DevBuf<uint32_t> used;
+            used.alloc((size_t)sv.nb);
+            F3M_HIP(hipMemsetAsync(used.p, 0, (size_t)sv.nb * sizeof(uint32_t), st));
+            mark_cols_kernel<<<dim3((unsigned)std::min<int64_t>(cdiv(lv.far_sz, 256), 1 << 20)), dim3(256), 0, st>>>(
+                lv.far_col.p, lv.far_sz, used.p);
+            F3M_HIP(hipGetLastError());
+            build_chunks(sv.start.p, sv.nb, P2M_CHUNK, sv.chunk_first, sv.chunk_box, sv.nchunks, tally, st, nullptr,
+                         used.p);
+            F3M_HIP(hipStreamSynchronize(st));   // `used` is released on leaving the scope
+        }
         if (sv.max_box > (int64_t)P2M_CHUNK * P2M_SLICE * 2) {
             // a box with more than a thousand chunks: its partial node weights are summed in two stages
             build_chunks(sv.chunk_first.p, sv.nb, P2M_SLICE, sv.slice_first, sv.slice_box, sv.nslices, tally, st);
