@@ -10,6 +10,11 @@ near-field P2P, permutations).  Prints ONE JSON line on stdout.
 The default workload is configuration 5 of the benchmark list: n = 1e9 points,
 D = 3, iid Uniform[0,1]^3, Gaussian lengthscale 1.0, b ~ N(0,1), 4 nodes per
 dimension, far ratio 2.
+
+With --xy the step is the two-set product v = K(X, Y) b (f3m_plan_xy + f3m_kmvm) on the
+stand-in for the paper's two-set experiment (Sec. 5 "KMVM experiments": uniformly
+distributed X, normally distributed Y): X ~ Uniform[0,1]^3, Y ~ N(0, I_3), --n points in
+EACH set (default 5e8, the largest size the paper runs in 3-D), same kernel and nodes.
 """
 import argparse
 import json
@@ -45,12 +50,30 @@ def cpu_baseline(cfg, n_sample):
                       % (n_sample, T.L, dt)}
 
 
+def cpu_baseline_xy(cfg, n_sample):
+    """The two-set CPU oracle on a bounded sample of the same two distributions."""
+    import oracle
+    from paper_2202_01085_amd import inputs
+    X = inputs.points_uniform(n_sample, 3, 1101).numpy()
+    Y = inputs.points_normal(n_sample, 3, 1102).numpy()
+    b = inputs.rhs_normal(n_sample, 1103).numpy()
+    t0 = time.time()
+    T = oracle.Tree2(X, Y, theta=cfg["theta"], zeta=128)
+    T.apply(b, cfg["lengthscale"], cfg["p"])
+    dt = time.time() - t0
+    return {"value": 2 * n_sample / dt, "unit": "points/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "two-set oracle F3M (trees + product, fp64) on %d + %d points of the same distributions, "
+                      "depth %d, %.1f s" % (n_sample, n_sample, T.L, dt)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--n", type=float, default=1e9, help="points (default: configuration 5, 1e9)")
+    ap.add_argument("--n", type=float, default=None, help="points (default: configuration 5, 1e9; with --xy: "
+                                                           "points per set, default 5e8)")
+    ap.add_argument("--xy", action="store_true", help="two point sets: X uniform (targets), Y normal (sources)")
     ap.add_argument("--rows", type=int, default=10000, help="sampled rows for the error against the exact product")
     ap.add_argument("--cpu-sample", type=int, default=400000, help="points of the CPU oracle sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -72,13 +95,20 @@ def main():
     import torch
     from paper_2202_01085_amd import f3m, inputs
 
-    n = int(args.n)
+    n = int(args.n if args.n is not None else (5e8 if args.xy else 1e9))
     k = 5 if n >= 500_000_000 else 3
     cfg = dict(inputs.CONFIGS[k], k=k)
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    log("generating n=%d %s points on the device ..." % (n, cfg["dist"]))
-    X, b, _ = inputs.make_config(k, n=n, device=dev)
+    Y = None
+    if args.xy:
+        log("generating %d uniform targets and %d normal sources on the device ..." % (n, n))
+        X = inputs.points_uniform(n, 3, 1101, device=dev)
+        Y = inputs.points_normal(n, 3, 1102, device=dev)
+        b = inputs.rhs_normal(n, 1103, device=dev)
+    else:
+        log("generating n=%d %s points on the device ..." % (n, cfg["dist"]))
+        X, b, _ = inputs.make_config(k, n=n, device=dev)
     y = torch.empty_like(b)
     torch.cuda.synchronize()
     if args.copy_calibration:
@@ -90,7 +120,7 @@ def main():
 
     def step():
         plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"], eta_smooth=args.eta_smooth,
-                        adaptive_far=args.adaptive_far)
+                        adaptive_far=args.adaptive_far, Y=Y)
         plan.kmvm(b, y)
         return plan
 
@@ -133,12 +163,12 @@ def main():
         # vector ALU.  `achieved` counts the multiply-adds it executes; `algorithmic_tflops` the dense equivalent.
         t = m2l_ms * 1e-3
         nb_L = int(inf.nboxes[L])
-        if D == 3 and cfg["p"] == 4 and cfg["theta"] == 2.0:
+        if D == 3 and cfg["p"] == 4 and cfg["theta"] == 2.0 and not args.xy:
             executed = 2.0 * 231 * 256 * nb_L
             kernel = "m2l_stencil_kernel"
         else:
             executed = 2.0 * D * r * cfg["p"] * far_L
-            kernel = "m2l_kron_kernel"
+            kernel = "m2l_kron_small_kernel" if r // cfg["p"] <= 32 else "m2l_kron_kernel"
         ach = executed / t / 1e12
         rooflines["m2l"] = {"kernel": "%s, leaf depth %d, %d far pairs, %d target boxes" % (kernel, L, far_L, nb_L),
                             "bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
@@ -163,7 +193,7 @@ def main():
                             "peak_note": "256 CU x 64 lanes x 2.4 GHz x 2 flop (FMA) = 78.6 TFLOP/s; the published "
                                          "157.3 needs packed FP32, which this build does not generate"}
     traffic_file = args.traffic
-    if traffic_file is None and n == 1_000_000_000:
+    if traffic_file is None and n == 1_000_000_000 and not args.xy:
         # HBM bytes per launch measured with rocprofv3 --pmc on this workload (profiles/hbm_traffic_config5_n1e9.md)
         cand = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_config5_n1e9.json")
         traffic_file = cand if os.path.exists(cand) else None
@@ -181,7 +211,10 @@ def main():
     # error against the exact product on sampled rows (fp64 row kernel, pinned to the oracle in the tests)
     rows = inputs.sample_rows(n, args.rows, 3000 + k)
     t1 = time.perf_counter()
-    y64 = f3m.direct_kmvm_rows_f64(X, b, cfg["lengthscale"], rows)
+    if args.xy:
+        y64 = f3m.direct_kmvm_xy_rows_f64(X, Y, b, cfg["lengthscale"], rows)
+    else:
+        y64 = f3m.direct_kmvm_rows_f64(X, b, cfg["lengthscale"], rows)
     torch.cuda.synchronize()
     t_rows = time.perf_counter() - t1
     yr = y[rows.to(dev)].double()
@@ -190,13 +223,16 @@ def main():
 
     out = {
         "metric": "full KMVM throughput (plan + product), F3M",
-        "value": n / (ms_per_step * 1e-3),
+        "value": (2 * n if args.xy else n) / (ms_per_step * 1e-3),
         "unit": "points/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config %d: n=%d D=%d %s, Gaussian lengthscale %g, b~N(0,1), %d nodes/dim, far ratio %g"
+        "config": {"workload": ("two sets: %d uniform targets x %d normal sources, D=3, Gaussian lengthscale %g, b~N(0,1), "
+                                "%d nodes/dim, far ratio %g (value counts the points of both sets)"
+                                % (n, n, cfg["lengthscale"], cfg["p"], cfg["theta"])) if args.xy else
+                               "config %d: n=%d D=%d %s, Gaussian lengthscale %g, b~N(0,1), %d nodes/dim, far ratio %g"
                                % (k, n, cfg["D"], cfg["dist"], cfg["lengthscale"], cfg["p"], cfg["theta"]),
                    "depth": L, "leaf_max": 128, "boxes_leaf": int(inf.nboxes[L]), "near_pairs_leaf": int(inf.near_pairs[L]),
                    "far_pairs_leaf": far_L, "device_bytes": int(inf.device_bytes),
@@ -208,12 +244,14 @@ def main():
         "level_ms": {str(l): {"p2m": v[0], "m2l": v[1], "l2p": v[2]} for l, v in level_ms.items()},
         "roofline": roof,
         "rooflines_all": rooflines,
-        "paper_context": "paper: 125.9 s (r=64) and 174.0+-76.6 s (mean over data sets) for n=1e9, D=3 on one V100-32GB",
+        "paper_context": ("paper: 74.9+-28.5 s mean over its data sets at n=5e8, D=3 on one V100-32GB (the uniform-and-normal "
+                          "pair is one of them, run up to n=5e8)") if args.xy else
+                         "paper: 125.9 s (r=64) and 174.0+-76.6 s (mean over data sets) for n=1e9, D=3 on one V100-32GB",
     }
     plan.close()
-    del X, y
+    del X, Y, y
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_sample)
+        out["cpu_baseline"] = cpu_baseline_xy(cfg, args.cpu_sample // 2) if args.xy else cpu_baseline(cfg, args.cpu_sample)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)
