@@ -103,23 +103,30 @@ __global__ __launch_bounds__(64) void p2p_kernel(const float *__restrict__ Xt, c
     float xi[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) xi[d] = active ? Xt[(int64_t)k * D + d] : 0.f;
-    float acc = 0.f;
+    double acc = 0.0;   // the runs are added in fp64 (one addition per 32 sources)
     const uint64_t e1 = near_ptr[a + 1];
     for (uint64_t e = near_ptr[a]; e < e1; ++e) {
         const uint32_t q = near_col[e];
         const uint32_t j1 = start[q + 1];
+        // runs of 32 sources are summed on their own and then added in fp64: a long row of terms of
+        // mixed sign loses fewer bits than with one running fp32 sum
+        for (uint32_t j0 = start[q]; j0 < j1; j0 += 32) {
+            const uint32_t je = min(j0 + 32u, j1);
+            float run = 0.f;
 #pragma unroll 4
-        for (uint32_t j = start[q]; j < j1; ++j) {
-            float r2 = 0.f;
+            for (uint32_t j = j0; j < je; ++j) {
+                float r2 = 0.f;
 #pragma unroll
-            for (int d = 0; d < D; ++d) {
-                float diff = Xs[(int64_t)j * D + d] - xi[d];
-                r2 = fmaf(diff, diff, r2);
+                for (int d = 0; d < D; ++d) {
+                    float diff = Xs[(int64_t)j * D + d] - xi[d];
+                    r2 = fmaf(diff, diff, r2);
+                }
+                run = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), bs[j], run);
             }
-            acc = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), bs[j], acc);
+            acc += (double)run;
         }
     }
-    if (active) ys[k] = accumulate ? ys[k] + acc : acc;
+    if (active) ys[k] = accumulate ? ys[k] + (float)acc : (float)acc;
 }
 
 // ------------------------------------------------------------------------------------
@@ -637,18 +644,23 @@ __global__ __launch_bounds__(64) void direct_kernel(const float *__restrict__ X,
     float xi[D];
 #pragma unroll
     for (int d = 0; d < D; ++d) xi[d] = active ? X[i * D + d] : 0.f;
-    float acc = 0.f;
+    double acc = 0.0;
+    for (int64_t j0 = 0; j0 < n; j0 += 32) {   // runs of 32 sources summed on their own, then added in fp64
+        const int64_t je = min(j0 + 32, n);
+        float run = 0.f;
 #pragma unroll 4
-    for (int64_t j = 0; j < n; ++j) {
-        float r2 = 0.f;
+        for (int64_t j = j0; j < je; ++j) {
+            float r2 = 0.f;
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            float diff = Y[j * D + d] - xi[d];
-            r2 = fmaf(diff, diff, r2);
+            for (int d = 0; d < D; ++d) {
+                float diff = Y[j * D + d] - xi[d];
+                r2 = fmaf(diff, diff, r2);
+            }
+            run = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), b[j], run);
         }
-        acc = fmaf(__builtin_amdgcn_exp2f(r2 * nc2), b[j], acc);
+        acc += (double)run;
     }
-    if (active) y[i] = acc;
+    if (active) y[i] = (float)acc;
 }
 
 // exact rows in fp64: lane = row, blockIdx.y = slice of the sources; partial sums per slice
