@@ -320,3 +320,43 @@ def f3m_xy(X, Y, b, gamma, p, theta=2.0, zeta=128, max_depth=0, force_all_near=F
     """CPU F3M product K(X, Y) b (fp64), original order of X."""
     return Tree2(X, Y, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, small_field).apply(
         b, gamma, p, adaptive=adaptive)
+
+
+# ----------------------------------------------------------------------------
+# kernel ridge regression by conjugate gradients (Sec. 5 "Kernel Ridge Regression experiment":
+# alpha = (k(X,X) + lambda I)^{-1} b, with F3M as the matrix-vector product of the solver)
+# ----------------------------------------------------------------------------
+def apply64(T, v, gamma, p, **kw):
+    """T.apply for an fp64 vector: the C routine takes fp32 weights, and the product is linear, so
+    v = hi + lo with hi = fl32(v), lo = fl32(v - hi) gives it to about 2^-48."""
+    v = np.asarray(v, dtype=np.float64)
+    hi = v.astype(np.float32)
+    lo = (v - hi.astype(np.float64)).astype(np.float32)
+    return T.apply(hi, gamma, p, **kw) + T.apply(lo, gamma, p, **kw)
+
+
+def cg_solve(T, b, lam, gamma, p, tol=1e-6, max_iter=100, **kw):
+    """Textbook conjugate gradients (Hestenes-Stiefel) for (K + lam I) x = b, K the F3M operator of the
+    tree T, from x_0 = 0, in fp64.  Stops after the first iteration with |r_k| <= tol |b|, or after
+    max_iter iterations.  Returns (x, history) with history[k] = |r_k| / |b|, k = 0..iterations."""
+    b = np.asarray(b, dtype=np.float64)
+    x = np.zeros_like(b)
+    r = b.copy()
+    d = r.copy()
+    rs = float(r @ r)
+    nb = np.sqrt(rs)
+    hist = [1.0 if nb > 0 else 0.0]
+    if nb == 0:
+        return x, np.array(hist)
+    for _ in range(max_iter):
+        Ad = apply64(T, d, gamma, p, **kw) + lam * d
+        alpha = rs / float(d @ Ad)
+        x = x + alpha * d
+        r = r - alpha * Ad
+        rs_new = float(r @ r)
+        hist.append(np.sqrt(rs_new) / nb)
+        if np.sqrt(rs_new) <= tol * nb:
+            break
+        d = r + (rs_new / rs) * d
+        rs = rs_new
+    return x, np.array(hist)
