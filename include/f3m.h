@@ -43,7 +43,8 @@ typedef enum {
     F3M_ERR_NONFINITE = 2,   /* NaN or Inf among the coordinates */
     F3M_ERR_UNSUPPORTED = 3, /* n >= 2^31, or interp_nodes^D above the node cap (4096) */
     F3M_ERR_OOM = 4,         /* a device allocation failed */
-    F3M_ERR_HIP = 5          /* any other HIP runtime error (message in f3m_last_error) */
+    F3M_ERR_HIP = 5,         /* any other HIP runtime error (message in f3m_last_error) */
+    F3M_ERR_BREAKDOWN = 6    /* f3m_cg_solve: a search direction with p.(K + lambda I)p <= 0 */
 } f3m_status;
 
 typedef struct {
@@ -200,6 +201,25 @@ f3m_status direct_kmvm_xy(const float *X, int64_t nx, const float *Y, int64_t ny
 f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, int64_t ny, int D,
                                    float lengthscale, const float *b, const int64_t *rows, int64_t m,
                                    double *y64, void *stream);
+
+/*
+ * f3m_cg_solve - kernel ridge regression x = (K(X,X) + lambda I)^{-1} b by conjugate gradients, with
+ * the plan's F3M product as the matrix-vector product of the solver (Sec. 5 "Kernel Ridge Regression
+ * experiment").  Hestenes-Stiefel recurrences from x_0 = 0 in fp32 vectors with fp64 inner products;
+ * stops after the first iteration k with |r_k| <= tol |b| or after max_iter iterations.
+ *   plan          a one-set plan (f3m_plan / f3m_plan_ex); a two-set plan is refused (not square)
+ *   lambda        ridge parameter, finite and >= 0
+ *   b, x          device fp32[n]; x is overwritten (no initial guess is read); they must not overlap
+ *   max_iter      >= 0;  tol >= 0 (0: run max_iter iterations)
+ *   iters_host    receives the number of iterations made (may be NULL)
+ *   history_host  max_iter + 1 floats, history[k] = |r_k| / |b| from the recurrence, k = 0..iterations
+ *                 (may be NULL)
+ * Allocates three work vectors of n floats for the duration of the call, runs on `stream` and
+ * returns when the solve has finished.  F3M_ERR_BREAKDOWN if a search direction p has
+ * p.(K + lambda I)p <= 0 (the approximate operator need not be positive definite for tiny lambda).
+ */
+f3m_status f3m_cg_solve(f3m_plan_t *plan, float lambda, const float *b, float *x, int max_iter, float tol,
+                        int *iters_host, float *history_host, void *stream);
 
 /* Frees the plan and its device memory (NULL is allowed). */
 void f3m_destroy(f3m_plan_t *plan);

@@ -190,6 +190,20 @@ f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, i
     return guarded([&] { f3m::run_direct_rows_f64(X, Y, ny, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
 }
 
+f3m_status f3m_cg_solve(f3m_plan_t *plan, float lambda, const float *b, float *x, int max_iter, float tol,
+                        int *iters_host, float *history_host, void *stream) {
+    if (iters_host) *iters_host = 0;
+    if (!plan) return set_error(F3M_ERR_INVALID_ARG, "plan is null");
+    if (plan->src) return set_error(F3M_ERR_INVALID_ARG, "f3m_cg_solve needs a one-set plan (a square operator)");
+    if (!(std::isfinite(lambda) && lambda >= 0.f)) return set_error(F3M_ERR_INVALID_ARG, "lambda must be finite and >= 0");
+    if (max_iter < 0) return set_error(F3M_ERR_INVALID_ARG, "max_iter must be >= 0");
+    if (!(std::isfinite(tol) && tol >= 0.f)) return set_error(F3M_ERR_INVALID_ARG, "tol must be finite and >= 0");
+    if (plan->n == 0) return F3M_OK;
+    if (!b || !x) return set_error(F3M_ERR_INVALID_ARG, "b or x is null");
+    if (b == x) return set_error(F3M_ERR_INVALID_ARG, "b and x must not overlap");
+    return guarded([&] { f3m::run_cg(*plan, lambda, b, x, max_iter, tol, iters_host, history_host, (hipStream_t)stream); });
+}
+
 void f3m_destroy(f3m_plan_t *plan) {
     if (!plan) return;
     (void)hipDeviceSynchronize();

@@ -146,6 +146,9 @@ void run_direct_rows_f64(const float *X, const float *Y, int64_t ny, int D, floa
                          const int64_t *rows, int64_t m, double *y64, hipStream_t st);
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of every far depth
+// solve.hip: conjugate gradients for (K + lambda I) x = b on a one-set plan (synchronises)
+void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter, float tol, int *iters_host,
+            float *history_host, hipStream_t st);
 // m2l.hip
 bool m2l_stencil_applies(const f3m_plan_s &P);                   // D = 3, 4 nodes/dim, far ratio 2
 bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);  // false: does not apply

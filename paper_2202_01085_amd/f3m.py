@@ -17,7 +17,7 @@ MAX_DIM = 7
 MAX_LEVELS = 20
 
 STATUS = {0: "F3M_OK", 1: "F3M_ERR_INVALID_ARG", 2: "F3M_ERR_NONFINITE", 3: "F3M_ERR_UNSUPPORTED",
-          4: "F3M_ERR_OOM", 5: "F3M_ERR_HIP"}
+          4: "F3M_ERR_OOM", 5: "F3M_ERR_HIP", 6: "F3M_ERR_BREAKDOWN"}
 
 
 class F3MError(RuntimeError):
@@ -76,6 +76,8 @@ def lib():
         L.f3m_plan_ex.argtypes = [vp, i64, ci, cf, ci, cf, ctypes.POINTER(Options), vp, ctypes.POINTER(vp)]
         L.f3m_plan_xy.argtypes = [vp, i64, vp, i64, ci, cf, ci, cf, ctypes.POINTER(Options), vp, ctypes.POINTER(vp)]
         L.f3m_kmvm.argtypes = [vp, vp, vp, vp]
+        L.f3m_cg_solve.argtypes = [vp, cf, vp, vp, ci, cf, ctypes.POINTER(ci), vp, vp]
+        L.f3m_cg_solve.restype = ci
         L.direct_kmvm_xy.argtypes = [vp, i64, vp, i64, ci, cf, vp, vp, vp]
         L.direct_kmvm_xy_rows_f64.argtypes = [vp, i64, vp, i64, ci, cf, vp, vp, i64, vp, vp]
         L.f3m_plan_source_info.argtypes = [vp, ctypes.POINTER(SourceInfo)]
@@ -164,6 +166,17 @@ class Plan:
             raise ValueError("b must have one entry per source and y one per target")
         _check(lib().f3m_kmvm(self._h, _dev_f32(b, "b") if self.ns else None, _dev_f32(y, "y"), _stream(stream)))
         return y
+
+    def cg_solve(self, b, lam, tol=1e-6, max_iter=100, x=None, stream=None):
+        """f3m_cg_solve: x = (K + lam I)^{-1} b by conjugate gradients; returns (x, iterations, history)."""
+        if x is None:
+            x = torch.empty_like(b)
+        iters = ctypes.c_int(0)
+        hist = np.zeros(max_iter + 1, dtype=np.float32)
+        _check(lib().f3m_cg_solve(self._h, float(lam), _dev_f32(b, "b") if self.n else None,
+                                  _dev_f32(x, "x") if self.n else None, int(max_iter), float(tol), ctypes.byref(iters),
+                                  _np_ptr(hist), _stream(stream)))
+        return x, int(iters.value), hist[:iters.value + 1]
 
     def source_info(self):
         out = SourceInfo()
