@@ -80,6 +80,10 @@ def main():
     ap.add_argument("--eta-smooth", type=float, default=0.0,
                     help="smooth-field limit of Sec. 4.3 (0 = off, the headline configuration; the paper uses 0.5)")
     ap.add_argument("--adaptive-far", action="store_true", help="adaptive far-field node rule of Sec. 4.3")
+    ap.add_argument("--cg", type=int, default=0,
+                    help="after the timed steps, also time this many conjugate-gradient iterations of f3m_cg_solve "
+                         "(kernel ridge regression, Sec. 5) on the last plan; reported under \"cg\", not part of `value`")
+    ap.add_argument("--cg-lambda", type=float, default=1.0, help="ridge parameter of --cg")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first copy 1 GiB device-to-device with a plain kernel: the reference that the "
                          "FETCH_SIZE / WRITE_SIZE counter readings of a rocprofv3 --pmc run are scaled by")
@@ -248,6 +252,23 @@ def main():
                           "pair is one of them, run up to n=5e8)") if args.xy else
                          "paper: 125.9 s (r=64) and 174.0+-76.6 s (mean over data sets) for n=1e9, D=3 on one V100-32GB",
     }
+    if args.cg > 0 and not args.xy:
+        # the paper's synthetic ridge-regression right-hand side: b = k(X, D) alpha + eps, D = the first 1000 points,
+        # alpha ~ N(0, I), eps ~ N(0, 0.1^2)
+        alpha = inputs.rhs_normal(1000, 4000 + k, device=dev)
+        bk = f3m.direct_kmvm_xy(X, X[:1000].contiguous(), alpha, cfg["lengthscale"])
+        bk += 0.1 * inputs.rhs_normal(n, 5000 + k, device=dev)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        _, iters, hist = plan.cg_solve(bk, args.cg_lambda, tol=0.0, max_iter=args.cg, x=y)
+        torch.cuda.synchronize()
+        t_cg = time.perf_counter() - t1
+        out["cg"] = {"iterations": iters, "ms_per_iteration": t_cg * 1e3 / max(iters, 1), "lambda": args.cg_lambda,
+                     "kmvm_ms": plan.stage_times()["kmvm_total"],
+                     "relative_residuals": [float(v) for v in hist],
+                     "note": "one f3m_kmvm + three fused vector passes + one 40-byte copy per iteration; fp32 products "
+                             "stall the residual near 5e-7 x condition number (no preconditioner here)"}
+        del bk
     plan.close()
     del X, Y, y
     if not args.no_cpu:
