@@ -214,7 +214,7 @@ f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, i
  *   iters_host    receives the number of iterations made (may be NULL)
  *   history_host  max_iter + 1 floats, history[k] = |r_k| / |b| from the recurrence, k = 0..iterations
  *                 (may be NULL)
- * Allocates three work vectors of n floats for the duration of the call, runs on `stream` and
+ * Allocates four work vectors of n floats for the duration of the call, runs on `stream` and
  * returns when the solve has finished.  F3M_ERR_BREAKDOWN if a search direction p has
  * p.(K + lambda I)p <= 0 (the approximate operator need not be positive definite for tiny lambda).
  */

@@ -70,6 +70,16 @@ __global__ __launch_bounds__(256) void scatter_kernel(const float *__restrict__ 
     int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k < n) y[perm[k]] = ys[k] + yn[k];
 }
+// the same two steps for a caller that keeps its vectors in box order (the solver)
+__global__ __launch_bounds__(256) void copy_kernel(const float *__restrict__ b, int64_t n, float *__restrict__ bs) {
+    int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) bs[k] = b[k];
+}
+__global__ __launch_bounds__(256) void add_kernel(const float *__restrict__ ys, const float *__restrict__ yn, int64_t n,
+                                                  float *__restrict__ y) {
+    int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k < n) y[k] = ys[k] + yn[k];
+}
 __global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ p, int64_t n) {
     int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k < n) p[k] = 0.f;
@@ -1486,8 +1496,9 @@ static void reduce_partials(f3m_plan_s &P, f3m_level &lv, int r, float *W, hipSt
     }
 }
 
+// box_order: b and y are in the plan's box order (one-set plans), so both permutations are plain passes
 template <int D>
-static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
+static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order) {
     const int64_t n = P.n;
     const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma));
     const int nev = 4 + 3 * (P.L + 1);
@@ -1501,7 +1512,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     const float *Ys = P.Ys();   // sources in box order (the targets themselves for one point set)
 
     F3M_HIP(hipEventRecord(P.ev[8], st));
-    gather_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.sperm(), P.ns(), P.bs.p);
+    if (box_order)
+        copy_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.ns(), P.bs.p);
+    else
+        gather_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.sperm(), P.ns(), P.bs.p);
     F3M_HIP(hipEventRecord(P.ev[9], st));
     // The near field goes to the plan's second stream (vector ALU work) and overlaps the
     // far field (matrix-core work) on the caller's stream; with no_overlap it runs in line.
@@ -1705,7 +1719,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st) 
     }
     if (P.side) F3M_HIP(hipStreamWaitEvent(st, P.ev_join, 0));
     F3M_HIP(hipEventRecord(P.ev[11], st));
-    if (!permute_out_bucketed(P, y, st)) {
+    if (box_order) {
+        add_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, n, y);
+        F3M_HIP(hipGetLastError());
+    } else if (!permute_out_bucketed(P, y, st)) {
         scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, P.perm.p, n, y);
         F3M_HIP(hipGetLastError());
     }
@@ -1719,15 +1736,15 @@ void run_zero(float *y, int64_t n, hipStream_t st) {
     F3M_HIP(hipGetLastError());
 }
 
-void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st) {
+void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order) {
     switch (P.D) {
-        case 1: run_kmvm_d<1>(P, b, y, st); break;
-        case 2: run_kmvm_d<2>(P, b, y, st); break;
-        case 3: run_kmvm_d<3>(P, b, y, st); break;
-        case 4: run_kmvm_d<4>(P, b, y, st); break;
-        case 5: run_kmvm_d<5>(P, b, y, st); break;
-        case 6: run_kmvm_d<6>(P, b, y, st); break;
-        case 7: run_kmvm_d<7>(P, b, y, st); break;
+        case 1: run_kmvm_d<1>(P, b, y, st, box_order); break;
+        case 2: run_kmvm_d<2>(P, b, y, st, box_order); break;
+        case 3: run_kmvm_d<3>(P, b, y, st, box_order); break;
+        case 4: run_kmvm_d<4>(P, b, y, st, box_order); break;
+        case 5: run_kmvm_d<5>(P, b, y, st, box_order); break;
+        case 6: run_kmvm_d<6>(P, b, y, st, box_order); break;
+        case 7: run_kmvm_d<7>(P, b, y, st, box_order); break;
         default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
     }
 }

@@ -137,7 +137,8 @@ void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far
 bool permute_out_bucketed(f3m_plan_s &P, float *y, hipStream_t st);   // false: n too small, use the plain scatter
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);   // far rows of an implicit depth
 // kmvm.hip
-void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st);
+// box_order: b and y are already in the plan's box order (one-set plans only; used by the solver)
+void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order = false);
 void run_zero(float *y, int64_t n, hipStream_t st);   // y = 0 with a fill kernel
 // exact sums of targets X (nx rows) against sources Y (ny rows, weights b); X == Y for one set
 void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float gamma, const float *b, float *y,

@@ -5,6 +5,9 @@
 // is accumulated in fp64 in a fixed order (grid-stride partial sums, one block adds the partials),
 // and the step lengths stay in device memory, so an iteration costs one f3m_kmvm, three fused
 // vector passes (48 n bytes) and one 40-byte copy to the host for the stopping test.
+// The solve works in the plan's box order: b is permuted once on the way in and x once on the
+// way out (inner products do not depend on the order), so the products inside the loop skip
+// both permutations of f3m_kmvm.
 #include <cmath>
 #include <vector>
 
@@ -31,13 +34,13 @@ __device__ inline void block_sum_to(double v, double *dst) {
     }
 }
 
-// x = 0, r = p = b; partial sums of b . b
-__global__ __launch_bounds__(CG_NT) void cg_init_kernel(const float *__restrict__ b, float *__restrict__ x,
-                                                        float *__restrict__ r, float *__restrict__ p, int64_t n,
-                                                        double *__restrict__ part) {
+// box order: x = 0, r = p = b[perm]; partial sums of b . b
+__global__ __launch_bounds__(CG_NT) void cg_init_kernel(const float *__restrict__ b, const uint32_t *__restrict__ perm,
+                                                        float *__restrict__ x, float *__restrict__ r,
+                                                        float *__restrict__ p, int64_t n, double *__restrict__ part) {
     double s = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * CG_NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * CG_NT) {
-        const float v = b[i];
+        const float v = b[perm[i]];
         x[i] = 0.f;
         r[i] = v;
         p[i] = v;
@@ -83,6 +86,14 @@ __global__ __launch_bounds__(CG_NT) void cg_direction_kernel(float *__restrict__
         p[i] = fmaf(beta, p[i], r[i]);
 }
 
+// the solution back in the caller's order
+__global__ __launch_bounds__(CG_NT) void cg_unpermute_kernel(const float *__restrict__ xs,
+                                                             const uint32_t *__restrict__ perm, int64_t n,
+                                                             float *__restrict__ x) {
+    for (int64_t i = (int64_t)blockIdx.x * CG_NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * CG_NT)
+        x[perm[i]] = xs[i];
+}
+
 // adds the partial sums in ascending order and advances the scalars:
 //   mode 0: rs = sum                      (after cg_init_kernel)
 //   mode 1: pq = sum, alpha = rs / pq     (after cg_shift_dot_kernel)
@@ -112,8 +123,9 @@ __global__ __launch_bounds__(CG_NT) void cg_reduce_kernel(const double *__restri
 void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter, float tol, int *iters_host,
             float *history_host, hipStream_t st) {
     const int64_t n = P.n;
-    DevBuf<float> r, p, q;
+    DevBuf<float> xs, r, p, q;   // box order
     DevBuf<double> part, scal;
+    xs.alloc((size_t)n);
     r.alloc((size_t)n);
     p.alloc((size_t)n);
     q.alloc((size_t)n);
@@ -126,7 +138,7 @@ void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter,
         F3M_HIP(hipMemcpyAsync(h, scal.p, sizeof(h), hipMemcpyDeviceToHost, st));
         F3M_HIP(hipStreamSynchronize(st));
     };
-    cg_init_kernel<<<dim3(blocks), dim3(CG_NT), 0, st>>>(b, x, r.p, p.p, n, part.p);
+    cg_init_kernel<<<dim3(blocks), dim3(CG_NT), 0, st>>>(b, P.perm.p, xs.p, r.p, p.p, n, part.p);
     cg_reduce_kernel<<<dim3(1), dim3(CG_NT), 0, st>>>(part.p, blocks, scal.p, 0);
     F3M_HIP(hipGetLastError());
     fetch();
@@ -135,10 +147,10 @@ void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter,
     if (history_host) history_host[0] = nb > 0.0 ? 1.f : 0.f;
     if (!std::isfinite(nb)) fail(F3M_ERR_NONFINITE, "the right-hand side holds a NaN or an infinity");
     while (nb > 0.0 && it < max_iter) {
-        run_kmvm(P, p.p, q.p, st);
+        run_kmvm(P, p.p, q.p, st, true);
         cg_shift_dot_kernel<<<dim3(blocks), dim3(CG_NT), 0, st>>>(p.p, q.p, lambda, n, part.p);
         cg_reduce_kernel<<<dim3(1), dim3(CG_NT), 0, st>>>(part.p, blocks, scal.p, 1);
-        cg_update_kernel<<<dim3(blocks), dim3(CG_NT), 0, st>>>(x, r.p, p.p, q.p, scal.p, n, part.p);
+        cg_update_kernel<<<dim3(blocks), dim3(CG_NT), 0, st>>>(xs.p, r.p, p.p, q.p, scal.p, n, part.p);
         cg_reduce_kernel<<<dim3(1), dim3(CG_NT), 0, st>>>(part.p, blocks, scal.p, 2);
         F3M_HIP(hipGetLastError());
         fetch();
@@ -156,6 +168,8 @@ void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter,
         F3M_HIP(hipGetLastError());
     }
     if (iters_host) *iters_host = it;
+    cg_unpermute_kernel<<<dim3(blocks), dim3(CG_NT), 0, st>>>(xs.p, P.perm.p, n, x);
+    F3M_HIP(hipGetLastError());
     F3M_HIP(hipStreamSynchronize(st));   // the work vectors are released on return
 }
 
