@@ -378,6 +378,11 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
 // target side half 0 = (hi, lo), half 1 = (hi, 0): hi*hi + hi*lo + lo*hi, the fourth product
 // meets a zero.  The right-hand sides of a step pass through 64 floats of LDS per wavefront
 // (written by the lane that owns the source, read as the 16 values a lane needs per block).
+// SPLIT: a problem with few target tiles and long rows (few targets against many sources) gives
+// every tile to `nsplit` wavefronts; wavefront s of a tile takes the s-th slice (a multiple of 64
+// positions) of the source sequence of every round and writes its sums to part[s][target]; they
+// are added in ascending s by p2p_split_sum_kernel.
+template <bool SPLIT>
 __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict__ Xt,
                                                         const uint32_t *__restrict__ startT,
                                                         const float *__restrict__ Xs, const float *__restrict__ bs,
@@ -388,12 +393,21 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ tile_box,
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
                                                         float g, float inv_l, CentreArg C, float *__restrict__ ys,
-                                                       int accumulate) {
+                                                        int accumulate, int nsplit, int64_t ntargets,
+                                                        float *__restrict__ part) {
     constexpr int D = 3, NC = 4;
     __shared__ __attribute__((aligned(16))) float bbuf[4][64];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int64_t t = block_index() * 4 + wv;
-    if (t >= ntiles) return;
+    int64_t t = block_index() * 4 + wv;
+    int slice = 0;
+    if constexpr (SPLIT) {
+        if (t >= ntiles * nsplit) return;
+        const int64_t tile = t / nsplit;
+        slice = (int)(t - tile * nsplit);
+        t = tile;
+    } else {
+        if (t >= ntiles) return;
+    }
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
     const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * 64u;
     const uint32_t kend = startT[a + 1];
@@ -492,8 +506,15 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             if (lane >= d) cend += up;
         }
         const uint32_t cbeg = cend - slen;
-        const uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // sources of this round
-        if (S == 0) continue;
+        uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // sources of this round
+        uint32_t wbeg = 0;                                   // this wavefront's positions: [wbeg, S)
+        if constexpr (SPLIT) {
+            const uint32_t per = ((S + (uint32_t)nsplit - 1) / (uint32_t)nsplit + 63u) & ~63u;
+            const uint64_t lo = (uint64_t)slice * per;
+            wbeg = lo < S ? (uint32_t)lo : S;
+            S = (uint64_t)wbeg + per < S ? wbeg + per : S;
+        }
+        if (wbeg >= S) continue;
         int r = 0;   // first near box that reaches into the current window (wave-uniform)
         // source index of position w0 + lane (any in-bounds index beyond the end of the sequence)
         auto locate = [&](uint32_t w0) {
@@ -510,12 +531,12 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         };
         float xn[D], bn;
         {
-            const uint32_t src = locate(0);
+            const uint32_t src = locate(wbeg);
 #pragma unroll
             for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
             bn = bs[src];
         }
-        for (uint32_t w0 = 0; w0 < S; w0 += 64) {
+        for (uint32_t w0 = wbeg; w0 < S; w0 += 64) {
             float xc[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) xc[d] = xn[d];
@@ -540,7 +561,21 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     acc1 += __shfl_xor(acc1, 32, 64);
     const float res = kk ? __builtin_amdgcn_exp2f(ni[1]) * acc1 : __builtin_amdgcn_exp2f(ni[0]) * acc0;
     const uint32_t kt = k0 + kk * 32 + nn;
-    if (kt < kend) ys[kt] = accumulate ? ys[kt] + res : res;
+    if constexpr (SPLIT) {
+        if (kt < kend) part[(int64_t)slice * ntargets + kt] = res;
+    } else {
+        if (kt < kend) ys[kt] = accumulate ? ys[kt] + res : res;
+    }
+}
+
+// sums of the slices of a split near-field launch, in ascending slice order
+__global__ __launch_bounds__(256) void p2p_split_sum_kernel(const float *__restrict__ part, int nsplit, int64_t n,
+                                                            float *__restrict__ ys, int accumulate) {
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= n) return;
+    float s = accumulate ? ys[k] : 0.f;
+    for (int j = 0; j < nsplit; ++j) s += part[(int64_t)j * n + k];
+    ys[k] = s;
 }
 
 // Direct sums for the small-field pairs of a depth (Sec. 4.2): both boxes of a pair hold few
@@ -1537,10 +1572,28 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
         // (the root pair of two point sets is near whatever its distance: no bound on the coordinates)
         const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 && !(P.src && l == 0);
-        if (gram && D == 3)
-            p2p_gram3_kernel<<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
+        // few target tiles with long rows: several wavefronts per tile, each on a slice of the sources
+        int nsplit = 1;
+        if (gram && D == 3 && ntiles > 0 && ntiles < 8192 && lv.nb > 0 && P.slev(l).nb > 0) {
+            const double row_sources = (double)(cols == lv.near_col.p ? lv.near_sz : lv.small_sz) / (double)lv.nb *
+                                       ((double)P.ns() / (double)P.slev(l).nb);   // average sources of a tile
+            nsplit = (int)std::min<double>(std::min<double>(64.0, (double)cdiv(16384, ntiles)), row_sources / 2048.0);
+            if (nsplit < 2) nsplit = 1;
+        }
+        if (nsplit > 1) {
+            if (P.p2p_part.count < (size_t)nsplit * (size_t)n) {
+                F3M_HIP(hipStreamSynchronize(sn));
+                P.p2p_part.release();
+                P.p2p_part.alloc((size_t)nsplit * (size_t)n, &P.bytes);
+            }
+            p2p_gram3_kernel<true><<<grid_for(cdiv(ntiles * nsplit, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
-                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate);
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, nsplit, n, P.p2p_part.p);
+            p2p_split_sum_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.p2p_part.p, nsplit, n, P.yn.p, accumulate);
+        } else if (gram && D == 3)
+            p2p_gram3_kernel<false><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, 1, n, nullptr);
         else if (gram)
             p2p_mfma_kernel<D><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,

@@ -79,6 +79,7 @@ struct f3m_plan_s {
     f3m::DevBuf<float> Xs;        // [n*D] coordinates in box order, row-major
     f3m::DevBuf<float> bs, ys;    // [n] right-hand side / far-field result in box order
     f3m::DevBuf<float> yn;        // [n] near-field result in box order
+    f3m::DevBuf<float> p2p_part;  // [slices][n] partial near-field sums when target tiles are split (few targets)
     f3m::DevBuf<float> W, V;      // [max_l nb_l * r] node weights / node potentials of one depth
     f3m::DevBuf<float> Wpart;     // [max_l nchunks_l * r] partial node weights
     f3m::DevBuf<double> Wslice;   // [max_l nslices_l * r] sums of the partial node weights of a slice

@@ -103,6 +103,9 @@ XY_CASES = [
     (20_000, 20_000, 3, "uniform", "normal", 0.5, 0.5, 4, 1.5, 2.0, 16, 0, 0, 0.05, True),   # smooth field + adaptive rule
     (10_000, 10_000, 2, "normal", "normal", 1.0, 0.1, 5, 2.0, 2.0, 8, 0, 12, 0.02, True),
     (3_000, 2_000, 3, "uniform", "normal", 0.05, 30.0, 4, 20.0, 2.0, 16, 0, 0, 0.0, False),  # distant sets: all far at depth 1
+    # few targets against many sources: the near-field tiles are split over several wavefronts
+    (3_000, 400_000, 3, "uniform", "uniform", 1.0, 0.0, 4, 1.0, 2.0, 128, 0, 0, 0.0, False),
+    (777, 123_457, 3, "normal", "normal", 1.0, 0.0, 4, 2.0, 2.0, 128, 0, 0, 0.0, False),
 ]
 
 
