@@ -148,6 +148,21 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
 f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream);
 
 /*
+ * f3m_kmvm_multi - m products with one plan: column j of Y = F3M product of column j of B, the same
+ * result as m calls of f3m_kmvm (to rounding: the order of the near-field sums differs).  A solver
+ * with several right-hand sides or probe vectors is the intended caller.  Where the near field runs on
+ * the 3-D Gram kernel it is evaluated for groups of up to 4 columns at once, which shares its dominant
+ * cost, the exponentials; otherwise the call is a loop of single products.
+ *   B   device fp32, column j at B + j*ldb, one entry per source (ldb >= number of sources)
+ *   Y   device fp32, column j at Y + j*ldy, n entries each (ldy >= n); overwritten; B and Y must not overlap
+ *   m   >= 0
+ * The first call on a plan allocates work space for 4 columns (about 8 floats per point), kept by the plan.
+ * Asynchronous on `stream` after that.
+ */
+f3m_status f3m_kmvm_multi(f3m_plan_t *plan, const float *B, int64_t ldb, float *Y, int64_t ldy, int m,
+                          void *stream);
+
+/*
  * f3m_plan_xy - the plan for v = K(X, Y) b with two point sets: X (nx targets, rows of v) and
  * Y (ny sources, one weight b_j per row), the general form the method is stated in (Sec. 3;
  * Algorithm 1 keeps one treecode per set).

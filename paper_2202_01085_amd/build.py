@@ -37,7 +37,7 @@ def build_lib(verbose=False):
         err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s" % (src, res.stderr))
-        if verbose and err.strip():
+        if err.strip():     # compiler warnings are always shown: they have pointed at real faults
             print(err, flush=True)
         return obj
 

@@ -141,6 +141,20 @@ f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream) {
     return guarded([&] { f3m::run_kmvm(*plan, b, y, (hipStream_t)stream); });
 }
 
+f3m_status f3m_kmvm_multi(f3m_plan_t *plan, const float *B, int64_t ldb, float *Y, int64_t ldy, int m, void *stream) {
+    if (!plan) return set_error(F3M_ERR_INVALID_ARG, "plan is null");
+    if (m < 0) return set_error(F3M_ERR_INVALID_ARG, "m must be >= 0");
+    if (m == 0 || plan->n == 0) return F3M_OK;
+    if (!Y) return set_error(F3M_ERR_INVALID_ARG, "Y is null");
+    if (ldy < plan->n) return set_error(F3M_ERR_INVALID_ARG, "ldy must be at least the number of targets");
+    if (plan->ns() == 0)
+        return guarded([&] { for (int j = 0; j < m; ++j) f3m::run_zero(Y + (int64_t)j * ldy, plan->n, (hipStream_t)stream); });
+    if (!B) return set_error(F3M_ERR_INVALID_ARG, "B is null");
+    if (ldb < plan->ns()) return set_error(F3M_ERR_INVALID_ARG, "ldb must be at least the number of sources");
+    if (B == Y) return set_error(F3M_ERR_INVALID_ARG, "B and Y must not overlap");
+    return guarded([&] { f3m::run_kmvm_multi(*plan, B, ldb, Y, ldy, m, (hipStream_t)stream); });
+}
+
 f3m_status direct_kmvm(const float *X, int64_t n, int D, float lengthscale, const float *b, float *y, void *stream) {
     f3m_status st = check_problem(X, n, D, lengthscale);
     if (st != F3M_OK) return st;

@@ -382,7 +382,15 @@ __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__
 // every tile to `nsplit` wavefronts; wavefront s of a tile takes the s-th slice (a multiple of 64
 // positions) of the source sequence of every round and writes its sums to part[s][target]; they
 // are added in ascending s by p2p_split_sum_kernel.
-template <bool SPLIT>
+// MB > 1: MB right-hand sides at once (MA.bs[j] -> MA.ys[j]); the exponents and the exponentials of a
+// block are formed once and every right-hand side adds its own 16 multiply-adds per lane, so the
+// dominant cost of the near field is shared by the columns.
+struct MultiArg {
+    const float *bs[4];
+    float *ys[4];
+};
+
+template <bool SPLIT, int MB>
 __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict__ Xt,
                                                         const uint32_t *__restrict__ startT,
                                                         const float *__restrict__ Xs, const float *__restrict__ bs,
@@ -394,9 +402,10 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
                                                         float g, float inv_l, CentreArg C, float *__restrict__ ys,
                                                         int accumulate, int nsplit, int64_t ntargets,
-                                                        float *__restrict__ part) {
+                                                        float *__restrict__ part, MultiArg MA) {
     constexpr int D = 3, NC = 4;
-    __shared__ __attribute__((aligned(16))) float bbuf[4][64];
+    static_assert(MB >= 1 && MB <= 4 && !(SPLIT && MB > 1), "unsupported variant");
+    __shared__ __attribute__((aligned(16))) float bbuf[4][MB * 64];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     int64_t t = block_index() * 4 + wv;
     int slice = 0;
@@ -436,6 +445,9 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         Bop[cb] = split_operand<NC, false>(u, 0, kk);
     }
     float acc0 = 0.f, acc1 = 0.f;
+    float accm0[MB], accm1[MB];   // MB > 1: one pair of accumulators per right-hand side
+#pragma unroll
+    for (int j = 0; j < MB; ++j) accm0[j] = accm1[j] = 0.f;
     const float g2l = 2.f * g * inv_l;
     const float nrm = -0.25f / g;
     float *bw = bbuf[wv];
@@ -466,6 +478,33 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     // sequences get merged by the compiler into one that addresses the accumulators through
     // scratch memory.)
     auto block = [&](const h8v &op, int first) {
+        if constexpr (MB > 1) {
+            // the exponentials once, then 16 multiply-adds per right-hand side and column block
+            f16v e0 = {0.f}, e1 = {0.f};
+            e0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[0], e0, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) e0[v] = __builtin_amdgcn_exp2f(e0[v]);
+            if (two) {
+                e1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], e1, 0, 0, 0);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) e1[v] = __builtin_amdgcn_exp2f(e1[v]);
+            }
+#pragma unroll
+            for (int j = 0; j < MB; ++j) {
+                float4 bq[4];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    bq[q4] = *reinterpret_cast<const float4 *>(bw + j * 64 + first + 8 * q4 + 4 * kk);
+                const float *bf = reinterpret_cast<const float *>(bq);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) accm0[j] = fmaf(e0[v], bf[v], accm0[j]);
+                if (two) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) accm1[j] = fmaf(e1[v], bf[v], accm1[j]);
+                }
+            }
+            return;
+        }
         float4 bq[4];
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) bq[q4] = *reinterpret_cast<const float4 *>(bw + first + 8 * q4 + 4 * kk);
@@ -529,33 +568,62 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             }
             return src;
         };
-        float xn[D], bn;
+        float xn[D], bn = 0.f;
+        float bnm[MB];
         {
             const uint32_t src = locate(wbeg);
 #pragma unroll
             for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
-            bn = bs[src];
+            if constexpr (MB > 1) {
+#pragma unroll
+                for (int j = 0; j < MB; ++j) bnm[j] = MA.bs[j][src];
+            } else {
+                bn = bs[src];
+            }
         }
         for (uint32_t w0 = wbeg; w0 < S; w0 += 64) {
             float xc[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) xc[d] = xn[d];
             const float bc = bn;
+            float bcm[MB];
+#pragma unroll
+            for (int j = 0; j < MB; ++j) bcm[j] = bnm[j];
             // the loads of the next step are in flight during this one (the last step reloads a
             // harmless address, so the number of loads in flight is fixed)
             const uint32_t src = w0 + 64 < S ? locate(w0 + 64) : 0u;
 #pragma unroll
             for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
-            bn = bs[src];
+            if constexpr (MB > 1) {
+#pragma unroll
+                for (int j = 0; j < MB; ++j) bnm[j] = MA.bs[j][src];
+            } else {
+                bn = bs[src];
+            }
             const bool live = w0 + lane < S;
             __builtin_amdgcn_wave_barrier();
-            bw[lane] = live ? bc : 0.f;
+            if constexpr (MB > 1) {
+#pragma unroll
+                for (int j = 0; j < MB; ++j) bw[j * 64 + lane] = live ? bcm[j] : 0.f;
+            } else {
+                bw[lane] = live ? bc : 0.f;
+            }
             __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
             h8v opA, opB;
             prepare(live, xc, opA, opB);
             block(opA, 0);
             if (w0 + 32 < S) block(opB, 32);
         }
+    }
+    if constexpr (MB > 1) {
+        const uint32_t kt = k0 + kk * 32 + nn;
+        const float scale = __builtin_amdgcn_exp2f(kk ? ni[1] : ni[0]);
+#pragma unroll
+        for (int j = 0; j < MB; ++j) {
+            const float a0 = accm0[j] + __shfl_xor(accm0[j], 32, 64), a1 = accm1[j] + __shfl_xor(accm1[j], 32, 64);
+            if (kt < kend) MA.ys[j][kt] = scale * (kk ? a1 : a0);
+        }
+        return;
     }
     acc0 += __shfl_xor(acc0, 32, 64);
     acc1 += __shfl_xor(acc1, 32, 64);
@@ -1531,9 +1599,15 @@ static void reduce_partials(f3m_plan_s &P, f3m_level &lv, int r, float *W, hipSt
     }
 }
 
-// box_order: b and y are in the plan's box order (one-set plans), so both permutations are plain passes
+// box_order: b and y are in the plan's box order (one-set plans), so both permutations are plain passes.
+// bs_in / yn_in (both or neither): the right-hand side already gathered into box order (padded like
+// the plan's own buffer) and the near-field result already computed for it; used by the products with
+// several right-hand sides, whose near field is evaluated for a group of columns at once.
 template <int D>
-static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order) {
+static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order,
+                       const float *bs_in = nullptr, const float *yn_in = nullptr) {
+    const float *bs = bs_in ? bs_in : P.bs.p;
+    const float *yn = yn_in ? yn_in : P.yn.p;
     const int64_t n = P.n;
     const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma));
     const int nev = 4 + 3 * (P.L + 1);
@@ -1547,7 +1621,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     const float *Ys = P.Ys();   // sources in box order (the targets themselves for one point set)
 
     F3M_HIP(hipEventRecord(P.ev[8], st));
-    if (box_order)
+    if (bs_in) {
+        // gathered by the caller
+    } else if (box_order)
         copy_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.ns(), P.bs.p);
     else
         gather_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.sperm(), P.ns(), P.bs.p);
@@ -1586,35 +1662,37 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
                 P.p2p_part.release();
                 P.p2p_part.alloc((size_t)nsplit * (size_t)n, &P.bytes);
             }
-            p2p_gram3_kernel<true><<<grid_for(cdiv(ntiles * nsplit, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
-                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, nsplit, n, P.p2p_part.p);
+            p2p_gram3_kernel<true, 1><<<grid_for(cdiv(ntiles * nsplit, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, nsplit, n, P.p2p_part.p, MultiArg{});
             p2p_split_sum_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.p2p_part.p, nsplit, n, P.yn.p, accumulate);
         } else if (gram && D == 3)
-            p2p_gram3_kernel<false><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
-                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, 1, n, nullptr);
+            p2p_gram3_kernel<false, 1><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, 1, n, nullptr, MultiArg{});
         else if (gram)
             p2p_mfma_kernel<D><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
+                P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
                 (float)(1.0 / CL.edge), CL, P.yn.p, accumulate);
         else
-            p2p_kernel<D><<<grid_for(ntiles), dim3(64), 0, sn>>>(P.Xs.p, lv.start.p, Ys, P.bs.p, sstart, row_ptr, cols,
+            p2p_kernel<D><<<grid_for(ntiles), dim3(64), 0, sn>>>(P.Xs.p, lv.start.p, Ys, bs, sstart, row_ptr, cols,
                                                                 tile_box, tile_first, ntiles, nc2, P.yn.p, accumulate);
         F3M_HIP(hipGetLastError());
     };
-    if (leaf.near_sz == 0) {
+    if (yn_in) {
+        // computed by the caller
+    } else if (leaf.near_sz == 0) {
         // every pair was interpolated (smooth field, Sec. 4.3) or summed at its own depth (small field)
         zero_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.yn.p, n);
     } else {
         direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, 0);
     }
     // small-field pairs of every depth (Sec. 4.2), added on top
-    for (int l = 1; l <= P.L; ++l) {
+    for (int l = 1; l <= P.L && !yn_in; ++l) {
         f3m_level &lv = P.lev[l];
         if (lv.small_sz > 0) {
             p2p_small_kernel<D><<<grid_for(cdiv(lv.sm_ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, lv.start.p, Ys, P.bs.p, P.slev(l).start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p,
+                P.Xs.p, lv.start.p, Ys, bs, P.slev(l).start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p,
                 lv.sm_tile_first.p, lv.sm_ntiles, nc2, P.yn.p);
             F3M_HIP(hipGetLastError());
         }
@@ -1649,16 +1727,16 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         {
             size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
             if (D == 3 && p == 4)
-                p2m34_kernel<<<grid_for(sv.nchunks), dim3(64), 0, st>>>(Ys, P.bs.p, sv.start.p, sv.cell.p,
+                p2m34_kernel<<<grid_for(sv.nchunks), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
                                                                       sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
                                                                       P.W.p, P.Wpart.p);
             else if (r <= 64)
                 p2m_kernel<D, 64><<<grid_for(sv.nchunks), dim3(64), sh, st>>>(
-                    Ys, P.bs.p, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
+                    Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
                     P.W.p, P.Wpart.p);
             else
                 p2m_kernel<D, 256><<<grid_for(sv.nchunks), dim3(256), sh, st>>>(
-                    Ys, P.bs.p, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
+                    Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
                     P.W.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
             if (sv.max_box > P2M_CHUNK)   // some box has several chunks
@@ -1720,7 +1798,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         {
             hipEvent_t *ev = level_events(L);
             F3M_HIP(hipEventRecord(ev[0], st));
-            p2m34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, P.bs.p, lf.start.p, lf.cell.p, lf.chunk_box.p,
+            p2m34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
                                                                   lf.chunk_first.p, lf.nchunks, make_centre(P, L),
                                                                   lf.Wl.p, P.Wpart.p);
             F3M_HIP(hipGetLastError());
@@ -1773,15 +1851,65 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     if (P.side) F3M_HIP(hipStreamWaitEvent(st, P.ev_join, 0));
     F3M_HIP(hipEventRecord(P.ev[11], st));
     if (box_order) {
-        add_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, n, y);
+        add_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, yn, n, y);
         F3M_HIP(hipGetLastError());
-    } else if (!permute_out_bucketed(P, y, st)) {
-        scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, P.yn.p, P.perm.p, n, y);
+    } else if (!permute_out_bucketed(P, yn, y, st)) {
+        scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, yn, P.perm.p, n, y);
         F3M_HIP(hipGetLastError());
     }
     if (!P.ev[12]) F3M_HIP(hipEventCreate(&P.ev[12]));
     F3M_HIP(hipEventRecord(P.ev[12], st));
     P.have_kmvm_times = true;
+}
+
+// Products with several right-hand sides: column j of B (ns entries from B + j ldb) gives column j of Y
+// (n entries at Y + j ldy).  Where the near field runs on the D = 3 Gram kernel, it is evaluated for groups
+// of up to 4 columns at once (the exponentials, the dominant cost, are shared); everything else is done
+// column by column with the kernels of the single product.  Otherwise: m single products.
+void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_t ldy, int m, hipStream_t st) {
+    const int64_t n = P.n, ns = P.ns();
+    f3m_level &leaf = P.lev[P.L];
+    const CentreArg CL = make_centre(P, P.L);
+    const double gl = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma) * CL.edge * CL.edge;
+    // the conditions under which the single product uses the plain D = 3 Gram kernel for its near field
+    const bool fused = m > 1 && P.D == 3 && gl * 3.0 <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 &&
+                       !(P.src && P.L == 0) && P.rho == 0 && leaf.near_sz > 0 && P.ntiles >= 8192;
+    if (!fused) {
+        for (int j = 0; j < m; ++j) run_kmvm(P, B + (int64_t)j * ldb, Y + (int64_t)j * ldy, st);
+        return;
+    }
+    const size_t bs_stride = (size_t)ns + PAD_POINTS;
+    if (!P.multi_bs.p) {
+        P.multi_bs.alloc(4 * bs_stride, &P.bytes);
+        P.multi_yn.alloc(4 * (size_t)n, &P.bytes);
+        F3M_HIP(hipMemsetAsync(P.multi_bs.p, 0, 4 * bs_stride * sizeof(float), st));   // the padding stays zero
+    }
+    for (int j0 = 0; j0 < m; j0 += 4) {
+        const int mb = std::min(4, m - j0);
+        if (mb == 1) {
+            run_kmvm(P, B + (int64_t)j0 * ldb, Y + (int64_t)j0 * ldy, st);
+            break;
+        }
+        MultiArg MA{};
+        for (int j = 0; j < mb; ++j) {
+            float *bsj = P.multi_bs.p + (size_t)j * bs_stride;
+            gather_kernel<<<dim3((unsigned)cdiv(ns, 256)), dim3(256), 0, st>>>(B + (int64_t)(j0 + j) * ldb, P.sperm(), ns, bsj);
+            MA.bs[j] = bsj;
+            MA.ys[j] = P.multi_yn.p + (size_t)j * (size_t)n;
+        }
+        F3M_HIP(hipGetLastError());
+        auto launch = [&](auto kern) {
+            kern<<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, st>>>(
+                P.Xs.p, leaf.start.p, P.Ys(), nullptr, P.slev(P.L).start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p,
+                P.tile_box.p, P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, nullptr, 0, 1, n, nullptr, MA);
+        };
+        if (mb == 2) launch(p2p_gram3_kernel<false, 2>);
+        else if (mb == 3) launch(p2p_gram3_kernel<false, 3>);
+        else launch(p2p_gram3_kernel<false, 4>);
+        F3M_HIP(hipGetLastError());
+        for (int j = 0; j < mb; ++j)
+            run_kmvm_d<3>(P, nullptr, Y + (int64_t)(j0 + j) * ldy, st, false, MA.bs[j], MA.ys[j]);
+    }
 }
 
 void run_zero(float *y, int64_t n, hipStream_t st) {

@@ -79,6 +79,8 @@ struct f3m_plan_s {
     f3m::DevBuf<float> Xs;        // [n*D] coordinates in box order, row-major
     f3m::DevBuf<float> bs, ys;    // [n] right-hand side / far-field result in box order
     f3m::DevBuf<float> yn;        // [n] near-field result in box order
+    f3m::DevBuf<float> multi_bs, multi_yn;   // [4][ns + pad], [4][n]: a group of right-hand sides in box order and its
+                                             // near-field results (f3m_kmvm_multi; allocated on first use)
     f3m::DevBuf<float> p2p_part;  // [slices][n] partial near-field sums when target tiles are split (few targets)
     f3m::DevBuf<float> W, V;      // [max_l nb_l * r] node weights / node potentials of one depth
     f3m::DevBuf<float> Wpart;     // [max_l nchunks_l * r] partial node weights
@@ -135,11 +137,13 @@ int adaptive_nodes(double E, int depth, double gamma, int p);                   
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, const float *Y, hipStream_t st);   // Y == nullptr: one set (P.src set otherwise)
 void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far_point_pairs, once (synchronises)
-bool permute_out_bucketed(f3m_plan_s &P, float *y, hipStream_t st);   // false: n too small, use the plain scatter
+// y[perm[k]] = ys[k] + yn[k] through buckets of destinations; false: n too small, use the plain scatter
+bool permute_out_bucketed(f3m_plan_s &P, const float *yn, float *y, hipStream_t st);
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);   // far rows of an implicit depth
 // kmvm.hip
 // box_order: b and y are already in the plan's box order (one-set plans only; used by the solver)
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order = false);
+void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_t ldy, int m, hipStream_t st);
 void run_zero(float *y, int64_t n, hipStream_t st);   // y = 0 with a fill kernel
 // exact sums of targets X (nx rows) against sources Y (ny rows, weights b); X == Y for one set
 void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float gamma, const float *b, float *y,

@@ -277,12 +277,12 @@ __global__ __launch_bounds__(256) void scatter_pairs_kernel(const uint32_t *__re
     if (i < n) y[dest[i]] = __uint_as_float(val[i]);
 }
 
-bool permute_out_bucketed(f3m_plan_s &P, float *y, hipStream_t st) {
+bool permute_out_bucketed(f3m_plan_s &P, const float *yn, float *y, hipStream_t st) {
     if (!P.po_offs.p) return false;
     const int64_t n = P.n;
     rs_scatter_kernel<<<dim3((unsigned)P.po_nblk), dim3(RS_NT), 0, st>>>(P.perm.p, nullptr, P.po_key.p, P.po_val.p, n,
                                                                         P.po_shift, P.po_offs.p, P.po_nblk, P.ys.p,
-                                                                        P.yn.p);
+                                                                        yn);
     F3M_HIP(hipGetLastError());
     const int64_t blocks = cdiv(n, 256);
     const dim3 grid = blocks <= 65536 ? dim3((unsigned)blocks) : dim3(65536u, (unsigned)cdiv(blocks, 65536));

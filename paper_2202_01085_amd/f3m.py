@@ -76,6 +76,8 @@ def lib():
         L.f3m_plan_ex.argtypes = [vp, i64, ci, cf, ci, cf, ctypes.POINTER(Options), vp, ctypes.POINTER(vp)]
         L.f3m_plan_xy.argtypes = [vp, i64, vp, i64, ci, cf, ci, cf, ctypes.POINTER(Options), vp, ctypes.POINTER(vp)]
         L.f3m_kmvm.argtypes = [vp, vp, vp, vp]
+        L.f3m_kmvm_multi.argtypes = [vp, vp, i64, vp, i64, ci, vp]
+        L.f3m_kmvm_multi.restype = ci
         L.f3m_cg_solve.argtypes = [vp, cf, vp, vp, ci, cf, ctypes.POINTER(ci), vp, vp]
         L.f3m_cg_solve.restype = ci
         L.direct_kmvm_xy.argtypes = [vp, i64, vp, i64, ci, cf, vp, vp, vp]
@@ -166,6 +168,21 @@ class Plan:
             raise ValueError("b must have one entry per source and y one per target")
         _check(lib().f3m_kmvm(self._h, _dev_f32(b, "b") if self.ns else None, _dev_f32(y, "y"), _stream(stream)))
         return y
+
+    def kmvm_multi(self, B, Y=None, stream=None):
+        """f3m_kmvm_multi: B is an (m, sources) tensor, one right-hand side per ROW (each row contiguous);
+        returns Y of shape (m, n) with Y[j] = product of B[j]."""
+        m = int(B.shape[0])
+        if B.dim() != 2 or B.shape[1] != self.ns:
+            raise ValueError("B must have shape (m, sources)")
+        if Y is None:
+            Y = torch.empty((m, self.n), dtype=torch.float32, device=B.device)
+        if Y.shape != (m, self.n):
+            raise ValueError("Y must have shape (m, n)")
+        if m and self.n:
+            _check(lib().f3m_kmvm_multi(self._h, _dev_f32(B, "B") if self.ns else None, self.ns, _dev_f32(Y, "Y"), self.n,
+                                        m, _stream(stream)))
+        return Y
 
     def cg_solve(self, b, lam, tol=1e-6, max_iter=100, x=None, stream=None):
         """f3m_cg_solve: x = (K + lam I)^{-1} b by conjugate gradients; returns (x, iterations, history)."""
