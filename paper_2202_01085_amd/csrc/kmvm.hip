@@ -1053,14 +1053,15 @@ __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs,
                                                    const uint32_t *__restrict__ start, const int32_t *__restrict__ cell,
                                                    const uint32_t *__restrict__ chunk_box,
                                                    const uint32_t *__restrict__ chunk_first, int64_t nchunks, CentreArg C,
-                                                   float *__restrict__ W, float *__restrict__ Wpart) {
+                                                   float *__restrict__ W, float *__restrict__ Wpart, int one_chunk) {
+    // one_chunk: every box is a single chunk (chunk index = box rank): two dependent table reads less
     __shared__ float tr[64 * TR_STRIDE];
     const int64_t c = block_index();
     if (c >= nchunks) return;
     const int lane = threadIdx.x;
-    const uint32_t a = __builtin_amdgcn_readfirstlane(chunk_box[c]);
-    const uint32_t ci = (uint32_t)(c - chunk_first[a]);
-    const uint32_t nch = chunk_first[a + 1] - chunk_first[a];
+    const uint32_t a = one_chunk ? (uint32_t)c : (uint32_t)__builtin_amdgcn_readfirstlane(chunk_box[c]);
+    const uint32_t ci = one_chunk ? 0u : (uint32_t)(c - chunk_first[a]);
+    const uint32_t nch = one_chunk ? 1u : chunk_first[a + 1] - chunk_first[a];
     const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
     const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
     double ctr[3];
@@ -1114,45 +1115,97 @@ __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs,
     }
 }
 
+constexpr int L2P_NCH = 4;   // chunks per wavefront: their loads are in flight together (a chunk alone is a chain
+                             // of dependent loads and the kernel is bound by that latency)
 __global__ __launch_bounds__(64) void l2p34_kernel(const float *__restrict__ Xs, const uint32_t *__restrict__ start,
                                                    const int32_t *__restrict__ cell,
                                                    const uint64_t *__restrict__ far_ptr,
                                                    const uint32_t *__restrict__ chunk_box,
                                                    const uint32_t *__restrict__ chunk_first, int64_t nchunks, CentreArg C,
-                                                   const float *__restrict__ V, float *__restrict__ ys) {
-    const int64_t c = block_index();
-    if (c >= nchunks) return;
+                                                   const float *__restrict__ V, float *__restrict__ ys, int one_chunk) {
+    // one_chunk: every box is a single chunk (chunk index = box rank): two dependent table reads less
+    __shared__ __attribute__((aligned(16))) float vbuf[L2P_NCH][64];
+    const int64_t c0 = block_index() * L2P_NCH;
+    if (c0 >= nchunks) return;
     const int lane = threadIdx.x;
-    const uint32_t a = __builtin_amdgcn_readfirstlane(chunk_box[c]);
-    // far_ptr given: skip boxes without far partner at this depth (V_p is zero); nullptr: V holds the
-    // potentials accumulated over all depths and every box is evaluated
-    if (far_ptr && far_ptr[a + 1] == far_ptr[a]) return;
-    const uint32_t ci = (uint32_t)(c - chunk_first[a]);
-    const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
-    const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
-    double ctr[3];
+    // chunk j of this wavefront (a chunk beyond the end repeats the last one and is switched off)
+    uint32_t a[L2P_NCH], k0[L2P_NCH], k1[L2P_NCH];
+    bool on[L2P_NCH];
 #pragma unroll
-    for (int d = 0; d < 3; ++d) ctr[d] = C.alpha[d] + ((double)cell[(int64_t)a * 3 + d] + 0.5) * C.edge;
-    const float *Vp = V + (int64_t)a * 64;  // wave-uniform
-    for (uint32_t kb = k0; kb < k1; kb += 64) {
-        const uint32_t k = kb + lane;
-        if (k < k1) {
-            float Lx[4], Ly[4], Lz[4];
-            weights34(Xs + (int64_t)k * 3, ctr, C.inv_half, Lx, Ly, Lz);
-            float y = 0.f;
+    for (int j = 0; j < L2P_NCH; ++j) {
+        const int64_t c = c0 + j < nchunks ? c0 + j : nchunks - 1;
+        on[j] = c0 + j < nchunks;
+        a[j] = one_chunk ? (uint32_t)c : (uint32_t)__builtin_amdgcn_readfirstlane(chunk_box[c]);
+    }
+    double ctr[L2P_NCH][3];
+    float vrow[L2P_NCH];
 #pragma unroll
-            for (int i3 = 0; i3 < 4; ++i3) {
-                float sy = 0.f;
+    for (int j = 0; j < L2P_NCH; ++j) {
+        const int64_t c = c0 + j < nchunks ? c0 + j : nchunks - 1;
+        // far_ptr given: skip boxes without far partner at this depth (V_p is zero); nullptr: V holds the
+        // potentials accumulated over all depths and every box is evaluated
+        if (far_ptr && far_ptr[a[j] + 1] == far_ptr[a[j]]) on[j] = false;
+        const uint32_t ci = one_chunk ? 0u : (uint32_t)(c - chunk_first[a[j]]);
+        k0[j] = start[a[j]] + ci * (uint32_t)P2M_CHUNK;     // a point of the box: always a valid index
+        k1[j] = min(k0[j] + (uint32_t)P2M_CHUNK, start[a[j] + 1]);
+        if (!on[j]) k1[j] = k0[j];
 #pragma unroll
-                for (int i2 = 0; i2 < 4; ++i2) {
-                    float sx = 0.f;
+        for (int d = 0; d < 3; ++d) ctr[j][d] = C.alpha[d] + ((double)cell[(int64_t)a[j] * 3 + d] + 0.5) * C.edge;
+        vrow[j] = V[(int64_t)a[j] * 64 + lane];             // the node potentials of the box, one per lane
+    }
+    // The node potentials reach the lanes as LDS broadcasts (every lane reads the same address);
+    // as scalar operands they arrive in four dependent batches per box.
 #pragma unroll
-                    for (int i1 = 0; i1 < 4; ++i1) sx = fmaf(Lx[i1], Vp[i1 + 4 * i2 + 16 * i3], sx);
-                    sy = fmaf(Ly[i2], sx, sy);
-                }
-                y = fmaf(Lz[i3], sy, y);
+    for (int j = 0; j < L2P_NCH; ++j) vbuf[j][lane] = vrow[j];
+    __builtin_amdgcn_wave_barrier();   // one wavefront per block; its LDS operations complete in order
+    // one run of 64 points of a chunk: y += sum_i L_i(t) V[i], nested over the dimensions
+    auto run = [&](int j, bool live, uint32_t k, const float (&x)[3], float yold) {
+        float Lx[4], Ly[4], Lz[4];
+        weights34(x, ctr[j], C.inv_half, Lx, Ly, Lz);
+        float y = 0.f;
+#pragma unroll
+        for (int i3 = 0; i3 < 4; ++i3) {
+            float sy = 0.f;
+#pragma unroll
+            for (int i2 = 0; i2 < 4; ++i2) {
+                const float4 v = *reinterpret_cast<const float4 *>(&vbuf[j][4 * i2 + 16 * i3]);
+                float sx = Lx[0] * v.x;
+                sx = fmaf(Lx[1], v.y, sx);
+                sx = fmaf(Lx[2], v.z, sx);
+                sx = fmaf(Lx[3], v.w, sx);
+                sy = fmaf(Ly[i2], sx, sy);
             }
-            ys[k] += y;
+            y = fmaf(Lz[i3], sy, y);
+        }
+        if (live) ys[k] = yold + y;
+    };
+    // Loads are unconditional with the index of a lane beyond the chunk clamped to the chunk's first
+    // point (a branch around them would make the compiler wait for every load on its own); the first
+    // run of every chunk has all its loads issued before any is used, then what is left of the chunks.
+    float x[L2P_NCH][3], yold[L2P_NCH];
+    bool live[L2P_NCH];
+    uint32_t kk[L2P_NCH];
+#pragma unroll
+    for (int j = 0; j < L2P_NCH; ++j) {
+        const uint32_t k = k0[j] + lane;
+        live[j] = k < k1[j];
+        kk[j] = live[j] ? k : k0[j];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) x[j][d] = Xs[(int64_t)kk[j] * 3 + d];
+        yold[j] = ys[kk[j]];
+    }
+#pragma unroll
+    for (int j = 0; j < L2P_NCH; ++j) run(j, live[j], kk[j], x[j], yold[j]);
+#pragma unroll
+    for (int j = 0; j < L2P_NCH; ++j) {
+        for (uint32_t kb = k0[j] + 64; kb < k1[j]; kb += 64) {
+            const uint32_t k = kb + lane;
+            const bool lv = k < k1[j];
+            const uint32_t kc = lv ? k : k0[j];
+            float xr[3];
+#pragma unroll
+            for (int d = 0; d < 3; ++d) xr[d] = Xs[(int64_t)kc * 3 + d];
+            run(j, lv, kc, xr, ys[kc]);
         }
     }
 }
@@ -1599,6 +1652,9 @@ static void reduce_partials(f3m_plan_s &P, f3m_level &lv, int r, float *W, hipSt
     }
 }
 
+// every box of the depth is exactly one chunk of the P2M / L2P work split (chunk index = box rank)
+static int single_chunks(const f3m_level &lv) { return lv.max_box <= P2M_CHUNK && lv.nchunks == lv.nb ? 1 : 0; }
+
 // box_order: b and y are in the plan's box order (one-set plans), so both permutations are plain passes.
 // bs_in / yn_in (both or neither): the right-hand side already gathered into box order (padded like
 // the plan's own buffer) and the near-field result already computed for it; used by the products with
@@ -1729,7 +1785,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
             if (D == 3 && p == 4)
                 p2m34_kernel<<<grid_for(sv.nchunks), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
                                                                       sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
-                                                                      P.W.p, P.Wpart.p);
+                                                                      P.W.p, P.Wpart.p, single_chunks(sv));
             else if (r <= 64)
                 p2m_kernel<D, 64><<<grid_for(sv.nchunks), dim3(64), sh, st>>>(
                     Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
@@ -1778,9 +1834,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         {
             size_t sh = (size_t)(r + P2M_CHUNK * (D * p + 1)) * sizeof(float);
             if (D == 3 && p == 4)
-                l2p34_kernel<<<grid_for(lv.nchunks), dim3(64), 0, st>>>(P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p,
+                l2p34_kernel<<<grid_for(cdiv(lv.nchunks, L2P_NCH)), dim3(64), 0, st>>>(P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p,
                                                                       lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, C,
-                                                                      P.V.p, P.ys.p);
+                                                                      P.V.p, P.ys.p, single_chunks(lv));
             else
                 l2p_kernel<D><<<grid_for(lv.nchunks), dim3(P2M_CHUNK), sh, st>>>(
                     P.Xs.p, lv.start.p, lv.cell.p, lv.far_ptr.p, lv.chunk_box.p, lv.chunk_first.p, lv.nchunks, p, r, C, N,
@@ -1800,7 +1856,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
             F3M_HIP(hipEventRecord(ev[0], st));
             p2m34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
                                                                   lf.chunk_first.p, lf.nchunks, make_centre(P, L),
-                                                                  lf.Wl.p, P.Wpart.p);
+                                                                  lf.Wl.p, P.Wpart.p, single_chunks(lf));
             F3M_HIP(hipGetLastError());
             if (lf.max_box > P2M_CHUNK)   // some box has several chunks
                 reduce_partials(P, lf, r, lf.Wl.p, st);
@@ -1833,9 +1889,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         {
             hipEvent_t *ev = level_events(L);
             if (P.tree_lmin == L) F3M_HIP(hipEventRecord(ev[4], st));
-            l2p34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, lf.start.p, lf.cell.p, nullptr, lf.chunk_box.p,
+            l2p34_kernel<<<grid_for(cdiv(lf.nchunks, L2P_NCH)), dim3(64), 0, st>>>(P.Xs.p, lf.start.p, lf.cell.p, nullptr, lf.chunk_box.p,
                                                                   lf.chunk_first.p, lf.nchunks, make_centre(P, L),
-                                                                  lf.Vl.p, P.ys.p);
+                                                                  lf.Vl.p, P.ys.p, single_chunks(lf));
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipEventRecord(ev[5], st));
         }
