@@ -652,7 +652,9 @@ __global__ __launch_bounds__(256) void p2p_split_sum_kernel(const float *__restr
 // (the lane-held segment table of p2p_gram3_kernel), 64 per step, and a wavefront handles a run
 // of at most SMALL_TT targets of one box, whose coordinates are wave-uniform.  Every lane keeps
 // one partial sum per target; they are added across the lanes once, at the end.  Differences
-// are formed directly (the pairs may be several boxes apart).  The result is ADDED to ys.
+// are formed directly (the pairs may be several boxes apart).  The result is added to ys
+// (accumulate) or written.  The same kernel takes the overflow tiles of the near field of the last
+// depth (overflow != 0): one tile per listed box, the targets behind its last full run of 64.
 template <int D>
 constexpr int small_tt() { return D <= 4 ? 16 : 8; }
 
@@ -665,14 +667,15 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ cols,
                                                         const uint32_t *__restrict__ tile_box,
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
-                                                        float nc2, float *__restrict__ ys) {
+                                                        float nc2, float *__restrict__ ys, int overflow, int accumulate) {
     constexpr int TT = small_tt<D>();
     const int lane = threadIdx.x & 63;
     const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
     if (t >= ntiles) return;
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
-    const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * (uint32_t)TT;
     const uint32_t kend = startT[a + 1];
+    const uint32_t k0 = overflow ? startT[a] + ((kend - startT[a]) & ~63u)
+                                 : startT[a] + (uint32_t)(t - tile_first[a]) * (uint32_t)TT;
     const int nt = (int)(kend - k0 < (uint32_t)TT ? kend - k0 : (uint32_t)TT);   // wave-uniform
     float xt[TT][D];   // target coordinates, wave-uniform (rows beyond nt repeat an in-bounds point)
 #pragma unroll
@@ -743,7 +746,7 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
             if (lane == tt) res = v;
         }
     }
-    if (lane < nt) ys[k0 + lane] += res;
+    if (lane < nt) ys[k0 + lane] = accumulate ? ys[k0 + lane] + res : res;
 }
 
 // exact product, all pairs (Sec. 2, KeOps paragraph): lane = target (rows of X, nx of them), the
@@ -1742,6 +1745,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         zero_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.yn.p, n);
     } else {
         direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, 0);
+        // last runs with few targets: sources on the lanes
+        if (P.notiles > 0)
+            p2p_small_kernel<D><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, leaf.start.p, Ys, bs, P.slev(P.L).start.p, leaf.near_ptr.p, leaf.near_col.p, P.otile_box.p,
+                P.otile_first.p, P.notiles, nc2, P.yn.p, 1, 0);
     }
     // small-field pairs of every depth (Sec. 4.2), added on top
     for (int l = 1; l <= P.L && !yn_in; ++l) {
@@ -1749,7 +1757,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         if (lv.small_sz > 0) {
             p2p_small_kernel<D><<<grid_for(cdiv(lv.sm_ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, bs, P.slev(l).start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p,
-                lv.sm_tile_first.p, lv.sm_ntiles, nc2, P.yn.p);
+                lv.sm_tile_first.p, lv.sm_ntiles, nc2, P.yn.p, 0, 1);
             F3M_HIP(hipGetLastError());
         }
     }
@@ -1963,6 +1971,14 @@ void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_
         else if (mb == 3) launch(p2p_gram3_kernel<false, 3>);
         else launch(p2p_gram3_kernel<false, 4>);
         F3M_HIP(hipGetLastError());
+        if (P.notiles > 0) {
+            const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma));
+            for (int j = 0; j < mb; ++j)
+                p2p_small_kernel<3><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, st>>>(
+                    P.Xs.p, leaf.start.p, P.Ys(), MA.bs[j], P.slev(P.L).start.p, leaf.near_ptr.p, leaf.near_col.p,
+                    P.otile_box.p, P.otile_first.p, P.notiles, nc2, MA.ys[j], 1, 0);
+            F3M_HIP(hipGetLastError());
+        }
         for (int j = 0; j < mb; ++j)
             run_kmvm_d<3>(P, nullptr, Y + (int64_t)(j0 + j) * ldy, st, false, MA.bs[j], MA.ys[j]);
     }

@@ -85,9 +85,14 @@ struct f3m_plan_s {
     f3m::DevBuf<float> W, V;      // [max_l nb_l * r] node weights / node potentials of one depth
     f3m::DevBuf<float> Wpart;     // [max_l nchunks_l * r] partial node weights
     f3m::DevBuf<double> Wslice;   // [max_l nslices_l * r] sums of the partial node weights of a slice
-    // near-field work split: a tile is a run of at most 64 targets of one leaf box
+    // near-field work split: a tile is a run of at most 64 targets of one leaf box (the full runs of 64, and the
+    // last run if it is not an overflow tile)
     int64_t ntiles = 0;
     f3m::DevBuf<uint32_t> tile_box, tile_first;   // [ntiles], [nb_L+1]
+    // ... and overflow tiles: a last run of a leaf box with so few targets (<= 10, <= 8 above 4-D) that the
+    // kernel with the sources on the lanes is cheaper; at most one per box
+    int64_t notiles = 0;
+    f3m::DevBuf<uint32_t> otile_box, otile_first;
     f3m_level lev[F3M_MAX_LEVELS + 1];          // boxes of X (targets); lists by target box
     std::unique_ptr<f3m_source> src;            // two-set plan: the partition of Y (sources)
     // the source side of either kind of plan

@@ -573,11 +573,47 @@ struct ChunkCountFlagIn {
     __device__ uint64_t operator()(int64_t a) const { return flag[a] ? (start[a + 1] - start[a] + chunk - 1) / chunk : 0; }
 };
 
+// Near-field tiles of the last depth.  A box is cut into runs of 64 targets; a last run of at most `ts`
+// targets (the overflow of a box a little above 64 points, or a box with very few points) would leave
+// most of a 64-wide tile idle, so it becomes an "overflow tile" for the kernel that puts the SOURCES on
+// the lanes instead.  Big tiles: the full runs, and the last run if it has more than ts targets.
+struct BigTileCountIn {
+    const uint32_t *start;
+    uint32_t ts;
+    __device__ uint64_t operator()(int64_t a) const {
+        const uint32_t cnt = start[a + 1] - start[a];
+        return cnt / 64u + ((cnt & 63u) > ts ? 1u : 0u);
+    }
+};
+struct OverflowTileCountIn {
+    const uint32_t *start;
+    uint32_t ts;
+    __device__ uint64_t operator()(int64_t a) const {
+        const uint32_t rem = (start[a + 1] - start[a]) & 63u;
+        return rem >= 1u && rem <= ts ? 1u : 0u;
+    }
+};
+
 // flag[c] = 1 for every column c of a list (equal values from several threads: plain vector stores)
 __global__ __launch_bounds__(256) void mark_cols_kernel(const uint32_t *__restrict__ cols, int64_t count,
                                                         uint32_t *__restrict__ flag) {
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256)
         flag[cols[e]] = 1u;
+}
+
+// work items counted per box by `count`: first[nb+1] (exclusive scan) and the box of every item
+template <class CountIn>
+static void build_items(CountIn count, int64_t nb, DevBuf<uint32_t> &first, DevBuf<uint32_t> &cbox, int64_t &nitems,
+                        int64_t *tally, hipStream_t st) {
+    first.alloc((size_t)nb + 1, tally);
+    uint64_t total = 0;
+    exclusive_scan(count, nb, U32Out{first.p}, &total, st);
+    nitems = (int64_t)total;
+    set_u32_kernel<<<1, 1, 0, st>>>(first.p + nb, (uint32_t)total);
+    cbox.alloc((size_t)nitems, tally);
+    if (nitems > 0)
+        chunk_box_kernel<<<dim3((unsigned)cdiv(nitems, 256)), dim3(256), 0, st>>>(first.p, nb, nitems, cbox.p);
+    F3M_HIP(hipGetLastError());
 }
 
 static void build_chunks(const uint32_t *start, int64_t nb, uint32_t chunk, DevBuf<uint32_t> &first,
@@ -919,7 +955,14 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         }
         max_part = std::max(max_part, sv.nchunks * (int64_t)lv.r);
     }
-    build_chunks(P.lev[P.L].start.p, P.lev[P.L].nb, 64, P.tile_first, P.tile_box, P.ntiles, tally, st);
+    {
+        const f3m_level &lf = P.lev[P.L];
+        // at most the targets a wavefront of p2p_small_kernel takes (16, 8 above 4-D); beyond about 10 targets a
+        // half-filled 64-wide tile is the cheaper of the two (measured at n = 1e9)
+        const uint32_t ts = D <= 4 ? 10 : 8;
+        build_items(BigTileCountIn{lf.start.p, ts}, lf.nb, P.tile_first, P.tile_box, P.ntiles, tally, st);
+        build_items(OverflowTileCountIn{lf.start.p, ts}, lf.nb, P.otile_first, P.otile_box, P.notiles, tally, st);
+    }
     // target tiles of the small-field rows of every depth (Sec. 4.2)
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
