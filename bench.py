@@ -188,7 +188,8 @@ def main():
         flops = (3.0 * D + 2.0) * pairs
         ach = flops / t / 1e12
         lane_slots_per_s = 256 * 64 * 2.4e9
-        rooflines["p2p"] = {"kernel": "p2p_gram3_kernel, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
+        rooflines["p2p"] = {"kernel": "near field: p2p_gram3_kernel (tiles of up to 64 targets) + p2p_small_kernel (last runs "
+                                      "of <= 10 targets), %d point pairs" % pairs, "bound": "alu", "achieved": ach,
                             "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS,
                             "traffic": None, "launch_ms": st["p2p"],
                             "pairs_per_s": pairs / t,

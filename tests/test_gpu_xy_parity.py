@@ -203,3 +203,47 @@ def test_xy_edge_cases():
     # column counts must agree
     with pytest.raises(ValueError):
         f3m.Plan(Xd, 1.0, 4, 2.0, Y=Yd[:, :2].contiguous())
+
+
+def test_xy_full_size_structure_adjoint_and_sampled_rows():
+    # the two-set workload bench.py --xy times: 5e8 uniform targets, 5e8 normal sources, D = 3.  The CPU
+    # oracle cannot follow at this size; checked instead: the coverage identity, the adjoint identity
+    # <a, F(X,Y) b> = <F(Y,X) a, b> with the plan of the swapped sets (the rules are symmetric and the
+    # interpolated block is L_X^T K L_Y, so the two operators are transposes of each other up to rounding;
+    # a wrong shift sign, anchor or table index breaks it), and sampled rows against the fp64 exact rows,
+    # themselves pinned to the CPU oracle on a few rows.  The error against the exact product is the
+    # method's own at this shape (the cube has edge ~11 against a lengthscale of 1) and is gated loosely.
+    n = 500_000_000
+    say("f3m xy full size: %d uniform targets x %d normal sources" % (n, n))
+    X = inputs.points_uniform(n, 3, 1101, device=DEV)
+    Y = inputs.points_normal(n, 3, 1102, device=DEV)
+    b = inputs.rhs_normal(n, 1103, device=DEV)
+    a = inputs.rhs_normal(n, 1104, device=DEV)
+    plan = f3m.Plan(X, 1.0, 4, 2.0, Y=Y)
+    inf, sinf = plan.info(), plan.source_info()
+    L = inf.depth
+    say("  L=%d boxes X %s Y %s" % (L, list(inf.nboxes)[:L + 1], list(sinf.nboxes)[:L + 1]))
+    assert min(inf.max_box[L], sinf.max_box[L]) <= 128 < min(inf.max_box[L - 1], sinf.max_box[L - 1]) or L == inf.quant_depth
+    assert inf.near_point_pairs + sum(inf.far_point_pairs[l] for l in range(L + 1)) == n * n
+    y = plan.kmvm(b)
+    torch.cuda.synchronize()
+    rows = inputs.sample_rows(n, 2_000, 3101)
+    y64 = f3m.direct_kmvm_xy_rows_f64(X, Y, b, 1.0, rows).cpu().numpy()
+    e = rel(y[rows.to(DEV)].cpu().numpy(), y64)
+    say("  rel err vs exact on %d rows %.3e" % (rows.numel(), e))
+    assert e <= 5e-3
+    sub = rows[:6].numpy()
+    assert rel(y64[:6], oracle.rows_xy(X.cpu().numpy(), Y.cpu().numpy(), b.cpu().numpy(), 1.0, sub)) <= 1e-12
+    lhs = torch.dot(a.double(), y.double()).item()
+    scale = (torch.linalg.norm(a.double()) * torch.linalg.norm(y.double())).item()
+    plan.close()
+    del y
+    swapped = f3m.Plan(Y, 1.0, 4, 2.0, Y=X)
+    assert swapped.info().depth == L
+    z = swapped.kmvm(a)
+    torch.cuda.synchronize()
+    rhs = torch.dot(z.double(), b.double()).item()
+    say("  a.(F(X,Y) b) = %.9e, (F(Y,X) a).b = %.9e, scaled difference %.2e" % (lhs, rhs, abs(lhs - rhs) / scale))
+    # an asymmetric error of relative size d in the operator shows up as about d / sqrt(n) on this scale
+    assert abs(lhs - rhs) <= 5e-8 * scale
+    swapped.close()
