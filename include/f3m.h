@@ -18,7 +18,8 @@
  *     boundary.  f3m_last_error() gives a thread-local message for the last
  *     failing call of the calling thread.
  *   - The caller owns X, b, y.  A plan owns all of its device buffers and
- *     keeps no reference to X after f3m_plan returns.
+ *     keeps no reference to X after f3m_plan returns.  Device memory of the
+ *     library is cached by a pool (see f3m_destroy, f3m_trim_memory).
  *   - There is no CPU fallback: without a HIP device every compute call
  *     returns F3M_ERR_HIP.
  */
@@ -236,8 +237,14 @@ f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, i
 f3m_status f3m_cg_solve(f3m_plan_t *plan, float lambda, const float *b, float *x, int max_iter, float tol,
                         int *iters_host, float *history_host, void *stream);
 
-/* Frees the plan and its device memory (NULL is allowed). */
+/* Destroys the plan (NULL is allowed); waits for the device first.  Its device buffers go back to the
+ * library's memory pool, where the next plan finds them again (building plan after plan then costs no
+ * hipMalloc / hipFree); the pool keeps at most 96 GiB and gives the rest back to the device at once. */
 void f3m_destroy(f3m_plan_t *plan);
+
+/* Gives every cached block of the pool back to the device (hipFree) and returns the bytes freed.  Buffers
+ * of living plans are not touched.  Call it when the device memory is wanted for something else. */
+int64_t f3m_trim_memory(void);
 
 /* Message of the last failing call on this thread ("" if none). */
 const char *f3m_last_error(void);

@@ -218,6 +218,12 @@ f3m_status f3m_cg_solve(f3m_plan_t *plan, float lambda, const float *b, float *x
     return guarded([&] { f3m::run_cg(*plan, lambda, b, x, max_iter, tol, iters_host, history_host, (hipStream_t)stream); });
 }
 
+int64_t f3m_trim_memory(void) {
+    int64_t freed = 0;
+    (void)guarded([&] { freed = (int64_t)f3m::pool_trim(); });
+    return freed;
+}
+
 void f3m_destroy(f3m_plan_t *plan) {
     if (!plan) return;
     (void)hipDeviceSynchronize();

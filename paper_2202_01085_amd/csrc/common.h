@@ -27,7 +27,13 @@ struct Error {
         }                                                                                     \
     } while (0)
 
-// A device allocation that frees itself; the byte count is added to *tally if given.
+// pool.hip: device memory through a caching pool (released blocks are kept for the next request of
+// the same size class; pool_trim gives them back to the device and returns the bytes freed)
+void *pool_alloc(size_t bytes);
+void pool_free(void *p, size_t bytes);
+size_t pool_trim();
+
+// A device allocation that releases itself; the byte count is added to *tally if given.
 template <class T>
 struct DevBuf {
     T *p = nullptr;
@@ -47,17 +53,18 @@ struct DevBuf {
         tally = tally_;
         count = n;
         size_t bytes = (n ? n : 1) * sizeof(T);
-        hipError_t e = hipMalloc((void **)&p, bytes);
-        if (e != hipSuccess) {
-            p = nullptr; count = 0;
-            (void)hipGetLastError();
-            fail(F3M_ERR_OOM, "hipMalloc of " + std::to_string(bytes) + " bytes failed: " + hipGetErrorString(e));
+        p = nullptr;
+        try {
+            p = (T *)pool_alloc(bytes);
+        } catch (...) {
+            count = 0;
+            throw;
         }
         if (tally) *tally += (int64_t)bytes;
     }
     void release() {
         if (p) {
-            (void)hipFree(p);
+            pool_free(p, (count ? count : 1) * sizeof(T));
             if (tally) *tally -= (int64_t)((count ? count : 1) * sizeof(T));
         }
         p = nullptr; count = 0;

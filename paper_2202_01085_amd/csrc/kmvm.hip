@@ -658,7 +658,7 @@ __global__ __launch_bounds__(256) void p2p_split_sum_kernel(const float *__restr
 template <int D>
 constexpr int small_tt() { return D <= 4 ? 16 : 8; }
 
-template <int D>
+template <int D, int TT>
 __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict__ Xt,
                                                         const uint32_t *__restrict__ startT,
                                                         const float *__restrict__ Xs, const float *__restrict__ bs,
@@ -668,7 +668,6 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ tile_box,
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
                                                         float nc2, float *__restrict__ ys, int overflow, int accumulate) {
-    constexpr int TT = small_tt<D>();
     const int lane = threadIdx.x & 63;
     const int64_t t = block_index() * 4 + (threadIdx.x >> 6);
     if (t >= ntiles) return;
@@ -707,7 +706,8 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
         const uint32_t S = __builtin_amdgcn_readlane(cend, 63);
         if (S == 0) continue;
         int r = 0;
-        for (uint32_t w0 = 0; w0 < S; w0 += 64) {
+        // source index of position w0 + lane (an in-bounds index beyond the end of the sequence)
+        auto locate = [&](uint32_t w0) {
             const uint32_t p = w0 + lane;
             while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;   // ends: w0 < S = cend of lane 63
             uint32_t src = 0;
@@ -717,10 +717,26 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
                 const uint32_t c1 = __builtin_amdgcn_readlane(cend, rr), s0 = __builtin_amdgcn_readlane(sfirst, rr);
                 if (p >= c0 && p < c1) src = s0 + (p - c0);
             }
+            return src;
+        };
+        float xn[D], bn;
+        {
+            const uint32_t src = locate(0);
+#pragma unroll
+            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
+            bn = bs[src];
+        }
+        for (uint32_t w0 = 0; w0 < S; w0 += 64) {
             float x[D];
 #pragma unroll
-            for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)src * D + d];
-            const float bv = p < S ? bs[src] : 0.f;   // positions beyond the sequence contribute nothing
+            for (int d = 0; d < D; ++d) x[d] = xn[d];
+            const float bv = w0 + lane < S ? bn : 0.f;   // positions beyond the sequence contribute nothing
+            // the loads of the next step are in flight during this one (the last step reloads a
+            // harmless address, so the number of loads in flight is fixed)
+            const uint32_t nsrc = w0 + 64 < S ? locate(w0 + 64) : 0u;
+#pragma unroll
+            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)nsrc * D + d];
+            bn = bs[nsrc];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 if (tt < nt) {
@@ -1747,7 +1763,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, 0);
         // last runs with few targets: sources on the lanes
         if (P.notiles > 0)
-            p2p_small_kernel<D><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, sn>>>(
+            p2p_small_kernel<D, overflow_targets(D)><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, leaf.start.p, Ys, bs, P.slev(P.L).start.p, leaf.near_ptr.p, leaf.near_col.p, P.otile_box.p,
                 P.otile_first.p, P.notiles, nc2, P.yn.p, 1, 0);
     }
@@ -1755,7 +1771,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     for (int l = 1; l <= P.L && !yn_in; ++l) {
         f3m_level &lv = P.lev[l];
         if (lv.small_sz > 0) {
-            p2p_small_kernel<D><<<grid_for(cdiv(lv.sm_ntiles, 4)), dim3(256), 0, sn>>>(
+            p2p_small_kernel<D, small_tt<D>()><<<grid_for(cdiv(lv.sm_ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, bs, P.slev(l).start.p, lv.small_ptr.p, lv.small_col.p, lv.sm_tile_box.p,
                 lv.sm_tile_first.p, lv.sm_ntiles, nc2, P.yn.p, 0, 1);
             F3M_HIP(hipGetLastError());
@@ -1974,7 +1990,7 @@ void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_
         if (P.notiles > 0) {
             const float nc2 = (float)(-1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma));
             for (int j = 0; j < mb; ++j)
-                p2p_small_kernel<3><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, st>>>(
+                p2p_small_kernel<3, overflow_targets(3)><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, st>>>(
                     P.Xs.p, leaf.start.p, P.Ys(), MA.bs[j], P.slev(P.L).start.p, leaf.near_ptr.p, leaf.near_col.p,
                     P.otile_box.p, P.otile_first.p, P.notiles, nc2, MA.ys[j], 1, 0);
             F3M_HIP(hipGetLastError());

@@ -132,6 +132,9 @@ namespace f3m {
 
 constexpr int P2M_CHUNK = 256;
 constexpr int P2M_SLICE = 512;   // chunks per slice of the two-stage sum of partial node weights
+// largest last run of a leaf box that is treated as an overflow tile (near field with the sources on the lanes):
+// beyond about 10 targets a half-filled 64-wide tile is the cheaper of the two (measured at n = 1e9)
+constexpr int overflow_targets(int D) { return D <= 4 ? 10 : 8; }
 constexpr int PAD_POINTS = 64;   // zero padding behind Xs and bs
 constexpr int MAX_NODES = 4096;
 

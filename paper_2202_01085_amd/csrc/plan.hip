@@ -957,9 +957,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
     }
     {
         const f3m_level &lf = P.lev[P.L];
-        // at most the targets a wavefront of p2p_small_kernel takes (16, 8 above 4-D); beyond about 10 targets a
-        // half-filled 64-wide tile is the cheaper of the two (measured at n = 1e9)
-        const uint32_t ts = D <= 4 ? 10 : 8;
+        const uint32_t ts = (uint32_t)overflow_targets(D);
         build_items(BigTileCountIn{lf.start.p, ts}, lf.nb, P.tile_first, P.tile_box, P.ntiles, tally, st);
         build_items(OverflowTileCountIn{lf.start.p, ts}, lf.nb, P.otile_first, P.otile_box, P.notiles, tally, st);
     }

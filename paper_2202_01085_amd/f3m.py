@@ -89,6 +89,8 @@ def lib():
         L.direct_kmvm_rows_f64.argtypes = [vp, i64, ci, cf, vp, vp, i64, vp, vp]
         L.f3m_destroy.argtypes = [vp]
         L.f3m_destroy.restype = None
+        L.f3m_trim_memory.argtypes = []
+        L.f3m_trim_memory.restype = ctypes.c_int64
         L.f3m_last_error.restype = ctypes.c_char_p
         L.f3m_plan_info.argtypes = [vp, ctypes.POINTER(Info)]
         L.f3m_plan_get_perm.argtypes = [vp, vp]
@@ -253,6 +255,11 @@ class Plan:
         out = Times()
         _check(lib().f3m_stage_times(self._h, ctypes.byref(out)))
         return out.as_dict()
+
+
+def trim_memory():
+    """f3m_trim_memory: give the library's cached device blocks back to the device; returns the bytes freed."""
+    return int(lib().f3m_trim_memory())
 
 
 def f3m_plan(X, lengthscale, interp_nodes, eta=2.0, **kw):

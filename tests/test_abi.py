@@ -30,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
             "f3m_last_error", "f3m_plan_info", "f3m_plan_get_perm", "f3m_plan_get_point_keys",
             "f3m_plan_get_boxes", "f3m_plan_get_list", "f3m_stage_times", "f3m_level_times", "f3m_plan_xy",
             "direct_kmvm_xy", "direct_kmvm_xy_rows_f64", "f3m_plan_source_info", "f3m_plan_get_source_perm",
-            "f3m_plan_get_source_boxes", "f3m_cg_solve", "f3m_kmvm_multi"} <= set(names)
+            "f3m_plan_get_source_boxes", "f3m_cg_solve", "f3m_kmvm_multi", "f3m_trim_memory"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
