@@ -26,7 +26,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_VALU_F32_TFLOPS = 78.6      # 256 CU x 64 lanes x 2.4 GHz x 2 flop, packed fp32 not used
+PEAK_VALU_F32_TFLOPS = 157.3     # published fp32 vector peak: 256 CU x 128 lanes-equivalents (packed) x 2.4 GHz x 2 flop
+UNPACKED_F32_TFLOPS = 78.6       # 256 CU x 64 lanes x 2.4 GHz x 2 flop: what plain (unpacked) FMAs can reach; this build
+                                 # generates no packed fp32 instructions
 PEAK_HBM_GBS = 8000.0
 
 
@@ -177,6 +179,7 @@ def main():
         rooflines["m2l"] = {"kernel": "%s, leaf depth %d, %d far pairs, %d target boxes" % (kernel, L, far_L, nb_L),
                             "bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
                             "frac": ach / PEAK_VALU_F32_TFLOPS, "traffic": None, "launch_ms": m2l_ms,
+                            "frac_of_unpacked_fp32_peak": ach / UNPACKED_F32_TFLOPS,
                             "algorithmic_tflops": 2.0 * r * r * far_L / t / 1e12,
                             "far_pairs_per_s": far_L / t}
     if pairs > 0 and st["p2p"] > 0:
@@ -194,9 +197,12 @@ def main():
                             "traffic": None, "launch_ms": st["p2p"],
                             "pairs_per_s": pairs / t,
                             "valu_slot_frac": 3.0 * pairs / t / lane_slots_per_s,
-                            "frac_of_packed_fp32_peak": ach / 157.3,
-                            "peak_note": "256 CU x 64 lanes x 2.4 GHz x 2 flop (FMA) = 78.6 TFLOP/s; the published "
-                                         "157.3 needs packed FP32, which this build does not generate"}
+                            "frac_of_unpacked_fp32_peak": ach / UNPACKED_F32_TFLOPS,
+                            "peak_note": "peak = the published fp32 vector figure, which needs packed FP32; this build "
+                                         "generates none, so plain FMAs top out at 78.6 TFLOP/s. The (3D+2)-flop count can "
+                                         "exceed that because the D-term part of every pair runs on the matrix cores; "
+                                         "valu_slot_frac (3 issue slots per pair: one half-rate exp2 + one FMA, over all "
+                                         "lane slots) is the utilisation figure to read"}
     traffic_file = args.traffic
     if traffic_file is None and n == 1_000_000_000 and not args.xy:
         # HBM bytes per launch measured with rocprofv3 --pmc on this workload (profiles/hbm_traffic_config5_n1e9.md)
