@@ -165,13 +165,14 @@ def main():
     if far_L > 0 and m2l_ms > 0:
         # algorithmic: 2 r^2 flop per far pair (the dense node-to-node product).  For D = 3 with 4 nodes per
         # dimension the kernel applies the Kronecker factors per candidate / line / plane of the 6x6x6 grid around
-        # the parent: 231 factor applications of 256 multiply-adds per target box instead of 189 x 4096, on the
-        # vector ALU.  `achieved` counts the multiply-adds it executes; `algorithmic_tflops` the dense equivalent.
+        # the parent, and shares the line and plane sums between the eight children: 936 factor applications of 256
+        # multiply-adds per parent (117 per target box) instead of 189 x 4096 per target, on the vector ALU.
+        # `achieved` counts the multiply-adds it executes; `algorithmic_tflops` the dense equivalent.
         t = m2l_ms * 1e-3
         nb_L = int(inf.nboxes[L])
         if D == 3 and cfg["p"] == 4 and cfg["theta"] == 2.0 and not args.xy:
-            executed = 2.0 * 231 * 256 * nb_L
-            kernel = "m2l_stencil_kernel"
+            executed = 2.0 * 117 * 256 * nb_L
+            kernel = "m2l_stencil_shared_kernel"
         else:
             executed = 2.0 * D * r * cfg["p"] * far_L
             kernel = "m2l_kron_small_kernel" if r // cfg["p"] <= 32 else "m2l_kron_kernel"

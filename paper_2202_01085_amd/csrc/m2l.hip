@@ -204,11 +204,222 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
     V[(int64_t)t * 64 + lane] = acc;
 }
 
+// ------------------------------------------------------------------------------------
+// The same sums with the work shared between the eight children of a parent (no small field).
+// The far sum of a target is the sum over ALL candidates of the 6 x 6 x 6 grid minus the sum over
+// the 3 x 3 x 3 block around the target, and the sum over all candidates factorises further: the
+// x factor of a candidate depends on the target's x parity only, so the line sums
+//   X_tx(cy, cz) = sum_cx G_{cx-2-tx} W_(cx,cy,cz)              2 x 36 lines, 6 applications each
+// serve four targets each, the plane sums
+//   Y_{tx,ty}(cz) = sum_cy G_{cy-2-ty} X_tx(cy, cz)             4 x 6 planes, 6 applications each
+// serve two, and a target needs only
+//   V_all = sum_cz G_{cz-2-tz} Y_{tx,ty}(cz)                    6 applications
+//   V_t   = V_all - sum over the near block, again by lines and planes: 27 + 9 + 3 applications.
+// Per parent 432 + 144 + 8 x (6 + 39) = 936 applications of a 4 x 4 factor to a 64-vector instead
+// of 8 x 231.  Rows of absent candidates are zero in LDS, so no masks are needed.  The
+// subtraction costs no accuracy that matters: |near part| / |far part| is of order one for wide
+// kernels, and for narrow ones both are part of a result dominated by the near field itself.
+// all_far (the smooth depth of Sec. 4.3, every candidate interpolated): no subtraction.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint64_t *__restrict__ up_near_ptr,
+                                                                 const uint32_t *__restrict__ up_near_col,
+                                                                 const uint32_t *__restrict__ up_cstart,
+                                                                 const int32_t *__restrict__ up_cell,
+                                                                 const int32_t *__restrict__ cell,
+                                                                 const uint32_t *__restrict__ key, int64_t nparents,
+                                                                 int64_t per_xcd, const float *__restrict__ G,
+                                                                 int all_far, const float *__restrict__ W,
+                                                                 float *__restrict__ V) {
+    __shared__ float rows[ST_CAND * 64];
+    __shared__ float xl[2 * 36 * 64];       // X_tx(cy, cz) at [(tx * 36 + cy + 6 cz) * 64 + node]
+    __shared__ float yp[4 * 6 * 64];        // Y_{tx,ty}(cz) at [((tx + 2 ty) * 6 + cz) * 64 + node]
+    // the candidate tables are needed only while the rows are loaded and live in the memory of xl
+    // (two workgroups per compute unit fit only below 80 KB each)
+    uint32_t *cand = reinterpret_cast<uint32_t *>(xl);          // candidate k of near parent j at [8 j + k]: rank or ~0
+    int *cpos = reinterpret_cast<int *>(xl) + ST_CAND;          // its position in the 6 x 6 x 6 grid
+    __shared__ uint32_t qfirst[27], qcount[27];
+    __shared__ float gs[7 * 16];            // the factor table
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t bi = block_index2();
+    const int64_t pb = (bi & 7) * per_xcd + (bi >> 3);
+    if ((bi >> 3) >= per_xcd || pb >= nparents) return;
+    if (tid < 27) {
+        const uint64_t e = up_near_ptr[pb] + tid;
+        uint32_t first = 0, count = 0;
+        if (e < up_near_ptr[pb + 1]) {
+            const uint32_t q = up_near_col[e];
+            first = up_cstart[q];
+            count = up_cstart[q + 1] - first;
+        }
+        qfirst[tid] = first;
+        qcount[tid] = count;
+    }
+    if (tid >= 256 && tid < 256 + 7 * 16) gs[tid - 256] = G[tid - 256];
+    // every row starts as zero: the rows of absent candidates stay that way (cheaper than testing)
+#pragma unroll
+    for (int i = 0; i < ST_CAND * 64 / 512; ++i) rows[tid + 512 * i] = 0.f;
+    __syncthreads();
+    if (tid < ST_CAND) {
+        const int j = tid >> 3, k = tid & 7;
+        uint32_t c = 0xFFFFFFFFu;
+        int pos = 0;
+        if ((uint32_t)k < qcount[j]) {
+            c = qfirst[j] + k;
+            const int px = cell[(int64_t)c * 3] - 2 * up_cell[pb * 3] + 2,
+                      py = cell[(int64_t)c * 3 + 1] - 2 * up_cell[pb * 3 + 1] + 2,
+                      pz = cell[(int64_t)c * 3 + 2] - 2 * up_cell[pb * 3 + 2] + 2;
+            pos = px + 6 * py + 36 * pz;     // in [0, 216): the near box is within one cell of the parent
+        }
+        cpos[tid] = pos;
+        cand[tid] = c;
+    }
+    __syncthreads();
+    {
+        float tmp[27];
+#pragma unroll
+        for (int i = 0; i < 27; ++i) {
+            const uint32_t c = cand[w + 8 * i];
+            tmp[i] = W[(int64_t)(c == 0xFFFFFFFFu ? 0u : c) * 64 + lane];
+        }
+#pragma unroll
+        for (int i = 0; i < 27; ++i)
+            if (cand[w + 8 * i] != 0xFFFFFFFFu) rows[cpos[w + 8 * i] * 64 + lane] = tmp[i];
+    }
+    __syncthreads();
+    const int tx = w & 1, ty = (w >> 1) & 1, tz = w >> 2;
+    const int ix = lane & 3, iy = (lane >> 2) & 3, iz = lane >> 4;
+    // out += sum_k f[k] * (entry k places further on in the lane's quad / row of 16 / wavefront);
+    // the input always comes straight from an LDS read (no vector-ALU write precedes the DPP reads)
+    auto xapply = [&](float &out, float v, const float (&f)[4]) {
+        asm("v_fmac_f32 %0, %2, %1\n\t"
+            "v_fmac_f32_dpp %0, %1, %3 quad_perm:[1,2,3,0] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %5 quad_perm:[3,0,1,2] row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "+v"(out)
+            : "v"(v), "v"(f[0]), "v"(f[1]), "v"(f[2]), "v"(f[3]));
+    };
+    auto yapply = [&](float &out, float v, const float (&f)[4]) {
+        asm("v_fmac_f32 %0, %2, %1\n\t"
+            "s_nop 0\n\t"
+            "v_fmac_f32_dpp %0, %1, %3 row_ror:12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %4 row_ror:8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %5 row_ror:4 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "+v"(out)
+            : "v"(v), "v"(f[0]), "v"(f[1]), "v"(f[2]), "v"(f[3]));
+    };
+    int zlane[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) zlane[k] = ix + 4 * iy + 16 * ((iz + k) & 3);
+    auto zapply = [&](float &out, float v, const float (&f)[4]) {
+        out = fmaf(f[0], v, out);
+#pragma unroll
+        for (int k = 1; k < 4; ++k) out = fmaf(f[k], __shfl(v, zlane[k], 64), out);
+    };
+    // factor entries for candidate coordinate c and target parity t: offset c - 2 - t, rotation k
+    auto factor = [&](int c, int t, int i, float (&f)[4]) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) f[k] = gs[(c + 1 - t) * 16 + i * 4 + ((i + k) & 3)];
+    };
+
+    // ---- line sums over x: wavefront w takes x parity w & 1 and the lines (w >> 1) + 4 i, i = 0..8
+    {
+        float fx[6][4];
+#pragma unroll
+        for (int c = 0; c < 6; ++c) factor(c, tx, ix, fx[c]);
+#pragma unroll
+        for (int i = 0; i < 9; ++i) {
+            const int ln = (w >> 1) + 4 * i;
+            float v[6];
+#pragma unroll
+            for (int cx = 0; cx < 6; ++cx) v[cx] = rows[(cx + 6 * ln) * 64 + lane];
+            float line = 0.f;
+#pragma unroll
+            for (int cx = 0; cx < 6; ++cx) xapply(line, v[cx], fx[cx]);
+            xl[(tx * 36 + ln) * 64 + lane] = line;
+        }
+    }
+    __syncthreads();
+    // ---- plane sums over y: wavefront w takes the parities (w & 3) and the planes 3 (w >> 2) .. + 2
+    {
+        float fy[6][4];
+#pragma unroll
+        for (int c = 0; c < 6; ++c) factor(c, ty, iy, fy[c]);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int cz = 3 * (w >> 2) + i;
+            float v[6];
+#pragma unroll
+            for (int cy = 0; cy < 6; ++cy) v[cy] = xl[(tx * 36 + cy + 6 * cz) * 64 + lane];
+            float plane = 0.f;
+#pragma unroll
+            for (int cy = 0; cy < 6; ++cy) yapply(plane, v[cy], fy[cy]);
+            yp[((w & 3) * 6 + cz) * 64 + lane] = plane;
+        }
+    }
+    __syncthreads();
+    // ---- the child with parity w, if it exists (no barrier below this point)
+    uint32_t t = 0xFFFFFFFFu;
+    for (uint32_t c = up_cstart[pb]; c < up_cstart[pb + 1]; ++c)
+        if ((key[c] & 7u) == (uint32_t)w) t = c;
+    if (t == 0xFFFFFFFFu) return;
+    float acc = 0.f;
+    {
+        float v[6];
+#pragma unroll
+        for (int cz = 0; cz < 6; ++cz) v[cz] = yp[((w & 3) * 6 + cz) * 64 + lane];
+#pragma unroll
+        for (int cz = 0; cz < 6; ++cz) {
+            float fz[4];
+            factor(cz, tz, iz, fz);
+            zapply(acc, v[cz], fz);
+        }
+    }
+    if (!all_far) {
+        // minus the near block: candidates t_d + 1 .. t_d + 3 in every dimension, offsets -1, 0, 1,
+        // whose factors G_{-1}, G_0, G_1 sit at table entries 2, 3, 4 whatever the parity
+        float nfx[3][4], nfy[3][4], nfz[3][4];
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                nfx[i][k] = gs[(i + 2) * 16 + ix * 4 + ((ix + k) & 3)];
+                nfy[i][k] = gs[(i + 2) * 16 + iy * 4 + ((iy + k) & 3)];
+                nfz[i][k] = gs[(i + 2) * 16 + iz * 4 + ((iz + k) & 3)];
+            }
+        float near = 0.f;
+#pragma unroll
+        for (int k3 = 0; k3 < 3; ++k3) {
+            float plane = 0.f;
+#pragma unroll
+            for (int k2 = 0; k2 < 3; ++k2) {
+                const int base = (tx + 1) + 6 * (ty + 1 + k2) + 36 * (tz + 1 + k3);
+                float v[3];
+#pragma unroll
+                for (int k1 = 0; k1 < 3; ++k1) v[k1] = rows[(base + k1) * 64 + lane];
+                float line = 0.f;
+#pragma unroll
+                for (int k1 = 0; k1 < 3; ++k1) xapply(line, v[k1], nfx[k1]);
+                yapply(plane, line, nfy[k2]);
+            }
+            zapply(near, plane, nfz[k3]);
+        }
+        acc -= near;
+    }
+    V[(int64_t)t * 64 + lane] = acc;
+}
+
 bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st) {
     if (!m2l_stencil_applies(P) || level < 1) return false;
     f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
     if (lv.gtab.p == nullptr || lv.gtab_omax != 3) return false;
     const int64_t per_xcd = cdiv(up.nb, 8);
+    if (P.rho == 0) {   // no small field: the variant that shares the line and plane sums between the children
+        m2l_stencil_shared_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p,
+                                                                           up.cell.p, lv.cell.p, lv.key.p, up.nb, per_xcd,
+                                                                           lv.gtab.p, lv.smooth ? 1 : 0, W, V);
+        F3M_HIP(hipGetLastError());
+        return true;
+    }
     m2l_stencil_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p, up.cell.p,
                                                                 lv.cell.p, lv.key.p, up.nb, per_xcd, lv.gtab.p,
                                                                 lv.smooth ? 1 : 0, lv.start.p, (uint32_t)P.rho, W, V);
