@@ -221,59 +221,66 @@ __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__rest
 // kernels, and for narrow ones both are part of a result dominated by the near field itself.
 // all_far (the smooth depth of Sec. 4.3, every candidate interpolated): no subtraction.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint64_t *__restrict__ up_near_ptr,
-                                                                 const uint32_t *__restrict__ up_near_col,
-                                                                 const uint32_t *__restrict__ up_cstart,
-                                                                 const int32_t *__restrict__ up_cell,
-                                                                 const int32_t *__restrict__ cell,
-                                                                 const uint32_t *__restrict__ key, int64_t nparents,
-                                                                 int64_t per_xcd, const float *__restrict__ G,
-                                                                 int all_far, const float *__restrict__ W,
-                                                                 float *__restrict__ V) {
+// tables for it, made once per plan and depth: for every parent the rank of the candidate at each
+// position of its 6 x 6 x 6 grid (~0: no such box) and its child of each parity (~0: none), so that a
+// workgroup starts with one table read instead of a chain of four dependent ones (near list ->
+// child ranges -> cells -> rows), which is what bounded the kernel
+__global__ __launch_bounds__(256) void stencil_table_kernel(const uint64_t *__restrict__ up_near_ptr,
+                                                            const uint32_t *__restrict__ up_near_col,
+                                                            const uint32_t *__restrict__ up_cstart,
+                                                            const int32_t *__restrict__ up_cell,
+                                                            const int32_t *__restrict__ cell,
+                                                            const uint32_t *__restrict__ key, int64_t nparents,
+                                                            uint32_t *__restrict__ cand_tab,
+                                                            uint32_t *__restrict__ child_tab) {
+    const int64_t pb = block_index2();
+    if (pb >= nparents) return;
+    const int tid = threadIdx.x;
+    if (tid < ST_CAND) {
+        const int j = tid >> 3, k = tid & 7;
+        const uint64_t e = up_near_ptr[pb] + j;
+        if (e < up_near_ptr[pb + 1]) {
+            const uint32_t q = up_near_col[e];
+            const uint32_t first = up_cstart[q], count = up_cstart[q + 1] - first;
+            if ((uint32_t)k < count) {
+                const uint32_t c = first + k;
+                const int px = cell[(int64_t)c * 3] - 2 * up_cell[pb * 3] + 2,
+                          py = cell[(int64_t)c * 3 + 1] - 2 * up_cell[pb * 3 + 1] + 2,
+                          pz = cell[(int64_t)c * 3 + 2] - 2 * up_cell[pb * 3 + 2] + 2;
+                // in [0, 6) each: a near box is within one cell of the parent
+                cand_tab[pb * ST_CAND + px + 6 * py + 36 * pz] = c;
+            }
+        }
+    } else if (tid < ST_CAND + 8) {
+        const uint32_t w = (uint32_t)(tid - ST_CAND);
+        for (uint32_t c = up_cstart[pb]; c < up_cstart[pb + 1]; ++c)
+            if ((key[c] & 7u) == w) child_tab[pb * 8 + w] = c;
+    }
+}
+
+__global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t *__restrict__ cand_tab,
+                                                                 const uint32_t *__restrict__ child_tab,
+                                                                 int64_t nparents, int64_t per_xcd,
+                                                                 const float *__restrict__ G, int all_far,
+                                                                 const float *__restrict__ W, float *__restrict__ V) {
     __shared__ float rows[ST_CAND * 64];
     __shared__ float xl[2 * 36 * 64];       // X_tx(cy, cz) at [(tx * 36 + cy + 6 cz) * 64 + node]
     __shared__ float yp[4 * 6 * 64];        // Y_{tx,ty}(cz) at [((tx + 2 ty) * 6 + cz) * 64 + node]
-    // the candidate tables are needed only while the rows are loaded and live in the memory of xl
+    // the candidate ranks are needed only while the rows are loaded and live in the memory of xl
     // (two workgroups per compute unit fit only below 80 KB each)
-    uint32_t *cand = reinterpret_cast<uint32_t *>(xl);          // candidate k of near parent j at [8 j + k]: rank or ~0
-    int *cpos = reinterpret_cast<int *>(xl) + ST_CAND;          // its position in the 6 x 6 x 6 grid
-    __shared__ uint32_t qfirst[27], qcount[27];
+    uint32_t *cand = reinterpret_cast<uint32_t *>(xl);
     __shared__ float gs[7 * 16];            // the factor table
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // consecutive parents (neighbours in space) on the same XCD, so that its L2 serves the overlap
     const int64_t bi = block_index2();
     const int64_t pb = (bi & 7) * per_xcd + (bi >> 3);
     if ((bi >> 3) >= per_xcd || pb >= nparents) return;
-    if (tid < 27) {
-        const uint64_t e = up_near_ptr[pb] + tid;
-        uint32_t first = 0, count = 0;
-        if (e < up_near_ptr[pb + 1]) {
-            const uint32_t q = up_near_col[e];
-            first = up_cstart[q];
-            count = up_cstart[q + 1] - first;
-        }
-        qfirst[tid] = first;
-        qcount[tid] = count;
-    }
+    if (tid < ST_CAND) cand[tid] = cand_tab[pb * ST_CAND + tid];
     if (tid >= 256 && tid < 256 + 7 * 16) gs[tid - 256] = G[tid - 256];
-    // every row starts as zero: the rows of absent candidates stay that way (cheaper than testing)
-#pragma unroll
-    for (int i = 0; i < ST_CAND * 64 / 512; ++i) rows[tid + 512 * i] = 0.f;
+    const uint32_t t = child_tab[pb * 8 + w];   // the child with parity w (wave-uniform), or ~0
     __syncthreads();
-    if (tid < ST_CAND) {
-        const int j = tid >> 3, k = tid & 7;
-        uint32_t c = 0xFFFFFFFFu;
-        int pos = 0;
-        if ((uint32_t)k < qcount[j]) {
-            c = qfirst[j] + k;
-            const int px = cell[(int64_t)c * 3] - 2 * up_cell[pb * 3] + 2,
-                      py = cell[(int64_t)c * 3 + 1] - 2 * up_cell[pb * 3 + 1] + 2,
-                      pz = cell[(int64_t)c * 3 + 2] - 2 * up_cell[pb * 3 + 2] + 2;
-            pos = px + 6 * py + 36 * pz;     // in [0, 216): the near box is within one cell of the parent
-        }
-        cpos[tid] = pos;
-        cand[tid] = c;
-    }
-    __syncthreads();
+    // node weights of the candidates into LDS at their grid position, zeros for absent ones: 27 rows
+    // per wavefront, all loads in flight together
     {
         float tmp[27];
 #pragma unroll
@@ -282,8 +289,7 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint64_t 
             tmp[i] = W[(int64_t)(c == 0xFFFFFFFFu ? 0u : c) * 64 + lane];
         }
 #pragma unroll
-        for (int i = 0; i < 27; ++i)
-            if (cand[w + 8 * i] != 0xFFFFFFFFu) rows[cpos[w + 8 * i] * 64 + lane] = tmp[i];
+        for (int i = 0; i < 27; ++i) rows[(w + 8 * i) * 64 + lane] = cand[w + 8 * i] == 0xFFFFFFFFu ? 0.f : tmp[i];
     }
     __syncthreads();
     const int tx = w & 1, ty = (w >> 1) & 1, tz = w >> 2;
@@ -358,9 +364,6 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint64_t 
     }
     __syncthreads();
     // ---- the child with parity w, if it exists (no barrier below this point)
-    uint32_t t = 0xFFFFFFFFu;
-    for (uint32_t c = up_cstart[pb]; c < up_cstart[pb + 1]; ++c)
-        if ((key[c] & 7u) == (uint32_t)w) t = c;
     if (t == 0xFFFFFFFFu) return;
     float acc = 0.f;
     {
@@ -408,14 +411,27 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint64_t 
     V[(int64_t)t * 64 + lane] = acc;
 }
 
+// candidate and child tables of a depth whose M2L runs on the candidate grid without a small field
+void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st) {
+    if (!m2l_stencil_applies(P) || level < 1 || P.rho != 0) return;
+    f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
+    if (!lv.far_implicit || lv.far_sz == 0 || lv.p == 0) return;
+    lv.st_cand.alloc((size_t)up.nb * ST_CAND, &P.bytes);
+    lv.st_child.alloc((size_t)up.nb * 8, &P.bytes);
+    F3M_HIP(hipMemsetAsync(lv.st_cand.p, 0xFF, (size_t)up.nb * ST_CAND * sizeof(uint32_t), st));
+    F3M_HIP(hipMemsetAsync(lv.st_child.p, 0xFF, (size_t)up.nb * 8 * sizeof(uint32_t), st));
+    stencil_table_kernel<<<grid2(up.nb), dim3(256), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p, up.cell.p,
+                                                            lv.cell.p, lv.key.p, up.nb, lv.st_cand.p, lv.st_child.p);
+    F3M_HIP(hipGetLastError());
+}
+
 bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st) {
     if (!m2l_stencil_applies(P) || level < 1) return false;
     f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
     if (lv.gtab.p == nullptr || lv.gtab_omax != 3) return false;
     const int64_t per_xcd = cdiv(up.nb, 8);
-    if (P.rho == 0) {   // no small field: the variant that shares the line and plane sums between the children
-        m2l_stencil_shared_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p,
-                                                                           up.cell.p, lv.cell.p, lv.key.p, up.nb, per_xcd,
+    if (lv.st_cand.p) {   // no small field: the variant that shares the line and plane sums between the children
+        m2l_stencil_shared_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(lv.st_cand.p, lv.st_child.p, up.nb, per_xcd,
                                                                            lv.gtab.p, lv.smooth ? 1 : 0, W, V);
         F3M_HIP(hipGetLastError());
         return true;

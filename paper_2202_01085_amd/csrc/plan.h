@@ -33,6 +33,9 @@ struct f3m_level {
     // D = 3, 4 nodes/dim, far ratio 2: the M2L enumerates the far partners on the candidate grid
     // around the parent (m2l.hip); far_ptr keeps the row lengths, far_col stays empty
     bool far_implicit = false;
+    // ... and, without a small field, per box of the depth ABOVE: the rank of the candidate at each of the 216
+    // positions of the grid around it and its child of each parity (~0: none)
+    f3m::DevBuf<uint32_t> st_cand, st_child;
     // Sec. 4.3: nodes per dimension used at this depth (interp_nodes, 3 under the adaptive rule, or 0 =
     // the far pairs of the depth are dropped), r = p^D, and whether every pair of the depth is interpolated
     int p = 0, r = 0;
@@ -164,7 +167,8 @@ void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension
 void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter, float tol, int *iters_host,
             float *history_host, hipStream_t st);
 // m2l.hip
-bool m2l_stencil_applies(const f3m_plan_s &P);                   // D = 3, 4 nodes/dim, far ratio 2
+bool m2l_stencil_applies(const f3m_plan_s &P);
+void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st);   // after the lists of the depth exist                   // D = 3, 4 nodes/dim, far ratio 2
 bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);  // false: does not apply
 
 }  // namespace f3m
