@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
     const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * 64u;
     const uint32_t kend = startT[a + 1];
-    const bool two = __builtin_amdgcn_readfirstlane((int)(kend - k0)) > 32;
+    const int ntg = __builtin_amdgcn_readfirstlane((int)(kend - k0));   // targets of the tile (wave-uniform)
     const int nn = lane & 31, kk = lane >> 5;
     float ctr[D];
 #pragma unroll
@@ -484,7 +484,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             e0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[0], e0, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) e0[v] = __builtin_amdgcn_exp2f(e0[v]);
-            if (two) {
+            if (ntg > 32) {
                 e1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], e1, 0, 0, 0);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) e1[v] = __builtin_amdgcn_exp2f(e1[v]);
@@ -498,7 +498,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
                 const float *bf = reinterpret_cast<const float *>(bq);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) accm0[j] = fmaf(e0[v], bf[v], accm0[j]);
-                if (two) {
+                if (ntg > 32) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) accm1[j] = fmaf(e1[v], bf[v], accm1[j]);
                 }
@@ -511,7 +511,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         const float *bf = reinterpret_cast<const float *>(bq);
         f16v c0 = {0.f};
         c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[0], c0, 0, 0, 0);
-        if (two) {
+        if (ntg > 32) {
             f16v c1 = {0.f};
             c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], c1, 0, 0, 0);
 #pragma unroll
@@ -545,6 +545,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             if (lane >= d) cend += up;
         }
         const uint32_t cbeg = cend - slen;
+        const uint32_t delta = sfirst - cbeg;   // position -> source index inside this lane's box (mod 2^32)
         uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // sources of this round
         uint32_t wbeg = 0;                                   // this wavefront's positions: [wbeg, S)
         if constexpr (SPLIT) {
@@ -555,16 +556,19 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         }
         if (wbeg >= S) continue;
         int r = 0;   // first near box that reaches into the current window (wave-uniform)
-        // source index of position w0 + lane (any in-bounds index beyond the end of the sequence)
+        // Source index of position w0 + lane; positions from S on take the last source of the
+        // sequence, so every index is in bounds.  Box r holds w0 (cbeg <= w0 < cend), so it is the
+        // box of every position until a later box begins at or before the position; a box without
+        // points is overridden by its successor, which begins at the same position.
         auto locate = [&](uint32_t w0) {
-            const uint32_t p = w0 + lane;
-            while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;   // ends: w0 < S = cend of lane 63
-            uint32_t src = 0;
-            for (int rr = r; rr < m; ++rr) {
+            const uint32_t p = min(w0 + (uint32_t)lane, S - 1u);
+            while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;   // ends: w0 < S <= cend of lane 63
+            uint32_t src = p + (uint32_t)__builtin_amdgcn_readlane(delta, r);
+            for (int rr = r + 1; rr < m; ++rr) {
                 const uint32_t c0 = __builtin_amdgcn_readlane(cbeg, rr);
                 if (c0 >= w0 + 64) break;
-                const uint32_t c1 = __builtin_amdgcn_readlane(cend, rr), s0 = __builtin_amdgcn_readlane(sfirst, rr);
-                if (p >= c0 && p < c1) src = s0 + (p - c0);
+                const uint32_t dl = __builtin_amdgcn_readlane(delta, rr);
+                src = p >= c0 ? p + dl : src;
             }
             return src;
         };
@@ -703,19 +707,21 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
             if (lane >= d) cend += up;
         }
         const uint32_t cbeg = cend - slen;
+        const uint32_t delta = sfirst - cbeg;   // position -> source index inside this lane's box (mod 2^32)
         const uint32_t S = __builtin_amdgcn_readlane(cend, 63);
         if (S == 0) continue;
         int r = 0;
-        // source index of position w0 + lane (an in-bounds index beyond the end of the sequence)
+        // source index of position w0 + lane, as in p2p_gram3_kernel (positions from S on take the
+        // last source of the sequence)
         auto locate = [&](uint32_t w0) {
-            const uint32_t p = w0 + lane;
+            const uint32_t p = min(w0 + (uint32_t)lane, S - 1u);
             while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;   // ends: w0 < S = cend of lane 63
-            uint32_t src = 0;
-            for (int rr = r; rr < m; ++rr) {
+            uint32_t src = p + (uint32_t)__builtin_amdgcn_readlane(delta, r);
+            for (int rr = r + 1; rr < m; ++rr) {
                 const uint32_t c0 = __builtin_amdgcn_readlane(cbeg, rr);
                 if (c0 >= w0 + 64) break;
-                const uint32_t c1 = __builtin_amdgcn_readlane(cend, rr), s0 = __builtin_amdgcn_readlane(sfirst, rr);
-                if (p >= c0 && p < c1) src = s0 + (p - c0);
+                const uint32_t dl = __builtin_amdgcn_readlane(delta, rr);
+                src = p >= c0 ? p + dl : src;
             }
             return src;
         };
