@@ -452,16 +452,18 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     const float nrm = -0.25f / g;
     float *bw = bbuf[wv];
 
-    // operands of the two blocks of 32 sources of a step; live = the lane's position is a source
-    auto prepare = [&](bool live, const float (&x)[D], h8v &opA, h8v &opB) {
+    // operands of the two blocks of 32 sources of a step.  A lane whose position lies behind the
+    // sequence holds the last source again (a near point like the others: finite exponent) and
+    // its right-hand side is zero.
+    auto prepare = [&](const float (&x)[D], h8v &opA, h8v &opB) {
         float w[NC];
         float s = 0.f;
 #pragma unroll
         for (int d = 0; d < D; ++d) {
-            w[d] = (x[d] - ctr[d]) * (live ? g2l : 0.f);     // 2 g w_d
+            w[d] = (x[d] - ctr[d]) * g2l;                    // 2 g w_d
             s = fmaf(w[d], w[d], s);
         }
-        w[D] = live ? s * nrm : -60000.f;                    // -g |w|^2; a dead row gives exp2(-huge) = 0
+        w[D] = s * nrm;                                      // -g |w|^2
         const uint32_t hi01 = pack_f16(w[0], w[1]), hi23 = pack_f16(w[2], w[3]);
         const f2v b01 = unpack_f16(hi01), b23 = unpack_f16(hi23);
         const uint32_t lo01 = pack_f16(w[0] - b01.x, w[1] - b01.y), lo23 = pack_f16(w[2] - b23.x, w[3] - b23.y);
@@ -511,7 +513,11 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         const float *bf = reinterpret_cast<const float *>(bq);
         f16v c0 = {0.f};
         c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[0], c0, 0, 0, 0);
-        if (ntg > 32) {
+        // the test is made on a scalar register at each use: kept as a lane mask across the loop it
+        // costs two vector instructions per step
+        int nt2 = ntg;
+        asm volatile("" : "+s"(nt2));
+        if (nt2 > 32) {
             f16v c1 = {0.f};
             c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], c1, 0, 0, 0);
 #pragma unroll
@@ -614,7 +620,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             }
             __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
             h8v opA, opB;
-            prepare(live, xc, opA, opB);
+            prepare(xc, opA, opB);
             block(opA, 0);
             if (w0 + 32 < S) block(opB, 32);
         }
