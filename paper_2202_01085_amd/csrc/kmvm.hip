@@ -522,13 +522,8 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, Bop[1], c1, 0, 0, 0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
-            float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; v += 2) {
-                s1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bf[v], s1);
-                s2 = fmaf(__builtin_amdgcn_exp2f(c1[v + 1]), bf[v + 1], s2);
-            }
-            acc1 += s1 + s2;
+            for (int v = 15; v >= 0; --v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bf[v], acc1);
         } else {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
@@ -595,13 +590,13 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             float xc[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) xc[d] = xn[d];
-            const float bc = bn;
+            const float bn0 = bn;
             float bcm[MB];
 #pragma unroll
             for (int j = 0; j < MB; ++j) bcm[j] = bnm[j];
-            // the loads of the next step are in flight during this one (the last step reloads a
-            // harmless address, so the number of loads in flight is fixed)
-            const uint32_t src = w0 + 64 < S ? locate(w0 + 64) : 0u;
+            // the loads of the next step are in flight during this one (the last step loads its own
+            // sources again, so the number of loads in flight is fixed)
+            const uint32_t src = locate(w0 + 64 < S ? w0 + 64 : w0);
 #pragma unroll
             for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
             if constexpr (MB > 1) {
@@ -610,13 +605,20 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             } else {
                 bn = bs[src];
             }
-            const bool live = w0 + lane < S;
+            float bc = bn0;
+            if (w0 + 64 > S) {   // last step only: the positions behind the sequence get weight zero
+                asm volatile("");   // keeps this a branch: as selects it costs every step three instructions
+                const bool live = w0 + lane < S;
+                bc = live ? bc : 0.f;
+#pragma unroll
+                for (int j = 0; j < MB; ++j) bcm[j] = live ? bcm[j] : 0.f;
+            }
             __builtin_amdgcn_wave_barrier();
             if constexpr (MB > 1) {
 #pragma unroll
-                for (int j = 0; j < MB; ++j) bw[j * 64 + lane] = live ? bcm[j] : 0.f;
+                for (int j = 0; j < MB; ++j) bw[j * 64 + lane] = bcm[j];
             } else {
-                bw[lane] = live ? bc : 0.f;
+                bw[lane] = bc;
             }
             __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
             h8v opA, opB;
@@ -742,10 +744,14 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
             float x[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) x[d] = xn[d];
-            const float bv = w0 + lane < S ? bn : 0.f;   // positions beyond the sequence contribute nothing
-            // the loads of the next step are in flight during this one (the last step reloads a
-            // harmless address, so the number of loads in flight is fixed)
-            const uint32_t nsrc = w0 + 64 < S ? locate(w0 + 64) : 0u;
+            float bv = bn;
+            if (w0 + 64 > S) {      // last step only: positions behind the sequence contribute nothing
+                asm volatile("");   // keeps this a branch (as a select it costs every step three instructions)
+                bv = w0 + lane < S ? bv : 0.f;
+            }
+            // the loads of the next step are in flight during this one (the last step loads its own
+            // sources again, so the number of loads in flight is fixed)
+            const uint32_t nsrc = locate(w0 + 64 < S ? w0 + 64 : w0);
 #pragma unroll
             for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)nsrc * D + d];
             bn = bs[nsrc];
