@@ -1085,6 +1085,9 @@ __device__ inline void weights34(const float *__restrict__ x, const double (&ctr
 }
 
 constexpr int TR_STRIDE = 36;  // floats per lane row in the LDS transpose of 32 accumulators (16-byte aligned, bank-shifted)
+constexpr int P2M_NCH = 4;     // chunks per wavefront: the table reads and the first loads of all of them are in
+                               // flight together (a chunk alone is a chain of dependent loads, and the kernel was
+                               // bound by that latency)
 
 __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
                                                    const uint32_t *__restrict__ start, const int32_t *__restrict__ cell,
@@ -1093,29 +1096,61 @@ __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs,
                                                    float *__restrict__ W, float *__restrict__ Wpart, int one_chunk) {
     // one_chunk: every box is a single chunk (chunk index = box rank): two dependent table reads less
     __shared__ float tr[64 * TR_STRIDE];
-    const int64_t c = block_index();
-    if (c >= nchunks) return;
+    const int64_t c0 = block_index() * P2M_NCH;
+    if (c0 >= nchunks) return;
     const int lane = threadIdx.x;
-    const uint32_t a = one_chunk ? (uint32_t)c : (uint32_t)__builtin_amdgcn_readfirstlane(chunk_box[c]);
-    const uint32_t ci = one_chunk ? 0u : (uint32_t)(c - chunk_first[a]);
-    const uint32_t nch = one_chunk ? 1u : chunk_first[a + 1] - chunk_first[a];
-    const uint32_t k0 = start[a] + ci * (uint32_t)P2M_CHUNK;
-    const uint32_t k1 = min(k0 + (uint32_t)P2M_CHUNK, start[a + 1]);
-    double ctr[3];
+    // chunk j of this wavefront (a chunk beyond the end repeats the last one and is switched off)
+    uint32_t a[P2M_NCH], k0[P2M_NCH], k1[P2M_NCH], nch[P2M_NCH];
+    int64_t cj[P2M_NCH];
+    bool on[P2M_NCH];
 #pragma unroll
-    for (int d = 0; d < 3; ++d) ctr[d] = C.alpha[d] + ((double)cell[(int64_t)a * 3 + d] + 0.5) * C.edge;
-    float acc[64];
+    for (int j = 0; j < P2M_NCH; ++j) {
+        cj[j] = c0 + j < nchunks ? c0 + j : nchunks - 1;
+        on[j] = c0 + j < nchunks;
+        a[j] = one_chunk ? (uint32_t)cj[j] : (uint32_t)__builtin_amdgcn_readfirstlane(chunk_box[cj[j]]);
+    }
+    double ctr[P2M_NCH][3];
 #pragma unroll
-    for (int i = 0; i < 64; ++i) acc[i] = 0.f;
-    for (uint32_t kb = k0; kb < k1; kb += 64) {
+    for (int j = 0; j < P2M_NCH; ++j) {
+        const uint32_t ci = one_chunk ? 0u : (uint32_t)(cj[j] - chunk_first[a[j]]);
+        nch[j] = one_chunk ? 1u : chunk_first[a[j] + 1] - chunk_first[a[j]];
+        k0[j] = start[a[j]] + ci * (uint32_t)P2M_CHUNK;     // a point of the box: always a valid index
+        k1[j] = min(k0[j] + (uint32_t)P2M_CHUNK, start[a[j] + 1]);
+#pragma unroll
+        for (int d = 0; d < 3; ++d) ctr[j][d] = C.alpha[d] + ((double)cell[(int64_t)a[j] * 3 + d] + 0.5) * C.edge;
+    }
+    // Loads are unconditional, the index of a lane beyond the chunk clamped to the chunk's first point
+    // and its weight set to zero (a branch around them would make every load wait on its own).
+    auto load = [&](int j, uint32_t kb, float (&x)[3], float &bv) {
         const uint32_t k = kb + lane;
-        if (k < k1) {
+        const bool live = k < k1[j];
+        const uint32_t kc = live ? k : k0[j];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) x[d] = Xs[(int64_t)kc * 3 + d];
+        const float bl = bs[kc];
+        bv = live ? bl : 0.f;
+    };
+    float x[P2M_NCH][3], bv[P2M_NCH];
+#pragma unroll
+    for (int j = 0; j < P2M_NCH; ++j) load(j, k0[j], x[j], bv[j]);
+    const int i = lane & 31, part = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < P2M_NCH; ++j) {
+        if (!on[j]) continue;   // wave-uniform
+        float acc[64];
+#pragma unroll
+        for (int q = 0; q < 64; ++q) acc[q] = 0.f;
+        float xc[3] = {x[j][0], x[j][1], x[j][2]}, bc = bv[j];
+        for (uint32_t kb = k0[j];;) {
+            // the next run of the chunk (boxes above 64 points) is loaded while this one is added
+            const bool more = kb + 64 < k1[j];
+            float xn[3] = {0.f, 0.f, 0.f}, bn = 0.f;
+            if (more) load(j, kb + 64, xn, bn);
             float Lx[4], Ly[4], Lz[4];
-            weights34(Xs + (int64_t)k * 3, ctr, C.inv_half, Lx, Ly, Lz);
-            const float bb = bs[k];
+            weights34(xc, ctr[j], C.inv_half, Lx, Ly, Lz);
 #pragma unroll
             for (int i3 = 0; i3 < 4; ++i3) {
-                const float zb = Lz[i3] * bb;
+                const float zb = Lz[i3] * bc;
 #pragma unroll
                 for (int i2 = 0; i2 < 4; ++i2) {
                     const float yz = Ly[i2] * zb;
@@ -1123,32 +1158,36 @@ __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs,
                     for (int i1 = 0; i1 < 4; ++i1) acc[i1 + 4 * i2 + 16 * i3] = fmaf(Lx[i1], yz, acc[i1 + 4 * i2 + 16 * i3]);
                 }
             }
+            if (!more) break;
+            kb += 64;
+#pragma unroll
+            for (int d = 0; d < 3; ++d) xc[d] = xn[d];
+            bc = bn;
         }
-    }
-    // sum over lanes, 32 nodes at a time (half the LDS, twice the resident wavefronts): lane l
-    // writes its row; lane (i, part) adds rows 32 part .. 32 part + 31 of column i, and the two
-    // parts meet through one shuffle
-    float *dst = nch == 1 ? W + (int64_t)a * 64 : Wpart + c * 64;
-    const int i = lane & 31, part = lane >> 5;
+        // sum over lanes, 32 nodes at a time (half the LDS, twice the resident wavefronts): lane l
+        // writes its row; lane (i, part) adds rows 32 part .. 32 part + 31 of column i, and the two
+        // parts meet through one shuffle
+        float *dst = nch[j] == 1 ? W + (int64_t)a[j] * 64 : Wpart + cj[j] * 64;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        if (q) __syncthreads();
+        for (int q = 0; q < 2; ++q) {
+            __syncthreads();   // the sums of the previous half (or chunk) have been read
 #pragma unroll
-        for (int g = 0; g < 8; ++g)
-            *reinterpret_cast<float4 *>(&tr[lane * TR_STRIDE + 4 * g]) =
-                make_float4(acc[32 * q + 4 * g], acc[32 * q + 4 * g + 1], acc[32 * q + 4 * g + 2], acc[32 * q + 4 * g + 3]);
-        __syncthreads();
-        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            for (int g = 0; g < 8; ++g)
+                *reinterpret_cast<float4 *>(&tr[lane * TR_STRIDE + 4 * g]) =
+                    make_float4(acc[32 * q + 4 * g], acc[32 * q + 4 * g + 1], acc[32 * q + 4 * g + 2], acc[32 * q + 4 * g + 3]);
+            __syncthreads();
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
-        for (int row = 0; row < 32; row += 4) {
-            s0 += tr[(32 * part + row + 0) * TR_STRIDE + i];
-            s1 += tr[(32 * part + row + 1) * TR_STRIDE + i];
-            s2 += tr[(32 * part + row + 2) * TR_STRIDE + i];
-            s3 += tr[(32 * part + row + 3) * TR_STRIDE + i];
+            for (int row = 0; row < 32; row += 4) {
+                s0 += tr[(32 * part + row + 0) * TR_STRIDE + i];
+                s1 += tr[(32 * part + row + 1) * TR_STRIDE + i];
+                s2 += tr[(32 * part + row + 2) * TR_STRIDE + i];
+                s3 += tr[(32 * part + row + 3) * TR_STRIDE + i];
+            }
+            float t = (s0 + s1) + (s2 + s3);
+            t += __shfl_xor(t, 32, 64);
+            if (part == 0) dst[32 * q + i] = t;
         }
-        float t = (s0 + s1) + (s2 + s3);
-        t += __shfl_xor(t, 32, 64);
-        if (part == 0) dst[32 * q + i] = t;
     }
 }
 
@@ -1825,7 +1864,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         {
             size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
             if (D == 3 && p == 4)
-                p2m34_kernel<<<grid_for(sv.nchunks), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
+                p2m34_kernel<<<grid_for(cdiv(sv.nchunks, P2M_NCH)), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
                                                                       sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
                                                                       P.W.p, P.Wpart.p, single_chunks(sv));
             else if (r <= 64)
@@ -1896,7 +1935,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         {
             hipEvent_t *ev = level_events(L);
             F3M_HIP(hipEventRecord(ev[0], st));
-            p2m34_kernel<<<grid_for(lf.nchunks), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
+            p2m34_kernel<<<grid_for(cdiv(lf.nchunks, P2M_NCH)), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
                                                                   lf.chunk_first.p, lf.nchunks, make_centre(P, L),
                                                                   lf.Wl.p, P.Wpart.p, single_chunks(lf));
             F3M_HIP(hipGetLastError());
