@@ -1325,69 +1325,124 @@ void upload_transfer(f3m_plan_s &P, hipStream_t st) {
     F3M_HIP(hipStreamSynchronize(st));
 }
 
-// one block (wavefront) per parent, lane = parent node i
+// Both transfers run one wavefront per PARENT with lane = node (ix + 4 iy + 16 iz) and apply the
+// three 4 x 4 factors one dimension at a time, 4 multiply-adds each: the other three entries of a
+// fibre sit in the lane's quad (x: DPP quad permutations), in its row of 16 lanes (y: DPP row
+// rotations by 4, 8, 12) and in the other rows (z: ds_bpermute).  f[k] is the factor entry for the
+// fibre element k places further on (cyclically).  All rows of the (at most 8) children are loaded
+// before the first is used: one round of memory latency per parent.
+template <int CTRL>
+__device__ inline float dpp_take(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+__device__ inline float fibre_x(float v, const float (&f)[4]) {
+    float o = f[0] * v;
+    o = fmaf(f[1], dpp_take<0x39>(v), o);    // quad_perm [1,2,3,0]
+    o = fmaf(f[2], dpp_take<0x4E>(v), o);    // quad_perm [2,3,0,1]
+    return fmaf(f[3], dpp_take<0x93>(v), o); // quad_perm [3,0,1,2]
+}
+
+__device__ inline float fibre_y(float v, const float (&f)[4]) {
+    float o = f[0] * v;
+    o = fmaf(f[1], dpp_take<0x12C>(v), o);    // row_ror:12 = the lane 4 further on in the row of 16
+    o = fmaf(f[2], dpp_take<0x128>(v), o);    // row_ror:8
+    return fmaf(f[3], dpp_take<0x124>(v), o); // row_ror:4
+}
+
+__device__ inline float fibre_z(float v, const float (&f)[4], int lane) {
+    float o = f[0] * v;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) o = fmaf(f[k], __shfl(v, (lane + 16 * k) & 63, 64), o);
+    return o;
+}
+
+// W_parent[i] = sum over children, sum_k T[half][i][k] (per dimension) W_child[k]
 __global__ __launch_bounds__(64) void m2m34_kernel(const uint32_t *__restrict__ cstart,
                                                    const uint32_t *__restrict__ child_key, int64_t nparents,
                                                    const float *__restrict__ T, const float *__restrict__ Wchild,
                                                    float *__restrict__ Wparent) {
+    __shared__ float tl[32];
     const int64_t P = block_index();
     if (P >= nparents) return;
-    const int i = threadIdx.x, ix = i & 3, iy = (i >> 2) & 3, iz = i >> 4;
-    float acc = 0.f;
-    const uint32_t c1 = cstart[P + 1];
-    for (uint32_t c = cstart[P]; c < c1; ++c) {
-        const uint32_t par = child_key[c] & 7u;   // bit d = upper half along dimension d
-        const float *Wc = Wchild + (int64_t)c * 64;   // wave-uniform
-        const float4 tx = *reinterpret_cast<const float4 *>(T + (par & 1) * 16 + ix * 4);
-        const float4 ty = *reinterpret_cast<const float4 *>(T + ((par >> 1) & 1) * 16 + iy * 4);
-        const float4 tz = *reinterpret_cast<const float4 *>(T + ((par >> 2) & 1) * 16 + iz * 4);
-        const float ax[4] = {tx.x, tx.y, tx.z, tx.w}, ay[4] = {ty.x, ty.y, ty.z, ty.w}, az[4] = {tz.x, tz.y, tz.z, tz.w};
-        float sz = 0.f;
-#pragma unroll
-        for (int kz = 0; kz < 4; ++kz) {
-            float sy = 0.f;
-#pragma unroll
-            for (int ky = 0; ky < 4; ++ky) {
-                float sx = 0.f;
-#pragma unroll
-                for (int kx = 0; kx < 4; ++kx) sx = fmaf(ax[kx], Wc[kx + 4 * ky + 16 * kz], sx);
-                sy = fmaf(ay[ky], sx, sy);
-            }
-            sz = fmaf(az[kz], sy, sz);
-        }
-        acc += sz;
+    const int lane = threadIdx.x, ix = lane & 3, iy = (lane >> 2) & 3, iz = lane >> 4;
+    const uint32_t c0 = cstart[P];
+    const int nc = min((int)(cstart[P + 1] - c0), 8);   // a box has at most 2^3 children
+    if (nc <= 0) {                                      // (boxes are never empty: cannot happen)
+        Wparent[P * 64 + lane] = 0.f;
+        return;
     }
-    Wparent[P * 64 + i] = acc;
+    if (lane < 32) tl[lane] = T[lane];
+    const uint32_t key = child_key[c0 + (uint32_t)min(lane, nc - 1)];
+    float w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w[j] = Wchild[(int64_t)(c0 + (uint32_t)min(j, nc - 1)) * 64 + lane];
+    __syncthreads();
+    float f[3][2][4];   // [dimension][half][k]: T[half][i][(i + k) & 3] with i the lane's node index in that dimension
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            f[0][h][k] = tl[h * 16 + ix * 4 + ((ix + k) & 3)];
+            f[1][h][k] = tl[h * 16 + iy * 4 + ((iy + k) & 3)];
+            f[2][h][k] = tl[h * 16 + iz * 4 + ((iz + k) & 3)];
+        }
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (j < nc) {
+            const uint32_t par = (uint32_t)__builtin_amdgcn_readlane((int)key, j) & 7u;   // bit d = upper half along d
+            float g[3][4];
+#pragma unroll
+            for (int d = 0; d < 3; ++d)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) g[d][k] = (par >> d) & 1u ? f[d][1][k] : f[d][0][k];
+            acc += fibre_z(fibre_y(fibre_x(w[j], g[0]), g[1]), g[2], lane);
+        }
+    }
+    Wparent[P * 64 + lane] = acc;
 }
 
-// one block (wavefront) per child, lane = child node k
-__global__ __launch_bounds__(64) void l2l34_kernel(const uint32_t *__restrict__ parent,
-                                                   const uint32_t *__restrict__ child_key, int64_t nchildren,
+// V_child[k] += sum_i T[half][i][k] (per dimension) V_parent[i], for every child of the parent
+__global__ __launch_bounds__(64) void l2l34_kernel(const uint32_t *__restrict__ cstart,
+                                                   const uint32_t *__restrict__ child_key, int64_t nparents,
                                                    const float *__restrict__ T, const float *__restrict__ Vparent,
                                                    float *__restrict__ Vchild) {
-    const int64_t c = block_index();
-    if (c >= nchildren) return;
-    const int k = threadIdx.x, kx = k & 3, ky = (k >> 2) & 3, kz = k >> 4;
-    const uint32_t par = child_key[c] & 7u;
-    const float *Tx = T + (par & 1) * 16 + kx, *Ty = T + ((par >> 1) & 1) * 16 + ky, *Tz = T + ((par >> 2) & 1) * 16 + kz;
-    float ax[4], ay[4], az[4];
+    __shared__ float tl[32];
+    const int64_t P = block_index();
+    if (P >= nparents) return;
+    const int lane = threadIdx.x, kx = lane & 3, ky = (lane >> 2) & 3, kz = lane >> 4;
+    const uint32_t c0 = cstart[P];
+    const int nc = min((int)(cstart[P + 1] - c0), 8);
+    if (nc <= 0) return;
+    if (lane < 32) tl[lane] = T[lane];
+    const uint32_t key = child_key[c0 + (uint32_t)min(lane, nc - 1)];
+    const float vp = Vparent[P * 64 + lane];
+    float vc[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { ax[i] = Tx[4 * i]; ay[i] = Ty[4 * i]; az[i] = Tz[4 * i]; }
-    const float *Vp = Vparent + (int64_t)parent[c] * 64;   // wave-uniform
-    float sz = 0.f;
+    for (int j = 0; j < 8; ++j) vc[j] = Vchild[(int64_t)(c0 + (uint32_t)min(j, nc - 1)) * 64 + lane];
+    __syncthreads();
+    float f[3][2][4];   // [dimension][half][j]: T[half][(k + j) & 3][k] with k the lane's node index in that dimension
 #pragma unroll
-    for (int iz = 0; iz < 4; ++iz) {
-        float sy = 0.f;
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-        for (int iy = 0; iy < 4; ++iy) {
-            float sx = 0.f;
-#pragma unroll
-            for (int ix = 0; ix < 4; ++ix) sx = fmaf(ax[ix], Vp[ix + 4 * iy + 16 * iz], sx);
-            sy = fmaf(ay[iy], sx, sy);
+        for (int j = 0; j < 4; ++j) {
+            f[0][h][j] = tl[h * 16 + ((kx + j) & 3) * 4 + kx];
+            f[1][h][j] = tl[h * 16 + ((ky + j) & 3) * 4 + ky];
+            f[2][h][j] = tl[h * 16 + ((kz + j) & 3) * 4 + kz];
         }
-        sz = fmaf(az[iz], sy, sz);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (j < nc) {
+            const uint32_t par = (uint32_t)__builtin_amdgcn_readlane((int)key, j) & 7u;
+            float g[3][4];
+#pragma unroll
+            for (int d = 0; d < 3; ++d)
+#pragma unroll
+                for (int k = 0; k < 4; ++k) g[d][k] = (par >> d) & 1u ? f[d][1][k] : f[d][0][k];
+            Vchild[(int64_t)(c0 + (uint32_t)j) * 64 + lane] = vc[j] + fibre_z(fibre_y(fibre_x(vp, g[0]), g[1]), g[2], lane);
+        }
     }
-    Vchild[c * 64 + k] += sz;
 }
 
 // ------------------------------------------------------------------------------------
@@ -1963,7 +2018,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
             f3m_level &lv = P.lev[l], &up = P.lev[l - 1];
             hipEvent_t *ev = level_events(l);
             F3M_HIP(hipEventRecord(ev[4], st));
-            l2l34_kernel<<<grid_for(lv.nb), dim3(64), 0, st>>>(lv.parent.p, lv.key.p, lv.nb, P.transfer.p, up.Vl.p, lv.Vl.p);
+            l2l34_kernel<<<grid_for(up.nb), dim3(64), 0, st>>>(up.cstart.p, lv.key.p, up.nb, P.transfer.p, up.Vl.p, lv.Vl.p);
             F3M_HIP(hipGetLastError());
             if (l < L) F3M_HIP(hipEventRecord(ev[5], st));
         }

@@ -164,7 +164,9 @@ def test_xy_with_the_same_set_twice_equals_the_one_set_plan():
             assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
     y1, y2 = one.kmvm(bd), two.kmvm(bd)
     torch.cuda.synchronize()
-    assert rel(y2.cpu().numpy(), y1.cpu().numpy()) <= 2e-6     # other kernels, the same sums
+    # other kernels, the same sums in another order: each result is within 3e-6 of the CPU F3M (1.1e-6 and
+    # 2.4e-6 measured), so the two differ by fp32 rounding only
+    assert rel(y2.cpu().numpy(), y1.cpu().numpy()) <= 4e-6
 
 
 def test_xy_edge_cases():
