@@ -80,6 +80,31 @@ __global__ __launch_bounds__(BBOX_NT) void bbox_kernel(const float *__restrict__
 // ------------------------------------------------------------------------------------
 struct AlphaArg { float a[F3M_MAX_DIM]; };
 
+// bit k of c -> bit k * D (c < 2^(32 / D))
+template <int D>
+__device__ inline uint32_t spread_bits(uint32_t c) {
+    if constexpr (D == 1) {
+        return c;
+    } else if constexpr (D == 2) {
+        c &= 0xFFFFu;
+        c = (c | (c << 8)) & 0x00FF00FFu;
+        c = (c | (c << 4)) & 0x0F0F0F0Fu;
+        c = (c | (c << 2)) & 0x33333333u;
+        return (c | (c << 1)) & 0x55555555u;
+    } else if constexpr (D == 3) {
+        c &= 0x3FFu;
+        c = (c | (c << 16)) & 0x030000FFu;
+        c = (c | (c << 8)) & 0x0300F00Fu;
+        c = (c | (c << 4)) & 0x030C30C3u;
+        return (c | (c << 2)) & 0x09249249u;
+    } else {
+        uint32_t r = 0;
+#pragma unroll
+        for (int k = 0; k < 32 / D; ++k) r |= ((c >> k) & 1u) << (k * D);
+        return r;
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void keys_kernel(const float *__restrict__ X, int64_t n, AlphaArg alpha, float s,
                                                    int Lq, uint32_t *__restrict__ keys) {
@@ -93,7 +118,7 @@ __global__ __launch_bounds__(256) void keys_kernel(const float *__restrict__ X, 
         float u = __fmul_rn(diff, s);
         uint32_t c = (uint32_t)u;
         c = c > cmax ? cmax : c;
-        for (int k = 0; k < Lq; ++k) key |= ((c >> k) & 1u) << (k * D + d);
+        key |= spread_bits<D>(c) << d;   // c < 2^Lq and Lq * D <= 32
     }
     keys[i] = key;
 }
@@ -497,6 +522,108 @@ __global__ __launch_bounds__(128) void lists_kernel(int pass, int64_t nb, const 
     }
 }
 
+// The same lists by parent (one point set, far rule only, D <= 3): the 2^D children of a parent
+// share their candidates, so one wavefront per parent enumerates them once, 64 to a step with a lane
+// per candidate, and tests them against every child.  The candidates of a round are the children
+// of up to 64 boxes near the parent, written into LDS in sequence order (lane = near box, running
+// sum of the child counts); ballots keep a child's near and far entries in that order.
+template <int D>
+__global__ __launch_bounds__(64) void lists_parent_kernel(int pass, int64_t nparents,
+                                                          const uint32_t *__restrict__ cstart,
+                                                          const int32_t *__restrict__ cell,
+                                                          const uint64_t *__restrict__ up_near_ptr,
+                                                          const uint32_t *__restrict__ up_near_col, ListArg A) {
+    constexpr int NC = 1 << D;   // children of a box, at most
+    __shared__ uint32_t cand[64 * NC];
+    const int64_t P = blockIdx.x;
+    if (P >= nparents) return;
+    const int lane = threadIdx.x;
+    const uint32_t a0 = cstart[P];
+    const int nt = min((int)(cstart[P + 1] - a0), NC);
+    if (nt <= 0) return;   // (boxes are never empty: cannot happen)
+    // lane t < nt holds the cell and the row offsets of child a0 + t
+    const uint32_t at = a0 + (uint32_t)min(lane, nt - 1);
+    int32_t tc[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) tc[d] = cell[(int64_t)at * D + d];
+    uint64_t nbase = 0, fbase = 0;
+    if (pass && A.near_ptr) nbase = A.near_ptr[at];
+    if (pass && A.far_ptr) fbase = A.far_ptr[at];
+    uint32_t nn[NC], nf[NC];   // entries so far per child (wave-uniform)
+#pragma unroll
+    for (int t = 0; t < NC; ++t) nn[t] = nf[t] = 0;
+    const uint64_t e0 = up_near_ptr[P], e1 = up_near_ptr[P + 1];
+    for (uint64_t er = e0; er < e1; er += 64) {
+        const int m = (int)(e1 - er < 64 ? e1 - er : 64);
+        uint32_t b0 = 0, nq = 0;
+        if (lane < m) {
+            const uint32_t Q = up_near_col[er + lane];
+            b0 = cstart[Q];
+            nq = min(cstart[Q + 1] - b0, (uint32_t)NC);
+        }
+        uint32_t cend = nq;   // inclusive running sum of the child counts over the lanes
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t up = __shfl_up(cend, d, 64);
+            if (lane >= d) cend += up;
+        }
+        const uint32_t cbeg = cend - nq;
+        const uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // candidates of this round, <= 64 NC
+        __syncthreads();   // the previous round has been read
+        for (uint32_t j = 0; j < nq; ++j) cand[cbeg + j] = b0 + j;
+        __syncthreads();
+        for (uint32_t w0 = 0; w0 < S; w0 += 64) {
+            const bool live = w0 + lane < S;
+            const uint32_t bq = live ? cand[w0 + lane] : 0u;   // (a lane beyond the sequence reads box 0, unused)
+            int32_t cc[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) cc[d] = A.cell_src[(int64_t)bq * D + d];
+#pragma unroll
+            for (int t = 0; t < NC; ++t) {
+                if (t < nt) {   // wave-uniform
+                    int d2 = 0;
+#pragma unroll
+                    for (int d = 0; d < D; ++d) {
+                        const int o = cc[d] - __builtin_amdgcn_readlane(tc[d], t);
+                        d2 += o * o;
+                    }
+                    const bool is_far = d2 >= A.T;
+                    const uint64_t mn = __ballot(live && !is_far), mf = __ballot(live && is_far);
+                    if (pass) {
+                        const uint64_t below = (1ull << lane) - 1ull;
+                        if (A.near_col && live && !is_far) {
+                            const uint64_t base = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(nbase >> 32), t) << 32) |
+                                                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)nbase, t);
+                            A.near_col[base + nn[t] + (uint32_t)__popcll(mn & below)] = bq;
+                        }
+                        if (A.far_col && live && is_far) {
+                            const uint64_t base = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(fbase >> 32), t) << 32) |
+                                                  (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)fbase, t);
+                            A.far_col[base + nf[t] + (uint32_t)__popcll(mf & below)] = bq;
+                        }
+                    }
+                    nn[t] += (uint32_t)__popcll(mn);
+                    nf[t] += (uint32_t)__popcll(mf);
+                }
+            }
+        }
+    }
+    if (!pass) {
+        uint32_t vn = 0, vf = 0;
+#pragma unroll
+        for (int t = 0; t < NC; ++t)
+            if (lane == t) { vn = nn[t]; vf = nf[t]; }
+        if (lane < nt) {
+            A.cnt_near[a0 + lane] = vn;
+            A.cnt_far[a0 + lane] = vf;
+            if (A.cnt_small) A.cnt_small[a0 + lane] = 0u;
+        }
+    }
+}
+
+// the rule of the depth is the plain far rule on one point set: the lists can be built by parent
+static bool lists_by_parent(const ListArg &A, int D) { return D <= 3 && !A.shifted && A.rho == 0 && A.mode == 0; }
+
 // the rule part of a list kernel argument for one depth of a plan
 static ListArg list_rules(const f3m_plan_s &P, int level) {
     const f3m_level &lv = P.lev[level], &sv = P.slev(level);
@@ -850,8 +977,17 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
             A.cnt_near = cn.p;
             A.cnt_far = cf.p;
             A.cnt_small = cs.p;
-            lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, sup.cstart.p, A);
+            if constexpr (D <= 3) {
+                if (lists_by_parent(A, D))
+                    lists_parent_kernel<D><<<dim3((unsigned)up.nb), dim3(64), 0, st>>>(0, up.nb, up.cstart.p, lv.cell.p,
+                                                                                       up.near_ptr.p, up.near_col.p, A);
+                else
+                    lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
+                                                                     up.near_col.p, sup.cstart.p, A);
+            } else {
+                lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
+                                                                 up.near_col.p, sup.cstart.p, A);
+            }
             F3M_HIP(hipGetLastError());
             uint64_t tn = 0, tf = 0, ts = 0;
             exclusive_scan(U32In{cn.p}, lv.nb, PtrOut{lv.near_ptr.p}, &tn, st);
@@ -885,8 +1021,17 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
             A.near_col = lv.near_col.p;
             A.far_col = lv.far_implicit ? nullptr : lv.far_col.p;
             A.small_col = lv.small_col.p;
-            lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
-                                                             up.near_col.p, sup.cstart.p, A);
+            if constexpr (D <= 3) {
+                if (lists_by_parent(A, D))
+                    lists_parent_kernel<D><<<dim3((unsigned)up.nb), dim3(64), 0, st>>>(1, up.nb, up.cstart.p, lv.cell.p,
+                                                                                       up.near_ptr.p, up.near_col.p, A);
+                else
+                    lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
+                                                                     up.near_col.p, sup.cstart.p, A);
+            } else {
+                lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
+                                                                 up.near_col.p, sup.cstart.p, A);
+            }
             F3M_HIP(hipGetLastError());
             F3M_HIP(hipStreamSynchronize(st));
         }
