@@ -2010,7 +2010,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         for (int l = P.tree_lmin; l <= L; ++l) {
             hipEvent_t *ev = level_events(l);
             F3M_HIP(hipEventRecord(ev[2], st));
-            if (!run_m2l_stencil(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st))
+            if (!run_m2l_stencil(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st, true))   // Wl ends with a row of zeros
                 fail(F3M_ERR_HIP, "internal: depth outside the candidate-grid M2L");
             F3M_HIP(hipEventRecord(ev[3], st));
         }

@@ -258,10 +258,14 @@ __global__ __launch_bounds__(256) void stencil_table_kernel(const uint64_t *__re
     }
 }
 
+// ZROW: W has a row of zeros behind its last box (index zero_row): an absent candidate (~0 in the table)
+// reads that row, which saves the compare-and-select pairs around every load.
+template <bool ZROW>
 __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t *__restrict__ cand_tab,
                                                                  const uint32_t *__restrict__ child_tab,
                                                                  int64_t nparents, int64_t per_xcd,
                                                                  const float *__restrict__ G, int all_far,
+                                                                 uint32_t zero_row,
                                                                  const float *__restrict__ W, float *__restrict__ V) {
     __shared__ float rows[ST_CAND * 64];
     __shared__ float xl[2 * 36 * 64];       // X_tx(cy, cz) at [(tx * 36 + cy + 6 cz) * 64 + node]
@@ -283,13 +287,20 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
     // per wavefront, all loads in flight together
     {
         float tmp[27];
+        if constexpr (ZROW) {
 #pragma unroll
-        for (int i = 0; i < 27; ++i) {
-            const uint32_t c = cand[w + 8 * i];
-            tmp[i] = W[(int64_t)(c == 0xFFFFFFFFu ? 0u : c) * 64 + lane];
+            for (int i = 0; i < 27; ++i) tmp[i] = W[(int64_t)min(cand[w + 8 * i], zero_row) * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < 27; ++i) rows[(w + 8 * i) * 64 + lane] = tmp[i];
+        } else {
+#pragma unroll
+            for (int i = 0; i < 27; ++i) {
+                const uint32_t c = cand[w + 8 * i];
+                tmp[i] = W[(int64_t)(c == 0xFFFFFFFFu ? 0u : c) * 64 + lane];
+            }
+#pragma unroll
+            for (int i = 0; i < 27; ++i) rows[(w + 8 * i) * 64 + lane] = cand[w + 8 * i] == 0xFFFFFFFFu ? 0.f : tmp[i];
         }
-#pragma unroll
-        for (int i = 0; i < 27; ++i) rows[(w + 8 * i) * 64 + lane] = cand[w + 8 * i] == 0xFFFFFFFFu ? 0.f : tmp[i];
     }
     __syncthreads();
     const int tx = w & 1, ty = (w >> 1) & 1, tz = w >> 2;
@@ -311,6 +322,24 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
             "v_fmac_f32_dpp %0, %1, %4 row_ror:8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
             "v_fmac_f32_dpp %0, %1, %5 row_ror:4 row_mask:0xf bank_mask:0xf bound_ctrl:1"
             : "+v"(out)
+            : "v"(v), "v"(f[0]), "v"(f[1]), "v"(f[2]), "v"(f[3]));
+    };
+    // the first application of a sum: out = ..., no zeroed accumulator to start from
+    auto xfirst = [&](float &out, float v, const float (&f)[4]) {
+        asm("v_mul_f32 %0, %2, %1\n\t"
+            "v_fmac_f32_dpp %0, %1, %3 quad_perm:[1,2,3,0] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %4 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %5 quad_perm:[3,0,1,2] row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "=&v"(out)
+            : "v"(v), "v"(f[0]), "v"(f[1]), "v"(f[2]), "v"(f[3]));
+    };
+    auto yfirst = [&](float &out, float v, const float (&f)[4]) {
+        asm("v_mul_f32 %0, %2, %1\n\t"
+            "s_nop 0\n\t"
+            "v_fmac_f32_dpp %0, %1, %3 row_ror:12 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %4 row_ror:8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+            "v_fmac_f32_dpp %0, %1, %5 row_ror:4 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "=&v"(out)
             : "v"(v), "v"(f[0]), "v"(f[1]), "v"(f[2]), "v"(f[3]));
     };
     int zlane[4];
@@ -338,9 +367,10 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
             float v[6];
 #pragma unroll
             for (int cx = 0; cx < 6; ++cx) v[cx] = rows[(cx + 6 * ln) * 64 + lane];
-            float line = 0.f;
+            float line;
+            xfirst(line, v[0], fx[0]);
 #pragma unroll
-            for (int cx = 0; cx < 6; ++cx) xapply(line, v[cx], fx[cx]);
+            for (int cx = 1; cx < 6; ++cx) xapply(line, v[cx], fx[cx]);
             xl[(tx * 36 + ln) * 64 + lane] = line;
         }
     }
@@ -356,9 +386,10 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
             float v[6];
 #pragma unroll
             for (int cy = 0; cy < 6; ++cy) v[cy] = xl[(tx * 36 + cy + 6 * cz) * 64 + lane];
-            float plane = 0.f;
+            float plane;
+            yfirst(plane, v[0], fy[0]);
 #pragma unroll
-            for (int cy = 0; cy < 6; ++cy) yapply(plane, v[cy], fy[cy]);
+            for (int cy = 1; cy < 6; ++cy) yapply(plane, v[cy], fy[cy]);
             yp[((w & 3) * 6 + cz) * 64 + lane] = plane;
         }
     }
@@ -399,9 +430,10 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
                 float v[3];
 #pragma unroll
                 for (int k1 = 0; k1 < 3; ++k1) v[k1] = rows[(base + k1) * 64 + lane];
-                float line = 0.f;
+                float line;
+                xfirst(line, v[0], nfx[0]);
 #pragma unroll
-                for (int k1 = 0; k1 < 3; ++k1) xapply(line, v[k1], nfx[k1]);
+                for (int k1 = 1; k1 < 3; ++k1) xapply(line, v[k1], nfx[k1]);
                 yapply(plane, line, nfy[k2]);
             }
             zapply(near, plane, nfz[k3]);
@@ -425,14 +457,18 @@ void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st) {
     F3M_HIP(hipGetLastError());
 }
 
-bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st) {
+bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st, bool zero_row) {
     if (!m2l_stencil_applies(P) || level < 1) return false;
     f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
     if (lv.gtab.p == nullptr || lv.gtab_omax != 3) return false;
     const int64_t per_xcd = cdiv(up.nb, 8);
     if (lv.st_cand.p) {   // no small field: the variant that shares the line and plane sums between the children
-        m2l_stencil_shared_kernel<<<grid2(per_xcd * 8), dim3(512), 0, st>>>(lv.st_cand.p, lv.st_child.p, up.nb, per_xcd,
-                                                                           lv.gtab.p, lv.smooth ? 1 : 0, W, V);
+        if (zero_row)   // W carries a row of zeros at index nb
+            m2l_stencil_shared_kernel<true><<<grid2(per_xcd * 8), dim3(512), 0, st>>>(
+                lv.st_cand.p, lv.st_child.p, up.nb, per_xcd, lv.gtab.p, lv.smooth ? 1 : 0, (uint32_t)lv.nb, W, V);
+        else
+            m2l_stencil_shared_kernel<false><<<grid2(per_xcd * 8), dim3(512), 0, st>>>(
+                lv.st_cand.p, lv.st_child.p, up.nb, per_xcd, lv.gtab.p, lv.smooth ? 1 : 0, 0u, W, V);
         F3M_HIP(hipGetLastError());
         return true;
     }

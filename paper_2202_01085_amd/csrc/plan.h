@@ -169,6 +169,6 @@ void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter,
 // m2l.hip
 bool m2l_stencil_applies(const f3m_plan_s &P);
 void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st);   // after the lists of the depth exist                   // D = 3, 4 nodes/dim, far ratio 2
-bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st);  // false: does not apply
+bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st, bool zero_row = false);  // false: does not apply
 
 }  // namespace f3m

@@ -1070,7 +1070,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         if (lv.far_sz == 0 || lv.p == 0) continue;   // nothing to interpolate, or dropped
         const bool tree = P.tree_lmin > 0 && k >= P.tree_lmin && k <= P.tree_lmax;
         if (tree) {
-            lv.Wl.alloc((size_t)lv.nb * lv.r, tally);
+            // one row of zeros behind the last box: what the candidate-grid M2L reads for an absent candidate
+            lv.Wl.alloc((size_t)(lv.nb + 1) * lv.r, tally);
+            F3M_HIP(hipMemsetAsync(lv.Wl.p + (size_t)lv.nb * lv.r, 0, (size_t)lv.r * sizeof(float), st));
             lv.Vl.alloc((size_t)lv.nb * lv.r, tally);
             if (k < P.tree_lmax) continue;   // only the last depth of the band needs chunks
         }
