@@ -42,11 +42,6 @@ bool m2l_stencil_applies(const f3m_plan_s &P) {
 // ------------------------------------------------------------------------------------
 constexpr int ST_CAND = 216;
 
-template <int CTRL>
-__device__ inline float dpp_quad(float v) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-
 __global__ __launch_bounds__(512) void m2l_stencil_kernel(const uint64_t *__restrict__ up_near_ptr,
                                                           const uint32_t *__restrict__ up_near_col,
                                                           const uint32_t *__restrict__ up_cstart,
