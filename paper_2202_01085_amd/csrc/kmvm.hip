@@ -1904,6 +1904,63 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         return ev;
     };
     const bool tree = P.tree_lmin > 0;   // D = 3, 4 nodes per dimension on depths tree_lmin..tree_lmax
+    // node weights of the source boxes of a depth, from the points, into P.W (the boxes its chunk list names)
+    auto p2m_depth = [&](int l) {
+        f3m_level &lv = P.lev[l];
+        f3m_level &sv = P.slev(l);
+        const int p = lv.p, r = lv.r;
+        const NodeArg N = make_nodes(p);
+        const CentreArg CS = make_centre(P, l, true);   // source grid
+        size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
+        if (D == 3 && p == 4)
+            p2m34_kernel<<<grid_for(cdiv(sv.nchunks, P2M_NCH)), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
+                                                                  sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
+                                                                  P.W.p, P.Wpart.p, single_chunks(sv));
+        else if (r <= 64)
+            p2m_kernel<D, 64><<<grid_for(sv.nchunks), dim3(64), sh, st>>>(
+                Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
+                P.W.p, P.Wpart.p);
+        else
+            p2m_kernel<D, 256><<<grid_for(sv.nchunks), dim3(256), sh, st>>>(
+                Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
+                P.W.p, P.Wpart.p);
+        F3M_HIP(hipGetLastError());
+        if (sv.max_box > P2M_CHUNK)   // some box has several chunks
+            reduce_partials(P, sv, r, P.W.p, st);
+        F3M_HIP(hipGetLastError());
+    };
+    // M2L of a depth from its far list, factor by factor; rows of V whose far row is empty are left alone
+    auto kron_m2l = [&](int l, const float *W, float *V) {
+        f3m_level &lv = P.lev[l];
+        f3m_level &sv = P.slev(l);
+        const int p = lv.p, r = lv.r;
+        const KronShape KS = kron_shape(P, l);
+        const int nfib = r / p;
+        const bool small = nfib <= 32;   // several far pairs per wavefront
+        const size_t sh = small ? (size_t)((64 / nfib) * r + D * KS.no * p * p) * sizeof(float) : (size_t)r * sizeof(float);
+        auto launch = [&](auto kern) {
+            kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
+                                                        lv.gtab.p, KS, W, V);
+        };
+        switch (small ? -p : p) {
+            case 2: launch(m2l_kron_kernel<2>); break;
+            case 3: launch(m2l_kron_kernel<3>); break;
+            case 4: launch(m2l_kron_kernel<4>); break;
+            case 5: launch(m2l_kron_kernel<5>); break;
+            case 6: launch(m2l_kron_kernel<6>); break;
+            case 7: launch(m2l_kron_kernel<7>); break;
+            case 8: launch(m2l_kron_kernel<8>); break;
+            case -2: launch(m2l_kron_small_kernel<2>); break;
+            case -3: launch(m2l_kron_small_kernel<3>); break;
+            case -4: launch(m2l_kron_small_kernel<4>); break;
+            case -5: launch(m2l_kron_small_kernel<5>); break;
+            case -6: launch(m2l_kron_small_kernel<6>); break;
+            case -7: launch(m2l_kron_small_kernel<7>); break;
+            case -8: launch(m2l_kron_small_kernel<8>); break;
+            default: fail(F3M_ERR_UNSUPPORTED, "interp_nodes must be in [2,8]");
+        }
+        F3M_HIP(hipGetLastError());
+    };
     // ---- depths that are handled on their own, straight from the points (Fig. 4 steps 1-3)
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
@@ -1913,58 +1970,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         const NodeArg N = make_nodes(p);
         hipEvent_t *ev = level_events(l);
         const CentreArg C = make_centre(P, l);          // target grid
-        const CentreArg CS = make_centre(P, l, true);   // source grid
-        f3m_level &sv = P.slev(l);                      // source boxes (lv itself for one point set)
         F3M_HIP(hipEventRecord(ev[0], st));
-        {
-            size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
-            if (D == 3 && p == 4)
-                p2m34_kernel<<<grid_for(cdiv(sv.nchunks, P2M_NCH)), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
-                                                                      sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
-                                                                      P.W.p, P.Wpart.p, single_chunks(sv));
-            else if (r <= 64)
-                p2m_kernel<D, 64><<<grid_for(sv.nchunks), dim3(64), sh, st>>>(
-                    Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
-                    P.W.p, P.Wpart.p);
-            else
-                p2m_kernel<D, 256><<<grid_for(sv.nchunks), dim3(256), sh, st>>>(
-                    Ys, bs, sv.start.p, sv.cell.p, sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, p, r, CS, N,
-                    P.W.p, P.Wpart.p);
-            F3M_HIP(hipGetLastError());
-            if (sv.max_box > P2M_CHUNK)   // some box has several chunks
-                reduce_partials(P, sv, r, P.W.p, st);
-            F3M_HIP(hipGetLastError());
-        }
+        p2m_depth(l);
         F3M_HIP(hipEventRecord(ev[1], st));
         F3M_HIP(hipEventRecord(ev[2], st));
-        if (!(lv.far_implicit && run_m2l_stencil(P, l, P.W.p, P.V.p, st))) {
-            const KronShape KS = kron_shape(P, l);
-            const int nfib = r / p;
-            const bool small = nfib <= 32;   // several far pairs per wavefront
-            const size_t sh = small ? (size_t)((64 / nfib) * r + D * KS.no * p * p) * sizeof(float) : (size_t)r * sizeof(float);
-            auto launch = [&](auto kern) {
-                kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
-                                                            lv.gtab.p, KS, P.W.p, P.V.p);
-            };
-            switch (small ? -p : p) {
-                case 2: launch(m2l_kron_kernel<2>); break;
-                case 3: launch(m2l_kron_kernel<3>); break;
-                case 4: launch(m2l_kron_kernel<4>); break;
-                case 5: launch(m2l_kron_kernel<5>); break;
-                case 6: launch(m2l_kron_kernel<6>); break;
-                case 7: launch(m2l_kron_kernel<7>); break;
-                case 8: launch(m2l_kron_kernel<8>); break;
-                case -2: launch(m2l_kron_small_kernel<2>); break;
-                case -3: launch(m2l_kron_small_kernel<3>); break;
-                case -4: launch(m2l_kron_small_kernel<4>); break;
-                case -5: launch(m2l_kron_small_kernel<5>); break;
-                case -6: launch(m2l_kron_small_kernel<6>); break;
-                case -7: launch(m2l_kron_small_kernel<7>); break;
-                case -8: launch(m2l_kron_small_kernel<8>); break;
-                default: fail(F3M_ERR_UNSUPPORTED, "interp_nodes must be in [2,8]");
-            }
-            F3M_HIP(hipGetLastError());
-        }
+        if (!(lv.far_implicit && run_m2l_stencil(P, l, P.W.p, P.V.p, st))) kron_m2l(l, P.W.p, P.V.p);
         F3M_HIP(hipEventRecord(ev[3], st));
         F3M_HIP(hipEventRecord(ev[4], st));
         {
@@ -1984,34 +1994,52 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     // ---- depths tree_lmin..tree_lmax: P2M at the last depth of the band, weights passed upward,
     //      M2L per depth, potentials passed downward, one L2P at the last depth of the band
     if (tree) {
+        // One point set: node weights from the points at the last depth of the band and upward from
+        // there.  Two point sets: only the targets' side uses the tree; the node weights of a depth come
+        // from the points of the source boxes that its far rows name (the sources' tree may hold many
+        // more boxes than are ever used, and a pass over all of them costs more than it saves).
         const int L = P.tree_lmax;
         const int r = 64;
         f3m_level &lf = P.lev[L];
-        {
-            hipEvent_t *ev = level_events(L);
-            F3M_HIP(hipEventRecord(ev[0], st));
-            p2m34_kernel<<<grid_for(cdiv(lf.nchunks, P2M_NCH)), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
-                                                                  lf.chunk_first.p, lf.nchunks, make_centre(P, L),
-                                                                  lf.Wl.p, P.Wpart.p, single_chunks(lf));
-            F3M_HIP(hipGetLastError());
-            if (lf.max_box > P2M_CHUNK)   // some box has several chunks
-                reduce_partials(P, lf, r, lf.Wl.p, st);
-            F3M_HIP(hipGetLastError());
-            F3M_HIP(hipEventRecord(ev[1], st));
-        }
-        for (int l = L - 1; l >= P.tree_lmin; --l) {
-            f3m_level &lv = P.lev[l], &dn = P.lev[l + 1];
-            hipEvent_t *ev = level_events(l);
-            F3M_HIP(hipEventRecord(ev[0], st));
-            m2m34_kernel<<<grid_for(lv.nb), dim3(64), 0, st>>>(lv.cstart.p, dn.key.p, lv.nb, P.transfer.p, dn.Wl.p, lv.Wl.p);
-            F3M_HIP(hipGetLastError());
-            F3M_HIP(hipEventRecord(ev[1], st));
+        if (!P.src) {
+            {
+                hipEvent_t *ev = level_events(L);
+                F3M_HIP(hipEventRecord(ev[0], st));
+                p2m34_kernel<<<grid_for(cdiv(lf.nchunks, P2M_NCH)), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
+                                                                      lf.chunk_first.p, lf.nchunks, make_centre(P, L),
+                                                                      lf.Wl.p, P.Wpart.p, single_chunks(lf));
+                F3M_HIP(hipGetLastError());
+                if (lf.max_box > P2M_CHUNK)   // some box has several chunks
+                    reduce_partials(P, lf, r, lf.Wl.p, st);
+                F3M_HIP(hipGetLastError());
+                F3M_HIP(hipEventRecord(ev[1], st));
+            }
+            for (int l = L - 1; l >= P.tree_lmin; --l) {
+                f3m_level &lv = P.lev[l], &dn = P.lev[l + 1];
+                hipEvent_t *ev = level_events(l);
+                F3M_HIP(hipEventRecord(ev[0], st));
+                m2m34_kernel<<<grid_for(lv.nb), dim3(64), 0, st>>>(lv.cstart.p, dn.key.p, lv.nb, P.transfer.p, dn.Wl.p, lv.Wl.p);
+                F3M_HIP(hipGetLastError());
+                F3M_HIP(hipEventRecord(ev[1], st));
+            }
         }
         for (int l = P.tree_lmin; l <= L; ++l) {
+            f3m_level &lv = P.lev[l];
             hipEvent_t *ev = level_events(l);
+            if (P.src) {
+                F3M_HIP(hipEventRecord(ev[0], st));
+                p2m_depth(l);
+                F3M_HIP(hipEventRecord(ev[1], st));
+            }
             F3M_HIP(hipEventRecord(ev[2], st));
-            if (!run_m2l_stencil(P, l, P.lev[l].Wl.p, P.lev[l].Vl.p, st, true))   // Wl ends with a row of zeros
-                fail(F3M_ERR_HIP, "internal: depth outside the candidate-grid M2L");
+            if (lv.far_implicit) {
+                if (!run_m2l_stencil(P, l, lv.Wl.p, lv.Vl.p, st, true))   // Wl ends with a row of zeros
+                    fail(F3M_ERR_HIP, "internal: depth outside the candidate-grid M2L");
+            } else {
+                // from the far list: the potentials of the boxes without far partners must read zero
+                zero_kernel<<<dim3((unsigned)cdiv(lv.nb * (int64_t)r, 256)), dim3(256), 0, st>>>(lv.Vl.p, lv.nb * (int64_t)r);
+                kron_m2l(l, P.src ? P.W.p : lv.Wl.p, lv.Vl.p);
+            }
             F3M_HIP(hipEventRecord(ev[3], st));
         }
         for (int l = P.tree_lmin + 1; l <= L; ++l) {

@@ -1053,7 +1053,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
     // depths, so only the last depth streams the points.
     // the band of depths with implicit far rows and 4 nodes per dimension (under the adaptive rule
     // the deepest depths may use 3 nodes and the coarsest may be dropped)
-    auto in_band = [&](int k) { return k >= 2 && P.lev[k].far_sz > 0 && P.lev[k].far_implicit && P.lev[k].p == 4; };
+    // (with 4 nodes per dimension in 3-D; the M2L of a depth in the band is the candidate-grid one where
+    // that applies, else the one that works from the far list: two point sets, other far ratios)
+    auto in_band = [&](int k) { return D == 3 && k >= 2 && P.lev[k].far_sz > 0 && P.lev[k].p == 4; };
     for (int k = P.L; k >= 2 && P.tree_lmax == 0; --k)
         if (in_band(k)) P.tree_lmax = k;
     if (P.tree_lmax > 0) {
@@ -1069,16 +1071,22 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         f3m_level &lv = P.lev[k];
         if (lv.far_sz == 0 || lv.p == 0) continue;   // nothing to interpolate, or dropped
         const bool tree = P.tree_lmin > 0 && k >= P.tree_lmin && k <= P.tree_lmax;
-        if (tree) {
-            // one row of zeros behind the last box: what the candidate-grid M2L reads for an absent candidate
-            lv.Wl.alloc((size_t)(lv.nb + 1) * lv.r, tally);
-            F3M_HIP(hipMemsetAsync(lv.Wl.p + (size_t)lv.nb * lv.r, 0, (size_t)lv.r * sizeof(float), st));
-            lv.Vl.alloc((size_t)lv.nb * lv.r, tally);
-            if (k < P.tree_lmax) continue;   // only the last depth of the band needs chunks
-        }
-        // runs of points for the L2P (targets) and the P2M (sources: the same runs for one point set)
-        build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
         f3m_level &sv = P.slev(k);
+        if (tree) {
+            // Node potentials are passed down the targets' tree.  One point set: node weights are passed up
+            // the same tree, and carry one row of zeros behind the last box (what the candidate-grid M2L reads
+            // for an absent candidate).  Two point sets: the node weights of every depth come from the points.
+            lv.Vl.alloc((size_t)lv.nb * lv.r, tally);
+            if (!P.src) {
+                lv.Wl.alloc((size_t)(lv.nb + 1) * lv.r, tally);
+                F3M_HIP(hipMemsetAsync(lv.Wl.p + (size_t)lv.nb * lv.r, 0, (size_t)lv.r * sizeof(float), st));
+                if (k < P.tree_lmax) continue;   // only the last depth of the band needs chunks
+            }
+        }
+        // runs of points for the L2P (targets: in the band only its last depth) and the P2M (sources: the
+        // same runs for one point set)
+        if (!tree || k == P.tree_lmax)
+            build_chunks(lv.start.p, lv.nb, P2M_CHUNK, lv.chunk_first, lv.chunk_box, lv.nchunks, tally, st);
         if (P.src) {
             // Only the source boxes that occur in a far row of this depth need node weights (the two sets
             // may overlap in a small part of the sources' cube only).
@@ -1097,10 +1105,8 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
             build_chunks(sv.chunk_first.p, sv.nb, P2M_SLICE, sv.slice_first, sv.slice_box, sv.nslices, tally, st);
             max_slice = std::max(max_slice, sv.nslices * (int64_t)lv.r);
         }
-        if (!tree) {
-            max_w = std::max(max_w, sv.nb * (int64_t)lv.r);
-            max_v = std::max(max_v, lv.nb * (int64_t)lv.r);
-        }
+        if (!tree || P.src) max_w = std::max(max_w, sv.nb * (int64_t)lv.r);
+        if (!tree) max_v = std::max(max_v, lv.nb * (int64_t)lv.r);
         max_part = std::max(max_part, sv.nchunks * (int64_t)lv.r);
     }
     {

@@ -95,6 +95,7 @@ XY_CASES = [
     (8_000, 8_000, 2, "normal", "normal", 1.5, 0.2, 6, 0.3, 2.0, 32, 0, 0, 0.0, False),
     (9_000, 7_000, 3, "normal", "uniform", 3.0, -1.5, 3, 0.8, 1.5, 40, 0, 0, 0.0, False),    # far ratio 1.5
     (6_000, 6_000, 3, "uniform", "normal", 0.4, 0.5, 2, 0.8, 3.0, 40, 0, 0, 0.0, False),     # far ratio 3
+    (9_000, 8_000, 3, "uniform", "normal", 0.4, 0.5, 4, 0.6, 1.5, 24, 0, 0, 0.0, False),     # 4 nodes, far ratio 1.5
     (6_000, 5_000, 4, "uniform", "normal", 0.4, 0.5, 3, 1.0, 2.0, 50, 2, 0, 0.0, False),
     (4_000, 4_500, 5, "uniform", "normal", 0.4, 0.5, 2, 1.0, 2.0, 60, 2, 0, 0.0, False),
     (3_000, 3_500, 7, "mixture", "mixture", 1.0, 0.5, 2, 2.5, 2.0, 100, 1, 0, 0.0, False),
