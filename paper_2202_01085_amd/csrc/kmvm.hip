@@ -1843,7 +1843,7 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         if (gram && D == 3 && ntiles > 0 && ntiles < 8192 && lv.nb > 0 && P.slev(l).nb > 0) {
             const double row_sources = (double)(cols == lv.near_col.p ? lv.near_sz : lv.small_sz) / (double)lv.nb *
                                        ((double)P.ns() / (double)P.slev(l).nb);   // average sources of a tile
-            nsplit = (int)std::min<double>(std::min<double>(64.0, (double)cdiv(32768, ntiles)), row_sources / 2048.0);
+            nsplit = (int)std::min<double>(std::min<double>(64.0, (double)cdiv(262144, ntiles)), row_sources / 2048.0);
             if (nsplit < 2) nsplit = 1;
         }
         if (nsplit > 1) {

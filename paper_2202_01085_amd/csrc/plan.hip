@@ -1111,7 +1111,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
     }
     {
         const f3m_level &lf = P.lev[P.L];
-        const uint32_t ts = (uint32_t)overflow_targets(D);
+        // Few boxes: rows are long, and the near field splits every tile over several wavefronts; an overflow
+        // tile would leave its whole row to one wavefront, so there are none (every run is a tile of its own).
+        const uint32_t ts = lf.nb < 8192 ? 0u : (uint32_t)overflow_targets(D);
         build_items(BigTileCountIn{lf.start.p, ts}, lf.nb, P.tile_first, P.tile_box, P.ntiles, tally, st);
         build_items(OverflowTileCountIn{lf.start.p, ts}, lf.nb, P.otile_first, P.otile_box, P.notiles, tally, st);
     }
