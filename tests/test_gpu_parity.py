@@ -114,6 +114,9 @@ PLAN_CASES = [
     # 4 nodes per dimension with other far ratios: weights and potentials pass through the tree, M2L from the far lists
     (9_000, 3, "normal", 4, 0.8, 1.5, 40, 0),
     (12_000, 3, "uniform", 4, 0.6, 3.0, 24, 0),
+    # more than 8192 leaf boxes (depth 5, about 9 points per box): the near field has overflow tiles
+    # (boxes of at most 10 points) beside the tiles of the Gram kernel, as at the full sizes
+    (300_000, 3, "uniform", 4, 0.5, 2.0, 40, 0),
     (6_000, 4, "uniform", 3, 1.0, 2.0, 50, 2),
     (4_000, 5, "uniform", 2, 1.0, 2.0, 60, 2),
     (6_000, 7, "mixture", 2, 1.5, 2.0, 100, 1),
