@@ -83,6 +83,19 @@ constexpr int SCAN_NT = 256;
 constexpr int SCAN_IPT = 8;
 constexpr int SCAN_TILE = SCAN_NT * SCAN_IPT;
 
+// inclusive running sum over the 64 lanes of a wavefront, every lane active: four shifts inside the
+// rows of 16 lanes, then the row totals are passed on (lane 15 of a row to the next row, lane 31 to
+// the upper half); a lane outside the source range adds zero
+__device__ inline uint32_t wave_incl_scan_u32(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1 and 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
 __device__ inline uint64_t wave_incl_scan_u64(uint64_t v, int lane) {
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {

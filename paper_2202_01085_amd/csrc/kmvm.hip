@@ -216,6 +216,20 @@ __device__ inline h8v split_source4(const float (&w)[4], int h) {
     return __builtin_bit_cast(h8v, r);
 }
 
+// target operand for four components (D = 3): the same layout as split_operand<4, false>, built
+// from packed pairs.  Lane half 0 holds (hi, lo), lane half 1 (hi, 0).
+__device__ inline h8v split_target4(const float (&u)[4], int h) {
+    const uint32_t hi01 = pack_f16(u[0], u[1]), hi23 = pack_f16(u[2], u[3]);
+    const f2v b01 = unpack_f16(hi01), b23 = unpack_f16(hi23);
+    const uint32_t lo01 = pack_f16(u[0] - b01.x, u[1] - b01.y), lo23 = pack_f16(u[2] - b23.x, u[3] - b23.y);
+    u4v r;
+    r.x = hi01;
+    r.y = hi23;
+    r.z = h ? 0u : lo01;
+    r.w = h ? 0u : lo23;
+    return __builtin_bit_cast(h8v, r);
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void p2p_mfma_kernel(const float *__restrict__ Xt,
                                                        const uint32_t *__restrict__ startT,
@@ -442,7 +456,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         }
         u[D] = 1.f;
         ni[cb] = -g * s;
-        Bop[cb] = split_operand<NC, false>(u, 0, kk);
+        Bop[cb] = split_target4(u, kk);
     }
     float acc0 = 0.f, acc1 = 0.f;
     float accm0[MB], accm1[MB];   // MB > 1: one pair of accumulators per right-hand side
@@ -539,12 +553,7 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             sfirst = start[q];
             slen = start[q + 1] - sfirst;
         }
-        uint32_t cend = slen;   // inclusive running sum of the lengths over the lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t up = __shfl_up(cend, d, 64);
-            if (lane >= d) cend += up;
-        }
+        const uint32_t cend = wave_incl_scan_u32(slen);   // inclusive running sum of the lengths over the lanes
         const uint32_t cbeg = cend - slen;
         const uint32_t delta = sfirst - cbeg;   // position -> source index inside this lane's box (mod 2^32)
         uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // sources of this round
@@ -711,12 +720,7 @@ __global__ __launch_bounds__(256) void p2p_small_kernel(const float *__restrict_
             sfirst = start[q];
             slen = start[q + 1] - sfirst;
         }
-        uint32_t cend = slen;   // inclusive running sum of the lengths over the lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t up = __shfl_up(cend, d, 64);
-            if (lane >= d) cend += up;
-        }
+        const uint32_t cend = wave_incl_scan_u32(slen);   // inclusive running sum of the lengths over the lanes
         const uint32_t cbeg = cend - slen;
         const uint32_t delta = sfirst - cbeg;   // position -> source index inside this lane's box (mod 2^32)
         const uint32_t S = __builtin_amdgcn_readlane(cend, 63);

@@ -561,12 +561,7 @@ __global__ __launch_bounds__(64) void lists_parent_kernel(int pass, int64_t npar
             b0 = cstart[Q];
             nq = min(cstart[Q + 1] - b0, (uint32_t)NC);
         }
-        uint32_t cend = nq;   // inclusive running sum of the child counts over the lanes
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const uint32_t up = __shfl_up(cend, d, 64);
-            if (lane >= d) cend += up;
-        }
+        const uint32_t cend = wave_incl_scan_u32(nq);   // inclusive running sum of the child counts over the lanes
         const uint32_t cbeg = cend - nq;
         const uint32_t S = __builtin_amdgcn_readlane(cend, 63);   // candidates of this round, <= 64 NC
         __syncthreads();   // the previous round has been read
