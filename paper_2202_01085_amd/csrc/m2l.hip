@@ -269,7 +269,8 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
     // (two workgroups per compute unit fit only below 80 KB each)
     uint32_t *cand = reinterpret_cast<uint32_t *>(xl);
     __shared__ float gs[7 * 16];            // the factor table
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // (the wavefront's number in a scalar register: the row addresses are then formed by scalar instructions)
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     // consecutive parents (neighbours in space) on the same XCD, so that its L2 serves the overlap
     const int64_t bi = block_index2();
     const int64_t pb = (bi & 7) * per_xcd + (bi >> 3);
