@@ -440,14 +440,22 @@ __global__ __launch_bounds__(512) void m2l_stencil_shared_kernel(const uint32_t 
 }
 
 // candidate and child tables of a depth whose M2L runs on the candidate grid without a small field
-void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st) {
-    if (!m2l_stencil_applies(P) || level < 1 || P.rho != 0) return;
+// the tables of a depth, preset to "none"; false: the depth does not use them
+bool stencil_tables_alloc(f3m_plan_s &P, int level, hipStream_t st) {
+    if (!m2l_stencil_applies(P) || level < 1 || P.rho != 0) return false;
     f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
-    if (!lv.far_implicit || lv.far_sz == 0 || lv.p == 0) return;
+    if (!lv.far_implicit || lv.far_sz == 0 || lv.p == 0) return false;
     lv.st_cand.alloc((size_t)up.nb * ST_CAND, &P.bytes);
     lv.st_child.alloc((size_t)up.nb * 8, &P.bytes);
     F3M_HIP(hipMemsetAsync(lv.st_cand.p, 0xFF, (size_t)up.nb * ST_CAND * sizeof(uint32_t), st));
     F3M_HIP(hipMemsetAsync(lv.st_child.p, 0xFF, (size_t)up.nb * 8 * sizeof(uint32_t), st));
+    return true;
+}
+
+void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st) {
+    if (level >= 1 && P.lev[level].st_cand.p) return;   // written by the list kernel already
+    if (!stencil_tables_alloc(P, level, st)) return;
+    f3m_level &lv = P.lev[level], &up = P.lev[level - 1];
     stencil_table_kernel<<<grid2(up.nb), dim3(256), 0, st>>>(up.near_ptr.p, up.near_col.p, up.cstart.p, up.cell.p,
                                                             lv.cell.p, lv.key.p, up.nb, lv.st_cand.p, lv.st_child.p);
     F3M_HIP(hipGetLastError());

@@ -168,7 +168,8 @@ void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter,
             float *history_host, hipStream_t st);
 // m2l.hip
 bool m2l_stencil_applies(const f3m_plan_s &P);
-void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st);   // after the lists of the depth exist                   // D = 3, 4 nodes/dim, far ratio 2
+void build_stencil_tables(f3m_plan_s &P, int level, hipStream_t st);
+bool stencil_tables_alloc(f3m_plan_s &P, int level, hipStream_t st);   // false: the depth has no such tables   // after the lists of the depth exist                   // D = 3, 4 nodes/dim, far ratio 2
 bool run_m2l_stencil(f3m_plan_s &P, int level, const float *W, float *V, hipStream_t st, bool zero_row = false);  // false: does not apply
 
 }  // namespace f3m

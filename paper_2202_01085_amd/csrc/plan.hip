@@ -461,6 +461,10 @@ struct ListArg {
     uint32_t *cnt_near, *cnt_far, *cnt_small;         // pass 0: row lengths
     const uint64_t *near_ptr, *far_ptr, *small_ptr;   // pass 1: row offsets
     uint32_t *near_col, *far_col, *small_col;         // pass 1: columns (null: that list is not written)
+    // pass 1 of the by-parent kernel, D = 3, far ratio 2: the tables of the candidate-grid M2L (or null):
+    // [parent][216] rank of the candidate at each position of the 6 x 6 x 6 grid around the parent,
+    // [parent][8] the child of each parity (both preset to ~0)
+    uint32_t *st_cand, *st_child;
 };
 
 // up_cstart: children intervals of the SOURCE-side boxes one depth up
@@ -573,6 +577,22 @@ __global__ __launch_bounds__(64) void lists_parent_kernel(int pass, int64_t npar
             int32_t cc[D];
 #pragma unroll
             for (int d = 0; d < D; ++d) cc[d] = A.cell_src[(int64_t)bq * D + d];
+            if constexpr (D == 3) {
+                if (pass && A.st_cand && live) {
+                    // grid position of the candidate: its cell minus twice the parent's cell, plus 2 (a box near
+                    // the parent is within one cell of it, so every coordinate lies in [0, 6))
+                    int pos = 0, mul = 1;
+                    bool inside = true;
+#pragma unroll
+                    for (int d = 0; d < D; ++d) {
+                        const int q = cc[d] - 2 * (__builtin_amdgcn_readlane(tc[d], 0) >> 1) + 2;
+                        inside = inside && q >= 0 && q < 6;
+                        pos += q * mul;
+                        mul *= 6;
+                    }
+                    if (inside) A.st_cand[P * 216 + pos] = bq;
+                }
+            }
 #pragma unroll
             for (int t = 0; t < NC; ++t) {
                 if (t < nt) {   // wave-uniform
@@ -602,6 +622,10 @@ __global__ __launch_bounds__(64) void lists_parent_kernel(int pass, int64_t npar
                 }
             }
         }
+    }
+    if constexpr (D == 3) {
+        if (pass && A.st_child && lane < nt)   // the child of each parity (bit d = upper half along dimension d)
+            A.st_child[P * 8 + ((tc[0] & 1) | ((tc[1] & 1) << 1) | ((tc[2] & 1) << 2))] = a0 + (uint32_t)lane;
     }
     if (!pass) {
         uint32_t vn = 0, vf = 0;
@@ -1016,6 +1040,13 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
             A.near_col = lv.near_col.p;
             A.far_col = lv.far_implicit ? nullptr : lv.far_col.p;
             A.small_col = lv.small_col.p;
+            if constexpr (D == 3) {
+                // the tables of the candidate-grid M2L come out of the same enumeration
+                if (lists_by_parent(A, D) && lv.far_implicit && lv.p != 0 && stencil_tables_alloc(P, l, st)) {
+                    A.st_cand = lv.st_cand.p;
+                    A.st_child = lv.st_child.p;
+                }
+            }
             if constexpr (D <= 3) {
                 if (lists_by_parent(A, D))
                     lists_parent_kernel<D><<<dim3((unsigned)up.nb), dim3(64), 0, st>>>(1, up.nb, up.cstart.p, lv.cell.p,
