@@ -208,6 +208,24 @@ f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthsc
                                 double *y64, void *stream);
 
 /*
+ * direct_kmvm_rows_f64_static - direct_kmvm_rows_f64 for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels, the same slicing of the sources and therefore the same bits in y64, but the partial sums
+ * of the slices live in a static device array of the library (32 MiB per device: 256 slices x 16384
+ * rows of doubles) instead of an allocation.  The call allocates and frees nothing and does not wait
+ * for the device: it only enqueues two kernels on `stream`.
+ *   Arguments as direct_kmvm_rows_f64, with m <= 16384; a larger m returns F3M_ERR_UNSUPPORTED and
+ *   enqueues nothing.
+ *   Every call on a device shares that device's array: two calls that overlap in time on one device
+ *   (different streams, or different threads) race on it and give wrong sums; calls on one stream are
+ *   ordered and safe.  Nothing needs clearing between calls (every partial sum that is read is
+ *   written first by the same call).
+ */
+f3m_status direct_kmvm_rows_f64_static(const float *X, int64_t n, int D, float lengthscale,
+                                       const float *b, const int64_t *rows, int64_t m,
+                                       double *y64, void *stream);
+
+/*
  * direct_kmvm_xy / direct_kmvm_xy_rows_f64 - the same exact sums for two point sets,
  * y_i = sum_j k(x_i, y_j) b_j (Sec. 2): X device nx x D, Y device ny x D, b device fp32[ny],
  * y device fp32[nx]; rows device int64[m], each in [0,nx); y64 device double[m].

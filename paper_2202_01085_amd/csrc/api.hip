@@ -189,6 +189,17 @@ f3m_status direct_kmvm_rows_f64(const float *X, int64_t n, int D, float lengthsc
     return guarded([&] { f3m::run_direct_rows_f64(X, X, n, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
 }
 
+f3m_status direct_kmvm_rows_f64_static(const float *X, int64_t n, int D, float lengthscale, const float *b,
+                                       const int64_t *rows, int64_t m, double *y64, void *stream) {
+    f3m_status st = check_problem(X, n, D, lengthscale);
+    if (st != F3M_OK) return st;
+    if (m < 0) return set_error(F3M_ERR_INVALID_ARG, "m must be >= 0");
+    if (m == 0) return F3M_OK;
+    if (n == 0) return set_error(F3M_ERR_INVALID_ARG, "rows requested of an empty problem");
+    if (!b || !rows || !y64) return set_error(F3M_ERR_INVALID_ARG, "b, rows or y64 is null");
+    return guarded([&] { f3m::run_direct_rows_f64_static(X, n, D, lengthscale, b, rows, m, y64, (hipStream_t)stream); });
+}
+
 f3m_status direct_kmvm_xy_rows_f64(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float lengthscale,
                                    const float *b, const int64_t *rows, int64_t m, double *y64, void *stream) {
     f3m_status st = check_problem(X, nx, D, lengthscale);

@@ -5,9 +5,37 @@
 #include <algorithm>
 #include <cmath>
 
+#include <mutex>
+
 #include "plan.h"
 
+// Partial sums of direct_kmvm_rows_f64_static, for callers that may not allocate: up to 256 source
+// slices of up to 16384 rows (32 MiB, held on every device the library runs on until the process
+// ends).  Host code never uses this name as an address: it asks for the array's address on the
+// current device once per device (rows_static_scratch) and passes that pointer to the kernels.
+constexpr int ROWS_MAX_SLICES = 256;
+constexpr int64_t ROWS_STATIC_MAX_M = 16384;
+static __device__ __align__(256) double scratch[(size_t)ROWS_MAX_SLICES * (size_t)ROWS_STATIC_MAX_M];
+
 namespace f3m {
+
+// address of `scratch` on the current device (every device holds its own copy at its own address)
+static double *rows_static_scratch() {
+    constexpr int MAX_DEVICES = 64;
+    static std::mutex mu;
+    static double *ptr[MAX_DEVICES] = {};
+    int dev = 0;
+    F3M_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) fail(F3M_ERR_UNSUPPORTED, "device ordinal above 63");
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        double *q = nullptr;
+        F3M_HIP(hipGetSymbolAddress((void **)&q, HIP_SYMBOL(scratch)));
+        if (!q) fail(F3M_ERR_HIP, "hipGetSymbolAddress gave a null address for the static scratch");
+        ptr[dev] = q;
+    }
+    return ptr[dev];
+}
 
 constexpr int P_MAX = 8;  // interpolation nodes per dimension supported by the kernels
 
@@ -2187,32 +2215,50 @@ void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, f
     }
 }
 
+static int rows_slices(int64_t n) { return (int)std::max<int64_t>(1, std::min<int64_t>(ROWS_MAX_SLICES, n / 4096)); }
+
+// part: slices * m doubles of scratch, every entry of which the first kernel writes
 template <int D>
 static void run_rows_d(const float *X, const float *Y, int64_t n, float gamma, const float *b, const int64_t *rows,
-                       int64_t m, double *y64, hipStream_t st) {
+                       int64_t m, double *y64, double *part, hipStream_t st) {
     const double nc = -1.0 / (2.0 * (double)gamma * (double)gamma);
-    const int slices = (int)std::max<int64_t>(1, std::min<int64_t>(256, n / 4096));
-    DevBuf<double> part;
-    part.alloc((size_t)slices * (size_t)m);
-    rows_f64_kernel<D><<<dim3((unsigned)cdiv(m, 64), (unsigned)slices), dim3(64), 0, st>>>(X, Y, b, n, rows, m, nc, part.p);
+    const int slices = rows_slices(n);
+    rows_f64_kernel<D><<<dim3((unsigned)cdiv(m, 64), (unsigned)slices), dim3(64), 0, st>>>(X, Y, b, n, rows, m, nc, part);
     F3M_HIP(hipGetLastError());
-    rows_f64_sum_kernel<<<dim3((unsigned)cdiv(m, 256)), dim3(256), 0, st>>>(part.p, m, slices, y64);
+    rows_f64_sum_kernel<<<dim3((unsigned)cdiv(m, 256)), dim3(256), 0, st>>>(part, m, slices, y64);
     F3M_HIP(hipGetLastError());
-    F3M_HIP(hipStreamSynchronize(st));  // `part` is released on return
+}
+
+static void run_rows(const float *X, const float *Y, int64_t ny, int D, float gamma, const float *b,
+                     const int64_t *rows, int64_t m, double *y64, double *part, hipStream_t st) {
+    switch (D) {
+        case 1: run_rows_d<1>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        case 2: run_rows_d<2>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        case 3: run_rows_d<3>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        case 4: run_rows_d<4>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        case 5: run_rows_d<5>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        case 6: run_rows_d<6>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        case 7: run_rows_d<7>(X, Y, ny, gamma, b, rows, m, y64, part, st); break;
+        default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
+    }
 }
 
 void run_direct_rows_f64(const float *X, const float *Y, int64_t ny, int D, float gamma, const float *b,
                          const int64_t *rows, int64_t m, double *y64, hipStream_t st) {
-    switch (D) {
-        case 1: run_rows_d<1>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        case 2: run_rows_d<2>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        case 3: run_rows_d<3>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        case 4: run_rows_d<4>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        case 5: run_rows_d<5>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        case 6: run_rows_d<6>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        case 7: run_rows_d<7>(X, Y, ny, gamma, b, rows, m, y64, st); break;
-        default: fail(F3M_ERR_INVALID_ARG, "D must be in [1,7]");
-    }
+    DevBuf<double> part;
+    part.alloc((size_t)rows_slices(ny) * (size_t)m);
+    run_rows(X, Y, ny, D, gamma, b, rows, m, y64, part.p, st);
+    F3M_HIP(hipStreamSynchronize(st));  // `part` is released on return
+}
+
+// The same sums with the partial results in the library's static device array instead of an
+// allocation: nothing here allocates or frees, and nothing waits for the device.
+void run_direct_rows_f64_static(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
+                                int64_t m, double *y64, hipStream_t st) {
+    if (m > ROWS_STATIC_MAX_M)
+        fail(F3M_ERR_UNSUPPORTED, "direct_kmvm_rows_f64_static: m = " + std::to_string(m) + " rows exceed the limit of " +
+                                      std::to_string(ROWS_STATIC_MAX_M) + " (the static scratch holds 256 slices of that many)");
+    run_rows(X, X, n, D, gamma, b, rows, m, y64, rows_static_scratch(), st);
 }
 
 }  // namespace f3m

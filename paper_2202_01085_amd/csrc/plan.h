@@ -161,6 +161,9 @@ void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, f
                 hipStream_t st);
 void run_direct_rows_f64(const float *X, const float *Y, int64_t ny, int D, float gamma, const float *b,
                          const int64_t *rows, int64_t m, double *y64, hipStream_t st);
+// the same with the partial sums in a static device array: no allocation, no wait (m <= 16384)
+void run_direct_rows_f64_static(const float *X, int64_t n, int D, float gamma, const float *b, const int64_t *rows,
+                                int64_t m, double *y64, hipStream_t st);
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of every far depth
 // solve.hip: conjugate gradients for (K + lambda I) x = b on a one-set plan (synchronises)

@@ -87,6 +87,7 @@ def lib():
         L.f3m_plan_get_source_boxes.argtypes = [vp, ci, vp, vp]
         L.direct_kmvm.argtypes = [vp, i64, ci, cf, vp, vp, vp]
         L.direct_kmvm_rows_f64.argtypes = [vp, i64, ci, cf, vp, vp, i64, vp, vp]
+        L.direct_kmvm_rows_f64_static.argtypes = [vp, i64, ci, cf, vp, vp, i64, vp, vp]
         L.f3m_destroy.argtypes = [vp]
         L.f3m_destroy.restype = None
         L.f3m_trim_memory.argtypes = []
@@ -102,7 +103,8 @@ def lib():
         for name in ("f3m_plan", "f3m_plan_ex", "f3m_kmvm", "direct_kmvm", "direct_kmvm_rows_f64", "f3m_plan_info",
                      "f3m_plan_get_perm", "f3m_plan_get_point_keys", "f3m_plan_get_boxes", "f3m_plan_get_list",
                      "f3m_stage_times", "f3m_level_times", "f3m_plan_xy", "direct_kmvm_xy", "direct_kmvm_xy_rows_f64",
-                     "f3m_plan_source_info", "f3m_plan_get_source_perm", "f3m_plan_get_source_boxes"):
+                     "f3m_plan_source_info", "f3m_plan_get_source_perm", "f3m_plan_get_source_boxes",
+                     "direct_kmvm_rows_f64_static"):
             getattr(L, name).restype = ci
         _lib = L
     return _lib
@@ -288,6 +290,20 @@ def direct_kmvm_rows_f64(X, b, lengthscale, rows, stream=None):
     _check(lib().direct_kmvm_rows_f64(_dev_f32(X, "X"), int(n), int(D), float(lengthscale), _dev_f32(b, "b"),
                                       ctypes.c_void_p(rows.data_ptr()), int(rows.numel()),
                                       ctypes.c_void_p(y64.data_ptr()), _stream(stream)))
+    return y64
+
+
+def direct_kmvm_rows_f64_static(X, b, lengthscale, rows, y64, stream=None):
+    """direct_kmvm_rows_f64_static: the same sums into the caller's y64 (device float64, one entry per row);
+    the library call allocates nothing (at most 16384 rows).  rows: device int64 tensor."""
+    n, D = X.shape
+    if not (rows.is_cuda and rows.dtype == torch.int64 and rows.is_contiguous()):
+        raise TypeError("rows must be a contiguous int64 device tensor")
+    if not (y64.is_cuda and y64.dtype == torch.float64 and y64.is_contiguous() and y64.numel() >= rows.numel()):
+        raise TypeError("y64 must be a contiguous float64 device tensor with one entry per row")
+    _check(lib().direct_kmvm_rows_f64_static(_dev_f32(X, "X"), int(n), int(D), float(lengthscale), _dev_f32(b, "b"),
+                                             ctypes.c_void_p(rows.data_ptr()), int(rows.numel()),
+                                             ctypes.c_void_p(y64.data_ptr()), _stream(stream)))
     return y64
 
 

@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported(lib):
             "f3m_last_error", "f3m_plan_info", "f3m_plan_get_perm", "f3m_plan_get_point_keys",
             "f3m_plan_get_boxes", "f3m_plan_get_list", "f3m_stage_times", "f3m_level_times", "f3m_plan_xy",
             "direct_kmvm_xy", "direct_kmvm_xy_rows_f64", "f3m_plan_source_info", "f3m_plan_get_source_perm",
-            "f3m_plan_get_source_boxes", "f3m_cg_solve", "f3m_kmvm_multi", "f3m_trim_memory"} <= set(names)
+            "f3m_plan_get_source_boxes", "f3m_cg_solve", "f3m_kmvm_multi", "f3m_trim_memory",
+            "direct_kmvm_rows_f64_static"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
 
@@ -77,6 +78,11 @@ def test_argument_checks_need_no_device(lib):
     assert lib.direct_kmvm_xy(fake, 10, fake, 5, 3, 1.0, fake, fake, None) == 1                  # b aliases y
     assert lib.direct_kmvm_xy(None, 0, fake, 5, 3, 1.0, fake, None, None) == 0                   # no targets
     assert lib.direct_kmvm_xy_rows_f64(fake, 10, fake, 5, 3, 1.0, fake, None, 4, fake, None) == 1  # null rows
+    # the entry point that allocates nothing refuses what its static scratch cannot hold, before any device call
+    assert lib.direct_kmvm_rows_f64_static(fake, 10, 3, 1.0, fake, fake, 16385, fake, None) == 3
+    assert b"16384" in lib.f3m_last_error()
+    assert lib.direct_kmvm_rows_f64_static(fake, 10, 3, 1.0, fake, None, 4, fake, None) == 1     # null rows
+    assert lib.direct_kmvm_rows_f64_static(fake, 10, 3, 1.0, fake, fake, 0, fake, None) == 0     # no rows
     assert lib.f3m_kmvm_multi(None, fake, 10, fake, 10, 2, None) == 1                            # null plan
     it = ctypes.c_int(-1)
     assert lib.f3m_cg_solve(None, 1.0, fake, fake, 10, 1e-6, ctypes.byref(it), None, None) == 1   # null plan
