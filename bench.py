@@ -5,7 +5,7 @@ already resident in HBM: f3m_plan (enclosing cube, keys, sort, box tables,
 interaction lists, kernel tables) followed by f3m_kmvm (P2M, M2L, L2P per depth,
 near-field P2P, permutations).  Prints ONE JSON line on stdout.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--n N] [--rows R] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5|3|4|2] [--n N] [--rows R] [--no-cpu]
 
 The default workload is configuration 5 of the benchmark list: n = 1e9 points,
 D = 3, iid Uniform[0,1]^3, Gaussian lengthscale 1.0, b ~ N(0,1), 4 nodes per
@@ -45,11 +45,14 @@ def cpu_baseline(cfg, n_sample):
     b = inputs.rhs_normal(n_sample, 2000 + cfg["k"]).numpy()
     t0 = time.time()
     T = oracle.Tree(X, theta=cfg["theta"], zeta=128)
+    t_tree = time.time() - t0
     T.apply(b, cfg["lengthscale"], cfg["p"])
     dt = time.time() - t0
+    leaf = n_sample / max(T.nboxes(T.L), 1)
     return {"value": n_sample / dt, "unit": "points/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "oracle F3M (tree + product, fp64) on n=%d points of the same distribution, depth %d, %.1f s"
-                      % (n_sample, T.L, dt)}
+            "sample": "oracle F3M (tree %.1f s + product, fp64, dense node-to-node matrices) on n=%d points of the same "
+                      "distribution: depth %d, %.0f points per leaf box, %.1f s in all"
+                      % (t_tree, n_sample, T.L, leaf, dt)}
 
 
 def cpu_baseline_xy(cfg, n_sample):
@@ -68,16 +71,83 @@ def cpu_baseline_xy(cfg, n_sample):
                       "depth %d, %.1f s" % (n_sample, n_sample, T.L, dt)}
 
 
+def source_digest():
+    """sha256 over the HIP sources of the library: stored with the counter figures under profiles/ so that a figure
+    measured on other kernels is never reported as this build's"""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2202_01085_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def load_counters(tag):
+    """profiles/counters_<tag>.json: HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy
+    of known size) and issue counters of the near-field kernel, with the digest of the sources they were measured
+    on.  Returns (bytes per stage, issue counters, note)."""
+    path = os.path.join(ROOT, "profiles", "counters_%s.json" % tag)
+    if not os.path.exists(path):
+        return {}, None, "no counter summary for this workload under profiles/"
+    with open(path) as f:
+        cj = json.load(f)
+    if cj.get("source_digest") != source_digest():
+        return {}, None, ("profiles/counters_%s.json was measured on other kernel sources (digest differs): traffic and "
+                          "issue counters withheld until it is measured again" % tag)
+    return cj.get("bytes_per_launch", {}), cj.get("issue_counters"), "profiles/counters_%s.json" % tag
+
+
+def median(v):
+    v = sorted(v)
+    m = len(v) // 2
+    return v[m] if len(v) % 2 else 0.5 * (v[m - 1] + v[m])
+
+
+def bench_direct(args):
+    """direct_kmvm (the exact product, Sec. 2) on configuration-1-shaped inputs of --direct points."""
+    import torch
+    from paper_2202_01085_amd import f3m, inputs
+    n = int(args.direct)
+    X, b, cfg = inputs.make_config(1, n=n, device="cuda:0")
+    y = torch.empty_like(b)
+    for _ in range(max(args.warmup, 1)):
+        f3m.direct_kmvm(X, b, cfg["lengthscale"], y=y)
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(args.steps):
+        t0 = time.perf_counter()
+        f3m.direct_kmvm(X, b, cfg["lengthscale"], y=y)
+        torch.cuda.synchronize()
+        times.append((time.perf_counter() - t0) * 1e3)
+    ms = sum(times) / len(times)
+    pairs = float(n) * n
+    ach = 11.0 * pairs / (ms * 1e-3) / 1e12
+    out = {"metric": "direct_kmvm throughput (exact product)", "value": n / (ms * 1e-3), "unit": "points/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "ms_per_step_median": median(times),
+           "ms_per_step_min": min(times), "ms_per_step_max": max(times), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "direct_kmvm: n=%d D=3 uniform, Gaussian lengthscale 1, b~N(0,1), all n^2 pairs" % n},
+           "roofline": {"kernel": "direct_kmvm", "bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS, "traffic": None, "launch_ms": ms,
+                        "pairs_per_s": pairs / (ms * 1e-3),
+                        "valu_slot_frac": 3.0 * pairs / (ms * 1e-3) / (256 * 64 * 2.4e9)},
+           "cpu_baseline": None}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--n", type=float, default=None, help="points (default: configuration 5, 1e9; with --xy: "
-                                                           "points per set, default 5e8)")
+    ap.add_argument("--config", type=int, default=None, choices=[2, 3, 4, 5],
+                    help="configuration of the benchmark list (default 5: n = 1e9 uniform 3-D points, the headline)")
+    ap.add_argument("--n", type=float, default=None, help="points: a reduced or enlarged n of the configuration's recipe "
+                                                           "(with --xy: points per set, default 5e8)")
     ap.add_argument("--xy", action="store_true", help="two point sets: X uniform (targets), Y normal (sources)")
     ap.add_argument("--rows", type=int, default=10000, help="sampled rows for the error against the exact product")
-    ap.add_argument("--cpu-sample", type=int, default=400000, help="points of the CPU oracle sample")
+    ap.add_argument("--cpu-sample", type=int, default=None, help="points of the CPU oracle sample")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--eta-smooth", type=float, default=0.0,
                     help="smooth-field limit of Sec. 4.3 (0 = off, the headline configuration; the paper uses 0.5)")
@@ -89,20 +159,25 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first copy 1 GiB device-to-device with a plain kernel: the reference that the "
                          "FETCH_SIZE / WRITE_SIZE counter readings of a rocprofv3 --pmc run are scaled by")
-    ap.add_argument("--traffic", type=str, default=None,
-                    help="JSON file with measured HBM bytes per launch, {\"p2p\": bytes, \"m2l\": bytes}, from "
-                         "the rocprofv3 --pmc runs summarised under profiles/")
+    ap.add_argument("--direct", type=float, default=0,
+                    help="time direct_kmvm (the exact O(n^2) product) on this many points instead of the F3M path")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the kernels are one GPU's share of the path; nothing "
               "here uses a second device); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.direct:
+        return bench_direct(args)
 
     import torch
     from paper_2202_01085_amd import f3m, inputs
 
-    n = int(args.n if args.n is not None else (5e8 if args.xy else 1e9))
-    k = 5 if n >= 500_000_000 else 3
+    if args.config is not None:
+        k = args.config
+        n = int(args.n if args.n is not None else inputs.CONFIGS[k]["n"])
+    else:
+        n = int(args.n if args.n is not None else (5e8 if args.xy else 1e9))
+        k = 5 if n >= 500_000_000 else 3
     cfg = dict(inputs.CONFIGS[k], k=k)
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -136,40 +211,84 @@ def main():
             plan.close()
         plan = step()
     torch.cuda.synchronize()
+    depth_known = None
     if plan is not None:
-        plan.close()
+        depth_known = plan.info().depth     # (the first f3m_plan_info of a plan counts point pairs on the device: not
+        plan.close()                        # something to call between the timed steps)
         plan = None
 
-    stage_sum, level_ms = {}, None
+    # K steps between two synchronisations.  Closing the previous step's plan (its memory is needed at n = 1e9) waits
+    # for the device, so the host clock read after it marks the end of that step: per-step durations come for free.
+    stage_runs, level_runs, marks = [], [], []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         if plan is not None:
-            plan.close()            # frees the previous step's plan (its memory is needed at n = 1e9)
+            stage_runs.append(plan.stage_times())        # HIP events of the finished step (read before the plan goes)
+            if depth_known is not None:
+                level_runs.append({l: plan.level_times(l) for l in range(1, depth_known + 1)})
+            plan.close()
+            marks.append(time.perf_counter())
         plan = step()
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    t_end = time.perf_counter()
+    wall = t_end - t0
     ms_per_step = wall * 1e3 / args.steps
+    marks = [t0] + marks + [t_end]
+    step_ms = [(marks[i + 1] - marks[i]) * 1e3 for i in range(args.steps)]
 
-    # per-kernel durations from the HIP events the library records on the launch stream
-    st = plan.stage_times()
+    # per-kernel durations from the HIP events the library records on the launch stream: median over the steps
     inf = plan.info()
     L = inf.depth
-    level_ms = {l: plan.level_times(l) for l in range(1, L + 1)}
+    stage_runs.append(plan.stage_times())
+    if depth_known not in (None, L):
+        level_runs = []
+    level_runs.append({l: plan.level_times(l) for l in range(1, L + 1)})
+    st = {key: median([run[key] for run in stage_runs]) for key in stage_runs[0]}
+    level_ms = {l: tuple(median([run[l][j] for run in level_runs]) for j in range(3)) for l in range(1, L + 1)}
     far_L = int(inf.far_pairs[L])
     r = inf.nodes_per_box
     m2l_ms = level_ms[L][1] if L >= 1 else 0.0
     D = cfg["D"]
     pairs = int(inf.near_point_pairs)
+    nb_L = int(inf.nboxes[L])
+    tag = ("xy_n%d" % n) if args.xy else "config%d_n%d" % (k, n)
+    traffic, issue, counters_note = load_counters(tag)
     rooflines = {}
+
+    def hbm_stage(name, kernel, nbytes, ms):
+        # algorithmic bytes: what the stage itself must move (stated per point / per box), not what the kernel moves
+        if ms <= 0:
+            return
+        ach = nbytes / (ms * 1e-3) / 1e9
+        rooflines[name] = {"kernel": kernel, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": ach / PEAK_HBM_GBS, "traffic": traffic.get(name), "launch_ms": ms,
+                           "algorithmic_bytes": nbytes}
+
+    ns = n                                                  # sources (= targets for one set)
+    key_bits = D * int(inf.quant_depth)
+    passes = (key_bits + 7) // 8
+    if not args.xy:
+        hbm_stage("bbox_keys", "bbox_kernel + keys_kernel: 4D B/pt read twice, 4 B/pt written", (8.0 * D + 4) * n, st["bbox_keys"])
+        hbm_stage("sort", "rs_hist_kernel + %d passes of rs_scatter_kernel over %d-bit keys: 4 + %d x 16 B/pt"
+                  % (passes, key_bits, passes), (4.0 + 16.0 * passes) * n, st["sort"])
+        hbm_stage("gather_x", "gather of the points into box order: 4 + 8D B/pt", (4.0 + 8.0 * D) * n, st["gather"])
+        hbm_stage("permute_in", "right-hand side into box order: 12 B/pt", 12.0 * ns, st["permute_in"])
+        hbm_stage("permute_out", "result back to the caller's order: 12 B/pt", 12.0 * n, st["permute_out"])
+        if L >= 1 and level_ms[L][0] > 0:
+            hbm_stage("p2m_leaf", "P2M at depth %d: 4(D+1) B/pt + 4r B/box" % L, 4.0 * (D + 1) * ns + 4.0 * r * nb_L,
+                      level_ms[L][0])
+        if L >= 1 and level_ms[L][2] > 0:
+            hbm_stage("l2p_leaf", "L2P at depth %d: (4D+8) B/pt + 4r B/box" % L, (4.0 * D + 8) * n + 4.0 * r * nb_L,
+                      level_ms[L][2])
     if far_L > 0 and m2l_ms > 0:
         # algorithmic: 2 r^2 flop per far pair (the dense node-to-node product).  For D = 3 with 4 nodes per
         # dimension the kernel applies the Kronecker factors per candidate / line / plane of the 6x6x6 grid around
         # the parent, and shares the line and plane sums between the eight children: 936 factor applications of 256
         # multiply-adds per parent (117 per target box) instead of 189 x 4096 per target, on the vector ALU.
+        # Every other shape applies D one-dimensional factors per far pair: 2 D r p flop.
         # `achieved` counts the multiply-adds it executes; `algorithmic_tflops` the dense equivalent.
         t = m2l_ms * 1e-3
-        nb_L = int(inf.nboxes[L])
         if D == 3 and cfg["p"] == 4 and cfg["theta"] == 2.0 and not args.xy:
             executed = 2.0 * 117 * 256 * nb_L
             kernel = "m2l_stencil_shared_kernel"
@@ -179,10 +298,12 @@ def main():
         ach = executed / t / 1e12
         rooflines["m2l"] = {"kernel": "%s, leaf depth %d, %d far pairs, %d target boxes" % (kernel, L, far_L, nb_L),
                             "bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",
-                            "frac": ach / PEAK_VALU_F32_TFLOPS, "traffic": None, "launch_ms": m2l_ms,
+                            "frac": ach / PEAK_VALU_F32_TFLOPS, "traffic": traffic.get("m2l"), "launch_ms": m2l_ms,
                             "frac_of_unpacked_fp32_peak": ach / UNPACKED_F32_TFLOPS,
                             "algorithmic_tflops": 2.0 * r * r * far_L / t / 1e12,
-                            "far_pairs_per_s": far_L / t}
+                            "far_pairs_per_s": far_L / t,
+                            "peak_note": "peak = the published fp32 vector figure (packed FP32); plain FMAs, the only kind "
+                                         "this build generates, reach 78.6 TFLOP/s on 256 CUs x 64 lanes at 2.4 GHz"}
     if pairs > 0 and st["p2p"] > 0:
         # algorithmic: D sub, D mul/fma, exp2, fma = 3D+2 flop per point pair.  The kernel computes the
         # D-term part as a Gram matrix on the matrix cores, so per pair the vector ALU is left with one
@@ -193,28 +314,22 @@ def main():
         ach = flops / t / 1e12
         lane_slots_per_s = 256 * 64 * 2.4e9
         rooflines["p2p"] = {"kernel": "near field: p2p_gram3_kernel (tiles of up to 64 targets) + p2p_small_kernel (last runs "
-                                      "of <= 10 targets), %d point pairs" % pairs, "bound": "alu", "achieved": ach,
+                                      "of <= 10 targets), %d point pairs" % pairs if D == 3 and not args.xy else
+                                      "near field, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
                             "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS,
-                            "traffic": None, "launch_ms": st["p2p"],
+                            "traffic": traffic.get("p2p"), "launch_ms": st["p2p"],
                             "pairs_per_s": pairs / t,
                             "valu_slot_frac": 3.0 * pairs / t / lane_slots_per_s,
                             "frac_of_unpacked_fp32_peak": ach / UNPACKED_F32_TFLOPS,
+                            "issue_counters": issue,
+                            "achieved_note": "flop-equivalent: (3D+2) flop per point pair / launch time; the D-term part of "
+                                             "every pair runs on the matrix cores (fp16-split operands, fp32 accumulate), so "
+                                             "this is not a count of executed VALU flops",
                             "peak_note": "peak = the published fp32 vector figure, which needs packed FP32; this build "
                                          "generates none, so plain FMAs top out at 78.6 TFLOP/s. The (3D+2)-flop count can "
                                          "exceed that because the D-term part of every pair runs on the matrix cores; "
                                          "valu_slot_frac (3 issue slots per pair: one half-rate exp2 + one FMA, over all "
                                          "lane slots) is the utilisation figure to read"}
-    traffic_file = args.traffic
-    if traffic_file is None and n == 1_000_000_000 and not args.xy:
-        # HBM bytes per launch measured with rocprofv3 --pmc on this workload (profiles/hbm_traffic_config5_n1e9.md)
-        cand = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_config5_n1e9.json")
-        traffic_file = cand if os.path.exists(cand) else None
-    if traffic_file:
-        with open(traffic_file) as f:
-            tj = json.load(f)
-        for name, nbytes in tj.get("bytes_per_launch", tj).items():
-            if name in rooflines:
-                rooflines[name]["traffic"] = nbytes
     # the dominant kernel of the step is the one reported as `roofline`
     roof = None
     if rooflines:
@@ -239,6 +354,7 @@ def main():
         "unit": "points/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_median": median(step_ms), "ms_per_step_min": min(step_ms), "ms_per_step_max": max(step_ms),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": ("two sets: %d uniform targets x %d normal sources, D=3, Gaussian lengthscale %g, b~N(0,1), "
@@ -246,16 +362,22 @@ def main():
                                 % (n, n, cfg["lengthscale"], cfg["p"], cfg["theta"])) if args.xy else
                                "config %d: n=%d D=%d %s, Gaussian lengthscale %g, b~N(0,1), %d nodes/dim, far ratio %g"
                                % (k, n, cfg["D"], cfg["dist"], cfg["lengthscale"], cfg["p"], cfg["theta"]),
-                   "depth": L, "leaf_max": 128, "boxes_leaf": int(inf.nboxes[L]), "near_pairs_leaf": int(inf.near_pairs[L]),
+                   "depth": L, "leaf_max": 128, "boxes_leaf": nb_L, "near_pairs_leaf": int(inf.near_pairs[L]),
                    "far_pairs_leaf": far_L, "device_bytes": int(inf.device_bytes),
                    "eta_smooth": args.eta_smooth, "adaptive_far": bool(args.adaptive_far),
-                   "smooth_depth": int(inf.smooth_depth)},
+                   "smooth_depth": int(inf.smooth_depth),
+                   "arithmetic": "fp32 throughout; the near-field exponents -|x-y|^2/(2 gamma^2) come from one fp16 MFMA on "
+                                 "operands split in two fp16 halves (3 cross terms, about 22 significant bits) with fp32 "
+                                 "accumulation, exp2 and the sums in fp32; cells in fp32, box centres and local "
+                                 "coordinates in fp64"},
         "wall_s_per_kmvm_with_plan": ms_per_step * 1e-3,
         "rel_err_vs_exact": rel_err, "rel_err_rows": int(rows.numel()),
         "stage_ms": st,
+        "stage_ms_note": "median over the timed steps of the HIP-event durations the library records on its launch stream",
         "level_ms": {str(l): {"p2m": v[0], "m2l": v[1], "l2p": v[2]} for l, v in level_ms.items()},
         "roofline": roof,
         "rooflines_all": rooflines,
+        "counters": counters_note,
         "paper_context": ("paper: 74.9+-28.5 s mean over its data sets at n=5e8, D=3 on one V100-32GB (the uniform-and-normal "
                           "pair is one of them, run up to n=5e8)") if args.xy else
                          "paper: 125.9 s (r=64) and 174.0+-76.6 s (mean over data sets) for n=1e9, D=3 on one V100-32GB",
@@ -280,7 +402,10 @@ def main():
     plan.close()
     del X, Y, y
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline_xy(cfg, args.cpu_sample // 2) if args.xy else cpu_baseline(cfg, args.cpu_sample)
+        # sample sizes of about 30 s of oracle work on 16 cores; 2e6 uniform points divide to depth 5 with 61 points
+        # per leaf box, the leaf occupancy of the 1e9-point workload at depth 8
+        sample = args.cpu_sample or {5: 2_000_000, 3: 2_000_000, 2: 300_000, 4: 1_500}[k]
+        out["cpu_baseline"] = cpu_baseline_xy(cfg, sample // 2) if args.xy else cpu_baseline(cfg, sample)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)

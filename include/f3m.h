@@ -42,7 +42,9 @@ typedef enum {
     F3M_ERR_INVALID_ARG = 1, /* null pointer, n < 0, D outside [1,7], interp_nodes < 2,
                                 lengthscale or eta not finite and positive, bad level/kind */
     F3M_ERR_NONFINITE = 2,   /* NaN or Inf among the coordinates */
-    F3M_ERR_UNSUPPORTED = 3, /* n >= 2^31, or interp_nodes^D above the node cap (4096) */
+    F3M_ERR_UNSUPPORTED = 3, /* n >= 2^31, interp_nodes > 8, interp_nodes^D above the node cap (4096), or an eta
+                                so large that the per-depth factor tables of the M2L exceed 64 KB (roughly
+                                eta > 25 .. 100, depending on D and interp_nodes) */
     F3M_ERR_OOM = 4,         /* a device allocation failed */
     F3M_ERR_HIP = 5,         /* any other HIP runtime error (message in f3m_last_error) */
     F3M_ERR_BREAKDOWN = 6    /* f3m_cg_solve: a search direction with p.(K + lambda I)p <= 0 */
@@ -72,6 +74,11 @@ typedef struct {
                                summed directly (exactly) at that depth, whatever its distance, and is not
                                divided further.  0 (default) = off; the paper suggests rho = 2 * nodes per
                                box. */
+    int32_t route_min_points; /* a point set with at least this many points moves b, y and its own coordinates
+                               between the caller's order and the box order in three streaming passes through
+                               LDS instead of one random gather or scatter (same values, bit for bit); 0 =
+                               library default (2^24: below it the caches hold the vectors).  A smaller value
+                               lets tests reach that path on small inputs. */
 } f3m_options;
 
 typedef struct {
@@ -122,8 +129,8 @@ typedef struct {
  *   n            number of points, 0 <= n < 2^31
  *   D            1..7
  *   lengthscale  gamma > 0
- *   interp_nodes p >= 2 Chebyshev nodes of the second kind per dimension
- *                (p = 4 in 3-D is the paper's r = 64)
+ *   interp_nodes 2 <= p <= 8 Chebyshev nodes of the second kind per dimension, with p^D <= 4096
+ *                (p = 4 in 3-D is the paper's r = 64); F3M_ERR_UNSUPPORTED above either limit
  *   eta          far-field distance ratio theta: boxes are far iff the distance
  *                of their centres is >= theta * (box edge); the paper uses 2.
  *                (NOT the paper's smooth-field limit: that is f3m_options.eta_smooth.)
@@ -143,7 +150,8 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
  * k(x,y)" (P2M, M2L, L2P), then the exact near-field sums of Sec. 3 eq. (1) at
  * the last depth, then the inverse permutation sigma.
  *   b, y   device fp32[n], caller's order; y is overwritten; they must not overlap.
- *   Asynchronous on `stream`; one call in flight per plan (the plan holds the
+ *   Asynchronous on `stream`: the call only enqueues kernels, it allocates nothing and never waits for
+ *   the device (every workspace was sized by f3m_plan); one call in flight per plan (the plan holds the
  *   workspace).
  */
 f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream);

@@ -33,6 +33,7 @@ def lib():
         L = ctypes.CDLL(build())
         c_i64, c_int, c_dbl, c_vp = ctypes.c_int64, ctypes.c_int, ctypes.c_double, ctypes.c_void_p
         L.oracle_num_threads.restype = c_int
+        L.oracle_set_verbose.argtypes = [c_int]
         L.oracle_rows_k.argtypes = [c_vp, c_i64, c_int, c_dbl, c_int, c_int, c_vp, c_vp, c_i64, c_vp]
         L.oracle_cheb2_nodes.argtypes = [c_int, c_vp]
         L.oracle_lagrange_product.argtypes = [c_int, c_vp, c_dbl, c_vp]
@@ -45,6 +46,10 @@ def lib():
         L.oracle_tree_build_ex.restype = c_vp
         L.oracle_tree_build_ex2.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int, c_dbl, c_dbl, c_i64]
         L.oracle_tree_build_ex2.restype = c_vp
+        L.oracle_tree_build_rows.argtypes = [c_vp, c_i64, c_int, c_dbl, c_i64, c_int, c_int, c_dbl, c_dbl, c_vp, c_i64]
+        L.oracle_tree_build_rows.restype = c_vp
+        L.oracle_f3m_apply_rows.argtypes = [c_vp, c_vp, c_dbl, c_int, c_int, c_int, c_vp, c_vp, c_i64, c_vp, c_int]
+        L.oracle_f3m_apply_rows.restype = c_int
         L.oracle_is_smooth_depth.argtypes = [c_dbl, c_int, c_int, c_dbl, c_dbl]
         L.oracle_is_smooth_depth.restype = c_int
         L.oracle_adaptive_nodes.argtypes = [c_dbl, c_int, c_dbl, c_int]
@@ -99,6 +104,11 @@ def _ptr(a):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def set_verbose(on):
+    """Progress lines on stderr, one per finished step of a tree build or a product."""
+    lib().oracle_set_verbose(int(bool(on)))
+
+
 def num_threads():
     return int(lib().oracle_num_threads())
 
@@ -150,14 +160,23 @@ class Tree:
     """Partition + interaction lists of Algorithm 1 for one point set."""
 
     def __init__(self, X, theta=2.0, zeta=128, max_depth=0, force_all_near=False, gamma=0.0, eta_smooth=0.0,
-                 small_field=0):
+                 small_field=0, rows=None):
         """eta_smooth > 0 switches the smooth field of Sec. 4.3 on (needs the lengthscale gamma);
-        small_field = rho > 0 the small field of Sec. 4.2."""
+        small_field = rho > 0 the small field of Sec. 4.2.  rows: build the interaction rows only for
+        the boxes that hold these points (for apply_rows on large inputs; not with the small field)."""
         self.X = _f32(X)
         self.n, self.D = self.X.shape
-        self._h = lib().oracle_tree_build_ex2(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
-                                              int(max_depth), int(bool(force_all_near)), float(gamma),
-                                              float(eta_smooth), int(small_field))
+        if rows is None:
+            self._h = lib().oracle_tree_build_ex2(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
+                                                  int(max_depth), int(bool(force_all_near)), float(gamma),
+                                                  float(eta_smooth), int(small_field))
+        else:
+            if small_field:
+                raise ValueError("a row-subset tree is not offered with the small field")
+            idx = np.ascontiguousarray(rows, dtype=np.int64)
+            self._h = lib().oracle_tree_build_rows(_ptr(self.X), self.n, self.D, float(theta), int(zeta),
+                                                   int(max_depth), int(bool(force_all_near)), float(gamma),
+                                                   float(eta_smooth), _ptr(idx), idx.size)
         if not self._h:
             raise ValueError("oracle_tree_build rejected its arguments")
         self.L = int(lib().oracle_tree_depth(self._h))
@@ -221,6 +240,17 @@ class Tree:
                                        _ptr(b), _ptr(y), int(bool(literal)), int(bool(adaptive)))
         if rc:
             raise ValueError("oracle_f3m_apply rejected its arguments")
+        return y
+
+    def apply_rows(self, b, gamma, p, rows, kernel_id=0, kparam=0, adaptive=False):
+        """The rows `rows` of apply(): the same steps over the boxes that hold them (same bits)."""
+        b = _f32(b)
+        idx = np.ascontiguousarray(rows, dtype=np.int64)
+        y = np.empty(idx.size, dtype=np.float64)
+        rc = lib().oracle_f3m_apply_rows(self._h, _ptr(self.X), float(gamma), int(p), kernel_id, kparam, _ptr(b),
+                                         _ptr(idx), idx.size, _ptr(y), int(bool(adaptive)))
+        if rc:
+            raise ValueError("oracle_f3m_apply_rows rejected its arguments (%d)" % rc)
         return y
 
 

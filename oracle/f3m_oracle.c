@@ -59,6 +59,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
@@ -99,6 +100,12 @@ static double kernel_eval(int kernel_id, int kparam, double gamma, int D,
     }
     return prod;
 }
+
+/* Progress lines on stderr, one per finished step of a tree build or a product (for runs on
+ * inputs of 1e8 .. 1e9 points that take minutes); off by default. */
+static int g_verbose = 0;
+void oracle_set_verbose(int on) { g_verbose = on; }
+#define PROGRESS(...) do { if (g_verbose) { fprintf(stderr, "[oracle] " __VA_ARGS__); fputc('\n', stderr); fflush(stderr); } } while (0)
 
 int oracle_num_threads(void)
 {
@@ -220,6 +227,8 @@ typedef struct {
     /* smooth field (Sec. 4.3): depth at which every adjacent pair is interpolated, or -1 */
     int smooth_depth;
     double gamma;      /* lengthscale the smooth rule was evaluated with (0: rule off) */
+    uint8_t *rows_mark; /* NULL, or [n] in box order: 1 for the points of the row subset whose boxes have
+                          interaction rows (oracle_tree_build_rows); every other row of the lists is empty */
 } otree;
 
 /* quantisation depth: as deep as a 32-bit key allows, at most 20 */
@@ -260,6 +269,35 @@ static int cmp_keyidx(const void *a, const void *b)
     return p->idx < q->idx ? -1 : (p->idx > q->idx);
 }
 
+/* Ascending (key, index).  All pairs are distinct, so the result is unique: qsort for
+ * small inputs; for large ones the pairs are first dealt into 4096 buckets by the top bits
+ * of the key (buckets ascend with the key) and every bucket is handed to qsort, the
+ * buckets in parallel.  Same order either way. */
+static void sort_keyidx(keyidx *ki, int64_t n, int key_bits)
+{
+    enum { BUCKET_BITS = 12, NBUCKET = 1 << BUCKET_BITS };
+    if (n < ((int64_t)1 << 20) || key_bits <= BUCKET_BITS) {
+        qsort(ki, (size_t)n, sizeof(keyidx), cmp_keyidx);
+        return;
+    }
+    int shift = key_bits - BUCKET_BITS;
+    int64_t *first = (int64_t *)calloc((size_t)NBUCKET + 1, sizeof(int64_t));
+    for (int64_t i = 0; i < n; ++i)
+        ++first[(ki[i].key >> shift) + 1];
+    for (int k = 0; k < NBUCKET; ++k)
+        first[k + 1] += first[k];
+    int64_t *fill = (int64_t *)malloc(sizeof(int64_t) * NBUCKET);
+    memcpy(fill, first, sizeof(int64_t) * NBUCKET);
+    keyidx *tmp = (keyidx *)malloc(sizeof(keyidx) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i)
+        tmp[fill[ki[i].key >> shift]++] = ki[i];
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int k = 0; k < NBUCKET; ++k)
+        qsort(tmp + first[k], (size_t)(first[k + 1] - first[k]), sizeof(keyidx), cmp_keyidx);
+    memcpy(ki, tmp, sizeof(keyidx) * (size_t)n);
+    free(tmp); free(fill); free(first);
+}
+
 static void free_level(olevel *lv)
 {
     free(lv->key); free(lv->start); free(lv->parent); free(lv->cstart);
@@ -274,7 +312,7 @@ void oracle_tree_free(otree *t)
         return;
     for (int l = 0; l <= ORACLE_MAX_LEVELS; ++l)
         free_level(&t->lev[l]);
-    free(t->cell); free(t->pkey); free(t->perm);
+    free(t->cell); free(t->pkey); free(t->perm); free(t->rows_mark);
     free(t);
 }
 
@@ -329,7 +367,7 @@ static int64_t max_box(const olevel *lv)
  * near and far (reading R4).  Rows come out sorted because the parent's row is
  * sorted and the children of a box have consecutive ranks. */
 static void new_interactions(otree *t, int l, double theta, int force_all_near, int all_interpolated,
-                             int64_t rho)
+                             int64_t rho, const uint8_t *only /* [nb] or NULL: rows to build (others stay empty) */)
 {
     olevel *lv = &t->lev[l], *up = &t->lev[l - 1];
     int D = t->D;
@@ -358,7 +396,7 @@ static void new_interactions(otree *t, int l, double theta, int force_all_near, 
             int64_t *fcol = pass ? lv->far_col + lv->far_ptr[a] : NULL;
             int64_t *scol = pass ? lv->small_col + lv->small_ptr[a] : NULL;
             int64_t cnt_a = lv->start[a + 1] - lv->start[a];
-            for (int64_t e = up->near_ptr[P]; e < up->near_ptr[P + 1]; ++e) {
+            for (int64_t e = (only && !only[a]) ? up->near_ptr[P + 1] : up->near_ptr[P]; e < up->near_ptr[P + 1]; ++e) {
                 int64_t Q = up->near_col[e];
                 for (int64_t bq = up->cstart[Q]; bq < up->cstart[Q + 1]; ++bq) {
                     deinterleave(lv->key[bq], D, l, cb);
@@ -452,6 +490,7 @@ static otree *partition_points(const float *X, int64_t n, int D, const float *al
     uint32_t cmax = (uint32_t)((1ull << t->Lq) - 1);
     t->cell = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)n * (size_t)D);
     keyidx *ki = (keyidx *)malloc(sizeof(keyidx) * (size_t)n);
+#pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) {
         for (int d = 0; d < D; ++d) {
             volatile float diff = X[i * D + d] - (float)t->alpha[d];
@@ -462,7 +501,9 @@ static otree *partition_points(const float *X, int64_t n, int D, const float *al
         ki[i].key = interleave(&t->cell[i * D], D, t->Lq);
         ki[i].idx = i;
     }
-    qsort(ki, (size_t)n, sizeof(keyidx), cmp_keyidx);
+    PROGRESS("cells and keys of %lld points", (long long)n);
+    sort_keyidx(ki, n, D * t->Lq);
+    PROGRESS("points sorted by (key, index)");
     t->pkey = (uint64_t *)malloc(sizeof(uint64_t) * (size_t)n);
     t->perm = (int64_t *)malloc(sizeof(int64_t) * (size_t)n);
     for (int64_t k = 0; k < n; ++k) {
@@ -478,6 +519,8 @@ otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int6
                             int force_all_near, double gamma, double eta_smooth);
 otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
                              int force_all_near, double gamma, double eta_smooth, int64_t rho);
+otree *oracle_tree_build_rows(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                              int force_all_near, double gamma, double eta_smooth, const int64_t *rows, int64_t m);
 
 /* Builds the partition and the interaction lists of Algorithm 1 (everything
  * that does not depend on b).  Returns NULL on bad arguments. */
@@ -496,10 +539,24 @@ otree *oracle_tree_build_ex(const float *X, int64_t n, int D, double theta, int6
     return oracle_tree_build_ex2(X, n, D, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, 0);
 }
 
-/* The same with the small field of Sec. 4.2 (rho > 0): a pair of boxes created by a division whose
- * point counts add up to at most rho goes on the direct list of that depth. */
-otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
-                             int force_all_near, double gamma, double eta_smooth, int64_t rho)
+/* for every box of depth l: does it hold one of the marked points?  selk is in box order */
+static uint8_t *boxes_with_marked_points(const otree *t, int l, const uint8_t *selk)
+{
+    const olevel *lv = &t->lev[l];
+    uint8_t *only = (uint8_t *)calloc((size_t)lv->nb, 1);
+#pragma omp parallel for schedule(static)
+    for (int64_t a = 0; a < lv->nb; ++a)
+        for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k)
+            if (selk[k]) {
+                only[a] = 1;
+                break;
+            }
+    return only;
+}
+
+static otree *tree_build_core(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                              int force_all_near, double gamma, double eta_smooth, int64_t rho,
+                              const int64_t *rows, int64_t m)
 {
     if (!X || n <= 0 || D < 1 || D > ORACLE_MAX_D || !(theta > 0.0) || zeta < 1)
         return NULL;
@@ -508,6 +565,19 @@ otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int
     float Ef = point_bounds(X, n, D, mn);
     otree *t = partition_points(X, n, D, mn, Ef);
     t->gamma = eta_smooth > 0.0 ? gamma : 0.0;
+
+    /* row subset: the points whose boxes get interaction rows, marked in box order */
+    uint8_t *selk = NULL;
+    if (rows) {
+        uint8_t *sel = (uint8_t *)calloc((size_t)n, 1);
+        for (int64_t a = 0; a < m; ++a)
+            sel[rows[a]] = 1;
+        selk = (uint8_t *)malloc((size_t)n);
+        for (int64_t k = 0; k < n; ++k)
+            selk[k] = sel[t->perm[k]];
+        free(sel);
+        t->rows_mark = selk;
+    }
 
     /* depth 0: one box, one (near) interaction */
     olevel *root = &t->lev[0];
@@ -529,12 +599,41 @@ otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int
         ++l;
         divide(t, l);
         int smooth = !force_all_near && oracle_is_smooth_depth(t->E, l, D, gamma, eta_smooth);
-        new_interactions(t, l, theta, force_all_near, smooth, rho);
+        uint8_t *only = selk ? boxes_with_marked_points(t, l, selk) : NULL;
+        new_interactions(t, l, theta, force_all_near, smooth, rho, only);
+        free(only);
+        PROGRESS("depth %d: %lld boxes, %lld near and %lld far pairs listed", l, (long long)t->lev[l].nb,
+                 (long long)t->lev[l].near_ptr[t->lev[l].nb], (long long)t->lev[l].far_ptr[t->lev[l].nb]);
         if (smooth)
             t->smooth_depth = l;
     }
     t->L = l;
     return t;
+}
+
+/* The same with the small field of Sec. 4.2 (rho > 0): a pair of boxes created by a division whose
+ * point counts add up to at most rho goes on the direct list of that depth. */
+otree *oracle_tree_build_ex2(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                             int force_all_near, double gamma, double eta_smooth, int64_t rho)
+{
+    return tree_build_core(X, n, D, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, rho, NULL, 0);
+}
+
+/* The tree for a subset of the rows of the product (Sec. 5, first paragraph: the error is measured
+ * on a subset of rows): the partition is the full one, but interaction rows are built only for the
+ * boxes that hold one of rows[0..m) (at every depth; all other rows stay empty), which is all that
+ * oracle_f3m_apply_rows reads.  Without the small field (not offered here) a box with a row always
+ * keeps its own pair until the smooth depth, so the loop of Algorithm 1 ends at the same depth as for
+ * the full lists.  Rows out of range give NULL. */
+otree *oracle_tree_build_rows(const float *X, int64_t n, int D, double theta, int64_t zeta, int max_depth,
+                              int force_all_near, double gamma, double eta_smooth, const int64_t *rows, int64_t m)
+{
+    if (!rows || m <= 0)
+        return NULL;
+    for (int64_t a = 0; a < m; ++a)
+        if (rows[a] < 0 || rows[a] >= n)
+            return NULL;
+    return tree_build_core(X, n, D, theta, zeta, max_depth, force_all_near, gamma, eta_smooth, 0, rows, m);
 }
 
 /* ---- introspection ---- */
@@ -683,6 +782,8 @@ void oracle_p2m_level(const otree *t, const float *X, const float *b, int p,
  * y is in ORIGINAL point order, fp64. */
 int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
                         const float *b, double *y, int literal, int adaptive);
+int oracle_f3m_apply_rows(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
+                          const float *b, const int64_t *rows, int64_t m, double *y_rows, int adaptive);
 
 int oracle_f3m_apply(const otree *t, const float *X, double gamma, int p,
                      int kernel_id, int kparam, const float *b, double *y, int literal)
@@ -690,18 +791,57 @@ int oracle_f3m_apply(const otree *t, const float *X, double gamma, int p,
     return oracle_f3m_apply_ex(t, X, gamma, p, kernel_id, kparam, b, y, literal, 0);
 }
 
-/* adaptive != 0: the node count of every depth follows oracle_adaptive_nodes (Sec. 4.3,
- * adaptive far-field approximation; a depth with 0 nodes contributes nothing). */
-int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
-                        const float *b, double *y, int literal, int adaptive)
+/* The rows of the product that are wanted: pos == NULL means every point (count == n, the value
+ * of point k of the box order sits at index k); otherwise pos[0..count) are the box-order positions
+ * of the wanted rows, ascending, and the value of pos[ip] sits at index ip. */
+typedef struct {
+    int64_t count;
+    const int64_t *pos;
+} rowsel;
+
+/* first index ip whose position is >= k */
+static int64_t rowsel_lower(const rowsel *S, int64_t k)
 {
-    if (!t || !X || !b || !y || p_all < 2 || p_all > 32)
-        return 1;
-    if (t->gamma != 0.0 && t->gamma != gamma)
-        return 2; /* the smooth rule of the tree was evaluated with another lengthscale */
+    if (!S->pos)
+        return k;
+    int64_t lo = 0, hi = S->count;
+    while (lo < hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (S->pos[mid] < k) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+/* The target boxes of a depth that hold a wanted row, ascending; all boxes for pos == NULL. */
+static int64_t *target_boxes(const olevel *lv, const rowsel *S, int64_t *count)
+{
+    int64_t *tb = (int64_t *)malloc(sizeof(int64_t) * (size_t)(S->pos ? S->count + 1 : lv->nb));
+    int64_t nt = 0;
+    if (!S->pos) {
+        for (int64_t a = 0; a < lv->nb; ++a) tb[nt++] = a;
+    } else {
+        for (int64_t ip = 0; ip < S->count; ++ip) {
+            /* box of position pos[ip]: last a with start[a] <= pos */
+            int64_t lo = 0, hi = lv->nb;
+            while (hi - lo > 1) {
+                int64_t mid = lo + (hi - lo) / 2;
+                if (lv->start[mid] <= S->pos[ip]) lo = mid; else hi = mid;
+            }
+            if (nt == 0 || tb[nt - 1] != lo) tb[nt++] = lo;
+        }
+    }
+    *count = nt;
+    return tb;
+}
+
+/* Algorithm 1 for the rows in S; ys[ip] receives the value of row ip of S.  The loops are the
+ * same for every S: per depth v1 (of the source boxes that some wanted target's far row names),
+ * v2 and v for the target boxes that hold a wanted row, then the exact sums. */
+static void f3m_apply_core(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
+                           const float *b, const rowsel *S, double *ys, int literal, int adaptive)
+{
     int D = t->D;
-    int64_t n = t->n;
-    double *ys = (double *)calloc((size_t)n, sizeof(double)); /* permuted order */
+    for (int64_t ip = 0; ip < S->count; ++ip) ys[ip] = 0.0;
 
     for (int l = 1; l <= t->L; ++l) {
         const olevel *lv = &t->lev[l];
@@ -713,62 +853,136 @@ int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all,
         int64_t r = ipow(p, D);
         double s[32];
         oracle_cheb2_nodes(p, s);
+        int64_t nt = 0;
+        int64_t *tb = target_boxes(lv, S, &nt);
+        /* v1 = L_Y b of the source boxes in use: slot[q] = row of W that holds box q, or -1 */
         double *W = NULL;
+        int64_t *slot = NULL;
         if (!literal) {
-            W = (double *)malloc(sizeof(double) * (size_t)lv->nb * (size_t)r);
-            oracle_p2m_level(t, X, b, p, l, W);
-        }
+            slot = (int64_t *)malloc(sizeof(int64_t) * (size_t)lv->nb);
+            int64_t nsrc = 0;
+            if (!S->pos) {
+                for (int64_t q = 0; q < lv->nb; ++q) slot[q] = q;
+                nsrc = lv->nb;
+            } else {
+                for (int64_t q = 0; q < lv->nb; ++q) slot[q] = -1;
+                for (int64_t ai = 0; ai < nt; ++ai)
+                    for (int64_t e = lv->far_ptr[tb[ai]]; e < lv->far_ptr[tb[ai] + 1]; ++e)
+                        slot[lv->far_col[e]] = 0;
+                for (int64_t q = 0; q < lv->nb; ++q)
+                    if (slot[q] == 0) slot[q] = nsrc++;
+            }
+            W = (double *)malloc(sizeof(double) * (size_t)(nsrc > 0 ? nsrc : 1) * (size_t)r);
 #pragma omp parallel
-        {
-            double *V = (double *)malloc(sizeof(double) * (size_t)r);
-            double *Wq = (double *)malloc(sizeof(double) * (size_t)r);
-            double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
-            double *xs = (double *)malloc(sizeof(double) * (size_t)r * D);
-            double cp[ORACLE_MAX_D], cq[ORACLE_MAX_D], xq[ORACLE_MAX_D];
-#pragma omp for schedule(dynamic, 4)
-            for (int64_t a = 0; a < lv->nb; ++a) {
-                if (lv->far_ptr[a + 1] == lv->far_ptr[a])
-                    continue;
-                box_centre(t, l, lv->key[a], cp);
-                for (int64_t i = 0; i < r; ++i)
-                    node_coords(t, l, cp, p, s, i, xs + i * D);
-                for (int64_t i = 0; i < r; ++i) V[i] = 0.0;
-                for (int64_t e = lv->far_ptr[a]; e < lv->far_ptr[a + 1]; ++e) {
-                    int64_t q = lv->far_col[e];
-                    const double *wq = W ? W + q * r : Wq;
-                    if (literal) {
+            {
+                double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
+#pragma omp for schedule(dynamic, 8)
+                for (int64_t q = 0; q < lv->nb; ++q)
+                    if (slot[q] >= 0)
+                        p2m_box(t, X, b, l, q, p, s, W + slot[q] * r, scratch);
+                free(scratch);
+            }
+            PROGRESS("depth %d: node weights of %lld source boxes", l, (long long)nsrc);
+        }
+        if (literal) {
+#pragma omp parallel
+            {
+                double *V = (double *)malloc(sizeof(double) * (size_t)r);
+                double *Wq = (double *)malloc(sizeof(double) * (size_t)r);
+                double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
+                double *xs = (double *)malloc(sizeof(double) * (size_t)r * D);
+                double cp[ORACLE_MAX_D], cq[ORACLE_MAX_D], xq[ORACLE_MAX_D];
+#pragma omp for schedule(dynamic, 1)
+                for (int64_t ai = 0; ai < nt; ++ai) {
+                    int64_t a = tb[ai];
+                    const int64_t ip0 = rowsel_lower(S, lv->start[a]), ip1 = rowsel_lower(S, lv->start[a + 1]);
+                    box_centre(t, l, lv->key[a], cp);
+                    for (int64_t i = 0; i < r; ++i)
+                        node_coords(t, l, cp, p, s, i, xs + i * D);
+                    /* every far pair on its own: v1 of the source box, v2 = K v1, v = L_X^T v2 */
+                    for (int64_t e = lv->far_ptr[a]; e < lv->far_ptr[a + 1]; ++e) {
+                        int64_t q = lv->far_col[e];
                         p2m_box(t, X, b, l, q, p, s, Wq, scratch);
                         for (int64_t i = 0; i < r; ++i) V[i] = 0.0;
-                    }
-                    box_centre(t, l, lv->key[q], cq);
-                    /* v2 = K v1 with K_ij = k(s^p_i, s^q_j) */
-                    for (int64_t j = 0; j < r; ++j) {
-                        node_coords(t, l, cq, p, s, j, xq);
-                        for (int64_t i = 0; i < r; ++i)
-                            V[i] += kernel_eval(kernel_id, kparam, gamma, D, xs + i * D, xq) * wq[j];
-                    }
-                    if (literal) {
-                        for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k) {
+                        box_centre(t, l, lv->key[q], cq);
+                        for (int64_t j = 0; j < r; ++j) {
+                            node_coords(t, l, cq, p, s, j, xq);
+                            for (int64_t i = 0; i < r; ++i)
+                                V[i] += kernel_eval(kernel_id, kparam, gamma, D, xs + i * D, xq) * Wq[j];
+                        }
+                        for (int64_t ip = ip0; ip < ip1; ++ip) {
+                            int64_t k = S->pos ? S->pos[ip] : ip;
                             point_weights(t, l, cp, p, s, X + t->perm[k] * D, scratch);
                             double acc = 0.0;
                             for (int64_t i = 0; i < r; ++i) acc += scratch[i] * V[i];
-                            ys[k] += acc;
+                            ys[ip] += acc;
                         }
                     }
                 }
-                if (!literal) {
-                    /* v = L_X^T v2 */
-                    for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k) {
-                        point_weights(t, l, cp, p, s, X + t->perm[k] * D, scratch);
-                        double acc = 0.0;
-                        for (int64_t i = 0; i < r; ++i) acc += scratch[i] * V[i];
-                        ys[k] += acc;
+                free(V); free(Wq); free(scratch); free(xs);
+            }
+        } else {
+            /* v2 = K v1 of every target box in use, summed over its far row: V[ai*r + i], i a node of
+             * target box tb[ai].  Every V[i] is summed over (far pair, source node) in list order; with
+             * few target boxes (a row subset) the nodes of a box are shared out between the threads in
+             * `parts` ranges, which changes no sum. */
+            double *V = (double *)malloc(sizeof(double) * (size_t)(nt > 0 ? nt : 1) * (size_t)r);
+            int64_t parts = (S->pos && nt < 64) ? (r < 64 ? r : 64) : 1;
+#pragma omp parallel
+            {
+                double *xs = (double *)malloc(sizeof(double) * (size_t)r * D);
+                double cp[ORACLE_MAX_D], cq[ORACLE_MAX_D], xq[ORACLE_MAX_D];
+#pragma omp for schedule(dynamic, 1)
+                for (int64_t item = 0; item < nt * parts; ++item) {
+                    int64_t ai = item / parts, part = item % parts;
+                    int64_t i0 = r * part / parts, i1 = r * (part + 1) / parts;
+                    int64_t a = tb[ai];
+                    double *Va = V + ai * r;
+                    box_centre(t, l, lv->key[a], cp);
+                    for (int64_t i = i0; i < i1; ++i)
+                        node_coords(t, l, cp, p, s, i, xs + i * D);
+                    for (int64_t i = i0; i < i1; ++i) Va[i] = 0.0;
+                    for (int64_t e = lv->far_ptr[a]; e < lv->far_ptr[a + 1]; ++e) {
+                        int64_t q = lv->far_col[e];
+                        const double *wq = W + slot[q] * r;
+                        box_centre(t, l, lv->key[q], cq);
+                        /* K_ij = k(s^p_i, s^q_j) */
+                        for (int64_t j = 0; j < r; ++j) {
+                            node_coords(t, l, cq, p, s, j, xq);
+                            for (int64_t i = i0; i < i1; ++i)
+                                Va[i] += kernel_eval(kernel_id, kparam, gamma, D, xs + i * D, xq) * wq[j];
+                        }
                     }
                 }
+                free(xs);
             }
-            free(V); free(Wq); free(scratch); free(xs);
+            /* v = L_X^T v2 */
+#pragma omp parallel
+            {
+                double *scratch = (double *)malloc(sizeof(double) * (size_t)r);
+                double cp[ORACLE_MAX_D];
+#pragma omp for schedule(dynamic, 1)
+                for (int64_t ai = 0; ai < nt; ++ai) {
+                    int64_t a = tb[ai];
+                    if (lv->far_ptr[a + 1] == lv->far_ptr[a])
+                        continue;
+                    const int64_t ip0 = rowsel_lower(S, lv->start[a]), ip1 = rowsel_lower(S, lv->start[a + 1]);
+                    const double *Va = V + ai * r;
+                    box_centre(t, l, lv->key[a], cp);
+                    for (int64_t ip = ip0; ip < ip1; ++ip) {
+                        int64_t k = S->pos ? S->pos[ip] : ip;
+                        point_weights(t, l, cp, p, s, X + t->perm[k] * D, scratch);
+                        double acc = 0.0;
+                        for (int64_t i = 0; i < r; ++i) acc += scratch[i] * Va[i];
+                        ys[ip] += acc;
+                    }
+                }
+                free(scratch);
+            }
+            free(V);
         }
-        free(W);
+        free(W); free(slot); free(tb);
+        PROGRESS("depth %d: far field of %lld target boxes", l, (long long)nt);
     }
 
     /* exact sums: the small-field pairs of every depth (Sec. 4.2) and the near-field
@@ -780,10 +994,15 @@ int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all,
         const int64_t *col = last ? lv->near_col : lv->small_col;
         if (!ptr || ptr[lv->nb] == 0)
             continue;
+        int64_t nt = 0;
+        int64_t *tb = target_boxes(lv, S, &nt);
 #pragma omp parallel for schedule(dynamic, 4)
-        for (int64_t a = 0; a < lv->nb; ++a) {
+        for (int64_t ai = 0; ai < nt; ++ai) {
+            int64_t a = tb[ai];
             double xi[ORACLE_MAX_D], xj[ORACLE_MAX_D];
-            for (int64_t k = lv->start[a]; k < lv->start[a + 1]; ++k) {
+            const int64_t ip0 = rowsel_lower(S, lv->start[a]), ip1 = rowsel_lower(S, lv->start[a + 1]);
+            for (int64_t ip = ip0; ip < ip1; ++ip) {
+                int64_t k = S->pos ? S->pos[ip] : ip;
                 int64_t i = t->perm[k];
                 for (int d = 0; d < D; ++d) xi[d] = (double)X[i * D + d];
                 double acc = 0.0;
@@ -795,14 +1014,100 @@ int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all,
                         acc += kernel_eval(kernel_id, kparam, gamma, D, xi, xj) * (double)b[j];
                     }
                 }
-                ys[k] += acc;
+                ys[ip] += acc;
             }
         }
+        free(tb);
     }
+}
+
+/* adaptive != 0: the node count of every depth follows oracle_adaptive_nodes (Sec. 4.3,
+ * adaptive far-field approximation; a depth with 0 nodes contributes nothing). */
+int oracle_f3m_apply_ex(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
+                        const float *b, double *y, int literal, int adaptive)
+{
+    if (!t || !X || !b || !y || p_all < 2 || p_all > 32)
+        return 1;
+    if (t->gamma != 0.0 && t->gamma != gamma)
+        return 2; /* the smooth rule of the tree was evaluated with another lengthscale */
+    if (t->rows_mark)
+        return 3; /* the tree holds the interaction rows of a row subset only */
+    int64_t n = t->n;
+    double *ys = (double *)malloc(sizeof(double) * (size_t)n); /* box order */
+    rowsel S = { n, NULL };
+    f3m_apply_core(t, X, gamma, p_all, kernel_id, kparam, b, &S, ys, literal, adaptive);
     /* back to the caller's order */
     for (int64_t k = 0; k < n; ++k)
         y[t->perm[k]] = ys[k];
     free(ys);
+    return 0;
+}
+
+typedef struct {
+    int64_t row, pos;
+} rowpos;
+
+static int cmp_rowpos(const void *a, const void *b)
+{
+    const rowpos *p = (const rowpos *)a, *q = (const rowpos *)b;
+    return p->row < q->row ? -1 : (p->row > q->row);
+}
+
+/* The rows rows[0..m) of the same product (Sec. 5, first paragraph: results are compared on a
+ * subset of rows): y_rows[a] = row rows[a] of oracle_f3m_apply_ex.  The steps are those of the
+ * full product, run over the boxes that hold a wanted row and over the source boxes their far rows
+ * name; every sum that reaches a wanted row is formed in the same order, so the values are the
+ * same bits.  Works on a full tree and on a tree of oracle_tree_build_rows whose subset holds
+ * every wanted row. */
+int oracle_f3m_apply_rows(const otree *t, const float *X, double gamma, int p_all, int kernel_id, int kparam,
+                          const float *b, const int64_t *rows, int64_t m, double *y_rows, int adaptive)
+{
+    if (!t || !X || !b || !y_rows || !rows || m < 0 || p_all < 2 || p_all > 32)
+        return 1;
+    if (t->gamma != 0.0 && t->gamma != gamma)
+        return 2;
+    int64_t n = t->n;
+    for (int64_t a = 0; a < m; ++a)
+        if (rows[a] < 0 || rows[a] >= n)
+            return 1;
+    /* box-order positions of the wanted rows, ascending, duplicates merged */
+    uint8_t *sel = (uint8_t *)calloc((size_t)n, 1);
+    for (int64_t a = 0; a < m; ++a)
+        sel[rows[a]] = 1;
+    int64_t count = 0;
+    for (int64_t i = 0; i < n; ++i)
+        count += sel[i];
+    int64_t *pos = (int64_t *)malloc(sizeof(int64_t) * (size_t)(count + 1));
+    rowpos *rp = (rowpos *)malloc(sizeof(rowpos) * (size_t)(count + 1));
+    int64_t c = 0;
+    int bad = 0;
+    for (int64_t k = 0; k < n; ++k)
+        if (sel[t->perm[k]]) {
+            if (t->rows_mark && !t->rows_mark[k])
+                bad = 1; /* the tree has no interaction rows for the box of this point */
+            pos[c] = k;
+            rp[c].row = t->perm[k];
+            rp[c].pos = c;
+            ++c;
+        }
+    free(sel);
+    if (bad) {
+        free(pos); free(rp);
+        return 3;
+    }
+    double *ys = (double *)malloc(sizeof(double) * (size_t)(count + 1));
+    rowsel S = { count, pos };
+    f3m_apply_core(t, X, gamma, p_all, kernel_id, kparam, b, &S, ys, 0, adaptive);
+    qsort(rp, (size_t)count, sizeof(rowpos), cmp_rowpos);
+    for (int64_t a = 0; a < m; ++a) {
+        int64_t lo = 0, hi = count;
+        while (hi - lo > 1) {
+            int64_t mid = lo + (hi - lo) / 2;
+            if (rp[mid].row <= rows[a]) lo = mid; else hi = mid;
+        }
+        y_rows[a] = ys[rp[lo].pos];
+    }
+    free(ys); free(pos); free(rp);
     return 0;
 }
 

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libf3m.so")
-SOURCES = ["api.hip", "plan.hip", "kmvm.hip", "m2l.hip", "solve.hip", "pool.hip"]
+SOURCES = ["api.hip", "plan.hip", "kmvm.hip", "m2l.hip", "solve.hip", "pool.hip", "route.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are not to be generated on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

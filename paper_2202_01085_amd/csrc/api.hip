@@ -72,6 +72,7 @@ static f3m_status make_plan(const float *X, int64_t n, const float *Y, int64_t n
     if (opt && (opt->leaf_max < 0 || opt->max_depth < 0))
         return set_error(F3M_ERR_INVALID_ARG, "negative option value");
     if (opt && opt->small_field < 0) return set_error(F3M_ERR_INVALID_ARG, "small_field must be >= 0");
+    if (opt && opt->route_min_points < 0) return set_error(F3M_ERR_INVALID_ARG, "route_min_points must be >= 0");
     if (opt && !(std::isfinite(opt->eta_smooth) && opt->eta_smooth >= 0.f))
         return set_error(F3M_ERR_INVALID_ARG, "eta_smooth must be finite and >= 0");
     if (interp_nodes > 8) return set_error(F3M_ERR_UNSUPPORTED, "interp_nodes above 8 is not supported");
@@ -97,6 +98,7 @@ static f3m_status make_plan(const float *X, int64_t n, const float *Y, int64_t n
         P->eta_smooth = opt ? opt->eta_smooth : 0.f;
         P->adaptive_far = opt ? (opt->adaptive_far != 0) : 0;
         P->rho = opt ? opt->small_field : 0;
+        P->route_min_n = (opt && opt->route_min_points > 0) ? opt->route_min_points : ((int64_t)1 << 24);
         F3M_HIP(hipGetDevice(&P->device));
         if (two_sets) {
             P->src.reset(new f3m_source());

@@ -1771,6 +1771,7 @@ static KronShape kron_shape(const f3m_plan_s &P, int level) {
 
 // per depth with far pairs: the 1-D factor matrices of the node-to-node kernel matrix, built in fp64
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
+    std::vector<std::vector<float>> host_tabs;
     for (int l = 1; l <= P.L; ++l) {
         f3m_level &lv = P.lev[l];
         if (lv.far_sz == 0 || lv.p == 0) continue;
@@ -1787,6 +1788,14 @@ void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
             lv.gtab_omax = 3;
         }
         const int ndim = lv.far_implicit ? 1 : P.D;
+        if (!lv.far_implicit && lv.r / p <= 32) {
+            // m2l_kron_small_kernel stages the factor tables of the depth in LDS beside its far-pair buffers
+            const size_t lds = (size_t)((64 / (lv.r / p)) * lv.r + P.D * S.no * p * p) * sizeof(float);
+            if (lds > 64 * 1024)
+                fail(F3M_ERR_UNSUPPORTED, "eta = " + std::to_string(P.theta) + " gives " + std::to_string(S.no) +
+                                              " cell offsets per dimension at depth " + std::to_string(l) +
+                                              ": the factor tables of the M2L exceed 64 KB of LDS for this D and interp_nodes");
+        }
         double u[F3M_MAX_DIM];
         P.grid_shift(l, u);
         std::vector<float> g((size_t)ndim * S.no * p * p);
@@ -1800,8 +1809,9 @@ void upload_kron_tables(f3m_plan_s &P, hipStream_t st) {
                     }
         lv.gtab.alloc(g.size(), &P.bytes);
         F3M_HIP(hipMemcpyAsync(lv.gtab.p, g.data(), g.size() * sizeof(float), hipMemcpyHostToDevice, st));
-        F3M_HIP(hipStreamSynchronize(st));
+        host_tabs.push_back(std::move(g));   // stays alive until the copies of all depths have been waited for
     }
+    if (!host_tabs.empty()) F3M_HIP(hipStreamSynchronize(st));
 }
 
 
@@ -1820,6 +1830,32 @@ static void reduce_partials(f3m_plan_s &P, f3m_level &lv, int r, float *W, hipSt
 
 // every box of the depth is exactly one chunk of the P2M / L2P work split (chunk index = box rank)
 static int single_chunks(const f3m_level &lv) { return lv.max_box <= P2M_CHUNK && lv.nchunks == lv.nb ? 1 : 0; }
+
+// g = log2(e) l^2 / (2 gamma^2) of a depth: c l^2 bounds the magnitude of the expanded exponent terms in
+// box-local coordinates (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2)
+static double gram_exponent_scale(const f3m_plan_s &P, int l) {
+    const CentreArg CL = make_centre(P, l);
+    const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
+    return c * CL.edge * CL.edge;
+}
+
+// the near field of a depth runs on the Gram kernels (expanded square on the matrix cores) while g D <= 6;
+// above the limit, and for the root pair of two point sets (near whatever its distance: no bound on the
+// coordinates), the difference form is used
+static bool gram_near_field(const f3m_plan_s &P, int l) {
+    const double gl = gram_exponent_scale(P, l);
+    return gl * (double)P.D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 && !(P.src && l == 0);
+}
+
+// Slices that a target tile of the 3-D Gram near field over the near list of depth l is cut into (1: none):
+// with few target tiles and long rows several wavefronts share a tile, each on a slice of the sources.
+int p2p_nsplit(const f3m_plan_s &P, int l, int64_t ntiles) {
+    const f3m_level &lv = P.lev[l];
+    if (!(P.D == 3 && gram_near_field(P, l) && ntiles > 0 && ntiles < 8192 && lv.nb > 0 && P.slev(l).nb > 0)) return 1;
+    const double row_sources = (double)lv.near_sz / (double)lv.nb * ((double)P.ns() / (double)P.slev(l).nb);   // per tile
+    const int nsplit = (int)std::min<double>(std::min<double>(64.0, (double)cdiv(262144, ntiles)), row_sources / 2048.0);
+    return nsplit < 2 ? 1 : nsplit;
+}
 
 // box_order: b and y are in the plan's box order (one-set plans), so both permutations are plain passes.
 // bs_in / yn_in (both or neither): the right-hand side already gathered into box order (padded like
@@ -1848,7 +1884,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     } else if (box_order)
         copy_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.ns(), P.bs.p);
     else
-        gather_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.sperm(), P.ns(), P.bs.p);
+        if (P.sroute())
+            route_gather(*P.sroute(), b, P.bs.p, P.route_a.p, P.route_b.p, st);
+        else
+            gather_kernel<<<dim3((unsigned)cdiv(P.ns(), 256)), dim3(256), 0, st>>>(b, P.sperm(), P.ns(), P.bs.p);
     F3M_HIP(hipEventRecord(P.ev[9], st));
     // The near field goes to the plan's second stream (vector ALU work) and overlaps the
     // far field (matrix-core work) on the caller's stream; with no_overlap it runs in line.
@@ -1863,27 +1902,15 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
                             const uint32_t *tile_first, int64_t ntiles, int accumulate) {
         f3m_level &lv = P.lev[l];
         const uint32_t *sstart = P.slev(l).start.p;
-        // c l^2 bounds the magnitude of the expanded exponent terms in box-local coordinates
-        // (|x'|^2 + |y'|^2 <= 7.5 D/3 l^2); above the limit the difference form is used
         const CentreArg CL = make_centre(P, l);
-        const double c = 1.4426950408889634 / (2.0 * (double)P.gamma * (double)P.gamma);
-        const double gl = c * CL.edge * CL.edge;     // g = log2(e) l^2 / (2 gamma^2)
-        // (the root pair of two point sets is near whatever its distance: no bound on the coordinates)
-        const bool gram = gl * (double)D <= 6.0 && gl > 1e-30 && !P.force_all_near && P.T <= 1024 && !(P.src && l == 0);
+        const double gl = gram_exponent_scale(P, l);
+        const bool gram = gram_near_field(P, l);
         // few target tiles with long rows: several wavefronts per tile, each on a slice of the sources
-        int nsplit = 1;
-        if (gram && D == 3 && ntiles > 0 && ntiles < 8192 && lv.nb > 0 && P.slev(l).nb > 0) {
-            const double row_sources = (double)(cols == lv.near_col.p ? lv.near_sz : lv.small_sz) / (double)lv.nb *
-                                       ((double)P.ns() / (double)P.slev(l).nb);   // average sources of a tile
-            nsplit = (int)std::min<double>(std::min<double>(64.0, (double)cdiv(262144, ntiles)), row_sources / 2048.0);
-            if (nsplit < 2) nsplit = 1;
-        }
+        const int nsplit = cols == lv.near_col.p ? p2p_nsplit(P, l, ntiles) : 1;
         if (nsplit > 1) {
-            if (P.p2p_part.count < (size_t)nsplit * (size_t)n) {
-                F3M_HIP(hipStreamSynchronize(sn));
-                P.p2p_part.release();
-                P.p2p_part.alloc((size_t)nsplit * (size_t)n, &P.bytes);
-            }
+            // the partial sums were sized when the plan was built: nothing is allocated here
+            if (P.p2p_part.count < (size_t)nsplit * (size_t)n)
+                fail(F3M_ERR_HIP, "internal: the plan holds no room for the split near field");
             p2p_gram3_kernel<true, 1><<<grid_for(cdiv(ntiles * nsplit, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
                 (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, nsplit, n, P.p2p_part.p, MultiArg{});
@@ -2108,7 +2135,9 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     if (box_order) {
         add_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, yn, n, y);
         F3M_HIP(hipGetLastError());
-    } else if (!permute_out_bucketed(P, yn, y, st)) {
+    } else if (P.route) {
+        route_scatter(*P.route, P.ys.p, yn, y, P.route_a.p, P.route_b.p, st);
+    } else {
         scatter_kernel<<<dim3(gn), dim3(256), 0, st>>>(P.ys.p, yn, P.perm.p, n, y);
         F3M_HIP(hipGetLastError());
     }
@@ -2148,7 +2177,10 @@ void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_
         MultiArg MA{};
         for (int j = 0; j < mb; ++j) {
             float *bsj = P.multi_bs.p + (size_t)j * bs_stride;
-            gather_kernel<<<dim3((unsigned)cdiv(ns, 256)), dim3(256), 0, st>>>(B + (int64_t)(j0 + j) * ldb, P.sperm(), ns, bsj);
+            if (P.sroute())
+                route_gather(*P.sroute(), B + (int64_t)(j0 + j) * ldb, bsj, P.route_a.p, P.route_b.p, st);
+            else
+                gather_kernel<<<dim3((unsigned)cdiv(ns, 256)), dim3(256), 0, st>>>(B + (int64_t)(j0 + j) * ldb, P.sperm(), ns, bsj);
             MA.bs[j] = bsj;
             MA.ys[j] = P.multi_yn.p + (size_t)j * (size_t)n;
         }

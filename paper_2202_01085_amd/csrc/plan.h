@@ -47,6 +47,17 @@ struct f3m_level {
     f3m::DevBuf<float> Wl, Vl;          // [nb*64]
 };
 
+// Tables of the three-pass permutation between the caller's order and the box order of one point set
+// (route.hip): per pass the place of every value in the LDS copy of its tile, per tile the first place of each
+// digit and where the tile's run of each digit lies in the next order.
+struct f3m_route {
+    int64_t n = 0, ntiles = 0;
+    int s2 = 0, B1 = 1, B2 = 1;
+    f3m::DevBuf<uint16_t> slot1, slot2, off3;      // [n] each
+    f3m::DevBuf<uint32_t> dstart1, dstart2;        // [ntiles][257]
+    f3m::DevBuf<uint32_t> gofs1, gofs2;            // [ntiles][256]
+};
+
 // The partition of the source set Y of a two-set plan, v = K(X, Y) b (Sec. 3 states the method for
 // two data matrices; Algorithm 1 keeps one treecode per set).  Both sets are divided by cubes of
 // the same edge, each anchored at its own per-dimension minimum, so the two grids have equal box
@@ -56,6 +67,7 @@ struct f3m_source {
     float alpha[F3M_MAX_DIM] = {0};
     f3m::DevBuf<uint32_t> keys, perm;   // [n]
     f3m::DevBuf<float> Xs;              // [n*D] coordinates in box order, padded
+    std::unique_ptr<f3m_route> route;   // large sets: the right-hand side comes into box order in three passes
     f3m_level lev[F3M_MAX_LEVELS + 1];  // box tables and P2M work splits only (no lists)
 };
 
@@ -118,11 +130,12 @@ struct f3m_plan_s {
                                         // tree_lmin..tree_lmax (D = 3, 4 nodes/dim); other depths work
                                         // straight from the points
     f3m::DevBuf<float> transfer;        // [2][4][4] parent basis at the child's nodes
-    // un-permutation through buckets of destinations (large n): tile offsets of the radix scatter on the
-    // top 8 bits of perm, and the bucketed (destination, value) pairs
-    f3m::DevBuf<uint32_t> po_offs, po_key, po_val;
-    int po_shift = 0;
-    int64_t po_nblk = 0;
+    // large n: both permutations of a product run as three streaming passes (route.hip); the two work
+    // vectors hold max(n, sources) floats each
+    int64_t route_min_n = 0;                    // the passes are used from this many points on
+    std::unique_ptr<f3m_route> route;           // of the targets (and of the sources of a one-set plan)
+    f3m::DevBuf<float> route_a, route_b;
+    const f3m_route *sroute() const { return src ? src->route.get() : route.get(); }
 
     hipEvent_t ev[16] = {nullptr};
     std::vector<hipEvent_t> far_events;   // 6 per depth, around the far-field kernels of that depth
@@ -148,13 +161,20 @@ int adaptive_nodes(double E, int depth, double gamma, int p);                   
 // plan.hip
 void build_plan(f3m_plan_s &P, const float *X, const float *Y, hipStream_t st);   // Y == nullptr: one set (P.src set otherwise)
 void compute_far_point_pairs(f3m_plan_s &P);   // near_point_pairs and lev[].far_point_pairs, once (synchronises)
-// y[perm[k]] = ys[k] + yn[k] through buckets of destinations; false: n too small, use the plain scatter
-bool permute_out_bucketed(f3m_plan_s &P, const float *yn, float *y, hipStream_t st);
+// route.hip: permutations of large vectors as three streaming passes with tables built once per plan
+void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, hipStream_t st);   // synchronises
+void route_scatter(const f3m_route &R, const float *in, const float *in2, float *out, float *tmp_a, float *tmp_b,
+                   hipStream_t st);                                   // out[perm[k]] = in[k] (+ in2[k])
+void route_gather(const f3m_route &R, const float *in, float *out, float *tmp_a, float *tmp_b, hipStream_t st);
+                                                                      // out[k] = in[perm[k]]
+void route_gather_rows3(const f3m_route &R, const float *in, float *out, float *tmp, hipStream_t st);
+                                                                      // rows of 3 floats; tmp: 3 n floats
 void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStream_t st);   // far rows of an implicit depth
 // kmvm.hip
 // box_order: b and y are already in the plan's box order (one-set plans only; used by the solver)
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order = false);
 void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_t ldy, int m, hipStream_t st);
+int p2p_nsplit(const f3m_plan_s &P, int l, int64_t ntiles);   // source slices per target tile of the near field (1: none)
 void run_zero(float *y, int64_t n, hipStream_t st);   // y = 0 with a fill kernel
 // exact sums of targets X (nx rows) against sources Y (ny rows, weights b); X == Y for one set
 void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float gamma, const float *b, float *y,

@@ -272,50 +272,6 @@ static bool radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uin
     return in_b;
 }
 
-// ------------------------------------------------------------------------------------
-// result back to the caller's order, y[perm[k]] = ys[k] + yn[k] (Sec. 3, after eq. (1)).
-// A plain scatter writes 4 bytes into 1e9 random cache lines (8x write amplification).  For
-// large n the pairs (perm[k], value) are first bucketed by the top 8 bits of the destination
-// with the stable radix scatter above (streaming reads and writes), so that the final
-// scatter works through one window of n/256 destinations at a time, which the caches hold.
-// The tile offsets depend on perm only and are computed once per plan.
-// ------------------------------------------------------------------------------------
-void permute_out_prepare(f3m_plan_s &P, hipStream_t st) {
-    const int64_t n = P.n;
-    if (n < (1ll << 24)) return;
-    int bits = 0;
-    while (((int64_t)1 << bits) < n) ++bits;
-    P.po_shift = bits > 8 ? bits - 8 : 0;
-    P.po_nblk = cdiv(n, RS_TILE);
-    P.po_offs.alloc((size_t)P.po_nblk * 256, &P.bytes);
-    P.po_key.alloc((size_t)n, &P.bytes);
-    P.po_val.alloc((size_t)n, &P.bytes);
-    rs_hist_kernel<<<dim3((unsigned)P.po_nblk), dim3(RS_NT), 0, st>>>(P.perm.p, n, P.po_shift, P.po_offs.p, P.po_nblk);
-    F3M_HIP(hipGetLastError());
-    exclusive_scan(U32In{P.po_offs.p}, P.po_nblk * 256, U32Out{P.po_offs.p}, nullptr, st);
-}
-
-__global__ __launch_bounds__(256) void scatter_pairs_kernel(const uint32_t *__restrict__ dest,
-                                                            const uint32_t *__restrict__ val, int64_t n,
-                                                            float *__restrict__ y) {
-    const int64_t i = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
-    if (i < n) y[dest[i]] = __uint_as_float(val[i]);
-}
-
-bool permute_out_bucketed(f3m_plan_s &P, const float *yn, float *y, hipStream_t st) {
-    if (!P.po_offs.p) return false;
-    const int64_t n = P.n;
-    rs_scatter_kernel<<<dim3((unsigned)P.po_nblk), dim3(RS_NT), 0, st>>>(P.perm.p, nullptr, P.po_key.p, P.po_val.p, n,
-                                                                        P.po_shift, P.po_offs.p, P.po_nblk, P.ys.p,
-                                                                        yn);
-    F3M_HIP(hipGetLastError());
-    const int64_t blocks = cdiv(n, 256);
-    const dim3 grid = blocks <= 65536 ? dim3((unsigned)blocks) : dim3(65536u, (unsigned)cdiv(blocks, 65536));
-    scatter_pairs_kernel<<<grid, dim3(256), 0, st>>>(P.po_key.p, P.po_val.p, n, y);
-    F3M_HIP(hipGetLastError());
-    return true;
-}
-
 __global__ void iota_kernel(uint32_t *p, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) p[i] = (uint32_t)i;
@@ -923,11 +879,13 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         F3M_HIP(hipGetLastError());
     }
     F3M_HIP(hipEventRecord(P.ev[1], st));
+    int bits_sorted = 0;
     for (const SetRef &S : sets) {
         DevBuf<uint32_t> keys_b, perm_b;
         keys_b.alloc((size_t)S.n);
         perm_b.alloc((size_t)S.n);
         int bits = P.E > 0.f ? D * P.Lq : 0;
+        bits_sorted = bits;
         bool in_b;
         if (bits == 0) {
             iota_kernel<<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.perm->p, S.n);
@@ -942,12 +900,27 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         F3M_HIP(hipStreamSynchronize(st));   // the second buffers are released on leaving the scope
     }
     F3M_HIP(hipEventRecord(P.ev[2], st));
-    for (const SetRef &S : sets) {
+    for (size_t k = 0; k < sets.size(); ++k) {
+        const SetRef &S = sets[k];
         // 64 zero points of padding after the last point: kernels may read whole 32-point blocks
         S.Xs->alloc(((size_t)S.n + PAD_POINTS) * D, tally);
         F3M_HIP(hipMemsetAsync(S.Xs->p + (size_t)S.n * D, 0, (size_t)PAD_POINTS * D * sizeof(float), st));
-        gather_rows_kernel<D><<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.X, S.perm->p, S.n, S.Xs->p);
-        F3M_HIP(hipGetLastError());
+        // A large set goes through the three-pass permutation, whose tables also serve every product
+        // (route.hip); its points follow the same way when they have three coordinates.
+        std::unique_ptr<f3m_route> &route = k ? P.src->route : P.route;
+        if (S.n >= P.route_min_n && bits_sorted > 0) {
+            route.reset(new f3m_route());
+            route_build(*route, S.perm->p, S.n, tally, st);
+        }
+        if (route && D == 3) {
+            DevBuf<float> tmp;
+            tmp.alloc((size_t)S.n * 3);
+            route_gather_rows3(*route, S.X, S.Xs->p, tmp.p, st);
+            F3M_HIP(hipStreamSynchronize(st));   // `tmp` is released on leaving the scope
+        } else {
+            gather_rows_kernel<D><<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.X, S.perm->p, S.n, S.Xs->p);
+            F3M_HIP(hipGetLastError());
+        }
     }
     F3M_HIP(hipEventRecord(P.ev[3], st));
     F3M_HIP(hipStreamSynchronize(st));
@@ -1091,7 +1064,6 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
     }
     upload_kron_tables(P, st);
     for (int k = 1; k <= P.L; ++k) build_stencil_tables(P, k, st);
-    permute_out_prepare(P, st);
     int64_t max_w = 0, max_v = 0, max_part = 0, max_slice = 0;
     for (int k = 1; k <= P.L; ++k) {
         f3m_level &lv = P.lev[k];
@@ -1149,6 +1121,16 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         if (lv.small_sz > 0)
             build_chunks(lv.start.p, lv.nb, D <= 4 ? 16 : 8, lv.sm_tile_first, lv.sm_tile_box, lv.sm_ntiles, tally, st,
                          lv.small_ptr.p);   // runs of targets as p2p_small_kernel takes them
+    }
+    {
+        // partial sums of a near field whose tiles are split over several wavefronts (few targets, long rows)
+        const int nsplit = P.lev[P.L].near_sz > 0 ? p2p_nsplit(P, P.L, P.ntiles) : 1;
+        if (nsplit > 1) P.p2p_part.alloc((size_t)nsplit * (size_t)n, tally);
+    }
+    if (P.route || (P.src && P.src->route)) {
+        const size_t m = (size_t)std::max<int64_t>(P.route ? n : 0, (P.src && P.src->route) ? P.src->n : (P.route ? n : 0));
+        P.route_a.alloc(m, tally);
+        P.route_b.alloc(m, tally);
     }
     P.bs.alloc((size_t)P.ns() + PAD_POINTS, tally);
     F3M_HIP(hipMemsetAsync(P.bs.p + P.ns(), 0, (size_t)PAD_POINTS * sizeof(float), st));

@@ -1,0 +1,432 @@
+// Permutations of 1e8 .. 2e9 values between the caller's point order and the plan's box order (the
+// reindexing vector sigma of Sec. 4.2; grouping of Sec. 4.1) as three streaming passes through LDS.
+//
+// A plain gather b[perm[k]] (or scatter) of a random permutation touches one 128-byte line per 4-byte value
+// once the array is larger than the caches: 130 GB of traffic for 4 GB at n = 1e9.  Here a value travels
+//     box order k  --pass 1-->  order p1  --pass 2-->  order p2  --pass 3-->  caller's order i = perm[k]
+// where, with windows of T = 32768 consecutive caller indices (w = i >> 15, split as w = d1 * B2 + d2):
+//   pass 1  deals every tile of T consecutive k into B1 <= 256 buckets by d1 (bucket d1 holds exactly the
+//           2^15 B2 values whose destination lies in its B2 windows, so it starts at d1 2^15 B2);
+//   pass 2  deals every tile of T consecutive p1 (a tile lies inside one bucket) into the B2 windows of that
+//           bucket (window w receives exactly its T values, at w T ...);
+//   pass 3  puts the T values of a window in their places inside LDS and writes the window out in one piece.
+// Every pass reads and writes runs that are contiguous in memory (some hundred values per bucket and tile),
+// and the places (the position of a value in the LDS copy of its tile, 16 bits per value and pass) depend on
+// perm only: they are computed once per plan by route_build, so a pass moves data and does nothing else.
+// The gather direction (caller's order -> box order) runs the same three passes backwards with the same tables.
+#include "plan.h"
+
+namespace f3m {
+
+constexpr int RT_BITS = 15;
+constexpr int RT_TILE = 1 << RT_BITS;    // values per tile and per window
+constexpr int RT_NT = 1024;              // threads of a workgroup: one tile
+constexpr int RT_IPT = RT_TILE / RT_NT;  // 32 values per thread
+constexpr int RT_NW = RT_NT / 64;        // 16 wavefronts
+
+struct RouteLevel {
+    int shift;        // digit of a destination index: (i >> shift) & mask
+    uint32_t mask;
+    int second;       // 0: pass 1 (buckets over all tiles), 1: pass 2 (windows inside the bucket of the tile)
+    int s2;           // B2 = 1 << s2 tiles per bucket of pass 1
+    int B;            // digits of this pass
+    int64_t ntiles;
+};
+
+// where the count of (tile t, digit b) sits in the array whose exclusive prefix sum gives the first position
+// of that tile's values of that digit: digit-major for pass 1; (bucket, digit, tile inside the bucket) for pass 2
+__device__ inline int64_t route_count_index(const RouteLevel &R, int64_t t, uint32_t b) {
+    if (!R.second) return (int64_t)b * R.ntiles + t;
+    const int64_t region = t >> R.s2;
+    return ((((region << R.s2) + b) << R.s2) + (t & ((1 << R.s2) - 1)));
+}
+
+__global__ __launch_bounds__(RT_NT) void route_hist_kernel(const uint32_t *__restrict__ dest, int64_t n, RouteLevel R,
+                                                           uint32_t *__restrict__ cnt) {
+    __shared__ uint32_t h[256];
+    const int tid = threadIdx.x;
+    if (tid < 256) h[tid] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * RT_TILE;
+#pragma unroll 4
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int64_t i = base + r * RT_NT + tid;
+        if (i < n) atomicAdd(&h[(dest[i] >> R.shift) & R.mask], 1u);
+    }
+    __syncthreads();
+    if (tid < R.B) cnt[route_count_index(R, blockIdx.x, (uint32_t)tid)] = h[tid];
+}
+
+// One tile of a pass: the place of every value in the LDS copy of the tile (values of a digit together,
+// digits ascending, inside a digit in tile order), the destinations moved along to the next order, and the
+// tile's tables (first place of each digit; global position of the tile's first value of each digit, minus
+// that place).  Tile order = (wavefront, round, lane); ranking by wave ballots against per-wave LDS counters.
+__global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__restrict__ dest_in, int64_t n, RouteLevel R,
+                                                           const uint32_t *__restrict__ offs,
+                                                           uint16_t *__restrict__ slot, uint32_t *__restrict__ dest_out,
+                                                           uint32_t *__restrict__ dstart_out,
+                                                           uint32_t *__restrict__ gofs_out) {
+    __shared__ uint32_t wcnt[RT_NW][256];   // per wave: values of each digit seen so far; later the wave's offset
+    __shared__ uint32_t dstart[257];        // first place of each digit
+    __shared__ uint32_t gbase[256];         // global position of the tile's first value of each digit
+    __shared__ uint32_t skey[RT_TILE];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (tid < 256) {
+#pragma unroll
+        for (int k = 0; k < RT_NW; ++k) wcnt[k][tid] = 0;
+        gbase[tid] = tid < R.B ? offs[route_count_index(R, blockIdx.x, (uint32_t)tid)] : 0u;
+    }
+    __syncthreads();
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t base = tile0 + (int64_t)w * (RT_IPT * 64);
+    uint32_t key[RT_IPT];
+    uint32_t rk[RT_IPT / 2];   // rank within (wave, digit), below 2048: two per register
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int64_t i = base + r * 64 + lane;
+        key[r] = i < n ? dest_in[i] : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < RT_IPT / 2; ++r) rk[r] = 0u;
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int64_t i = base + r * 64 + lane;
+        const bool valid = i < n;
+        const uint32_t digit = (key[r] >> R.shift) & R.mask;
+        uint64_t peers = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (digit >> b) & 1u;
+            const uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        const uint32_t before = (uint32_t)__popcll(peers & lt_mask);
+        uint32_t cnt = 0;
+        if (valid) cnt = wcnt[w][digit];
+        rk[r / 2] |= (cnt + before) << (16 * (r & 1));
+        // the wave runs in lockstep and its LDS operations complete in order: every lane has read the
+        // counter before the first lane of each digit group updates it
+        if (valid && before == 0) wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    // per digit: the waves' counts become the waves' offsets; the totals go to dstart
+    if (tid < 256) {
+        uint32_t run = 0;
+#pragma unroll
+        for (int k = 0; k < RT_NW; ++k) {
+            const uint32_t c = wcnt[k][tid];
+            wcnt[k][tid] = run;
+            run += c;
+        }
+        dstart[tid] = run;
+    }
+    __syncthreads();
+    if (w == 0) {   // exclusive prefix sum of the 256 totals: four digits per lane
+        uint32_t v[4], s = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[k] = dstart[lane * 4 + k]; s += v[k]; }
+        uint32_t ex = wave_incl_scan_u32(s) - s;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { dstart[lane * 4 + k] = ex; ex += v[k]; }
+        if (lane == 63) dstart[256] = ex;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int64_t i = base + r * 64 + lane;
+        if (i < n) {
+            const uint32_t k = dest_in[i];   // read again: keeping the first copy would not fit the registers
+            const uint32_t digit = (k >> R.shift) & R.mask;
+            const uint32_t pos = dstart[digit] + wcnt[w][digit] + ((rk[r / 2] >> (16 * (r & 1))) & 0xFFFFu);
+            skey[pos] = k;
+            slot[i] = (uint16_t)pos;
+        }
+    }
+    __syncthreads();
+    const int64_t left = n - tile0;
+    const int cntile = (int)(left < RT_TILE ? left : RT_TILE);
+#pragma unroll 4
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int pos = r * RT_NT + tid;
+        if (pos < cntile) {
+            const uint32_t k = skey[pos];
+            const uint32_t digit = (k >> R.shift) & R.mask;
+            dest_out[gbase[digit] + ((uint32_t)pos - dstart[digit])] = k;
+        }
+    }
+    if (tid <= 256) dstart_out[(int64_t)blockIdx.x * 257 + tid] = dstart[tid];
+    if (tid < 256) gofs_out[(int64_t)blockIdx.x * 256 + tid] = gbase[tid] - dstart[tid];
+}
+
+__global__ __launch_bounds__(256) void route_offsets_kernel(const uint32_t *__restrict__ dest, int64_t n,
+                                                            uint16_t *__restrict__ off) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) off[i] = (uint16_t)(dest[i] & (RT_TILE - 1));
+}
+
+// ------------------------------------------------------------------------------------
+// the passes.  A source or destination with several components per value (the rows of X) is addressed as
+// base[(index) * stride + component]; the orders between the passes hold one array per component.
+// ------------------------------------------------------------------------------------
+// pass 1 or 2 forwards: tile of `in` (tile order, in2 added if given) -> runs of `out`
+__global__ __launch_bounds__(RT_NT) void route_deal_kernel(const float *__restrict__ in, const float *__restrict__ in2,
+                                                           float *__restrict__ out, const uint16_t *__restrict__ slot,
+                                                           const uint32_t *__restrict__ dstart_tab,
+                                                           const uint32_t *__restrict__ gofs_tab, int B, int64_t n) {
+    __shared__ float stage[RT_TILE];
+    __shared__ uint32_t ds[257], go[256];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t left = n - tile0;
+    const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
+    if (tid <= 256) ds[tid] = dstart_tab[(int64_t)blockIdx.x * 257 + tid];
+    if (tid < 256) go[tid] = gofs_tab[(int64_t)blockIdx.x * 256 + tid];
+    uint16_t sl[RT_IPT];
+    float v[RT_IPT];
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int e = r * RT_NT + tid;
+        sl[r] = e < cnt ? slot[tile0 + e] : (uint16_t)0;
+        v[r] = e < cnt ? in[tile0 + e] : 0.f;
+    }
+    if (in2) {
+#pragma unroll
+        for (int r = 0; r < RT_IPT; ++r) {
+            const int e = r * RT_NT + tid;
+            if (e < cnt) v[r] += in2[tile0 + e];
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r)
+        if (r * RT_NT + tid < cnt) stage[sl[r]] = v[r];
+    __syncthreads();
+    for (int b = w; b < B; b += RT_NW) {
+        const uint32_t s = ds[b], e = ds[b + 1], g = go[b];
+        for (uint32_t q = s + lane; q < e; q += 64) out[g + q] = stage[q];
+    }
+}
+
+// pass 2 or 1 backwards: runs of `in` -> tile of `out` (tile order); NC components, one array each on the
+// input side (in + c * in_stride); on the output side one array each (ROWS == false) or rows of NC values
+template <int NC, bool ROWS>
+__global__ __launch_bounds__(RT_NT) void route_collect_kernel(const float *__restrict__ in, int64_t in_stride,
+                                                              float *__restrict__ out, int64_t out_stride,
+                                                              const uint16_t *__restrict__ slot,
+                                                              const uint32_t *__restrict__ dstart_tab,
+                                                              const uint32_t *__restrict__ gofs_tab, int B, int64_t n) {
+    __shared__ float stage[RT_TILE];
+    __shared__ uint32_t ds[257], go[256];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t left = n - tile0;
+    const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
+    if (tid <= 256) ds[tid] = dstart_tab[(int64_t)blockIdx.x * 257 + tid];
+    if (tid < 256) go[tid] = gofs_tab[(int64_t)blockIdx.x * 256 + tid];
+    uint32_t sl[RT_IPT / 2];   // two places per register
+#pragma unroll
+    for (int r = 0; r < RT_IPT; r += 2) {
+        const int e0 = r * RT_NT + tid, e1 = e0 + RT_NT;
+        const uint32_t a = e0 < cnt ? slot[tile0 + e0] : 0u, b = e1 < cnt ? slot[tile0 + e1] : 0u;
+        sl[r / 2] = a | (b << 16);
+    }
+    __syncthreads();
+    float v[ROWS ? NC : 1][RT_IPT];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const float *src = in + (int64_t)c * in_stride;
+        for (int b = w; b < B; b += RT_NW) {
+            const uint32_t s = ds[b], e = ds[b + 1], g = go[b];
+            for (uint32_t q = s + lane; q < e; q += 64) stage[q] = src[g + q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < RT_IPT; ++r) v[ROWS ? c : 0][r] = stage[(sl[r / 2] >> (16 * (r & 1))) & 0xFFFFu];
+        if (!ROWS) {
+            float *dst = out + (int64_t)c * out_stride;
+#pragma unroll
+            for (int r = 0; r < RT_IPT; ++r) {
+                const int e = r * RT_NT + tid;
+                if (e < cnt) dst[tile0 + e] = v[0][r];
+            }
+        }
+        __syncthreads();
+    }
+    if (ROWS) {
+#pragma unroll
+        for (int r = 0; r < RT_IPT; ++r) {
+            const int e = r * RT_NT + tid;
+            if (e < cnt) {
+#pragma unroll
+                for (int c = 0; c < NC; ++c) out[(tile0 + e) * NC + c] = v[ROWS ? c : 0][r];
+            }
+        }
+    }
+}
+
+// pass 3 forwards: the values of a window, each to its place inside the window
+__global__ __launch_bounds__(RT_NT) void route_place_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                                            const uint16_t *__restrict__ off, int64_t n) {
+    __shared__ float stage[RT_TILE];
+    const int tid = threadIdx.x;
+    const int64_t win0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t left = n - win0;
+    const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
+    uint16_t o[RT_IPT];
+    float v[RT_IPT];
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int e = r * RT_NT + tid;
+        o[r] = e < cnt ? off[win0 + e] : (uint16_t)0;
+        v[r] = e < cnt ? in[win0 + e] : 0.f;
+    }
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r)
+        if (r * RT_NT + tid < cnt) stage[o[r]] = v[r];
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int e = r * RT_NT + tid;
+        if (e < cnt) out[win0 + e] = stage[e];
+    }
+}
+
+// pass 3 backwards: a window of the caller's array (NC values per row, row-major) -> order p2, one array per
+// component
+template <int NC>
+__global__ __launch_bounds__(RT_NT) void route_pick_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                                           int64_t out_stride, const uint16_t *__restrict__ off,
+                                                           int64_t n) {
+    __shared__ float stage[RT_TILE];
+    const int tid = threadIdx.x;
+    const int64_t win0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t left = n - win0;
+    const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
+    uint16_t o[RT_IPT];
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const int e = r * RT_NT + tid;
+        o[r] = e < cnt ? off[win0 + e] : (uint16_t)0;
+    }
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int r = 0; r < RT_IPT; ++r) {
+            const int e = r * RT_NT + tid;
+            if (e < cnt) stage[e] = in[(win0 + e) * NC + c];
+        }
+        __syncthreads();
+        float *dst = out + (int64_t)c * out_stride;
+#pragma unroll
+        for (int r = 0; r < RT_IPT; ++r) {
+            const int e = r * RT_NT + tid;
+            if (e < cnt) dst[win0 + e] = stage[o[r]];
+        }
+        __syncthreads();
+    }
+}
+
+struct RouteU32In {
+    const uint32_t *p;
+    __device__ uint64_t operator()(int64_t i) const { return p[i]; }
+};
+struct RouteU32Out {
+    uint32_t *p;
+    __device__ void operator()(int64_t i, uint64_t ex, uint64_t) const { p[i] = (uint32_t)ex; }
+};
+
+// ------------------------------------------------------------------------------------
+static RouteLevel route_level(const f3m_route &R, int pass) {
+    RouteLevel L{};
+    L.second = pass == 2;
+    L.s2 = R.s2;
+    L.ntiles = R.ntiles;
+    if (pass == 1) {
+        L.shift = RT_BITS + R.s2;
+        L.mask = 0xFFu;
+        L.B = R.B1;
+    } else {
+        L.shift = RT_BITS;
+        L.mask = (1u << R.s2) - 1u;
+        L.B = R.B2;
+    }
+    return L;
+}
+
+// Tables of the three passes for the permutation perm (n entries, box order -> caller's index).
+void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, hipStream_t st) {
+    R.n = n;
+    R.ntiles = cdiv(n, RT_TILE);
+    int wbits = 0;
+    while (((int64_t)1 << wbits) < R.ntiles) ++wbits;
+    R.s2 = (wbits + 1) / 2;
+    R.B2 = 1 << R.s2;
+    R.B1 = (int)cdiv(R.ntiles, R.B2);
+    if (R.B1 > 256 || R.B2 > 256) fail(F3M_ERR_UNSUPPORTED, "too many points for the three-pass permutation");
+    R.slot1.alloc((size_t)n, tally);
+    R.slot2.alloc((size_t)n, tally);
+    R.off3.alloc((size_t)n, tally);
+    R.dstart1.alloc((size_t)R.ntiles * 257, tally);
+    R.dstart2.alloc((size_t)R.ntiles * 257, tally);
+    R.gofs1.alloc((size_t)R.ntiles * 256, tally);
+    R.gofs2.alloc((size_t)R.ntiles * 256, tally);
+    DevBuf<uint32_t> dest1, dest2, cnt;
+    dest1.alloc((size_t)n);
+    dest2.alloc((size_t)n);
+    const int64_t ncnt = std::max<int64_t>((int64_t)R.B1 * R.ntiles, (int64_t)R.B1 * R.B2 * R.B2);
+    cnt.alloc((size_t)ncnt);
+    const unsigned grid = (unsigned)R.ntiles;
+    for (int pass = 1; pass <= 2; ++pass) {
+        const RouteLevel L = route_level(R, pass);
+        const uint32_t *din = pass == 1 ? perm : dest1.p;
+        F3M_HIP(hipMemsetAsync(cnt.p, 0, (size_t)ncnt * sizeof(uint32_t), st));
+        route_hist_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(din, n, L, cnt.p);
+        F3M_HIP(hipGetLastError());
+        exclusive_scan(RouteU32In{cnt.p}, ncnt, RouteU32Out{cnt.p}, nullptr, st);
+        route_rank_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(din, n, L, cnt.p, pass == 1 ? R.slot1.p : R.slot2.p,
+                                                             pass == 1 ? dest1.p : dest2.p,
+                                                             pass == 1 ? R.dstart1.p : R.dstart2.p,
+                                                             pass == 1 ? R.gofs1.p : R.gofs2.p);
+        F3M_HIP(hipGetLastError());
+    }
+    route_offsets_kernel<<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(dest2.p, n, R.off3.p);
+    F3M_HIP(hipGetLastError());
+    F3M_HIP(hipStreamSynchronize(st));   // the work arrays are released on return
+}
+
+// out[perm[k]] = in[k] (+ in2[k]); tmp_a, tmp_b: n floats each
+void route_scatter(const f3m_route &R, const float *in, const float *in2, float *out, float *tmp_a, float *tmp_b,
+                   hipStream_t st) {
+    const unsigned grid = (unsigned)R.ntiles;
+    route_deal_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(in, in2, tmp_a, R.slot1.p, R.dstart1.p, R.gofs1.p, R.B1, R.n);
+    route_deal_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp_a, nullptr, tmp_b, R.slot2.p, R.dstart2.p, R.gofs2.p, R.B2,
+                                                         R.n);
+    route_place_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp_b, out, R.off3.p, R.n);
+    F3M_HIP(hipGetLastError());
+}
+
+// out[k] = in[perm[k]]; tmp_a, tmp_b: n floats each
+void route_gather(const f3m_route &R, const float *in, float *out, float *tmp_a, float *tmp_b, hipStream_t st) {
+    const unsigned grid = (unsigned)R.ntiles;
+    route_pick_kernel<1><<<dim3(grid), dim3(RT_NT), 0, st>>>(in, tmp_a, 0, R.off3.p, R.n);
+    route_collect_kernel<1, false><<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp_a, 0, tmp_b, 0, R.slot2.p, R.dstart2.p,
+                                                                      R.gofs2.p, R.B2, R.n);
+    route_collect_kernel<1, false><<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp_b, 0, out, 0, R.slot1.p, R.dstart1.p,
+                                                                      R.gofs1.p, R.B1, R.n);
+    F3M_HIP(hipGetLastError());
+}
+
+// rows of three coordinates: out[k][0..2] = in[perm[k]][0..2].  `out` (3 n floats) first serves as the
+// three component arrays of order p2; tmp: 3 n floats.
+void route_gather_rows3(const f3m_route &R, const float *in, float *out, float *tmp, hipStream_t st) {
+    const unsigned grid = (unsigned)R.ntiles;
+    route_pick_kernel<3><<<dim3(grid), dim3(RT_NT), 0, st>>>(in, out, R.n, R.off3.p, R.n);
+    route_collect_kernel<3, false><<<dim3(grid), dim3(RT_NT), 0, st>>>(out, R.n, tmp, R.n, R.slot2.p, R.dstart2.p,
+                                                                      R.gofs2.p, R.B2, R.n);
+    route_collect_kernel<3, true><<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp, R.n, out, 0, R.slot1.p, R.dstart1.p,
+                                                                     R.gofs1.p, R.B1, R.n);
+    F3M_HIP(hipGetLastError());
+}
+
+}  // namespace f3m

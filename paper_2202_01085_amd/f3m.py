@@ -29,7 +29,8 @@ class F3MError(RuntimeError):
 class Options(ctypes.Structure):
     _fields_ = [("leaf_max", ctypes.c_int32), ("max_depth", ctypes.c_int32),
                 ("force_all_near", ctypes.c_int32), ("overlap", ctypes.c_int32),
-                ("eta_smooth", ctypes.c_float), ("adaptive_far", ctypes.c_int32), ("small_field", ctypes.c_int32)]
+                ("eta_smooth", ctypes.c_float), ("adaptive_far", ctypes.c_int32), ("small_field", ctypes.c_int32),
+                ("route_min_points", ctypes.c_int32)]
 
 
 class Info(ctypes.Structure):
@@ -136,13 +137,14 @@ class Plan:
     with Y given, f3m_plan_xy: targets X and sources Y, for v = K(X, Y) b."""
 
     def __init__(self, X, lengthscale, interp_nodes, eta=2.0, leaf_max=0, max_depth=0, force_all_near=False,
-                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False, small_field=0, Y=None):
+                 overlap=False, stream=None, eta_smooth=0.0, adaptive_far=False, small_field=0, Y=None,
+                 route_min_points=0):
         n, D = X.shape
         self.n, self.D = int(n), int(D)
         self.ns = self.n
         self._h = ctypes.c_void_p()
         opt = Options(int(leaf_max), int(max_depth), int(bool(force_all_near)), int(bool(overlap)),
-                      float(eta_smooth), int(bool(adaptive_far)), int(small_field))
+                      float(eta_smooth), int(bool(adaptive_far)), int(small_field), int(route_min_points))
         xp = _dev_f32(X, "X") if n > 0 else ctypes.c_void_p()
         if Y is None:
             _check(lib().f3m_plan_ex(xp, self.n, self.D, float(lengthscale), int(interp_nodes), float(eta),

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_struct_sizes_match_the_header():
-    assert ctypes.sizeof(f3m.Options) == 4 * 4 + 4 + 4 + 4
+    assert ctypes.sizeof(f3m.Options) == 4 * 4 + 4 + 4 + 4 + 4
     assert ctypes.sizeof(f3m.Info) == 8 + 6 * 4 + 2 * 4 + 7 * 4 + 4 + 5 * 21 * 8 + 8 + 8 + 4 + 21 * 4 + 2 * 21 * 8
     assert ctypes.sizeof(f3m.Times) == 14 * 4
     assert ctypes.sizeof(f3m.SourceInfo) == 8 + 4 + 7 * 4 + 2 * 21 * 8

@@ -781,3 +781,93 @@ def test_small_field_keeps_low_degree_exactness_and_does_not_hurt_accuracy():
     e0 = rel(oracle.f3m(X, b, 0.4, 4, zeta=16))
     e1 = rel(oracle.f3m(X, b, 0.4, 4, zeta=16, small_field=128))
     assert e1 <= 1.05 * e0
+
+
+# ----------------------------------------------------------------------------
+# a subset of the rows of the product (Sec. 5, first paragraph: results are compared on a subset of
+# rows): the row-subset mode runs the steps of Algorithm 1 over the boxes that hold the wanted rows
+# only, and must give the bits of the full product; a tree built for a row subset must hold the rows
+# of the full lists for exactly the boxes with a wanted point
+# ----------------------------------------------------------------------------
+ROWS_CASES = [
+    # n, D, dist, p, gamma, theta, zeta, eta_smooth, adaptive
+    (6000, 3, "uniform", 4, 0.3, 2.0, 32, 0.0, False),
+    (3000, 2, "normal", 5, 0.2, 1.5, 16, 0.0, False),
+    (4000, 3, "uniform", 4, 0.3, 2.0, 32, 0.3, True),
+    (1500, 5, "mixture", 2, 1.0, 2.0, 8, 0.0, False),
+    (900, 7, "mixture", 2, 1.5, 3.0, 4, 0.0, False),
+]
+
+
+@pytest.mark.parametrize("n,D,dist,p,gamma,theta,zeta,eta_smooth,adaptive", ROWS_CASES)
+def test_row_subset_gives_the_bits_of_the_full_product(n, D, dist, p, gamma, theta, zeta, eta_smooth, adaptive):
+    X = _cloud(n, D, 71 + D, dist)
+    b = inputs.rhs_normal(n, 72).numpy()
+    T = oracle.Tree(X, theta=theta, zeta=zeta, gamma=gamma, eta_smooth=eta_smooth)
+    y = T.apply(b, gamma, p, adaptive=adaptive)
+    rows = inputs.sample_rows(n, 41, 73).numpy()
+    rows = np.concatenate([rows, rows[:4], [0, n - 1]])          # duplicates and the end points
+    assert np.array_equal(T.apply_rows(b, gamma, p, rows, adaptive=adaptive), y[rows])
+    # one row, and all rows in reverse order
+    assert np.array_equal(T.apply_rows(b, gamma, p, [rows[5]], adaptive=adaptive), y[rows[5:6]])
+    everything = np.arange(n)[::-1]
+    assert np.array_equal(T.apply_rows(b, gamma, p, everything, adaptive=adaptive), y[everything])
+    # the tree built for these rows: same partition and depth, the rows of the full lists for the boxes
+    # that hold a wanted point, empty rows elsewhere; and the same bits of y
+    Tr = oracle.Tree(X, theta=theta, zeta=zeta, gamma=gamma, eta_smooth=eta_smooth, rows=rows)
+    assert Tr.L == T.L and Tr.smooth_depth == T.smooth_depth and np.array_equal(Tr.perm(), T.perm())
+    inv = np.empty(n, dtype=np.int64)
+    inv[T.perm()] = np.arange(n)
+    for l in range(T.L + 1):
+        starts = T.boxes(l)[1]
+        assert np.array_equal(Tr.boxes(l)[0], T.boxes(l)[0]) and np.array_equal(Tr.boxes(l)[1], starts)
+        holds = np.zeros(len(starts) - 1, dtype=bool)
+        holds[np.searchsorted(starts, inv[rows], side="right") - 1] = True
+        for kind in (0, 1):
+            ptr, cols = T.interactions(l, kind)
+            rptr, rcols = Tr.interactions(l, kind)
+            lens = np.where(holds, np.diff(ptr), 0) if l > 0 else np.diff(ptr)
+            assert np.array_equal(np.diff(rptr), lens)
+            for a in np.flatnonzero(holds):
+                assert np.array_equal(rcols[rptr[a]:rptr[a + 1]], cols[ptr[a]:ptr[a + 1]])
+    assert np.array_equal(Tr.apply_rows(b, gamma, p, rows, adaptive=adaptive), y[rows])
+    # a row outside the subset has no interaction rows in that tree, and the full product needs them all
+    other = int(np.setdiff1d(np.arange(n), rows)[0])
+    with pytest.raises(ValueError):
+        Tr.apply_rows(b, gamma, p, [other])
+    with pytest.raises(ValueError):
+        Tr.apply(b, gamma, p)
+
+
+def test_row_subset_with_every_pair_near_is_the_exact_row():
+    # pinned to the hand-checked exact sums, not to the full product: all-near rows are oracle.rows
+    n = 2500
+    X = _cloud(n, 3, 81, "normal")
+    b = inputs.rhs_normal(n, 82).numpy()
+    rows = inputs.sample_rows(n, 60, 83).numpy()
+    T = oracle.Tree(X, zeta=16, force_all_near=True, rows=rows)
+    got = T.apply_rows(b, 0.4, 4, rows)
+    want = oracle.rows(X, b, 0.4, rows)
+    assert np.max(np.abs(got - want)) <= 1e-12 * np.max(np.abs(want))
+
+
+def test_row_subset_is_exact_for_polynomial_kernels():
+    # far-field machinery of the subset mode against brute force with a kernel of degree < p
+    n = 3000
+    X = _cloud(n, 3, 84, "uniform")
+    b = inputs.rhs_normal(n, 85).numpy()
+    rows = inputs.sample_rows(n, 50, 86).numpy()
+    T = oracle.Tree(X, zeta=16, rows=rows)
+    assert T.L >= 3
+    got = T.apply_rows(b, 1.0, 4, rows, kernel_id=2, kparam=3)
+    want = oracle.rows(X, b, 1.0, rows, kernel_id=2, kparam=3)
+    assert np.max(np.abs(got - want)) <= 1e-10 * np.max(np.abs(want))
+
+
+def test_large_input_sort_path_gives_the_same_order():
+    # above 2^20 points the (key, index) pairs are dealt into buckets before sorting: same unique order
+    n = (1 << 20) + 12345
+    X = inputs.points_normal(n, 3, 87).numpy()
+    T = oracle.Tree(X, zeta=1 << 30)           # depth 0: only the partition is built
+    pk = T.point_keys()
+    assert np.array_equal(T.perm(), np.lexsort((np.arange(n), pk)))
