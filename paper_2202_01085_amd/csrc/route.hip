@@ -10,6 +10,7 @@
 //   pass 2  deals every tile of T consecutive p1 (a tile lies inside one bucket) into the B2 windows of that
 //           bucket (window w receives exactly its T values, at w T ...);
 //   pass 3  puts the T values of a window in their places inside LDS and writes the window out in one piece.
+// (T = 32768 because 128 KB of the 160 KB of LDS then hold one tile of floats.)
 // Every pass reads and writes runs that are contiguous in memory (some hundred values per bucket and tile),
 // and the places (the position of a value in the LDS copy of its tile, 16 bits per value and pass) depend on
 // perm only: they are computed once per plan by route_build, so a pass moves data and does nothing else.
@@ -64,6 +65,7 @@ __global__ __launch_bounds__(RT_NT) void route_hist_kernel(const uint32_t *__res
 __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__restrict__ dest_in, int64_t n, RouteLevel R,
                                                            const uint32_t *__restrict__ offs,
                                                            uint16_t *__restrict__ slot, uint32_t *__restrict__ dest_out,
+                                                           uint16_t *__restrict__ off_out,
                                                            uint32_t *__restrict__ dstart_out,
                                                            uint32_t *__restrict__ gofs_out) {
     __shared__ uint32_t wcnt[RT_NW][256];   // per wave: values of each digit seen so far; later the wave's offset
@@ -80,35 +82,39 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
     const int64_t base = tile0 + (int64_t)w * (RT_IPT * 64);
-    uint32_t key[RT_IPT];
     uint32_t rk[RT_IPT / 2];   // rank within (wave, digit), below 2048: two per register
-#pragma unroll
-    for (int r = 0; r < RT_IPT; ++r) {
-        const int64_t i = base + r * 64 + lane;
-        key[r] = i < n ? dest_in[i] : 0u;
-    }
 #pragma unroll
     for (int r = 0; r < RT_IPT / 2; ++r) rk[r] = 0u;
 #pragma unroll
-    for (int r = 0; r < RT_IPT; ++r) {
-        const int64_t i = base + r * 64 + lane;
-        const bool valid = i < n;
-        const uint32_t digit = (key[r] >> R.shift) & R.mask;
-        uint64_t peers = __ballot(valid);
+    for (int h = 0; h < RT_IPT; h += 8) {   // eight rounds at a time: their loads are in flight together
+        uint32_t key[8];
 #pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const bool bit = (digit >> b) & 1u;
-            const uint64_t m = __ballot(bit);
-            peers &= bit ? m : ~m;
+        for (int r = 0; r < 8; ++r) {
+            const int64_t i = base + (h + r) * 64 + lane;
+            key[r] = i < n ? dest_in[i] : 0u;
         }
-        const uint32_t before = (uint32_t)__popcll(peers & lt_mask);
-        uint32_t cnt = 0;
-        if (valid) cnt = wcnt[w][digit];
-        rk[r / 2] |= (cnt + before) << (16 * (r & 1));
-        // the wave runs in lockstep and its LDS operations complete in order: every lane has read the
-        // counter before the first lane of each digit group updates it
-        if (valid && before == 0) wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
-        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int64_t i = base + (h + r) * 64 + lane;
+            const bool valid = i < n;
+            const uint32_t digit = (key[r] >> R.shift) & R.mask;
+            uint64_t peers = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bool bit = (digit >> b) & 1u;
+                const uint64_t m = __ballot(bit);
+                peers &= bit ? m : ~m;
+            }
+            const uint32_t before = (uint32_t)__popcll(peers & lt_mask);
+            uint32_t cnt = 0;
+            if (valid) cnt = wcnt[w][digit];
+            rk[(h + r) / 2] |= (cnt + before) << (16 * ((h + r) & 1));
+            // the wave runs in lockstep and its LDS operations complete in order: every lane has read the
+            // counter before the first lane of each digit group updates it
+            if (valid && before == 0) wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
+            __builtin_amdgcn_wave_barrier();
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
     // per digit: the waves' counts become the waves' offsets; the totals go to dstart
@@ -134,15 +140,24 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < RT_IPT; ++r) {
-        const int64_t i = base + r * 64 + lane;
-        if (i < n) {
-            const uint32_t k = dest_in[i];   // read again: keeping the first copy would not fit the registers
-            const uint32_t digit = (k >> R.shift) & R.mask;
-            const uint32_t pos = dstart[digit] + wcnt[w][digit] + ((rk[r / 2] >> (16 * (r & 1))) & 0xFFFFu);
-            skey[pos] = k;
-            slot[i] = (uint16_t)pos;
+    for (int h = 0; h < RT_IPT; h += 8) {
+        uint32_t key[8];   // read again: keeping the first copy would not fit the registers
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int64_t i = base + (h + r) * 64 + lane;
+            key[r] = i < n ? dest_in[i] : 0u;
         }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int64_t i = base + (h + r) * 64 + lane;
+            if (i < n) {
+                const uint32_t digit = (key[r] >> R.shift) & R.mask;
+                const uint32_t pos = dstart[digit] + wcnt[w][digit] + ((rk[(h + r) / 2] >> (16 * ((h + r) & 1))) & 0xFFFFu);
+                skey[pos] = key[r];
+                slot[i] = (uint16_t)pos;
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keeps the chunks apart: all 32 loads at once would not fit the registers
     }
     __syncthreads();
     const int64_t left = n - tile0;
@@ -153,23 +168,29 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
         if (pos < cntile) {
             const uint32_t k = skey[pos];
             const uint32_t digit = (k >> R.shift) & R.mask;
-            dest_out[gbase[digit] + ((uint32_t)pos - dstart[digit])] = k;
+            const uint32_t g = gbase[digit] + ((uint32_t)pos - dstart[digit]);
+            // the last pass needs no more than the place inside the window
+            if (off_out) off_out[g] = (uint16_t)(k & (RT_TILE - 1));
+            else dest_out[g] = k;
         }
     }
     if (tid <= 256) dstart_out[(int64_t)blockIdx.x * 257 + tid] = dstart[tid];
     if (tid < 256) gofs_out[(int64_t)blockIdx.x * 256 + tid] = gbase[tid] - dstart[tid];
 }
 
-__global__ __launch_bounds__(256) void route_offsets_kernel(const uint32_t *__restrict__ dest, int64_t n,
-                                                            uint16_t *__restrict__ off) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) off[i] = (uint16_t)(dest[i] & (RT_TILE - 1));
-}
-
 // ------------------------------------------------------------------------------------
 // the passes.  A source or destination with several components per value (the rows of X) is addressed as
 // base[(index) * stride + component]; the orders between the passes hold one array per component.
 // ------------------------------------------------------------------------------------
+// digit whose run of places [ds[b], ds[b+1]) holds place q (ds ascending, ds[256] = values of the tile)
+__device__ inline int route_digit_of(const uint32_t *ds, uint32_t q) {
+    int b = 0;
+#pragma unroll
+    for (int step = 128; step >= 1; step >>= 1)
+        if (ds[b + step] <= q) b += step;
+    return b;
+}
+
 // pass 1 or 2 forwards: tile of `in` (tile order, in2 added if given) -> runs of `out`
 __global__ __launch_bounds__(RT_NT) void route_deal_kernel(const float *__restrict__ in, const float *__restrict__ in2,
                                                            float *__restrict__ out, const uint16_t *__restrict__ slot,
@@ -177,7 +198,7 @@ __global__ __launch_bounds__(RT_NT) void route_deal_kernel(const float *__restri
                                                            const uint32_t *__restrict__ gofs_tab, int B, int64_t n) {
     __shared__ float stage[RT_TILE];
     __shared__ uint32_t ds[257], go[256];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x;
     const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
     const int64_t left = n - tile0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
@@ -202,9 +223,12 @@ __global__ __launch_bounds__(RT_NT) void route_deal_kernel(const float *__restri
     for (int r = 0; r < RT_IPT; ++r)
         if (r * RT_NT + tid < cnt) stage[sl[r]] = v[r];
     __syncthreads();
-    for (int b = w; b < B; b += RT_NW) {
-        const uint32_t s = ds[b], e = ds[b + 1], g = go[b];
-        for (uint32_t q = s + lane; q < e; q += 64) out[g + q] = stage[q];
+    // a thread per place: consecutive places of a run go to consecutive addresses, and all the stores of a
+    // thread are independent (a wavefront per run would wait for one short run after the other)
+#pragma unroll
+    for (int r = 0; r < RT_IPT; ++r) {
+        const uint32_t q = (uint32_t)(r * RT_NT + tid);
+        if ((int)q < cnt) out[go[route_digit_of(ds, q)] + q] = stage[q];
     }
 }
 
@@ -218,7 +242,7 @@ __global__ __launch_bounds__(RT_NT) void route_collect_kernel(const float *__res
                                                               const uint32_t *__restrict__ gofs_tab, int B, int64_t n) {
     __shared__ float stage[RT_TILE];
     __shared__ uint32_t ds[257], go[256];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x;
     const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
     const int64_t left = n - tile0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
@@ -233,12 +257,21 @@ __global__ __launch_bounds__(RT_NT) void route_collect_kernel(const float *__res
     }
     __syncthreads();
     float v[ROWS ? NC : 1][RT_IPT];
+    // a thread per place (see route_deal_kernel): place q comes from go[digit of q] + q in the order before
+    constexpr int FLY = ROWS ? 8 : 16;   // loads in flight per thread (the row variant is short of registers)
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const float *src = in + (int64_t)c * in_stride;
-        for (int b = w; b < B; b += RT_NW) {
-            const uint32_t s = ds[b], e = ds[b + 1], g = go[b];
-            for (uint32_t q = s + lane; q < e; q += 64) stage[q] = src[g + q];
+#pragma unroll
+        for (int h = 0; h < RT_IPT; h += FLY) {
+            float t[FLY];
+#pragma unroll
+            for (int r = 0; r < FLY; ++r) {
+                const uint32_t q = (uint32_t)((h + r) * RT_NT + tid);
+                t[r] = (int)q < cnt ? src[go[route_digit_of(ds, q)] + q] : 0.f;
+            }
+#pragma unroll
+            for (int r = 0; r < FLY; ++r) stage[(h + r) * RT_NT + tid] = t[r];
         }
         __syncthreads();
 #pragma unroll
@@ -371,9 +404,8 @@ void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, 
     R.dstart2.alloc((size_t)R.ntiles * 257, tally);
     R.gofs1.alloc((size_t)R.ntiles * 256, tally);
     R.gofs2.alloc((size_t)R.ntiles * 256, tally);
-    DevBuf<uint32_t> dest1, dest2, cnt;
+    DevBuf<uint32_t> dest1, cnt;
     dest1.alloc((size_t)n);
-    dest2.alloc((size_t)n);
     const int64_t ncnt = std::max<int64_t>((int64_t)R.B1 * R.ntiles, (int64_t)R.B1 * R.B2 * R.B2);
     cnt.alloc((size_t)ncnt);
     const unsigned grid = (unsigned)R.ntiles;
@@ -385,13 +417,12 @@ void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, 
         F3M_HIP(hipGetLastError());
         exclusive_scan(RouteU32In{cnt.p}, ncnt, RouteU32Out{cnt.p}, nullptr, st);
         route_rank_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(din, n, L, cnt.p, pass == 1 ? R.slot1.p : R.slot2.p,
-                                                             pass == 1 ? dest1.p : dest2.p,
+                                                             pass == 1 ? dest1.p : nullptr,
+                                                             pass == 1 ? nullptr : R.off3.p,
                                                              pass == 1 ? R.dstart1.p : R.dstart2.p,
                                                              pass == 1 ? R.gofs1.p : R.gofs2.p);
         F3M_HIP(hipGetLastError());
     }
-    route_offsets_kernel<<<dim3((unsigned)cdiv(n, 256)), dim3(256), 0, st>>>(dest2.p, n, R.off3.p);
-    F3M_HIP(hipGetLastError());
     F3M_HIP(hipStreamSynchronize(st));   // the work arrays are released on return
 }
 
