@@ -294,7 +294,9 @@ def main():
             kernel = "m2l_stencil_shared_kernel"
         else:
             executed = 2.0 * D * r * cfg["p"] * far_L
-            kernel = "m2l_kron_small_kernel" if r // cfg["p"] <= 32 else "m2l_kron_kernel"
+            kernel = "m2l_kron_small_kernel" if r // cfg["p"] <= 32 else \
+                "m2l_kron_grouped_kernel (shares partial sums between far partners, so it executes fewer than the " \
+                "2 D r p flop per far pair counted here)"
         ach = executed / t / 1e12
         rooflines["m2l"] = {"kernel": "%s, leaf depth %d, %d far pairs, %d target boxes" % (kernel, L, far_L, nb_L),
                             "bound": "alu", "achieved": ach, "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s",

@@ -6,6 +6,7 @@
 #include <cmath>
 
 #include <mutex>
+#include <type_traits>
 
 #include "plan.h"
 
@@ -1511,125 +1512,206 @@ constexpr int kron_max_fibres(int p) {
     return r / p;
 }
 
-template <int PN>
-__global__ __launch_bounds__(64) void m2l_kron_kernel(const int32_t *__restrict__ cellT,
-                                                      const int32_t *__restrict__ cellS,
-                                                      const uint64_t *__restrict__ far_ptr,
-                                                      const uint32_t *__restrict__ far_col, int64_t nb, int D, int r,
-                                                      const float *__restrict__ G, KronShape S,
-                                                      const float *__restrict__ W, float *__restrict__ V) {
-    constexpr int NF = (kron_max_fibres(PN) + 63) / 64;   // fibres per lane, at most
-    extern __shared__ float lds[];                        // [r]
+// ---- far rows in the order of the row-major cell index ------------------------------------------
+// The grouped M2L below shares work between far partners whose cells differ in the leading dimensions
+// only, so it wants the partners of a target ordered by (c_{D-1}, ..., c_1, c_0), most significant first:
+// ascending row-major index beta = sum_d c_d 2^(depth d) (the box index of Sec. 4.2).  The far lists are
+// stored ascending in the interleaved key; far_ord holds every row once more in beta order.  A row is
+// sorted in pieces of at most FO_CH entries (bitonic network in LDS); the M2L is correct for any
+// order, a piece boundary only costs it a few shared sums.
+constexpr int FO_CH = 16384;
+__global__ __launch_bounds__(1024) void far_order_kernel(const uint64_t *__restrict__ far_ptr,
+                                                         const uint32_t *__restrict__ far_col,
+                                                         const int32_t *__restrict__ cellS, int D, int depth, int64_t nb,
+                                                         uint32_t *__restrict__ far_ord) {
+    __shared__ uint64_t key[FO_CH];
+    const int64_t a = block_index();
+    if (a >= nb) return;
+    const int tid = threadIdx.x;
+    const uint64_t e0 = far_ptr[a], e1 = far_ptr[a + 1];
+    for (uint64_t c0 = e0; c0 < e1; c0 += FO_CH) {
+        const int len = (int)(e1 - c0 < (uint64_t)FO_CH ? e1 - c0 : (uint64_t)FO_CH);
+        int n2 = 2;
+        while (n2 < len) n2 <<= 1;
+        for (int i = tid; i < n2; i += 1024) {
+            uint64_t k = ~0ull;
+            if (i < len) {
+                const uint32_t q = far_col[c0 + i];
+                uint64_t beta = 0;
+                for (int d = 0; d < D; ++d) beta |= (uint64_t)(uint32_t)cellS[(int64_t)q * D + d] << (depth * d);
+                k = (beta << 32) | q;
+            }
+            key[i] = k;
+        }
+        __syncthreads();
+        for (int k = 2; k <= n2; k <<= 1)
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int i = tid; i < n2; i += 1024) {
+                    const int ixj = i ^ j;
+                    if (ixj > i) {
+                        const uint64_t x = key[i], y = key[ixj];
+                        if ((x > y) == ((i & k) == 0)) {
+                            key[i] = y;
+                            key[ixj] = x;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        for (int i = tid; i < len; i += 1024) far_ord[c0 + i] = (uint32_t)key[i];
+        __syncthreads();
+    }
+}
+
+constexpr int ipow_c(int p, int d) { return d <= 0 ? 1 : p * ipow_c(p, d - 1); }
+
+// Grouped M2L: the far partners q of a target t are taken in the order of far_ord, and the sum
+//   V_t = sum_q (G_{o_{D-1}(q)} x ... x G_{o_0(q)}) W_q
+// is nested over the dimensions,
+//   V_t = sum_{o_{D-1}} G_{o_{D-1}} [ sum_{o_{D-2}} G_{o_{D-2}} [ ... sum_{o_0} G_{o_0} W_q ] ]:
+// level d keeps a partial sum S_d over the partners that agree in (o_{d+1}, ..., o_{D-1}); when the next
+// partner differs in one of those, S_d is multiplied by the factor of dimension d+1 and added to S_{d+1}
+// ("flush").  Every partner costs one factor (dimension 0, on data straight from global memory), every
+// group of a level one more, instead of D factors per partner: the same sums as the dense products, in
+// another order.  For partners in any other order the result is the same (more flushes).
+// One workgroup of 256 threads per target; a thread owns up to NFL fibres of every dimension (a fibre =
+// the p entries along one dimension) and keeps S_d of its fibres of dimension d in registers; a flush
+// passes S_d through LDS (node layout) to the owners of the fibres of dimension d+1, alternating
+// between two buffers so that one barrier per flush is enough.
+template <int PN, int DD>
+__global__ __launch_bounds__(256) void m2l_kron_grouped_kernel(const int32_t *__restrict__ cellT,
+                                                               const int32_t *__restrict__ cellS,
+                                                               const uint64_t *__restrict__ far_ptr,
+                                                               const uint32_t *__restrict__ far_ord, int64_t nb,
+                                                               const float *__restrict__ G, KronShape S,
+                                                               const float *__restrict__ W, float *__restrict__ V) {
+    constexpr int R = ipow_c(PN, DD), NFIB = R / PN, NFL = (NFIB + 255) / 256;
+    __shared__ float buf[2][R];
     const int64_t a = block_index();
     if (a >= nb) return;
     const uint64_t e0 = far_ptr[a], e1 = far_ptr[a + 1];
-    if (e0 == e1) return;
-    const int lane = threadIdx.x;
-    const int nfib = r / PN;
-    float acc[NF][PN];
+    if (e0 == e1) return;   // no far partner at this depth: the row of V is left alone
+    const int tid = threadIdx.x;
+    float acc[DD][NFL][PN];
 #pragma unroll
-    for (int k = 0; k < NF; ++k)
+    for (int d = 0; d < DD; ++d)
 #pragma unroll
-        for (int i = 0; i < PN; ++i) acc[k][i] = 0.f;
-    int ca[F3M_MAX_DIM];
-    for (int d = 0; d < D; ++d) ca[d] = cellT[a * D + d];
+        for (int k = 0; k < NFL; ++k)
+#pragma unroll
+            for (int i = 0; i < PN; ++i) acc[d][k][i] = 0.f;
+    int ca[DD], prev[DD];
+#pragma unroll
+    for (int d = 0; d < DD; ++d) ca[d] = cellT[a * DD + d];
     // factor matrix of dimension d for a source cell coordinate (the index is clamped to the table:
     // every far pair lies inside it by construction)
-    auto factor = [&](int d, int cs) {
+    auto factor = [&](int d, int cs) __attribute__((always_inline)) {
         int k = cs - ca[d] - S.omin[d];
         k = k < 0 ? 0 : (k >= S.no ? S.no - 1 : k);
         return G + ((int64_t)d * S.no + k) * (PN * PN);
     };
-
-    // out[i] = sum_j g[i][j] in[j] with g wave-uniform
-    auto apply = [&](const float *__restrict__ g, const float (&in)[PN], float (&out)[PN]) {
+    int flip = 0;
+    // S_d, times the factor of dimension d+1 for source cell coordinate cs1, is added to S_{d+1}; S_d = 0
+    auto flush = [&](auto dconst, int cs1) __attribute__((always_inline)) {
+        constexpr int d = decltype(dconst)::value;
+        constexpr int sd = ipow_c(PN, d), sd1 = sd * PN;
+        float *B = buf[flip];
+        flip ^= 1;
 #pragma unroll
-        for (int i = 0; i < PN; ++i) {
-            float t = 0.f;
+        for (int k = 0; k < NFL; ++k) {
+            const int f = tid + 256 * k;
+            if (f < NFIB) {
+                const int hi = f / sd, base = hi * sd1 + (f - hi * sd);
 #pragma unroll
-            for (int j = 0; j < PN; ++j) t = fmaf(g[i * PN + j], in[j], t);
-            out[i] = t;
+                for (int j = 0; j < PN; ++j) {
+                    B[base + j * sd] = acc[d][k][j];
+                    acc[d][k][j] = 0.f;
+                }
+            }
+        }
+        __syncthreads();
+        const float *__restrict__ g = factor(d + 1, cs1);
+#pragma unroll
+        for (int k = 0; k < NFL; ++k) {
+            const int f = tid + 256 * k;
+            if (f < NFIB) {
+                const int hi = f / sd1, base = hi * sd1 * PN + (f - hi * sd1);
+                float in[PN];
+#pragma unroll
+                for (int j = 0; j < PN; ++j) in[j] = B[base + j * sd1];
+#pragma unroll
+                for (int i = 0; i < PN; ++i) {
+                    float t = acc[d + 1][k][i];
+#pragma unroll
+                    for (int j = 0; j < PN; ++j) t = fmaf(g[i * PN + j], in[j], t);
+                    acc[d + 1][k][i] = t;
+                }
+            }
         }
     };
+    // the levels below `upto` end their groups (upto = DD: all of them)
+    auto flush_below = [&](int upto) __attribute__((always_inline)) {
+        if constexpr (DD > 1) { if (upto > 0) flush(std::integral_constant<int, 0>{}, prev[1]); }
+        if constexpr (DD > 2) { if (upto > 1) flush(std::integral_constant<int, 1>{}, prev[2]); }
+        if constexpr (DD > 3) { if (upto > 2) flush(std::integral_constant<int, 2>{}, prev[3]); }
+        if constexpr (DD > 4) { if (upto > 3) flush(std::integral_constant<int, 3>{}, prev[4]); }
+        if constexpr (DD > 5) { if (upto > 4) flush(std::integral_constant<int, 4>{}, prev[5]); }
+        if constexpr (DD > 6) { if (upto > 5) flush(std::integral_constant<int, 5>{}, prev[6]); }
+    };
+    // the fibres of dimension 0 of a partner's node weights: p consecutive floats each
+    auto load = [&](uint32_t q, float (&w)[NFL][PN]) __attribute__((always_inline)) {
+        const float *Wq = W + (int64_t)q * R;
+#pragma unroll
+        for (int k = 0; k < NFL; ++k) {
+            const int f = tid + 256 * k;
+#pragma unroll
+            for (int j = 0; j < PN; ++j) w[k][j] = f < NFIB ? Wq[f * PN + j] : 0.f;
+        }
+    };
+    float wn[NFL][PN];
+    uint32_t qn = __builtin_amdgcn_readfirstlane(far_ord[e0]);
+    load(qn, wn);
     for (uint64_t e = e0; e < e1; ++e) {
-        const uint32_t q = __builtin_amdgcn_readfirstlane(far_col[e]);
-        const float *Wq = W + (int64_t)q * r;
-        float *cur = lds;
-        __syncthreads();   // the last pass of the previous pair has read the buffer
-        {
-            const float *g = factor(0, cellS[(int64_t)q * D]);
+        const uint32_t q = qn;
+        float wc[NFL][PN];
 #pragma unroll
-            for (int k = 0; k < NF; ++k) {
-                if (64 * k >= nfib) break;
-                const int f = lane + 64 * k;
-                if (f < nfib) {
-                    float in[PN], out[PN];
+        for (int k = 0; k < NFL; ++k)
 #pragma unroll
-                    for (int j = 0; j < PN; ++j) in[j] = Wq[f * PN + j];
-                    apply(g, in, out);
-                    if (D == 1) {
-#pragma unroll
-                        for (int i = 0; i < PN; ++i) acc[k][i] += out[i];
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < PN; ++i) cur[f + i * nfib] = out[i];
-                    }
-                }
-            }
+            for (int j = 0; j < PN; ++j) wc[k][j] = wn[k][j];
+        if (e + 1 < e1) {   // the next partner's weights are on their way during this one's sums
+            qn = __builtin_amdgcn_readfirstlane(far_ord[e + 1]);
+            load(qn, wn);
         }
-        int stride = 1;   // of dimension d in the LDS layout (dimensions 1..D-1 fastest first, then 0)
-        for (int d = 1; d < D; ++d) {
-            __syncthreads();
-            const float *g = factor(d, cellS[(int64_t)q * D + d]);
-            const float inv = 1.f / (float)stride;
-            const bool last = d == D - 1;
+        int cs[DD];
 #pragma unroll
-            for (int k = 0; k < NF; ++k) {
-                if (64 * k >= nfib) break;
-                const int f = lane + 64 * k;
-                if (f < nfib) {
-                    const int hi = (int)(((float)f + 0.5f) * inv);   // f / stride, exact for these sizes
-                    const int base = hi * stride * PN + (f - hi * stride);
-                    float in[PN], out[PN];
+        for (int d = 0; d < DD; ++d) cs[d] = __builtin_amdgcn_readfirstlane(cellS[(int64_t)q * DD + d]);
+        if (e > e0) {
+            int upto = 0;   // one more than the highest dimension >= 1 in which this partner differs from the last
 #pragma unroll
-                    for (int j = 0; j < PN; ++j) in[j] = cur[base + j * stride];
-                    apply(g, in, out);
-                    if (last) {
-#pragma unroll
-                        for (int i = 0; i < PN; ++i) acc[k][i] += out[i];
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < PN; ++i) cur[base + i * stride] = out[i];
-                    }
-                }
-            }
-            stride *= PN;
+            for (int d = 1; d < DD; ++d) upto = cs[d] != prev[d] ? d : upto;
+            flush_below(upto);
         }
-    }
-    // accumulators of the last pass (dimension D-1, stride r/p^2 in the LDS layout) back to the
-    // flat node index i = sum_d i_d p^d
-    float *Va = V + a * r;
-    int stride = 1;
-    for (int d = 2; d < D; ++d) stride *= PN;
-    const float inv = 1.f / (float)stride;
+        const float *__restrict__ g = factor(0, cs[0]);
 #pragma unroll
-    for (int k = 0; k < NF; ++k) {
-        if (64 * k >= nfib) break;
-        const int f = lane + 64 * k;
-        if (f < nfib) {
+        for (int k = 0; k < NFL; ++k)
 #pragma unroll
             for (int i = 0; i < PN; ++i) {
-                int flat;
-                if (D == 1) {
-                    flat = f * PN + i;
-                } else {
-                    const int hi = (int)(((float)f + 0.5f) * inv);
-                    const int idx = hi * stride * PN + (f - hi * stride) + i * stride;   // LDS layout index
-                    const int i0 = idx / nfib;
-                    flat = i0 + PN * (idx - i0 * nfib);
-                }
-                Va[flat] = acc[k][i];
+                float t = acc[0][k][i];
+#pragma unroll
+                for (int j = 0; j < PN; ++j) t = fmaf(g[i * PN + j], wc[k][j], t);
+                acc[0][k][i] = t;
             }
+#pragma unroll
+        for (int d = 0; d < DD; ++d) prev[d] = cs[d];
+    }
+    flush_below(DD);
+    // S_{D-1} is the row of V: node (fibre f of the last dimension, entry j) = j r/p + f
+    float *Va = V + a * R;
+#pragma unroll
+    for (int k = 0; k < NFL; ++k) {
+        const int f = tid + 256 * k;
+        if (f < NFIB) {
+#pragma unroll
+            for (int j = 0; j < PN; ++j) Va[j * NFIB + f] = acc[DD - 1][k][j];
         }
     }
 }
@@ -1767,6 +1849,19 @@ static KronShape kron_shape(const f3m_plan_s &P, int level) {
         S.no = std::max(S.no, (int)(hi - lo) + 1);
     }
     return S;
+}
+
+// Depths whose M2L is the grouped one (more than 32 fibres per box, far rows stored): every far row once more,
+// ordered by the row-major cell index of the partner.
+void build_far_orders(f3m_plan_s &P, hipStream_t st) {
+    for (int l = 1; l <= P.L; ++l) {
+        f3m_level &lv = P.lev[l];
+        if (lv.far_sz == 0 || lv.p == 0 || lv.far_implicit || lv.r / lv.p <= 32) continue;
+        lv.far_ord.alloc((size_t)lv.far_sz, &P.bytes);
+        far_order_kernel<<<grid_for(lv.nb), dim3(1024), 0, st>>>(lv.far_ptr.p, lv.far_col.p, P.slev(l).cell.p, P.D, l, lv.nb,
+                                                                lv.far_ord.p);
+        F3M_HIP(hipGetLastError());
+    }
 }
 
 // per depth with far pairs: the 1-D factor matrices of the node-to-node kernel matrix, built in fp64
@@ -1998,28 +2093,47 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         const int p = lv.p, r = lv.r;
         const KronShape KS = kron_shape(P, l);
         const int nfib = r / p;
-        const bool small = nfib <= 32;   // several far pairs per wavefront
-        const size_t sh = small ? (size_t)((64 / nfib) * r + D * KS.no * p * p) * sizeof(float) : (size_t)r * sizeof(float);
-        auto launch = [&](auto kern) {
-            kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
-                                                        lv.gtab.p, KS, W, V);
-        };
-        switch (small ? -p : p) {
-            case 2: launch(m2l_kron_kernel<2>); break;
-            case 3: launch(m2l_kron_kernel<3>); break;
-            case 4: launch(m2l_kron_kernel<4>); break;
-            case 5: launch(m2l_kron_kernel<5>); break;
-            case 6: launch(m2l_kron_kernel<6>); break;
-            case 7: launch(m2l_kron_kernel<7>); break;
-            case 8: launch(m2l_kron_kernel<8>); break;
-            case -2: launch(m2l_kron_small_kernel<2>); break;
-            case -3: launch(m2l_kron_small_kernel<3>); break;
-            case -4: launch(m2l_kron_small_kernel<4>); break;
-            case -5: launch(m2l_kron_small_kernel<5>); break;
-            case -6: launch(m2l_kron_small_kernel<6>); break;
-            case -7: launch(m2l_kron_small_kernel<7>); break;
-            case -8: launch(m2l_kron_small_kernel<8>); break;
-            default: fail(F3M_ERR_UNSUPPORTED, "interp_nodes must be in [2,8]");
+        if (nfib <= 32) {   // several far pairs per wavefront
+            const size_t sh = (size_t)((64 / nfib) * r + D * KS.no * p * p) * sizeof(float);
+            auto launch = [&](auto kern) {
+                kern<<<grid_for(lv.nb), dim3(64), sh, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_col.p, lv.nb, D, r,
+                                                            lv.gtab.p, KS, W, V);
+            };
+            switch (p) {
+                case 2: launch(m2l_kron_small_kernel<2>); break;
+                case 3: launch(m2l_kron_small_kernel<3>); break;
+                case 4: launch(m2l_kron_small_kernel<4>); break;
+                case 5: launch(m2l_kron_small_kernel<5>); break;
+                case 6: launch(m2l_kron_small_kernel<6>); break;
+                case 7: launch(m2l_kron_small_kernel<7>); break;
+                case 8: launch(m2l_kron_small_kernel<8>); break;
+                default: fail(F3M_ERR_UNSUPPORTED, "interp_nodes must be in [2,8]");
+            }
+        } else {
+            if (!lv.far_ord.p) fail(F3M_ERR_HIP, "internal: the far rows of this depth have not been ordered");
+            auto launch = [&](auto kern) {
+                kern<<<grid_for(lv.nb), dim3(256), 0, st>>>(lv.cell.p, sv.cell.p, lv.far_ptr.p, lv.far_ord.p, lv.nb, lv.gtab.p,
+                                                           KS, W, V);
+            };
+            // every (nodes per dimension, D) with more than 32 fibres and at most 4096 nodes
+            switch (p * 8 + D) {
+                case 2 * 8 + 7: launch(m2l_kron_grouped_kernel<2, 7>); break;
+                case 3 * 8 + 5: launch(m2l_kron_grouped_kernel<3, 5>); break;
+                case 3 * 8 + 6: launch(m2l_kron_grouped_kernel<3, 6>); break;
+                case 3 * 8 + 7: launch(m2l_kron_grouped_kernel<3, 7>); break;
+                case 4 * 8 + 4: launch(m2l_kron_grouped_kernel<4, 4>); break;
+                case 4 * 8 + 5: launch(m2l_kron_grouped_kernel<4, 5>); break;
+                case 4 * 8 + 6: launch(m2l_kron_grouped_kernel<4, 6>); break;
+                case 5 * 8 + 4: launch(m2l_kron_grouped_kernel<5, 4>); break;
+                case 5 * 8 + 5: launch(m2l_kron_grouped_kernel<5, 5>); break;
+                case 6 * 8 + 3: launch(m2l_kron_grouped_kernel<6, 3>); break;
+                case 6 * 8 + 4: launch(m2l_kron_grouped_kernel<6, 4>); break;
+                case 7 * 8 + 3: launch(m2l_kron_grouped_kernel<7, 3>); break;
+                case 7 * 8 + 4: launch(m2l_kron_grouped_kernel<7, 4>); break;
+                case 8 * 8 + 3: launch(m2l_kron_grouped_kernel<8, 3>); break;
+                case 8 * 8 + 4: launch(m2l_kron_grouped_kernel<8, 4>); break;
+                default: fail(F3M_ERR_UNSUPPORTED, "no M2L kernel for this number of nodes and dimensions");
+            }
         }
         F3M_HIP(hipGetLastError());
     };

@@ -14,6 +14,7 @@ struct f3m_level {
     f3m::DevBuf<int32_t> cell;          // [nb*D] integer cell coordinates
     f3m::DevBuf<uint64_t> near_ptr, far_ptr;   // [nb+1]
     f3m::DevBuf<uint32_t> near_col, far_col;
+    f3m::DevBuf<uint32_t> far_ord;      // [far_sz] the far rows in the order of the partners' row-major cell index (grouped M2L)
     int64_t near_sz = 0, far_sz = 0;
     int64_t far_point_pairs = 0;        // sum of |p||q| over the far pairs of this depth
     // small field (Sec. 4.2): pairs summed directly at this depth, and the target tiles of their rows
@@ -186,6 +187,7 @@ void run_direct_rows_f64_static(const float *X, int64_t n, int D, float gamma, c
                                 int64_t m, double *y64, hipStream_t st);
 void upload_transfer(f3m_plan_s &P, hipStream_t st);            // parent-basis-at-child-nodes table
 void upload_kron_tables(f3m_plan_s &P, hipStream_t st);         // per-dimension kernel factors of every far depth
+void build_far_orders(f3m_plan_s &P, hipStream_t st);           // far rows in row-major cell order for the grouped M2L
 // solve.hip: conjugate gradients for (K + lambda I) x = b on a one-set plan (synchronises)
 void run_cg(f3m_plan_s &P, float lambda, const float *b, float *x, int max_iter, float tol, int *iters_host,
             float *history_host, hipStream_t st);

@@ -1063,6 +1063,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         upload_transfer(P, st);
     }
     upload_kron_tables(P, st);
+    build_far_orders(P, st);
     for (int k = 1; k <= P.L; ++k) build_stencil_tables(P, k, st);
     int64_t max_w = 0, max_v = 0, max_part = 0, max_slice = 0;
     for (int k = 1; k <= P.L; ++k) {
