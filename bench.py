@@ -254,6 +254,11 @@ def main():
     nb_L = int(inf.nboxes[L])
     tag = ("xy_n%d" % n) if args.xy else "config%d_n%d" % (k, n)
     traffic, issue, counters_note = load_counters(tag)
+    rates = None
+    rates_path = os.path.join(ROOT, "profiles", "pipe_rates_mi355x.json")
+    if os.path.exists(rates_path):
+        with open(rates_path) as f:
+            rates = json.load(f)
     rooflines = {}
 
     def hbm_stage(name, kernel, nbytes, ms):
@@ -324,6 +329,10 @@ def main():
                             "valu_slot_frac": 3.0 * pairs / t / lane_slots_per_s,
                             "frac_of_unpacked_fp32_peak": ach / UNPACKED_F32_TFLOPS,
                             "issue_counters": issue,
+                            "frac_of_measured_exp2_fma_rate": (pairs / t / rates["exp2_fma_pairs_per_s"]) if rates else None,
+                            "measured_rate_note": "profiles/pipe_rates_mi355x.json: one v_exp_f32 + one v_fma_f32 per lane "
+                                                  "issue at 1.37e13 pairs/s on this device; no near-field kernel that "
+                                                  "evaluates one exponential per pair can pass that",
                             "achieved_note": "flop-equivalent: (3D+2) flop per point pair / launch time; the D-term part of "
                                              "every pair runs on the matrix cores (fp16-split operands, fp32 accumulate), so "
                                              "this is not a count of executed VALU flops",

@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libf3m.so")
+RATES = os.path.join(HERE, "f3m_rates")
 SOURCES = ["api.hip", "plan.hip", "kmvm.hip", "m2l.hip", "solve.hip", "pool.hip", "route.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are not to be generated on the test machines
@@ -47,6 +48,10 @@ def build_lib(verbose=False):
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
+    # the stand-alone rate probe (instruction and copy rates of the device, see csrc/rates.hip)
+    res = subprocess.run([hipcc, *FLAGS, os.path.join(CSRC, "rates.hip"), "-o", RATES], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed for rates.hip:\n" + res.stderr)
     return LIB
 
 
