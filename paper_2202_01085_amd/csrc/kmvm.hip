@@ -1490,11 +1490,9 @@ __global__ __launch_bounds__(64) void l2l34_kernel(const uint32_t *__restrict__ 
 // dimension at a time (D passes of r p multiply-adds instead of r^2 kernel values): the same
 // sums as the dense product, in another order.  The table G[o + omax][i][j] is built in fp64
 // per depth at plan time.
-// One wavefront per target box.  Pass 0 reads W_q from global memory and writes to LDS with
-// dimension 0 slowest (index = rest + i_0 r/p: conflict-free writes); the middle passes work
-// in place in LDS (a fibre is read and written by the same lane); the last pass adds into
-// register accumulators that are stored once per target.  A fibre = the p entries along the
-// pass's dimension; lane = fibre.
+// Boxes with more than 32 fibres (a fibre = the p entries along one dimension) take
+// m2l_kron_grouped_kernel, which also nests the sum over the far partners over the dimensions;
+// boxes with fewer take m2l_kron_small_kernel, several far pairs per wavefront.
 // For two point sets the grids are shifted by u_d box edges in dimension d, so the factor of
 // dimension d depends on o + u_d: the table is kept per dimension, G[d][o - omin_d][i][j] with
 // G = exp(-(l/2)^2 (2 (o + u_d) + s_j - s_i)^2 / (2 gamma^2)), `no` offsets per dimension
@@ -1505,13 +1503,6 @@ struct KronShape {
     int no;                  // tabulated offsets per dimension
 };
 
-// largest number of fibres (r/p) that p nodes per dimension allow with D <= 7 and r <= 4096
-constexpr int kron_max_fibres(int p) {
-    int r = 1;
-    for (int d = 0; d < F3M_MAX_DIM && r * p <= MAX_NODES; ++d) r *= p;
-    return r / p;
-}
-
 // ---- far rows in the order of the row-major cell index ------------------------------------------
 // The grouped M2L below shares work between far partners whose cells differ in the leading dimensions
 // only, so it wants the partners of a target ordered by (c_{D-1}, ..., c_1, c_0), most significant first:
@@ -1519,8 +1510,9 @@ constexpr int kron_max_fibres(int p) {
 // stored ascending in the interleaved key; far_ord holds every row once more in beta order.  A row is
 // sorted in pieces of at most FO_CH entries (bitonic network in LDS); the M2L is correct for any
 // order, a piece boundary only costs it a few shared sums.
-constexpr int FO_CH = 16384;
-__global__ __launch_bounds__(1024) void far_order_kernel(const uint64_t *__restrict__ far_ptr,
+constexpr int FO_CH = 8192;    // 64 KB of keys: two workgroups per compute unit
+constexpr int FO_NT = 512;
+__global__ __launch_bounds__(FO_NT) void far_order_kernel(const uint64_t *__restrict__ far_ptr,
                                                          const uint32_t *__restrict__ far_col,
                                                          const int32_t *__restrict__ cellS, int D, int depth, int64_t nb,
                                                          uint32_t *__restrict__ far_ord) {
@@ -1533,7 +1525,7 @@ __global__ __launch_bounds__(1024) void far_order_kernel(const uint64_t *__restr
         const int len = (int)(e1 - c0 < (uint64_t)FO_CH ? e1 - c0 : (uint64_t)FO_CH);
         int n2 = 2;
         while (n2 < len) n2 <<= 1;
-        for (int i = tid; i < n2; i += 1024) {
+        for (int i = tid; i < n2; i += FO_NT) {
             uint64_t k = ~0ull;
             if (i < len) {
                 const uint32_t q = far_col[c0 + i];
@@ -1546,7 +1538,7 @@ __global__ __launch_bounds__(1024) void far_order_kernel(const uint64_t *__restr
         __syncthreads();
         for (int k = 2; k <= n2; k <<= 1)
             for (int j = k >> 1; j > 0; j >>= 1) {
-                for (int i = tid; i < n2; i += 1024) {
+                for (int i = tid; i < n2; i += FO_NT) {
                     const int ixj = i ^ j;
                     if (ixj > i) {
                         const uint64_t x = key[i], y = key[ixj];
@@ -1558,7 +1550,7 @@ __global__ __launch_bounds__(1024) void far_order_kernel(const uint64_t *__restr
                 }
                 __syncthreads();
             }
-        for (int i = tid; i < len; i += 1024) far_ord[c0 + i] = (uint32_t)key[i];
+        for (int i = tid; i < len; i += FO_NT) far_ord[c0 + i] = (uint32_t)key[i];
         __syncthreads();
     }
 }
@@ -1858,7 +1850,7 @@ void build_far_orders(f3m_plan_s &P, hipStream_t st) {
         f3m_level &lv = P.lev[l];
         if (lv.far_sz == 0 || lv.p == 0 || lv.far_implicit || lv.r / lv.p <= 32) continue;
         lv.far_ord.alloc((size_t)lv.far_sz, &P.bytes);
-        far_order_kernel<<<grid_for(lv.nb), dim3(1024), 0, st>>>(lv.far_ptr.p, lv.far_col.p, P.slev(l).cell.p, P.D, l, lv.nb,
+        far_order_kernel<<<grid_for(lv.nb), dim3(FO_NT), 0, st>>>(lv.far_ptr.p, lv.far_col.p, P.slev(l).cell.p, P.D, l, lv.nb,
                                                                 lv.far_ord.p);
         F3M_HIP(hipGetLastError());
     }

@@ -1,6 +1,6 @@
 // M2L, v2 = K v1 (arXiv 2202.01085, Sec. 3 "Interpolating k(x,y)", Fig. 4 step 2), for D = 3
 // with 4 nodes per dimension (r = 64 nodes per box) and the paper's far rule (ratio 2).
-// Everything else (other D, node counts, far ratios) takes m2l_kron_kernel in kmvm.hip.
+// Everything else (other D, node counts, far ratios) takes the Kronecker-factor kernels in kmvm.hip.
 #include <algorithm>
 #include <cmath>
 

@@ -165,9 +165,7 @@ __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__res
                                                            const uint32_t *__restrict__ vals_in,
                                                            uint32_t *__restrict__ keys_out,
                                                            uint32_t *__restrict__ vals_out, int64_t n, int shift,
-                                                           const uint32_t *__restrict__ offs, int64_t nblk,
-                                                           const float *__restrict__ fa,
-                                                           const float *__restrict__ fb) {
+                                                           const uint32_t *__restrict__ offs, int64_t nblk) {
     constexpr int NW = RS_NT / 64;
     __shared__ uint32_t wcnt[NW][256];      // per wave: keys of each digit seen so far
     __shared__ uint32_t dstart[256];        // first tile-local position of each digit
@@ -186,8 +184,8 @@ __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__res
         const int64_t i = base + r * 64 + lane;
         const bool valid = i < n;
         key[r] = valid ? keys_in[i] : 0u;
-        // value: the bits of fa[i] + fb[i], or vals_in[i], or the position itself
-        val[r] = !valid ? 0u : fa ? __float_as_uint(fa[i] + fb[i]) : vals_in ? vals_in[i] : (uint32_t)i;
+        // value: vals_in[i], or the position itself
+        val[r] = !valid ? 0u : vals_in ? vals_in[i] : (uint32_t)i;
     }
 #pragma unroll
     for (int r = 0; r < RS_IPT; ++r) {
@@ -262,8 +260,7 @@ static bool radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uin
         rs_hist_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, n, shift, hist.p, nblk);
         F3M_HIP(hipGetLastError());
         exclusive_scan(U32In{hist.p}, nblk * 256, U32Out{hist.p}, nullptr, st);
-        rs_scatter_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk,
-                                                                        nullptr, nullptr);
+        rs_scatter_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk);
         F3M_HIP(hipGetLastError());
         in_b = !in_b;
         first = false;

@@ -326,7 +326,8 @@ __global__ __launch_bounds__(RT_NT) void route_place_kernel(const float *__restr
 }
 
 // pass 3 backwards: a window of the caller's array (NC values per row, row-major) -> order p2, one array per
-// component
+// component.  A thread reads its rows once, whole (the window of a point set is not read again per coordinate),
+// and passes them through the LDS copy one coordinate at a time.
 template <int NC>
 __global__ __launch_bounds__(RT_NT) void route_pick_kernel(const float *__restrict__ in, float *__restrict__ out,
                                                            int64_t out_stride, const uint16_t *__restrict__ off,
@@ -336,25 +337,33 @@ __global__ __launch_bounds__(RT_NT) void route_pick_kernel(const float *__restri
     const int64_t win0 = (int64_t)blockIdx.x * RT_TILE;
     const int64_t left = n - win0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
-    uint16_t o[RT_IPT];
+    struct Row { float v[NC]; };
+    Row row[RT_IPT];
+    const Row *rows = reinterpret_cast<const Row *>(in);
 #pragma unroll
     for (int r = 0; r < RT_IPT; ++r) {
         const int e = r * RT_NT + tid;
-        o[r] = e < cnt ? off[win0 + e] : (uint16_t)0;
+        row[r] = rows[win0 + (e < cnt ? e : 0)];
     }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
 #pragma unroll
-        for (int r = 0; r < RT_IPT; ++r) {
-            const int e = r * RT_NT + tid;
-            if (e < cnt) stage[e] = in[(win0 + e) * NC + c];
-        }
+        for (int r = 0; r < RT_IPT; ++r) stage[r * RT_NT + tid] = row[r].v[c];
         __syncthreads();
         float *dst = out + (int64_t)c * out_stride;
 #pragma unroll
-        for (int r = 0; r < RT_IPT; ++r) {
-            const int e = r * RT_NT + tid;
-            if (e < cnt) dst[win0 + e] = stage[o[r]];
+        for (int h = 0; h < RT_IPT; h += 8) {
+            uint32_t o[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int e = (h + r) * RT_NT + tid;
+                o[r] = e < cnt ? off[win0 + e] : 0u;
+            }
+#pragma unroll
+            for (int r = 0; r < 8; ++r) {
+                const int e = (h + r) * RT_NT + tid;
+                if (e < cnt) dst[win0 + e] = stage[o[r]];
+            }
         }
         __syncthreads();
     }
