@@ -1227,6 +1227,107 @@ __global__ __launch_bounds__(64) void p2m34_kernel(const float *__restrict__ Xs,
     }
 }
 
+// P2M where every box is one chunk (no box above P2M_CHUNK points): a box per HALF wavefront.  The kernel is
+// bound by its instruction stream, and a third of that stream is the sum of the 64 accumulators over the lanes;
+// with 32 lanes per box that sum covers two boxes at once (per pass of 32 accumulators a lane adds 32 rows
+// instead of 32 rows of one box out of 64), and a box of some 60 points takes two rounds of 32 lanes instead of
+// one round of 64, which costs the same.  Lane = point; the two halves of a wavefront work on boxes a and a + 1,
+// four such pairs per wavefront with the first loads of all of them in flight together.
+constexpr int P2M_NPAIR = 4;
+__global__ __launch_bounds__(64) void p2m34_pair_kernel(const float *__restrict__ Xs, const float *__restrict__ bs,
+                                                        const uint32_t *__restrict__ start,
+                                                        const int32_t *__restrict__ cell, int64_t nb, CentreArg C,
+                                                        float *__restrict__ W) {
+    // rows of the upper half are shifted by 32 floats so that the two halves read different banks
+    __shared__ __attribute__((aligned(16))) float tr[64 * TR_STRIDE + 32];
+    const int64_t b0 = block_index() * (2 * P2M_NPAIR);
+    if (b0 >= nb) return;
+    const int lane = threadIdx.x, half = lane >> 5, t = lane & 31;
+    uint32_t k0[P2M_NPAIR], k1[P2M_NPAIR];
+    int64_t a[P2M_NPAIR];
+    bool on[P2M_NPAIR];
+    double ctr[P2M_NPAIR][3];
+#pragma unroll
+    for (int j = 0; j < P2M_NPAIR; ++j) {
+        a[j] = b0 + 2 * j + half;
+        on[j] = a[j] < nb;
+        const int64_t ac = on[j] ? a[j] : nb - 1;
+        k0[j] = start[ac];
+        k1[j] = on[j] ? start[ac + 1] : k0[j];   // a box beyond the end has no points
+#pragma unroll
+        for (int d = 0; d < 3; ++d) ctr[j][d] = C.alpha[d] + ((double)cell[ac * 3 + d] + 0.5) * C.edge;
+    }
+    // Loads are unconditional, the index of a lane beyond the box clamped to the box's first point and its
+    // weight set to zero (a branch around them would make every load wait on its own).
+    auto load = [&](int j, uint32_t kb, float (&x)[3], float &bv) __attribute__((always_inline)) {
+        const uint32_t k = kb + (uint32_t)t;
+        const bool live = k < k1[j];
+        const uint32_t kc = live ? k : k0[j];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) x[d] = Xs[(int64_t)kc * 3 + d];
+        const float bl = bs[kc];
+        bv = live ? bl : 0.f;
+    };
+    float x[P2M_NPAIR][3], bv[P2M_NPAIR];
+#pragma unroll
+    for (int j = 0; j < P2M_NPAIR; ++j) load(j, k0[j], x[j], bv[j]);
+    const int rowbase = lane * TR_STRIDE + half * 32;
+#pragma unroll
+    for (int j = 0; j < P2M_NPAIR; ++j) {
+        if (b0 + 2 * j >= nb) break;   // wave-uniform: neither box of the pair exists
+        float acc[64];
+#pragma unroll
+        for (int q = 0; q < 64; ++q) acc[q] = 0.f;
+        float xc[3] = {x[j][0], x[j][1], x[j][2]}, bc = bv[j];
+        for (uint32_t kb = k0[j];;) {
+            // the next round (a box above 32 points) is loaded while this one is added; the wavefront goes on
+            // while either half has points left
+            const bool more = __ballot(kb + 32 < k1[j]) != 0ull;
+            float xn[3] = {0.f, 0.f, 0.f}, bn = 0.f;
+            if (more) load(j, kb + 32, xn, bn);
+            float Lx[4], Ly[4], Lz[4];
+            weights34(xc, ctr[j], C.inv_half, Lx, Ly, Lz);
+#pragma unroll
+            for (int i3 = 0; i3 < 4; ++i3) {
+                const float zb = Lz[i3] * bc;
+#pragma unroll
+                for (int i2 = 0; i2 < 4; ++i2) {
+                    const float yz = Ly[i2] * zb;
+#pragma unroll
+                    for (int i1 = 0; i1 < 4; ++i1) acc[i1 + 4 * i2 + 16 * i3] = fmaf(Lx[i1], yz, acc[i1 + 4 * i2 + 16 * i3]);
+                }
+            }
+            if (!more) break;
+            kb += 32;
+#pragma unroll
+            for (int d = 0; d < 3; ++d) xc[d] = xn[d];
+            bc = bn;
+        }
+        // sum over the 32 lanes of each half, 32 nodes at a time: lane l writes its row; lane t of a half adds
+        // the 32 rows of its half in column t
+        float *dst = W + a[j] * 64;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            __syncthreads();   // the sums of the previous pass (or pair) have been read
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+                *reinterpret_cast<float4 *>(&tr[rowbase + 4 * g]) =
+                    make_float4(acc[32 * q + 4 * g], acc[32 * q + 4 * g + 1], acc[32 * q + 4 * g + 2], acc[32 * q + 4 * g + 3]);
+            __syncthreads();
+            const float *col = tr + (32 * half) * TR_STRIDE + half * 32 + t;
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+            for (int row = 0; row < 32; row += 4) {
+                s0 += col[(row + 0) * TR_STRIDE];
+                s1 += col[(row + 1) * TR_STRIDE];
+                s2 += col[(row + 2) * TR_STRIDE];
+                s3 += col[(row + 3) * TR_STRIDE];
+            }
+            if (on[j]) dst[32 * q + t] = (s0 + s1) + (s2 + s3);
+        }
+    }
+}
+
 constexpr int L2P_NCH = 4;   // chunks per wavefront: their loads are in flight together (a chunk alone is a chain
                              // of dependent loads and the kernel is bound by that latency)
 __global__ __launch_bounds__(64) void l2p34_kernel(const float *__restrict__ Xs, const uint32_t *__restrict__ start,
@@ -2061,7 +2162,10 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         const NodeArg N = make_nodes(p);
         const CentreArg CS = make_centre(P, l, true);   // source grid
         size_t sh = (size_t)(FF_TP * D * p + FF_TP) * sizeof(float);
-        if (D == 3 && p == 4)
+        if (D == 3 && p == 4 && single_chunks(sv))
+            p2m34_pair_kernel<<<grid_for(cdiv(sv.nb, 2 * P2M_NPAIR)), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p, sv.nb,
+                                                                                        CS, P.W.p);
+        else if (D == 3 && p == 4)
             p2m34_kernel<<<grid_for(cdiv(sv.nchunks, P2M_NCH)), dim3(64), 0, st>>>(Ys, bs, sv.start.p, sv.cell.p,
                                                                   sv.chunk_box.p, sv.chunk_first.p, sv.nchunks, CS,
                                                                   P.W.p, P.Wpart.p, single_chunks(sv));
@@ -2173,9 +2277,13 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
             {
                 hipEvent_t *ev = level_events(L);
                 F3M_HIP(hipEventRecord(ev[0], st));
-                p2m34_kernel<<<grid_for(cdiv(lf.nchunks, P2M_NCH)), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
-                                                                      lf.chunk_first.p, lf.nchunks, make_centre(P, L),
-                                                                      lf.Wl.p, P.Wpart.p, single_chunks(lf));
+                if (single_chunks(lf))
+                    p2m34_pair_kernel<<<grid_for(cdiv(lf.nb, 2 * P2M_NPAIR)), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p,
+                                                                                                lf.nb, make_centre(P, L), lf.Wl.p);
+                else
+                    p2m34_kernel<<<grid_for(cdiv(lf.nchunks, P2M_NCH)), dim3(64), 0, st>>>(P.Xs.p, bs, lf.start.p, lf.cell.p, lf.chunk_box.p,
+                                                                          lf.chunk_first.p, lf.nchunks, make_centre(P, L),
+                                                                          lf.Wl.p, P.Wpart.p, single_chunks(lf));
                 F3M_HIP(hipGetLastError());
                 if (lf.max_box > P2M_CHUNK)   // some box has several chunks
                     reduce_partials(P, lf, r, lf.Wl.p, st);
