@@ -445,7 +445,8 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
                                                         const uint32_t *__restrict__ tile_first, int64_t ntiles,
                                                         float g, float inv_l, CentreArg C, float *__restrict__ ys,
                                                         int accumulate, int nsplit, int64_t ntargets,
-                                                        float *__restrict__ part, MultiArg MA) {
+                                                        float *__restrict__ part, MultiArg MA,
+                                                        const uint8_t *__restrict__ paired) {
     constexpr int D = 3, NC = 4;
     static_assert(MB >= 1 && MB <= 4 && !(SPLIT && MB > 1), "unsupported variant");
     __shared__ __attribute__((aligned(16))) float bbuf[4][MB * 64];
@@ -461,7 +462,9 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
         if (t >= ntiles) return;
     }
     const uint32_t a = __builtin_amdgcn_readfirstlane(tile_box[t]);
-    const uint32_t k0 = startT[a] + (uint32_t)(t - tile_first[a]) * 64u;
+    // paired (or null): boxes whose first run of targets is worked by p2p_gram3_pair_kernel; the tile list
+    // then starts at their second run
+    const uint32_t k0 = startT[a] + ((uint32_t)(t - tile_first[a]) + (paired && paired[a] ? 1u : 0u)) * 64u;
     const uint32_t kend = startT[a + 1];
     const int ntg = __builtin_amdgcn_readfirstlane((int)(kend - k0));   // targets of the tile (wave-uniform)
     const int nn = lane & 31, kk = lane >> 5;
@@ -687,6 +690,230 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
     } else {
         if (kt < kend) ys[kt] = accumulate ? ys[kt] + res : res;
     }
+}
+
+// The 3-D Gram near field for PAIRS of target tiles.  Two leaf boxes a and a + 1 with the same parent and
+// cells next to each other share most of their near boxes (18 of 27 with far ratio 2), and the cost of a step
+// of p2p_gram3_kernel that is not exponentials and multiply-adds (finding and loading 64 sources, preparing
+// their operands) does not depend on the number of target columns.  One wavefront takes the first run of
+// targets of both boxes: coordinates are relative to the midpoint of the two box centres, and the source
+// sequence is cut in three segments,
+//   [ boxes near both | boxes near a only | boxes near a + 1 only ],
+// each walked like the sequence of p2p_gram3_kernel; the first segment is worked against four column blocks.
+// The segments come from the two near rows (at most 32 entries each: lanes 0-31 hold the row of a, lanes 32-63
+// that of a + 1): an entry of a's row is also near a + 1 iff its squared cell offset from a + 1 is below the
+// far threshold T (the integer rule that built the rows), and the copies in the row of a + 1 are dropped.
+// Within a segment boxes keep their list order.
+__global__ __launch_bounds__(256) void p2p_gram3_pair_kernel(const float *__restrict__ Xs,
+                                                             const uint32_t *__restrict__ start,
+                                                             const float *__restrict__ bs,
+                                                             const int32_t *__restrict__ cell,
+                                                             const uint64_t *__restrict__ near_ptr,
+                                                             const uint32_t *__restrict__ near_col,
+                                                             const uint32_t *__restrict__ pair_box, int64_t npairs,
+                                                             int T, float g, float inv_l, CentreArg C,
+                                                             float *__restrict__ ys) {
+    constexpr int D = 3, NC = 4;
+    __shared__ __attribute__((aligned(16))) float bbuf[4][64];
+    __shared__ uint32_t tab_first[4][64], tab_len[4][64];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int64_t t = block_index() * 4 + wv;
+    if (t >= npairs) return;
+    const uint32_t a = __builtin_amdgcn_readfirstlane(pair_box[t]);   // the pair is (a, a + 1)
+    const int nn = lane & 31, kk = lane >> 5;
+    int32_t ca[D], eo[D];   // cell of a, and the cell of a + 1 relative to it
+    float ctr[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        ca[d] = cell[(int64_t)a * D + d];
+        eo[d] = cell[(int64_t)(a + 1) * D + d] - ca[d];
+        ctr[d] = (float)(C.alpha[d] + ((double)ca[d] + 0.5 + 0.5 * (double)eo[d]) * C.edge);
+    }
+    const uint32_t kA = start[a], kB = start[a + 1], kBe = start[a + 2];
+    const int ntA = __builtin_amdgcn_readfirstlane((int)min(kB - kA, 64u));    // targets of the two tiles
+    const int ntB = __builtin_amdgcn_readfirstlane((int)min(kBe - kB, 64u));
+
+    // B operands: column blocks 0, 1 are the targets of a, blocks 2, 3 those of a + 1
+    h8v Bop[4];
+    float ni[4];
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+        const int idx = (cb & 1) * 32 + nn;
+        const uint32_t kt = (cb < 2 ? kA : kB) + (uint32_t)idx;
+        const float valid = idx < (cb < 2 ? ntA : ntB) ? 1.f : 0.f;   // loads are in bounds (padding), masked by a factor
+        float u[NC];
+        float s = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            u[d] = (Xs[(int64_t)kt * D + d] - ctr[d]) * inv_l * valid;
+            s = fmaf(u[d], u[d], s);
+        }
+        u[D] = 1.f;
+        ni[cb] = -g * s;
+        Bop[cb] = split_target4(u, kk);
+    }
+
+    // the table of the source boxes: lane = position in [both | a only | a + 1 only]
+    int nboth, nonly_a, m;
+    uint32_t sfirst, slen;
+    {
+        const bool of_a = lane < 32;
+        const uint64_t e0 = near_ptr[a], e1 = near_ptr[a + 1], e2 = near_ptr[a + 2];
+        const int len = (int)(of_a ? e1 - e0 : e2 - e1);
+        const bool have = (lane & 31) < len;
+        const uint32_t q = have ? near_col[(of_a ? e0 : e1) + (uint64_t)(lane & 31)] : a;
+        int d2 = 0;   // squared cell offset of q from the OTHER box of the pair
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int o = cell[(int64_t)q * D + d] - ca[d] - (of_a ? eo[d] : 0);
+            d2 += o * o;
+        }
+        const bool other = d2 < T;
+        const bool is_both = have && of_a && other, is_a = have && of_a && !other, is_b = have && !of_a && !other;
+        const uint64_t mboth = __ballot(is_both), ma = __ballot(is_a), mb = __ballot(is_b);
+        const uint64_t below = (1ull << lane) - 1ull;
+        nboth = __popcll(mboth);
+        nonly_a = __popcll(ma);
+        m = nboth + nonly_a + __popcll(mb);
+        const int slot = is_both ? __popcll(mboth & below)
+                       : is_a    ? nboth + __popcll(ma & below)
+                                 : nboth + nonly_a + __popcll(mb & below);
+        const uint32_t f = start[q], l = start[q + 1] - f;
+        tab_first[wv][lane] = 0u;
+        tab_len[wv][lane] = 0u;
+        __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
+        if (is_both || is_a || is_b) {
+            tab_first[wv][slot] = f;
+            tab_len[wv][slot] = l;
+        }
+        __builtin_amdgcn_wave_barrier();
+        sfirst = tab_first[wv][lane];
+        slen = tab_len[wv][lane];
+    }
+    const uint32_t cend = wave_incl_scan_u32(slen);   // inclusive running sum of the lengths over the lanes
+    const uint32_t cbeg = cend - slen;
+    const uint32_t delta = sfirst - cbeg;   // position -> source index inside this lane's box (mod 2^32)
+    const uint32_t S1 = nboth > 0 ? (uint32_t)__builtin_amdgcn_readlane(cend, nboth - 1) : 0u;
+    const uint32_t S2 = nboth + nonly_a > 0 ? (uint32_t)__builtin_amdgcn_readlane(cend, nboth + nonly_a - 1) : 0u;
+    const uint32_t S3 = __builtin_amdgcn_readlane(cend, 63);
+
+    float accA0 = 0.f, accA1 = 0.f, accB0 = 0.f, accB1 = 0.f;
+    const float g2l = 2.f * g * inv_l;
+    const float nrm = -0.25f / g;
+    float *bw = bbuf[wv];
+    int r = 0;   // first box of the table that reaches into the current window (wave-uniform, only grows)
+
+    // operands of the two blocks of 32 sources of a step, as in p2p_gram3_kernel
+    auto prepare = [&](const float (&x)[D], h8v &opA, h8v &opB) __attribute__((always_inline)) {
+        float w[NC];
+        float s = 0.f;
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            w[d] = (x[d] - ctr[d]) * g2l;                    // 2 g w_d
+            s = fmaf(w[d], w[d], s);
+        }
+        w[D] = s * nrm;                                      // -g |w|^2
+        const uint32_t hi01 = pack_f16(w[0], w[1]), hi23 = pack_f16(w[2], w[3]);
+        const f2v b01 = unpack_f16(hi01), b23 = unpack_f16(hi23);
+        const uint32_t lo01 = pack_f16(w[0] - b01.x, w[1] - b01.y), lo23 = pack_f16(w[2] - b23.x, w[3] - b23.y);
+        const auto s01 = __builtin_amdgcn_permlane32_swap(hi01, lo01, false, false);
+        const auto s23 = __builtin_amdgcn_permlane32_swap(hi23, lo23, false, false);
+        u4v ra, rb;
+        ra.x = s01[0]; ra.y = s23[0]; ra.z = s01[0]; ra.w = s23[0];
+        rb.x = s01[1]; rb.y = s23[1]; rb.z = s01[1]; rb.w = s23[1];
+        opA = __builtin_bit_cast(h8v, ra);
+        opB = __builtin_bit_cast(h8v, rb);
+    };
+    // one block of 32 sources against the column blocks of one tile
+    auto columns = [&](const h8v &op, const float *bf, const h8v &B0, const h8v &B1, int nt, float &acc0,
+                       float &acc1) __attribute__((always_inline)) {
+        f16v c0 = {0.f};
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, B0, c0, 0, 0, 0);
+        int nt2 = nt;
+        asm volatile("" : "+s"(nt2));   // the test on a scalar register at each use, not on a kept lane mask
+        if (nt2 > 32) {
+            f16v c1 = {0.f};
+            c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(op, B1, c1, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
+#pragma unroll
+            for (int v = 15; v >= 0; --v) acc1 = fmaf(__builtin_amdgcn_exp2f(c1[v]), bf[v], acc1);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0 = fmaf(__builtin_amdgcn_exp2f(c0[v]), bf[v], acc0);
+        }
+    };
+    // the positions [wbeg, S) of the sequence against the tiles in `which` (1: a, 2: a + 1, 3: both)
+    auto segment = [&](uint32_t wbeg, uint32_t S, auto which) __attribute__((always_inline)) {
+        constexpr int W = decltype(which)::value;
+        if (wbeg >= S) return;
+        // source index of position w0 + lane, as in p2p_gram3_kernel; positions from S on take the last source
+        // of the segment (w0 < S <= cend of lane 63 ends the search)
+        auto locate = [&](uint32_t w0) __attribute__((always_inline)) {
+            const uint32_t p = min(w0 + (uint32_t)lane, S - 1u);
+            while ((uint32_t)__builtin_amdgcn_readlane(cend, r) <= w0) ++r;
+            uint32_t src = p + (uint32_t)__builtin_amdgcn_readlane(delta, r);
+            for (int rr = r + 1; rr < m; ++rr) {
+                const uint32_t c0 = __builtin_amdgcn_readlane(cbeg, rr);
+                if (c0 >= w0 + 64) break;
+                const uint32_t dl = __builtin_amdgcn_readlane(delta, rr);
+                src = p >= c0 ? p + dl : src;
+            }
+            return src;
+        };
+        float xn[D], bn;
+        {
+            const uint32_t src = locate(wbeg);
+#pragma unroll
+            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
+            bn = bs[src];
+        }
+        for (uint32_t w0 = wbeg; w0 < S; w0 += 64) {
+            float xc[D];
+#pragma unroll
+            for (int d = 0; d < D; ++d) xc[d] = xn[d];
+            float bc = bn;
+            // the loads of the next step are in flight during this one (the last step loads its own sources again)
+            const uint32_t src = locate(w0 + 64 < S ? w0 + 64 : w0);
+#pragma unroll
+            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
+            bn = bs[src];
+            if (w0 + 64 > S) {   // last step only: the positions behind the segment get weight zero
+                asm volatile("");
+                bc = w0 + lane < S ? bc : 0.f;
+            }
+            __builtin_amdgcn_wave_barrier();
+            bw[lane] = bc;
+            __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
+            h8v opA, opB;
+            prepare(xc, opA, opB);
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                if (half == 1 && w0 + 32 >= S) break;
+                float4 bq[4];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    bq[q4] = *reinterpret_cast<const float4 *>(bw + 32 * half + 8 * q4 + 4 * kk);
+                const float *bf = reinterpret_cast<const float *>(bq);
+                const h8v &op = half ? opB : opA;
+                if constexpr ((W & 1) != 0) columns(op, bf, Bop[0], Bop[1], ntA, accA0, accA1);
+                if constexpr ((W & 2) != 0) columns(op, bf, Bop[2], Bop[3], ntB, accB0, accB1);
+            }
+        }
+    };
+    segment(0u, S1, std::integral_constant<int, 3>{});
+    segment(S1, S2, std::integral_constant<int, 1>{});
+    segment(S2, S3, std::integral_constant<int, 2>{});
+
+    accA0 += __shfl_xor(accA0, 32, 64);
+    accA1 += __shfl_xor(accA1, 32, 64);
+    accB0 += __shfl_xor(accB0, 32, 64);
+    accB1 += __shfl_xor(accB1, 32, 64);
+    const int idx = kk * 32 + nn;
+    const float resA = kk ? __builtin_amdgcn_exp2f(ni[1]) * accA1 : __builtin_amdgcn_exp2f(ni[0]) * accA0;
+    const float resB = kk ? __builtin_amdgcn_exp2f(ni[3]) * accB1 : __builtin_amdgcn_exp2f(ni[2]) * accB0;
+    if (idx < ntA) ys[kA + (uint32_t)idx] = resA;
+    if (idx < ntB) ys[kB + (uint32_t)idx] = resB;
 }
 
 // sums of the slices of a split near-field launch, in ascending slice order
@@ -2037,6 +2264,14 @@ static bool gram_near_field(const f3m_plan_s &P, int l) {
 
 // Slices that a target tile of the 3-D Gram near field over the near list of depth l is cut into (1: none):
 // with few target tiles and long rows several wavefronts share a tile, each on a slice of the sources.
+// Tiles of the last depth may be worked in pairs by p2p_gram3_pair_kernel: one point set in 3-D on the Gram
+// path.  Coordinates relative to the midpoint of a pair are up to 1.6 times those relative to a box centre in
+// the products of the expanded square, so the limit on g D is that of the Gram path divided by 1.6.
+bool p2p_pairs_allowed(const f3m_plan_s &P) {
+    return P.D == 3 && !P.src && gram_near_field(P, P.L) && gram_exponent_scale(P, P.L) * 3.0 <= 3.75 &&
+           p2p_nsplit(P, P.L, P.ntiles) == 1;
+}
+
 int p2p_nsplit(const f3m_plan_s &P, int l, int64_t ntiles) {
     const f3m_level &lv = P.lev[l];
     if (!(P.D == 3 && gram_near_field(P, l) && ntiles > 0 && ntiles < 8192 && lv.nb > 0 && P.slev(l).nb > 0)) return 1;
@@ -2087,7 +2322,8 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     F3M_HIP(hipEventRecord(P.ev_p2p0, sn));
     // exact sums over a CSR list of box pairs of one depth (target tiles given), into yn
     auto direct_pairs = [&](int l, const uint64_t *row_ptr, const uint32_t *cols, const uint32_t *tile_box,
-                            const uint32_t *tile_first, int64_t ntiles, int accumulate) {
+                            const uint32_t *tile_first, int64_t ntiles, int accumulate,
+                            const uint8_t *paired = nullptr) {
         f3m_level &lv = P.lev[l];
         const uint32_t *sstart = P.slev(l).start.p;
         const CentreArg CL = make_centre(P, l);
@@ -2101,12 +2337,14 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
                 fail(F3M_ERR_HIP, "internal: the plan holds no room for the split near field");
             p2p_gram3_kernel<true, 1><<<grid_for(cdiv(ntiles * nsplit, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
-                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, nsplit, n, P.p2p_part.p, MultiArg{});
+                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, nsplit, n, P.p2p_part.p, MultiArg{}, nullptr);
             p2p_split_sum_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.p2p_part.p, nsplit, n, P.yn.p, accumulate);
-        } else if (gram && D == 3)
-            p2p_gram3_kernel<false, 1><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
-                P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
-                (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, 1, n, nullptr, MultiArg{});
+        } else if (gram && D == 3) {
+            if (ntiles > 0)
+                p2p_gram3_kernel<false, 1><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
+                    P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles,
+                    (float)gl, (float)(1.0 / CL.edge), CL, P.yn.p, accumulate, 1, n, nullptr, MultiArg{}, paired);
+        }
         else if (gram)
             p2p_mfma_kernel<D><<<grid_for(cdiv(ntiles, 4)), dim3(256), 0, sn>>>(
                 P.Xs.p, lv.start.p, Ys, bs, sstart, lv.cell.p, row_ptr, cols, tile_box, tile_first, ntiles, (float)gl,
@@ -2122,7 +2360,18 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
         // every pair was interpolated (smooth field, Sec. 4.3) or summed at its own depth (small field)
         zero_kernel<<<dim3(gn), dim3(256), 0, sn>>>(P.yn.p, n);
     } else {
-        direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, 0);
+        if (P.npairs > 0) {
+            // the first runs of paired boxes two at a time, every other big tile on its own
+            const CentreArg CL = make_centre(P, P.L);
+            p2p_gram3_pair_kernel<<<grid_for(cdiv(P.npairs, 4)), dim3(256), 0, sn>>>(
+                P.Xs.p, leaf.start.p, bs, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p, P.pair_box.p, P.npairs, P.T,
+                (float)gram_exponent_scale(P, P.L), (float)(1.0 / CL.edge), CL, P.yn.p);
+            F3M_HIP(hipGetLastError());
+            direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.rtile_box.p, P.rtile_first.p, P.nrtiles, 0,
+                         P.paired.p);
+        } else {
+            direct_pairs(P.L, leaf.near_ptr.p, leaf.near_col.p, P.tile_box.p, P.tile_first.p, P.ntiles, 0);
+        }
         // last runs with few targets: sources on the lanes
         if (P.notiles > 0)
             p2p_small_kernel<D, overflow_targets(D)><<<grid_for(cdiv(P.notiles, 4)), dim3(256), 0, sn>>>(
@@ -2402,7 +2651,8 @@ void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_
         auto launch = [&](auto kern) {
             kern<<<grid_for(cdiv(P.ntiles, 4)), dim3(256), 0, st>>>(
                 P.Xs.p, leaf.start.p, P.Ys(), nullptr, P.slev(P.L).start.p, leaf.cell.p, leaf.near_ptr.p, leaf.near_col.p,
-                P.tile_box.p, P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, nullptr, 0, 1, n, nullptr, MA);
+                P.tile_box.p, P.tile_first.p, P.ntiles, (float)gl, (float)(1.0 / CL.edge), CL, nullptr, 0, 1, n, nullptr, MA,
+                nullptr);
         };
         if (mb == 2) launch(p2p_gram3_kernel<false, 2>);
         else if (mb == 3) launch(p2p_gram3_kernel<false, 3>);

@@ -109,6 +109,15 @@ struct f3m_plan_s {
     // kernel with the sources on the lanes is cheaper; at most one per box
     int64_t notiles = 0;
     f3m::DevBuf<uint32_t> otile_box, otile_first;
+    // ... and pairs of tiles (D = 3, Gram near field, one point set): the first runs of two leaf boxes a, a + 1 with
+    // the same parent and cells next to each other are worked by one wavefront, which shares the preparation of
+    // the sources near both.  pair_box[i] = a; paired[b] != 0 for both boxes of a pair; rtile_* is the tile list
+    // without the first runs of paired boxes (tile_* keeps every run: the products with several right-hand sides
+    // and the split near field use it).
+    int64_t npairs = 0, nrtiles = 0;
+    f3m::DevBuf<uint32_t> pair_box, pair_first;
+    f3m::DevBuf<uint8_t> paired;
+    f3m::DevBuf<uint32_t> rtile_box, rtile_first;
     f3m_level lev[F3M_MAX_LEVELS + 1];          // boxes of X (targets); lists by target box
     std::unique_ptr<f3m_source> src;            // two-set plan: the partition of Y (sources)
     // the source side of either kind of plan
@@ -176,6 +185,7 @@ void materialize_far(const f3m_plan_s &P, int level, uint32_t *cols_dev, hipStre
 void run_kmvm(f3m_plan_s &P, const float *b, float *y, hipStream_t st, bool box_order = false);
 void run_kmvm_multi(f3m_plan_s &P, const float *B, int64_t ldb, float *Y, int64_t ldy, int m, hipStream_t st);
 int p2p_nsplit(const f3m_plan_s &P, int l, int64_t ntiles);   // source slices per target tile of the near field (1: none)
+bool p2p_pairs_allowed(const f3m_plan_s &P);                  // the near field of the last depth may work tiles in pairs
 void run_zero(float *y, int64_t n, hipStream_t st);   // y = 0 with a fill kernel
 // exact sums of targets X (nx rows) against sources Y (ny rows, weights b); X == Y for one set
 void run_direct(const float *X, int64_t nx, const float *Y, int64_t ny, int D, float gamma, const float *b, float *y,

@@ -693,6 +693,55 @@ struct OverflowTileCountIn {
     }
 };
 
+// Pairs of leaf boxes for the paired near field: one thread per parent walks its children in rank order and
+// pairs child i with child i + 1 when their cells differ in one dimension only (by one cell, being siblings),
+// both first runs of targets are big tiles (64 targets, or more than ts) and both near rows have at most 32
+// entries.  paired[a] = 1 for the first box of a pair, 2 for the second, 0 otherwise.
+__global__ __launch_bounds__(256) void pair_flag_kernel(int64_t nparents, const uint32_t *__restrict__ cstart,
+                                                        const int32_t *__restrict__ cell,
+                                                        const uint32_t *__restrict__ start,
+                                                        const uint64_t *__restrict__ near_ptr, uint32_t ts,
+                                                        uint8_t *__restrict__ paired) {
+    const int64_t P = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (P >= nparents) return;
+    const uint32_t c0 = cstart[P], c1 = cstart[P + 1];
+    auto fits = [&](uint32_t a) {
+        const uint32_t cnt = start[a + 1] - start[a];
+        return (cnt >= 64u || cnt > ts) && near_ptr[a + 1] - near_ptr[a] <= 32u;
+    };
+    uint32_t a = c0;
+    while (a < c1) {
+        bool pair = false;
+        if (a + 1 < c1 && fits(a) && fits(a + 1)) {
+            int differ = 0;
+            for (int d = 0; d < 3; ++d) differ += cell[(int64_t)a * 3 + d] != cell[(int64_t)(a + 1) * 3 + d];
+            pair = differ == 1;
+        }
+        if (pair) {
+            paired[a] = 1;
+            paired[a + 1] = 2;
+            a += 2;
+        } else {
+            paired[a] = 0;
+            a += 1;
+        }
+    }
+}
+struct PairCountIn {
+    const uint8_t *paired;
+    __device__ uint64_t operator()(int64_t a) const { return paired[a] == 1 ? 1u : 0u; }
+};
+// the big tiles of a box without the first run of a paired box
+struct RestTileCountIn {
+    const uint32_t *start;
+    uint32_t ts;
+    const uint8_t *paired;
+    __device__ uint64_t operator()(int64_t a) const {
+        const uint32_t cnt = start[a + 1] - start[a];
+        return cnt / 64u + ((cnt & 63u) > ts ? 1u : 0u) - (paired[a] ? 1u : 0u);
+    }
+};
+
 // flag[c] = 1 for every column c of a list (equal values from several threads: plain vector stores)
 __global__ __launch_bounds__(256) void mark_cols_kernel(const uint32_t *__restrict__ cols, int64_t count,
                                                         uint32_t *__restrict__ flag) {
@@ -1112,6 +1161,17 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
         const uint32_t ts = lf.nb < 8192 ? 0u : (uint32_t)overflow_targets(D);
         build_items(BigTileCountIn{lf.start.p, ts}, lf.nb, P.tile_first, P.tile_box, P.ntiles, tally, st);
         build_items(OverflowTileCountIn{lf.start.p, ts}, lf.nb, P.otile_first, P.otile_box, P.notiles, tally, st);
+        // tiles worked in pairs (the rows must come from the plain far rule: the kernel tells the shared near
+        // boxes of a pair by it)
+        if (P.L >= 1 && ts > 0 && lf.near_sz > 0 && !lf.smooth && P.rho == 0 && p2p_pairs_allowed(P)) {
+            const f3m_level &up = P.lev[P.L - 1];
+            P.paired.alloc((size_t)lf.nb, tally);
+            pair_flag_kernel<<<dim3((unsigned)cdiv(up.nb, 256)), dim3(256), 0, st>>>(
+                up.nb, up.cstart.p, lf.cell.p, lf.start.p, lf.near_ptr.p, ts, P.paired.p);
+            F3M_HIP(hipGetLastError());
+            build_items(PairCountIn{P.paired.p}, lf.nb, P.pair_first, P.pair_box, P.npairs, tally, st);
+            build_items(RestTileCountIn{lf.start.p, ts, P.paired.p}, lf.nb, P.rtile_first, P.rtile_box, P.nrtiles, tally, st);
+        }
     }
     // target tiles of the small-field rows of every depth (Sec. 4.2)
     for (int k = 1; k <= P.L; ++k) {
