@@ -617,39 +617,23 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             }
             return src;
         };
-        float xn[D], bn = 0.f;
-        float bnm[MB];
-        {
-            const uint32_t src = locate(wbeg);
+        // Two register sets take turns as "current" and "next" step (no copies at the end of a step): the loads
+        // of the next step are in flight during the current one; the last step loads its own sources again,
+        // so the number of loads in flight is fixed.
+        auto fetch = [&](uint32_t w0, float (&x)[D], float &b1, float (&bm)[MB]) __attribute__((always_inline)) {
+            const uint32_t src = locate(w0);
 #pragma unroll
-            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
+            for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)src * D + d];
             if constexpr (MB > 1) {
 #pragma unroll
-                for (int j = 0; j < MB; ++j) bnm[j] = MA.bs[j][src];
+                for (int j = 0; j < MB; ++j) bm[j] = MA.bs[j][src];
             } else {
-                bn = bs[src];
+                b1 = bs[src];
             }
-        }
-        for (uint32_t w0 = wbeg; w0 < S; w0 += 64) {
-            float xc[D];
-#pragma unroll
-            for (int d = 0; d < D; ++d) xc[d] = xn[d];
-            const float bn0 = bn;
-            float bcm[MB];
-#pragma unroll
-            for (int j = 0; j < MB; ++j) bcm[j] = bnm[j];
-            // the loads of the next step are in flight during this one (the last step loads its own
-            // sources again, so the number of loads in flight is fixed)
-            const uint32_t src = locate(w0 + 64 < S ? w0 + 64 : w0);
-#pragma unroll
-            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
-            if constexpr (MB > 1) {
-#pragma unroll
-                for (int j = 0; j < MB; ++j) bnm[j] = MA.bs[j][src];
-            } else {
-                bn = bs[src];
-            }
-            float bc = bn0;
+        };
+        auto step = [&](uint32_t w0, const float (&xc)[D], float bc, float (&bcm)[MB], float (&xnext)[D], float &bnext,
+                        float (&bnextm)[MB]) __attribute__((always_inline)) {
+            fetch(w0 + 64 < S ? w0 + 64 : w0, xnext, bnext, bnextm);
             if (w0 + 64 > S) {   // last step only: the positions behind the sequence get weight zero
                 asm volatile("");   // keeps this a branch: as selects it costs every step three instructions
                 const bool live = w0 + lane < S;
@@ -669,6 +653,19 @@ __global__ __launch_bounds__(256) void p2p_gram3_kernel(const float *__restrict_
             prepare(xc, opA, opB);
             block(opA, 0);
             if (w0 + 32 < S) block(opB, 32);
+        };
+        float xa[D], xb[D], ba = 0.f, bb = 0.f;
+        float bam[MB], bbm[MB];
+#pragma unroll
+        for (int j = 0; j < MB; ++j) bam[j] = bbm[j] = 0.f;
+        fetch(wbeg, xa, ba, bam);
+        for (uint32_t w0 = wbeg;;) {
+            step(w0, xa, ba, bam, xb, bb, bbm);
+            w0 += 64;
+            if (w0 >= S) break;
+            step(w0, xb, bb, bbm, xa, ba, bam);
+            w0 += 64;
+            if (w0 >= S) break;
         }
     }
     if constexpr (MB > 1) {
@@ -861,23 +858,16 @@ __global__ __launch_bounds__(256) void p2p_gram3_pair_kernel(const float *__rest
             }
             return src;
         };
-        float xn[D], bn;
-        {
-            const uint32_t src = locate(wbeg);
+        // two register sets take turns as current and next step, as in p2p_gram3_kernel
+        auto fetch = [&](uint32_t w0, float (&x)[D], float &b1) __attribute__((always_inline)) {
+            const uint32_t src = locate(w0);
 #pragma unroll
-            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
-            bn = bs[src];
-        }
-        for (uint32_t w0 = wbeg; w0 < S; w0 += 64) {
-            float xc[D];
-#pragma unroll
-            for (int d = 0; d < D; ++d) xc[d] = xn[d];
-            float bc = bn;
-            // the loads of the next step are in flight during this one (the last step loads its own sources again)
-            const uint32_t src = locate(w0 + 64 < S ? w0 + 64 : w0);
-#pragma unroll
-            for (int d = 0; d < D; ++d) xn[d] = Xs[(int64_t)src * D + d];
-            bn = bs[src];
+            for (int d = 0; d < D; ++d) x[d] = Xs[(int64_t)src * D + d];
+            b1 = bs[src];
+        };
+        auto step = [&](uint32_t w0, const float (&xc)[D], float bc, float (&xnext)[D], float &bnext)
+                        __attribute__((always_inline)) {
+            fetch(w0 + 64 < S ? w0 + 64 : w0, xnext, bnext);
             if (w0 + 64 > S) {   // last step only: the positions behind the segment get weight zero
                 asm volatile("");
                 bc = w0 + lane < S ? bc : 0.f;
@@ -899,6 +889,16 @@ __global__ __launch_bounds__(256) void p2p_gram3_pair_kernel(const float *__rest
                 if constexpr ((W & 1) != 0) columns(op, bf, Bop[0], Bop[1], ntA, accA0, accA1);
                 if constexpr ((W & 2) != 0) columns(op, bf, Bop[2], Bop[3], ntB, accB0, accB1);
             }
+        };
+        float xa[D], xb[D], ba, bb;
+        fetch(wbeg, xa, ba);
+        for (uint32_t w0 = wbeg;;) {
+            step(w0, xa, ba, xb, bb);
+            w0 += 64;
+            if (w0 >= S) break;
+            step(w0, xb, bb, xa, ba);
+            w0 += 64;
+            if (w0 >= S) break;
         }
     };
     segment(0u, S1, std::integral_constant<int, 3>{});
