@@ -104,6 +104,11 @@ PLAN_CASES = [
     # more than 8192 leaf boxes (depth 5, about 9 points per box): the near field has overflow tiles
     # (boxes of at most 10 points) beside the tiles of the Gram kernel, as at the full sizes
     (300_000, 3, "uniform", 4, 0.5, 2.0, 40, 0),
+    # about 46 points per box at depth 5: the first runs of most sibling boxes are worked in pairs by one
+    # wavefront, and boxes above 64 points add second tiles and overflow tiles
+    (1_500_000, 3, "uniform", 4, 0.5, 2.0, 128, 0),
+    # far ratio 3: near rows of up to 93 boxes, too long for the paired kernel, which leaves them to the tiles
+    (300_000, 3, "uniform", 4, 0.5, 3.0, 40, 0),
     (6_000, 4, "uniform", 3, 1.0, 2.0, 50, 2),
     (4_000, 5, "uniform", 2, 1.0, 2.0, 60, 2),
     (6_000, 7, "mixture", 2, 1.5, 2.0, 100, 1),
