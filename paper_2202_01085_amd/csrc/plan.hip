@@ -158,10 +158,12 @@ struct U32Out {
 };
 
 // Stable scatter of one tile of RS_TILE keys.  Tile order = (wave, round, lane): every wave
-// ranks its own 16 rounds of 64 keys with ballots and a private LDS counter array, with no
-// block barrier inside the loop; then the tile is put in digit order in LDS and written out
-// so that consecutive threads write consecutive addresses of a digit run.
-__global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__restrict__ keys_in,
+// ranks its own 32 rounds of 64 keys with a private LDS counter array, with no block barrier
+// inside the loop; then the tile is put in digit order in LDS and written out so that
+// consecutive threads write consecutive addresses of a digit run.  The buffers must be readable
+// for a whole tile behind the last key.
+template <bool FIRST>   // FIRST: the values are the positions themselves (vals_in is not read)
+__global__ __launch_bounds__(RS_NT, 4) void rs_scatter_kernel(const uint32_t *__restrict__ keys_in,
                                                            const uint32_t *__restrict__ vals_in,
                                                            uint32_t *__restrict__ keys_out,
                                                            uint32_t *__restrict__ vals_out, int64_t n, int shift,
@@ -170,42 +172,60 @@ __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__res
     __shared__ uint32_t wcnt[NW][256];      // per wave: keys of each digit seen so far
     __shared__ uint32_t dstart[256];        // first tile-local position of each digit
     __shared__ uint32_t gbase[256];         // global position of the tile's first key of each digit
-    __shared__ uint32_t skey[RS_TILE], sval[RS_TILE];
+    __shared__ __attribute__((aligned(8))) uint32_t sbuf[RS_TILE];   // the tile in digit order: first its keys, then its values
+    // per wave, while the keys are ranked (sbuf is not in use yet): the lanes that hold each digit in the current round
+    uint64_t (*wmask)[256] = reinterpret_cast<uint64_t (*)[256]>(sbuf);
+    static_assert(sizeof(uint64_t) * NW * 256 <= sizeof(uint32_t) * RS_TILE, "the lane masks must fit the tile buffer");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // Workgroups go to the 8 dies in turn; every die takes a contiguous range of tiles, so that the runs
+    // which neighbouring tiles append to the same digit meet in one L2 and leave it as whole lines.
+    const int64_t per_die = (nblk + 7) / 8;
+    const int64_t tile = (int64_t)(blockIdx.x & 7u) * per_die + (blockIdx.x >> 3);
+    if (tile >= nblk) return;
 #pragma unroll
-    for (int k = 0; k < NW; ++k) wcnt[k][tid] = 0;
-    gbase[tid] = offs[(int64_t)tid * nblk + blockIdx.x];
-    __syncthreads();
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-    const int64_t base = (int64_t)blockIdx.x * RS_TILE + (int64_t)w * (RS_IPT * 64);
-    uint32_t key[RS_IPT], val[RS_IPT], rk[RS_IPT];   // rk = rank within (wave, digit), or ~0 if out of range
-#pragma unroll
-    for (int r = 0; r < RS_IPT; ++r) {
-        const int64_t i = base + r * 64 + lane;
-        const bool valid = i < n;
-        key[r] = valid ? keys_in[i] : 0u;
-        // value: vals_in[i], or the position itself
-        val[r] = !valid ? 0u : vals_in ? vals_in[i] : (uint32_t)i;
+    for (int k = 0; k < NW; ++k) {
+        wcnt[k][tid] = 0;
+        wmask[k][tid] = 0ull;
     }
+    gbase[tid] = offs[(int64_t)tid * nblk + tile];
+    __syncthreads();
+    const int64_t base = tile * RS_TILE + (int64_t)w * (RS_IPT * 64);
+    // Registers are what bounds the number of resident workgroups: ranks and positions are kept as 16-bit
+    // halves (a tile has 8192 places; 0xFFFF = out of range), the digits of the written keys as bytes.
+    uint32_t key[RS_IPT], val[RS_IPT], rk[RS_IPT / 2];
+    const int64_t left = n - tile * RS_TILE;
+    const int cntile = (int)(left < RS_TILE ? left : RS_TILE);   // keys of this tile (the last one may be short)
+    const int local = w * (RS_IPT * 64) + lane;                  // tile-local index of this thread's first key
+    // loads without branches: the buffers carry a tile of slack, and what is read behind the end is left out of
+    // the ranking below
+    const uint32_t *kp = keys_in + base + lane, *vp = vals_in + base + lane;
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) key[r] = kp[r * 64];
+    // Rank of a key among the earlier keys of its wave with the same digit.  The lanes of a round that hold the
+    // same digit find each other through LDS: every lane ORs its own bit into the 64-bit word of its digit
+    // (an atomic OR: the result does not depend on the order), reads the word back, and counts the bits below
+    // its own.  The first lane of each group then adds the group to the running count of the digit and clears
+    // the word.  (LDS operations of a wave complete in order, and the wave runs in lockstep.)
+    const uint64_t mybit = 1ull << lane;
 #pragma unroll
     for (int r = 0; r < RS_IPT; ++r) {
-        const int64_t i = base + r * 64 + lane;
-        const bool valid = i < n;
+        const bool valid = local + r * 64 < cntile;
         const uint32_t digit = (key[r] >> shift) & 255u;
-        uint64_t peers = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const bool bit = (digit >> b) & 1u;
-            const uint64_t m = __ballot(bit);
-            peers &= bit ? m : ~m;
+        uint32_t rank = 0xFFFFu;
+        if (valid) {
+            atomicOr(reinterpret_cast<unsigned long long *>(&wmask[w][digit]), (unsigned long long)mybit);
+            __builtin_amdgcn_wave_barrier();
+            const uint64_t peers = wmask[w][digit];
+            const uint32_t cnt = wcnt[w][digit];
+            const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+            rank = cnt + before;   // within (wave, digit): below 2048
+            __builtin_amdgcn_wave_barrier();
+            if (before == 0) {
+                wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
+                wmask[w][digit] = 0ull;
+            }
         }
-        const uint32_t before = (uint32_t)__popcll(peers & lt_mask);
-        uint32_t cnt = 0;
-        if (valid) cnt = wcnt[w][digit];
-        rk[r] = valid ? cnt + before : 0xFFFFFFFFu;
-        // the wave runs in lockstep and LDS operations of a wave complete in order: all lanes
-        // have read the counter before the leader of each digit group updates it
-        if (valid && before == 0) wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
+        rk[r >> 1] = (r & 1) ? (rk[r >> 1] | (rank << 16)) : rank;
         __builtin_amdgcn_wave_barrier();   // keep the rounds' LDS accesses in program order
     }
     __syncthreads();
@@ -219,28 +239,52 @@ __global__ __launch_bounds__(RS_NT) void rs_scatter_kernel(const uint32_t *__res
         dstart[tid] = ex;
     }
     __syncthreads();
+    // keys and values pass through the same 32 KB of LDS one after the other
 #pragma unroll
     for (int r = 0; r < RS_IPT; ++r) {
-        if (rk[r] != 0xFFFFFFFFu) {
+        const uint32_t rank = (rk[r >> 1] >> (16 * (r & 1))) & 0xFFFFu;
+        if (rank != 0xFFFFu) {
             const uint32_t digit = (key[r] >> shift) & 255u;
-            uint32_t pos = dstart[digit] + rk[r];
+            uint32_t pos = dstart[digit] + rank;
             for (int k = 0; k < w; ++k) pos += wcnt[k][digit];
-            skey[pos] = key[r];
-            sval[pos] = val[r];
+            rk[r >> 1] = (r & 1) ? ((rk[r >> 1] & 0xFFFFu) | (pos << 16)) : ((rk[r >> 1] & 0xFFFF0000u) | pos);
+            sbuf[pos] = key[r];
         }
     }
+    // the values are loaded only now, into the registers of the keys (keys, values and ranks together would not
+    // fit the register budget of four workgroups per compute unit); they arrive while the keys are written out
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        if constexpr (FIRST) val[r] = (uint32_t)(base + r * 64 + lane);
+        else val[r] = vp[r * 64];
+    }
     __syncthreads();
-    const int64_t left = n - (int64_t)blockIdx.x * RS_TILE;
-    const int cntile = (int)(left < RS_TILE ? left : RS_TILE);
+    uint32_t dig[RS_IPT / 4];   // digit of the tile's entry r * RS_NT + tid
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        const int pos = r * RS_NT + tid;
+        uint32_t digit = 0;
+        if (pos < cntile) {
+            const uint32_t k = sbuf[pos];
+            digit = (k >> shift) & 255u;
+            keys_out[gbase[digit] + ((uint32_t)pos - dstart[digit])] = k;
+        }
+        dig[r >> 2] = (r & 3) ? (dig[r >> 2] | (digit << (8 * (r & 3)))) : digit;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < RS_IPT; ++r) {
+        const uint32_t pos = (rk[r >> 1] >> (16 * (r & 1))) & 0xFFFFu;
+        if (pos != 0xFFFFu) sbuf[pos] = val[r];
+    }
+    __syncthreads();
 #pragma unroll
     for (int r = 0; r < RS_IPT; ++r) {
         const int pos = r * RS_NT + tid;
         if (pos < cntile) {
-            const uint32_t k = skey[pos];
-            const uint32_t digit = (k >> shift) & 255u;
-            const uint32_t g = gbase[digit] + ((uint32_t)pos - dstart[digit]);
-            keys_out[g] = k;
-            vals_out[g] = sval[pos];
+            const uint32_t digit = (dig[r >> 2] >> (8 * (r & 3))) & 255u;
+            vals_out[gbase[digit] + ((uint32_t)pos - dstart[digit])] = sbuf[pos];
         }
     }
 }
@@ -260,7 +304,11 @@ static bool radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uin
         rs_hist_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, n, shift, hist.p, nblk);
         F3M_HIP(hipGetLastError());
         exclusive_scan(U32In{hist.p}, nblk * 256, U32Out{hist.p}, nullptr, st);
-        rs_scatter_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk);
+        const unsigned grid = (unsigned)((nblk + 7) / 8 * 8);   // a whole number of rounds over the dies
+        if (first)
+            rs_scatter_kernel<true><<<dim3(grid), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk);
+        else
+            rs_scatter_kernel<false><<<dim3(grid), dim3(RS_NT), 0, st>>>(kin, vin, kout, vout, n, shift, hist.p, nblk);
         F3M_HIP(hipGetLastError());
         in_b = !in_b;
         first = false;
@@ -917,8 +965,9 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
 
     // ---- keys, sort, gather
     for (const SetRef &S : sets) {
-        S.keys->alloc((size_t)S.n, tally);
-        S.perm->alloc((size_t)S.n, tally);
+        // (one tile of slack behind the keys and the indices: the sort reads whole tiles)
+        S.keys->alloc((size_t)S.n + RS_TILE, tally);
+        S.perm->alloc((size_t)S.n + RS_TILE, tally);
         AlphaArg aa;
         for (int d = 0; d < F3M_MAX_DIM; ++d) aa.a[d] = S.alpha[d];
         keys_kernel<D><<<dim3((unsigned)cdiv(S.n, 256)), dim3(256), 0, st>>>(S.X, S.n, aa, P.scale, P.Lq, S.keys->p);
@@ -928,8 +977,8 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
     int bits_sorted = 0;
     for (const SetRef &S : sets) {
         DevBuf<uint32_t> keys_b, perm_b;
-        keys_b.alloc((size_t)S.n);
-        perm_b.alloc((size_t)S.n);
+        keys_b.alloc((size_t)S.n + RS_TILE);
+        perm_b.alloc((size_t)S.n + RS_TILE);
         int bits = P.E > 0.f ? D * P.Lq : 0;
         bits_sorted = bits;
         bool in_b;
