@@ -42,45 +42,66 @@ __device__ inline int64_t route_count_index(const RouteLevel &R, int64_t t, uint
     return ((((region << R.s2) + b) << R.s2) + (t & ((1 << R.s2) - 1)));
 }
 
+// Tile of this workgroup.  Workgroups go to the 8 dies (each with its own L2) in turn; every die takes a
+// contiguous range of tiles, so that the runs which neighbouring tiles write to (or read from) the same bucket
+// meet in one L2 as whole lines.  The grid holds a whole number of rounds over the dies (route_grid); a
+// workgroup beyond the last tile returns at once.
+__device__ inline int64_t route_tile(int64_t n) {
+    const int64_t ntiles = (n + RT_TILE - 1) / RT_TILE, per_die = (ntiles + 7) >> 3;
+    const int64_t t = (int64_t)(blockIdx.x & 7u) * per_die + (int64_t)(blockIdx.x >> 3);
+    return t < ntiles ? t : -1;
+}
+static unsigned route_grid(int64_t ntiles) { return (unsigned)((ntiles + 7) / 8 * 8); }
+
 __global__ __launch_bounds__(RT_NT) void route_hist_kernel(const uint32_t *__restrict__ dest, int64_t n, RouteLevel R,
                                                            uint32_t *__restrict__ cnt) {
+    const int64_t tb = route_tile(n);
+    if (tb < 0) return;
     __shared__ uint32_t h[256];
     const int tid = threadIdx.x;
     if (tid < 256) h[tid] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t base = tb * RT_TILE;
 #pragma unroll 4
     for (int r = 0; r < RT_IPT; ++r) {
         const int64_t i = base + r * RT_NT + tid;
         if (i < n) atomicAdd(&h[(dest[i] >> R.shift) & R.mask], 1u);
     }
     __syncthreads();
-    if (tid < R.B) cnt[route_count_index(R, blockIdx.x, (uint32_t)tid)] = h[tid];
+    if (tid < R.B) cnt[route_count_index(R, tb, (uint32_t)tid)] = h[tid];
 }
 
 // One tile of a pass: the place of every value in the LDS copy of the tile (values of a digit together,
 // digits ascending, inside a digit in tile order), the destinations moved along to the next order, and the
 // tile's tables (first place of each digit; global position of the tile's first value of each digit, minus
-// that place).  Tile order = (wavefront, round, lane); ranking by wave ballots against per-wave LDS counters.
+// that place).  Tile order = (wavefront, round, lane); ranking against per-wave LDS counters.
 __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__restrict__ dest_in, int64_t n, RouteLevel R,
                                                            const uint32_t *__restrict__ offs,
                                                            uint16_t *__restrict__ slot, uint32_t *__restrict__ dest_out,
                                                            uint16_t *__restrict__ off_out,
                                                            uint32_t *__restrict__ dstart_out,
                                                            uint32_t *__restrict__ gofs_out) {
+    const int64_t tb = route_tile(n);
+    if (tb < 0) return;
     __shared__ uint32_t wcnt[RT_NW][256];   // per wave: values of each digit seen so far; later the wave's offset
     __shared__ uint32_t dstart[257];        // first place of each digit
     __shared__ uint32_t gbase[256];         // global position of the tile's first value of each digit
-    __shared__ uint32_t skey[RT_TILE];
+    __shared__ __attribute__((aligned(8))) uint32_t skey[RT_TILE];
+    // per wave, while the values are ranked (skey is not in use yet): the lanes that hold each digit in the current round
+    uint64_t (*wmask)[256] = reinterpret_cast<uint64_t (*)[256]>(skey);
+    static_assert(sizeof(uint64_t) * RT_NW * 256 <= sizeof(uint32_t) * RT_TILE, "the lane masks must fit the tile buffer");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     if (tid < 256) {
 #pragma unroll
-        for (int k = 0; k < RT_NW; ++k) wcnt[k][tid] = 0;
-        gbase[tid] = tid < R.B ? offs[route_count_index(R, blockIdx.x, (uint32_t)tid)] : 0u;
+        for (int k = 0; k < RT_NW; ++k) {
+            wcnt[k][tid] = 0;
+            wmask[k][tid] = 0ull;
+        }
+        gbase[tid] = tid < R.B ? offs[route_count_index(R, tb, (uint32_t)tid)] : 0u;
     }
     __syncthreads();
-    const uint64_t lt_mask = (1ull << lane) - 1ull;
-    const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
+    const uint64_t mybit = 1ull << lane;
+    const int64_t tile0 = tb * RT_TILE;
     const int64_t base = tile0 + (int64_t)w * (RT_IPT * 64);
     uint32_t rk[RT_IPT / 2];   // rank within (wave, digit), below 2048: two per register
 #pragma unroll
@@ -98,20 +119,25 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
             const int64_t i = base + (h + r) * 64 + lane;
             const bool valid = i < n;
             const uint32_t digit = (key[r] >> R.shift) & R.mask;
-            uint64_t peers = __ballot(valid);
-#pragma unroll
-            for (int b = 0; b < 8; ++b) {
-                const bool bit = (digit >> b) & 1u;
-                const uint64_t m = __ballot(bit);
-                peers &= bit ? m : ~m;
+            // The lanes of the round with the same digit find each other through LDS: every lane ORs its own
+            // bit into the 64-bit word of its digit (an atomic OR: the result does not depend on the order),
+            // reads the word back and counts the bits below its own; the first lane of each group adds the
+            // group to the digit's running count and clears the word.  (The wave runs in lockstep and its
+            // LDS operations complete in order.)
+            if (valid) {
+                atomicOr(reinterpret_cast<unsigned long long *>(&wmask[w][digit]), (unsigned long long)mybit);
+                __builtin_amdgcn_wave_barrier();
+                const uint64_t peers = wmask[w][digit];
+                const uint32_t cnt = wcnt[w][digit];
+                const uint32_t before =
+                    __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+                rk[(h + r) / 2] |= (cnt + before) << (16 * ((h + r) & 1));
+                __builtin_amdgcn_wave_barrier();
+                if (before == 0) {
+                    wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
+                    wmask[w][digit] = 0ull;
+                }
             }
-            const uint32_t before = (uint32_t)__popcll(peers & lt_mask);
-            uint32_t cnt = 0;
-            if (valid) cnt = wcnt[w][digit];
-            rk[(h + r) / 2] |= (cnt + before) << (16 * ((h + r) & 1));
-            // the wave runs in lockstep and its LDS operations complete in order: every lane has read the
-            // counter before the first lane of each digit group updates it
-            if (valid && before == 0) wcnt[w][digit] = cnt + (uint32_t)__popcll(peers);
             __builtin_amdgcn_wave_barrier();
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -174,8 +200,8 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
             else dest_out[g] = k;
         }
     }
-    if (tid <= 256) dstart_out[(int64_t)blockIdx.x * 257 + tid] = dstart[tid];
-    if (tid < 256) gofs_out[(int64_t)blockIdx.x * 256 + tid] = gbase[tid] - dstart[tid];
+    if (tid <= 256) dstart_out[tb * 257 + tid] = dstart[tid];
+    if (tid < 256) gofs_out[tb * 256 + tid] = gbase[tid] - dstart[tid];
 }
 
 // ------------------------------------------------------------------------------------
@@ -196,14 +222,16 @@ __global__ __launch_bounds__(RT_NT) void route_deal_kernel(const float *__restri
                                                            float *__restrict__ out, const uint16_t *__restrict__ slot,
                                                            const uint32_t *__restrict__ dstart_tab,
                                                            const uint32_t *__restrict__ gofs_tab, int B, int64_t n) {
+    const int64_t tb = route_tile(n);
+    if (tb < 0) return;
     __shared__ float stage[RT_TILE];
     __shared__ uint32_t ds[257], go[256];
     const int tid = threadIdx.x;
-    const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t tile0 = tb * RT_TILE;
     const int64_t left = n - tile0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
-    if (tid <= 256) ds[tid] = dstart_tab[(int64_t)blockIdx.x * 257 + tid];
-    if (tid < 256) go[tid] = gofs_tab[(int64_t)blockIdx.x * 256 + tid];
+    if (tid <= 256) ds[tid] = dstart_tab[tb * 257 + tid];
+    if (tid < 256) go[tid] = gofs_tab[tb * 256 + tid];
     uint16_t sl[RT_IPT];
     float v[RT_IPT];
 #pragma unroll
@@ -240,14 +268,16 @@ __global__ __launch_bounds__(RT_NT) void route_collect_kernel(const float *__res
                                                               const uint16_t *__restrict__ slot,
                                                               const uint32_t *__restrict__ dstart_tab,
                                                               const uint32_t *__restrict__ gofs_tab, int B, int64_t n) {
+    const int64_t tb = route_tile(n);
+    if (tb < 0) return;
     __shared__ float stage[RT_TILE];
     __shared__ uint32_t ds[257], go[256];
     const int tid = threadIdx.x;
-    const int64_t tile0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t tile0 = tb * RT_TILE;
     const int64_t left = n - tile0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
-    if (tid <= 256) ds[tid] = dstart_tab[(int64_t)blockIdx.x * 257 + tid];
-    if (tid < 256) go[tid] = gofs_tab[(int64_t)blockIdx.x * 256 + tid];
+    if (tid <= 256) ds[tid] = dstart_tab[tb * 257 + tid];
+    if (tid < 256) go[tid] = gofs_tab[tb * 256 + tid];
     uint32_t sl[RT_IPT / 2];   // two places per register
 #pragma unroll
     for (int r = 0; r < RT_IPT; r += 2) {
@@ -301,9 +331,11 @@ __global__ __launch_bounds__(RT_NT) void route_collect_kernel(const float *__res
 // pass 3 forwards: the values of a window, each to its place inside the window
 __global__ __launch_bounds__(RT_NT) void route_place_kernel(const float *__restrict__ in, float *__restrict__ out,
                                                             const uint16_t *__restrict__ off, int64_t n) {
+    const int64_t tb = route_tile(n);
+    if (tb < 0) return;
     __shared__ float stage[RT_TILE];
     const int tid = threadIdx.x;
-    const int64_t win0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t win0 = tb * RT_TILE;
     const int64_t left = n - win0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
     uint16_t o[RT_IPT];
@@ -332,9 +364,11 @@ template <int NC>
 __global__ __launch_bounds__(RT_NT) void route_pick_kernel(const float *__restrict__ in, float *__restrict__ out,
                                                            int64_t out_stride, const uint16_t *__restrict__ off,
                                                            int64_t n) {
+    const int64_t tb = route_tile(n);
+    if (tb < 0) return;
     __shared__ float stage[RT_TILE];
     const int tid = threadIdx.x;
-    const int64_t win0 = (int64_t)blockIdx.x * RT_TILE;
+    const int64_t win0 = tb * RT_TILE;
     const int64_t left = n - win0;
     const int cnt = (int)(left < RT_TILE ? left : RT_TILE);
     struct Row { float v[NC]; };
@@ -417,7 +451,7 @@ void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, 
     dest1.alloc((size_t)n);
     const int64_t ncnt = std::max<int64_t>((int64_t)R.B1 * R.ntiles, (int64_t)R.B1 * R.B2 * R.B2);
     cnt.alloc((size_t)ncnt);
-    const unsigned grid = (unsigned)R.ntiles;
+    const unsigned grid = route_grid(R.ntiles);
     for (int pass = 1; pass <= 2; ++pass) {
         const RouteLevel L = route_level(R, pass);
         const uint32_t *din = pass == 1 ? perm : dest1.p;
@@ -438,7 +472,7 @@ void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, 
 // out[perm[k]] = in[k] (+ in2[k]); tmp_a, tmp_b: n floats each
 void route_scatter(const f3m_route &R, const float *in, const float *in2, float *out, float *tmp_a, float *tmp_b,
                    hipStream_t st) {
-    const unsigned grid = (unsigned)R.ntiles;
+    const unsigned grid = route_grid(R.ntiles);
     route_deal_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(in, in2, tmp_a, R.slot1.p, R.dstart1.p, R.gofs1.p, R.B1, R.n);
     route_deal_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp_a, nullptr, tmp_b, R.slot2.p, R.dstart2.p, R.gofs2.p, R.B2,
                                                          R.n);
@@ -448,7 +482,7 @@ void route_scatter(const f3m_route &R, const float *in, const float *in2, float 
 
 // out[k] = in[perm[k]]; tmp_a, tmp_b: n floats each
 void route_gather(const f3m_route &R, const float *in, float *out, float *tmp_a, float *tmp_b, hipStream_t st) {
-    const unsigned grid = (unsigned)R.ntiles;
+    const unsigned grid = route_grid(R.ntiles);
     route_pick_kernel<1><<<dim3(grid), dim3(RT_NT), 0, st>>>(in, tmp_a, 0, R.off3.p, R.n);
     route_collect_kernel<1, false><<<dim3(grid), dim3(RT_NT), 0, st>>>(tmp_a, 0, tmp_b, 0, R.slot2.p, R.dstart2.p,
                                                                       R.gofs2.p, R.B2, R.n);
@@ -460,7 +494,7 @@ void route_gather(const f3m_route &R, const float *in, float *out, float *tmp_a,
 // rows of three coordinates: out[k][0..2] = in[perm[k]][0..2].  `out` (3 n floats) first serves as the
 // three component arrays of order p2; tmp: 3 n floats.
 void route_gather_rows3(const f3m_route &R, const float *in, float *out, float *tmp, hipStream_t st) {
-    const unsigned grid = (unsigned)R.ntiles;
+    const unsigned grid = route_grid(R.ntiles);
     route_pick_kernel<3><<<dim3(grid), dim3(RT_NT), 0, st>>>(in, out, R.n, R.off3.p, R.n);
     route_collect_kernel<3, false><<<dim3(grid), dim3(RT_NT), 0, st>>>(out, R.n, tmp, R.n, R.slot2.p, R.dstart2.p,
                                                                       R.gofs2.p, R.B2, R.n);
