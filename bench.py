@@ -320,8 +320,9 @@ def main():
         flops = (3.0 * D + 2.0) * pairs
         ach = flops / t / 1e12
         lane_slots_per_s = 256 * 64 * 2.4e9
-        rooflines["p2p"] = {"kernel": "near field: p2p_gram3_kernel (tiles of up to 64 targets) + p2p_small_kernel (last runs "
-                                      "of <= 10 targets), %d point pairs" % pairs if D == 3 and not args.xy else
+        rooflines["p2p"] = {"kernel": "near field: p2p_gram3_pair_kernel (first runs of up to 64 targets of two sibling boxes "
+                                      "per wavefront) + p2p_gram3_kernel (the other runs) + p2p_small_kernel (last runs of "
+                                      "<= 10 targets), %d point pairs" % pairs if D == 3 and not args.xy else
                                       "near field, %d point pairs" % pairs, "bound": "alu", "achieved": ach,
                             "peak": PEAK_VALU_F32_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32_TFLOPS,
                             "traffic": traffic.get("p2p"), "launch_ms": st["p2p"],
