@@ -136,16 +136,20 @@ constexpr int RS_TILE = RS_NT * RS_IPT;
 __global__ __launch_bounds__(RS_NT) void rs_hist_kernel(const uint32_t *__restrict__ keys, int64_t n, int shift,
                                                         uint32_t *__restrict__ hist, int64_t nblk) {
     __shared__ uint32_t h[256];
+    // tiles are dealt to the dies like those of the scatter kernel (the counts of neighbouring tiles share lines)
+    const int64_t per_die = (nblk + 7) / 8;
+    const int64_t tile = (int64_t)(blockIdx.x & 7u) * per_die + (blockIdx.x >> 3);
+    if (tile >= nblk) return;
     h[threadIdx.x] = 0;
     __syncthreads();
-    int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    int64_t base = tile * RS_TILE;
 #pragma unroll
     for (int k = 0; k < RS_IPT; ++k) {
         int64_t i = base + k * RS_NT + threadIdx.x;
         if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
     }
     __syncthreads();
-    hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+    hist[(int64_t)threadIdx.x * nblk + tile] = h[threadIdx.x];
 }
 
 struct U32In {
@@ -301,7 +305,7 @@ static bool radix_sort(uint32_t *keys_a, uint32_t *vals_a, uint32_t *keys_b, uin
         const uint32_t *vin = first ? nullptr : (in_b ? vals_b : vals_a);
         uint32_t *kout = in_b ? keys_a : keys_b;
         uint32_t *vout = in_b ? vals_a : vals_b;
-        rs_hist_kernel<<<dim3((unsigned)nblk), dim3(RS_NT), 0, st>>>(kin, n, shift, hist.p, nblk);
+        rs_hist_kernel<<<dim3((unsigned)((nblk + 7) / 8 * 8)), dim3(RS_NT), 0, st>>>(kin, n, shift, hist.p, nblk);
         F3M_HIP(hipGetLastError());
         exclusive_scan(U32In{hist.p}, nblk * 256, U32Out{hist.p}, nullptr, st);
         const unsigned grid = (unsigned)((nblk + 7) / 8 * 8);   // a whole number of rounds over the dies
@@ -540,7 +544,10 @@ __global__ __launch_bounds__(64) void lists_parent_kernel(int pass, int64_t npar
                                                           const uint32_t *__restrict__ up_near_col, ListArg A) {
     constexpr int NC = 1 << D;   // children of a box, at most
     __shared__ uint32_t cand[64 * NC];
-    const int64_t P = blockIdx.x;
+    // workgroups go to the 8 dies in turn; every die takes a contiguous range of parents, whose rows and candidates
+    // neighbour each other in memory (whole lines leave one L2, shared candidates are read into one L2)
+    const int64_t per_die = (nparents + 7) >> 3;
+    const int64_t P = (int64_t)(blockIdx.x & 7u) * per_die + (int64_t)(blockIdx.x >> 3);
     if (P >= nparents) return;
     const int lane = threadIdx.x;
     const uint32_t a0 = cstart[P];
@@ -1066,7 +1073,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
             A.cnt_small = cs.p;
             if constexpr (D <= 3) {
                 if (lists_by_parent(A, D))
-                    lists_parent_kernel<D><<<dim3((unsigned)up.nb), dim3(64), 0, st>>>(0, up.nb, up.cstart.p, lv.cell.p,
+                    lists_parent_kernel<D><<<dim3((unsigned)((up.nb + 7) / 8 * 8)), dim3(64), 0, st>>>(0, up.nb, up.cstart.p, lv.cell.p,
                                                                                        up.near_ptr.p, up.near_col.p, A);
                 else
                     lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(0, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,
@@ -1117,7 +1124,7 @@ static void build_plan_d(f3m_plan_s &P, const float *X, const float *Y, hipStrea
             }
             if constexpr (D <= 3) {
                 if (lists_by_parent(A, D))
-                    lists_parent_kernel<D><<<dim3((unsigned)up.nb), dim3(64), 0, st>>>(1, up.nb, up.cstart.p, lv.cell.p,
+                    lists_parent_kernel<D><<<dim3((unsigned)((up.nb + 7) / 8 * 8)), dim3(64), 0, st>>>(1, up.nb, up.cstart.p, lv.cell.p,
                                                                                        up.near_ptr.p, up.near_col.p, A);
                 else
                     lists_kernel<D><<<dim3(grid), dim3(128), 0, st>>>(1, lv.nb, lv.parent.p, lv.cell.p, up.near_ptr.p,

@@ -317,12 +317,17 @@ __global__ __launch_bounds__(RT_NT) void route_collect_kernel(const float *__res
         __syncthreads();
     }
     if (ROWS) {
+        // a row leaves as one store of NC values
+        struct Row { float v[NC]; };
+        Row *rows = reinterpret_cast<Row *>(out);
 #pragma unroll
         for (int r = 0; r < RT_IPT; ++r) {
             const int e = r * RT_NT + tid;
             if (e < cnt) {
+                Row t;
 #pragma unroll
-                for (int c = 0; c < NC; ++c) out[(tile0 + e) * NC + c] = v[ROWS ? c : 0][r];
+                for (int c = 0; c < NC; ++c) t.v[c] = v[ROWS ? c : 0][r];
+                rows[tile0 + e] = t;
             }
         }
     }
