@@ -34,14 +34,6 @@ struct RouteLevel {
     int64_t ntiles;
 };
 
-// where the count of (tile t, digit b) sits in the array whose exclusive prefix sum gives the first position
-// of that tile's values of that digit: digit-major for pass 1; (bucket, digit, tile inside the bucket) for pass 2
-__device__ inline int64_t route_count_index(const RouteLevel &R, int64_t t, uint32_t b) {
-    if (!R.second) return (int64_t)b * R.ntiles + t;
-    const int64_t region = t >> R.s2;
-    return ((((region << R.s2) + b) << R.s2) + (t & ((1 << R.s2) - 1)));
-}
-
 // Tile of this workgroup.  Workgroups go to the 8 dies (each with its own L2) in turn; every die takes a
 // contiguous range of tiles, so that the runs which neighbouring tiles write to (or read from) the same bucket
 // meet in one L2 as whole lines.  The grid holds a whole number of rounds over the dies (route_grid); a
@@ -53,22 +45,16 @@ __device__ inline int64_t route_tile(int64_t n) {
 }
 static unsigned route_grid(int64_t ntiles) { return (unsigned)((ntiles + 7) / 8 * 8); }
 
-__global__ __launch_bounds__(RT_NT) void route_hist_kernel(const uint32_t *__restrict__ dest, int64_t n, RouteLevel R,
-                                                           uint32_t *__restrict__ cnt) {
-    const int64_t tb = route_tile(n);
-    if (tb < 0) return;
-    __shared__ uint32_t h[256];
-    const int tid = threadIdx.x;
-    if (tid < 256) h[tid] = 0;
-    __syncthreads();
-    const int64_t base = tb * RT_TILE;
-#pragma unroll 4
-    for (int r = 0; r < RT_IPT; ++r) {
-        const int64_t i = base + r * RT_NT + tid;
-        if (i < n) atomicAdd(&h[(dest[i] >> R.shift) & R.mask], 1u);
-    }
-    __syncthreads();
-    if (tid < R.B) cnt[route_count_index(R, tb, (uint32_t)tid)] = h[tid];
+// Where the runs of a pass begin.  The buckets of pass 1 and the windows of pass 2 have known sizes (bucket d1
+// holds exactly the values bound for its B2 windows, a window its T values), so their first positions need no
+// counting: bucket d1 starts at d1 B2 T, window w at w T.  A tile reserves the run of each of its digits by an
+// atomic add on the cursor of the bucket (pass 1) or window (pass 2); the order of the runs inside a bucket is
+// then the order in which the tiles got there, which is as good as any: the places of the later passes are
+// computed from the order that came out, and the values end where perm says whatever the order in between.
+__global__ __launch_bounds__(256) void route_cursor_init_kernel(uint32_t *__restrict__ cursor, int64_t count,
+                                                                uint32_t step) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < count) cursor[i] = (uint32_t)i * step;
 }
 
 // One tile of a pass: the place of every value in the LDS copy of the tile (values of a digit together,
@@ -76,7 +62,7 @@ __global__ __launch_bounds__(RT_NT) void route_hist_kernel(const uint32_t *__res
 // tile's tables (first place of each digit; global position of the tile's first value of each digit, minus
 // that place).  Tile order = (wavefront, round, lane); ranking against per-wave LDS counters.
 __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__restrict__ dest_in, int64_t n, RouteLevel R,
-                                                           const uint32_t *__restrict__ offs,
+                                                           uint32_t *__restrict__ cursor,
                                                            uint16_t *__restrict__ slot, uint32_t *__restrict__ dest_out,
                                                            uint16_t *__restrict__ off_out,
                                                            uint32_t *__restrict__ dstart_out,
@@ -97,7 +83,6 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
             wcnt[k][tid] = 0;
             wmask[k][tid] = 0ull;
         }
-        gbase[tid] = tid < R.B ? offs[route_count_index(R, tb, (uint32_t)tid)] : 0u;
     }
     __syncthreads();
     const uint64_t mybit = 1ull << lane;
@@ -165,6 +150,17 @@ __global__ __launch_bounds__(RT_NT) void route_rank_kernel(const uint32_t *__res
         if (lane == 63) dstart[256] = ex;
     }
     __syncthreads();
+    // the runs of this tile: digit b takes the next dstart[b + 1] - dstart[b] positions of its bucket (pass 1)
+    // or of its window inside the bucket of this tile (pass 2)
+    if (tid < 256) {
+        uint32_t g = 0;
+        if (tid < R.B) {
+            const uint32_t count = dstart[tid + 1] - dstart[tid];
+            const int64_t c = R.second ? ((tb >> R.s2) << R.s2) + tid : (int64_t)tid;
+            if (count > 0) g = atomicAdd(&cursor[c], count);
+        }
+        gbase[tid] = g;
+    }
 #pragma unroll
     for (int h = 0; h < RT_IPT; h += 8) {
         uint32_t key[8];   // read again: keeping the first copy would not fit the registers
@@ -408,15 +404,6 @@ __global__ __launch_bounds__(RT_NT) void route_pick_kernel(const float *__restri
     }
 }
 
-struct RouteU32In {
-    const uint32_t *p;
-    __device__ uint64_t operator()(int64_t i) const { return p[i]; }
-};
-struct RouteU32Out {
-    uint32_t *p;
-    __device__ void operator()(int64_t i, uint64_t ex, uint64_t) const { p[i] = (uint32_t)ex; }
-};
-
 // ------------------------------------------------------------------------------------
 static RouteLevel route_level(const f3m_route &R, int pass) {
     RouteLevel L{};
@@ -452,19 +439,19 @@ void route_build(f3m_route &R, const uint32_t *perm, int64_t n, int64_t *tally, 
     R.dstart2.alloc((size_t)R.ntiles * 257, tally);
     R.gofs1.alloc((size_t)R.ntiles * 256, tally);
     R.gofs2.alloc((size_t)R.ntiles * 256, tally);
-    DevBuf<uint32_t> dest1, cnt;
+    DevBuf<uint32_t> dest1, cursor;
     dest1.alloc((size_t)n);
-    const int64_t ncnt = std::max<int64_t>((int64_t)R.B1 * R.ntiles, (int64_t)R.B1 * R.B2 * R.B2);
-    cnt.alloc((size_t)ncnt);
+    const int64_t nwin = (int64_t)R.B1 * R.B2;   // windows, counting the empty ones behind the last value
+    cursor.alloc((size_t)nwin);
     const unsigned grid = route_grid(R.ntiles);
     for (int pass = 1; pass <= 2; ++pass) {
         const RouteLevel L = route_level(R, pass);
         const uint32_t *din = pass == 1 ? perm : dest1.p;
-        F3M_HIP(hipMemsetAsync(cnt.p, 0, (size_t)ncnt * sizeof(uint32_t), st));
-        route_hist_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(din, n, L, cnt.p);
-        F3M_HIP(hipGetLastError());
-        exclusive_scan(RouteU32In{cnt.p}, ncnt, RouteU32Out{cnt.p}, nullptr, st);
-        route_rank_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(din, n, L, cnt.p, pass == 1 ? R.slot1.p : R.slot2.p,
+        // first positions: bucket d1 at d1 B2 T, window w at w T
+        const int64_t ncur = pass == 1 ? R.B1 : nwin;
+        route_cursor_init_kernel<<<dim3((unsigned)cdiv(ncur, 256)), dim3(256), 0, st>>>(
+            cursor.p, ncur, pass == 1 ? (uint32_t)R.B2 * (uint32_t)RT_TILE : (uint32_t)RT_TILE);
+        route_rank_kernel<<<dim3(grid), dim3(RT_NT), 0, st>>>(din, n, L, cursor.p, pass == 1 ? R.slot1.p : R.slot2.p,
                                                              pass == 1 ? dest1.p : nullptr,
                                                              pass == 1 ? nullptr : R.off3.p,
                                                              pass == 1 ? R.dstart1.p : R.dstart2.p,
