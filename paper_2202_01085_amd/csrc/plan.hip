@@ -142,11 +142,22 @@ __global__ __launch_bounds__(RS_NT) void rs_hist_kernel(const uint32_t *__restri
     if (tile >= nblk) return;
     h[threadIdx.x] = 0;
     __syncthreads();
-    int64_t base = tile * RS_TILE;
+    // all loads first, four keys each, without a bounds test (the key buffers carry a tile of slack behind the
+    // last key); what lies behind the end is left out of the counts
+    const int64_t base = tile * RS_TILE;
+    const int64_t left = n - base;
+    const int cntile = (int)(left < RS_TILE ? left : RS_TILE);
+    const uint4 *kp = reinterpret_cast<const uint4 *>(keys + base);
+    uint4 v[RS_IPT / 4];
 #pragma unroll
-    for (int k = 0; k < RS_IPT; ++k) {
-        int64_t i = base + k * RS_NT + threadIdx.x;
-        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+    for (int k = 0; k < RS_IPT / 4; ++k) v[k] = kp[k * RS_NT + threadIdx.x];
+#pragma unroll
+    for (int k = 0; k < RS_IPT / 4; ++k) {
+        const int i0 = (k * RS_NT + (int)threadIdx.x) * 4;
+        const uint32_t key4[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (i0 + c < cntile) atomicAdd(&h[(key4[c] >> shift) & 255u], 1u);
     }
     __syncthreads();
     hist[(int64_t)threadIdx.x * nblk + tile] = h[threadIdx.x];
