@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "../../include/f3m.h"
@@ -124,13 +125,33 @@ __device__ inline uint64_t block_excl_scan_u64(uint64_t v, uint64_t *total) {
     return base + incl - v;
 }
 
+// The SCAN_IPT consecutive inputs of a thread (zero behind the end).  An input type may hand over a whole run
+// at once (load_run(base, v), base a multiple of SCAN_IPT, all of the run inside the array): it can then read
+// its array with a few wide loads instead of one dependent narrow load per input.
+template <class T, class = void>
+struct has_load_run : std::false_type {};
+template <class T>
+struct has_load_run<T, std::void_t<decltype(&T::load_run)>> : std::true_type {};
+template <class In>
+__device__ inline void scan_load(const In &in, int64_t base, int64_t n, uint64_t (&v)[SCAN_IPT]) {
+    if constexpr (has_load_run<In>::value) {
+        if (base + SCAN_IPT <= n) {
+            in.load_run(base, v);
+            return;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < SCAN_IPT; ++k) v[k] = (base + k < n) ? in(base + k) : 0;
+}
+
 template <class In>
 __global__ __launch_bounds__(SCAN_NT) void scan_reduce_kernel(In in, int64_t n, uint64_t *block_sums) {
     int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_IPT;
+    uint64_t v[SCAN_IPT];
+    scan_load(in, base, n, v);
     uint64_t s = 0;
 #pragma unroll
-    for (int k = 0; k < SCAN_IPT; ++k)
-        if (base + k < n) s += in(base + k);
+    for (int k = 0; k < SCAN_IPT; ++k) s += v[k];
     uint64_t tot;
     block_excl_scan_u64(s, &tot);
     if (threadIdx.x == 0) block_sums[blockIdx.x] = tot;
@@ -140,12 +161,10 @@ template <class In, class Out>
 __global__ __launch_bounds__(SCAN_NT) void scan_apply_kernel(In in, int64_t n, const uint64_t *block_offsets, Out out) {
     int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_IPT;
     uint64_t v[SCAN_IPT];
+    scan_load(in, base, n, v);
     uint64_t s = 0;
 #pragma unroll
-    for (int k = 0; k < SCAN_IPT; ++k) {
-        v[k] = (base + k < n) ? in(base + k) : 0;
-        s += v[k];
-    }
+    for (int k = 0; k < SCAN_IPT; ++k) s += v[k];
     uint64_t tot;
     uint64_t ex = block_excl_scan_u64(s, &tot) + (block_offsets ? block_offsets[blockIdx.x] : 0);
 #pragma unroll

@@ -357,6 +357,16 @@ struct HeadIn {
         if (i == 0) return 1;
         return ((uint64_t)keys[i] >> shift) != ((uint64_t)keys[i - 1] >> shift);
     }
+    // a run of 8 keys (base a multiple of 8, so 32-byte aligned: the arrays come from the pool) in two loads
+    __device__ void load_run(int64_t base, uint64_t (&v)[SCAN_IPT]) const {
+        static_assert(SCAN_IPT == 8, "two loads of four keys");
+        const uint4 *p = reinterpret_cast<const uint4 *>(keys + base);
+        const uint4 a = p[0], b = p[1];
+        const uint32_t k[9] = {base > 0 ? keys[base - 1] : 0u, a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = ((uint64_t)k[j + 1] >> shift) != ((uint64_t)k[j] >> shift);
+        if (base == 0) v[0] = 1;
+    }
 };
 struct HeadOut {
     const uint32_t *keys;
