@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--eta-smooth", type=float, default=0.0,
                     help="smooth-field limit of Sec. 4.3 (0 = off, the headline configuration; the paper uses 0.5)")
     ap.add_argument("--adaptive-far", action="store_true", help="adaptive far-field node rule of Sec. 4.3")
+    ap.add_argument("--overlap", action="store_true",
+                    help="f3m_options.overlap: the near field on the plan's second stream beside the far field")
     ap.add_argument("--cg", type=int, default=0,
                     help="after the timed steps, also time this many conjugate-gradient iterations of f3m_cg_solve "
                          "(kernel ridge regression, Sec. 5) on the last plan; reported under \"cg\", not part of `value`")
@@ -201,7 +203,7 @@ def main():
 
     def step():
         plan = f3m.Plan(X, cfg["lengthscale"], cfg["p"], cfg["theta"], eta_smooth=args.eta_smooth,
-                        adaptive_far=args.adaptive_far, Y=Y)
+                        adaptive_far=args.adaptive_far, Y=Y, overlap=args.overlap)
         plan.kmvm(b, y)
         return plan
 

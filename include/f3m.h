@@ -152,7 +152,10 @@ f3m_status f3m_plan_ex(const float *X, int64_t n, int D, float lengthscale, int 
  *   b, y   device fp32[n], caller's order; y is overwritten; they must not overlap.
  *   Asynchronous on `stream`: the call only enqueues kernels, it allocates nothing and never waits for
  *   the device (every workspace was sized by f3m_plan); one call in flight per plan (the plan holds the
- *   workspace).
+ *   workspace).  It may therefore be captured into a HIP graph (stream capture on `stream`; the plan's
+ *   own second stream joins the capture through an event and is joined back before the call returns):
+ *   a replay computes the product of what b holds then, into y.  A captured call records no times
+ *   (f3m_stage_times reports the stages of the plan only after it).
  */
 f3m_status f3m_kmvm(f3m_plan_t *plan, const float *b, float *y, void *stream);
 

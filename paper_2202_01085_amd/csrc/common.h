@@ -23,6 +23,7 @@ struct Error {
     do {                                                                                      \
         hipError_t e_ = (expr);                                                               \
         if (e_ != hipSuccess) {                                                               \
+            (void)hipGetLastError(); /* reported here: the next call must not find it again */ \
             ::f3m::fail(e_ == hipErrorOutOfMemory ? F3M_ERR_OOM : F3M_ERR_HIP,                \
                         std::string(#expr) + ": " + hipGetErrorString(e_));                   \
         }                                                                                     \

@@ -2606,7 +2606,11 @@ static void run_kmvm_d(f3m_plan_s &P, const float *b, float *y, hipStream_t st, 
     }
     if (!P.ev[12]) F3M_HIP(hipEventCreate(&P.ev[12]));
     F3M_HIP(hipEventRecord(P.ev[12], st));
-    P.have_kmvm_times = true;
+    // A product that is being captured into a graph has no times: its event records are nodes of the graph, not
+    // time stamps the host can read (f3m_stage_times then reports the stages of the plan only).
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    F3M_HIP(hipStreamIsCapturing(st, &capturing));
+    P.have_kmvm_times = capturing == hipStreamCaptureStatusNone;
 }
 
 // Products with several right-hand sides: column j of B (ns entries from B + j ldb) gives column j of Y

@@ -321,6 +321,47 @@ def test_kmvm_only_enqueues():
     plan.close()
 
 
+@pytest.mark.parametrize("overlap", [False, True])
+def test_kmvm_in_a_hip_graph(overlap):
+    # f3m_kmvm only enqueues work (on the caller's stream and, with the overlap option, on the plan's second
+    # stream, which joins through events), so it can be captured into a HIP graph.  The product is captured on a plan that has never run
+    # eagerly, replayed three times with the library's own eager work and synchronisations in between, and every
+    # replay must give the bits of the eager product; a captured call leaves no times behind, an eager one does.
+    n = 300_000
+    X = inputs.points_uniform(n, 3, 71, device=DEV)
+    b = inputs.rhs_normal(n, 72, device=DEV)
+    say("f3m_kmvm captured into a graph, n=%d, overlap=%s" % (n, overlap))
+    want = f3m.Plan(X, 0.5, 4, 2.0).kmvm(b)
+    plan = f3m.Plan(X, 0.5, 4, 2.0, overlap=overlap)
+    got = torch.empty_like(want)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        plan.kmvm(b, y=got)
+    torch.cuda.synchronize()
+    t = plan.stage_times()
+    assert t["kmvm_total"] == 0.0 and t["plan_total"] > 0.0
+    for rep in range(3):
+        got.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), "replay %d" % rep
+        again = plan.kmvm(b)                      # eager work on the same plan between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(again, want)
+        assert plan.stage_times()["kmvm_total"] > 0.0
+    # a replay reads what b holds at that time
+    b2 = inputs.rhs_normal(n, 73, device=DEV)
+    want2 = plan.kmvm(b2)
+    b.copy_(b2)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(got, want2)
+    plan.close()
+
+
 def test_force_all_near_equals_direct():
     X = cloud("normal", 12_000, 3, 9)
     b = inputs.rhs_normal(12_000, 10)
